@@ -1,0 +1,101 @@
+"""ctypes binding of libfsrgemm.so: the same entry points as include/fsrgemm.h.
+
+Only argument marshalling happens here.  Pointers may be given as integers
+(device addresses) or as objects with a ``data_ptr()`` method (torch tensors);
+``stream`` is a hipStream_t handle as an integer (0 = default stream).
+There is no fallback: if the library has not been built, every call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+__all__ = [
+    "load", "library_path", "gemm_f32", "gemm_bf16", "fsrgemm_kernel_for_f32", "fsrgemm_kernel_for_bf16",
+    "fsrgemm_status_string", "fsrgemm_version", "check", "FsrGemmError", "EXPORTS",
+    "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
+]
+
+FSRGEMM_OK = 0
+FSRGEMM_ERR_INVALID_ARG = -1
+FSRGEMM_ERR_LAUNCH = -2
+FSRGEMM_ERR_UNSUPPORTED_DEVICE = -3
+
+_i64, _vp = ctypes.c_int64, ctypes.c_void_p
+_GEMM = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp]
+_QUERY = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64]
+# every symbol include/fsrgemm.h declares: name -> (restype, argtypes)
+EXPORTS = {
+    "gemm_f32": (ctypes.c_int, _GEMM),
+    "gemm_bf16": (ctypes.c_int, _GEMM),
+    "fsrgemm_kernel_for_f32": (ctypes.c_char_p, _QUERY),
+    "fsrgemm_kernel_for_bf16": (ctypes.c_char_p, _QUERY),
+    "fsrgemm_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "fsrgemm_version": (ctypes.c_int, []),
+}
+
+_lib = None
+
+
+class FsrGemmError(RuntimeError):
+    pass
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfsrgemm.so")
+
+
+def load():
+    """Load libfsrgemm.so (once).  Raises FsrGemmError if it has not been built."""
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise FsrGemmError(
+                "%s is missing: build it first (python -m paper_2506_09092_amd.build); there is no fallback path" % path)
+        lib = ctypes.CDLL(path)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return int(x)
+
+
+def gemm_f32(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
+    return load().gemm_f32(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _ptr(stream) or None)
+
+
+def gemm_bf16(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
+    return load().gemm_bf16(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _ptr(stream) or None)
+
+
+def fsrgemm_kernel_for_f32(M, N, K, A, lda, B, ldb, C, ldc):
+    r = load().fsrgemm_kernel_for_f32(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc)
+    return None if r is None else r.decode()
+
+
+def fsrgemm_kernel_for_bf16(M, N, K, A, lda, B, ldb, C, ldc):
+    r = load().fsrgemm_kernel_for_bf16(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc)
+    return None if r is None else r.decode()
+
+
+def fsrgemm_status_string(status: int) -> str:
+    return load().fsrgemm_status_string(int(status)).decode()
+
+
+def fsrgemm_version() -> int:
+    return int(load().fsrgemm_version())
+
+
+def check(status: int) -> None:
+    """Raise FsrGemmError unless status is FSRGEMM_OK."""
+    if status != FSRGEMM_OK:
+        raise FsrGemmError("fsrgemm: %s (%d)" % (fsrgemm_status_string(status), status))
