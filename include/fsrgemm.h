@@ -1,0 +1,107 @@
+/*
+ * fsrgemm -- dense matrix multiplication C = A x B for AMD MI355X (gfx950).
+ *
+ * The operation is the one the paper states for its Task 2 (task-prompt
+ * table in the appendix): given A of M x K and B of K x N, produce the
+ * M x N product.  There is no alpha/beta scaling and C is overwritten.
+ * The paper's Function Validator and Performance Profiler (Section 3.2)
+ * call a kernel through a fixed host harness that owns all memory; this
+ * library plays the kernel's part and leaves allocation, transfers and
+ * result checking to the caller in the same way.
+ *
+ * Conventions shared by every entry point
+ *   - All matrix pointers are DEVICE pointers, valid on the current HIP
+ *     device.  The library allocates nothing and keeps no workspace.
+ *   - M, N, K and the leading dimensions are counted in ELEMENTS.
+ *   - Pointers need only the natural alignment of their element type;
+ *     faster kernels are picked automatically when base addresses and
+ *     leading dimensions are multiples of 16 bytes.
+ *   - A, B and C must not overlap.  Padding (columns N..ldc-1 of C) is
+ *     never written; padding of A and B is never read.
+ *   - M == 0 or N == 0: nothing is launched, FSRGEMM_OK.  K == 0: the
+ *     M x N block of C is set to +0 (empty sum).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream).  The call enqueues work and returns without synchronising.
+ *   - Results are deterministic: the same inputs give bit-identical C.
+ *   - Errors are reported through the return value only.  Argument errors
+ *     are detected before any HIP call is made, so they can be exercised on
+ *     a machine without a GPU.
+ */
+#ifndef FSRGEMM_H
+#define FSRGEMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FSRGEMM_OK = 0,
+    /* negative extent, leading dimension too small, NULL pointer with a
+     * non-empty matrix, or an extent beyond the supported range */
+    FSRGEMM_ERR_INVALID_ARG = -1,
+    /* the HIP runtime refused the launch (kept apart from a wrong result,
+     * as the paper's refinement prompts keep "failed to launch" apart from
+     * "output mismatch", Appendix B) */
+    FSRGEMM_ERR_LAUNCH = -2,
+    /* current device is not gfx950 */
+    FSRGEMM_ERR_UNSUPPORTED_DEVICE = -3
+} fsrgemm_status;
+
+/*
+ * fp32 product, the precision of the paper's Task 2.
+ *   C[M x N] = A[M x K] . B[K x N], all three ROW-major:
+ *   A[i][k] at A[i*lda + k] (lda >= K), B[k][j] at B[k*ldb + j] (ldb >= N),
+ *   C[i][j] at C[i*ldc + j] (ldc >= N).
+ * Products and sums are IEEE fp32 (matrix-core FMA chains, no reduced
+ * precision); the order of summation over k is fixed but unspecified.
+ * M, N, K must each be < 2^31.
+ */
+int gemm_f32(int64_t M, int64_t N, int64_t K,
+             const float *A, int64_t lda,
+             const float *B, int64_t ldb,
+             float *C, int64_t ldc,
+             void *stream);
+
+/*
+ * bf16 inputs, fp32 accumulation and fp32 output.
+ *   A is ROW-major bf16: A[i][k] at A[i*lda + k] (lda >= K).
+ *   B is COLUMN-major bf16: B[k][j] at B[j*ldb + k] (ldb >= K), i.e. both
+ *   operands are contiguous along k.
+ *   C is row-major fp32 (ldc >= N).
+ * bf16 values are raw 16-bit patterns (the upper half of an IEEE fp32
+ * word).  Each product is exact in fp32; sums are fp32.
+ */
+int gemm_bf16(int64_t M, int64_t N, int64_t K,
+              const uint16_t *A, int64_t lda,
+              const uint16_t *B, int64_t ldb,
+              float *C, int64_t ldc,
+              void *stream);
+
+/*
+ * Name of the kernel variant the dispatcher would launch for this problem
+ * (same argument checks as the gemm calls; launches nothing, touches no
+ * device memory).  Returns a pointer to static storage, or NULL when the
+ * arguments are invalid.  The Performance-Profiler side of the bench uses it
+ * to label timings and to find the kernel in a profiler trace.
+ */
+const char *fsrgemm_kernel_for_f32(int64_t M, int64_t N, int64_t K,
+                                   const float *A, int64_t lda,
+                                   const float *B, int64_t ldb,
+                                   const float *C, int64_t ldc);
+const char *fsrgemm_kernel_for_bf16(int64_t M, int64_t N, int64_t K,
+                                    const uint16_t *A, int64_t lda,
+                                    const uint16_t *B, int64_t ldb,
+                                    const float *C, int64_t ldc);
+
+/* Human-readable text for a status code; static storage, never NULL. */
+const char *fsrgemm_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int fsrgemm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FSRGEMM_H */

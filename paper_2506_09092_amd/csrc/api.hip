@@ -1,0 +1,156 @@
+// C ABI of the library (declared in include/fsrgemm.h): argument checks,
+// choice of tile configuration and load mode, launch on the caller's stream.
+#include "../../include/fsrgemm.h"
+
+#include <string.h>
+
+#include "common.hpp"
+
+using namespace fsrgemm;
+
+namespace {
+
+struct Plan {
+    int cfg;
+    int mode;
+};
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks shared by both precisions.  ldb_min is N for a row-major B, K for a
+// column-major one.  Returns FSRGEMM_OK when the problem is well formed.
+int check_args(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+               int64_t ldb_min, const void *C, int64_t ldc)
+{
+    const int64_t lim = (int64_t)1 << 31;
+    if (M < 0 || N < 0 || K < 0 || M >= lim || N >= lim || K >= lim) return FSRGEMM_ERR_INVALID_ARG;
+    if (lda < K || ldb < ldb_min || ldc < N) return FSRGEMM_ERR_INVALID_ARG;
+    if (M > 0 && N > 0 && C == nullptr) return FSRGEMM_ERR_INVALID_ARG;
+    if (M > 0 && N > 0 && K > 0 && (A == nullptr || B == nullptr)) return FSRGEMM_ERR_INVALID_ARG;
+    return FSRGEMM_OK;
+}
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Largest tile whose grid still gives every compute unit work; the small tile
+// otherwise.  Grids beyond 2^31 - 1 workgroups are rejected.
+int plan_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb, Plan *p)
+{
+    const bool big = ceil_div(M, 128) * ceil_div(N, 128) >= 256;
+    const int bm = big ? 128 : 64, bn = bm;
+    if (ceil_div(M, bm) * ceil_div(N, bn) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
+    const bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
+    p->cfg = big ? kF32_128x128 : kF32_64x64;
+    p->mode = !vec ? kScalar : (M % bm == 0 && N % bn == 0 && K % 16 == 0) ? kFast : kVecPred;
+    return FSRGEMM_OK;
+}
+
+int plan_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+              Plan *p)
+{
+    const bool big = ceil_div(M, 256) * ceil_div(N, 256) >= 128;
+    const int bm = big ? 256 : 128, bn = bm;
+    if (ceil_div(M, bm) * ceil_div(N, bn) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
+    const bool vec = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0;
+    p->cfg = big ? kBf16_256x256 : kBf16_128x128;
+    p->mode = !vec ? kScalar : (M % bm == 0 && N % bn == 0 && K % 64 == 0) ? kFast : kVecPred;
+    return FSRGEMM_OK;
+}
+
+// gfx950 check for the current device, cached per device ordinal.
+int device_ok()
+{
+    constexpr int kMaxDev = 64;
+    static int cache[kMaxDev];     // 0 = unknown, 1 = gfx950, 2 = something else
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return FSRGEMM_ERR_UNSUPPORTED_DEVICE;
+    if (dev >= 0 && dev < kMaxDev && cache[dev]) return cache[dev] == 1 ? FSRGEMM_OK : FSRGEMM_ERR_UNSUPPORTED_DEVICE;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return FSRGEMM_ERR_UNSUPPORTED_DEVICE;
+    const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+    if (dev >= 0 && dev < kMaxDev) cache[dev] = ok ? 1 : 2;
+    return ok ? FSRGEMM_OK : FSRGEMM_ERR_UNSUPPORTED_DEVICE;
+}
+
+GemmArgs pack(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb, float *C,
+              int64_t ldc)
+{
+    GemmArgs a;
+    a.M = (int)M;
+    a.N = (int)N;
+    a.K = (int)K;
+    a.A = A;
+    a.lda = lda;
+    a.B = B;
+    a.ldb = ldb;
+    a.C = C;
+    a.ldc = ldc;
+    return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb, float *C,
+             int64_t ldc, void *stream)
+{
+    int rc = check_args(M, N, K, A, lda, B, ldb, N, C, ldc);
+    if (rc != FSRGEMM_OK) return rc;
+    Plan p;
+    rc = plan_f32(M, N, K, A, lda, B, ldb, &p);
+    if (rc != FSRGEMM_OK) return rc;
+    if (M == 0 || N == 0) return FSRGEMM_OK;
+    rc = device_ok();
+    if (rc != FSRGEMM_OK) return rc;
+    const hipError_t e = launch_f32(p.cfg, p.mode, pack(M, N, K, A, lda, B, ldb, C, ldc), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+}
+
+int gemm_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+              float *C, int64_t ldc, void *stream)
+{
+    int rc = check_args(M, N, K, A, lda, B, ldb, K, C, ldc);
+    if (rc != FSRGEMM_OK) return rc;
+    Plan p;
+    rc = plan_bf16(M, N, K, A, lda, B, ldb, &p);
+    if (rc != FSRGEMM_OK) return rc;
+    if (M == 0 || N == 0) return FSRGEMM_OK;
+    rc = device_ok();
+    if (rc != FSRGEMM_OK) return rc;
+    const hipError_t e = launch_bf16(p.cfg, p.mode, pack(M, N, K, A, lda, B, ldb, C, ldc), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+}
+
+const char *fsrgemm_kernel_for_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                                   int64_t ldb, const float *C, int64_t ldc)
+{
+    Plan p;
+    if (check_args(M, N, K, A, lda, B, ldb, N, C, ldc) != FSRGEMM_OK) return nullptr;
+    if (plan_f32(M, N, K, A, lda, B, ldb, &p) != FSRGEMM_OK) return nullptr;
+    return f32_kernel_name(p.cfg, p.mode);
+}
+
+const char *fsrgemm_kernel_for_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
+                                    const uint16_t *B, int64_t ldb, const float *C, int64_t ldc)
+{
+    Plan p;
+    if (check_args(M, N, K, A, lda, B, ldb, K, C, ldc) != FSRGEMM_OK) return nullptr;
+    if (plan_bf16(M, N, K, A, lda, B, ldb, &p) != FSRGEMM_OK) return nullptr;
+    return bf16_kernel_name(p.cfg, p.mode);
+}
+
+const char *fsrgemm_status_string(int status)
+{
+    switch (status) {
+    case FSRGEMM_OK: return "ok";
+    case FSRGEMM_ERR_INVALID_ARG: return "invalid argument";
+    case FSRGEMM_ERR_LAUNCH: return "kernel launch failed";
+    case FSRGEMM_ERR_UNSUPPORTED_DEVICE: return "current device is not gfx950";
+    default: return "unknown status";
+    }
+}
+
+int fsrgemm_version(void) { return 100; }
+
+}  // extern "C"

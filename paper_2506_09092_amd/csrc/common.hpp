@@ -1,0 +1,66 @@
+// Shared device/host helpers for the gfx950 GEMM kernels: vector types, the
+// workgroup-id -> output-tile mapping and the launcher declarations that the
+// C ABI in api.hip dispatches to.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fsrgemm {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;     // CDNA wavefront width
+constexpr int kXcds = 8;      // MI355X: 8 accelerator dies, each with a private L2
+constexpr int kGroupM = 8;    // tile rows walked together inside one die's share
+
+// Workgroups are handed to the 8 dies round-robin (id % 8).  Re-number them so
+// that each die owns one contiguous run of the tile sequence, then walk that
+// sequence in column-major order inside bands of kGroupM tile rows.  A die's
+// resident workgroups then share a few A row-panels and B column-panels in its
+// own L2 instead of every die streaming every panel.
+__device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int total = tiles_m * tiles_n;
+    const int per = total / kXcds, rem = total % kXcds;
+    const int xcd = pid % kXcds, loc = pid / kXcds;
+    const int lin = xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
+    const int width = kGroupM * tiles_n;
+    const int band = lin / width;
+    const int first_m = band * kGroupM;
+    const int rows = min(tiles_m - first_m, kGroupM);
+    const int in_band = lin - band * width;
+    tm = first_m + in_band % rows;
+    tn = in_band / rows;
+}
+
+struct GemmArgs {
+    int M, N, K;
+    const void *A;
+    int64_t lda;
+    const void *B;
+    int64_t ldb;
+    float *C;
+    int64_t ldc;
+};
+
+// How global loads are issued.
+//   kFast:    16-byte vectors, no bounds checks (aligned, tile-multiple shapes)
+//   kVecPred: 16-byte vectors where a whole vector is in range, element-wise
+//             zero-filled loads at the ragged edge (aligned bases and lds)
+//   kScalar:  element-wise predicated loads (any alignment, any shape)
+enum LoadMode { kFast = 0, kVecPred = 1, kScalar = 2 };
+
+// fp32 tile configurations (gemm_f32.hip)
+enum F32Config { kF32_128x128 = 0, kF32_64x64 = 1, kF32ConfigCount };
+const char *f32_kernel_name(int cfg, int mode);
+hipError_t launch_f32(int cfg, int mode, const GemmArgs &a, hipStream_t s);
+
+// bf16 tile configurations (gemm_bf16.hip)
+enum Bf16Config { kBf16_256x256 = 0, kBf16_128x128 = 1, kBf16ConfigCount };
+const char *bf16_kernel_name(int cfg, int mode);
+hipError_t launch_bf16(int cfg, int mode, const GemmArgs &a, hipStream_t s);
+
+}  // namespace fsrgemm

@@ -1,0 +1,70 @@
+"""Shared plumbing for the GPU parity tests: moves seeded operands to the
+device with canary padding, calls the C ABI, brings C back and checks the
+canaries.  No arithmetic of the product happens here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2506_09092_amd import inputs
+
+SENTINEL = np.float32(-7.25e30)      # pre-fill of C and its padding
+
+
+def _dev(buf: np.ndarray) -> torch.Tensor:
+    if buf.dtype == np.uint16:
+        return torch.from_numpy(buf.view(np.int16)).cuda()
+    return torch.from_numpy(buf).cuda()
+
+
+def run_f32(lib, A: np.ndarray, B: np.ndarray, lda=None, ldb=None, ldc=None, offset=0, repeat=1):
+    """C = A.B through gemm_f32 with padded, canaried buffers.  Returns the M x N result (numpy)."""
+    M, K = A.shape
+    N = B.shape[1]
+    lda, ldb, ldc = lda or max(K, 1), ldb or max(N, 1), ldc or max(N, 1)
+    a = _dev(inputs.embed(A, lda, np.float32(np.nan), offset))
+    b = _dev(inputs.embed(B, ldb, np.float32(np.nan), offset))
+    c_host = np.full(offset + M * ldc + 3, SENTINEL, dtype=np.float32)
+    outs = []
+    for _ in range(repeat):
+        c = _dev(c_host)
+        st = lib.gemm_f32(M, N, K, a.data_ptr() + 4 * offset, lda, b.data_ptr() + 4 * offset, ldb,
+                          c.data_ptr() + 4 * offset, ldc, torch.cuda.current_stream().cuda_stream)
+        lib.check(st)
+        torch.cuda.synchronize()
+        outs.append(_unpack(c.cpu().numpy(), M, N, ldc, offset))
+    for o in outs[1:]:
+        assert np.array_equal(o.view(np.uint32), outs[0].view(np.uint32)), "run-to-run results differ"
+    return outs[0]
+
+
+def run_bf16(lib, A: np.ndarray, Bt: np.ndarray, lda=None, ldb=None, ldc=None, offset=0, repeat=1):
+    """C = A.B through gemm_bf16; A is (M, K) bf16 bits, Bt is (N, K) bf16 bits (column-major B)."""
+    M, K = A.shape
+    N = Bt.shape[0]
+    assert Bt.shape[1] == K
+    lda, ldb, ldc = lda or max(K, 1), ldb or max(K, 1), ldc or max(N, 1)
+    nan16 = np.uint16(0x7FC0)
+    a = _dev(inputs.embed(A, lda, nan16, offset))
+    b = _dev(inputs.embed(Bt, ldb, nan16, offset))
+    c_host = np.full(offset + M * ldc + 3, SENTINEL, dtype=np.float32)
+    outs = []
+    for _ in range(repeat):
+        c = _dev(c_host)
+        st = lib.gemm_bf16(M, N, K, a.data_ptr() + 2 * offset, lda, b.data_ptr() + 2 * offset, ldb,
+                           c.data_ptr() + 4 * offset, ldc, torch.cuda.current_stream().cuda_stream)
+        lib.check(st)
+        torch.cuda.synchronize()
+        outs.append(_unpack(c.cpu().numpy(), M, N, ldc, offset))
+    for o in outs[1:]:
+        assert np.array_equal(o.view(np.uint32), outs[0].view(np.uint32)), "run-to-run results differ"
+    return outs[0]
+
+
+def _unpack(flat: np.ndarray, M: int, N: int, ldc: int, offset: int) -> np.ndarray:
+    """Checks that everything outside the M x N block still holds the sentinel; returns the block."""
+    assert np.all(flat[:offset] == SENTINEL), "wrote before C"
+    assert np.all(flat[offset + M * ldc:] == SENTINEL), "wrote past C"
+    body = flat[offset:offset + M * ldc].reshape(M, ldc)
+    assert np.all(body[:, N:] == SENTINEL), "wrote into C's row padding"
+    return body[:, :N].copy()

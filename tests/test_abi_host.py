@@ -1,0 +1,73 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header
+declares, and rejects malformed problems before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2506_09092_amd as lib
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "fsrgemm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"})
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"gemm_f32", "gemm_bf16", "fsrgemm_status_string", "fsrgemm_version"} <= set(names)
+    assert set(names) == set(lib.EXPORTS)
+    handle = ctypes.CDLL(lib.library_path())
+    for n in names:
+        assert hasattr(handle, n), n
+    assert lib.fsrgemm_version() >= 100
+
+
+def test_status_strings():
+    seen = {lib.fsrgemm_status_string(s) for s in (0, -1, -2, -3)}
+    assert len(seen) == 4 and "ok" in seen
+    assert "unknown" in lib.fsrgemm_status_string(-99)
+
+
+P = 0x1000      # a non-null, 16-byte aligned fake address: never dereferenced by the checks
+
+
+@pytest.mark.parametrize("fn", ["gemm_f32", "gemm_bf16"])
+def test_invalid_arguments_are_rejected_without_a_device(fn):
+    f = getattr(lib, fn)
+    ldb_min = 8 if fn == "gemm_f32" else 16          # N for row-major B, K for column-major B
+    ok = dict(M=4, N=8, K=16, A=P, lda=16, B=P, ldb=ldb_min, C=P, ldc=8)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["M"], a["N"], a["K"], a["A"], a["lda"], a["B"], a["ldb"], a["C"], a["ldc"], 0)
+
+    bad = lib.FSRGEMM_ERR_INVALID_ARG
+    assert call(M=-1) == bad and call(N=-1) == bad and call(K=-1) == bad
+    assert call(lda=15) == bad and call(ldb=ldb_min - 1) == bad and call(ldc=7) == bad
+    assert call(A=None) == bad and call(B=None) == bad and call(C=None) == bad
+    assert call(M=2 ** 31) == bad and call(K=2 ** 31) == bad
+    # empty outputs are fine and launch nothing, whatever the pointers
+    assert call(M=0, A=None, C=None) == lib.FSRGEMM_OK
+    assert call(N=0, ldb=ldb_min if fn == "gemm_bf16" else 0, ldc=0, B=None, C=None) == lib.FSRGEMM_OK
+    with pytest.raises(lib.FsrGemmError):
+        lib.check(bad)
+
+
+def test_dispatch_query_names_variants():
+    q = lib.fsrgemm_kernel_for_f32
+    fast = q(4096, 4096, 4096, P, 4096, P, 4096, P, 4096)
+    ragged = q(4097, 17, 1000, P, 1000, P, 20, P, 17)
+    unaligned = q(123, 5, 8, P + 4, 8, P + 4, 5, P, 5)
+    assert "128x128" in fast and fast.endswith("fast")
+    assert ragged.endswith("vecpred") and unaligned.endswith("scalar")
+    assert q(4, 4, 4, P, 3, P, 4, P, 4) is None
+    qb = lib.fsrgemm_kernel_for_bf16
+    assert "256x256" in qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192)
+    assert qb(100, 100, 100, P, 100, P, 100, P, 100).endswith("scalar")     # ld not a multiple of 8
+    assert qb(100, 100, 100, P, 104, P, 104, P, 100).endswith("vecpred")
