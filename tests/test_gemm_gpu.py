@@ -1,0 +1,185 @@
+"""Parity of the HIP path against the CPU oracle, called through the C ABI.
+
+Gate: e = max_ij |got - ref| / S_ij with S = |A||B| (fp64, from the oracle);
+e <= 1e-5 for fp32, e <= 1e-2 for bf16 inputs; bit-exact on small-integer
+operands, where every summation order is exact.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2506_09092_amd import inputs
+
+from gpu_harness import run_bf16, run_f32
+
+pytestmark = pytest.mark.gpu
+TOL_F32 = 1e-5
+TOL_BF16 = 1e-2
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def check_f32(lib, A, B, tol=TOL_F32, **kw):
+    got = run_f32(lib, A, B, **kw)
+    ref, S = oracle.gemm(A, B)
+    e = oracle.componentwise_error(got, ref, S)
+    assert e <= tol, "componentwise error %.3e > %.1e" % (e, tol)
+    return got, ref, e
+
+
+def check_bf16(lib, A, Bt, tol=TOL_BF16, **kw):
+    got = run_bf16(lib, A, Bt, **kw)
+    ref, S = oracle.gemm(A, Bt.T)
+    e = oracle.componentwise_error(got, ref, S)
+    assert e <= tol, "componentwise error %.3e > %.1e" % (e, tol)
+    return got, ref, e
+
+
+def test_f32_256_uniform(gpu):
+    say("fp32 256^3 uniform seed 0")
+    check_f32(gpu, inputs.uniform_pm1(0, 1, 256, 256), inputs.uniform_pm1(0, 2, 256, 256), repeat=2)
+
+
+def test_f32_256_integers_bit_exact(gpu):
+    say("fp32 256^3 integers seed 0")
+    A, B = inputs.small_ints(0, 3, 256, 256), inputs.small_ints(0, 4, 256, 256)
+    got = run_f32(gpu, A, B)
+    ref, _ = oracle.gemm(A, B)
+    assert np.array_equal(got.astype(np.float64), ref)
+    assert not np.any(np.signbit(got[got == 0]))
+
+
+def test_f32_1024_uniform(gpu):
+    say("fp32 1024^3 uniform seed 1")
+    check_f32(gpu, inputs.uniform_pm1(1, 1, 1024, 1024), inputs.uniform_pm1(1, 2, 1024, 1024))
+
+
+def test_f32_sweep_64_shapes(gpu):
+    cases = inputs.sweep_cases(3, 64)
+    failed = []
+    for c in cases:
+        say("sweep case %(index)d: M=%(M)d N=%(N)d K=%(K)d lda=%(lda)d ldb=%(ldb)d ldc=%(ldc)d off=%(offset)d" % c)
+        A = inputs.uniform_pm1(3, 2 * c["index"] + 10, c["M"], c["K"])
+        B = inputs.uniform_pm1(3, 2 * c["index"] + 11, c["K"], c["N"])
+        got = run_f32(gpu, A, B, lda=c["lda"], ldb=c["ldb"], ldc=c["ldc"], offset=c["offset"], repeat=2)
+        ref, S = oracle.gemm(A, B)
+        e = oracle.componentwise_error(got, ref, S)
+        if not e <= TOL_F32:
+            failed.append((c["index"], e))
+    assert not failed, failed
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (17, 17, 17), (128, 128, 128), (130, 70, 200), (257, 255, 129),
+                                   (33, 65, 31), (512, 384, 1000), (300, 520, 64)])
+def test_bf16_shapes(gpu, shape):
+    M, N, K = shape
+    say("bf16 %dx%dx%d" % shape)
+    A = inputs.bf16_normal_scaled(4, 20, M, K, 1 / math.sqrt(K))
+    Bt = inputs.bf16_normal_scaled(4, 21, N, K, 1 / math.sqrt(K))
+    check_bf16(gpu, A, Bt, repeat=2)
+    pad = 8 if (M + N) % 2 == 0 else 3                     # aligned and unaligned leading dimensions
+    check_bf16(gpu, A, Bt, lda=K + pad, ldb=K + pad, ldc=N + 5, offset=1 if pad == 3 else 0)
+
+
+def test_bf16_512_integers_bit_exact(gpu):
+    say("bf16 512^3 integers")
+    A, Bt = inputs.bf16_small_ints(4, 30, 512, 512), inputs.bf16_small_ints(4, 31, 512, 512)
+    got = run_bf16(gpu, A, Bt)
+    ref, _ = oracle.gemm(A, Bt.T)
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
+def test_bf16_big_tile_config_ragged(gpu):
+    # large enough for the 256x256 configuration, not a tile multiple
+    M, N, K = 2900, 3000, 200
+    say("bf16 %dx%dx%d (256-tile, ragged)" % (M, N, K))
+    A = inputs.bf16_normal_scaled(4, 40, M, K, 1 / math.sqrt(K))
+    Bt = inputs.bf16_normal_scaled(4, 41, N, K, 1 / math.sqrt(K))
+    assert "256x256" in gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N)
+    check_bf16(gpu, A, Bt)
+
+
+def test_degenerate_extents(gpu):
+    say("degenerate extents")
+    A0, B0 = np.zeros((5, 0), np.float32), np.zeros((0, 7), np.float32)
+    got = run_f32(gpu, A0, B0)                              # K = 0: empty sums
+    assert got.shape == (5, 7) and np.all(got == 0) and not np.any(np.signbit(got))
+    got = run_bf16(gpu, np.zeros((5, 0), np.uint16), np.zeros((7, 0), np.uint16))
+    assert np.all(got == 0) and not np.any(np.signbit(got))
+    assert gpu.gemm_f32(0, 7, 3, None, 3, None, 7, None, 7, 0) == gpu.FSRGEMM_OK
+    assert gpu.gemm_bf16(4, 0, 3, None, 3, None, 3, None, 1, 0) == gpu.FSRGEMM_OK
+
+
+def _sample_indices(M, N, tile, n_rand, seed):
+    rng = np.random.default_rng(seed)
+    ii, jj = [rng.integers(0, M, n_rand)], [rng.integers(0, N, n_rand)]
+    # the four entries around every interior tile-boundary crossing
+    bm = np.arange(tile, M, tile)
+    bn = np.arange(tile, N, tile)
+    for di in (-1, 0):
+        for dj in (-1, 0):
+            gi, gj = np.meshgrid(bm + di, bn + dj, indexing="ij")
+            ii.append(gi.ravel())
+            jj.append(gj.ravel())
+    return np.concatenate(ii), np.concatenate(jj)
+
+
+def test_f32_4096_normal_full_size(gpu):
+    say("fp32 4096^3 normal seed 2 (sampled rows, columns, entries + Freivalds)")
+    n = 4096
+    A, B = inputs.normal(2, 1, n, n), inputs.normal(2, 2, n, n)
+    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n).endswith("128x128x16_fast")
+    got = run_f32(gpu, A, B)
+    rng = np.random.default_rng(2)
+    rows, cols = np.sort(rng.choice(n, 64, replace=False)), np.sort(rng.choice(n, 64, replace=False))
+    ref, S = oracle.gemm(A[rows], B)
+    assert oracle.componentwise_error(got[rows], ref, S) <= TOL_F32
+    ref, S = oracle.gemm(A, np.ascontiguousarray(B[:, cols]))
+    assert oracle.componentwise_error(got[:, cols], ref, S) <= TOL_F32
+    ii, jj = _sample_indices(n, n, 128, 65536, 2)
+    c, s = oracle.gemm_entries(A, B, ii, jj)
+    assert oracle.componentwise_error(got[ii, jj], c, s) <= TOL_F32
+    assert oracle.freivalds_residual(A, B, got) <= TOL_F32
+
+
+def test_bf16_8192_full_size(gpu):
+    say("bf16 8192^3 normal/sqrt(K) seed 4 (sampled rows, columns, entries + Freivalds)")
+    n = 8192
+    A = inputs.bf16_normal_scaled(4, 1, n, n, 1 / math.sqrt(n))
+    Bt = inputs.bf16_normal_scaled(4, 2, n, n, 1 / math.sqrt(n))
+    assert gpu.fsrgemm_kernel_for_bf16(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n).endswith("256x256x64_fast")
+    got = run_bf16(gpu, A, Bt)
+    say("  GPU done; oracle on samples")
+    rng = np.random.default_rng(4)
+    rows, cols = np.sort(rng.choice(n, 128, replace=False)), np.sort(rng.choice(n, 128, replace=False))
+    B_rm = np.ascontiguousarray(Bt.T)                       # same values, row-major, for a cache-friendly oracle walk
+    ref, S = oracle.gemm(A[rows], B_rm)
+    assert oracle.componentwise_error(got[rows], ref, S) <= TOL_BF16
+    say("  rows ok")
+    ref, S = oracle.gemm(A, np.ascontiguousarray(B_rm[:, cols]))
+    assert oracle.componentwise_error(got[:, cols], ref, S) <= TOL_BF16
+    say("  cols ok")
+    ii, jj = _sample_indices(n, n, 256, 262144, 4)
+    c, s = oracle.gemm_entries(A, Bt.T, ii, jj)
+    assert oracle.componentwise_error(got[ii, jj], c, s) <= TOL_BF16
+    say("  entries ok")
+    del B_rm
+    assert oracle.freivalds_residual(A, Bt.T, got) <= TOL_BF16
+
+
+def test_f32_paper_task2_shape(gpu):
+    # the paper's own Task 2 operand shapes (input-size table): A (size, 4096), B (4096, 2048); smallest size
+    say("fp32 1024x2048x4096 (paper Task 2, size 2^10)")
+    M, N, K = 1024, 2048, 4096
+    A, B = inputs.uniform_pm1(5, 1, M, K), inputs.uniform_pm1(5, 2, K, N)
+    got = run_f32(gpu, A, B)
+    rows = np.arange(0, M, 37)
+    ref, S = oracle.gemm(A[rows], B)
+    assert oracle.componentwise_error(got[rows], ref, S) <= TOL_F32
+    assert oracle.freivalds_residual(A, B, got) <= TOL_F32
