@@ -53,6 +53,12 @@ def load():
         if not os.path.exists(path):
             raise FsrGemmError(
                 "%s is missing: build it first (python -m paper_2506_09092_amd.build); there is no fallback path" % path)
+        try:
+            # torch carries its own HIP runtime; import it first so that the library binds to the
+            # runtime that owns the caller's tensors and streams instead of loading a second one
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = ctypes.CDLL(path)
         for name, (res, args) in EXPORTS.items():
             fn = getattr(lib, name)

@@ -1,12 +1,12 @@
-"""Shared plumbing for the GPU parity tests: moves seeded operands to the
-device with canary padding, calls the C ABI, brings C back and checks the
-canaries.  No arithmetic of the product happens here."""
+"""Validator-side plumbing shared by the bench and the GPU tests: moves seeded
+operands to the device with canary padding, calls the C ABI, brings C back and
+checks the canaries.  No arithmetic of the product happens here."""
 from __future__ import annotations
 
 import numpy as np
 import torch
 
-from paper_2506_09092_amd import inputs
+from . import inputs
 
 SENTINEL = np.float32(-7.25e30)      # pre-fill of C and its padding
 

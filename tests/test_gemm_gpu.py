@@ -13,7 +13,7 @@ import pytest
 import oracle
 from paper_2506_09092_amd import inputs
 
-from gpu_harness import run_bf16, run_f32
+from paper_2506_09092_amd.harness import run_bf16, run_f32
 
 pytestmark = pytest.mark.gpu
 TOL_F32 = 1e-5
