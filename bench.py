@@ -105,7 +105,7 @@ def cpu_baseline(w):
     """The oracle as it stands, timed on the host cores over a slab of rows of the same workload."""
     import oracle
 
-    rows = 1024 if w["kind"] == "f32" else 256
+    rows = w["M"] if w["kind"] == "f32" else 2048           # a few seconds to ~10 s of host time
     A = w["hostA"][:rows]
     B = w["hostB"] if w["kind"] == "f32" else w["hostB"].T.copy()       # row-major copy: same values
     t0 = time.perf_counter()
@@ -113,7 +113,7 @@ def cpu_baseline(w):
     dt = time.perf_counter() - t0
     return {"value": 2.0 * rows * w["N"] * w["K"] / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": dt,
-            "sample": "first %d of %d rows of C for the %s workload (fp64 triple loop, OpenMP over rows)" % (rows, w["M"], w["name"])}
+            "sample": "%s %d of %d rows of C for the %s workload (fp64 triple loop, OpenMP over rows)" % ("all" if rows == w["M"] else "first", rows, w["M"], w["name"])}
 
 
 def main():

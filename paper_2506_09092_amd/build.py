@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libfsrgemm.so")
-SOURCES = ("api.hip", "gemm_f32.hip", "gemm_bf16.hip")
+SOURCES = ("api.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_main.hip")
 HIPCC_FLAGS = (
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-fp32 code generation is switched off for every device compile

@@ -54,6 +54,8 @@ int plan_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, c
     const bool vec = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0;
     p->cfg = big ? kBf16_256x256 : kBf16_128x128;
     p->mode = !vec ? kScalar : (M % bm == 0 && N % bn == 0 && K % 64 == 0) ? kFast : kVecPred;
+    // the scheduled kernel needs whole tiles and 32-bit lane offsets
+    if (big && p->mode == kFast && K >= 64 && lda < (1 << 25) && ldb < (1 << 25)) p->cfg = kBf16_Main;
     return FSRGEMM_OK;
 }
 

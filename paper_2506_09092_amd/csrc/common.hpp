@@ -55,12 +55,16 @@ enum LoadMode { kFast = 0, kVecPred = 1, kScalar = 2 };
 
 // fp32 tile configurations (gemm_f32.hip)
 enum F32Config { kF32_128x128 = 0, kF32_64x64 = 1, kF32ConfigCount };
+// Names are substrings of the kernel symbols as a profiler trace prints them.
 const char *f32_kernel_name(int cfg, int mode);
 hipError_t launch_f32(int cfg, int mode, const GemmArgs &a, hipStream_t s);
 
-// bf16 tile configurations (gemm_bf16.hip)
-enum Bf16Config { kBf16_256x256 = 0, kBf16_128x128 = 1, kBf16ConfigCount };
+// bf16 tile configurations: the scheduled 256x256 kernel for aligned, tile-multiple problems
+// (gemm_bf16_main.hip) and two predicated general-purpose configurations (gemm_bf16.hip)
+enum Bf16Config { kBf16_Main = 0, kBf16_256x256 = 1, kBf16_128x128 = 2, kBf16ConfigCount };
 const char *bf16_kernel_name(int cfg, int mode);
 hipError_t launch_bf16(int cfg, int mode, const GemmArgs &a, hipStream_t s);
+const char *bf16_main_kernel_name();
+hipError_t launch_bf16_main(const GemmArgs &a, hipStream_t s);
 
 }  // namespace fsrgemm

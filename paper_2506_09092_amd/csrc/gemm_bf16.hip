@@ -10,8 +10,12 @@
 // operand -- exactly one 16-byte LDS read per operand block.
 //
 // LDS rows are 128 bytes with no padding; the 16-byte chunk c of row r is kept
-// at chunk position c ^ (r & 7), so that the 32 rows a half-wavefront reads at
-// one k-offset spread over all banks.
+// at chunk position c ^ ((r >> 1) & 7), so that the 16 rows that one group of
+// lanes reads at one k-offset cover all 64 banks exactly once.
+//
+// This file holds the general-purpose configurations (any shape, any
+// alignment); large aligned problems go to the scheduled kernel in
+// gemm_bf16_main.hip.
 #include "common.hpp"
 
 namespace fsrgemm {
@@ -20,7 +24,7 @@ namespace {
 constexpr int kBK = 64;                 // bf16 elements per K-tile: one 128-byte row
 constexpr int kChunks = kBK / 8;        // 16-byte chunks per row
 
-__device__ __forceinline__ int swizzled(int row, int chunk) { return row * kBK + ((chunk ^ (row & 7)) * 8); }
+__device__ __forceinline__ int swizzled(int row, int chunk) { return row * kBK + ((chunk ^ ((row >> 1) & 7)) * 8); }
 
 template <int MODE>
 __device__ __forceinline__ u32x4 load8(const uint16_t *__restrict__ p, bool row_ok, int col, int col_limit)
@@ -187,16 +191,17 @@ hipError_t launch_cfg(int mode, const GemmArgs &a, hipStream_t s)
 
 const char *bf16_kernel_name(int cfg, int mode)
 {
-    static const char *names[kBf16ConfigCount][3] = {
-        {"gemm_bf16_256x256x64_fast", "gemm_bf16_256x256x64_vecpred", "gemm_bf16_256x256x64_scalar"},
-        {"gemm_bf16_128x128x64_fast", "gemm_bf16_128x128x64_vecpred", "gemm_bf16_128x128x64_scalar"},
+    static const char *names[2][3] = {
+        {"gemm_bf16_kernel<256, 256, 2, 4, 0>", "gemm_bf16_kernel<256, 256, 2, 4, 1>", "gemm_bf16_kernel<256, 256, 2, 4, 2>"},
+        {"gemm_bf16_kernel<128, 128, 2, 2, 0>", "gemm_bf16_kernel<128, 128, 2, 2, 1>", "gemm_bf16_kernel<128, 128, 2, 2, 2>"},
     };
-    return names[cfg][mode];
+    return cfg == kBf16_Main ? bf16_main_kernel_name() : names[cfg - 1][mode];
 }
 
 hipError_t launch_bf16(int cfg, int mode, const GemmArgs &a, hipStream_t s)
 {
     switch (cfg) {
+    case kBf16_Main: return launch_bf16_main(a, s);
     case kBf16_256x256: return launch_cfg<256, 256, 2, 4>(mode, a, s);
     default: return launch_cfg<128, 128, 2, 2>(mode, a, s);
     }

@@ -186,8 +186,8 @@ hipError_t launch_cfg(int mode, const GemmArgs &a, hipStream_t s)
 const char *f32_kernel_name(int cfg, int mode)
 {
     static const char *names[kF32ConfigCount][3] = {
-        {"gemm_f32_128x128x16_fast", "gemm_f32_128x128x16_vecpred", "gemm_f32_128x128x16_scalar"},
-        {"gemm_f32_64x64x16_fast", "gemm_f32_64x64x16_vecpred", "gemm_f32_64x64x16_scalar"},
+        {"gemm_f32_kernel<128, 128, 0>", "gemm_f32_kernel<128, 128, 1>", "gemm_f32_kernel<128, 128, 2>"},
+        {"gemm_f32_kernel<64, 64, 0>", "gemm_f32_kernel<64, 64, 1>", "gemm_f32_kernel<64, 64, 2>"},
     };
     return names[cfg][mode];
 }

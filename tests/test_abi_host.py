@@ -64,10 +64,11 @@ def test_dispatch_query_names_variants():
     fast = q(4096, 4096, 4096, P, 4096, P, 4096, P, 4096)
     ragged = q(4097, 17, 1000, P, 1000, P, 20, P, 17)
     unaligned = q(123, 5, 8, P + 4, 8, P + 4, 5, P, 5)
-    assert "128x128" in fast and fast.endswith("fast")
-    assert ragged.endswith("vecpred") and unaligned.endswith("scalar")
+    assert fast == "gemm_f32_kernel<128, 128, 0>"                           # <BM, BN, load mode>: 0 fast, 1 vector+predicated, 2 scalar
+    assert ragged == "gemm_f32_kernel<64, 64, 1>" and unaligned == "gemm_f32_kernel<64, 64, 2>"
     assert q(4, 4, 4, P, 3, P, 4, P, 4) is None
     qb = lib.fsrgemm_kernel_for_bf16
-    assert "256x256" in qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192)
-    assert qb(100, 100, 100, P, 100, P, 100, P, 100).endswith("scalar")     # ld not a multiple of 8
-    assert qb(100, 100, 100, P, 104, P, 104, P, 100).endswith("vecpred")
+    assert qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel"
+    assert qb(8192, 8192, 8200, P, 8200, P, 8200, P, 8192) == "gemm_bf16_kernel<256, 256, 2, 4, 1>"   # K not a multiple of 64
+    assert qb(100, 100, 100, P, 100, P, 100, P, 100) == "gemm_bf16_kernel<128, 128, 2, 2, 2>"         # ld not a multiple of 8
+    assert qb(100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<128, 128, 2, 2, 1>"

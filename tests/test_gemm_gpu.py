@@ -101,8 +101,25 @@ def test_bf16_big_tile_config_ragged(gpu):
     say("bf16 %dx%dx%d (256-tile, ragged)" % (M, N, K))
     A = inputs.bf16_normal_scaled(4, 40, M, K, 1 / math.sqrt(K))
     Bt = inputs.bf16_normal_scaled(4, 41, N, K, 1 / math.sqrt(K))
-    assert "256x256" in gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N)
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_kernel<256, 256, 2, 4, 1>"
     check_bf16(gpu, A, Bt)
+
+
+@pytest.mark.parametrize("K", [64, 128, 192, 448])
+def test_bf16_main_kernel_small_k(gpu, K):
+    # the scheduled 256x256 kernel with 1, 2, 3 and 7 K-tiles: prologue, odd/even tails, clamped prefetch
+    M, N = 2048, 4096
+    say("bf16 main kernel %dx%dx%d" % (M, N, K))
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_main_kernel"
+    A = inputs.bf16_normal_scaled(4, 50 + K, M, K, 1 / math.sqrt(K))
+    Bt = inputs.bf16_normal_scaled(4, 51 + K, N, K, 1 / math.sqrt(K))
+    check_bf16(gpu, A, Bt, repeat=2)
+    if K == 192:                                            # padded leading dimensions stay on the same kernel
+        assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K + 8, 0x1000, K + 72, 0x1000, N + 3) == "gemm_bf16_main_kernel"
+        check_bf16(gpu, A, Bt, lda=K + 8, ldb=K + 72, ldc=N + 3)
+        Ai, Bi = inputs.bf16_small_ints(4, 60, M, K), inputs.bf16_small_ints(4, 61, N, K)
+        got = run_bf16(gpu, Ai, Bi)
+        assert np.array_equal(got.astype(np.float64), oracle.gemm(Ai, Bi.T)[0])
 
 
 def test_degenerate_extents(gpu):
@@ -134,7 +151,7 @@ def test_f32_4096_normal_full_size(gpu):
     say("fp32 4096^3 normal seed 2 (sampled rows, columns, entries + Freivalds)")
     n = 4096
     A, B = inputs.normal(2, 1, n, n), inputs.normal(2, 2, n, n)
-    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n).endswith("128x128x16_fast")
+    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_kernel<128, 128, 0>"
     got = run_f32(gpu, A, B)
     rng = np.random.default_rng(2)
     rows, cols = np.sort(rng.choice(n, 64, replace=False)), np.sort(rng.choice(n, 64, replace=False))
@@ -153,7 +170,7 @@ def test_bf16_8192_full_size(gpu):
     n = 8192
     A = inputs.bf16_normal_scaled(4, 1, n, n, 1 / math.sqrt(n))
     Bt = inputs.bf16_normal_scaled(4, 2, n, n, 1 / math.sqrt(n))
-    assert gpu.fsrgemm_kernel_for_bf16(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n).endswith("256x256x64_fast")
+    assert gpu.fsrgemm_kernel_for_bf16(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_bf16_main_kernel"
     got = run_bf16(gpu, A, Bt)
     say("  GPU done; oracle on samples")
     rng = np.random.default_rng(4)
