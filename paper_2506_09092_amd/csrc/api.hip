@@ -42,6 +42,11 @@ int plan_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const
     const bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
     p->cfg = big ? kF32_128x128 : kF32_64x64;
     p->mode = !vec ? kScalar : (M % bm == 0 && N % bn == 0 && K % 16 == 0) ? kFast : kVecPred;
+    // scheduled kernels: whole tiles only, and enough of them to occupy the chip
+    if (vec && K % 16 == 0 && K >= 16) {
+        if (M % 256 == 0 && N % 128 == 0 && (M / 256) * (N / 128) >= 384) p->cfg = kF32_Sched256x128, p->mode = kFast;
+        else if (M % 128 == 0 && N % 128 == 0 && (M / 128) * (N / 128) >= 256) p->cfg = kF32_Sched128x128, p->mode = kFast;
+    }
     return FSRGEMM_OK;
 }
 

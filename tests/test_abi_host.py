@@ -64,7 +64,7 @@ def test_dispatch_query_names_variants():
     fast = q(4096, 4096, 4096, P, 4096, P, 4096, P, 4096)
     ragged = q(4097, 17, 1000, P, 1000, P, 20, P, 17)
     unaligned = q(123, 5, 8, P + 4, 8, P + 4, 5, P, 5)
-    assert fast == "gemm_f32_kernel<128, 128, 0>"                           # <BM, BN, load mode>: 0 fast, 1 vector+predicated, 2 scalar
+    assert fast == "gemm_f32_sched_kernel<4, 2, 2>"                          # scheduled 256x128 kernel <TM, TN, min waves>
     assert ragged == "gemm_f32_kernel<64, 64, 1>" and unaligned == "gemm_f32_kernel<64, 64, 2>"
     assert q(4, 4, 4, P, 3, P, 4, P, 4) is None
     qb = lib.fsrgemm_kernel_for_bf16

@@ -105,6 +105,26 @@ def test_bf16_big_tile_config_ragged(gpu):
     check_bf16(gpu, A, Bt)
 
 
+@pytest.mark.parametrize("shape,kernel", [((2048, 2048, 16), "gemm_f32_sched_kernel<2, 2, 3>"),
+                                          ((2048, 2048, 32), "gemm_f32_sched_kernel<2, 2, 3>"),
+                                          ((2048, 2048, 112), "gemm_f32_sched_kernel<2, 2, 3>"),
+                                          ((4096, 3072, 16), "gemm_f32_sched_kernel<4, 2, 2>"),
+                                          ((4096, 3072, 48), "gemm_f32_sched_kernel<4, 2, 2>"),
+                                          ((4096, 3072, 160), "gemm_f32_sched_kernel<4, 2, 2>")])
+def test_f32_scheduled_kernels_small_k(gpu, shape, kernel):
+    # prologue, odd/even K-tile tails and the clamped prefetch of the scheduled kernels; full oracle comparison
+    M, N, K = shape
+    say("fp32 scheduled kernel %dx%dx%d" % shape)
+    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == kernel
+    A, B = inputs.uniform_pm1(6, K, M, K), inputs.uniform_pm1(6, K + 1, K, N)
+    check_f32(gpu, A, B, repeat=2)
+    if K in (112, 160):
+        assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K + 4, 0x1000, N + 12, 0x1000, N + 1) == kernel
+        check_f32(gpu, A, B, lda=K + 4, ldb=N + 12, ldc=N + 1)
+        Ai, Bi = inputs.small_ints(6, 90, M, K), inputs.small_ints(6, 91, K, N)
+        assert np.array_equal(run_f32(gpu, Ai, Bi).astype(np.float64), oracle.gemm(Ai, Bi)[0])
+
+
 @pytest.mark.parametrize("K", [64, 128, 192, 448])
 def test_bf16_main_kernel_small_k(gpu, K):
     # the scheduled 256x256 kernel with 1, 2, 3 and 7 K-tiles: prologue, odd/even tails, clamped prefetch
@@ -151,7 +171,7 @@ def test_f32_4096_normal_full_size(gpu):
     say("fp32 4096^3 normal seed 2 (sampled rows, columns, entries + Freivalds)")
     n = 4096
     A, B = inputs.normal(2, 1, n, n), inputs.normal(2, 2, n, n)
-    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_kernel<128, 128, 0>"
+    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_sched_kernel<4, 2, 2>"
     got = run_f32(gpu, A, B)
     rng = np.random.default_rng(2)
     rows, cols = np.sort(rng.choice(n, 64, replace=False)), np.sort(rng.choice(n, 64, replace=False))
