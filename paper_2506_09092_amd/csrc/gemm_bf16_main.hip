@@ -8,25 +8,36 @@
 //                256 accumulator registers (the whole AccVGPR file)
 //   K-tile     : 64 elements = one 128-byte row per tile row, 4 MFMA k-steps
 //   LDS        : two stages of (A 32 KB + B 32 KB); stage t%2 is read while
-//                stage (t+1)%2 is filled
-//   registers  : two staging sets of 16 x 16 bytes per lane hold K-tiles t+2 and
-//                t+3 while they are in flight from L2/HBM, so a load has two
-//                full K-tiles of MFMA work to land before it is needed
+//                stage (t+1)%2 is filled by direct global->LDS loads
 //
 // A large tile is what keeps the path inside the L2 bandwidth: each K-tile
 // moves 64 KB into the workgroup for 33.5 MFLOP.  With one wavefront per SIMD
-// nothing else can fill an issue bubble, so the loop is written as an explicit
-// schedule: every MFMA is followed by exactly one other instruction (an LDS
-// fragment read, an LDS store of staged data, or a global load) and the pairs
-// are fenced so the compiler keeps that order.  Per K-tile that is 64 MFMAs,
-// 32 LDS reads, 16 LDS writes, 16 global loads and one workgroup barrier,
-// placed after the third k-step, when this stage's last fragments are already
-// in registers and the next stage is completely written.
+// nothing else can fill an issue bubble, so the loop is an explicit schedule:
+// every MFMA is followed by at most one other instruction (an LDS fragment
+// read or a global->LDS load) and the pairs are fenced so the compiler keeps
+// that order.  Measured on this part, a 16-byte LDS read in an MFMA's shadow
+// costs about 4 cycles and a global->LDS load about 5, while a global load that
+// returns into VGPRs stalls the matrix pipe for about 32; hence the operands
+// never pass through registers on their way to LDS.
+//
+// Per K-tile: 64 MFMAs, 32 LDS reads, 16 global->LDS loads, one prefetch touch
+// and one workgroup barrier.  The barrier sits after the third k-step: by then
+// this stage's last fragments are in registers and the next stage has landed,
+// so the stage just read can be refilled (for K-tile t+2) during the fourth
+// k-step and the first k-step of the next K-tile.
+//
+// That leaves a load roughly three k-steps to arrive, enough for an L2 hit but
+// not for a first touch that has to come over the fabric.  Each workgroup
+// therefore also touches, several K-tiles ahead, its share of the operand rows
+// that the workgroups running beside it on the same XCD read as well (with the
+// tile order of tile_coords, 4 neighbours share an A panel and 8 share a B
+// panel): one 4-byte global->LDS load per wavefront whose lanes each hit a
+// different 128-byte line.  The data is discarded; the lines are then in L2
+// when the real loads of all sharers arrive.
 //
 // LDS rows are 128 bytes, unpadded; 16-byte chunk c of row r is stored at chunk
 // position c ^ ((r >> 1) & 7).  A 16-lane group of a 128-bit LDS read then
-// touches all 64 banks once (rows r, r+1 fill the two 128-byte halves of a bank
-// row, the XOR spreads 8 row pairs over the 8 chunk positions).
+// touches all 64 banks once (measured: zero bank conflicts).
 #include <type_traits>
 
 #include "common.hpp"
@@ -34,10 +45,17 @@
 namespace fsrgemm {
 namespace {
 
+#define FSR_AS1 __attribute__((address_space(1)))
+#define FSR_AS3 __attribute__((address_space(3)))
+
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kTileBytes = kBM * kBK * 2;       // one operand tile: 32 KB
 constexpr int kStageBytes = 2 * kTileBytes;     // A + B: 64 KB
+constexpr int kScratchBytes = 1024;             // landing zone of the prefetch touches (256 B per wavefront)
+constexpr int kLdsBytes = 2 * kStageBytes + kScratchBytes;
 constexpr int kThreads = 256;
+constexpr int kEarly = 8;        // loads of a K-tile issued right after the barrier; the other 8 one k-step later
+constexpr int kTouchAhead = 4;   // K-tiles between a prefetch touch and the loads it serves
 
 struct Frag {
     bf16x8 a[4];
@@ -56,33 +74,46 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
     const int li = lane & 31, lh = lane >> 5;
     const int nk = g.K / kBK;
-
-    // Global side: per pass s = 0..7 the workgroup fetches 32 rows; lane covers
-    // row (tid >> 3) + 32 s, chunk tid & 7, so a wavefront reads 8 full 128-byte rows.
-    const int grow = tid >> 3, gchunk = tid & 7;
     const uint16_t *A = static_cast<const uint16_t *>(g.A);
     const uint16_t *B = static_cast<const uint16_t *>(g.B);
-    const uint32_t a_lane = (uint32_t)(grow * g.lda + gchunk * 8) * 2u;
-    const uint32_t b_lane = (uint32_t)(grow * g.ldb + gchunk * 8) * 2u;
-    const char *a_base = reinterpret_cast<const char *>(A + (int64_t)m0 * g.lda);
-    const char *b_base = reinterpret_cast<const char *>(B + (int64_t)n0 * g.ldb);
-    const int64_t a_step = 32 * g.lda * 2, b_step = 32 * g.ldb * 2;
 
-    u32x4 ra[2][8], rb[2][8];       // two staging sets
-    // idx 0..7: pass idx of A, 8..15: pass idx-8 of B.  Tiles past the end are
-    // clamped to the last one: the data is loaded but never consumed.
-    auto gload = [&](int set, int idx, int t) {
+    // Global -> LDS.  A load instruction moves 64 x 16 bytes to 1 KB of contiguous LDS = 8 tile rows.
+    // Wavefront w fills rows 64 w + 8 q + lane/8 (q = 0..7) of the A tile and of the B tile; the lane
+    // fetches the chunk that belongs at its LDS position: (lane % 8) ^ ((row >> 1) & 7).
+    const int lrow = lane >> 3, lpos = lane & 7;
+    // ((64 w + 8 q + lrow) >> 1) & 7 = 4 (q & 1) + (lrow >> 1): one lane offset for even q, one for odd q
+    const int sw_even = (lrow >> 1) & 3, sw_odd = sw_even ^ 4;
+    const uint32_t a_lane[2] = {(uint32_t)(lrow * g.lda + (lpos ^ sw_even) * 8) * 2u,
+                                (uint32_t)(lrow * g.lda + (lpos ^ sw_odd) * 8) * 2u};
+    const uint32_t b_lane[2] = {(uint32_t)(lrow * g.ldb + (lpos ^ sw_even) * 8) * 2u,
+                                (uint32_t)(lrow * g.ldb + (lpos ^ sw_odd) * 8) * 2u};
+    const char *a_base = reinterpret_cast<const char *>(A + (int64_t)(m0 + wave * 64) * g.lda);
+    const char *b_base = reinterpret_cast<const char *>(B + (int64_t)(n0 + wave * 64) * g.ldb);
+    const int64_t a_step = 8 * g.lda * 2, b_step = 8 * g.ldb * 2;
+    // idx 0..7: A rows 8 idx.., 8..15: B rows 8 (idx-8)...  K-tiles past the end are clamped to the
+    // last one: the data lands in a stage that is never read again.
+    auto dma = [&](int stage, int idx, int t) {
         const int tc = t < nk ? t : nk - 1;
-        if (idx < 8)
-            ra[set][idx] = *reinterpret_cast<const u32x4 *>(a_base + idx * a_step + (int64_t)tc * (kBK * 2) + a_lane);
-        else
-            rb[set][idx - 8] =
-                *reinterpret_cast<const u32x4 *>(b_base + (idx - 8) * b_step + (int64_t)tc * (kBK * 2) + b_lane);
+        const int q = idx & 7;
+        char *dst = smem + stage * kStageBytes + (idx < 8 ? 0 : kTileBytes) + (wave * 64 + q * 8) * 128;
+        const uint32_t lane_off = idx < 8 ? a_lane[q & 1] : b_lane[q & 1];
+        const char *src = (idx < 8 ? a_base + q * a_step : b_base + q * b_step) + (int64_t)tc * (kBK * 2) + lane_off;
+        __builtin_amdgcn_global_load_lds((const FSR_AS1 void *)src, (FSR_AS3 void *)dst, 16, 0, 0);
     };
-    const int w_off = grow * 128 + ((gchunk ^ ((grow >> 1) & 7)) * 16);
-    auto lwrite = [&](int stage, int set, int idx) {
-        char *p = smem + stage * kStageBytes + w_off + (idx < 8 ? idx * 4096 : kTileBytes + (idx - 8) * 4096);
-        *reinterpret_cast<u32x4 *>(p) = idx < 8 ? ra[set][idx] : rb[set][idx - 8];
+
+    // Prefetch touches: lanes 0-15 take A rows 64 (tile_n % 4) + 16 w + lane, lanes 16-23 take B rows
+    // 32 (tile_m % 8) + 8 w + (lane - 16); the remaining lanes repeat lane 0 and coalesce with it.
+    const char *touch_ptr;
+    {
+        const int tl = lane < 24 ? lane : 0;
+        touch_ptr = tl < 16
+            ? reinterpret_cast<const char *>(A + (int64_t)(m0 + (tile_n & 3) * 64 + wave * 16 + tl) * g.lda)
+            : reinterpret_cast<const char *>(B + (int64_t)(n0 + (tile_m & 7) * 32 + wave * 8 + (tl - 16)) * g.ldb);
+    }
+    auto touch = [&](int t) {
+        const int tc = t < nk ? t : nk - 1;
+        __builtin_amdgcn_global_load_lds((const FSR_AS1 void *)(touch_ptr + (int64_t)tc * (kBK * 2)),
+                                         (FSR_AS3 void *)(smem + 2 * kStageBytes + wave * 256), 4, 0, 0);
     };
 
     // Fragment reads: block row li of the wavefront's A (or B) rows, k-chunk 2 kk + lh.
@@ -113,11 +144,12 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // One K-tile t of parity P.  Reads stage P; stores K-tile t+1 (staging set
-    // 1-P) into stage 1-P and refills that set with K-tile t+3.
+    // One K-tile t of parity P: reads stage X = P; K-tile t+1 lands in Y = 1-P.  Of K-tile t+1's 16
+    // loads the first kEarly were issued in k-step 3 of K-tile t-1, the rest go out in k-step 0 here;
+    // k-step 3 starts refilling X with K-tile t+2.
     auto k_tile = [&](auto parity, int t) {
         constexpr int P = decltype(parity)::value;
-        constexpr int X = P, Y = 1 - P, SET = 1 - P;
+        constexpr int X = P, Y = 1 - P;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             const int fc = kk & 1, fn = fc ^ 1;
@@ -127,38 +159,33 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
                                                                              acc[m >> 2][m & 3], 0, 0, 0);
                 if (m < 8) {                        // fragments of the next k-step (next stage after the barrier)
                     if (kk < 3) lread(X, kk + 1, fn, m); else lread(Y, 0, fn, m);
-                } else {                            // 16 LDS stores, each register reloaded only after its store
+                } else {
                     const int c = m - 8;
-                    if (kk == 0) { if (c < 7) lwrite(Y, SET, c); else gload(SET, 0, t + 3); }
-                    else if (kk == 1) { if (c < 6) lwrite(Y, SET, 7 + c); else gload(SET, 1 + (c - 6), t + 3); }
-                    else if (kk == 2) { if (c < 3) lwrite(Y, SET, 13 + c); else gload(SET, 3 + (c - 3), t + 3); }
-                    else gload(SET, 8 + c, t + 3);
+                    if (kk == 3) dma(X, c, t + 2);
+                    else if (kk == 0) dma(Y, kEarly + c, t + 1);
+                    else if (kk == 1 && c == 7) touch(t + kTouchAhead);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (kk == 2) {
-                // every wavefront has its last fragments of stage X in registers and has finished
-                // writing stage Y: after this barrier Y may be read and X may be overwritten
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                // All loads but the newest (the touch) have landed: K-tile t+1 is complete in Y.  Every
+                // wavefront also has its last fragments of X in registers, so after the barrier Y may be
+                // read and X overwritten.
+                asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
 
-    // Prologue: K-tiles 0 and 1 into the staging sets, 0 on into stage 0, set 0 refilled with K-tile 2.
+    // Prologue: K-tile 0 into stage 0, then the early half of K-tile 1 into stage 1 and the first fragments.
 #pragma unroll
-    for (int idx = 0; idx < 16; ++idx) gload(0, idx, 0);
-#pragma unroll
-    for (int idx = 0; idx < 16; ++idx) gload(1, idx, 1);
-#pragma unroll
-    for (int idx = 0; idx < 16; ++idx) lwrite(0, 0, idx);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int idx = 0; idx < 16; ++idx) gload(0, idx, 2);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    for (int idx = 0; idx < 16; ++idx) dma(0, idx, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int idx = 0; idx < kEarly; ++idx) dma(1, idx, 1);
 #pragma unroll
     for (int idx = 0; idx < 8; ++idx) lread(0, 0, 0, idx);
     __builtin_amdgcn_sched_barrier(0);
@@ -169,6 +196,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         k_tile(std::integral_constant<int, 1>{}, t + 1);
     }
     if (t < nk) k_tile(std::integral_constant<int, 0>{}, t);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no load may still be writing LDS when the wavefront ends
 
     // Register r of a 32x32 block holds row (r/4)*8 + 4*(lane/32) + r%4, column lane%32.
     float *__restrict__ C = g.C;
@@ -196,12 +224,12 @@ hipError_t launch_bf16_main(const GemmArgs &a, hipStream_t s)
     static bool configured = false;     // idempotent attribute: a race between first calls is benign
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_main_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int tiles_m = a.M / kBM, tiles_n = a.N / kBN;
-    hipLaunchKernelGGL(gemm_bf16_main_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), 2 * kStageBytes, s, a,
+    hipLaunchKernelGGL(gemm_bf16_main_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLdsBytes, s, a,
                        tiles_m, tiles_n);
     return hipGetLastError();
 }
