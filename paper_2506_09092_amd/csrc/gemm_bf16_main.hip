@@ -20,8 +20,8 @@
 // returns into VGPRs stalls the matrix pipe for about 32; hence the operands
 // never pass through registers on their way to LDS.
 //
-// Per K-tile: 64 MFMAs, 32 LDS reads, 16 global->LDS loads, one prefetch touch
-// and one workgroup barrier.  The barrier sits after the third k-step: by then
+// Per K-tile: 64 MFMAs, 32 LDS reads (even slots), 16 global->LDS loads and one
+// prefetch touch (odd slots) and one workgroup barrier.  The barrier sits after the third k-step: by then
 // this stage's last fragments are in registers and the next stage has landed,
 // so the stage just read can be refilled (for K-tile t+2) during the fourth
 // k-step and the first k-step of the next K-tile.
@@ -157,13 +157,13 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
             for (int m = 0; m < 16; ++m) {
                 acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F[fc].a[m >> 2], F[fc].b[m & 3],
                                                                              acc[m >> 2][m & 3], 0, 0, 0);
-                if (m < 8) {                        // fragments of the next k-step (next stage after the barrier)
-                    if (kk < 3) lread(X, kk + 1, fn, m); else lread(Y, 0, fn, m);
-                } else {
-                    const int c = m - 8;
+                if ((m & 1) == 0) {                 // even slots: fragments of the next k-step (next stage after the barrier)
+                    if (kk < 3) lread(X, kk + 1, fn, m >> 1); else lread(Y, 0, fn, m >> 1);
+                } else {                            // odd slots: loads, so that LDS reads never queue back to back
+                    const int c = m >> 1;
                     if (kk == 3) dma(X, c, t + 2);
                     else if (kk == 0) dma(Y, kEarly + c, t + 1);
-                    else if (kk == 1 && c == 7) touch(t + kTouchAhead);
+                    else if (kk == 1 && c == 0) touch(t + kTouchAhead);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
