@@ -178,12 +178,17 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         }
     };
 
-    // Prologue: K-tile 0 into stage 0, then the early half of K-tile 1 into stage 1 and the first fragments.
+    // Prologue: K-tile 0 into stage 0 and touches for the K-tiles the loop's own touches come too late for;
+    // only K-tile 0 is waited for (the touches are the youngest kTouchAhead - 1 loads).
 #pragma unroll
     for (int idx = 0; idx < 16; ++idx) dma(0, idx, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int p = 1; p < kTouchAhead; ++p) touch(p);
+    static_assert(kTouchAhead == 4, "the wait below skips kTouchAhead - 1 touches");
+    asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
+    // then the early half of K-tile 1 into stage 1 and the first fragments
 #pragma unroll
     for (int idx = 0; idx < kEarly; ++idx) dma(1, idx, 1);
 #pragma unroll
