@@ -126,6 +126,33 @@ def report(w, t, lib):
     )
 
 
+def paper_task2_sizes(lib, torch, launches=5):
+    """Latency of the paper's own Task 2 shapes (appendix input-size table): A (size, 4096), B (4096, 2048), fp32,
+    size = 2^10 .. 2^18.  Profiler leg only; values are random normal (correctness of these shapes is a GPU test)."""
+    out = []
+    K, N = 4096, 2048
+    b = torch.randn(K, N, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    for e in (10, 12, 14, 16, 18):
+        M = 1 << e
+        a = torch.randn(M, K, device="cuda")
+        c = torch.empty(M, N, device="cuda")
+        for _ in range(2):
+            lib.check(lib.gemm_f32(M, N, K, a, K, b, N, c, N, stream))
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
+        for e0, e1 in evs:
+            e0.record()
+            lib.check(lib.gemm_f32(M, N, K, a, K, b, N, c, N, stream))
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sorted(x.elapsed_time(y) for x, y in evs)[launches // 2]
+        out.append({"size": M, "kernel": lib.fsrgemm_kernel_for_f32(M, N, K, a, K, b, N, c, N), "ms": ms,
+                    "tflops": 2.0 * M * N * K / (ms * 1e-3) / 1e12})
+        del a, c
+    return out
+
+
 def cpu_baseline(w):
     """The oracle as it stands, timed on the host cores over a slab of rows of the same workload."""
     import oracle
@@ -186,6 +213,9 @@ def main():
         del w
         torch.cuda.empty_cache()
 
+    task2 = paper_task2_sizes(lib, torch)
+    torch.cuda.empty_cache()
+
     if args.copy_calibration:
         src = torch.empty(1 << 28, device="cuda", dtype=torch.float32).fill_(1.0)
         dst = torch.empty_like(src)
@@ -206,6 +236,7 @@ def main():
         "cpu_baseline": baselines.get(args.workload),
         "other_workload": other,
         "sweep": sweep,
+        "paper_task2_shapes": task2,
         "paper_context": "paper reports only speedups over hand-written CUDA for the group holding Task 2: 5.95-68.3x (RTX 3090 Ti), 6.06-60.0x (GTX 1660 SUPER)",
     }
     print(json.dumps(out), flush=True)

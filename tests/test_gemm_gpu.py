@@ -210,6 +210,36 @@ def test_bf16_8192_full_size(gpu):
     assert oracle.freivalds_residual(A, Bt.T, got) <= TOL_BF16
 
 
+def test_f32_paper_task2_largest_size(gpu):
+    # the paper's largest Task 2 input (input-size table): A (2^18, 4096), B (4096, 2048).  A is 4 GiB, so element
+    # offsets reach 2^30 and byte offsets 2^32: this is the 64-bit indexing case.  A is built from one seeded
+    # 4096-row block repeated 64 times with a different power-of-two scale per copy, so a row fetched from the
+    # wrong copy would not pass.
+    import torch
+
+    M, N, K = 1 << 18, 2048, 4096
+    say("fp32 %dx%dx%d (paper Task 2, size 2^18)" % (M, N, K))
+    block = inputs.uniform_pm1(5, 11, 4096, K)
+    B = inputs.uniform_pm1(5, 12, K, N)
+    A = np.empty((M, K), dtype=np.float32)
+    for b in range(64):
+        A[b * 4096:(b + 1) * 4096] = block * np.float32(2.0 ** ((b % 5) - 2))
+    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == "gemm_f32_sched_kernel<4, 2, 2>"
+    a, b_, c = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), torch.full((M, N), float("nan"), device="cuda")
+    gpu.check(gpu.gemm_f32(M, N, K, a, K, b_, N, c, N, torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(18)
+    rows = np.unique(np.concatenate([rng.integers(0, M, 96), np.arange(0, M, 4096), np.arange(4095, M, 4096), [M - 1]]))
+    got = c[torch.from_numpy(rows).cuda()].cpu().numpy()
+    ref, S = oracle.gemm(A[rows], B)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+    cols = np.sort(rng.choice(N, 8, replace=False))
+    got_cols = c[:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    assert np.all(np.isfinite(got_cols))
+    ref, S = oracle.gemm(A, np.ascontiguousarray(B[:, cols]))
+    assert oracle.componentwise_error(got_cols, ref, S) <= TOL_F32
+
+
 def test_f32_paper_task2_shape(gpu):
     # the paper's own Task 2 operand shapes (input-size table): A (size, 4096), B (4096, 2048); smallest size
     say("fp32 1024x2048x4096 (paper Task 2, size 2^10)")
