@@ -46,6 +46,7 @@ int plan_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const
     if (vec && K % 16 == 0 && K >= 16) {
         if (M % 256 == 0 && N % 128 == 0 && (M / 256) * (N / 128) >= 384) p->cfg = kF32_Sched256x128, p->mode = kFast;
         else if (M % 128 == 0 && N % 128 == 0 && (M / 128) * (N / 128) >= 256) p->cfg = kF32_Sched128x128, p->mode = kFast;
+        else if (M % 64 == 0 && N % 64 == 0) p->cfg = kF32_Sched64x64, p->mode = kFast;
     }
     return FSRGEMM_OK;
 }

@@ -191,7 +191,8 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_sched_kernel(Gem
     constexpr int NA = BM / 64, NB = BN / 64, NG = NA + NB;   // 16-byte vectors per lane per K-tile
     constexpr int NR = TM + 4 * TN;                           // fragment reads per 8-k chunk
     constexpr int NMF = 4 * TM * TN;                          // MFMAs per chunk
-    static_assert(NMF >= NR + NG, "a chunk needs one MFMA slot per companion instruction");
+    constexpr int NC = NR + NG;                               // companion instructions per chunk
+    constexpr int PER_SLOT = (NC + NMF - 1) / NMF;            // 1 for the large tiles, 2 for 64 x 64
 
     __shared__ __attribute__((aligned(16))) float As[2 * A_ST];
     __shared__ __attribute__((aligned(16))) float Bs[2 * B_ST];
@@ -261,10 +262,13 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_sched_kernel(Gem
             for (int m = 0; m < NMF; ++m) {
                 const int tt = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[fc][i][tt], fb[fc][j][tt], acc[i][j], 0, 0, 0);
-                if (m < NR) {
-                    if (kk == 0) lread(X, 1, fn, m); else lread(Y, 0, fn, m);
-                } else if (m < NR + NG) {
-                    if (kk == 0) lwrite(Y, m - NR); else gload(m - NR, t + 2);
+#pragma unroll
+                for (int c = m * PER_SLOT; c < (m + 1) * PER_SLOT && c < NC; ++c) {
+                    if (c < NR) {
+                        if (kk == 0) lread(X, 1, fn, c); else lread(Y, 0, fn, c);
+                    } else {
+                        if (kk == 0) lwrite(Y, c - NR); else gload(c - NR, t + 2);
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -343,6 +347,7 @@ const char *f32_kernel_name(int cfg, int mode)
     };
     if (cfg == kF32_Sched256x128) return "gemm_f32_sched_kernel<4, 2, 2>";
     if (cfg == kF32_Sched128x128) return "gemm_f32_sched_kernel<2, 2, 3>";
+    if (cfg == kF32_Sched64x64) return "gemm_f32_sched_kernel<1, 1, 4>";
     return names[cfg - kF32_128x128][mode];
 }
 
@@ -351,6 +356,7 @@ hipError_t launch_f32(int cfg, int mode, const GemmArgs &a, hipStream_t s)
     switch (cfg) {
     case kF32_Sched256x128: return launch_sched<4, 2, 2>(a, s);
     case kF32_Sched128x128: return launch_sched<2, 2, 3>(a, s);
+    case kF32_Sched64x64: return launch_sched<1, 1, 4>(a, s);
     case kF32_128x128: return launch_cfg<128, 128>(mode, a, s);
     default: return launch_cfg<64, 64>(mode, a, s);
     }
