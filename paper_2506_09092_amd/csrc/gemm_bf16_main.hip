@@ -55,7 +55,8 @@ constexpr int kScratchBytes = 1024;             // landing zone of the prefetch 
 constexpr int kLdsBytes = 2 * kStageBytes + kScratchBytes;
 constexpr int kThreads = 256;
 constexpr int kEarly = 8;        // loads of a K-tile issued right after the barrier; the other 8 one k-step later
-constexpr int kTouchAhead = 4;   // K-tiles between a prefetch touch and the loads it serves
+constexpr int kTouchAhead = 3;   // K-tiles between a prefetch touch and the loads it serves: 2 is too late, 4 and
+                                 // more let touched lines be evicted before use (more fabric reads, same time)
 
 struct Frag {
     bf16x8 a[4];
@@ -184,8 +185,8 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     for (int idx = 0; idx < 16; ++idx) dma(0, idx, 0);
 #pragma unroll
     for (int p = 1; p < kTouchAhead; ++p) touch(p);
-    static_assert(kTouchAhead == 4, "the wait below skips kTouchAhead - 1 touches");
-    asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+    static_assert(kTouchAhead == 3, "the wait below skips kTouchAhead - 1 touches");
+    asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     // then the early half of K-tile 1 into stage 1 and the first fragments
