@@ -32,22 +32,18 @@ int check_args(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, cons
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Largest tile whose grid still gives every compute unit work; the small tile
-// otherwise.  Grids beyond 2^31 - 1 workgroups are rejected.
+// The largest tile whose grid still fills the chip (256 compute units, two or more workgroups each for the
+// smaller tiles); the load mode follows from alignment and divisibility.  Grids beyond 2^31 - 1 workgroups are
+// rejected.
 int plan_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb, Plan *p)
 {
-    const bool big = ceil_div(M, 128) * ceil_div(N, 128) >= 256;
-    const int bm = big ? 128 : 64, bn = bm;
+    int bm, bn;
+    if (ceil_div(M, 256) * ceil_div(N, 128) >= 384) p->cfg = kF32_256x128, bm = 256, bn = 128;
+    else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kF32_128x128, bm = 128, bn = 128;
+    else p->cfg = kF32_64x64, bm = 64, bn = 64;
     if (ceil_div(M, bm) * ceil_div(N, bn) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
     const bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
-    p->cfg = big ? kF32_128x128 : kF32_64x64;
-    p->mode = !vec ? kScalar : (M % bm == 0 && N % bn == 0 && K % 16 == 0) ? kFast : kVecPred;
-    // scheduled kernels: whole tiles only, and enough of them to occupy the chip
-    if (vec && K % 16 == 0 && K >= 16) {
-        if (M % 256 == 0 && N % 128 == 0 && (M / 256) * (N / 128) >= 384) p->cfg = kF32_Sched256x128, p->mode = kFast;
-        else if (M % 128 == 0 && N % 128 == 0 && (M / 128) * (N / 128) >= 256) p->cfg = kF32_Sched128x128, p->mode = kFast;
-        else if (M % 64 == 0 && N % 64 == 0) p->cfg = kF32_Sched64x64, p->mode = kFast;
-    }
+    p->mode = !vec ? kScalar : (M % bm == 0 && N % bn == 0 && K % 16 == 0 && K > 0) ? kFast : kVecPred;
     return FSRGEMM_OK;
 }
 

@@ -53,9 +53,8 @@ struct GemmArgs {
 //   kScalar:  element-wise predicated loads (any alignment, any shape)
 enum LoadMode { kFast = 0, kVecPred = 1, kScalar = 2 };
 
-// fp32 tile configurations (gemm_f32.hip): two scheduled kernels for aligned tile-multiple problems,
-// two general-purpose predicated ones
-enum F32Config { kF32_Sched256x128 = 0, kF32_Sched128x128 = 1, kF32_Sched64x64 = 2, kF32_128x128 = 3, kF32_64x64 = 4, kF32ConfigCount };
+// fp32 tile configurations (gemm_f32.hip), each available in the three load modes
+enum F32Config { kF32_256x128 = 0, kF32_128x128 = 1, kF32_64x64 = 2, kF32ConfigCount };
 // Names are substrings of the kernel symbols as a profiler trace prints them.
 const char *f32_kernel_name(int cfg, int mode);
 hipError_t launch_f32(int cfg, int mode, const GemmArgs &a, hipStream_t s);

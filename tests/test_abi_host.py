@@ -64,8 +64,11 @@ def test_dispatch_query_names_variants():
     fast = q(4096, 4096, 4096, P, 4096, P, 4096, P, 4096)
     ragged = q(4097, 17, 1000, P, 1000, P, 20, P, 17)
     unaligned = q(123, 5, 8, P + 4, 8, P + 4, 5, P, 5)
-    assert fast == "gemm_f32_sched_kernel<4, 2, 2>"                          # scheduled 256x128 kernel <TM, TN, min waves>
-    assert ragged == "gemm_f32_kernel<64, 64, 1>" and unaligned == "gemm_f32_kernel<64, 64, 2>"
+    # <TM, TN, min waves, load mode>: tile (64 TM) x (64 TN); mode 0 unchecked vectors, 1 vectors + predicated edges, 2 scalar
+    assert fast == "gemm_f32_kernel<4, 2, 2, 0>"
+    assert ragged == "gemm_f32_kernel<1, 1, 4, 1>" and unaligned == "gemm_f32_kernel<1, 1, 4, 2>"
+    assert q(4097, 4097, 129, P, 132, P, 4100, P, 4097) == "gemm_f32_kernel<4, 2, 2, 1>"
+    assert q(64, 64, 0, P, 4, P, 64, P, 64) == "gemm_f32_kernel<1, 1, 4, 1>"                    # K = 0 never takes the unchecked mode
     assert q(4, 4, 4, P, 3, P, 4, P, 4) is None
     qb = lib.fsrgemm_kernel_for_bf16
     assert qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel"

@@ -105,16 +105,16 @@ def test_bf16_big_tile_config_ragged(gpu):
     check_bf16(gpu, A, Bt)
 
 
-@pytest.mark.parametrize("shape,kernel", [((2048, 2048, 16), "gemm_f32_sched_kernel<2, 2, 3>"),
-                                          ((2048, 2048, 32), "gemm_f32_sched_kernel<2, 2, 3>"),
-                                          ((2048, 2048, 112), "gemm_f32_sched_kernel<2, 2, 3>"),
-                                          ((4096, 3072, 16), "gemm_f32_sched_kernel<4, 2, 2>"),
-                                          ((4096, 3072, 48), "gemm_f32_sched_kernel<4, 2, 2>"),
-                                          ((4096, 3072, 160), "gemm_f32_sched_kernel<4, 2, 2>")])
-def test_f32_scheduled_kernels_small_k(gpu, shape, kernel):
-    # prologue, odd/even K-tile tails and the clamped prefetch of the scheduled kernels; full oracle comparison
+@pytest.mark.parametrize("shape,kernel", [((2048, 2048, 16), "gemm_f32_kernel<2, 2, 3, 0>"),
+                                          ((2048, 2048, 32), "gemm_f32_kernel<2, 2, 3, 0>"),
+                                          ((2048, 2048, 112), "gemm_f32_kernel<2, 2, 3, 0>"),
+                                          ((4096, 3072, 16), "gemm_f32_kernel<4, 2, 2, 0>"),
+                                          ((4096, 3072, 48), "gemm_f32_kernel<4, 2, 2, 0>"),
+                                          ((4096, 3072, 160), "gemm_f32_kernel<4, 2, 2, 0>")])
+def test_f32_tile_configs_small_k(gpu, shape, kernel):
+    # prologue, odd/even K-tile tails and the clamped prefetch of the two large tile configurations; full oracle comparison
     M, N, K = shape
-    say("fp32 scheduled kernel %dx%dx%d" % shape)
+    say("fp32 %dx%dx%d" % shape)
     assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == kernel
     A, B = inputs.uniform_pm1(6, K, M, K), inputs.uniform_pm1(6, K + 1, K, N)
     check_f32(gpu, A, B, repeat=2)
@@ -171,7 +171,7 @@ def test_f32_4096_normal_full_size(gpu):
     say("fp32 4096^3 normal seed 2 (sampled rows, columns, entries + Freivalds)")
     n = 4096
     A, B = inputs.normal(2, 1, n, n), inputs.normal(2, 2, n, n)
-    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_sched_kernel<4, 2, 2>"
+    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_kernel<4, 2, 2, 0>"
     got = run_f32(gpu, A, B)
     rng = np.random.default_rng(2)
     rows, cols = np.sort(rng.choice(n, 64, replace=False)), np.sort(rng.choice(n, 64, replace=False))
@@ -224,7 +224,7 @@ def test_f32_paper_task2_largest_size(gpu):
     A = np.empty((M, K), dtype=np.float32)
     for b in range(64):
         A[b * 4096:(b + 1) * 4096] = block * np.float32(2.0 ** ((b % 5) - 2))
-    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == "gemm_f32_sched_kernel<4, 2, 2>"
+    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == "gemm_f32_kernel<4, 2, 2, 0>"
     a, b_, c = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), torch.full((M, N), float("nan"), device="cuda")
     gpu.check(gpu.gemm_f32(M, N, K, a, K, b_, N, c, N, torch.cuda.current_stream().cuda_stream))
     torch.cuda.synchronize()
