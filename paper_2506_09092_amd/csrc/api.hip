@@ -50,14 +50,15 @@ int plan_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const
 int plan_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
               Plan *p)
 {
-    const bool big = ceil_div(M, 256) * ceil_div(N, 256) >= 128;
-    const int bm = big ? 256 : 128, bn = bm;
-    if (ceil_div(M, bm) * ceil_div(N, bn) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
+    int b;
+    if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) p->cfg = kBf16_256x256, b = 256;
+    else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kBf16_128x128, b = 128;
+    else p->cfg = kBf16_64x64, b = 64;
+    if (ceil_div(M, b) * ceil_div(N, b) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
     const bool vec = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0;
-    p->cfg = big ? kBf16_256x256 : kBf16_128x128;
-    p->mode = !vec ? kScalar : (M % bm == 0 && N % bn == 0 && K % 64 == 0) ? kFast : kVecPred;
-    // the scheduled kernel needs whole tiles and 32-bit lane offsets
-    if (big && p->mode == kFast && K >= 64 && lda < (1 << 25) && ldb < (1 << 25)) p->cfg = kBf16_Main;
+    p->mode = !vec ? kScalar : (M % b == 0 && N % b == 0 && K % 64 == 0 && K > 0) ? kFast : kVecPred;
+    // the direct-to-LDS kernel needs whole 256 x 256 x 64 tiles and 32-bit lane offsets
+    if (b == 256 && p->mode == kFast && lda < (1 << 25) && ldb < (1 << 25)) p->cfg = kBf16_Main;
     return FSRGEMM_OK;
 }
 

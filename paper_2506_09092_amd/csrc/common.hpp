@@ -59,9 +59,9 @@ enum F32Config { kF32_256x128 = 0, kF32_128x128 = 1, kF32_64x64 = 2, kF32ConfigC
 const char *f32_kernel_name(int cfg, int mode);
 hipError_t launch_f32(int cfg, int mode, const GemmArgs &a, hipStream_t s);
 
-// bf16 tile configurations: the scheduled 256x256 kernel for aligned, tile-multiple problems
-// (gemm_bf16_main.hip) and two predicated general-purpose configurations (gemm_bf16.hip)
-enum Bf16Config { kBf16_Main = 0, kBf16_256x256 = 1, kBf16_128x128 = 2, kBf16ConfigCount };
+// bf16 configurations: the direct-to-LDS 256x256 kernel for aligned, tile-multiple problems
+// (gemm_bf16_main.hip) and three tile sizes of the general kernel (gemm_bf16.hip), each in the three load modes
+enum Bf16Config { kBf16_Main = 0, kBf16_256x256 = 1, kBf16_128x128 = 2, kBf16_64x64 = 3, kBf16ConfigCount };
 const char *bf16_kernel_name(int cfg, int mode);
 hipError_t launch_bf16(int cfg, int mode, const GemmArgs &a, hipStream_t s);
 const char *bf16_main_kernel_name();

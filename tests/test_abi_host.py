@@ -72,6 +72,8 @@ def test_dispatch_query_names_variants():
     assert q(4, 4, 4, P, 3, P, 4, P, 4) is None
     qb = lib.fsrgemm_kernel_for_bf16
     assert qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel"
-    assert qb(8192, 8192, 8200, P, 8200, P, 8200, P, 8192) == "gemm_bf16_kernel<256, 256, 2, 4, 1>"   # K not a multiple of 64
-    assert qb(100, 100, 100, P, 100, P, 100, P, 100) == "gemm_bf16_kernel<128, 128, 2, 2, 2>"         # ld not a multiple of 8
-    assert qb(100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<128, 128, 2, 2, 1>"
+    # general kernel <T, min waves, load mode>: tile (64 T) x (64 T)
+    assert qb(8192, 8192, 8200, P, 8200, P, 8200, P, 8192) == "gemm_bf16_kernel<4, 1, 1>"   # K not a multiple of 64
+    assert qb(2048, 2048, 512, P, 512, P, 512, P, 2048) == "gemm_bf16_kernel<2, 2, 0>"
+    assert qb(100, 100, 100, P, 100, P, 100, P, 100) == "gemm_bf16_kernel<1, 4, 2>"         # ld not a multiple of 8
+    assert qb(100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1>"

@@ -76,7 +76,8 @@ def test_f32_sweep_64_shapes(gpu):
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (17, 17, 17), (128, 128, 128), (130, 70, 200), (257, 255, 129),
-                                   (33, 65, 31), (512, 384, 1000), (300, 520, 64)])
+                                   (33, 65, 31), (512, 384, 1000), (300, 520, 64),
+                                   (2048, 2048, 192), (2000, 2100, 100)])          # the last two: 128 x 128 tiles
 def test_bf16_shapes(gpu, shape):
     M, N, K = shape
     say("bf16 %dx%dx%d" % shape)
@@ -101,7 +102,7 @@ def test_bf16_big_tile_config_ragged(gpu):
     say("bf16 %dx%dx%d (256-tile, ragged)" % (M, N, K))
     A = inputs.bf16_normal_scaled(4, 40, M, K, 1 / math.sqrt(K))
     Bt = inputs.bf16_normal_scaled(4, 41, N, K, 1 / math.sqrt(K))
-    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_kernel<256, 256, 2, 4, 1>"
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_kernel<4, 1, 1>"
     check_bf16(gpu, A, Bt)
 
 
