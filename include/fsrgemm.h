@@ -23,6 +23,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default
  *     stream).  The call enqueues work and returns without synchronising.
  *   - Results are deterministic: the same inputs give bit-identical C.
+ *   - Entry points may be called from several host threads at once.
  *   - Errors are reported through the return value only.  Argument errors
  *     are detected before any HIP call is made, so they can be exercised on
  *     a machine without a GPU.

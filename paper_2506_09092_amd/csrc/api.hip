@@ -62,18 +62,22 @@ int plan_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, c
     return FSRGEMM_OK;
 }
 
-// gfx950 check for the current device, cached per device ordinal.
+// gfx950 check for the current device, cached per device ordinal (racing first calls just repeat the query).
 int device_ok()
 {
     constexpr int kMaxDev = 64;
-    static int cache[kMaxDev];     // 0 = unknown, 1 = gfx950, 2 = something else
+    static std::atomic<int> cache[kMaxDev];     // 0 = unknown, 1 = gfx950, 2 = something else
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return FSRGEMM_ERR_UNSUPPORTED_DEVICE;
-    if (dev >= 0 && dev < kMaxDev && cache[dev]) return cache[dev] == 1 ? FSRGEMM_OK : FSRGEMM_ERR_UNSUPPORTED_DEVICE;
+    const bool cached = dev >= 0 && dev < kMaxDev;
+    if (cached) {
+        const int c = cache[dev].load(std::memory_order_relaxed);
+        if (c) return c == 1 ? FSRGEMM_OK : FSRGEMM_ERR_UNSUPPORTED_DEVICE;
+    }
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return FSRGEMM_ERR_UNSUPPORTED_DEVICE;
     const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
-    if (dev >= 0 && dev < kMaxDev) cache[dev] = ok ? 1 : 2;
+    if (cached) cache[dev].store(ok ? 1 : 2, std::memory_order_relaxed);
     return ok ? FSRGEMM_OK : FSRGEMM_ERR_UNSUPPORTED_DEVICE;
 }
 
@@ -94,6 +98,23 @@ GemmArgs pack(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const
 }
 
 }  // namespace
+
+namespace fsrgemm {
+
+hipError_t ensure_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < 64;
+    const uint64_t bit = tracked ? (uint64_t)1 << dev : 0;
+    if (tracked && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && tracked) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
+}  // namespace fsrgemm
 
 extern "C" {
 

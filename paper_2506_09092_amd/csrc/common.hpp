@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace fsrgemm {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -35,6 +37,10 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
     tm = first_m + in_band % rows;
     tn = in_band / rows;
 }
+
+// Raises a kernel's dynamic-LDS limit once per device (the attribute belongs to the device's copy of the
+// kernel).  `done` is the caller's per-kernel bitmap of devices already configured; safe to call concurrently.
+hipError_t ensure_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done);
 
 struct GemmArgs {
     int M, N, K;

@@ -202,13 +202,9 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t s)
     constexpr int BM = 64 * T;
     constexpr int lds = 2 * 2 * BM * kRowBytes;
     auto kern = gemm_bf16_kernel<T, MIN_WAVES, MODE>;
-    static bool configured = false;     // raising the dynamic-LDS limit is idempotent, so a race here is benign
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static std::atomic<uint64_t> configured{0};
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, configured);
+    if (e != hipSuccess) return e;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BM - 1) / BM;
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), lds, s, a, tiles_m, tiles_n);
     return hipGetLastError();

@@ -227,13 +227,9 @@ const char *bf16_main_kernel_name() { return "gemm_bf16_main_kernel"; }
 // lda % 8 == 0, ldb % 8 == 0 and leading dimensions below 2^25 (32-bit lane offsets).
 hipError_t launch_bf16_main(const GemmArgs &a, hipStream_t s)
 {
-    static bool configured = false;     // idempotent attribute: a race between first calls is benign
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_main_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static std::atomic<uint64_t> configured{0};
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_main_kernel), kLdsBytes, configured);
+    if (e != hipSuccess) return e;
     const int tiles_m = a.M / kBM, tiles_n = a.N / kBN;
     hipLaunchKernelGGL(gemm_bf16_main_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLdsBytes, s, a,
                        tiles_m, tiles_n);

@@ -154,6 +154,45 @@ def test_degenerate_extents(gpu):
     assert gpu.gemm_bf16(4, 0, 3, None, 3, None, 3, None, 1, 0) == gpu.FSRGEMM_OK
 
 
+def test_side_streams_and_host_threads(gpu):
+    # the call enqueues on the caller's stream and may be issued from several host threads at once
+    import threading
+
+    import torch
+
+    say("side streams + host threads")
+    shapes = [(384, 320, 200), (257, 255, 129), (512, 512, 256), (130, 70, 200)]
+    data, results, errors = [], [None] * len(shapes), []
+    for idx, (M, N, K) in enumerate(shapes):
+        data.append((inputs.uniform_pm1(8, 2 * idx, M, K), inputs.uniform_pm1(8, 2 * idx + 1, K, N)))
+
+    def worker(idx):
+        try:
+            torch.cuda.set_device(0)
+            M, N, K = shapes[idx]
+            A, B = data[idx]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                a, b = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+                c = torch.full((M, N), float("nan"), device="cuda")
+                for _ in range(20):
+                    gpu.check(gpu.gemm_f32(M, N, K, a, K, b, N, c, N, stream.cuda_stream))
+                stream.synchronize()
+                results[idx] = c.cpu().numpy()
+        except Exception as ex:          # surfaced in the main thread below
+            errors.append(ex)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(len(shapes))]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    for idx, (A, B) in enumerate(data):
+        ref, S = oracle.gemm(A, B)
+        assert oracle.componentwise_error(results[idx], ref, S) <= TOL_F32
+
+
 def _sample_indices(M, N, tile, n_rand, seed):
     rng = np.random.default_rng(seed)
     ii, jj = [rng.integers(0, M, n_rand)], [rng.integers(0, N, n_rand)]
