@@ -28,8 +28,8 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense MFMA peaks
 # profiles/gemm_f32_4096_bf16_8192_hbm_traffic.txt (scaled by a 1 GiB copy).  Each entry is tied to the
 # kernel sources it was measured on: once those change the figure is stale and the bench reports null.
 TRAFFIC = {
-    "f32_4096": {"bytes": 874405812, "sources": {"gemm_f32.hip": "fd18733c0b6de127", "common.hpp": "2d0e0a351715b998"}},
-    "bf16_8192": {"bytes": 2406541670, "sources": {"gemm_bf16_main.hip": "7ba2f7442e663439", "common.hpp": "2d0e0a351715b998"}},
+    "f32_4096": {"bytes": 859409417, "sources": {"gemm_f32.hip": "1109f4d4afac0d14", "common.hpp": "698bf142b70fbd57"}},
+    "bf16_8192": {"bytes": 2097082851, "sources": {"gemm_bf16_main.hip": "c6a1c22d97fd57a6", "common.hpp": "698bf142b70fbd57"}},
 }
 
 
