@@ -4,49 +4,73 @@
 //
 // Shape of the computation
 //   workgroup  : 256 lanes = 4 wavefronts, one per SIMD, 256 x 256 tile of C
-//   wavefront  : 128 x 128 of that tile = 4 x 4 blocks of V_MFMA_F32_32X32X16_BF16,
+//   wavefront  : 128 x 128 of that tile = 8 x 8 blocks of V_MFMA_F32_16X16X32_BF16,
 //                256 accumulator registers (the whole AccVGPR file)
-//   K-tile     : 64 elements = one 128-byte row per tile row, 4 MFMA k-steps
+//   K-tile     : 64 elements = one 128-byte row per tile row, 2 MFMA k-steps of 32
 //   LDS        : two stages of (A 32 KB + B 32 KB); stage t%2 is read while
 //                stage (t+1)%2 is filled by direct global->LDS loads
 //
+// Why the 16x16x32 instruction: this part runs bf16 matrix work against its
+// power limit, not its issue rate.  Per flop the 16x16x32 form moves half the
+// accumulator data of the 32x32x16 form through the register file; a
+// register-only loop on random operands sustains about 2.0 PFLOP/s with it
+// against 1.7-1.8 with 32x32x16 (both reach 2.4 on zeros).
+//
 // A large tile is what keeps the path inside the L2 bandwidth: each K-tile
 // moves 64 KB into the workgroup for 33.5 MFLOP.  With one wavefront per SIMD
-// nothing else can fill an issue bubble, so the loop is an explicit schedule:
-// every MFMA is followed by at most one other instruction (an LDS fragment
-// read or a global->LDS load) and the pairs are fenced so the compiler keeps
-// that order.  Measured on this part, a 16-byte LDS read in an MFMA's shadow
-// costs about 4 cycles and a global->LDS load about 5, while a global load that
-// returns into VGPRs stalls the matrix pipe for about 32; hence the operands
-// never pass through registers on their way to LDS.
+// nothing else can fill an issue bubble, and a 16-cycle MFMA leaves room for
+// about three other instructions, so the loop is an explicit schedule, fenced
+// slot by slot: 128 MFMAs per K-tile carry 32 LDS fragment reads, 16
+// global->LDS loads, one prefetch touch and a handful of address updates, never
+// more than two of them behind one MFMA.
 //
-// Per K-tile: 64 MFMAs, 32 LDS reads (even slots), 16 global->LDS loads and one
-// prefetch touch (odd slots) and one workgroup barrier.  The barrier sits after the third k-step: by then
-// this stage's last fragments are in registers and the next stage has landed,
-// so the stage just read can be refilled (for K-tile t+2) during the fourth
-// k-step and the first k-step of the next K-tile.
+// The loads are issued by hand.  Through the compiler's builtin a load costs a
+// 64-bit vector add, an M0 write, a wait state and the load itself -- more than
+// a slot holds.  Here the address is a scalar row-group base (16 of them, fixed
+// for the tile) plus a 32-bit lane offset that also carries the K position (4
+// registers, advanced once per K-tile); M0 (the LDS destination) is written
+// one slot ahead, so the MFMA in between is the wait state M0 needs.
 //
-// That leaves a load roughly three k-steps to arrive, enough for an L2 hit but
-// not for a first touch that has to come over the fabric.  Each workgroup
-// therefore also touches, several K-tiles ahead, its share of the operand rows
-// that the workgroups running beside it on the same XCD read as well (with the
-// tile order of tile_coords, 4 neighbours share an A panel and 8 share a B
-// panel): one 4-byte global->LDS load per wavefront whose lanes each hit a
-// different 128-byte line.  The data is discarded; the lines are then in L2
-// when the real loads of all sharers arrive.
+// The MFMAs are inline assembly for one reason: written with the builtin, the
+// register allocator permutes the 64 four-register accumulators across the
+// loop's back edge and fills the loop with hundreds of accumulator moves.  With
+// "+a" operands every block stays where it is.  The compiler cannot see that
+// these statements are MFMAs, so the hazards it would cover are kept away by
+// construction: a block is touched again only 64 MFMAs later, and the epilogue
+// starts behind explicit wait states.
+//
+// Per K-tile t of parity P (stage X = P holds t, Y = 1 - P receives t+1):
+//   k-step 0 : MFMAs on X's first half; fragment reads of X's second half; the
+//              late loads of K-tile t+1 into Y; the prefetch touch
+//   barrier  : all loads but the touch have landed (Y complete), every
+//              wavefront has its last fragments of X in registers
+//   k-step 1 : MFMAs on X's second half; fragment reads of Y's first half; the
+//              early loads of K-tile t+2 into X
+// A load thus has at least half a K-tile (about 1000 cycles) to arrive: enough
+// for an L2 hit, not for a first touch that has to come over the fabric.  Each
+// workgroup therefore also touches, three K-tiles ahead, its share of the
+// operand rows that the workgroups running beside it on the same XCD read as
+// well (with the tile order of tile_coords, 4 neighbours share an A panel and 8
+// share a B panel): one 4-byte global->LDS load per wavefront whose lanes each
+// hit a different 128-byte line.  The data is discarded; the lines are then in
+// L2 when the real loads of all sharers arrive.
 //
 // LDS rows are 128 bytes, unpadded; 16-byte chunk c of row r is stored at chunk
-// position c ^ ((r >> 1) & 7).  A 16-lane group of a 128-bit LDS read then
-// touches all 64 banks once (measured: zero bank conflicts).
+// position c ^ ((r >> 1) & 7).  A 16-lane group of a 128-bit LDS read (16 rows,
+// one chunk) then touches all 64 banks once.
 #include <type_traits>
+#include <utility>
 
 #include "common.hpp"
 
 namespace fsrgemm {
 namespace {
 
-#define FSR_AS1 __attribute__((address_space(1)))
 #define FSR_AS3 __attribute__((address_space(3)))
+
+// M0 is on the clobber lists below on purpose (the loads take their LDS address from it); clang warns
+// that it is a reserved register.  Nothing the compiler emits for this kernel uses M0.
+#pragma clang diagnostic ignored "-Winline-asm"
 
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kTileBytes = kBM * kBK * 2;       // one operand tile: 32 KB
@@ -54,14 +78,31 @@ constexpr int kStageBytes = 2 * kTileBytes;     // A + B: 64 KB
 constexpr int kScratchBytes = 1024;             // landing zone of the prefetch touches (256 B per wavefront)
 constexpr int kLdsBytes = 2 * kStageBytes + kScratchBytes;
 constexpr int kThreads = 256;
-constexpr int kEarly = 8;        // loads of a K-tile issued right after the barrier; the other 8 one k-step later
+constexpr int kEarly = 12;       // loads of K-tile t+2 issued in k-step 1 of K-tile t; the other 4 in k-step 0 of t+1
 constexpr int kTouchAhead = 3;   // K-tiles between a prefetch touch and the loads it serves: 2 is too late, 4 and
                                  // more let touched lines be evicted before use (more fabric reads, same time)
+constexpr int kReadEvery = 3;    // a fragment read behind every third MFMA: the 16 reads of a k-step are done by slot 45
+constexpr int kLoadEvery = 4;    // a load behind every fourth MFMA (slots 2, 6, ...): denser loads stall the matrix pipe
 
 struct Frag {
-    bf16x8 a[4];
-    bf16x8 b[4];
+    bf16x8 a[8];
+    bf16x8 b[8];
 };
+
+template <int I>
+using Int = std::integral_constant<int, I>;
+
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(Int<Is>{}), ...);
+}
+// f(Int<0>{}), ..., f(Int<N-1>{}): a loop whose index is a compile-time constant in the body
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, int tiles_m, int tiles_n)
 {
@@ -73,33 +114,50 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
-    const int li = lane & 31, lh = lane >> 5;
+    const int l16 = lane & 15, lq = lane >> 4;
     const int nk = g.K / kBK;
     const uint16_t *A = static_cast<const uint16_t *>(g.A);
     const uint16_t *B = static_cast<const uint16_t *>(g.B);
 
     // Global -> LDS.  A load instruction moves 64 x 16 bytes to 1 KB of contiguous LDS = 8 tile rows.
-    // Wavefront w fills rows 64 w + 8 q + lane/8 (q = 0..7) of the A tile and of the B tile; the lane
-    // fetches the chunk that belongs at its LDS position: (lane % 8) ^ ((row >> 1) & 7).
+    // Wavefront w fills rows 64 w + 8 q + lane/8 (q = 0..7) of the A tile (load index q) and of the B
+    // tile (load index 8 + q); the lane fetches the chunk that belongs at its LDS position:
+    // (lane % 8) ^ ((row >> 1) & 7), and ((64 w + 8 q + lane/8) >> 1) & 7 = 4 (q & 1) + (lane/8 >> 1):
+    // one lane offset for even q and one for odd q, per operand.
     const int lrow = lane >> 3, lpos = lane & 7;
-    // ((64 w + 8 q + lrow) >> 1) & 7 = 4 (q & 1) + (lrow >> 1): one lane offset for even q, one for odd q
     const int sw_even = (lrow >> 1) & 3, sw_odd = sw_even ^ 4;
-    const uint32_t a_lane[2] = {(uint32_t)(lrow * g.lda + (lpos ^ sw_even) * 8) * 2u,
-                                (uint32_t)(lrow * g.lda + (lpos ^ sw_odd) * 8) * 2u};
-    const uint32_t b_lane[2] = {(uint32_t)(lrow * g.ldb + (lpos ^ sw_even) * 8) * 2u,
-                                (uint32_t)(lrow * g.ldb + (lpos ^ sw_odd) * 8) * 2u};
-    const char *a_base = reinterpret_cast<const char *>(A + (int64_t)(m0 + wave * 64) * g.lda);
-    const char *b_base = reinterpret_cast<const char *>(B + (int64_t)(n0 + wave * 64) * g.ldb);
-    const int64_t a_step = 8 * g.lda * 2, b_step = 8 * g.ldb * 2;
-    // idx 0..7: A rows 8 idx.., 8..15: B rows 8 (idx-8)...  K-tiles past the end are clamped to the
-    // last one: the data lands in a stage that is never read again.
-    auto dma = [&](int stage, int idx, int t) {
-        const int tc = t < nk ? t : nk - 1;
-        const int q = idx & 7;
-        char *dst = smem + stage * kStageBytes + (idx < 8 ? 0 : kTileBytes) + (wave * 64 + q * 8) * 128;
-        const uint32_t lane_off = idx < 8 ? a_lane[q & 1] : b_lane[q & 1];
-        const char *src = (idx < 8 ? a_base + q * a_step : b_base + q * b_step) + (int64_t)tc * (kBK * 2) + lane_off;
-        __builtin_amdgcn_global_load_lds((const FSR_AS1 void *)src, (FSR_AS3 void *)dst, 16, 0, 0);
+    // lane offsets in bytes: A even q, A odd q, B even q, B odd q; they also carry the K position
+    uint32_t voff[4] = {(uint32_t)(lrow * g.lda + (lpos ^ sw_even) * 8) * 2u,
+                        (uint32_t)(lrow * g.lda + (lpos ^ sw_odd) * 8) * 2u,
+                        (uint32_t)(lrow * g.ldb + (lpos ^ sw_even) * 8) * 2u,
+                        (uint32_t)(lrow * g.ldb + (lpos ^ sw_odd) * 8) * 2u};
+    const char *rbase[16];          // row-group bases: uniform, fixed for the tile
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        rbase[q] = reinterpret_cast<const char *>(A + (int64_t)(m0 + wave * 64 + q * 8) * g.lda);
+        rbase[8 + q] = reinterpret_cast<const char *>(B + (int64_t)(n0 + wave * 64 + q * 8) * g.ldb);
+    }
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(FSR_AS3 char *)smem);
+    const uint32_t wave_lds = lds0 + wave * (64 * 128);
+    // M0 <- LDS address of load `idx` in `stage`; at least one instruction must follow before the load
+    auto load_m0 = [&](auto stage, auto idx) {
+        constexpr int kOff = decltype(stage)::value * kStageBytes + (decltype(idx)::value < 8 ? 0 : kTileBytes) +
+                             (decltype(idx)::value & 7) * 1024;
+        const uint32_t w = wave_lds;
+        asm volatile("s_add_u32 m0, %0, %1" ::"s"(w), "n"(kOff) : "m0", "scc");
+    };
+    auto load_go = [&](auto idx) {
+        constexpr int I = decltype(idx)::value;
+        const uint32_t vo = voff[(I < 8 ? 0 : 2) + (I & 1)];
+        const char *rb = rbase[I];
+        asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(vo), "s"(rb) : "memory");
+    };
+    // after the last load of a K-tile: the lane offsets move on to K-tile `next`; past the end they stay on
+    // the last K-tile, whose data then lands once more in a stage that is never read again
+    auto advance = [&](int next) {
+        const uint32_t step = next < nk ? (uint32_t)(kBK * 2) : 0u;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) voff[q] += step;
     };
 
     // Prefetch touches: lanes 0-15 take A rows 64 (tile_n % 4) + 16 w + lane, lanes 16-23 take B rows
@@ -111,109 +169,138 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
             ? reinterpret_cast<const char *>(A + (int64_t)(m0 + (tile_n & 3) * 64 + wave * 16 + tl) * g.lda)
             : reinterpret_cast<const char *>(B + (int64_t)(n0 + (tile_m & 7) * 32 + wave * 8 + (tl - 16)) * g.ldb);
     }
-    auto touch = [&](int t) {
+    const uint32_t touch_lds = lds0 + 2 * kStageBytes + wave * 256;
+    auto touch_m0 = [&]() {
+        const uint32_t w = touch_lds;
+        asm volatile("s_mov_b32 m0, %0" ::"s"(w) : "m0");
+    };
+    auto touch_go = [&](int t) {
         const int tc = t < nk ? t : nk - 1;
-        __builtin_amdgcn_global_load_lds((const FSR_AS1 void *)(touch_ptr + (int64_t)tc * (kBK * 2)),
-                                         (FSR_AS3 void *)(smem + 2 * kStageBytes + wave * 256), 4, 0, 0);
+        const char *p = touch_ptr + (int64_t)tc * (kBK * 2);
+        asm volatile("global_load_lds_dword %0, off" ::"v"(p) : "memory");
     };
 
-    // Fragment reads: block row li of the wavefront's A (or B) rows, k-chunk 2 kk + lh.
-    int ra_off[4], rb_off[4];
+    // Fragment of 16 rows x 32 k: the lane reads row l16 of the block, 16-byte chunk 4 kk + lq.
+    int ra_off[2], rb_off[2];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        const int pos = (2 * kk + lh) ^ ((li >> 1) & 7);
-        ra_off[kk] = (wm0 + li) * 128 + pos * 16;
-        rb_off[kk] = kTileBytes + (wn0 + li) * 128 + pos * 16;
+    for (int kk = 0; kk < 2; ++kk) {
+        const int pos = (4 * kk + lq) ^ ((l16 >> 1) & 7);
+        ra_off[kk] = (wm0 + l16) * 128 + pos * 16;
+        rb_off[kk] = kTileBytes + (wn0 + l16) * 128 + pos * 16;
     }
     Frag F[2];
-    // idx orders the eight reads as the next k-step consumes them: a0, b0..b3, a1..a3
+    // idx orders the sixteen reads as the next k-step consumes them: a0, b0..b7, a1..a7
     auto lread = [&](int stage, int kk, int fi, int idx) {
         const char *s = smem + stage * kStageBytes;
         if (idx == 0)
             F[fi].a[0] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk]);
-        else if (idx <= 4)
-            F[fi].b[idx - 1] = *reinterpret_cast<const bf16x8 *>(s + rb_off[kk] + (idx - 1) * 4096);
+        else if (idx <= 8)
+            F[fi].b[idx - 1] = *reinterpret_cast<const bf16x8 *>(s + rb_off[kk] + (idx - 1) * 2048);
         else
-            F[fi].a[idx - 4] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk] + (idx - 4) * 4096);
+            F[fi].a[idx - 8] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk] + (idx - 8) * 2048);
     };
 
-    f32x16 acc[4][4];
+    f32x4 acc[8][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // One K-tile t of parity P: reads stage X = P; K-tile t+1 lands in Y = 1-P.  Of K-tile t+1's 16
-    // loads the first kEarly were issued in k-step 3 of K-tile t-1, the rest go out in k-step 0 here;
-    // k-step 3 starts refilling X with K-tile t+2.
+    constexpr int kLate = 16 - kEarly;
+    constexpr int kTouchSlot = kLoadEvery * kLate + 1;      // behind the late loads, so the touch is the youngest load at the barrier
+    static_assert(kLoadEvery * 16 <= 64 && kReadEvery * 15 < 64 && kTouchSlot + 2 < 64, "slots of one k-step");
+
     auto k_tile = [&](auto parity, int t) {
         constexpr int P = decltype(parity)::value;
         constexpr int X = P, Y = 1 - P;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int fc = kk & 1, fn = fc ^ 1;
-#pragma unroll
-            for (int m = 0; m < 16; ++m) {
-                acc[m >> 2][m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F[fc].a[m >> 2], F[fc].b[m & 3],
-                                                                             acc[m >> 2][m & 3], 0, 0, 0);
-                if ((m & 1) == 0) {                 // even slots: fragments of the next k-step (next stage after the barrier)
-                    if (kk < 3) lread(X, kk + 1, fn, m >> 1); else lread(Y, 0, fn, m >> 1);
-                } else {                            // odd slots: loads, so that LDS reads never queue back to back
-                    const int c = m >> 1;
-                    if (kk == 3) dma(X, c, t + 2);
-                    else if (kk == 0) dma(Y, kEarly + c, t + 1);
-                    else if (kk == 1 && c == 0) touch(t + kTouchAhead);
+        static_for<2>([&](auto kkc) {
+            constexpr int kk = decltype(kkc)::value;
+            static_for<64>([&](auto mc) {
+                constexpr int m = decltype(mc)::value;
+                constexpr int i = m >> 3, j = m & 7;
+                constexpr int c = m / kLoadEvery;               // load of this group of slots
+                constexpr bool has_load = kk == 1 ? c < kEarly : c < kLate;
+                if constexpr (m % kLoadEvery == 1 && has_load) {
+                    if constexpr (kk == 1) load_m0(Int<X>{}, Int<c>{});
+                    else load_m0(Int<Y>{}, Int<kEarly + c>{});
                 }
+                if constexpr (kk == 0 && m == kTouchSlot) touch_m0();
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(F[kk].a[i]), "v"(F[kk].b[j]));
+                if constexpr (m % kReadEvery == 0 && m / kReadEvery < 16) {
+                    // fragments of the next k-step (the next K-tile's first, from Y, once the barrier is passed)
+                    if constexpr (kk == 0) lread(X, 1, 1, m / kReadEvery);
+                    else lread(Y, 0, 0, m / kReadEvery);
+                }
+                if constexpr (m % kLoadEvery == 2 && has_load) {
+                    if constexpr (kk == 1) load_go(Int<c>{});
+                    else load_go(Int<kEarly + c>{});
+                }
+                if constexpr (kk == 0 && m == kTouchSlot + 1) touch_go(t + kTouchAhead);
+                if constexpr (kk == 0 && m == kTouchSlot + 2) advance(t + 2);
                 __builtin_amdgcn_sched_barrier(0);
-            }
-            if (kk == 2) {
-                // All loads but the newest (the touch) have landed: K-tile t+1 is complete in Y.  Every
+            });
+            if constexpr (kk == 0) {
+                // All loads but the youngest (the touch) have landed: K-tile t+1 is complete in Y.  Every
                 // wavefront also has its last fragments of X in registers, so after the barrier Y may be
-                // read and X overwritten.
-                asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)" ::: "memory");
+                // read and X overwritten.  The LDS counter is drained through the builtin so that the
+                // compiler knows it and adds no waits of its own in front of the MFMAs.
+                asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0xC07F);             // lgkmcnt(0)
                 __builtin_amdgcn_s_barrier();
-                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                __builtin_amdgcn_s_waitcnt(0xC07F);             // lgkmcnt(0): the next K-tile's first fragments
             }
-        }
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
 
     // Prologue: K-tile 0 into stage 0 and touches for the K-tiles the loop's own touches come too late for;
     // only K-tile 0 is waited for (the touches are the youngest kTouchAhead - 1 loads).
+    static_for<16>([&](auto ic) {
+        load_m0(Int<0>{}, ic);
+        asm volatile("s_nop 0");
+        load_go(ic);
+    });
+    touch_m0();
+    asm volatile("s_nop 0");
 #pragma unroll
-    for (int idx = 0; idx < 16; ++idx) dma(0, idx, 0);
-#pragma unroll
-    for (int p = 1; p < kTouchAhead; ++p) touch(p);
+    for (int p = 1; p < kTouchAhead; ++p) touch_go(p);
+    advance(1);
     static_assert(kTouchAhead == 3, "the wait below skips kTouchAhead - 1 touches");
     asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    // then the early half of K-tile 1 into stage 1 and the first fragments
+    // then the early loads of K-tile 1 into stage 1 and the first fragments
+    static_for<kEarly>([&](auto ic) {
+        load_m0(Int<1>{}, ic);
+        asm volatile("s_nop 0");
+        load_go(ic);
+    });
 #pragma unroll
-    for (int idx = 0; idx < kEarly; ++idx) dma(1, idx, 1);
-#pragma unroll
-    for (int idx = 0; idx < 8; ++idx) lread(0, 0, 0, idx);
+    for (int idx = 0; idx < 16; ++idx) lread(0, 0, 0, idx);
+    __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_sched_barrier(0);
 
     int t = 0;
     for (; t + 1 < nk; t += 2) {
-        k_tile(std::integral_constant<int, 0>{}, t);
-        k_tile(std::integral_constant<int, 1>{}, t + 1);
+        k_tile(Int<0>{}, t);
+        k_tile(Int<1>{}, t + 1);
     }
-    if (t < nk) k_tile(std::integral_constant<int, 0>{}, t);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no load may still be writing LDS when the wavefront ends
+    if (t < nk) k_tile(Int<0>{}, t);
+    // no load may still be writing LDS when the wavefront ends, and the last MFMAs must have retired
+    // before the accumulators are read (the compiler does not know what wrote them)
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
-    // Register r of a 32x32 block holds row (r/4)*8 + 4*(lane/32) + r%4, column lane%32.
+    // Register r of a 16x16 block holds row 4 (lane / 16) + r, column lane % 16.
     float *__restrict__ C = g.C;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = n0 + wn0 + j * 32 + li;
+        for (int j = 0; j < 8; ++j) {
+            const int col = n0 + wn0 + j * 16 + l16;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
+            for (int r = 0; r < 4; ++r) {
+                const int row = m0 + wm0 + i * 16 + lq * 4 + r;
                 C[(int64_t)row * g.ldc + col] = acc[i][j][r];
             }
         }
