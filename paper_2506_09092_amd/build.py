@@ -15,6 +15,24 @@ HIPCC_FLAGS = (
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 )
+# Sources whose kernels issue loads from inline assembly.  The compiler cannot place hazard wait states
+# around those, which is safe only while it reloads no spilled register next to them: such kernels must
+# compile without spills (checked below from the compiler's own resource-usage remarks).
+NO_SPILL_SOURCES = ("gemm_bf16_main.hip",)
+
+
+def check_no_spills(src: str, remarks: str) -> str:
+    """Parse hipcc's kernel-resource-usage remarks; raise unless every kernel of `src` is free of spills."""
+    import re
+
+    fields = re.findall(r"remark:\s+(Function Name|SGPRs Spill|VGPRs Spill|ScratchSize \[bytes/lane\]):\s*(\S+)", remarks)
+    names = [v for k, v in fields if k == "Function Name"]
+    if not names:
+        raise RuntimeError("no kernel-resource-usage remarks for %s: cannot verify that it compiled without spills" % src)
+    bad = [(k, v) for k, v in fields if k != "Function Name" and v != "0"]
+    if bad:
+        raise RuntimeError("%s must compile without register spills, got %s" % (src, bad))
+    return "%d kernel(s), no spills, no scratch" % len(names)
 
 
 def build_library(verbose: bool = False) -> str:
@@ -26,12 +44,19 @@ def build_library(verbose: bool = False) -> str:
     def compile_one(src: str) -> str:
         obj = os.path.join(bdir, src.replace(".hip", ".o"))
         cmd = [hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        if src in NO_SPILL_SOURCES:
+            cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed on %s:\n%s" % (src, err))
+        if src in NO_SPILL_SOURCES:
+            usage = check_no_spills(src, err)
+            err = "\n".join(l for l in err.splitlines() if "kernel-resource-usage" not in l and l.strip(" |^0123456789{"))
+            if verbose:
+                print("%s: %s" % (src, usage))
         if verbose and err.strip():
             print(err)
         return obj

@@ -201,10 +201,6 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     };
 
     f32x4 acc[8][8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     constexpr int kLate = 16 - kEarly;
     constexpr int kTouchSlot = kLoadEvery * kLate + 1;      // behind the late loads, so the touch is the youngest load at the barrier
@@ -266,6 +262,16 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
 #pragma unroll
     for (int p = 1; p < kTouchAhead; ++p) touch_go(p);
     advance(1);
+    // the accumulators are cleared while K-tile 0 is on its way
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) asm volatile("" : "+a"(acc[i][j]));      // pins the clears here
+    __builtin_amdgcn_sched_barrier(0);
     static_assert(kTouchAhead == 3, "the wait below skips kTouchAhead - 1 touches");
     asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
     __builtin_amdgcn_s_barrier();

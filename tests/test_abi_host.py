@@ -77,3 +77,21 @@ def test_dispatch_query_names_variants():
     assert qb(2048, 2048, 512, P, 512, P, 512, P, 2048) == "gemm_bf16_kernel<2, 2, 0>"
     assert qb(100, 100, 100, P, 100, P, 100, P, 100) == "gemm_bf16_kernel<1, 4, 2>"         # ld not a multiple of 8
     assert qb(100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1>"
+
+
+def test_build_refuses_spills_in_hand_scheduled_kernels():
+    # the build parses the compiler's resource-usage remarks for the kernels that issue loads from
+    # inline assembly; any spill (or missing remarks) must stop it
+    from paper_2506_09092_amd import build
+
+    ok = ("x.hip:1:1: remark: Function Name: k [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark:     SGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark:     VGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]\n")
+    assert "no spills" in build.check_no_spills("x.hip", ok)
+    for field in ("SGPRs Spill: 0", "VGPRs Spill: 0", "ScratchSize [bytes/lane]: 0"):
+        with pytest.raises(RuntimeError):
+            build.check_no_spills("x.hip", ok.replace(field, field[:-1] + "4"))
+    with pytest.raises(RuntimeError):
+        build.check_no_spills("x.hip", "")
+    assert "gemm_bf16_main.hip" in build.NO_SPILL_SOURCES
