@@ -28,8 +28,8 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense MFMA peaks
 # profiles/gemm_f32_4096_bf16_8192_hbm_traffic.txt (scaled by a 1 GiB copy).  Each entry is tied to the
 # kernel sources it was measured on: once those change the figure is stale and the bench reports null.
 TRAFFIC = {
-    "f32_4096": {"bytes": 859409417, "sources": {"gemm_f32.hip": "1109f4d4afac0d14", "common.hpp": "698bf142b70fbd57"}},
-    "bf16_8192": {"bytes": 2097082851, "sources": {"gemm_bf16_main.hip": "c6a1c22d97fd57a6", "common.hpp": "698bf142b70fbd57"}},
+    "f32_4096": {"bytes": 878692613, "sources": {"gemm_f32.hip": "1109f4d4afac0d14", "common.hpp": "698bf142b70fbd57"}},
+    "bf16_8192": {"bytes": 2106153332, "sources": {"gemm_bf16_main.hip": "fe3f91e20ee8bc30", "common.hpp": "698bf142b70fbd57"}},
 }
 
 
