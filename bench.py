@@ -153,6 +153,29 @@ def paper_task2_sizes(lib, torch, launches=5):
     return out
 
 
+def transposed_storage_4096(lib, torch, launches=7):
+    """fp32 4096^3 with A, B or both handed over in transposed storage (gemm_f32_ex): median launch time of each
+    of the four storage pairs on the same random operands.  Profiler leg only; parity of these paths is a GPU test."""
+    n = 4096
+    a, b, c = torch.randn(n, n, device="cuda"), torch.randn(n, n, device="cuda"), torch.empty(n, n, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    out = []
+    for ta, tb in ((0, 0), (0, 1), (1, 0), (1, 1)):
+        for _ in range(2):
+            lib.check(lib.gemm_f32_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream))
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
+        for e0, e1 in evs:
+            e0.record()
+            lib.check(lib.gemm_f32_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream))
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sorted(x.elapsed_time(y) for x, y in evs)[launches // 2]
+        out.append({"transA": ta, "transB": tb, "kernel": lib.fsrgemm_kernel_for_f32_ex(ta, tb, n, n, n, a, n, b, n, c, n),
+                    "ms": ms, "tflops": 2.0 * n ** 3 / (ms * 1e-3) / 1e12})
+    return out
+
+
 def cpu_baseline(w):
     """The oracle as it stands, timed on the host cores over a slab of rows of the same workload."""
     import oracle
@@ -214,6 +237,7 @@ def main():
         torch.cuda.empty_cache()
 
     task2 = paper_task2_sizes(lib, torch)
+    layouts = transposed_storage_4096(lib, torch)
     torch.cuda.empty_cache()
 
     if args.copy_calibration:
@@ -237,6 +261,7 @@ def main():
         "other_workload": other,
         "sweep": sweep,
         "paper_task2_shapes": task2,
+        "transposed_storage_f32_4096": layouts,
         "paper_context": "paper reports only speedups over hand-written CUDA for the group holding Task 2: 5.95-68.3x (RTX 3090 Ti), 6.06-60.0x (GTX 1660 SUPER)",
     }
     print(json.dumps(out), flush=True)

@@ -66,6 +66,22 @@ int gemm_f32(int64_t M, int64_t N, int64_t K,
              void *stream);
 
 /*
+ * The same fp32 product with either operand stored transposed.  The paper's task table defines Task 2 by
+ * its shapes only and names a storage order (row-major) just for its convolution and transpose tasks, so a
+ * harness may hold either operand either way.
+ *   transA == 0: A[i][k] at A[i*lda + k] (lda >= K);  transA != 0: A[i][k] at A[k*lda + i] (lda >= M)
+ *   transB == 0: B[k][j] at B[k*ldb + j] (ldb >= N);  transB != 0: B[k][j] at B[j*ldb + k] (ldb >= K)
+ * C is row-major as in gemm_f32, and gemm_f32(...) is gemm_f32_ex(0, 0, ...).  Everything else
+ * (arithmetic, alignment rules, empty extents, errors) is as for gemm_f32.
+ */
+int gemm_f32_ex(int transA, int transB,
+                int64_t M, int64_t N, int64_t K,
+                const float *A, int64_t lda,
+                const float *B, int64_t ldb,
+                float *C, int64_t ldc,
+                void *stream);
+
+/*
  * bf16 inputs, fp32 accumulation and fp32 output.
  *   A is ROW-major bf16: A[i][k] at A[i*lda + k] (lda >= K).
  *   B is COLUMN-major bf16: B[k][j] at B[j*ldb + k] (ldb >= K), i.e. both
@@ -91,6 +107,11 @@ const char *fsrgemm_kernel_for_f32(int64_t M, int64_t N, int64_t K,
                                    const float *A, int64_t lda,
                                    const float *B, int64_t ldb,
                                    const float *C, int64_t ldc);
+const char *fsrgemm_kernel_for_f32_ex(int transA, int transB,
+                                      int64_t M, int64_t N, int64_t K,
+                                      const float *A, int64_t lda,
+                                      const float *B, int64_t ldb,
+                                      const float *C, int64_t ldc);
 const char *fsrgemm_kernel_for_bf16(int64_t M, int64_t N, int64_t K,
                                     const uint16_t *A, int64_t lda,
                                     const uint16_t *B, int64_t ldb,

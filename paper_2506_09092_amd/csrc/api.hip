@@ -17,14 +17,14 @@ struct Plan {
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Checks shared by both precisions.  ldb_min is N for a row-major B, K for a
-// column-major one.  Returns FSRGEMM_OK when the problem is well formed.
-int check_args(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
-               int64_t ldb_min, const void *C, int64_t ldc)
+// Checks shared by all entry points.  lda_min / ldb_min are the extents of the operands' contiguous index (K or M
+// for A, N or K for B, by storage order).  Returns FSRGEMM_OK when the problem is well formed.
+int check_args(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, int64_t lda_min, const void *B,
+               int64_t ldb, int64_t ldb_min, const void *C, int64_t ldc)
 {
     const int64_t lim = (int64_t)1 << 31;
     if (M < 0 || N < 0 || K < 0 || M >= lim || N >= lim || K >= lim) return FSRGEMM_ERR_INVALID_ARG;
-    if (lda < K || ldb < ldb_min || ldc < N) return FSRGEMM_ERR_INVALID_ARG;
+    if (lda < lda_min || ldb < ldb_min || ldc < N) return FSRGEMM_ERR_INVALID_ARG;
     if (M > 0 && N > 0 && C == nullptr) return FSRGEMM_ERR_INVALID_ARG;
     if (M > 0 && N > 0 && K > 0 && (A == nullptr || B == nullptr)) return FSRGEMM_ERR_INVALID_ARG;
     return FSRGEMM_OK;
@@ -121,7 +121,13 @@ extern "C" {
 int gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb, float *C,
              int64_t ldc, void *stream)
 {
-    int rc = check_args(M, N, K, A, lda, B, ldb, N, C, ldc);
+    return gemm_f32_ex(0, 0, M, N, K, A, lda, B, ldb, C, ldc, stream);
+}
+
+int gemm_f32_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                int64_t ldb, float *C, int64_t ldc, void *stream)
+{
+    int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
     if (rc != FSRGEMM_OK) return rc;
     Plan p;
     rc = plan_f32(M, N, K, A, lda, B, ldb, &p);
@@ -129,14 +135,15 @@ int gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const
     if (M == 0 || N == 0) return FSRGEMM_OK;
     rc = device_ok();
     if (rc != FSRGEMM_OK) return rc;
-    const hipError_t e = launch_f32(p.cfg, p.mode, pack(M, N, K, A, lda, B, ldb, C, ldc), static_cast<hipStream_t>(stream));
+    const hipError_t e = launch_f32(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig,
+                                    pack(M, N, K, A, lda, B, ldb, C, ldc), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
 }
 
 int gemm_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
               float *C, int64_t ldc, void *stream)
 {
-    int rc = check_args(M, N, K, A, lda, B, ldb, K, C, ldc);
+    int rc = check_args(M, N, K, A, lda, K, B, ldb, K, C, ldc);
     if (rc != FSRGEMM_OK) return rc;
     Plan p;
     rc = plan_bf16(M, N, K, A, lda, B, ldb, &p);
@@ -151,17 +158,23 @@ int gemm_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, c
 const char *fsrgemm_kernel_for_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
                                    int64_t ldb, const float *C, int64_t ldc)
 {
+    return fsrgemm_kernel_for_f32_ex(0, 0, M, N, K, A, lda, B, ldb, C, ldc);
+}
+
+const char *fsrgemm_kernel_for_f32_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A,
+                                      int64_t lda, const float *B, int64_t ldb, const float *C, int64_t ldc)
+{
     Plan p;
-    if (check_args(M, N, K, A, lda, B, ldb, N, C, ldc) != FSRGEMM_OK) return nullptr;
+    if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
     if (plan_f32(M, N, K, A, lda, B, ldb, &p) != FSRGEMM_OK) return nullptr;
-    return f32_kernel_name(p.cfg, p.mode);
+    return f32_kernel_name(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig);
 }
 
 const char *fsrgemm_kernel_for_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
                                     const uint16_t *B, int64_t ldb, const float *C, int64_t ldc)
 {
     Plan p;
-    if (check_args(M, N, K, A, lda, B, ldb, K, C, ldc) != FSRGEMM_OK) return nullptr;
+    if (check_args(M, N, K, A, lda, K, B, ldb, K, C, ldc) != FSRGEMM_OK) return nullptr;
     if (plan_bf16(M, N, K, A, lda, B, ldb, &p) != FSRGEMM_OK) return nullptr;
     return bf16_kernel_name(p.cfg, p.mode);
 }

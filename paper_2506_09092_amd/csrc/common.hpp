@@ -59,11 +59,15 @@ struct GemmArgs {
 //   kScalar:  element-wise predicated loads (any alignment, any shape)
 enum LoadMode { kFast = 0, kVecPred = 1, kScalar = 2 };
 
-// fp32 tile configurations (gemm_f32.hip), each available in the three load modes
+// Which index of an operand tile is contiguous in memory: k (a row-major A, a transposed B) or the
+// m / n index (a transposed A, a row-major B).
+enum OperandLayout { kKContig = 0, kMnContig = 1 };
+
+// fp32 tile configurations (gemm_f32.hip), each available in the three load modes and the four layout pairs
 enum F32Config { kF32_256x128 = 0, kF32_128x128 = 1, kF32_64x64 = 2, kF32ConfigCount };
 // Names are substrings of the kernel symbols as a profiler trace prints them.
-const char *f32_kernel_name(int cfg, int mode);
-hipError_t launch_f32(int cfg, int mode, const GemmArgs &a, hipStream_t s);
+const char *f32_kernel_name(int cfg, int mode, int a_lay, int b_lay);
+hipError_t launch_f32(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 
 // bf16 configurations: the direct-to-LDS 256x256 kernel for aligned, tile-multiple problems
 // (gemm_bf16_main.hip) and three tile sizes of the general kernel (gemm_bf16.hip), each in the three load modes

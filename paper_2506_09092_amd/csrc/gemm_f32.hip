@@ -1,5 +1,6 @@
-// fp32 GEMM for gfx950: C[M x N] = A[M x K] . B[K x N], all row-major
-// (the paper's Task 2 definition: a 32-bit floating point matrix product).
+// fp32 GEMM for gfx950: C[M x N] = A[M x K] . B[K x N], C row-major, each
+// operand stored row-major or transposed (the paper's Task 2 definition: a
+// 32-bit floating point matrix product; the paper fixes no storage order for it).
 //
 // One workgroup of 256 lanes (4 wavefronts in a 2 x 2 grid) owns a
 // (64 TM) x (64 TN) tile of C, each wavefront a (32 TM) x (32 TN) part of it as
@@ -7,13 +8,19 @@
 // stages A[BM x 16] and B[16 x BN] through registers into a double-buffered
 // LDS region.
 //
+// Operand layouts.  What matters to the kernel is which index of an operand
+// tile is contiguous in memory: k (a row-major A, a transposed B) or the m / n
+// index (a transposed A, a row-major B).  LDS keeps the memory order, so global
+// loads and LDS stores are 16-byte vectors either way.
+//
 // Operand mapping.  The 32x32x2 MFMA takes, per lane l, one A value
-// A[l % 32][l / 32] and one B value B[l / 32][l % 32].  A is contiguous along
-// k in memory and in LDS, so a lane fetches four consecutive k with a single
-// 16-byte LDS read.  To make that useful the eight k of a chunk are assigned to
-// MFMA steps in permuted order: lanes 0-31 hold k = 0..3, lanes 32-63 hold
-// k = 4..7, and step t contracts the pair {t, 4 + t}.  B is read to match
-// (row 4h + t for half h).  The sum over k is unchanged; only its order is.
+// A[l % 32][l / 32] and one B value B[l / 32][l % 32].  An operand that is
+// contiguous along k lets a lane fetch four consecutive k with a single 16-byte
+// LDS read.  To make that useful the eight k of a chunk are assigned to MFMA
+// steps in permuted order: lanes 0-31 hold k = 0..3, lanes 32-63 hold
+// k = 4..7, and step t contracts the pair {t, 4 + t}.  An operand contiguous
+// along m / n is read to match, one value per step (row 4h + t for half h).
+// The sum over k is unchanged; only its order is.
 //
 // The loop is an explicit schedule: every MFMA is followed by its share of the
 // other instructions of the chunk -- LDS fragment reads for the next 8-k chunk,
@@ -26,6 +33,8 @@
 // that are a whole number of tiles with K a multiple of 16), vectors with
 // element-wise zero-filled edges (aligned, ragged), element-wise predicated
 // loads (any alignment).  Ragged modes also mask the stores.
+#include <stdio.h>
+
 #include <type_traits>
 
 #include "common.hpp"
@@ -57,17 +66,68 @@ __device__ __forceinline__ f32x4 load4(const float *__restrict__ p, bool row_ok,
     }
 }
 
-template <int TM, int TN, int MIN_WAVES, int MODE>
+// One operand tile of EXT rows (m or n) by kBK columns (k), in either storage order.
+//   kKContig : element (r, k) at base[r * ld + k]; LDS rows of kBK + kPadA floats, one per r
+//   kMnContig: element (r, k) at base[k * ld + r]; LDS rows of EXT + kPadB floats, one per k
+// Either way a lane moves EXT / 64 16-byte vectors per K-tile.
+template <int EXT, int LAY>
+struct Operand {
+    static constexpr int kRow = LAY == kKContig ? kBK + kPadA : EXT + kPadB;              // LDS row stride, floats
+    static constexpr int kStage = LAY == kKContig ? EXT * (kBK + kPadA) : kBK * (EXT + kPadB);   // floats per stage
+    static constexpr int kVectors = EXT / 64;
+    static constexpr int kReads = LAY == kKContig ? 1 : 4;      // fragment reads per 32-row block and 8-k chunk
+
+    // vector s of this lane: tile row / k column it starts at (kKContig: 4 consecutive k; kMnContig: 4 consecutive rows)
+    static __device__ __forceinline__ void where(int tid, int s, int &r, int &k)
+    {
+        if constexpr (LAY == kKContig) {
+            r = (tid >> 2) + 64 * s;
+            k = (tid & 3) * 4;
+        } else {
+            const int e = tid + kThreads * s;
+            k = e / (EXT / 4);
+            r = (e % (EXT / 4)) * 4;
+        }
+    }
+    template <int MODE>
+    static __device__ __forceinline__ f32x4 gload(const float *__restrict__ base, int64_t ld, int r0, int rows, int k0,
+                                                  int K, int tid, int s)
+    {
+        int r, k;
+        where(tid, s, r, k);
+        if constexpr (LAY == kKContig)
+            return load4<MODE>(base + (int64_t)(r0 + r) * ld + k0 + k, r0 + r < rows, k0 + k, K);
+        else
+            return load4<MODE>(base + (int64_t)(k0 + k) * ld + r0 + r, k0 + k < K, r0 + r, rows);
+    }
+    static __device__ __forceinline__ int lds_store_at(int tid, int s)
+    {
+        int r, k;
+        where(tid, s, r, k);
+        return LAY == kKContig ? r * kRow + k : k * kRow + r;
+    }
+    // fragment read `q` of block `blk` for chunk kk; w = wavefront's first row + lane % 32, h = lane / 32
+    static __device__ __forceinline__ void fragment(const float *stage, int w, int h, int blk, int kk, int q, f32x4 &f)
+    {
+        if constexpr (LAY == kKContig)
+            f = *reinterpret_cast<const f32x4 *>(&stage[(w + 32 * blk) * kRow + 4 * h + kk * 8]);
+        else
+            f[q] = stage[(kk * 8 + 4 * h + q) * kRow + w + 32 * blk];
+    }
+};
+
+template <int TM, int TN, int MIN_WAVES, int MODE, int ALAY, int BLAY>
 __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs g, int tiles_m, int tiles_n)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr int LDA_S = kBK + kPadA, LDB_S = BN + kPadB;
-    constexpr int A_ST = BM * LDA_S, B_ST = kBK * LDB_S;    // floats per LDS stage
-    constexpr int NA = BM / 64, NB = BN / 64, NG = NA + NB;   // 16-byte vectors per lane per K-tile
-    constexpr int NR = TM + 4 * TN;                           // fragment reads per 8-k chunk
+    using OpA = Operand<BM, ALAY>;
+    using OpB = Operand<BN, BLAY>;
+    constexpr int A_ST = OpA::kStage, B_ST = OpB::kStage;     // floats per LDS stage
+    constexpr int NA = OpA::kVectors, NB = OpB::kVectors, NG = NA + NB;   // 16-byte vectors per lane per K-tile
+    constexpr int NRA = OpA::kReads * TM, NR = NRA + OpB::kReads * TN;    // fragment reads per 8-k chunk
     constexpr int NMF = 4 * TM * TN;                          // MFMAs per chunk
     constexpr int NC = NR + NG;                               // companion instructions per chunk
-    constexpr int PER_SLOT = (NC + NMF - 1) / NMF;            // 1 for the large tiles, 2 for 64 x 64
+    constexpr int PER_SLOT = (NC + NMF - 1) / NMF;            // 1 for the large row-major tiles, up to 3 for 64 x 64
 
     __shared__ __attribute__((aligned(16))) float As[2 * A_ST];
     __shared__ __attribute__((aligned(16))) float Bs[2 * B_ST];
@@ -93,40 +153,20 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
         return;
     }
 
-    // A tile: lane -> row (tid >> 2) + 64 s, columns 4 (tid & 3) ..; B tile: vector e = tid + 256 s -> row e / (BN/4)
-    const int a_row = tid >> 2, a_col = (tid & 3) * 4;
-    const float *a_ptr = A + (int64_t)(m0 + a_row) * g.lda + a_col;
-    const int64_t a_step = 64 * g.lda;
     f32x4 rg[NG];
     auto gload = [&](int idx, int t) {      // K-tiles past the end are clamped: loaded again, never consumed
         const int k0 = (t < nk ? t : nk - 1) * kBK;
-        if (idx < NA) {
-            rg[idx] = load4<MODE>(a_ptr + idx * a_step + k0, m0 + a_row + 64 * idx < M, k0 + a_col, K);
-        } else {
-            const int e = tid + kThreads * (idx - NA);
-            const int kr = k0 + e / (BN / 4), nc = n0 + (e % (BN / 4)) * 4;
-            rg[idx] = load4<MODE>(B + (int64_t)kr * g.ldb + nc, kr < K, nc, N);
-        }
+        if (idx < NA) rg[idx] = OpA::template gload<MODE>(A, g.lda, m0, M, k0, K, tid, idx);
+        else rg[idx] = OpB::template gload<MODE>(B, g.ldb, n0, N, k0, K, tid, idx - NA);
     };
-    const int aw = a_row * LDA_S + a_col;
     auto lwrite = [&](int stage, int idx) {
-        if (idx < NA) {
-            *reinterpret_cast<f32x4 *>(&As[stage * A_ST + aw + idx * 64 * LDA_S]) = rg[idx];
-        } else {
-            const int e = tid + kThreads * (idx - NA);
-            *reinterpret_cast<f32x4 *>(&Bs[stage * B_ST + (e / (BN / 4)) * LDB_S + (e % (BN / 4)) * 4]) = rg[idx];
-        }
+        if (idx < NA) *reinterpret_cast<f32x4 *>(&As[stage * A_ST + OpA::lds_store_at(tid, idx)]) = rg[idx];
+        else *reinterpret_cast<f32x4 *>(&Bs[stage * B_ST + OpB::lds_store_at(tid, idx - NA)]) = rg[idx];
     };
-    const int ar = (wm0 + li) * LDA_S + 4 * lh, br = (4 * lh) * LDB_S + wn0 + li;
-    f32x4 fa[2][TM];
-    float fb[2][TN][4];
-    auto lread = [&](int stage, int kk, int fi, int idx) {    // idx < TM: A block idx; then B, step-major
-        if (idx < TM) {
-            fa[fi][idx] = *reinterpret_cast<const f32x4 *>(&As[stage * A_ST + ar + idx * 32 * LDA_S + kk * 8]);
-        } else {
-            const int q = idx - TM, j = q % TN, t = q / TN;
-            fb[fi][j][t] = Bs[stage * B_ST + br + (kk * 8 + t) * LDB_S + j * 32];
-        }
+    f32x4 fa[2][TM], fb[2][TN];     // component t of a fragment feeds MFMA step t of the chunk
+    auto lread = [&](int stage, int kk, int fi, int idx) {    // A's reads first, then B's; block-minor
+        if (idx < NRA) OpA::fragment(&As[stage * A_ST], wm0 + li, lh, idx % TM, kk, idx / TM, fa[fi][idx % TM]);
+        else OpB::fragment(&Bs[stage * B_ST], wn0 + li, lh, (idx - NRA) % TN, kk, (idx - NRA) / TN, fb[fi][(idx - NRA) % TN]);
     };
 
     f32x16 acc[TM][TN];
@@ -203,39 +243,59 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
         }
 }
 
-template <int TM, int TN, int MIN_WAVES>
-hipError_t launch_cfg(int mode, const GemmArgs &a, hipStream_t s)
+template <int TM, int TN, int MIN_WAVES, int ALAY, int BLAY>
+hipError_t launch_lay(int mode, const GemmArgs &a, hipStream_t s)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(kThreads);
     switch (mode) {
-    case kFast: hipLaunchKernelGGL((gemm_f32_kernel<TM, TN, MIN_WAVES, kFast>), grid, block, 0, s, a, tiles_m, tiles_n); break;
-    case kVecPred: hipLaunchKernelGGL((gemm_f32_kernel<TM, TN, MIN_WAVES, kVecPred>), grid, block, 0, s, a, tiles_m, tiles_n); break;
-    default: hipLaunchKernelGGL((gemm_f32_kernel<TM, TN, MIN_WAVES, kScalar>), grid, block, 0, s, a, tiles_m, tiles_n); break;
+    case kFast: hipLaunchKernelGGL((gemm_f32_kernel<TM, TN, MIN_WAVES, kFast, ALAY, BLAY>), grid, block, 0, s, a, tiles_m, tiles_n); break;
+    case kVecPred: hipLaunchKernelGGL((gemm_f32_kernel<TM, TN, MIN_WAVES, kVecPred, ALAY, BLAY>), grid, block, 0, s, a, tiles_m, tiles_n); break;
+    default: hipLaunchKernelGGL((gemm_f32_kernel<TM, TN, MIN_WAVES, kScalar, ALAY, BLAY>), grid, block, 0, s, a, tiles_m, tiles_n); break;
     }
     return hipGetLastError();
 }
 
-}  // namespace
-
-// <TM, TN, minimum wavefronts per SIMD, load mode>, as a profiler trace prints the kernel
-const char *f32_kernel_name(int cfg, int mode)
+template <int TM, int TN, int MIN_WAVES>
+hipError_t launch_cfg(int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
-    static const char *names[kF32ConfigCount][3] = {
-        {"gemm_f32_kernel<4, 2, 2, 0>", "gemm_f32_kernel<4, 2, 2, 1>", "gemm_f32_kernel<4, 2, 2, 2>"},
-        {"gemm_f32_kernel<2, 2, 3, 0>", "gemm_f32_kernel<2, 2, 3, 1>", "gemm_f32_kernel<2, 2, 3, 2>"},
-        {"gemm_f32_kernel<1, 1, 4, 0>", "gemm_f32_kernel<1, 1, 4, 1>", "gemm_f32_kernel<1, 1, 4, 2>"},
-    };
-    return names[cfg][mode];
+    if (a_lay == kKContig) {
+        return b_lay == kMnContig ? launch_lay<TM, TN, MIN_WAVES, kKContig, kMnContig>(mode, a, s)
+                                  : launch_lay<TM, TN, MIN_WAVES, kKContig, kKContig>(mode, a, s);
+    }
+    return b_lay == kMnContig ? launch_lay<TM, TN, MIN_WAVES, kMnContig, kMnContig>(mode, a, s)
+                              : launch_lay<TM, TN, MIN_WAVES, kMnContig, kKContig>(mode, a, s);
 }
 
-hipError_t launch_f32(int cfg, int mode, const GemmArgs &a, hipStream_t s)
+}  // namespace
+
+// <TM, TN, minimum wavefronts per SIMD, load mode, A layout, B layout>, as a profiler trace prints the kernel
+const char *f32_kernel_name(int cfg, int mode, int a_lay, int b_lay)
+{
+    struct Names {
+        char text[kF32ConfigCount][3][2][2][40];
+        Names()
+        {
+            static const char *shapes[kF32ConfigCount] = {"4, 2, 2", "2, 2, 3", "1, 1, 4"};
+            for (int c = 0; c < kF32ConfigCount; ++c)
+                for (int m = 0; m < 3; ++m)
+                    for (int x = 0; x < 2; ++x)
+                        for (int y = 0; y < 2; ++y)
+                            snprintf(text[c][m][x][y], sizeof text[c][m][x][y], "gemm_f32_kernel<%s, %d, %d, %d>",
+                                     shapes[c], m, x, y);
+        }
+    };
+    static const Names names;
+    return names.text[cfg][mode][a_lay][b_lay];
+}
+
+hipError_t launch_f32(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
     switch (cfg) {
-    case kF32_256x128: return launch_cfg<4, 2, 2>(mode, a, s);
-    case kF32_128x128: return launch_cfg<2, 2, 3>(mode, a, s);
-    default: return launch_cfg<1, 1, 4>(mode, a, s);
+    case kF32_256x128: return launch_cfg<4, 2, 2>(mode, a_lay, b_lay, a, s);
+    case kF32_128x128: return launch_cfg<2, 2, 3>(mode, a_lay, b_lay, a, s);
+    default: return launch_cfg<1, 1, 4>(mode, a_lay, b_lay, a, s);
     }
 }
 

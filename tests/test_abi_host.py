@@ -64,11 +64,12 @@ def test_dispatch_query_names_variants():
     fast = q(4096, 4096, 4096, P, 4096, P, 4096, P, 4096)
     ragged = q(4097, 17, 1000, P, 1000, P, 20, P, 17)
     unaligned = q(123, 5, 8, P + 4, 8, P + 4, 5, P, 5)
-    # <TM, TN, min waves, load mode>: tile (64 TM) x (64 TN); mode 0 unchecked vectors, 1 vectors + predicated edges, 2 scalar
-    assert fast == "gemm_f32_kernel<4, 2, 2, 0>"
-    assert ragged == "gemm_f32_kernel<1, 1, 4, 1>" and unaligned == "gemm_f32_kernel<1, 1, 4, 2>"
-    assert q(4097, 4097, 129, P, 132, P, 4100, P, 4097) == "gemm_f32_kernel<4, 2, 2, 1>"
-    assert q(64, 64, 0, P, 4, P, 64, P, 64) == "gemm_f32_kernel<1, 1, 4, 1>"                    # K = 0 never takes the unchecked mode
+    # <TM, TN, min waves, load mode, A layout, B layout>: tile (64 TM) x (64 TN); mode 0 unchecked vectors,
+    # 1 vectors + predicated edges, 2 scalar; row-major A is contiguous along k (0), row-major B along n (1)
+    assert fast == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
+    assert ragged == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>" and unaligned == "gemm_f32_kernel<1, 1, 4, 2, 0, 1>"
+    assert q(4097, 4097, 129, P, 132, P, 4100, P, 4097) == "gemm_f32_kernel<4, 2, 2, 1, 0, 1>"
+    assert q(64, 64, 0, P, 4, P, 64, P, 64) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"                    # K = 0 never takes the unchecked mode
     assert q(4, 4, 4, P, 3, P, 4, P, 4) is None
     qb = lib.fsrgemm_kernel_for_bf16
     assert qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel"
@@ -77,6 +78,25 @@ def test_dispatch_query_names_variants():
     assert qb(2048, 2048, 512, P, 512, P, 512, P, 2048) == "gemm_bf16_kernel<2, 2, 0>"
     assert qb(100, 100, 100, P, 100, P, 100, P, 100) == "gemm_bf16_kernel<1, 4, 2>"         # ld not a multiple of 8
     assert qb(100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1>"
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_transposed_storage_arguments(ta, tb):
+    # leading dimensions are checked against the extent that is contiguous in the stated storage order
+    M, N, K = 6, 10, 16
+    lda_min, ldb_min = (M if ta else K), (K if tb else N)
+
+    def call(lda, ldb, ldc=N):
+        return lib.gemm_f32_ex(ta, tb, M, N, K, P, lda, P, ldb, P, ldc, 0)
+
+    bad = lib.FSRGEMM_ERR_INVALID_ARG
+    assert call(lda_min - 1, ldb_min) == bad and call(lda_min, ldb_min - 1) == bad and call(lda_min, ldb_min, N - 1) == bad
+    assert lib.gemm_f32_ex(ta, tb, 0, N, K, None, lda_min, P, ldb_min, None, N, 0) == lib.FSRGEMM_OK
+    q = lib.fsrgemm_kernel_for_f32_ex
+    # <TM, TN, min waves, load mode, A layout, B layout>: layout 0 = contiguous along k, 1 = along m / n
+    assert q(ta, tb, 4096, 4096, 4096, P, 4096, P, 4096, P, 4096) == "gemm_f32_kernel<4, 2, 2, 0, %d, %d>" % (ta, 1 - tb)
+    assert q(ta, tb, M, N, K, P, lda_min - 1, P, ldb_min, P, N) is None
+    assert lib.fsrgemm_kernel_for_f32(4096, 4096, 4096, P, 4096, P, 4096, P, 4096) == q(0, 0, 4096, 4096, 4096, P, 4096, P, 4096, P, 4096)
 
 
 def test_build_refuses_spills_in_hand_scheduled_kernels():

@@ -13,7 +13,7 @@ import pytest
 import oracle
 from paper_2506_09092_amd import inputs
 
-from paper_2506_09092_amd.harness import run_bf16, run_f32
+from paper_2506_09092_amd.harness import run_bf16, run_f32, run_f32_ex
 
 pytestmark = pytest.mark.gpu
 TOL_F32 = 1e-5
@@ -75,6 +75,53 @@ def test_f32_sweep_64_shapes(gpu):
     assert not failed, failed
 
 
+LAYOUTS = [(0, 1), (1, 0), (1, 1)]          # (transA, transB) beyond the plain row-major pair
+
+
+def test_f32_transposed_storage_sweep(gpu):
+    # the 64 sweep shapes again with A, B or both stored transposed; one oracle result per shape serves all three
+    cases = inputs.sweep_cases(3, 64)
+    failed = []
+    for c in cases:
+        M, N, K = c["M"], c["N"], c["K"]
+        say("transposed sweep case %d: M=%d N=%d K=%d" % (c["index"], M, N, K))
+        A = inputs.uniform_pm1(3, 2 * c["index"] + 10, M, K)
+        B = inputs.uniform_pm1(3, 2 * c["index"] + 11, K, N)
+        ref, S = oracle.gemm(A, B)
+        pad_a, pad_b = c["lda"] - K, c["ldb"] - N          # the case's padding, applied to whichever extent is contiguous
+        for ta, tb in LAYOUTS:
+            lda, ldb = (M if ta else K) + pad_a, (K if tb else N) + pad_b
+            got = run_f32_ex(gpu, ta, tb, A, B, lda=max(lda, 1), ldb=max(ldb, 1), ldc=c["ldc"], offset=c["offset"], repeat=2)
+            e = oracle.componentwise_error(got, ref, S)
+            if not e <= TOL_F32:
+                failed.append((c["index"], ta, tb, e))
+    assert not failed, failed
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_f32_transposed_storage_tile_configs(gpu, ta, tb):
+    # every tile configuration in its unchecked-vector mode, small K included, and integers bit for bit
+    for (M, N, K), name in (((2048, 2048, 48), "gemm_f32_kernel<2, 2, 3, 0, %d, %d>"),
+                            ((4096, 3072, 16), "gemm_f32_kernel<4, 2, 2, 0, %d, %d>"),
+                            ((4096, 3072, 112), "gemm_f32_kernel<4, 2, 2, 0, %d, %d>"),
+                            ((1024, 1024, 1024), "gemm_f32_kernel<1, 1, 4, 0, %d, %d>")):
+        say("transposed %d%d %dx%dx%d" % (ta, tb, M, N, K))
+        lda, ldb = (M if ta else K), (K if tb else N)
+        assert gpu.fsrgemm_kernel_for_f32_ex(ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name % (ta, 1 - tb)
+        A, B = inputs.uniform_pm1(6, 1, M, K), inputs.uniform_pm1(6, 2, K, N)
+        got = run_f32_ex(gpu, ta, tb, A, B, repeat=2)
+        ref, S = oracle.gemm(A, B)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+    A, B = inputs.small_ints(0, 3, 256, 256), inputs.small_ints(0, 4, 256, 256)
+    ref, _ = oracle.gemm(A, B)
+    assert np.array_equal(run_f32_ex(gpu, ta, tb, A, B).astype(np.float64), ref)
+
+
+def test_f32_ex_plain_is_gemm_f32(gpu):
+    A, B = inputs.uniform_pm1(6, 5, 300, 200), inputs.uniform_pm1(6, 6, 200, 260)
+    assert np.array_equal(run_f32_ex(gpu, 0, 0, A, B).view(np.uint32), run_f32(gpu, A, B).view(np.uint32))
+
+
 @pytest.mark.parametrize("shape", [(1, 1, 1), (17, 17, 17), (128, 128, 128), (130, 70, 200), (257, 255, 129),
                                    (33, 65, 31), (512, 384, 1000), (300, 520, 64),
                                    (2048, 2048, 192), (2000, 2100, 100)])          # the last two: 128 x 128 tiles
@@ -106,12 +153,12 @@ def test_bf16_big_tile_config_ragged(gpu):
     check_bf16(gpu, A, Bt)
 
 
-@pytest.mark.parametrize("shape,kernel", [((2048, 2048, 16), "gemm_f32_kernel<2, 2, 3, 0>"),
-                                          ((2048, 2048, 32), "gemm_f32_kernel<2, 2, 3, 0>"),
-                                          ((2048, 2048, 112), "gemm_f32_kernel<2, 2, 3, 0>"),
-                                          ((4096, 3072, 16), "gemm_f32_kernel<4, 2, 2, 0>"),
-                                          ((4096, 3072, 48), "gemm_f32_kernel<4, 2, 2, 0>"),
-                                          ((4096, 3072, 160), "gemm_f32_kernel<4, 2, 2, 0>")])
+@pytest.mark.parametrize("shape,kernel", [((2048, 2048, 16), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
+                                          ((2048, 2048, 32), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
+                                          ((2048, 2048, 112), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
+                                          ((4096, 3072, 16), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+                                          ((4096, 3072, 48), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+                                          ((4096, 3072, 160), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")])
 def test_f32_tile_configs_small_k(gpu, shape, kernel):
     # prologue, odd/even K-tile tails and the clamped prefetch of the two large tile configurations; full oracle comparison
     M, N, K = shape
@@ -211,7 +258,7 @@ def test_f32_4096_normal_full_size(gpu):
     say("fp32 4096^3 normal seed 2 (sampled rows, columns, entries + Freivalds)")
     n = 4096
     A, B = inputs.normal(2, 1, n, n), inputs.normal(2, 2, n, n)
-    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_kernel<4, 2, 2, 0>"
+    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
     got = run_f32(gpu, A, B)
     rng = np.random.default_rng(2)
     rows, cols = np.sort(rng.choice(n, 64, replace=False)), np.sort(rng.choice(n, 64, replace=False))
@@ -264,7 +311,7 @@ def test_f32_paper_task2_largest_size(gpu):
     A = np.empty((M, K), dtype=np.float32)
     for b in range(64):
         A[b * 4096:(b + 1) * 4096] = block * np.float32(2.0 ** ((b % 5) - 2))
-    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == "gemm_f32_kernel<4, 2, 2, 0>"
+    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
     a, b_, c = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), torch.full((M, N), float("nan"), device="cuda")
     gpu.check(gpu.gemm_f32(M, N, K, a, K, b_, N, c, N, torch.cuda.current_stream().cuda_stream))
     torch.cuda.synchronize()
