@@ -97,6 +97,19 @@ int gemm_bf16(int64_t M, int64_t N, int64_t K,
               void *stream);
 
 /*
+ * The bf16 product with either operand in either storage order; transA / transB mean what they mean for
+ * gemm_f32_ex (transB == 0 is a ROW-major B, B[k][j] at B[k*ldb + j], ldb >= N), so
+ * gemm_bf16(...) is gemm_bf16_ex(0, 1, ...).  Operands that are contiguous along m or n are regrouped on
+ * their way into on-chip memory; the fastest path is the one gemm_bf16 takes.
+ */
+int gemm_bf16_ex(int transA, int transB,
+                 int64_t M, int64_t N, int64_t K,
+                 const uint16_t *A, int64_t lda,
+                 const uint16_t *B, int64_t ldb,
+                 float *C, int64_t ldc,
+                 void *stream);
+
+/*
  * Name of the kernel variant the dispatcher would launch for this problem
  * (same argument checks as the gemm calls; launches nothing, touches no
  * device memory).  Returns a pointer to static storage, or NULL when the
@@ -116,6 +129,12 @@ const char *fsrgemm_kernel_for_bf16(int64_t M, int64_t N, int64_t K,
                                     const uint16_t *A, int64_t lda,
                                     const uint16_t *B, int64_t ldb,
                                     const float *C, int64_t ldc);
+
+const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB,
+                                       int64_t M, int64_t N, int64_t K,
+                                       const uint16_t *A, int64_t lda,
+                                       const uint16_t *B, int64_t ldb,
+                                       const float *C, int64_t ldc);
 
 /* Human-readable text for a status code; static storage, never NULL. */
 const char *fsrgemm_status_string(int status);

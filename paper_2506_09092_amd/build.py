@@ -19,20 +19,24 @@ HIPCC_FLAGS = (
 # around those, which is safe only while it reloads no spilled register next to them: such kernels must
 # compile without spills (checked below from the compiler's own resource-usage remarks).
 NO_SPILL_SOURCES = ("gemm_bf16_main.hip",)
+# Every other kernel must at least stay out of scratch memory: a loop the compiler failed to unroll puts a
+# kernel's register arrays there, which is correct but many times slower.
+KERNEL_SOURCES = ("gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_main.hip")
 
 
-def check_no_spills(src: str, remarks: str) -> str:
-    """Parse hipcc's kernel-resource-usage remarks; raise unless every kernel of `src` is free of spills."""
+def check_no_spills(src: str, remarks: str, scratch_only: bool = False) -> str:
+    """Parse hipcc's kernel-resource-usage remarks; raise unless every kernel of `src` is free of spills
+    (scratch_only: free of scratch memory; spills into spare registers are tolerated)."""
     import re
 
     fields = re.findall(r"remark:\s+(Function Name|SGPRs Spill|VGPRs Spill|ScratchSize \[bytes/lane\]):\s*(\S+)", remarks)
     names = [v for k, v in fields if k == "Function Name"]
     if not names:
         raise RuntimeError("no kernel-resource-usage remarks for %s: cannot verify that it compiled without spills" % src)
-    bad = [(k, v) for k, v in fields if k != "Function Name" and v != "0"]
+    bad = [(k, v) for k, v in fields if k != "Function Name" and v != "0" and (not scratch_only or k.startswith("Scratch"))]
     if bad:
-        raise RuntimeError("%s must compile without register spills, got %s" % (src, bad))
-    return "%d kernel(s), no spills, no scratch" % len(names)
+        raise RuntimeError("%s must compile without %s, got %s" % (src, "scratch memory" if scratch_only else "register spills", bad))
+    return "%d kernel(s), %s" % (len(names), "no scratch" if scratch_only else "no spills, no scratch")
 
 
 def build_library(verbose: bool = False) -> str:
@@ -44,7 +48,7 @@ def build_library(verbose: bool = False) -> str:
     def compile_one(src: str) -> str:
         obj = os.path.join(bdir, src.replace(".hip", ".o"))
         cmd = [hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
-        if src in NO_SPILL_SOURCES:
+        if src in KERNEL_SOURCES:
             cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -52,8 +56,8 @@ def build_library(verbose: bool = False) -> str:
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed on %s:\n%s" % (src, err))
-        if src in NO_SPILL_SOURCES:
-            usage = check_no_spills(src, err)
+        if src in KERNEL_SOURCES:
+            usage = check_no_spills(src, err, scratch_only=src not in NO_SPILL_SOURCES)
             err = "\n".join(l for l in err.splitlines() if "kernel-resource-usage" not in l and l.strip(" |^0123456789{"))
             if verbose:
                 print("%s: %s" % (src, usage))

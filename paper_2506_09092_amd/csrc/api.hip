@@ -47,8 +47,8 @@ int plan_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const
     return FSRGEMM_OK;
 }
 
-int plan_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
-              Plan *p)
+int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B,
+              int64_t ldb, Plan *p)
 {
     int b;
     if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) p->cfg = kBf16_256x256, b = 256;
@@ -57,8 +57,9 @@ int plan_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, c
     if (ceil_div(M, b) * ceil_div(N, b) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
     const bool vec = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0;
     p->mode = !vec ? kScalar : (M % b == 0 && N % b == 0 && K % 64 == 0 && K > 0) ? kFast : kVecPred;
-    // the direct-to-LDS kernel needs whole 256 x 256 x 64 tiles and 32-bit lane offsets
-    if (b == 256 && p->mode == kFast && lda < (1 << 25) && ldb < (1 << 25)) p->cfg = kBf16_Main;
+    // the direct-to-LDS kernel needs both operands contiguous along k, whole 256 x 256 x 64 tiles and 32-bit lane offsets
+    if (b == 256 && p->mode == kFast && a_lay == kKContig && b_lay == kKContig && lda < (1 << 25) && ldb < (1 << 25))
+        p->cfg = kBf16_Main;
     return FSRGEMM_OK;
 }
 
@@ -143,15 +144,23 @@ int gemm_f32_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const f
 int gemm_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
               float *C, int64_t ldc, void *stream)
 {
-    int rc = check_args(M, N, K, A, lda, K, B, ldb, K, C, ldc);
+    return gemm_bf16_ex(0, 1, M, N, K, A, lda, B, ldb, C, ldc, stream);
+}
+
+int gemm_bf16_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
+                 const uint16_t *B, int64_t ldb, float *C, int64_t ldc, void *stream)
+{
+    int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
     if (rc != FSRGEMM_OK) return rc;
+    const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
     Plan p;
-    rc = plan_bf16(M, N, K, A, lda, B, ldb, &p);
+    rc = plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, &p);
     if (rc != FSRGEMM_OK) return rc;
     if (M == 0 || N == 0) return FSRGEMM_OK;
     rc = device_ok();
     if (rc != FSRGEMM_OK) return rc;
-    const hipError_t e = launch_bf16(p.cfg, p.mode, pack(M, N, K, A, lda, B, ldb, C, ldc), static_cast<hipStream_t>(stream));
+    const hipError_t e = launch_bf16(p.cfg, p.mode, a_lay, b_lay, pack(M, N, K, A, lda, B, ldb, C, ldc),
+                                     static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
 }
 
@@ -173,10 +182,17 @@ const char *fsrgemm_kernel_for_f32_ex(int transA, int transB, int64_t M, int64_t
 const char *fsrgemm_kernel_for_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
                                     const uint16_t *B, int64_t ldb, const float *C, int64_t ldc)
 {
+    return fsrgemm_kernel_for_bf16_ex(0, 1, M, N, K, A, lda, B, ldb, C, ldc);
+}
+
+const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A,
+                                       int64_t lda, const uint16_t *B, int64_t ldb, const float *C, int64_t ldc)
+{
     Plan p;
-    if (check_args(M, N, K, A, lda, K, B, ldb, K, C, ldc) != FSRGEMM_OK) return nullptr;
-    if (plan_bf16(M, N, K, A, lda, B, ldb, &p) != FSRGEMM_OK) return nullptr;
-    return bf16_kernel_name(p.cfg, p.mode);
+    if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
+    const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
+    if (plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, &p) != FSRGEMM_OK) return nullptr;
+    return bf16_kernel_name(p.cfg, p.mode, a_lay, b_lay);
 }
 
 const char *fsrgemm_status_string(int status)

@@ -69,11 +69,12 @@ enum F32Config { kF32_256x128 = 0, kF32_128x128 = 1, kF32_64x64 = 2, kF32ConfigC
 const char *f32_kernel_name(int cfg, int mode, int a_lay, int b_lay);
 hipError_t launch_f32(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 
-// bf16 configurations: the direct-to-LDS 256x256 kernel for aligned, tile-multiple problems
-// (gemm_bf16_main.hip) and three tile sizes of the general kernel (gemm_bf16.hip), each in the three load modes
+// bf16 configurations: the direct-to-LDS 256x256 kernel for aligned, tile-multiple problems with both
+// operands contiguous along k (gemm_bf16_main.hip) and three tile sizes of the general kernel
+// (gemm_bf16.hip), each in the three load modes and the four layout pairs
 enum Bf16Config { kBf16_Main = 0, kBf16_256x256 = 1, kBf16_128x128 = 2, kBf16_64x64 = 3, kBf16ConfigCount };
-const char *bf16_kernel_name(int cfg, int mode);
-hipError_t launch_bf16(int cfg, int mode, const GemmArgs &a, hipStream_t s);
+const char *bf16_kernel_name(int cfg, int mode, int a_lay, int b_lay);
+hipError_t launch_bf16(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 const char *bf16_main_kernel_name();
 hipError_t launch_bf16_main(const GemmArgs &a, hipStream_t s);
 

@@ -1,30 +1,41 @@
-// bf16 x bf16 -> fp32 GEMM for gfx950: C[M x N] = A[M x K] . B[K x N] with A
-// row-major and B column-major, so both operands are contiguous along k (the
-// same product as the paper's Task 2, at the reduced input precision that
-// matrix cores are built for; accumulation and output stay fp32).
+// bf16 x bf16 -> fp32 GEMM for gfx950: C[M x N] = A[M x K] . B[K x N], C row-major
+// fp32, each operand in either storage order (the same product as the paper's
+// Task 2, at the reduced input precision that matrix cores are built for;
+// accumulation and output stay fp32).
 //
-// This file holds the general-purpose kernel: any shape, any alignment, three
-// tile sizes.  Large aligned problems go to the kernel in gemm_bf16_main.hip.
+// This file holds the general-purpose kernel: any shape, any alignment, any
+// storage order, three tile sizes.  Large aligned problems whose operands are
+// both contiguous along k go to the kernel in gemm_bf16_main.hip.
 //
 // One workgroup of 256 lanes (4 wavefronts, 2 x 2) owns a (64 T) x (64 T) tile
-// of C, each wavefront T x T blocks of V_MFMA_F32_32X32X16_BF16: lane l
-// supplies eight consecutive k (16 bytes) of row l % 32, k-offset 8 * (l / 32),
-// for each operand -- one 16-byte LDS read per operand block and k-step.  Per
-// K-tile of 64 (one 128-byte row per tile row, four k-steps) A[BM x 64] and
+// of C, each wavefront 2T x 2T blocks of V_MFMA_F32_16X16X32_BF16: lane l
+// supplies eight consecutive k (16 bytes) of row l % 16, k-offset 8 * (l / 16),
+// for each operand -- one 16-byte LDS read per operand block and k-step of 32.
+// Per K-tile of 64 (one 128-byte row per tile row, two k-steps) A[BM x 64] and
 // B^T[BN x 64] are staged through registers into double-buffered LDS; staging
-// through registers is what lets ragged edges be zero-filled lane by lane.
+// through registers is what lets ragged edges be zero-filled lane by lane and
+// lets an operand that is contiguous along m / n be transposed on the way: a
+// lane then loads an 8-row x NV-k block as NV vectors of 8 rows, regroups the
+// 16-bit values in registers and stores 8 row pieces of NV k.
 //
 // LDS rows are 128 bytes with no padding; the 16-byte chunk c of row r is kept
 // at chunk position c ^ ((r >> 1) & 7), so that the 16 rows that one group of
 // lanes reads at one k-offset cover all 64 banks exactly once.
 //
-// The loop is an explicit schedule, fenced so the compiler keeps it: every
-// MFMA of k-step kk is followed by its share of that k-step's other
-// instructions -- the fragment reads of k-step kk+1, then LDS stores of the
-// next K-tile (k-steps 0 and 1) or global loads of the one after (k-steps 2 and
-// 3, each register reloaded only after it has been stored).  The one barrier
-// per K-tile follows k-step 2: the last fragments of this stage are in
-// registers by then and the next stage is completely written.
+// The loop is an explicit schedule, fenced so the compiler keeps it: the MFMAs
+// of a k-step carry, evenly spread, the fragment reads of the next k-step and
+// either the LDS stores of the next K-tile (k-step 0) or the global loads of the
+// one after (k-step 1, each register reloaded only after it has been stored).
+// The one barrier per K-tile sits between the k-steps: the last fragments of
+// this stage are in registers by then and the next stage is completely written.
+// Of the three load modes (as in gemm_f32.hip), the one for aligned but ragged
+// problems lets a workgroup whose tile lies inside the matrix load its whole
+// K-tiles unchecked; only the ragged end of K and the edge tiles pay for checks.
+// The MFMAs are inline assembly so that every accumulator block stays in its
+// registers across the loop (see gemm_bf16_main.hip); a block is touched again
+// NB * NB >= 4 MFMAs later and the epilogue starts behind explicit wait states.
+#include <stdio.h>
+
 #include <type_traits>
 
 #include "common.hpp"
@@ -39,7 +50,7 @@ constexpr int kRowBytes = kBK * 2;
 template <int MODE>
 __device__ __forceinline__ u32x4 load8(const uint16_t *__restrict__ p, bool row_ok, int col, int col_limit)
 {
-    // p points at element (row, col); the vector covers col .. col+7 of that row.
+    // p points at element (row, col) of the stored matrix; the vector covers col .. col+7 of that row.
     if constexpr (MODE == kFast) {
         return *reinterpret_cast<const u32x4 *>(p);
     } else {
@@ -55,7 +66,56 @@ __device__ __forceinline__ u32x4 load8(const uint16_t *__restrict__ p, bool row_
     }
 }
 
-template <int T, int MIN_WAVES, int MODE>
+// A lane's share of one operand tile (EXT rows of m or n, 64 k) on its way global -> registers -> LDS.
+// NV = EXT / 32 vectors of 16 bytes per lane either way.
+//   kKContig : vector s = row (tid >> 3) + 32 s of the tile, 16-byte chunk tid & 7 of its 64 k: stored as loaded
+//   kMnContig: the lane owns rows 8 rb .. 8 rb + 7 and k = NV kg .. NV kg + NV - 1 (kg = tid % (64 / NV),
+//              rb = tid / (64 / NV)); vector s holds those 8 rows at k = NV kg + s.  Eight row pieces of NV k
+//              (2 NV bytes) go to LDS, `8 / NV` of them per store step so that both layouts take NV steps.
+template <int EXT, int LAY>
+struct Staging {
+    static constexpr int NV = EXT / 32;
+    static constexpr int KG = kBK / NV;
+
+    template <int MODE>
+    static __device__ __forceinline__ u32x4 gload(const uint16_t *__restrict__ base, int64_t ld, int r0, int rows, int k0,
+                                                  int K, int tid, int s)
+    {
+        if constexpr (LAY == kKContig) {
+            const int r = (tid >> 3) + 32 * s, k = (tid & 7) * 8;
+            return load8<MODE>(base + (int64_t)(r0 + r) * ld + k0 + k, r0 + r < rows, k0 + k, K);
+        } else {
+            const int r = 8 * (tid / KG), k = NV * (tid % KG) + s;
+            return load8<MODE>(base + (int64_t)(k0 + k) * ld + r0 + r, k0 + k < K, r0 + r, rows);
+        }
+    }
+    // store step s of this operand; v = the lane's NV vectors, tile = LDS address of the operand tile's stage
+    static __device__ __forceinline__ void lstore(char *tile, const u32x4 *v, int tid, int s)
+    {
+        if constexpr (LAY == kKContig) {
+            const int r = (tid >> 3) + 32 * s, c = tid & 7;
+            *reinterpret_cast<u32x4 *>(tile + r * kRowBytes + ((c ^ ((r >> 1) & 7)) * 16)) = v[s];
+        } else {
+            const int kb = NV * (tid % KG) * 2;         // byte offset of the lane's k range inside a row
+#pragma unroll
+            for (int i = s * (8 / NV); i < (s + 1) * (8 / NV); ++i) {
+                const int r = 8 * (tid / KG) + i;
+                uint32_t w[NV / 2];
+#pragma unroll
+                for (int j = 0; j < NV / 2; ++j) {      // k = 2j, 2j + 1 of row i: one half of a dword from each vector
+                    const uint32_t x = v[2 * j][i >> 1], y = v[2 * j + 1][i >> 1];
+                    w[j] = (i & 1) ? (x >> 16) | (y & 0xFFFF0000u) : (x & 0xFFFFu) | (y << 16);
+                }
+                char *p = tile + r * kRowBytes + (((kb >> 4) ^ ((r >> 1) & 7)) * 16) + (kb & 15);
+                if constexpr (NV == 8) *reinterpret_cast<u32x4 *>(p) = u32x4{w[0], w[1], w[2], w[3]};
+                else if constexpr (NV == 4) *reinterpret_cast<uint2 *>(p) = uint2{w[0], w[1]};
+                else *reinterpret_cast<uint32_t *>(p) = w[0];
+            }
+        }
+    }
+};
+
+template <int T, int MIN_WAVES, int MODE, int ALAY, int BLAY>
 __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs g, int tiles_m, int tiles_n)
 {
     constexpr int BM = 64 * T, BN = 64 * T;
@@ -63,10 +123,13 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
     constexpr int STAGE_B = 2 * TILE_B;             // A + B
     constexpr int NV = BM / 32;                     // 16-byte vectors per lane per operand and K-tile
     constexpr int NG = 2 * NV;                      // ... of both operands
-    constexpr int NR = 2 * T;                       // fragment reads per k-step
-    constexpr int NMF = T * T;                      // MFMAs per k-step
-    constexpr int NC = NR + NG / 2;                 // companion instructions per k-step
-    constexpr int PER_SLOT = (NC + NMF - 1) / NMF;
+    constexpr int NB = 2 * T;                       // 16-row blocks per wavefront and operand
+    constexpr int NR = 2 * NB;                      // fragment reads per k-step; equals NG
+    constexpr int NMF = NB * NB;                    // MFMAs per k-step
+    constexpr int NC = NR + NG;                     // companion instructions per k-step, alternating read / memory
+    static_assert(NR == NG, "reads and memory operations alternate");
+    using StA = Staging<BM, ALAY>;
+    using StB = Staging<BN, BLAY>;
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
@@ -80,7 +143,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave >> 1) * 32 * T, wn0 = (wave & 1) * 32 * T;
-    const int li = lane & 31, lh = lane >> 5;
+    const int l16 = lane & 15, lq = lane >> 4;
     const int nk = (K + kBK - 1) / kBK;
 
     if (nk == 0) {      // K == 0: every entry is an empty sum
@@ -91,69 +154,64 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
         return;
     }
 
-    // Global side: per pass s the workgroup fetches 32 rows; lane covers row (tid >> 3) + 32 s, chunk tid & 7.
-    const int grow = tid >> 3, gchunk = tid & 7;
-    const uint16_t *a_ptr = A + (int64_t)(m0 + grow) * g.lda + gchunk * 8;
-    const uint16_t *b_ptr = B + (int64_t)(n0 + grow) * g.ldb + gchunk * 8;
-    const int64_t a_step = 32 * g.lda, b_step = 32 * g.ldb;
-    u32x4 rg[NG];       // idx < NV: A pass idx; else B pass idx - NV
-    auto gload = [&](int idx, int t) {      // K-tiles past the end are clamped: loaded again, never consumed
+    // A workgroup whose tile lies inside the matrix needs no check on whole K-tiles even when the problem as a
+    // whole is ragged: `unchecked` counts the leading K-tiles it may load like the unchecked mode does.
+    const int unchecked = MODE == kFast ? nk : (MODE == kVecPred && m0 + BM <= M && n0 + BN <= N) ? K / kBK : 0;
+    u32x4 rg[NG];       // idx < NV: A's vectors; else B's
+    auto gload = [&](auto load_mode, int idx, int t) {      // K-tiles past the end are clamped: loaded again, never consumed
+        constexpr int LM = decltype(load_mode)::value;
         const int k0 = (t < nk ? t : nk - 1) * kBK;
-        if (idx < NV) rg[idx] = load8<MODE>(a_ptr + idx * a_step + k0, m0 + grow + 32 * idx < M, k0 + gchunk * 8, K);
-        else rg[idx] = load8<MODE>(b_ptr + (idx - NV) * b_step + k0, n0 + grow + 32 * (idx - NV) < N, k0 + gchunk * 8, K);
+        if (idx < NV) rg[idx] = StA::template gload<LM>(A, g.lda, m0, M, k0, K, tid, idx);
+        else rg[idx] = StB::template gload<LM>(B, g.ldb, n0, N, k0, K, tid, idx - NV);
     };
-    const int w_off = grow * kRowBytes + ((gchunk ^ ((grow >> 1) & 7)) * 16);
+    using Checked = std::integral_constant<int, MODE>;
+    using Unchecked = std::integral_constant<int, kFast>;
     auto lwrite = [&](int stage, int idx) {
-        char *p = smem + stage * STAGE_B + w_off + (idx < NV ? idx * 32 * kRowBytes : TILE_B + (idx - NV) * 32 * kRowBytes);
-        *reinterpret_cast<u32x4 *>(p) = rg[idx];
+        if (idx < NV) StA::lstore(smem + stage * STAGE_B, rg, tid, idx);
+        else StB::lstore(smem + stage * STAGE_B + TILE_B, rg + NV, tid, idx - NV);
     };
-    // Fragment reads: block row li of the wavefront's A (or B) rows, k-chunk 2 kk + lh.
-    const int ra0 = (wm0 + li) * kRowBytes, rb0 = TILE_B + (wn0 + li) * kRowBytes;
-    const int rsw = (li >> 1) & 7;
-    bf16x8 fa[2][T], fb[2][T];
-    auto lread = [&](int stage, int kk, int fi, int idx) {    // idx < T: A block idx; else B block idx - T
-        const int pos = ((2 * kk + lh) ^ rsw) * 16;
+    // Fragment of 16 rows x 32 k: the lane reads row l16 of the block, 16-byte chunk 4 kk + lq.
+    const int ra0 = (wm0 + l16) * kRowBytes, rb0 = TILE_B + (wn0 + l16) * kRowBytes;
+    const int rsw = (l16 >> 1) & 7;
+    bf16x8 fa[2][NB], fb[2][NB];
+    auto lread = [&](int stage, int kk, int idx) {    // into the fragments of k-step kk; idx < NB: A block idx; else B block
+        const int pos = ((4 * kk + lq) ^ rsw) * 16;
         const char *s = smem + stage * STAGE_B + pos;
-        if (idx < T) fa[fi][idx] = *reinterpret_cast<const bf16x8 *>(s + ra0 + idx * 32 * kRowBytes);
-        else fb[fi][idx - T] = *reinterpret_cast<const bf16x8 *>(s + rb0 + (idx - T) * 32 * kRowBytes);
+        if (idx < NB) fa[kk][idx] = *reinterpret_cast<const bf16x8 *>(s + ra0 + idx * 16 * kRowBytes);
+        else fb[kk][idx - NB] = *reinterpret_cast<const bf16x8 *>(s + rb0 + (idx - NB) * 16 * kRowBytes);
     };
 
-    f32x16 acc[T][T];
+    f32x4 acc[NB][NB];
 #pragma unroll
-    for (int i = 0; i < T; ++i)
+    for (int i = 0; i < NB; ++i)
 #pragma unroll
-        for (int j = 0; j < T; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // K-tile t of parity P reads stage X = P; K-tile t+1 (in rg) is stored to Y = 1-P during k-steps 0 and 1,
-    // rg is refilled with K-tile t+2 during k-steps 2 and 3.
-    auto k_tile = [&](auto parity, int t) {
+    // K-tile t of parity P reads stage X = P; K-tile t+1 (in rg) is stored to Y = 1-P during k-step 0,
+    // rg is refilled with K-tile t+2 during k-step 1.
+    auto k_tile = [&](auto parity, auto load_mode, int t) {
         constexpr int P = decltype(parity)::value;
         constexpr int X = P, Y = 1 - P;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int fc = kk & 1, fn = fc ^ 1;
+        for (int kk = 0; kk < 2; ++kk) {
 #pragma unroll
             for (int m = 0; m < NMF; ++m) {
-                acc[m / T][m % T] =
-                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[fc][m / T], fb[fc][m % T], acc[m / T][m % T], 0, 0, 0);
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
+                             : "+a"(acc[m / NB][m % NB])
+                             : "v"(fa[kk][m / NB]), "v"(fb[kk][m % NB]));
 #pragma unroll
-                for (int c = m * PER_SLOT; c < (m + 1) * PER_SLOT && c < NC; ++c) {
-                    if (c < NR) {
-                        if (kk < 3) lread(X, kk + 1, fn, c); else lread(Y, 0, fn, c);
+                for (int c = m * NC / NMF; c < (m + 1) * NC / NMF; ++c) {
+                    const int q = c >> 1;
+                    if ((c & 1) == 0) {
+                        if (kk == 0) lread(X, 1, q); else lread(Y, 0, q);
                     } else {
-                        const int h = c - NR;       // 0 .. NG/2 - 1
-                        if (kk == 0) lwrite(Y, h);
-                        else if (kk == 1) lwrite(Y, NG / 2 + h);
-                        else if (kk == 2) gload(h, t + 2);
-                        else gload(NG / 2 + h, t + 2);
+                        if (kk == 0) lwrite(Y, q); else gload(load_mode, q, t + 2);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (kk == 2) {
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (kk == 0) {
+                __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0): this wavefront's LDS stores and reads are done
                 __builtin_amdgcn_s_barrier();
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -161,47 +219,66 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
     };
 
     // Prologue: K-tile 0 through the registers into stage 0, K-tile 1 into the registers, first fragments.
+    if (MODE == kVecPred && unchecked >= 1) {
 #pragma unroll
-    for (int idx = 0; idx < NG; ++idx) gload(idx, 0);
+        for (int idx = 0; idx < NG; ++idx) gload(Unchecked{}, idx, 0);
+    } else {
+#pragma unroll
+        for (int idx = 0; idx < NG; ++idx) gload(Checked{}, idx, 0);
+    }
 #pragma unroll
     for (int idx = 0; idx < NG; ++idx) lwrite(0, idx);
     __builtin_amdgcn_sched_barrier(0);
+    if (MODE == kVecPred && unchecked >= 2) {
 #pragma unroll
-    for (int idx = 0; idx < NG; ++idx) gload(idx, 1);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        for (int idx = 0; idx < NG; ++idx) gload(Unchecked{}, idx, 1);
+    } else {
+#pragma unroll
+        for (int idx = 0; idx < NG; ++idx) gload(Checked{}, idx, 1);
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int idx = 0; idx < NR; ++idx) lread(0, 0, 0, idx);
+    for (int idx = 0; idx < NR; ++idx) lread(0, 0, idx);
     __builtin_amdgcn_sched_barrier(0);
 
     int t = 0;
-    for (; t + 1 < nk; t += 2) {
-        k_tile(std::integral_constant<int, 0>{}, t);
-        k_tile(std::integral_constant<int, 1>{}, t + 1);
+    if constexpr (MODE == kVecPred) {
+        // K-tile t loads K-tile t + 2: this loop runs while t + 3 is still an unchecked K-tile
+        for (; t + 3 < unchecked; t += 2) {
+            k_tile(std::integral_constant<int, 0>{}, Unchecked{}, t);
+            k_tile(std::integral_constant<int, 1>{}, Unchecked{}, t + 1);
+        }
     }
-    if (t < nk) k_tile(std::integral_constant<int, 0>{}, t);
+    for (; t + 1 < nk; t += 2) {
+        k_tile(std::integral_constant<int, 0>{}, Checked{}, t);
+        k_tile(std::integral_constant<int, 1>{}, Checked{}, t + 1);
+    }
+    if (t < nk) k_tile(std::integral_constant<int, 0>{}, Checked{}, t);
+    // the last MFMAs must have retired before the accumulators are read (the compiler does not know what wrote them)
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
-    // Register r of a 32x32 block holds row (r/4)*8 + 4*(lane/32) + r%4, column lane%32.
+    // Register r of a 16x16 block holds row 4 (lane / 16) + r, column lane % 16.
 #pragma unroll
-    for (int i = 0; i < T; ++i)
+    for (int i = 0; i < NB; ++i)
 #pragma unroll
-        for (int j = 0; j < T; ++j) {
-            const int col = n0 + wn0 + j * 32 + li;
+        for (int j = 0; j < NB; ++j) {
+            const int col = n0 + wn0 + j * 16 + l16;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
+            for (int r = 0; r < 4; ++r) {
+                const int row = m0 + wm0 + i * 16 + lq * 4 + r;
                 if (MODE == kFast || (row < M && col < N)) C[(int64_t)row * g.ldc + col] = acc[i][j][r];
             }
         }
 }
 
-template <int T, int MIN_WAVES, int MODE>
+template <int T, int MIN_WAVES, int MODE, int ALAY, int BLAY>
 hipError_t launch_one(const GemmArgs &a, hipStream_t s)
 {
     constexpr int BM = 64 * T;
     constexpr int lds = 2 * 2 * BM * kRowBytes;
-    auto kern = gemm_bf16_kernel<T, MIN_WAVES, MODE>;
+    auto kern = gemm_bf16_kernel<T, MIN_WAVES, MODE, ALAY, BLAY>;
     static std::atomic<uint64_t> configured{0};
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, configured);
     if (e != hipSuccess) return e;
@@ -210,36 +287,56 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int T, int MIN_WAVES>
-hipError_t launch_cfg(int mode, const GemmArgs &a, hipStream_t s)
+template <int T, int MIN_WAVES, int ALAY, int BLAY>
+hipError_t launch_lay(int mode, const GemmArgs &a, hipStream_t s)
 {
     switch (mode) {
-    case kFast: return launch_one<T, MIN_WAVES, kFast>(a, s);
-    case kVecPred: return launch_one<T, MIN_WAVES, kVecPred>(a, s);
-    default: return launch_one<T, MIN_WAVES, kScalar>(a, s);
+    case kFast: return launch_one<T, MIN_WAVES, kFast, ALAY, BLAY>(a, s);
+    case kVecPred: return launch_one<T, MIN_WAVES, kVecPred, ALAY, BLAY>(a, s);
+    default: return launch_one<T, MIN_WAVES, kScalar, ALAY, BLAY>(a, s);
     }
+}
+
+template <int T, int MIN_WAVES>
+hipError_t launch_cfg(int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
+{
+    if (a_lay == kKContig) {
+        return b_lay == kKContig ? launch_lay<T, MIN_WAVES, kKContig, kKContig>(mode, a, s)
+                                 : launch_lay<T, MIN_WAVES, kKContig, kMnContig>(mode, a, s);
+    }
+    return b_lay == kKContig ? launch_lay<T, MIN_WAVES, kMnContig, kKContig>(mode, a, s)
+                             : launch_lay<T, MIN_WAVES, kMnContig, kMnContig>(mode, a, s);
 }
 
 }  // namespace
 
-// <T, minimum wavefronts per SIMD, load mode>: tile (64 T) x (64 T); as a profiler trace prints the kernel
-const char *bf16_kernel_name(int cfg, int mode)
+// <T, minimum wavefronts per SIMD, load mode, A layout, B layout>: tile (64 T) x (64 T); as a profiler trace prints it
+const char *bf16_kernel_name(int cfg, int mode, int a_lay, int b_lay)
 {
-    static const char *names[3][3] = {
-        {"gemm_bf16_kernel<4, 1, 0>", "gemm_bf16_kernel<4, 1, 1>", "gemm_bf16_kernel<4, 1, 2>"},
-        {"gemm_bf16_kernel<2, 2, 0>", "gemm_bf16_kernel<2, 2, 1>", "gemm_bf16_kernel<2, 2, 2>"},
-        {"gemm_bf16_kernel<1, 4, 0>", "gemm_bf16_kernel<1, 4, 1>", "gemm_bf16_kernel<1, 4, 2>"},
+    struct Names {
+        char text[3][3][2][2][40];
+        Names()
+        {
+            static const char *shapes[3] = {"4, 1", "2, 2", "1, 4"};
+            for (int c = 0; c < 3; ++c)
+                for (int m = 0; m < 3; ++m)
+                    for (int x = 0; x < 2; ++x)
+                        for (int y = 0; y < 2; ++y)
+                            snprintf(text[c][m][x][y], sizeof text[c][m][x][y], "gemm_bf16_kernel<%s, %d, %d, %d>", shapes[c],
+                                     m, x, y);
+        }
     };
-    return cfg == kBf16_Main ? bf16_main_kernel_name() : names[cfg - 1][mode];
+    static const Names names;
+    return cfg == kBf16_Main ? bf16_main_kernel_name() : names.text[cfg - 1][mode][a_lay][b_lay];
 }
 
-hipError_t launch_bf16(int cfg, int mode, const GemmArgs &a, hipStream_t s)
+hipError_t launch_bf16(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
     switch (cfg) {
     case kBf16_Main: return launch_bf16_main(a, s);
-    case kBf16_256x256: return launch_cfg<4, 1>(mode, a, s);
-    case kBf16_128x128: return launch_cfg<2, 2>(mode, a, s);
-    default: return launch_cfg<1, 4>(mode, a, s);
+    case kBf16_256x256: return launch_cfg<4, 1>(mode, a_lay, b_lay, a, s);
+    case kBf16_128x128: return launch_cfg<2, 2>(mode, a_lay, b_lay, a, s);
+    default: return launch_cfg<1, 4>(mode, a_lay, b_lay, a, s);
     }
 }
 

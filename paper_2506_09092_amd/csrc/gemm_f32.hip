@@ -32,7 +32,10 @@
 // Three load modes share the code: unchecked 16-byte vectors (aligned problems
 // that are a whole number of tiles with K a multiple of 16), vectors with
 // element-wise zero-filled edges (aligned, ragged), element-wise predicated
-// loads (any alignment).  Ragged modes also mask the stores.
+// loads (any alignment).  Ragged modes also mask the stores.  In the second
+// mode a workgroup whose tile lies inside the matrix runs its whole K-tiles
+// through the unchecked loads and only the ragged end of K through the checked
+// ones, so a ragged problem pays for its edges only at its edges.
 #include <stdio.h>
 
 #include <type_traits>
@@ -153,12 +156,18 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
         return;
     }
 
+    // A workgroup whose tile lies inside the matrix needs no check on whole K-tiles even when the problem as a
+    // whole is ragged: `unchecked` counts the leading K-tiles it may load like the unchecked mode does.
+    const int unchecked = MODE == kFast ? nk : (MODE == kVecPred && m0 + BM <= M && n0 + BN <= N) ? K / kBK : 0;
     f32x4 rg[NG];
-    auto gload = [&](int idx, int t) {      // K-tiles past the end are clamped: loaded again, never consumed
+    auto gload = [&](auto load_mode, int idx, int t) {      // K-tiles past the end are clamped: loaded again, never consumed
+        constexpr int LM = decltype(load_mode)::value;
         const int k0 = (t < nk ? t : nk - 1) * kBK;
-        if (idx < NA) rg[idx] = OpA::template gload<MODE>(A, g.lda, m0, M, k0, K, tid, idx);
-        else rg[idx] = OpB::template gload<MODE>(B, g.ldb, n0, N, k0, K, tid, idx - NA);
+        if (idx < NA) rg[idx] = OpA::template gload<LM>(A, g.lda, m0, M, k0, K, tid, idx);
+        else rg[idx] = OpB::template gload<LM>(B, g.ldb, n0, N, k0, K, tid, idx - NA);
     };
+    using Checked = std::integral_constant<int, MODE>;
+    using Unchecked = std::integral_constant<int, kFast>;
     auto lwrite = [&](int stage, int idx) {
         if (idx < NA) *reinterpret_cast<f32x4 *>(&As[stage * A_ST + OpA::lds_store_at(tid, idx)]) = rg[idx];
         else *reinterpret_cast<f32x4 *>(&Bs[stage * B_ST + OpB::lds_store_at(tid, idx - NA)]) = rg[idx];
@@ -179,7 +188,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
 
     // K-tile t of parity P reads stage P.  Chunk 0: fragments of chunk 1, then the staged K-tile t+1 goes to
     // stage 1-P; barrier.  Chunk 1: fragments of K-tile t+1's chunk 0 from stage 1-P, then global loads of t+2.
-    auto k_tile = [&](auto parity, int t) {
+    auto k_tile = [&](auto parity, auto load_mode, int t) {
         constexpr int P = decltype(parity)::value;
         constexpr int X = P, Y = 1 - P;
 #pragma unroll
@@ -194,7 +203,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
                     if (c < NR) {
                         if (kk == 0) lread(X, 1, fn, c); else lread(Y, 0, fn, c);
                     } else {
-                        if (kk == 0) lwrite(Y, c - NR); else gload(c - NR, t + 2);
+                        if (kk == 0) lwrite(Y, c - NR); else gload(load_mode, c - NR, t + 2);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -207,13 +216,23 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
         }
     };
 
+    if (MODE == kVecPred && unchecked >= 1) {
 #pragma unroll
-    for (int idx = 0; idx < NG; ++idx) gload(idx, 0);
+        for (int idx = 0; idx < NG; ++idx) gload(Unchecked{}, idx, 0);
+    } else {
+#pragma unroll
+        for (int idx = 0; idx < NG; ++idx) gload(Checked{}, idx, 0);
+    }
 #pragma unroll
     for (int idx = 0; idx < NG; ++idx) lwrite(0, idx);
     __builtin_amdgcn_sched_barrier(0);
+    if (MODE == kVecPred && unchecked >= 2) {
 #pragma unroll
-    for (int idx = 0; idx < NG; ++idx) gload(idx, 1);
+        for (int idx = 0; idx < NG; ++idx) gload(Unchecked{}, idx, 1);
+    } else {
+#pragma unroll
+        for (int idx = 0; idx < NG; ++idx) gload(Checked{}, idx, 1);
+    }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -222,11 +241,18 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
     __builtin_amdgcn_sched_barrier(0);
 
     int t = 0;
-    for (; t + 1 < nk; t += 2) {
-        k_tile(std::integral_constant<int, 0>{}, t);
-        k_tile(std::integral_constant<int, 1>{}, t + 1);
+    if constexpr (MODE == kVecPred) {
+        // K-tile t loads K-tile t + 2: this loop runs while t + 3 is still an unchecked K-tile
+        for (; t + 3 < unchecked; t += 2) {
+            k_tile(std::integral_constant<int, 0>{}, Unchecked{}, t);
+            k_tile(std::integral_constant<int, 1>{}, Unchecked{}, t + 1);
+        }
     }
-    if (t < nk) k_tile(std::integral_constant<int, 0>{}, t);
+    for (; t + 1 < nk; t += 2) {
+        k_tile(std::integral_constant<int, 0>{}, Checked{}, t);
+        k_tile(std::integral_constant<int, 1>{}, Checked{}, t + 1);
+    }
+    if (t < nk) k_tile(std::integral_constant<int, 0>{}, Checked{}, t);
 
     // Register r of a 32x32 block holds row (r/4)*8 + 4*(lane/32) + r%4, column lane%32: each store
     // instruction writes two 128-byte row segments.

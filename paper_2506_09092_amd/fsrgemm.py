@@ -12,7 +12,7 @@ import os
 
 __all__ = [
     "load", "library_path", "gemm_f32", "gemm_f32_ex", "gemm_bf16", "fsrgemm_kernel_for_f32",
-    "fsrgemm_kernel_for_f32_ex", "fsrgemm_kernel_for_bf16",
+    "fsrgemm_kernel_for_f32_ex", "fsrgemm_kernel_for_bf16", "gemm_bf16_ex", "fsrgemm_kernel_for_bf16_ex",
     "fsrgemm_status_string", "fsrgemm_version", "check", "FsrGemmError", "EXPORTS",
     "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
 ]
@@ -30,9 +30,11 @@ EXPORTS = {
     "gemm_f32": (ctypes.c_int, _GEMM),
     "gemm_f32_ex": (ctypes.c_int, [ctypes.c_int, ctypes.c_int] + _GEMM),
     "gemm_bf16": (ctypes.c_int, _GEMM),
+    "gemm_bf16_ex": (ctypes.c_int, [ctypes.c_int, ctypes.c_int] + _GEMM),
     "fsrgemm_kernel_for_f32": (ctypes.c_char_p, _QUERY),
     "fsrgemm_kernel_for_f32_ex": (ctypes.c_char_p, [ctypes.c_int, ctypes.c_int] + _QUERY),
     "fsrgemm_kernel_for_bf16": (ctypes.c_char_p, _QUERY),
+    "fsrgemm_kernel_for_bf16_ex": (ctypes.c_char_p, [ctypes.c_int, ctypes.c_int] + _QUERY),
     "fsrgemm_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "fsrgemm_version": (ctypes.c_int, []),
 }
@@ -91,6 +93,11 @@ def gemm_bf16(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
     return load().gemm_bf16(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _ptr(stream) or None)
 
 
+def gemm_bf16_ex(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
+    return load().gemm_bf16_ex(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
+                               _ptr(stream) or None)
+
+
 def fsrgemm_kernel_for_f32(M, N, K, A, lda, B, ldb, C, ldc):
     r = load().fsrgemm_kernel_for_f32(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc)
     return None if r is None else r.decode()
@@ -103,6 +110,11 @@ def fsrgemm_kernel_for_f32_ex(transA, transB, M, N, K, A, lda, B, ldb, C, ldc):
 
 def fsrgemm_kernel_for_bf16(M, N, K, A, lda, B, ldb, C, ldc):
     r = load().fsrgemm_kernel_for_bf16(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc)
+    return None if r is None else r.decode()
+
+
+def fsrgemm_kernel_for_bf16_ex(transA, transB, M, N, K, A, lda, B, ldb, C, ldc):
+    r = load().fsrgemm_kernel_for_bf16_ex(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc)
     return None if r is None else r.decode()
 
 

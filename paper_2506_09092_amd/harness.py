@@ -86,6 +86,32 @@ def run_bf16(lib, A: np.ndarray, Bt: np.ndarray, lda=None, ldb=None, ldc=None, o
     return outs[0]
 
 
+def run_bf16_ex(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, lda=None, ldb=None, ldc=None, offset=0,
+                repeat=1):
+    """C = A.B through gemm_bf16_ex.  A (M x K) and B (K x N) are the logical operands as bf16 bits; an operand
+    flagged transposed is handed to the library in transposed storage (K x M, N x K)."""
+    M, K = A.shape
+    N = B.shape[1]
+    sa = np.ascontiguousarray(A.T) if transA else A
+    sb = np.ascontiguousarray(B.T) if transB else B
+    lda, ldb, ldc = lda or max(sa.shape[1], 1), ldb or max(sb.shape[1], 1), ldc or max(N, 1)
+    nan16 = np.uint16(0x7FC0)
+    a = _dev(inputs.embed(sa, lda, nan16, offset))
+    b = _dev(inputs.embed(sb, ldb, nan16, offset))
+    c_host = np.full(offset + M * ldc + 3, SENTINEL, dtype=np.float32)
+    outs = []
+    for _ in range(repeat):
+        c = _dev(c_host)
+        st = lib.gemm_bf16_ex(transA, transB, M, N, K, a.data_ptr() + 2 * offset, lda, b.data_ptr() + 2 * offset, ldb,
+                              c.data_ptr() + 4 * offset, ldc, torch.cuda.current_stream().cuda_stream)
+        lib.check(st)
+        torch.cuda.synchronize()
+        outs.append(_unpack(c.cpu().numpy(), M, N, ldc, offset))
+    for o in outs[1:]:
+        assert np.array_equal(o.view(np.uint32), outs[0].view(np.uint32)), "run-to-run results differ"
+    return outs[0]
+
+
 def _unpack(flat: np.ndarray, M: int, N: int, ldc: int, offset: int) -> np.ndarray:
     """Checks that everything outside the M x N block still holds the sentinel; returns the block."""
     assert np.all(flat[:offset] == SENTINEL), "wrote before C"

@@ -74,10 +74,17 @@ def test_dispatch_query_names_variants():
     qb = lib.fsrgemm_kernel_for_bf16
     assert qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel"
     # general kernel <T, min waves, load mode>: tile (64 T) x (64 T)
-    assert qb(8192, 8192, 8200, P, 8200, P, 8200, P, 8192) == "gemm_bf16_kernel<4, 1, 1>"   # K not a multiple of 64
-    assert qb(2048, 2048, 512, P, 512, P, 512, P, 2048) == "gemm_bf16_kernel<2, 2, 0>"
-    assert qb(100, 100, 100, P, 100, P, 100, P, 100) == "gemm_bf16_kernel<1, 4, 2>"         # ld not a multiple of 8
-    assert qb(100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1>"
+    assert qb(8192, 8192, 8200, P, 8200, P, 8200, P, 8192) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"   # K not a multiple of 64
+    assert qb(2048, 2048, 512, P, 512, P, 512, P, 2048) == "gemm_bf16_kernel<2, 2, 0, 0, 0>"
+    assert qb(100, 100, 100, P, 100, P, 100, P, 100) == "gemm_bf16_kernel<1, 4, 2, 0, 0>"         # ld not a multiple of 8
+    assert qb(100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1, 0, 0>"
+    # other storage orders: <.., A layout, B layout> with 0 = contiguous along k, 1 = along m / n; never the main kernel
+    qx = lib.fsrgemm_kernel_for_bf16_ex
+    assert qx(0, 1, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel"
+    assert qx(0, 0, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_kernel<4, 1, 0, 0, 1>"
+    assert qx(1, 1, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_kernel<4, 1, 0, 1, 0>"
+    assert qx(1, 0, 100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1, 1, 1>"
+    assert qx(1, 0, 100, 90, 80, P, 99, P, 90, P, 90) is None                                 # lda < M for a transposed A
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
@@ -114,4 +121,8 @@ def test_build_refuses_spills_in_hand_scheduled_kernels():
             build.check_no_spills("x.hip", ok.replace(field, field[:-1] + "4"))
     with pytest.raises(RuntimeError):
         build.check_no_spills("x.hip", "")
+    # the other kernels only have to stay out of scratch memory
+    assert "no scratch" in build.check_no_spills("x.hip", ok.replace("VGPRs Spill: 0", "VGPRs Spill: 9"), scratch_only=True)
+    with pytest.raises(RuntimeError):
+        build.check_no_spills("x.hip", ok.replace("ScratchSize [bytes/lane]: 0", "ScratchSize [bytes/lane]: 64"), scratch_only=True)
     assert "gemm_bf16_main.hip" in build.NO_SPILL_SOURCES

@@ -13,7 +13,7 @@ import pytest
 import oracle
 from paper_2506_09092_amd import inputs
 
-from paper_2506_09092_amd.harness import run_bf16, run_f32, run_f32_ex
+from paper_2506_09092_amd.harness import run_bf16, run_bf16_ex, run_f32, run_f32_ex
 
 pytestmark = pytest.mark.gpu
 TOL_F32 = 1e-5
@@ -135,6 +135,37 @@ def test_bf16_shapes(gpu, shape):
     check_bf16(gpu, A, Bt, lda=K + pad, ldb=K + pad, ldc=N + 5, offset=1 if pad == 3 else 0)
 
 
+BF16_STORAGE = [(0, 0), (1, 0), (1, 1)]      # (transA, transB); (0, 1) is what gemm_bf16 takes
+
+
+@pytest.mark.parametrize("ta,tb", BF16_STORAGE)
+@pytest.mark.parametrize("shape", [(1, 1, 1), (17, 17, 17), (130, 70, 200), (257, 255, 129), (33, 65, 31),
+                                   (512, 384, 1000), (300, 520, 64),
+                                   (2048, 2048, 192), (2000, 2100, 100),             # 128 x 128 tiles
+                                   (4096, 2048, 128), (4100, 2052, 72)])             # 256 x 256 tiles
+def test_bf16_storage_orders(gpu, shape, ta, tb):
+    M, N, K = shape
+    say("bf16 storage %d%d %dx%dx%d" % (ta, tb, M, N, K))
+    A = inputs.bf16_normal_scaled(4, 40, M, K, 1 / math.sqrt(K))
+    B = inputs.bf16_normal_scaled(4, 41, K, N, 1 / math.sqrt(K))
+    ref, S = oracle.gemm(A, B)
+    got = run_bf16_ex(gpu, ta, tb, A, B, repeat=2)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+    pad = 8 if (M + N) % 2 == 0 else 3                     # aligned and unaligned leading dimensions
+    lda, ldb = (M if ta else K) + pad, (K if tb else N) + pad
+    got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 5, offset=1 if pad == 3 else 0)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+
+
+@pytest.mark.parametrize("ta,tb", BF16_STORAGE + [(0, 1)])
+def test_bf16_storage_orders_integers_bit_exact(gpu, ta, tb):
+    A, B = inputs.bf16_small_ints(4, 42, 384, 512), inputs.bf16_small_ints(4, 43, 512, 320)
+    ref, _ = oracle.gemm(A, B)
+    assert np.array_equal(run_bf16_ex(gpu, ta, tb, A, B).astype(np.float64), ref)
+    if (ta, tb) == (0, 1):          # the plain entry point is this storage pair
+        assert np.array_equal(run_bf16(gpu, A, np.ascontiguousarray(B.T)).astype(np.float64), ref)
+
+
 def test_bf16_512_integers_bit_exact(gpu):
     say("bf16 512^3 integers")
     A, Bt = inputs.bf16_small_ints(4, 30, 512, 512), inputs.bf16_small_ints(4, 31, 512, 512)
@@ -149,7 +180,7 @@ def test_bf16_big_tile_config_ragged(gpu):
     say("bf16 %dx%dx%d (256-tile, ragged)" % (M, N, K))
     A = inputs.bf16_normal_scaled(4, 40, M, K, 1 / math.sqrt(K))
     Bt = inputs.bf16_normal_scaled(4, 41, N, K, 1 / math.sqrt(K))
-    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_kernel<4, 1, 1>"
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"
     check_bf16(gpu, A, Bt)
 
 
