@@ -176,6 +176,33 @@ def transposed_storage_4096(lib, torch, launches=7):
     return out
 
 
+def storage_orders_bf16_8192(lib, torch, launches=7):
+    """bf16 8192^3 in the four storage pairs of gemm_bf16_ex: (0, 1) is the headline kernel's pair, the others
+    take the general kernel.  Median launch time on random operands; parity of these paths is a GPU test."""
+    import math
+
+    n = 8192
+    a = (torch.randn(n, n, device="cuda") / math.sqrt(n)).to(torch.bfloat16)
+    b = (torch.randn(n, n, device="cuda") / math.sqrt(n)).to(torch.bfloat16)
+    c = torch.empty(n, n, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    out = []
+    for ta, tb in ((0, 1), (0, 0), (1, 1), (1, 0)):
+        for _ in range(2):
+            lib.check(lib.gemm_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream))
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
+        for e0, e1 in evs:
+            e0.record()
+            lib.check(lib.gemm_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream))
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sorted(x.elapsed_time(y) for x, y in evs)[launches // 2]
+        out.append({"transA": ta, "transB": tb, "kernel": lib.fsrgemm_kernel_for_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n),
+                    "ms": ms, "tflops": 2.0 * n ** 3 / (ms * 1e-3) / 1e12})
+    return out
+
+
 def cpu_baseline(w):
     """The oracle as it stands, timed on the host cores over a slab of rows of the same workload."""
     import oracle
@@ -238,6 +265,7 @@ def main():
 
     task2 = paper_task2_sizes(lib, torch)
     layouts = transposed_storage_4096(lib, torch)
+    layouts_bf16 = storage_orders_bf16_8192(lib, torch)
     torch.cuda.empty_cache()
 
     if args.copy_calibration:
@@ -262,6 +290,7 @@ def main():
         "sweep": sweep,
         "paper_task2_shapes": task2,
         "transposed_storage_f32_4096": layouts,
+        "storage_orders_bf16_8192": layouts_bf16,
         "paper_context": "paper reports only speedups over hand-written CUDA for the group holding Task 2: 5.95-68.3x (RTX 3090 Ti), 6.06-60.0x (GTX 1660 SUPER)",
     }
     print(json.dumps(out), flush=True)
