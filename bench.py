@@ -176,7 +176,7 @@ def transposed_storage_4096(lib, torch, launches=7):
     return out
 
 
-def storage_orders_bf16_8192(lib, torch, launches=7):
+def storage_orders_bf16_8192(lib, torch, launches=15):
     """bf16 8192^3 in the four storage pairs of gemm_bf16_ex: (0, 1) is the headline kernel's pair, the others
     take the general kernel.  Median launch time on random operands; parity of these paths is a GPU test."""
     import math
@@ -188,7 +188,7 @@ def storage_orders_bf16_8192(lib, torch, launches=7):
     stream = torch.cuda.current_stream().cuda_stream
     out = []
     for ta, tb in ((0, 1), (0, 0), (1, 1), (1, 0)):
-        for _ in range(2):
+        for _ in range(8):
             lib.check(lib.gemm_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream))
         torch.cuda.synchronize()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
@@ -200,6 +200,40 @@ def storage_orders_bf16_8192(lib, torch, launches=7):
         ms = sorted(x.elapsed_time(y) for x, y in evs)[launches // 2]
         out.append({"transA": ta, "transB": tb, "kernel": lib.fsrgemm_kernel_for_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n),
                     "ms": ms, "tflops": 2.0 * n ** 3 / (ms * 1e-3) / 1e12})
+    return out
+
+
+def split_k_f32(lib, torch, launches=9):
+    """fp32 shapes with few output tiles and a long K (row or column vector times matrix, small squares of long dot
+    products): gemm_f32 against gemm_f32_ws with the workspace the library asks for.  These are HBM-bound:
+    bytes = the operands and the result once, against the 8 TB/s peak."""
+    stream = torch.cuda.current_stream().cuda_stream
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
+    out = []
+
+    def median_ms(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
+        for e0, e1 in evs:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        return sorted(x.elapsed_time(y) for x, y in evs)[launches // 2]
+
+    for M, N, K in ((1, 4096, 4096), (4096, 1, 4096), (1, 16384, 16384), (8, 8192, 8192), (64, 64, 4097), (256, 256, 65536),
+                    (512, 512, 16384)):
+        a, b, c = torch.randn(M, K, device="cuda"), torch.randn(K, N, device="cuda"), torch.empty(M, N, device="cuda")
+        need = lib.gemm_f32_workspace_bytes(0, 0, M, N, K)
+        plain = median_ms(lambda: lib.check(lib.gemm_f32(M, N, K, a, K, b, N, c, N, stream)))
+        split = median_ms(lambda: lib.check(lib.gemm_f32_ws(0, 0, M, N, K, a, K, b, N, c, N, ws, need, stream)))
+        byts = 4.0 * (M * K + K * N + M * N)
+        out.append({"M": M, "N": N, "K": K, "slices": need // (4 * M * N), "workspace_bytes": need, "plain_ms": plain,
+                    "ms": split, "tflops": 2.0 * M * N * K / (split * 1e-3) / 1e12,
+                    "hbm_GBps_algorithmic": byts / (split * 1e-3) / 1e9, "hbm_frac_of_8TBps": byts / (split * 1e-3) / 8e12})
+        del a, b, c
     return out
 
 
@@ -266,6 +300,7 @@ def main():
     task2 = paper_task2_sizes(lib, torch)
     layouts = transposed_storage_4096(lib, torch)
     layouts_bf16 = storage_orders_bf16_8192(lib, torch)
+    skinny = split_k_f32(lib, torch)
     torch.cuda.empty_cache()
 
     if args.copy_calibration:
@@ -291,6 +326,7 @@ def main():
         "paper_task2_shapes": task2,
         "transposed_storage_f32_4096": layouts,
         "storage_orders_bf16_8192": layouts_bf16,
+        "split_k_f32": skinny,
         "paper_context": "paper reports only speedups over hand-written CUDA for the group holding Task 2: 5.95-68.3x (RTX 3090 Ti), 6.06-60.0x (GTX 1660 SUPER)",
     }
     print(json.dumps(out), flush=True)

@@ -11,7 +11,7 @@
  *
  * Conventions shared by every entry point
  *   - All matrix pointers are DEVICE pointers, valid on the current HIP
- *     device.  The library allocates nothing and keeps no workspace.
+ *     device.  The library allocates nothing and keeps no workspace (gemm_f32_ws takes one from the caller).
  *   - M, N, K and the leading dimensions are counted in ELEMENTS.
  *   - Pointers need only the natural alignment of their element type;
  *     faster kernels are picked automatically when base addresses and
@@ -79,6 +79,30 @@ int gemm_f32_ex(int transA, int transB,
                 const float *A, int64_t lda,
                 const float *B, int64_t ldb,
                 float *C, int64_t ldc,
+                void *stream);
+
+/*
+ * fp32 product with a caller-provided device workspace.  The paper's validator runs a kernel on inputs of
+ * several sizes (Section 3.2, appendix table of test sizes); for the sizes with few output elements and a long
+ * K -- a row or column vector times a matrix, a small square of long dot products -- too few output tiles
+ * exist to occupy the device.  With a workspace such problems are cut along K: every slice's partial product
+ * goes to the workspace and a second kernel adds the slices in slice order, so the result is still the same
+ * on every call (it may differ in the last bits from gemm_f32_ex, which sums along K in one piece).
+ *   gemm_f32_workspace_bytes: bytes that make the split possible for this shape, 0 when the problem is not
+ *     split (the answer depends on M, N, K only; at most 16 MiB).
+ *   gemm_f32_ws: as gemm_f32_ex; `workspace` is device memory of `workspace_bytes` bytes, 4-byte aligned, not
+ *     overlapping A, B or C, owned by the caller and free for reuse once the stream has passed the call.
+ *     Its contents on entry are ignored, on exit unspecified.  With a NULL, misaligned or too small workspace
+ *     the call does exactly what gemm_f32_ex does.  Calls that share one workspace must be ordered by the
+ *     caller (same stream, or events).
+ */
+int64_t gemm_f32_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K);
+int gemm_f32_ws(int transA, int transB,
+                int64_t M, int64_t N, int64_t K,
+                const float *A, int64_t lda,
+                const float *B, int64_t ldb,
+                float *C, int64_t ldc,
+                void *workspace, int64_t workspace_bytes,
                 void *stream);
 
 /*

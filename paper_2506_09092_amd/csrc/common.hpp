@@ -50,6 +50,10 @@ struct GemmArgs {
     int64_t ldb;
     float *C;
     int64_t ldc;
+    // split-K (fp32 kernels): number of K slices (1 = none) and the distance in floats between the partial
+    // products of consecutive slices behind C
+    int k_slices;
+    int64_t slice_stride;
 };
 
 // How global loads are issued.
@@ -68,6 +72,10 @@ enum F32Config { kF32_256x128 = 0, kF32_128x128 = 1, kF32_64x64 = 2, kF32ConfigC
 // Names are substrings of the kernel symbols as a profiler trace prints them.
 const char *f32_kernel_name(int cfg, int mode, int a_lay, int b_lay);
 hipError_t launch_f32(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
+// second half of a split-K product: C = sum over slices, in slice order
+const char *splitk_reduce_kernel_name();
+hipError_t launch_splitk_reduce(const float *ws, int slices, int64_t slice_stride, float *C, int M, int N, int64_t ldc,
+                                hipStream_t s);
 
 // bf16 configurations: the direct-to-LDS 256x256 kernel for aligned, tile-multiple problems with both
 // operands contiguous along k (gemm_bf16_main.hip) and three tile sizes of the general kernel

@@ -137,18 +137,26 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
 
     const float *__restrict__ A = static_cast<const float *>(g.A);
     const float *__restrict__ B = static_cast<const float *>(g.B);
-    float *__restrict__ C = g.C;
     const int M = g.M, N = g.N, K = g.K;
+    // Split-K: workgroup ids beyond the first tiles_m * tiles_n belong to further K slices.  Slice s takes
+    // K-tiles [s * per, (s + 1) * per) of the whole range and writes its partial product to the s-th M x N
+    // block behind g.C (a workspace then, tightly packed: the launcher sets ldc = N).
+    const int tiles = tiles_m * tiles_n;
+    const int slice = g.k_slices > 1 ? (int)blockIdx.x / tiles : 0;
+    const int nk_all = (K + kBK - 1) / kBK;
+    const int per = (nk_all + g.k_slices - 1) / g.k_slices;
+    const int t0 = slice * per;                                     // first K-tile of this slice
+    const int nk = max(0, min(per, nk_all - t0));
+    float *__restrict__ C = g.C + (int64_t)slice * g.slice_stride;
     int tile_m, tile_n;
-    tile_coords(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    tile_coords((int)blockIdx.x - slice * tiles, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave >> 1) * 32 * TM, wn0 = (wave & 1) * 32 * TN;
     const int li = lane & 31, lh = lane >> 5;
-    const int nk = (K + kBK - 1) / kBK;
 
-    if (nk == 0) {      // K == 0: every entry is an empty sum
+    if (nk == 0) {      // K == 0 (or a slice past the end of K): every entry is an empty sum
         for (int e = tid; e < BM * BN; e += kThreads) {
             const int row = m0 + e / BN, col = n0 + e % BN;
             if (row < M && col < N) C[(int64_t)row * g.ldc + col] = 0.f;
@@ -158,11 +166,12 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
 
     // A workgroup whose tile lies inside the matrix needs no check on whole K-tiles even when the problem as a
     // whole is ragged: `unchecked` counts the leading K-tiles it may load like the unchecked mode does.
-    const int unchecked = MODE == kFast ? nk : (MODE == kVecPred && m0 + BM <= M && n0 + BN <= N) ? K / kBK : 0;
+    const int unchecked = MODE == kFast ? nk
+                          : (MODE == kVecPred && m0 + BM <= M && n0 + BN <= N) ? max(0, min(nk, K / kBK - t0)) : 0;
     f32x4 rg[NG];
     auto gload = [&](auto load_mode, int idx, int t) {      // K-tiles past the end are clamped: loaded again, never consumed
         constexpr int LM = decltype(load_mode)::value;
-        const int k0 = (t < nk ? t : nk - 1) * kBK;
+        const int k0 = (t0 + (t < nk ? t : nk - 1)) * kBK;
         if (idx < NA) rg[idx] = OpA::template gload<LM>(A, g.lda, m0, M, k0, K, tid, idx);
         else rg[idx] = OpB::template gload<LM>(B, g.ldb, n0, N, k0, K, tid, idx - NA);
     };
@@ -274,7 +283,7 @@ hipError_t launch_lay(int mode, const GemmArgs &a, hipStream_t s)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(kThreads);
+    const dim3 grid((unsigned)(tiles_m * tiles_n * a.k_slices)), block(kThreads);
     switch (mode) {
     case kFast: hipLaunchKernelGGL((gemm_f32_kernel<TM, TN, MIN_WAVES, kFast, ALAY, BLAY>), grid, block, 0, s, a, tiles_m, tiles_n); break;
     case kVecPred: hipLaunchKernelGGL((gemm_f32_kernel<TM, TN, MIN_WAVES, kVecPred, ALAY, BLAY>), grid, block, 0, s, a, tiles_m, tiles_n); break;
@@ -295,6 +304,33 @@ hipError_t launch_cfg(int mode, int a_lay, int b_lay, const GemmArgs &a, hipStre
 }
 
 }  // namespace
+
+namespace {
+
+// C[i][j] = ws[0][i][j] + ws[1][i][j] + ... in that order: the second half of a split-K product.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ ws, int slices, int64_t slice_stride,
+                                                            float *__restrict__ C, int M, int N, int64_t ldc)
+{
+    const int64_t total = (int64_t)M * N;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        float sum = ws[e];
+        for (int s = 1; s < slices; ++s) sum += ws[(int64_t)s * slice_stride + e];
+        C[(e / N) * ldc + e % N] = sum;
+    }
+}
+
+}  // namespace
+
+const char *splitk_reduce_kernel_name() { return "splitk_reduce_kernel"; }
+
+hipError_t launch_splitk_reduce(const float *ws, int slices, int64_t slice_stride, float *C, int M, int N, int64_t ldc,
+                                hipStream_t s)
+{
+    const int64_t total = (int64_t)M * N;
+    const unsigned blocks = (unsigned)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, s, ws, slices, slice_stride, C, M, N, ldc);
+    return hipGetLastError();
+}
 
 // <TM, TN, minimum wavefronts per SIMD, load mode, A layout, B layout>, as a profiler trace prints the kernel
 const char *f32_kernel_name(int cfg, int mode, int a_lay, int b_lay)

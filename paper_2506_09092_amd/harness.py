@@ -63,6 +63,37 @@ def run_f32_ex(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, ld
     return outs[0]
 
 
+def run_f32_ws(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, workspace_bytes=None, lda=None, ldb=None,
+               ldc=None, offset=0, repeat=1):
+    """C = A.B through gemm_f32_ws with a canaried workspace of `workspace_bytes` (default: what the library asks
+    for).  Returns the M x N result; checks that nothing behind the stated workspace size was written."""
+    M, K = A.shape
+    N = B.shape[1]
+    sa = np.ascontiguousarray(A.T) if transA else A
+    sb = np.ascontiguousarray(B.T) if transB else B
+    lda, ldb, ldc = lda or max(sa.shape[1], 1), ldb or max(sb.shape[1], 1), ldc or max(N, 1)
+    a = _dev(inputs.embed(sa, lda, np.float32(np.nan), offset))
+    b = _dev(inputs.embed(sb, ldb, np.float32(np.nan), offset))
+    if workspace_bytes is None:
+        workspace_bytes = lib.gemm_f32_workspace_bytes(transA, transB, M, N, K)
+    guard = 64
+    ws_host = np.full(workspace_bytes // 4 + guard, SENTINEL, dtype=np.float32)
+    c_host = np.full(offset + M * ldc + 3, SENTINEL, dtype=np.float32)
+    outs = []
+    for _ in range(repeat):
+        c, ws = _dev(c_host), _dev(ws_host)
+        st = lib.gemm_f32_ws(transA, transB, M, N, K, a.data_ptr() + 4 * offset, lda, b.data_ptr() + 4 * offset, ldb,
+                             c.data_ptr() + 4 * offset, ldc, ws.data_ptr() if workspace_bytes else None, workspace_bytes,
+                             torch.cuda.current_stream().cuda_stream)
+        lib.check(st)
+        torch.cuda.synchronize()
+        assert np.all(ws.cpu().numpy()[workspace_bytes // 4:] == SENTINEL), "wrote past the workspace"
+        outs.append(_unpack(c.cpu().numpy(), M, N, ldc, offset))
+    for o in outs[1:]:
+        assert np.array_equal(o.view(np.uint32), outs[0].view(np.uint32)), "run-to-run results differ"
+    return outs[0]
+
+
 def run_bf16(lib, A: np.ndarray, Bt: np.ndarray, lda=None, ldb=None, ldc=None, offset=0, repeat=1):
     """C = A.B through gemm_bf16; A is (M, K) bf16 bits, Bt is (N, K) bf16 bits (column-major B)."""
     M, K = A.shape

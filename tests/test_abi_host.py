@@ -106,6 +106,22 @@ def test_transposed_storage_arguments(ta, tb):
     assert lib.fsrgemm_kernel_for_f32(4096, 4096, 4096, P, 4096, P, 4096, P, 4096) == q(0, 0, 4096, 4096, 4096, P, 4096, P, 4096, P, 4096)
 
 
+def test_workspace_query_and_argument_checks():
+    wb = lib.gemm_f32_workspace_bytes
+    assert wb(0, 0, 1, 4096, 4096) == 16 * 1 * 4096 * 4             # 64 tiles, 256 K-tiles -> 16 slices of 16 K-tiles
+    assert wb(0, 0, 1, 16384, 16384) == 4 * 16384 * 4               # 256 tiles -> 4 slices
+    assert wb(0, 0, 1024, 1024, 1024) == 0                           # 256 tiles, but only 64 K-tiles
+    assert wb(0, 0, 256, 256, 65536) == 64 * 256 * 256 * 4           # 16 tiles -> the cap of 64 slices: 16 MiB
+    assert wb(1, 1, 256, 256, 65536) == wb(0, 0, 256, 256, 65536)
+    assert wb(0, 0, 64, 64, 256) == 0                                 # K too short to cut
+    assert wb(0, 0, 4096, 4096, 4096) == 0 and wb(0, 0, 0, 5, 4096) == 0 and wb(0, 0, -1, 5, 4096) == 0
+    bad = lib.FSRGEMM_ERR_INVALID_ARG
+    assert lib.gemm_f32_ws(0, 0, 1, 8, 4096, P, 4096, P, 8, P, 8, None, 64, 0) == bad      # bytes without a pointer
+    assert lib.gemm_f32_ws(0, 0, 1, 8, 4096, P, 4096, P, 8, P, 8, P, -1, 0) == bad
+    assert lib.gemm_f32_ws(0, 0, 1, 8, 4096, P, 4095, P, 8, P, 8, P, 1 << 20, 0) == bad    # lda < K
+    assert lib.gemm_f32_ws(0, 0, 0, 8, 4096, None, 4096, P, 8, None, 8, None, 0, 0) == lib.FSRGEMM_OK
+
+
 def test_build_refuses_spills_in_hand_scheduled_kernels():
     # the build parses the compiler's resource-usage remarks for the kernels that issue loads from
     # inline assembly; any spill (or missing remarks) must stop it

@@ -13,7 +13,7 @@ import pytest
 import oracle
 from paper_2506_09092_amd import inputs
 
-from paper_2506_09092_amd.harness import run_bf16, run_bf16_ex, run_f32, run_f32_ex
+from paper_2506_09092_amd.harness import run_bf16, run_bf16_ex, run_f32, run_f32_ex, run_f32_ws
 
 pytestmark = pytest.mark.gpu
 TOL_F32 = 1e-5
@@ -133,6 +133,43 @@ def test_bf16_shapes(gpu, shape):
     check_bf16(gpu, A, Bt, repeat=2)
     pad = 8 if (M + N) % 2 == 0 else 3                     # aligned and unaligned leading dimensions
     check_bf16(gpu, A, Bt, lda=K + pad, ldb=K + pad, ldc=N + 5, offset=1 if pad == 3 else 0)
+
+
+SKINNY = [(1, 4096, 4096), (4096, 1, 4096), (1, 1, 4096), (64, 64, 4097), (16, 1000, 3000), (257, 100, 2049),
+          (3, 700, 1031), (300, 5, 8192), (128, 128, 16384), (512, 512, 1024)]
+
+
+@pytest.mark.parametrize("shape", SKINNY)
+def test_f32_workspace_split_k(gpu, shape):
+    # few output tiles, long K: with the workspace the product is cut along K and summed in slice order
+    M, N, K = shape
+    need = gpu.gemm_f32_workspace_bytes(0, 0, M, N, K)
+    say("split-K %dx%dx%d workspace %d bytes" % (M, N, K, need))
+    assert need > 0 and need % (4 * M * N) == 0 and need <= 16 << 20
+    A, B = inputs.uniform_pm1(7, 1, M, K), inputs.uniform_pm1(7, 2, K, N)
+    ref, S = oracle.gemm(A, B)
+    for ta, tb in ((0, 0), (0, 1), (1, 0), (1, 1)):
+        assert gpu.gemm_f32_workspace_bytes(ta, tb, M, N, K) == need
+        got = run_f32_ws(gpu, ta, tb, A, B, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+    pad = 3 if (M + N) % 2 else 4
+    got = run_f32_ws(gpu, 0, 0, A, B, lda=K + pad, ldb=N + pad, ldc=N + 1, offset=1 if pad == 3 else 0, repeat=2)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+    # a workspace one float short, or none, must leave the call equal to gemm_f32_ex bit for bit
+    plain = run_f32_ex(gpu, 0, 0, A, B)
+    assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=need - 4).view(np.uint32), plain.view(np.uint32))
+    assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=0).view(np.uint32), plain.view(np.uint32))
+
+
+def test_f32_workspace_integers_bit_exact_and_large_problem_unsplit(gpu):
+    A, B = inputs.small_ints(0, 5, 48, 4000), inputs.small_ints(0, 6, 4000, 200)
+    assert gpu.gemm_f32_workspace_bytes(0, 0, 48, 200, 4000) > 0
+    ref, _ = oracle.gemm(A, B)
+    assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B).astype(np.float64), ref)
+    # enough tiles already: no workspace wanted, and one that is offered is not touched
+    assert gpu.gemm_f32_workspace_bytes(0, 0, 2048, 2048, 4096) == 0
+    A, B = inputs.uniform_pm1(7, 3, 1024, 256), inputs.uniform_pm1(7, 4, 256, 1024)
+    assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=4096).view(np.uint32), run_f32(gpu, A, B).view(np.uint32))
 
 
 BF16_STORAGE = [(0, 0), (1, 0), (1, 1)]      # (transA, transB); (0, 1) is what gemm_bf16 takes
