@@ -203,10 +203,13 @@ def storage_orders_bf16_8192(lib, torch, launches=15):
     return out
 
 
-def split_k_f32(lib, torch, launches=9):
-    """fp32 shapes with few output tiles and a long K (row or column vector times matrix, small squares of long dot
-    products): gemm_f32 against gemm_f32_ws with the workspace the library asks for.  These are HBM-bound:
-    bytes = the operands and the result once, against the 8 TB/s peak."""
+def split_k(lib, torch, kind, launches=9):
+    """Shapes with few output tiles and a long K (row or column vector times matrix, a few rows against a large
+    weight matrix, small squares of long dot products): the plain entry point against the workspace one with the
+    workspace the library asks for.  These are HBM-bound: bytes = the operands and the result once, against the
+    8 TB/s peak.  kind: "f32" (row-major operands) or "bf16" (A row-major, B column-major)."""
+    import math
+
     stream = torch.cuda.current_stream().cuda_stream
     ws = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
     out = []
@@ -223,13 +226,24 @@ def split_k_f32(lib, torch, launches=9):
         torch.cuda.synchronize()
         return sorted(x.elapsed_time(y) for x, y in evs)[launches // 2]
 
-    for M, N, K in ((1, 4096, 4096), (4096, 1, 4096), (1, 16384, 16384), (8, 8192, 8192), (64, 64, 4097), (256, 256, 65536),
-                    (512, 512, 16384)):
-        a, b, c = torch.randn(M, K, device="cuda"), torch.randn(K, N, device="cuda"), torch.empty(M, N, device="cuda")
-        need = lib.gemm_f32_workspace_bytes(0, 0, M, N, K)
-        plain = median_ms(lambda: lib.check(lib.gemm_f32(M, N, K, a, K, b, N, c, N, stream)))
-        split = median_ms(lambda: lib.check(lib.gemm_f32_ws(0, 0, M, N, K, a, K, b, N, c, N, ws, need, stream)))
-        byts = 4.0 * (M * K + K * N + M * N)
+    shapes = (((1, 4096, 4096), (4096, 1, 4096), (1, 16384, 16384), (8, 8192, 8192), (64, 64, 4097), (256, 256, 65536),
+               (512, 512, 16384)) if kind == "f32" else
+              ((1, 8192, 8192), (16, 8192, 8192), (32, 28672, 8192), (256, 256, 65536), (512, 512, 16384)))
+    for M, N, K in shapes:
+        c = torch.empty(M, N, device="cuda")
+        if kind == "f32":
+            a, b = torch.randn(M, K, device="cuda"), torch.randn(K, N, device="cuda")
+            need = lib.gemm_f32_workspace_bytes(0, 0, M, N, K)
+            plain = median_ms(lambda: lib.check(lib.gemm_f32(M, N, K, a, K, b, N, c, N, stream)))
+            split = median_ms(lambda: lib.check(lib.gemm_f32_ws(0, 0, M, N, K, a, K, b, N, c, N, ws, need, stream)))
+            byts = 4.0 * (M * K + K * N + M * N)
+        else:
+            a = (torch.randn(M, K, device="cuda") / math.sqrt(K)).to(torch.bfloat16)
+            b = (torch.randn(N, K, device="cuda") / math.sqrt(K)).to(torch.bfloat16)
+            need = lib.gemm_bf16_workspace_bytes(0, 1, M, N, K)
+            plain = median_ms(lambda: lib.check(lib.gemm_bf16(M, N, K, a, K, b, K, c, N, stream)))
+            split = median_ms(lambda: lib.check(lib.gemm_bf16_ws(0, 1, M, N, K, a, K, b, K, c, N, ws, need, stream)))
+            byts = 2.0 * (M * K + K * N) + 4.0 * M * N
         out.append({"M": M, "N": N, "K": K, "slices": need // (4 * M * N), "workspace_bytes": need, "plain_ms": plain,
                     "ms": split, "tflops": 2.0 * M * N * K / (split * 1e-3) / 1e12,
                     "hbm_GBps_algorithmic": byts / (split * 1e-3) / 1e9, "hbm_frac_of_8TBps": byts / (split * 1e-3) / 8e12})
@@ -300,7 +314,8 @@ def main():
     task2 = paper_task2_sizes(lib, torch)
     layouts = transposed_storage_4096(lib, torch)
     layouts_bf16 = storage_orders_bf16_8192(lib, torch)
-    skinny = split_k_f32(lib, torch)
+    skinny = split_k(lib, torch, "f32")
+    skinny_bf16 = split_k(lib, torch, "bf16")
     torch.cuda.empty_cache()
 
     if args.copy_calibration:
@@ -327,6 +342,7 @@ def main():
         "transposed_storage_f32_4096": layouts,
         "storage_orders_bf16_8192": layouts_bf16,
         "split_k_f32": skinny,
+        "split_k_bf16": skinny_bf16,
         "paper_context": "paper reports only speedups over hand-written CUDA for the group holding Task 2: 5.95-68.3x (RTX 3090 Ti), 6.06-60.0x (GTX 1660 SUPER)",
     }
     print(json.dumps(out), flush=True)

@@ -134,6 +134,19 @@ int gemm_bf16_ex(int transA, int transB,
                  void *stream);
 
 /*
+ * The bf16 product with a caller-provided workspace: gemm_bf16_ex's arguments, gemm_f32_ws's workspace rules
+ * (partial products are fp32; the split depends on M, N, K only; at most 16 MiB).
+ */
+int64_t gemm_bf16_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K);
+int gemm_bf16_ws(int transA, int transB,
+                 int64_t M, int64_t N, int64_t K,
+                 const uint16_t *A, int64_t lda,
+                 const uint16_t *B, int64_t ldb,
+                 float *C, int64_t ldc,
+                 void *workspace, int64_t workspace_bytes,
+                 void *stream);
+
+/*
  * Name of the kernel variant the dispatcher would launch for this problem
  * (same argument checks as the gemm calls; launches nothing, touches no
  * device memory).  Returns a pointer to static storage, or NULL when the

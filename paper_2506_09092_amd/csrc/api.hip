@@ -100,17 +100,17 @@ GemmArgs pack(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const
     return a;
 }
 
-// Split-K plan for fp32: problems with few 64 x 64 output tiles and a long K are cut into K slices so that about
-// 1024 workgroups stream the operands.  A slice keeps at least 16 K-tiles (256 k) when the tiles alone leave
-// half the compute units idle, 64 K-tiles when they would fill them once or twice; the partial products stay
-// within 16 MiB.  Depends on the shape only, so the order of summation, and with it the result, is the same on
-// every call.  1 = do not split.
-int splitk_slices(int64_t M, int64_t N, int64_t K)
+// Split-K plan: problems with few 64 x 64 output tiles and a long K are cut into K slices so that about 1024
+// workgroups stream the operands.  A slice keeps at least 256 k when the tiles alone leave half the compute
+// units idle, 1024 k when they would fill them once or twice; at most 64 slices, partial products within
+// 16 MiB.  Depends on the shape only, so the order of summation, and with it the result, is the same on every
+// call.  k_tile = 16 for fp32, 64 for bf16.  1 = do not split.
+int splitk_slices(int64_t M, int64_t N, int64_t K, int k_tile)
 {
-    const int64_t tiles = ceil_div(M, 64) * ceil_div(N, 64), nk = ceil_div(K, 16);
+    const int64_t tiles = ceil_div(M, 64) * ceil_div(N, 64), nk = ceil_div(K, k_tile);
     if (M == 0 || N == 0 || tiles > 512) return 1;
     int64_t s = 1024 / tiles;
-    const int64_t longest = nk / (tiles <= 128 ? 16 : 64);
+    const int64_t longest = nk / ((tiles <= 128 ? 256 : 1024) / k_tile);
     if (s > longest) s = longest;
     if (s > 64) s = 64;
     const int64_t cap = ((int64_t)16 << 20) / (M * N * 4);
@@ -189,7 +189,7 @@ int64_t gemm_f32_workspace_bytes(int transA, int transB, int64_t M, int64_t N, i
     (void)transA;
     (void)transB;
     if (M < 0 || N < 0 || K < 0 || M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31)) return 0;
-    const int slices = splitk_slices(M, N, K);
+    const int slices = splitk_slices(M, N, K, 16);
     return slices > 1 ? (int64_t)slices * M * N * 4 : 0;
 }
 
@@ -199,7 +199,7 @@ int gemm_f32_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const f
     int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
     if (rc != FSRGEMM_OK) return rc;
     if (workspace_bytes < 0 || (workspace_bytes > 0 && workspace == nullptr)) return FSRGEMM_ERR_INVALID_ARG;
-    const int slices = splitk_slices(M, N, K);
+    const int slices = splitk_slices(M, N, K, 16);
     const int64_t need = (int64_t)slices * M * N * 4;
     if (slices < 2 || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 3u))
         return gemm_f32_ex(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, stream);
@@ -214,6 +214,43 @@ int gemm_f32_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const f
     a.slice_stride = M * N;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = launch_f32(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, a, s);
+    if (e == hipSuccess) e = launch_splitk_reduce(ws, slices, M * N, C, (int)M, (int)N, ldc, s);
+    return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+}
+
+int64_t gemm_bf16_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K)
+{
+    (void)transA;
+    (void)transB;
+    if (M < 0 || N < 0 || K < 0 || M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31)) return 0;
+    const int slices = splitk_slices(M, N, K, 64);
+    return slices > 1 ? (int64_t)slices * M * N * 4 : 0;
+}
+
+int gemm_bf16_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
+                 const uint16_t *B, int64_t ldb, float *C, int64_t ldc, void *workspace, int64_t workspace_bytes,
+                 void *stream)
+{
+    int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
+    if (rc != FSRGEMM_OK) return rc;
+    if (workspace_bytes < 0 || (workspace_bytes > 0 && workspace == nullptr)) return FSRGEMM_ERR_INVALID_ARG;
+    const int slices = splitk_slices(M, N, K, 64);
+    const int64_t need = (int64_t)slices * M * N * 4;
+    if (slices < 2 || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 3u))
+        return gemm_bf16_ex(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, stream);
+    const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
+    Plan p;
+    rc = plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, &p);
+    if (rc != FSRGEMM_OK) return rc;
+    if (p.cfg == kBf16_Main) return FSRGEMM_ERR_LAUNCH;      // cannot happen: a split problem has at most 512 small tiles
+    rc = device_ok();
+    if (rc != FSRGEMM_OK) return rc;
+    float *ws = static_cast<float *>(workspace);
+    GemmArgs a = pack(M, N, K, A, lda, B, ldb, ws, N);
+    a.k_slices = slices;
+    a.slice_stride = M * N;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_bf16(p.cfg, p.mode, a_lay, b_lay, a, s);
     if (e == hipSuccess) e = launch_splitk_reduce(ws, slices, M * N, C, (int)M, (int)N, ldc, s);
     return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
 }

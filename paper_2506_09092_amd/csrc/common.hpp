@@ -50,7 +50,7 @@ struct GemmArgs {
     int64_t ldb;
     float *C;
     int64_t ldc;
-    // split-K (fp32 kernels): number of K slices (1 = none) and the distance in floats between the partial
+    // split-K (fp32 kernels and the general bf16 kernel): number of K slices (1 = none) and the distance in floats between the partial
     // products of consecutive slices behind C
     int k_slices;
     int64_t slice_stride;

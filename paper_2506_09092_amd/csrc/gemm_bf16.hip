@@ -135,18 +135,26 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
 
     const uint16_t *__restrict__ A = static_cast<const uint16_t *>(g.A);
     const uint16_t *__restrict__ B = static_cast<const uint16_t *>(g.B);
-    float *__restrict__ C = g.C;
     const int M = g.M, N = g.N, K = g.K;
+    // Split-K: workgroup ids beyond the first tiles_m * tiles_n belong to further K slices.  Slice s takes
+    // K-tiles [s * per, (s + 1) * per) of the whole range and writes its partial product to the s-th M x N
+    // block behind g.C (a workspace then, tightly packed: the launcher sets ldc = N).
+    const int tiles = tiles_m * tiles_n;
+    const int slice = g.k_slices > 1 ? (int)blockIdx.x / tiles : 0;
+    const int nk_all = (K + kBK - 1) / kBK;
+    const int per = (nk_all + g.k_slices - 1) / g.k_slices;
+    const int t0 = slice * per;                                     // first K-tile of this slice
+    const int nk = max(0, min(per, nk_all - t0));
+    float *__restrict__ C = g.C + (int64_t)slice * g.slice_stride;
     int tile_m, tile_n;
-    tile_coords(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    tile_coords((int)blockIdx.x - slice * tiles, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave >> 1) * 32 * T, wn0 = (wave & 1) * 32 * T;
     const int l16 = lane & 15, lq = lane >> 4;
-    const int nk = (K + kBK - 1) / kBK;
 
-    if (nk == 0) {      // K == 0: every entry is an empty sum
+    if (nk == 0) {      // K == 0 (or a slice past the end of K): every entry is an empty sum
         for (int e = tid; e < BM * BN; e += kThreads) {
             const int row = m0 + e / BN, col = n0 + e % BN;
             if (row < M && col < N) C[(int64_t)row * g.ldc + col] = 0.f;
@@ -156,11 +164,12 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
 
     // A workgroup whose tile lies inside the matrix needs no check on whole K-tiles even when the problem as a
     // whole is ragged: `unchecked` counts the leading K-tiles it may load like the unchecked mode does.
-    const int unchecked = MODE == kFast ? nk : (MODE == kVecPred && m0 + BM <= M && n0 + BN <= N) ? K / kBK : 0;
+    const int unchecked = MODE == kFast ? nk
+                          : (MODE == kVecPred && m0 + BM <= M && n0 + BN <= N) ? max(0, min(nk, K / kBK - t0)) : 0;
     u32x4 rg[NG];       // idx < NV: A's vectors; else B's
     auto gload = [&](auto load_mode, int idx, int t) {      // K-tiles past the end are clamped: loaded again, never consumed
         constexpr int LM = decltype(load_mode)::value;
-        const int k0 = (t < nk ? t : nk - 1) * kBK;
+        const int k0 = (t0 + (t < nk ? t : nk - 1)) * kBK;
         if (idx < NV) rg[idx] = StA::template gload<LM>(A, g.lda, m0, M, k0, K, tid, idx);
         else rg[idx] = StB::template gload<LM>(B, g.ldb, n0, N, k0, K, tid, idx - NV);
     };
@@ -283,7 +292,7 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t s)
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, configured);
     if (e != hipSuccess) return e;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BM - 1) / BM;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), lds, s, a, tiles_m, tiles_n);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n * a.k_slices)), dim3(kThreads), lds, s, a, tiles_m, tiles_n);
     return hipGetLastError();
 }
 

@@ -13,7 +13,7 @@ import os
 __all__ = [
     "load", "library_path", "gemm_f32", "gemm_f32_ex", "gemm_bf16", "fsrgemm_kernel_for_f32",
     "fsrgemm_kernel_for_f32_ex", "fsrgemm_kernel_for_bf16", "gemm_bf16_ex", "fsrgemm_kernel_for_bf16_ex",
-    "gemm_f32_ws", "gemm_f32_workspace_bytes",
+    "gemm_f32_ws", "gemm_f32_workspace_bytes", "gemm_bf16_ws", "gemm_bf16_workspace_bytes",
     "fsrgemm_status_string", "fsrgemm_version", "check", "FsrGemmError", "EXPORTS",
     "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
 ]
@@ -32,6 +32,8 @@ EXPORTS = {
     "gemm_f32_ex": (ctypes.c_int, [ctypes.c_int, ctypes.c_int] + _GEMM),
     "gemm_f32_workspace_bytes": (_i64, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64]),
     "gemm_f32_ws": (ctypes.c_int, [ctypes.c_int, ctypes.c_int] + _GEMM[:-1] + [_vp, _i64, _vp]),
+    "gemm_bf16_workspace_bytes": (_i64, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64]),
+    "gemm_bf16_ws": (ctypes.c_int, [ctypes.c_int, ctypes.c_int] + _GEMM[:-1] + [_vp, _i64, _vp]),
     "gemm_bf16": (ctypes.c_int, _GEMM),
     "gemm_bf16_ex": (ctypes.c_int, [ctypes.c_int, ctypes.c_int] + _GEMM),
     "fsrgemm_kernel_for_f32": (ctypes.c_char_p, _QUERY),
@@ -99,6 +101,15 @@ def gemm_f32_workspace_bytes(transA, transB, M, N, K) -> int:
 def gemm_f32_ws(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, workspace, workspace_bytes, stream=0) -> int:
     return load().gemm_f32_ws(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
                               _ptr(workspace), int(workspace_bytes), _ptr(stream) or None)
+
+
+def gemm_bf16_workspace_bytes(transA, transB, M, N, K) -> int:
+    return int(load().gemm_bf16_workspace_bytes(int(transA), int(transB), M, N, K))
+
+
+def gemm_bf16_ws(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, workspace, workspace_bytes, stream=0) -> int:
+    return load().gemm_bf16_ws(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
+                               _ptr(workspace), int(workspace_bytes), _ptr(stream) or None)
 
 
 def gemm_bf16(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:

@@ -63,28 +63,27 @@ def run_f32_ex(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, ld
     return outs[0]
 
 
-def run_f32_ws(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, workspace_bytes=None, lda=None, ldb=None,
-               ldc=None, offset=0, repeat=1):
-    """C = A.B through gemm_f32_ws with a canaried workspace of `workspace_bytes` (default: what the library asks
-    for).  Returns the M x N result; checks that nothing behind the stated workspace size was written."""
+def _run_ws(lib, kind: str, transA, transB, A, B, workspace_bytes, lda, ldb, ldc, offset, repeat):
     M, K = A.shape
     N = B.shape[1]
     sa = np.ascontiguousarray(A.T) if transA else A
     sb = np.ascontiguousarray(B.T) if transB else B
     lda, ldb, ldc = lda or max(sa.shape[1], 1), ldb or max(sb.shape[1], 1), ldc or max(N, 1)
-    a = _dev(inputs.embed(sa, lda, np.float32(np.nan), offset))
-    b = _dev(inputs.embed(sb, ldb, np.float32(np.nan), offset))
+    esize, fill = (4, np.float32(np.nan)) if kind == "f32" else (2, np.uint16(0x7FC0))
+    gemm, query = (lib.gemm_f32_ws, lib.gemm_f32_workspace_bytes) if kind == "f32" else (lib.gemm_bf16_ws, lib.gemm_bf16_workspace_bytes)
+    a = _dev(inputs.embed(sa, lda, fill, offset))
+    b = _dev(inputs.embed(sb, ldb, fill, offset))
     if workspace_bytes is None:
-        workspace_bytes = lib.gemm_f32_workspace_bytes(transA, transB, M, N, K)
+        workspace_bytes = query(transA, transB, M, N, K)
     guard = 64
     ws_host = np.full(workspace_bytes // 4 + guard, SENTINEL, dtype=np.float32)
     c_host = np.full(offset + M * ldc + 3, SENTINEL, dtype=np.float32)
     outs = []
     for _ in range(repeat):
         c, ws = _dev(c_host), _dev(ws_host)
-        st = lib.gemm_f32_ws(transA, transB, M, N, K, a.data_ptr() + 4 * offset, lda, b.data_ptr() + 4 * offset, ldb,
-                             c.data_ptr() + 4 * offset, ldc, ws.data_ptr() if workspace_bytes else None, workspace_bytes,
-                             torch.cuda.current_stream().cuda_stream)
+        st = gemm(transA, transB, M, N, K, a.data_ptr() + esize * offset, lda, b.data_ptr() + esize * offset, ldb,
+                  c.data_ptr() + 4 * offset, ldc, ws.data_ptr() if workspace_bytes else None, workspace_bytes,
+                  torch.cuda.current_stream().cuda_stream)
         lib.check(st)
         torch.cuda.synchronize()
         assert np.all(ws.cpu().numpy()[workspace_bytes // 4:] == SENTINEL), "wrote past the workspace"
@@ -92,6 +91,20 @@ def run_f32_ws(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, wo
     for o in outs[1:]:
         assert np.array_equal(o.view(np.uint32), outs[0].view(np.uint32)), "run-to-run results differ"
     return outs[0]
+
+
+def run_f32_ws(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, workspace_bytes=None, lda=None, ldb=None,
+               ldc=None, offset=0, repeat=1):
+    """C = A.B through gemm_f32_ws with a canaried workspace of `workspace_bytes` (default: what the library asks
+    for).  A (M x K), B (K x N) are the logical operands.  Checks that nothing behind the stated workspace size
+    was written; returns the M x N result."""
+    return _run_ws(lib, "f32", transA, transB, A, B, workspace_bytes, lda, ldb, ldc, offset, repeat)
+
+
+def run_bf16_ws(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, workspace_bytes=None, lda=None, ldb=None,
+                ldc=None, offset=0, repeat=1):
+    """The same through gemm_bf16_ws; operands are bf16 bit patterns."""
+    return _run_ws(lib, "bf16", transA, transB, A, B, workspace_bytes, lda, ldb, ldc, offset, repeat)
 
 
 def run_bf16(lib, A: np.ndarray, Bt: np.ndarray, lda=None, ldb=None, ldc=None, offset=0, repeat=1):

@@ -115,7 +115,12 @@ def test_workspace_query_and_argument_checks():
     assert wb(1, 1, 256, 256, 65536) == wb(0, 0, 256, 256, 65536)
     assert wb(0, 0, 64, 64, 256) == 0                                 # K too short to cut
     assert wb(0, 0, 4096, 4096, 4096) == 0 and wb(0, 0, 0, 5, 4096) == 0 and wb(0, 0, -1, 5, 4096) == 0
+    wh = lib.gemm_bf16_workspace_bytes
+    assert wh(0, 1, 1, 4096, 4096) == 16 * 4096 * 4 and wh(0, 1, 64, 64, 256) == 0 and wh(0, 1, 8192, 8192, 8192) == 0
+    assert wh(0, 1, 1, 16384, 16384) == 4 * 16384 * 4
     bad = lib.FSRGEMM_ERR_INVALID_ARG
+    assert lib.gemm_bf16_ws(0, 1, 1, 8, 4096, P, 4096, P, 4096, P, 8, None, 64, 0) == bad
+    assert lib.gemm_bf16_ws(0, 1, 1, 8, 4096, P, 4096, P, 4095, P, 8, P, 1 << 20, 0) == bad   # ldb < K
     assert lib.gemm_f32_ws(0, 0, 1, 8, 4096, P, 4096, P, 8, P, 8, None, 64, 0) == bad      # bytes without a pointer
     assert lib.gemm_f32_ws(0, 0, 1, 8, 4096, P, 4096, P, 8, P, 8, P, -1, 0) == bad
     assert lib.gemm_f32_ws(0, 0, 1, 8, 4096, P, 4095, P, 8, P, 8, P, 1 << 20, 0) == bad    # lda < K

@@ -13,7 +13,7 @@ import pytest
 import oracle
 from paper_2506_09092_amd import inputs
 
-from paper_2506_09092_amd.harness import run_bf16, run_bf16_ex, run_f32, run_f32_ex, run_f32_ws
+from paper_2506_09092_amd.harness import run_bf16, run_bf16_ex, run_bf16_ws, run_f32, run_f32_ex, run_f32_ws
 
 pytestmark = pytest.mark.gpu
 TOL_F32 = 1e-5
@@ -170,6 +170,28 @@ def test_f32_workspace_integers_bit_exact_and_large_problem_unsplit(gpu):
     assert gpu.gemm_f32_workspace_bytes(0, 0, 2048, 2048, 4096) == 0
     A, B = inputs.uniform_pm1(7, 3, 1024, 256), inputs.uniform_pm1(7, 4, 256, 1024)
     assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=4096).view(np.uint32), run_f32(gpu, A, B).view(np.uint32))
+
+
+@pytest.mark.parametrize("shape", [(1, 4096, 4096), (4096, 1, 4096), (8, 1000, 3000), (64, 64, 4100), (130, 70, 2050),
+                                   (16, 8192, 2048), (256, 256, 8192)])
+def test_bf16_workspace_split_k(gpu, shape):
+    M, N, K = shape
+    need = gpu.gemm_bf16_workspace_bytes(0, 1, M, N, K)
+    say("bf16 split-K %dx%dx%d workspace %d bytes" % (M, N, K, need))
+    assert need > 0 and need % (4 * M * N) == 0 and need <= 16 << 20
+    A = inputs.bf16_normal_scaled(4, 50, M, K, 1 / math.sqrt(K))
+    B = inputs.bf16_normal_scaled(4, 51, K, N, 1 / math.sqrt(K))
+    ref, S = oracle.gemm(A, B)
+    for ta, tb in ((0, 1), (0, 0), (1, 0), (1, 1)):
+        got = run_bf16_ws(gpu, ta, tb, A, B, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+    got = run_bf16_ws(gpu, 0, 1, A, B, lda=K + 3, ldb=K + 3, ldc=N + 1, offset=1, repeat=2)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+    plain = run_bf16_ex(gpu, 0, 1, A, B)
+    assert np.array_equal(run_bf16_ws(gpu, 0, 1, A, B, workspace_bytes=need - 4).view(np.uint32), plain.view(np.uint32))
+    Ai, Bi = inputs.bf16_small_ints(4, 52, M, K), inputs.bf16_small_ints(4, 53, K, N)
+    refi, _ = oracle.gemm(Ai, Bi)
+    assert np.array_equal(run_bf16_ws(gpu, 0, 1, Ai, Bi).astype(np.float64), refi)
 
 
 BF16_STORAGE = [(0, 0), (1, 0), (1, 1)]      # (transA, transB); (0, 1) is what gemm_bf16 takes
