@@ -43,7 +43,9 @@ int plan_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const
     else p->cfg = kF32_64x64, bm = 64, bn = 64;
     if (ceil_div(M, bm) * ceil_div(N, bn) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
     const bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
-    p->mode = !vec ? kScalar : (M % bm == 0 && N % bn == 0 && K % 16 == 0 && K > 0) ? kFast : kVecPred;
+    // unchecked loads and stores need whole K-tiles and a matrix at least one tile wide and high (a ragged last
+    // tile is shifted back into the matrix)
+    p->mode = !vec ? kScalar : (M >= bm && N >= bn && K % 16 == 0 && K > 0) ? kFast : kVecPred;
     return FSRGEMM_OK;
 }
 
@@ -56,8 +58,8 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     else p->cfg = kBf16_64x64, b = 64;
     if (ceil_div(M, b) * ceil_div(N, b) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
     const bool vec = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0;
-    p->mode = !vec ? kScalar : (M % b == 0 && N % b == 0 && K % 64 == 0 && K > 0) ? kFast : kVecPred;
-    // the direct-to-LDS kernel needs both operands contiguous along k, whole 256 x 256 x 64 tiles and 32-bit lane offsets
+    p->mode = !vec ? kScalar : (M >= b && N >= b && K % 64 == 0 && K > 0) ? kFast : kVecPred;
+    // the direct-to-LDS kernel needs both operands contiguous along k, unchecked 256 x 256 x 64 tiles and 32-bit lane offsets
     if (b == 256 && p->mode == kFast && a_lay == kKContig && b_lay == kKContig && lda < (1 << 25) && ldb < (1 << 25))
         p->cfg = kBf16_Main;
     return FSRGEMM_OK;

@@ -38,6 +38,16 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
     tn = in_band / rows;
 }
 
+// First row (or column) of output tile `tile` when tiles are `size` wide and the matrix has `extent` rows.
+// The last tile of a matrix that is not a whole number of tiles is shifted back so that it ends with the
+// matrix: it then overlaps its neighbour, both compute the overlap with the same operands in the same order
+// and store the same bits, and no load or store of a full tile can leave the matrix.  Matrices narrower than
+// one tile keep their single tile at 0 and need checked loads and stores.
+__device__ __forceinline__ int tile_origin(int tile, int size, int extent)
+{
+    return extent >= size ? min(tile * size, extent - size) : 0;
+}
+
 // Raises a kernel's dynamic-LDS limit once per device (the attribute belongs to the device's copy of the
 // kernel).  `done` is the caller's per-kernel bitmap of devices already configured; safe to call concurrently.
 hipError_t ensure_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done);

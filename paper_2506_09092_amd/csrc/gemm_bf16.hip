@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
     float *__restrict__ C = g.C + (int64_t)slice * g.slice_stride;
     int tile_m, tile_n;
     tile_coords((int)blockIdx.x - slice * tiles, tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int m0 = tile_origin(tile_m, BM, M), n0 = tile_origin(tile_n, BN, N);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave >> 1) * 32 * T, wn0 = (wave & 1) * 32 * T;

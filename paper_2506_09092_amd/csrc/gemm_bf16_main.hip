@@ -1,4 +1,4 @@
-// Main bf16 kernel for large, tile-aligned problems: C[M x N] = A . B with A
+// Main bf16 kernel for large, aligned problems: C[M x N] = A . B with A
 // row-major and B column-major (both contiguous along k), fp32 accumulate and
 // output -- the Task 2 product at matrix-core input precision.
 //
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
 
     int tile_m, tile_n;
     tile_coords(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * kBM, n0 = tile_n * kBN;
+    const int m0 = tile_origin(tile_m, kBM, g.M), n0 = tile_origin(tile_n, kBN, g.N);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
@@ -316,14 +316,14 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
 
 const char *bf16_main_kernel_name() { return "gemm_bf16_main_kernel"; }
 
-// Requires M % 256 == 0, N % 256 == 0, K % 64 == 0, K >= 64, 16-byte aligned bases,
-// lda % 8 == 0, ldb % 8 == 0 and leading dimensions below 2^25 (32-bit lane offsets).
+// Requires M >= 256, N >= 256, K % 64 == 0, K >= 64, 16-byte aligned bases, lda % 8 == 0, ldb % 8 == 0 and
+// leading dimensions below 2^25 (32-bit lane offsets).  M and N need not be multiples of 256 (tile_origin).
 hipError_t launch_bf16_main(const GemmArgs &a, hipStream_t s)
 {
     static std::atomic<uint64_t> configured{0};
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_main_kernel), kLdsBytes, configured);
     if (e != hipSuccess) return e;
-    const int tiles_m = a.M / kBM, tiles_n = a.N / kBN;
+    const int tiles_m = (a.M + kBM - 1) / kBM, tiles_n = (a.N + kBN - 1) / kBN;
     hipLaunchKernelGGL(gemm_bf16_main_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLdsBytes, s, a,
                        tiles_m, tiles_n);
     return hipGetLastError();

@@ -243,6 +243,45 @@ def test_bf16_big_tile_config_ragged(gpu):
     check_bf16(gpu, A, Bt)
 
 
+@pytest.mark.parametrize("shape,kernel", [((4000, 2100, 256), "gemm_bf16_main_kernel"),           # 16 x 9 tiles of 256, both ragged
+                                          ((2304, 4090, 64), "gemm_bf16_main_kernel"),            # one K-tile, ragged N
+                                          ((257, 33000, 128), "gemm_bf16_main_kernel"),           # second tile row overlaps all but one row
+                                          ((2000, 2100, 128), "gemm_bf16_kernel<2, 2, 0, 0, 0>"),  # 128 x 128 tiles, unchecked
+                                          ((300, 520, 64), "gemm_bf16_kernel<1, 4, 0, 0, 0>")])    # 64 x 64 tiles, unchecked
+def test_bf16_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
+    # aligned problems that are not a whole number of tiles run the unchecked kernels: the last tile row and
+    # column start early enough to end with the matrix
+    M, N, K = shape
+    say("bf16 %dx%dx%d (shifted last tiles)" % shape)
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == kernel
+    A = inputs.bf16_normal_scaled(4, 60, M, K, 1 / math.sqrt(K))
+    Bt = inputs.bf16_normal_scaled(4, 61, N, K, 1 / math.sqrt(K))
+    check_bf16(gpu, A, Bt, repeat=2)
+    check_bf16(gpu, A, Bt, lda=K + 8, ldb=K + 24, ldc=N + 3, repeat=2)
+    Ai, Bi = inputs.bf16_small_ints(4, 62, M, K), inputs.bf16_small_ints(4, 63, N, K)
+    ref, _ = oracle.gemm(Ai, Bi.T)
+    assert np.array_equal(run_bf16(gpu, Ai, Bi).astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("shape,kernel", [((4000, 3000, 64), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+                                          ((2050, 2100, 48), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
+                                          ((1000, 1000, 1008), "gemm_f32_kernel<1, 1, 4, 0, 0, 1>"),
+                                          ((65, 129, 32), "gemm_f32_kernel<1, 1, 4, 0, 0, 1>")])
+def test_f32_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
+    M, N, K = shape
+    say("fp32 %dx%dx%d (shifted last tiles)" % shape)
+    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N + (-N) % 4, 0x1000, N) == kernel
+    A, B = inputs.uniform_pm1(8, 1, M, K), inputs.uniform_pm1(8, 2, K, N)
+    ref, S = oracle.gemm(A, B)
+    for ta, tb in ((0, 0), (1, 1)):
+        lda, ldb = (M if ta else K), (K if tb else N)
+        got = run_f32_ex(gpu, ta, tb, A, B, lda=lda + (-lda) % 4, ldb=ldb + (-ldb) % 4, ldc=N + 1, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+    Ai, Bi = inputs.small_ints(0, 7, M, K), inputs.small_ints(0, 8, K, N)
+    refi, _ = oracle.gemm(Ai, Bi)
+    assert np.array_equal(run_f32(gpu, Ai, Bi, lda=K, ldb=N + (-N) % 4).astype(np.float64), refi)
+
+
 @pytest.mark.parametrize("shape,kernel", [((2048, 2048, 16), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
                                           ((2048, 2048, 32), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
                                           ((2048, 2048, 112), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
