@@ -71,7 +71,11 @@ struct GemmArgs {
 //   kVecPred: 16-byte vectors where a whole vector is in range, element-wise
 //             zero-filled loads at the ragged edge (aligned bases and lds)
 //   kScalar:  element-wise predicated loads (any alignment, any shape)
-enum LoadMode { kFast = 0, kVecPred = 1, kScalar = 2 };
+// Kernels are instantiated for these three; inside a kernel the whole K-tiles of a tile that lies inside the
+// matrix are loaded without checks in every mode: as kFast, or, in a kScalar kernel, as
+//   kUnalignedVec: 16-byte loads from addresses with only the element's alignment, no bounds checks (the
+//             compiler picks the widest load the target allows for such an address)
+enum LoadMode { kFast = 0, kVecPred = 1, kScalar = 2, kUnalignedVec = 3 };
 
 // Which index of an operand tile is contiguous in memory: k (a row-major A, a transposed B) or the
 // m / n index (a transposed A, a row-major B).

@@ -28,9 +28,10 @@
 // one after (k-step 1, each register reloaded only after it has been stored).
 // The one barrier per K-tile sits between the k-steps: the last fragments of
 // this stage are in registers by then and the next stage is completely written.
-// Of the three load modes (as in gemm_f32.hip), the one for aligned but ragged
-// problems lets a workgroup whose tile lies inside the matrix load its whole
-// K-tiles unchecked; only the ragged end of K and the edge tiles pay for checks.
+// Of the three load modes (as in gemm_f32.hip), the two checked ones let a
+// workgroup whose tile lies inside the matrix load its whole K-tiles unchecked
+// (from merely element-aligned addresses in the unaligned mode); only the
+// ragged end of K and matrices narrower than a tile pay for checks.
 // The MFMAs are inline assembly so that every accumulator block stays in its
 // registers across the loop (see gemm_bf16_main.hip); a block is touched again
 // NB * NB >= 4 MFMAs later and the epilogue starts behind explicit wait states.
@@ -53,6 +54,10 @@ __device__ __forceinline__ u32x4 load8(const uint16_t *__restrict__ p, bool row_
     // p points at element (row, col) of the stored matrix; the vector covers col .. col+7 of that row.
     if constexpr (MODE == kFast) {
         return *reinterpret_cast<const u32x4 *>(p);
+    } else if constexpr (MODE == kUnalignedVec) {
+        u32x4 v;
+        __builtin_memcpy(&v, p, sizeof v);
+        return v;
     } else {
         u32x4 v = {0u, 0u, 0u, 0u};
         if (!row_ok) return v;
@@ -164,8 +169,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
 
     // A workgroup whose tile lies inside the matrix needs no check on whole K-tiles even when the problem as a
     // whole is ragged: `unchecked` counts the leading K-tiles it may load like the unchecked mode does.
-    const int unchecked = MODE == kFast ? nk
-                          : (MODE == kVecPred && m0 + BM <= M && n0 + BN <= N) ? max(0, min(nk, K / kBK - t0)) : 0;
+    const int unchecked = MODE == kFast ? nk : (m0 + BM <= M && n0 + BN <= N) ? max(0, min(nk, K / kBK - t0)) : 0;
     u32x4 rg[NG];       // idx < NV: A's vectors; else B's
     auto gload = [&](auto load_mode, int idx, int t) {      // K-tiles past the end are clamped: loaded again, never consumed
         constexpr int LM = decltype(load_mode)::value;
@@ -174,7 +178,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
         else rg[idx] = StB::template gload<LM>(B, g.ldb, n0, N, k0, K, tid, idx - NV);
     };
     using Checked = std::integral_constant<int, MODE>;
-    using Unchecked = std::integral_constant<int, kFast>;
+    using Unchecked = std::integral_constant<int, MODE == kScalar ? kUnalignedVec : kFast>;
     auto lwrite = [&](int stage, int idx) {
         if (idx < NV) StA::lstore(smem + stage * STAGE_B, rg, tid, idx);
         else StB::lstore(smem + stage * STAGE_B + TILE_B, rg + NV, tid, idx - NV);
@@ -228,7 +232,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
     };
 
     // Prologue: K-tile 0 through the registers into stage 0, K-tile 1 into the registers, first fragments.
-    if (MODE == kVecPred && unchecked >= 1) {
+    if (MODE != kFast && unchecked >= 1) {
 #pragma unroll
         for (int idx = 0; idx < NG; ++idx) gload(Unchecked{}, idx, 0);
     } else {
@@ -238,7 +242,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
 #pragma unroll
     for (int idx = 0; idx < NG; ++idx) lwrite(0, idx);
     __builtin_amdgcn_sched_barrier(0);
-    if (MODE == kVecPred && unchecked >= 2) {
+    if (MODE != kFast && unchecked >= 2) {
 #pragma unroll
         for (int idx = 0; idx < NG; ++idx) gload(Unchecked{}, idx, 1);
     } else {
@@ -253,7 +257,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_bf16_kernel(GemmArgs
     __builtin_amdgcn_sched_barrier(0);
 
     int t = 0;
-    if constexpr (MODE == kVecPred) {
+    if constexpr (MODE != kFast) {
         // K-tile t loads K-tile t + 2: this loop runs while t + 3 is still an unchecked K-tile
         for (; t + 3 < unchecked; t += 2) {
             k_tile(std::integral_constant<int, 0>{}, Unchecked{}, t);

@@ -33,9 +33,10 @@
 // that are a whole number of tiles with K a multiple of 16), vectors with
 // element-wise zero-filled edges (aligned, ragged), element-wise predicated
 // loads (any alignment).  Ragged modes also mask the stores.  In the second
-// mode a workgroup whose tile lies inside the matrix runs its whole K-tiles
-// through the unchecked loads and only the ragged end of K through the checked
-// ones, so a ragged problem pays for its edges only at its edges.
+// and third mode a workgroup whose tile lies inside the matrix runs its whole
+// K-tiles through unchecked loads (16-byte loads from merely element-aligned
+// addresses in the third) and only the ragged end of K through the checked
+// ones, so a ragged or unaligned problem pays for its edges only at its edges.
 #include <stdio.h>
 
 #include <type_traits>
@@ -56,6 +57,10 @@ __device__ __forceinline__ f32x4 load4(const float *__restrict__ p, bool row_ok,
     // p points at element (row, col); the vector covers col .. col+3 of that row.
     if constexpr (MODE == kFast) {
         return *reinterpret_cast<const f32x4 *>(p);
+    } else if constexpr (MODE == kUnalignedVec) {
+        f32x4 v;
+        __builtin_memcpy(&v, p, sizeof v);
+        return v;
     } else {
         f32x4 v = {0.f, 0.f, 0.f, 0.f};
         if (!row_ok) return v;
@@ -166,8 +171,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
 
     // A workgroup whose tile lies inside the matrix needs no check on whole K-tiles even when the problem as a
     // whole is ragged: `unchecked` counts the leading K-tiles it may load like the unchecked mode does.
-    const int unchecked = MODE == kFast ? nk
-                          : (MODE == kVecPred && m0 + BM <= M && n0 + BN <= N) ? max(0, min(nk, K / kBK - t0)) : 0;
+    const int unchecked = MODE == kFast ? nk : (m0 + BM <= M && n0 + BN <= N) ? max(0, min(nk, K / kBK - t0)) : 0;
     f32x4 rg[NG];
     auto gload = [&](auto load_mode, int idx, int t) {      // K-tiles past the end are clamped: loaded again, never consumed
         constexpr int LM = decltype(load_mode)::value;
@@ -176,7 +180,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
         else rg[idx] = OpB::template gload<LM>(B, g.ldb, n0, N, k0, K, tid, idx - NA);
     };
     using Checked = std::integral_constant<int, MODE>;
-    using Unchecked = std::integral_constant<int, kFast>;
+    using Unchecked = std::integral_constant<int, MODE == kScalar ? kUnalignedVec : kFast>;
     auto lwrite = [&](int stage, int idx) {
         if (idx < NA) *reinterpret_cast<f32x4 *>(&As[stage * A_ST + OpA::lds_store_at(tid, idx)]) = rg[idx];
         else *reinterpret_cast<f32x4 *>(&Bs[stage * B_ST + OpB::lds_store_at(tid, idx - NA)]) = rg[idx];
@@ -225,7 +229,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
         }
     };
 
-    if (MODE == kVecPred && unchecked >= 1) {
+    if (MODE != kFast && unchecked >= 1) {
 #pragma unroll
         for (int idx = 0; idx < NG; ++idx) gload(Unchecked{}, idx, 0);
     } else {
@@ -235,7 +239,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
 #pragma unroll
     for (int idx = 0; idx < NG; ++idx) lwrite(0, idx);
     __builtin_amdgcn_sched_barrier(0);
-    if (MODE == kVecPred && unchecked >= 2) {
+    if (MODE != kFast && unchecked >= 2) {
 #pragma unroll
         for (int idx = 0; idx < NG; ++idx) gload(Unchecked{}, idx, 1);
     } else {
@@ -250,7 +254,7 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
     __builtin_amdgcn_sched_barrier(0);
 
     int t = 0;
-    if constexpr (MODE == kVecPred) {
+    if constexpr (MODE != kFast) {
         // K-tile t loads K-tile t + 2: this loop runs while t + 3 is still an unchecked K-tile
         for (; t + 3 < unchecked; t += 2) {
             k_tile(std::integral_constant<int, 0>{}, Unchecked{}, t);
