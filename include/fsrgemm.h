@@ -11,11 +11,13 @@
  *
  * Conventions shared by every entry point
  *   - All matrix pointers are DEVICE pointers, valid on the current HIP
- *     device.  The library allocates nothing and keeps no workspace (gemm_f32_ws takes one from the caller).
+ *     device.  The library allocates nothing and keeps no workspace
+ *     (the *_ws entry points take one from the caller).
  *   - M, N, K and the leading dimensions are counted in ELEMENTS.
  *   - Pointers need only the natural alignment of their element type;
- *     faster kernels are picked automatically when base addresses and
- *     leading dimensions are multiples of 16 bytes.
+ *     the fastest kernels are picked automatically when base addresses
+ *     and leading dimensions are multiples of 16 bytes.  M and N may be
+ *     any size; K is fastest as a multiple of 16 (fp32) or 64 (bf16).
  *   - A, B and C must not overlap.  Padding (columns N..ldc-1 of C) is
  *     never written; padding of A and B is never read.
  *   - M == 0 or N == 0: nothing is launched, FSRGEMM_OK.  K == 0: the
