@@ -59,8 +59,10 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     if (ceil_div(M, b) * ceil_div(N, b) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
     const bool vec = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0;
     p->mode = !vec ? kScalar : (M >= b && N >= b && K % 64 == 0 && K > 0) ? kFast : kVecPred;
-    // the direct-to-LDS kernel needs both operands contiguous along k, unchecked 256 x 256 x 64 tiles and 32-bit lane offsets
-    if (b == 256 && p->mode == kFast && a_lay == kKContig && b_lay == kKContig && lda < (1 << 25) && ldb < (1 << 25))
+    // the direct-to-LDS kernel needs unchecked 256 x 256 x 64 tiles, 32-bit lane offsets and, for an operand
+    // that is contiguous along m (n), M (N) a multiple of 8: a shifted last tile must still start 16-byte aligned
+    if (b == 256 && p->mode == kFast && lda < (1 << 25) && ldb < (1 << 25) && (a_lay == kKContig || M % 8 == 0) &&
+        (b_lay == kKContig || N % 8 == 0))
         p->cfg = kBf16_Main;
     return FSRGEMM_OK;
 }

@@ -91,13 +91,13 @@ const char *splitk_reduce_kernel_name();
 hipError_t launch_splitk_reduce(const float *ws, int slices, int64_t slice_stride, float *C, int M, int N, int64_t ldc,
                                 hipStream_t s);
 
-// bf16 configurations: the direct-to-LDS 256x256 kernel for aligned, tile-multiple problems with both
-// operands contiguous along k (gemm_bf16_main.hip) and three tile sizes of the general kernel
-// (gemm_bf16.hip), each in the three load modes and the four layout pairs
+// bf16 configurations: the direct-to-LDS 256x256 kernel for large aligned problems (gemm_bf16_main.hip, the
+// four layout pairs) and three tile sizes of the general kernel (gemm_bf16.hip), each in the three load
+// modes and the four layout pairs
 enum Bf16Config { kBf16_Main = 0, kBf16_256x256 = 1, kBf16_128x128 = 2, kBf16_64x64 = 3, kBf16ConfigCount };
 const char *bf16_kernel_name(int cfg, int mode, int a_lay, int b_lay);
 hipError_t launch_bf16(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
-const char *bf16_main_kernel_name();
-hipError_t launch_bf16_main(const GemmArgs &a, hipStream_t s);
+const char *bf16_main_kernel_name(int a_lay, int b_lay);
+hipError_t launch_bf16_main(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 
 }  // namespace fsrgemm

@@ -4,8 +4,8 @@
 // accumulation and output stay fp32).
 //
 // This file holds the general-purpose kernel: any shape, any alignment, any
-// storage order, three tile sizes.  Large aligned problems whose operands are
-// both contiguous along k go to the kernel in gemm_bf16_main.hip.
+// storage order, three tile sizes.  Large aligned problems go to the kernel in
+// gemm_bf16_main.hip.
 //
 // One workgroup of 256 lanes (4 wavefronts, 2 x 2) owns a (64 T) x (64 T) tile
 // of C, each wavefront 2T x 2T blocks of V_MFMA_F32_16X16X32_BF16: lane l
@@ -340,13 +340,13 @@ const char *bf16_kernel_name(int cfg, int mode, int a_lay, int b_lay)
         }
     };
     static const Names names;
-    return cfg == kBf16_Main ? bf16_main_kernel_name() : names.text[cfg - 1][mode][a_lay][b_lay];
+    return cfg == kBf16_Main ? bf16_main_kernel_name(a_lay, b_lay) : names.text[cfg - 1][mode][a_lay][b_lay];
 }
 
 hipError_t launch_bf16(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
     switch (cfg) {
-    case kBf16_Main: return launch_bf16_main(a, s);
+    case kBf16_Main: return launch_bf16_main(a_lay, b_lay, a, s);
     case kBf16_256x256: return launch_cfg<4, 1>(mode, a_lay, b_lay, a, s);
     case kBf16_128x128: return launch_cfg<2, 2>(mode, a_lay, b_lay, a, s);
     default: return launch_cfg<1, 4>(mode, a_lay, b_lay, a, s);

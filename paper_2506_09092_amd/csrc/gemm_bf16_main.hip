@@ -1,6 +1,9 @@
-// Main bf16 kernel for large, aligned problems: C[M x N] = A . B with A
-// row-major and B column-major (both contiguous along k), fp32 accumulate and
-// output -- the Task 2 product at matrix-core input precision.
+// Main bf16 kernel for large, aligned problems: C[M x N] = A . B, fp32
+// accumulate and output -- the Task 2 product at matrix-core input precision.
+// Either operand may be contiguous along k (a row-major A, a column-major B:
+// the tile's rows are 128 bytes of 64 k) or along m / n (a transposed A, a
+// row-major B: the tile's rows are k-rows of 512 bytes); LDS keeps the memory
+// order and the fragment reads do the rest (see "Fragments" below).
 //
 // Shape of the computation
 //   workgroup  : 256 lanes = 4 wavefronts, one per SIMD, 256 x 256 tile of C
@@ -55,9 +58,22 @@
 // hit a different 128-byte line.  The data is discarded; the lines are then in
 // L2 when the real loads of all sharers arrive.
 //
-// LDS rows are 128 bytes, unpadded; 16-byte chunk c of row r is stored at chunk
-// position c ^ ((r >> 1) & 7).  A 16-lane group of a 128-bit LDS read (16 rows,
-// one chunk) then touches all 64 banks once.
+// Fragments.  The MFMA wants, per lane, 8 consecutive k of row l % 16 at
+// k-offset 8 (l / 16).  For an operand contiguous along k that is one 16-byte
+// LDS read: rows are 128 bytes, unpadded, 16-byte chunk c of row r stored at
+// chunk position c ^ ((r >> 1) & 7), so that a 16-lane group (16 rows, one
+// chunk) touches all 64 banks once.  For an operand contiguous along m / n it
+// is two transposing reads (DS_READ_B64_TR_B16): within a 16-lane group, lane
+// i receives element i % 4 of the 8 bytes that lanes i / 4, 4 + i / 4,
+// 8 + i / 4 and 12 + i / 4 point at.  Lane s therefore points at k-row
+// k0 + s / 4, rows 4 (s % 4) .. + 3 of the block, and lane i ends up with
+// k0 .. k0 + 3 of row i; k0 = 8 (l / 16) for the first read, + 4 for the second.
+// Such a tile's k-rows are 512 bytes; 16-byte chunk c of k-row k is stored at
+// c ^ f(k), f(k) = 2 (k % 4) + 8 ((k / 8) % 2): the 32 lanes one pass of the
+// read serves (4 + 4 k-rows, 32 bytes each) then cover all 64 banks once.  A
+// block's reads differ by an XOR in address bits 5-7, so a lane keeps one
+// address per block (8 registers per such operand) and reaches k-step, half
+// and stage through immediate offsets.
 #include <type_traits>
 #include <utility>
 
@@ -89,6 +105,9 @@ struct Frag {
     bf16x8 b[8];
 };
 
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
 template <int I>
 using Int = std::integral_constant<int, I>;
 
@@ -104,8 +123,13 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
+// chunk swizzle of a tile whose rows are k-rows (operand contiguous along m / n)
+__device__ __forceinline__ int kswz(int k) { return ((k & 3) << 1) | (((k >> 3) & 1) << 3); }
+
+template <int ALAY, int BLAY>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, int tiles_m, int tiles_n)
 {
+    constexpr bool AMC = ALAY == kMnContig, BMC = BLAY == kMnContig;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     int tile_m, tile_n;
@@ -119,24 +143,35 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     const uint16_t *A = static_cast<const uint16_t *>(g.A);
     const uint16_t *B = static_cast<const uint16_t *>(g.B);
 
-    // Global -> LDS.  A load instruction moves 64 x 16 bytes to 1 KB of contiguous LDS = 8 tile rows.
-    // Wavefront w fills rows 64 w + 8 q + lane/8 (q = 0..7) of the A tile (load index q) and of the B
-    // tile (load index 8 + q); the lane fetches the chunk that belongs at its LDS position:
-    // (lane % 8) ^ ((row >> 1) & 7), and ((64 w + 8 q + lane/8) >> 1) & 7 = 4 (q & 1) + (lane/8 >> 1):
-    // one lane offset for even q and one for odd q, per operand.
+    // Global -> LDS.  A load instruction moves 64 x 16 bytes to 1 KB of contiguous LDS; a wavefront fills 8 KB
+    // of each operand tile with 8 loads (index q = 0..7 for A, 8 + q for B).
+    //   contiguous along k    : 8 tile rows per load: rows 64 w + 8 q + lane / 8; the lane fetches the chunk that
+    //                           belongs at its position, (lane % 8) ^ ((row >> 1) & 7), and
+    //                           ((64 w + 8 q + lane / 8) >> 1) & 7 = 4 (q & 1) + (lane / 8 >> 1): one lane offset for
+    //                           even q, one for odd q.  The lane offsets also carry the K position.
+    //   contiguous along m / n: 2 k-rows per load: k-rows 16 w + 2 q + lane / 32; chunk (lane % 32) ^ kswz(k-row),
+    //                           k-row % 4 = 2 (q & 1) + lane / 32 and (k-row / 8) % 2 = q / 4: four lane offsets,
+    //                           index (q & 1) + 2 (q >> 2).  The K position is carried by the scalar row bases.
     const int lrow = lane >> 3, lpos = lane & 7;
     const int sw_even = (lrow >> 1) & 3, sw_odd = sw_even ^ 4;
-    // lane offsets in bytes: A even q, A odd q, B even q, B odd q; they also carry the K position
-    uint32_t voff[4] = {(uint32_t)(lrow * g.lda + (lpos ^ sw_even) * 8) * 2u,
-                        (uint32_t)(lrow * g.lda + (lpos ^ sw_odd) * 8) * 2u,
-                        (uint32_t)(lrow * g.ldb + (lpos ^ sw_even) * 8) * 2u,
-                        (uint32_t)(lrow * g.ldb + (lpos ^ sw_odd) * 8) * 2u};
-    const char *rbase[16];          // row-group bases: uniform, fixed for the tile
+    const int hrow = lane >> 5, hpos = lane & 31;
+    uint32_t voff_a[4], voff_b[4];      // bytes
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int kr = 2 * (v & 1) + hrow + 8 * (v >> 1);
+        const int kc_chunk = lpos ^ ((v & 1) ? sw_odd : sw_even);
+        voff_a[v] = AMC ? (uint32_t)(hrow * g.lda * 2 + (hpos ^ kswz(kr)) * 16) : (uint32_t)(lrow * g.lda + kc_chunk * 8) * 2u;
+        voff_b[v] = BMC ? (uint32_t)(hrow * g.ldb * 2 + (hpos ^ kswz(kr)) * 16) : (uint32_t)(lrow * g.ldb + kc_chunk * 8) * 2u;
+    }
+    const char *rbase[16];          // row-group bases: uniform; fixed for the tile unless they carry the K position
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-        rbase[q] = reinterpret_cast<const char *>(A + (int64_t)(m0 + wave * 64 + q * 8) * g.lda);
-        rbase[8 + q] = reinterpret_cast<const char *>(B + (int64_t)(n0 + wave * 64 + q * 8) * g.ldb);
+        rbase[q] = AMC ? reinterpret_cast<const char *>(A + (int64_t)(wave * 16 + q * 2) * g.lda + m0)
+                       : reinterpret_cast<const char *>(A + (int64_t)(m0 + wave * 64 + q * 8) * g.lda);
+        rbase[8 + q] = BMC ? reinterpret_cast<const char *>(B + (int64_t)(wave * 16 + q * 2) * g.ldb + n0)
+                           : reinterpret_cast<const char *>(B + (int64_t)(n0 + wave * 64 + q * 8) * g.ldb);
     }
+    const int64_t kstep_a = 64 * g.lda * 2, kstep_b = 64 * g.ldb * 2;       // one K-tile of k-rows, in bytes
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(FSR_AS3 char *)smem);
     const uint32_t wave_lds = lds0 + wave * (64 * 128);
     // M0 <- LDS address of load `idx` in `stage`; at least one instruction must follow before the load
@@ -146,28 +181,43 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         const uint32_t w = wave_lds;
         asm volatile("s_add_u32 m0, %0, %1" ::"s"(w), "n"(kOff) : "m0", "scc");
     };
+    bool more = 1 < nk;     // the K-tile after the one now being loaded lies inside K (else the last one is loaded again)
     auto load_go = [&](auto idx) {
-        constexpr int I = decltype(idx)::value;
-        const uint32_t vo = voff[(I < 8 ? 0 : 2) + (I & 1)];
+        constexpr int I = decltype(idx)::value, q = I & 7;
+        constexpr bool mc = I < 8 ? AMC : BMC;
+        constexpr int v = mc ? (q & 1) + 2 * (q >> 2) : (q & 1);
+        const uint32_t vo = I < 8 ? voff_a[v] : voff_b[v];
         const char *rb = rbase[I];
         asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(vo), "s"(rb) : "memory");
+        if constexpr (mc) rbase[I] += more ? (I < 8 ? kstep_a : kstep_b) : 0;      // its next use is the next K-tile
     };
-    // after the last load of a K-tile: the lane offsets move on to K-tile `next`; past the end they stay on
+    // after the last load of a K-tile: the following loads fetch K-tile `next`; past the end they stay on
     // the last K-tile, whose data then lands once more in a stage that is never read again
     auto advance = [&](int next) {
+        more = next + 1 < nk;
         const uint32_t step = next < nk ? (uint32_t)(kBK * 2) : 0u;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) voff[q] += step;
+        if (!AMC) voff_a[0] += step, voff_a[1] += step;
+        if (!BMC) voff_b[0] += step, voff_b[1] += step;
     };
 
-    // Prefetch touches: lanes 0-15 take A rows 64 (tile_n % 4) + 16 w + lane, lanes 16-23 take B rows
-    // 32 (tile_m % 8) + 8 w + (lane - 16); the remaining lanes repeat lane 0 and coalesce with it.
+    // Prefetch touches, one 128-byte line per lane.  Contiguous along k: lanes 0-15 take A rows
+    // 64 (tile_n % 4) + 16 w + lane, lanes 16-23 take B rows 32 (tile_m % 8) + 8 w + (lane - 16).  Contiguous
+    // along m / n (a K-tile is 64 k-rows of 4 lines): lanes 0-15 take A k-rows 16 (tile_n % 4) + 4 w + lane / 4,
+    // line lane % 4; lanes 16-23 take B k-rows 8 (tile_m % 8) + 2 w + (lane - 16) / 4, line (lane - 16) % 4.
+    // The remaining lanes repeat lane 0 and coalesce with it.
     const char *touch_ptr;
+    int64_t touch_step;
     {
-        const int tl = lane < 24 ? lane : 0;
-        touch_ptr = tl < 16
-            ? reinterpret_cast<const char *>(A + (int64_t)(m0 + (tile_n & 3) * 64 + wave * 16 + tl) * g.lda)
-            : reinterpret_cast<const char *>(B + (int64_t)(n0 + (tile_m & 7) * 32 + wave * 8 + (tl - 16)) * g.ldb);
+        const int tl = lane < 24 ? lane : 0, u = tl - 16;
+        if (tl < 16) {
+            touch_ptr = AMC ? reinterpret_cast<const char *>(A + (int64_t)((tile_n & 3) * 16 + wave * 4 + (tl >> 2)) * g.lda + m0 + (tl & 3) * 64)
+                            : reinterpret_cast<const char *>(A + (int64_t)(m0 + (tile_n & 3) * 64 + wave * 16 + tl) * g.lda);
+            touch_step = AMC ? kstep_a : kBK * 2;
+        } else {
+            touch_ptr = BMC ? reinterpret_cast<const char *>(B + (int64_t)((tile_m & 7) * 8 + wave * 2 + (u >> 2)) * g.ldb + n0 + (u & 3) * 64)
+                            : reinterpret_cast<const char *>(B + (int64_t)(n0 + (tile_m & 7) * 32 + wave * 8 + u) * g.ldb);
+            touch_step = BMC ? kstep_b : kBK * 2;
+        }
     }
     const uint32_t touch_lds = lds0 + 2 * kStageBytes + wave * 256;
     auto touch_m0 = [&]() {
@@ -176,28 +226,48 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     };
     auto touch_go = [&](int t) {
         const int tc = t < nk ? t : nk - 1;
-        const char *p = touch_ptr + (int64_t)tc * (kBK * 2);
+        const char *p = touch_ptr + (int64_t)tc * touch_step;
         asm volatile("global_load_lds_dword %0, off" ::"v"(p) : "memory");
     };
 
-    // Fragment of 16 rows x 32 k: the lane reads row l16 of the block, 16-byte chunk 4 kk + lq.
-    int ra_off[2], rb_off[2];
+    // Fragment addresses.  Contiguous along k: row l16 of the block, chunk 4 kk + lq; blocks are 2 KB apart.
+    // Contiguous along m / n: as the source of a transposing read the lane points at k-row
+    // 32 kk + 8 lq + 4 h + l16 / 4 (h = 0, 1: the two reads), rows 16 b + 4 (l16 % 4) .. + 3 of the wavefront's
+    // part; block b flips address bits 5-7 with b, k-step and half add 16 KB and 2 KB.
+    int ra_off[2], rb_off[2], ra_blk[8], rb_blk[8];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
         const int pos = (4 * kk + lq) ^ ((l16 >> 1) & 7);
         ra_off[kk] = (wm0 + l16) * 128 + pos * 16;
         rb_off[kk] = kTileBytes + (wn0 + l16) * 128 + pos * 16;
     }
+    {
+        const int fk = kswz((l16 >> 2) + 8 * lq), half = (l16 >> 1) & 1;
+        const int row_part = (8 * lq + (l16 >> 2)) * 512 + (l16 & 1) * 8;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            ra_blk[b] = (row_part + ((wm0 / 8) | fk | half) * 16) ^ (b << 5);
+            rb_blk[b] = kTileBytes + ((row_part + ((wn0 / 8) | fk | half) * 16) ^ (b << 5));
+        }
+    }
     Frag F[2];
-    // idx orders the sixteen reads as the next k-step consumes them: a0, b0..b7, a1..a7
+    auto tr_read = [&](const char *p) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)p);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)(p + 2048));
+        return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // idx orders the sixteen fragments as the next k-step consumes them: a0, b0..b7, a1..a7
     auto lread = [&](int stage, int kk, int fi, int idx) {
         const char *s = smem + stage * kStageBytes;
-        if (idx == 0)
-            F[fi].a[0] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk]);
-        else if (idx <= 8)
-            F[fi].b[idx - 1] = *reinterpret_cast<const bf16x8 *>(s + rb_off[kk] + (idx - 1) * 2048);
-        else
-            F[fi].a[idx - 8] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk] + (idx - 8) * 2048);
+        if (idx == 0 || idx > 8) {
+            const int i = idx == 0 ? 0 : idx - 8;
+            if (AMC) F[fi].a[i] = tr_read(s + ra_blk[i] + kk * 16384);
+            else F[fi].a[i] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk] + i * 2048);
+        } else {
+            const int j = idx - 1;
+            if (BMC) F[fi].b[j] = tr_read(s + rb_blk[j] + kk * 16384);
+            else F[fi].b[j] = *reinterpret_cast<const bf16x8 *>(s + rb_off[kk] + j * 2048);
+        }
     };
 
     f32x4 acc[8][8];
@@ -297,36 +367,59 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     // before the accumulators are read (the compiler does not know what wrote them)
     asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
-    // Register r of a 16x16 block holds row 4 (lane / 16) + r, column lane % 16.
+    // Register r of a 16x16 block holds row 4 (lane / 16) + r, column lane % 16.  The lane ids are taken
+    // afresh so that no store address is kept in a register across the loop; blocks are fenced so that the
+    // accumulators are copied out a block at a time.
     float *__restrict__ C = g.C;
+    int l16e = lane & 15, lqe = lane >> 4;
+    asm volatile("" : "+v"(l16e), "+v"(lqe));
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int col = n0 + wn0 + j * 16 + l16;
+            const int col = n0 + wn0 + j * 16 + l16e;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int row = m0 + wm0 + i * 16 + lq * 4 + r;
+                const int row = m0 + wm0 + i * 16 + lqe * 4 + r;
                 C[(int64_t)row * g.ldc + col] = acc[i][j][r];
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
 }
 
 }  // namespace
 
-const char *bf16_main_kernel_name() { return "gemm_bf16_main_kernel"; }
-
-// Requires M >= 256, N >= 256, K % 64 == 0, K >= 64, 16-byte aligned bases, lda % 8 == 0, ldb % 8 == 0 and
-// leading dimensions below 2^25 (32-bit lane offsets).  M and N need not be multiples of 256 (tile_origin).
-hipError_t launch_bf16_main(const GemmArgs &a, hipStream_t s)
+// <A layout, B layout> with 0 = contiguous along k, 1 = along m / n; as a profiler trace prints the kernel
+const char *bf16_main_kernel_name(int a_lay, int b_lay)
 {
+    static const char *names[2][2] = {{"gemm_bf16_main_kernel<0, 0>", "gemm_bf16_main_kernel<0, 1>"},
+                                      {"gemm_bf16_main_kernel<1, 0>", "gemm_bf16_main_kernel<1, 1>"}};
+    return names[a_lay][b_lay];
+}
+
+namespace {
+
+template <int ALAY, int BLAY>
+hipError_t launch_main(const GemmArgs &a, hipStream_t s)
+{
+    auto kern = gemm_bf16_main_kernel<ALAY, BLAY>;
     static std::atomic<uint64_t> configured{0};
-    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_main_kernel), kLdsBytes, configured);
+    const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kLdsBytes, configured);
     if (e != hipSuccess) return e;
     const int tiles_m = (a.M + kBM - 1) / kBM, tiles_n = (a.N + kBN - 1) / kBN;
-    hipLaunchKernelGGL(gemm_bf16_main_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLdsBytes, s, a,
-                       tiles_m, tiles_n);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLdsBytes, s, a, tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+}  // namespace
+
+// Requires M >= 256, N >= 256, K % 64 == 0, K >= 64, 16-byte aligned bases, lda % 8 == 0, ldb % 8 == 0 and
+// leading dimensions below 2^25 (32-bit lane offsets).  M and N need not be multiples of 256 (tile_origin), but an
+// operand contiguous along m (n) needs M % 8 == 0 (N % 8 == 0) so that a shifted tile still starts 16-byte aligned.
+hipError_t launch_bf16_main(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
+{
+    if (a_lay == kKContig) return b_lay == kKContig ? launch_main<kKContig, kKContig>(a, s) : launch_main<kKContig, kMnContig>(a, s);
+    return b_lay == kKContig ? launch_main<kMnContig, kKContig>(a, s) : launch_main<kMnContig, kMnContig>(a, s);
 }
 
 }  // namespace fsrgemm

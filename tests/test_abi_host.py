@@ -72,7 +72,7 @@ def test_dispatch_query_names_variants():
     assert q(64, 64, 0, P, 4, P, 64, P, 64) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"                    # K = 0 never takes the unchecked mode
     assert q(4, 4, 4, P, 3, P, 4, P, 4) is None
     qb = lib.fsrgemm_kernel_for_bf16
-    assert qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel"
+    assert qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<0, 0>"
     # general kernel <T, min waves, load mode>: tile (64 T) x (64 T)
     assert qb(8192, 8192, 8200, P, 8200, P, 8200, P, 8192) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"   # K not a multiple of 64
     assert qb(2048, 2048, 512, P, 512, P, 512, P, 2048) == "gemm_bf16_kernel<2, 2, 0, 0, 0>"
@@ -80,18 +80,24 @@ def test_dispatch_query_names_variants():
     assert qb(100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1, 0, 0>"
     # leading dimensions of 2^25 elements and more do not fit the main kernel's 32-bit lane offsets
     assert qb(8192, 8192, 8192, P, 1 << 25, P, 8192, P, 8192) == "gemm_bf16_kernel<4, 1, 0, 0, 0>"
-    assert qb(8192, 8192, 8192, P, (1 << 25) - 8, P, 8192, P, 8192) == "gemm_bf16_main_kernel"
+    assert qb(8192, 8192, 8192, P, (1 << 25) - 8, P, 8192, P, 8192) == "gemm_bf16_main_kernel<0, 0>"
     # ragged M and N still take the unchecked kernels (last tiles are shifted back); a ragged K does not
-    assert qb(8000, 8000, 8000, P, 8000, P, 8000, P, 8000) == "gemm_bf16_main_kernel"
+    assert qb(8000, 8000, 8000, P, 8000, P, 8000, P, 8000) == "gemm_bf16_main_kernel<0, 0>"
     assert qb(8000, 8000, 8008, P, 8008, P, 8008, P, 8000) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"
     assert qb(255, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_kernel<1, 4, 0, 0, 0>"          # 4 x 128 tiles of 64
     assert q(4000, 4000, 4000, P, 4000, P, 4000, P, 4000) == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
     assert q(63, 4000, 4000, P, 4000, P, 4000, P, 4000) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"            # narrower than a tile
-    # other storage orders: <.., A layout, B layout> with 0 = contiguous along k, 1 = along m / n; never the main kernel
+    # other storage orders: <.., A layout, B layout> with 0 = contiguous along k, 1 = along m / n
     qx = lib.fsrgemm_kernel_for_bf16_ex
-    assert qx(0, 1, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel"
-    assert qx(0, 0, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_kernel<4, 1, 0, 0, 1>"
-    assert qx(1, 1, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_kernel<4, 1, 0, 1, 0>"
+    assert qx(0, 1, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<0, 0>"
+    assert qx(0, 0, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<0, 1>"
+    assert qx(1, 1, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<1, 0>"
+    assert qx(1, 0, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<1, 1>"
+    # an operand contiguous along m (n) keeps the main kernel only if M (N) is a multiple of 8
+    assert qx(1, 0, 8000, 4008, 512, P, 8000, P, 4008, P, 4008) == "gemm_bf16_main_kernel<1, 1>"
+    assert qx(1, 1, 8004, 8000, 512, P, 8008, P, 512, P, 8000) == "gemm_bf16_kernel<4, 1, 0, 1, 0>"
+    assert qx(0, 0, 8004, 8004, 512, P, 512, P, 8008, P, 8004) == "gemm_bf16_kernel<4, 1, 0, 0, 1>"
+    assert qx(0, 1, 8004, 8004, 512, P, 512, P, 512, P, 8004) == "gemm_bf16_main_kernel<0, 0>"
     assert qx(1, 0, 100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1, 1, 1>"
     assert qx(1, 0, 100, 90, 80, P, 99, P, 90, P, 90) is None                                 # lda < M for a transposed A
 

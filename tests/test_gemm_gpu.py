@@ -216,6 +216,29 @@ def test_bf16_storage_orders(gpu, shape, ta, tb):
     assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
 
 
+@pytest.mark.parametrize("ta,tb", BF16_STORAGE)
+@pytest.mark.parametrize("shape", [(4096, 2048, 64), (4096, 2048, 192), (2304, 4096, 448),      # whole tiles, 1 / 3 / 7 K-tiles
+                                   (4000, 2104, 256), (2312, 3992, 128), (264, 33000, 64)])       # shifted last tiles
+def test_bf16_main_kernel_storage_orders(gpu, shape, ta, tb):
+    # operands contiguous along m / n in the direct-to-LDS kernel: k-row tiles and transposing fragment reads
+    M, N, K = shape
+    say("bf16 main kernel storage %d%d %dx%dx%d" % (ta, tb, M, N, K))
+    lda, ldb = (M if ta else K), (K if tb else N)
+    name = "gemm_bf16_main_kernel<%d, %d>" % (ta, 1 - tb)
+    assert gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name
+    A = inputs.bf16_normal_scaled(4, 70, M, K, 1 / math.sqrt(K))
+    B = inputs.bf16_normal_scaled(4, 71, K, N, 1 / math.sqrt(K))
+    ref, S = oracle.gemm(A, B)
+    got = run_bf16_ex(gpu, ta, tb, A, B, repeat=2)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+    assert gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, 0x1000, lda + 8, 0x1000, ldb + 40, 0x1000, N + 3) == name
+    got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda + 8, ldb=ldb + 40, ldc=N + 3, repeat=2)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+    Ai, Bi = inputs.bf16_small_ints(4, 72, M, K), inputs.bf16_small_ints(4, 73, K, N)
+    refi, _ = oracle.gemm(Ai, Bi)
+    assert np.array_equal(run_bf16_ex(gpu, ta, tb, Ai, Bi).astype(np.float64), refi)
+
+
 @pytest.mark.parametrize("ta,tb", BF16_STORAGE + [(0, 1)])
 def test_bf16_storage_orders_integers_bit_exact(gpu, ta, tb):
     A, B = inputs.bf16_small_ints(4, 42, 384, 512), inputs.bf16_small_ints(4, 43, 512, 320)
@@ -243,9 +266,9 @@ def test_bf16_big_tile_config_ragged(gpu):
     check_bf16(gpu, A, Bt)
 
 
-@pytest.mark.parametrize("shape,kernel", [((4000, 2100, 256), "gemm_bf16_main_kernel"),           # 16 x 9 tiles of 256, both ragged
-                                          ((2304, 4090, 64), "gemm_bf16_main_kernel"),            # one K-tile, ragged N
-                                          ((257, 33000, 128), "gemm_bf16_main_kernel"),           # second tile row overlaps all but one row
+@pytest.mark.parametrize("shape,kernel", [((4000, 2100, 256), "gemm_bf16_main_kernel<0, 0>"),           # 16 x 9 tiles of 256, both ragged
+                                          ((2304, 4090, 64), "gemm_bf16_main_kernel<0, 0>"),            # one K-tile, ragged N
+                                          ((257, 33000, 128), "gemm_bf16_main_kernel<0, 0>"),           # second tile row overlaps all but one row
                                           ((2000, 2100, 128), "gemm_bf16_kernel<2, 2, 0, 0, 0>"),  # 128 x 128 tiles, unchecked
                                           ((300, 520, 64), "gemm_bf16_kernel<1, 4, 0, 0, 0>")])    # 64 x 64 tiles, unchecked
 def test_bf16_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
@@ -307,12 +330,12 @@ def test_bf16_main_kernel_small_k(gpu, K):
     # the scheduled 256x256 kernel with 1, 2, 3 and 7 K-tiles: prologue, odd/even tails, clamped prefetch
     M, N = 2048, 4096
     say("bf16 main kernel %dx%dx%d" % (M, N, K))
-    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_main_kernel"
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_main_kernel<0, 0>"
     A = inputs.bf16_normal_scaled(4, 50 + K, M, K, 1 / math.sqrt(K))
     Bt = inputs.bf16_normal_scaled(4, 51 + K, N, K, 1 / math.sqrt(K))
     check_bf16(gpu, A, Bt, repeat=2)
     if K == 192:                                            # padded leading dimensions stay on the same kernel
-        assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K + 8, 0x1000, K + 72, 0x1000, N + 3) == "gemm_bf16_main_kernel"
+        assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K + 8, 0x1000, K + 72, 0x1000, N + 3) == "gemm_bf16_main_kernel<0, 0>"
         check_bf16(gpu, A, Bt, lda=K + 8, ldb=K + 72, ldc=N + 3)
         Ai, Bi = inputs.bf16_small_ints(4, 60, M, K), inputs.bf16_small_ints(4, 61, N, K)
         got = run_bf16(gpu, Ai, Bi)
@@ -406,7 +429,7 @@ def test_bf16_8192_full_size(gpu):
     n = 8192
     A = inputs.bf16_normal_scaled(4, 1, n, n, 1 / math.sqrt(n))
     Bt = inputs.bf16_normal_scaled(4, 2, n, n, 1 / math.sqrt(n))
-    assert gpu.fsrgemm_kernel_for_bf16(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_bf16_main_kernel"
+    assert gpu.fsrgemm_kernel_for_bf16(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_bf16_main_kernel<0, 0>"
     got = run_bf16(gpu, A, Bt)
     say("  GPU done; oracle on samples")
     rng = np.random.default_rng(4)
