@@ -1,12 +1,14 @@
-"""CPU oracle for C = A x B (the paper's Task 2, task-prompt table).
+"""CPU oracle for C = A x B (the paper's Task 2, task-prompt table) and for
+matrix transposition (Task 8).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
 bench's cpu_baseline leg.  The GPU library never imports or calls it, and the
 two share no code.
 
-The arithmetic lives in ``gemm_oracle.c`` (a plain fp64 triple loop); this
-module compiles it with gcc, loads it with ctypes and adds the error metrics
-that the parity tests gate on.  Matrices are numpy arrays; their strides are
+The arithmetic lives in ``gemm_oracle.c`` (a plain fp64 triple loop) and
+``transpose_oracle.c`` (an element-by-element move); this module compiles them
+with gcc, loads them with ctypes and adds the error metrics that the parity
+tests gate on.  Matrices are numpy arrays; their strides are
 passed through unchanged, so any row/column-major or padded view works.
 """
 from __future__ import annotations
@@ -19,16 +21,18 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gemm_oracle.c")
+_SRC_T = os.path.join(_HERE, "transpose_oracle.c")
 _LIB = os.path.join(_HERE, "libgemm_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile gemm_oracle.c into libgemm_oracle.so beside it (gcc, OpenMP)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile the oracle's C sources into libgemm_oracle.so beside them (gcc, OpenMP)."""
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_T))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-o", tmp, _SRC, "-lm"]
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-o", tmp, _SRC, _SRC_T, "-lm"]
         )
         os.replace(tmp, _LIB)
     return _LIB
@@ -50,6 +54,8 @@ def _load():
             fn = getattr(lib, name)
             fn.argtypes = sig
             fn.restype = ctypes.c_int
+        lib.oracle_transpose_f32.argtypes = [i64, i64, vp, i64, i64, vp, i64, i64]
+        lib.oracle_transpose_f32.restype = ctypes.c_int
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -101,6 +107,19 @@ def gemm(A: np.ndarray, B: np.ndarray, want_scale: bool = True):
             C.ctypes.data, N, S.ctypes.data if want_scale else None, N)
     assert rc == 0
     return C, S
+
+
+def transpose(A: np.ndarray) -> np.ndarray:
+    """T with T[j][i] = A[i][j]: a new C-contiguous (cols, rows) float32 array.  Any strides are accepted."""
+    if A.dtype != np.float32 or A.ndim != 2:
+        raise TypeError("oracle.transpose takes a 2-D float32 array")
+    rows, cols = A.shape
+    T = np.empty((cols, rows), dtype=np.float32)
+    if rows and cols:
+        a_rs, a_cs = _strides(A)
+        rc = _load().oracle_transpose_f32(rows, cols, A.ctypes.data, a_rs, a_cs, T.ctypes.data, rows, 1)
+        assert rc == 0
+    return T
 
 
 def gemm_entries(A: np.ndarray, B: np.ndarray, ii, jj):

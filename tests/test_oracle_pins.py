@@ -255,3 +255,78 @@ def test_error_metric_and_freivalds_detect_planted_mistakes():
     assert oracle.componentwise_error(bad, C, S) == float("inf")
     assert oracle.freivalds_residual(A, B, bad) == float("inf")
     assert oracle.componentwise_error(np.zeros((0, 3)), np.zeros((0, 3)), np.zeros((0, 3))) == 0.0
+
+
+# ---- transposition (Task 8) ----
+
+def _golden_transposes():
+    path = os.path.join(os.path.dirname(__file__), "golden", "task8_tiny.txt")
+    cases, cur = [], {}
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        tok = line.split()
+        if tok[0] == "ROWS":
+            cur = {"rows": int(tok[1]), "cols": int(tok[3])}
+            cases.append(cur)
+        else:
+            cur[tok[0]] = np.array([float(x) for x in tok[1:]], dtype=np.float32)
+    return cases
+
+
+def test_transpose_golden_worked_examples():
+    cases = _golden_transposes()
+    assert len(cases) == 3
+    for c in cases:
+        T = oracle.transpose(c["A"].reshape(c["rows"], c["cols"]))
+        assert T.shape == (c["cols"], c["rows"]) and T.flags["C_CONTIGUOUS"]
+        assert np.array_equal(T.ravel(), c["T"])
+
+
+def test_transpose_brute_force_and_strided_views():
+    rng = np.random.default_rng(5)
+    for rows, cols in ((1, 1), (1, 7), (7, 1), (2, 3), (5, 5), (13, 4), (31, 33), (64, 65)):
+        A = rng.standard_normal((rows, cols)).astype(np.float32)
+        T = oracle.transpose(A)
+        for i in range(rows):
+            for j in range(cols):
+                assert T[j, i] == A[i, j]
+        # the same logical matrix seen through padded and column-major storage
+        padded = np.full((rows, cols + 3), np.float32(np.nan)); padded[:, :cols] = A
+        assert np.array_equal(oracle.transpose(padded[:, :cols]), T)
+        assert np.array_equal(oracle.transpose(np.asfortranarray(A)), T)
+
+
+def test_transpose_is_an_involution_and_matches_the_library_view():
+    rng = np.random.default_rng(6)
+    A = rng.standard_normal((37, 91)).astype(np.float32)
+    bits = A.view(np.uint32)
+    bits[0, 0], bits[1, 2], bits[3, 4], bits[5, 6] = 0x80000000, 0x7FC12345, 0xFFC00001, 0x00000001   # -0, NaNs with payload, denormal
+    T = oracle.transpose(A)
+    assert np.array_equal(oracle.transpose(T).view(np.uint32), bits)          # twice is the identity, bit for bit
+    assert np.array_equal(T.view(np.uint32), np.ascontiguousarray(A.T).view(np.uint32))   # numpy's own transposition
+    Q = rng.standard_normal((37, 37)).astype(np.float32)
+    S = Q + Q.T                                                                # a symmetric matrix is its own transpose
+    assert np.array_equal(oracle.transpose(S), S)
+    eye = np.eye(9, dtype=np.float32)
+    assert np.array_equal(oracle.transpose(eye), eye)
+
+
+def test_transpose_ties_in_with_the_product_oracle():
+    # (A B)^T = B^T A^T with the transposes taken by this oracle and the products by the other one: every sum
+    # has the same terms in the same order, so the two sides agree bit for bit
+    A, B = inputs.uniform_pm1(9, 1, 23, 17), inputs.uniform_pm1(9, 2, 17, 29)
+    left, _ = oracle.gemm(A, B)
+    right, _ = oracle.gemm(oracle.transpose(B), oracle.transpose(A))
+    assert np.array_equal(left.T, right)
+
+
+def test_transpose_detects_planted_mistakes():
+    A = inputs.uniform_pm1(9, 3, 6, 6)
+    T = oracle.transpose(A)
+    assert not np.array_equal(T, A)                              # a plain copy is not a transpose
+    assert not np.array_equal(T, A[::-1, ::-1])                  # nor is a reversal
+    wrong = T.copy(); wrong[2, 3], wrong[3, 2] = T[3, 2], T[2, 3]
+    assert not np.array_equal(wrong, T)
+    assert oracle.transpose(np.zeros((0, 5), dtype=np.float32)).shape == (5, 0)
+    assert oracle.transpose(np.zeros((4, 0), dtype=np.float32)).shape == (0, 4)
