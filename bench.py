@@ -251,6 +251,37 @@ def split_k(lib, torch, kind, launches=9):
     return out
 
 
+def transpose_sizes(lib, torch, launches=9):
+    """The paper's Task 8 (matrix transposition) on its five sizes N x N, N = 2^10 .. 2^14: median time per launch
+    and the HBM roofline (every element read once and written once against 8 TB/s).  The two smallest sizes are
+    timed as 16 launches in a row, since one of them is shorter than the gap between launches; they (and partly
+    4096^2) stay in the chip's caches between launches.  Parity is a GPU test."""
+    stream = torch.cuda.current_stream().cuda_stream
+    out = []
+    for e in (10, 11, 12, 13, 14):
+        n = 1 << e
+        reps = 16 if n <= 2048 else 1
+        a = torch.randn(n, n, device="cuda")
+        t = torch.empty(n, n, device="cuda")
+        for _ in range(3):
+            lib.check(lib.transpose_f32(n, n, a, n, t, n, stream))
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
+        for e0, e1 in evs:
+            e0.record()
+            for _ in range(reps):
+                lib.check(lib.transpose_f32(n, n, a, n, t, n, stream))
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sorted(x.elapsed_time(y) for x, y in evs)[launches // 2] / reps
+        byts = 8.0 * n * n
+        out.append({"n": n, "ms": ms, "launches_per_timing": reps,
+                    "roofline": {"bound": "hbm", "kernel": lib.fsrgemm_kernel_for_transpose_f32(n, n, a, n, t, n),
+                                 "achieved": byts / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s", "frac": byts / (ms * 1e-3) / 8e12}})
+        del a, t
+    return out
+
+
 def cpu_baseline(w):
     """The oracle as it stands, timed on the host cores over a slab of rows of the same workload."""
     import oracle
@@ -313,13 +344,14 @@ def main():
         del w
         torch.cuda.empty_cache()
 
-    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = None
+    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = None
     if not args.headline_only:
         task2 = paper_task2_sizes(lib, torch)
         layouts = transposed_storage_4096(lib, torch)
         layouts_bf16 = storage_orders_bf16_8192(lib, torch)
         skinny = split_k(lib, torch, "f32")
         skinny_bf16 = split_k(lib, torch, "bf16")
+        task8 = transpose_sizes(lib, torch)
     torch.cuda.empty_cache()
 
     if args.copy_calibration:
@@ -347,6 +379,7 @@ def main():
         "storage_orders_bf16_8192": layouts_bf16,
         "split_k_f32": skinny,
         "split_k_bf16": skinny_bf16,
+        "paper_task8_transpose": task8,
         "paper_context": "paper reports only speedups over hand-written CUDA for the group holding Task 2: 5.95-68.3x (RTX 3090 Ti), 6.06-60.0x (GTX 1660 SUPER)",
     }
     print(json.dumps(out), flush=True)

@@ -1,5 +1,6 @@
 /*
- * fsrgemm -- dense matrix multiplication C = A x B for AMD MI355X (gfx950).
+ * fsrgemm -- dense matrix multiplication C = A x B for AMD MI355X (gfx950)
+ * (and, at the end of this file, matrix transposition).
  *
  * The operation is the one the paper states for its Task 2 (task-prompt
  * table in the appendix): given A of M x K and B of K x N, produce the
@@ -174,6 +175,24 @@ const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB,
                                        const uint16_t *A, int64_t lda,
                                        const uint16_t *B, int64_t ldb,
                                        const float *C, int64_t ldc);
+
+/*
+ * Matrix transposition, the paper's Task 8 (task-prompt table: a rows x cols matrix of 32-bit floating point
+ * numbers becomes a cols x rows one, all matrices row-major), the memory-bound counterpart of the product:
+ *   T[j][i] = A[i][j]:  A[i][j] at A[i*lda + j] (lda >= cols),  T[j][i] at T[j*ldt + i] (ldt >= rows).
+ * Values are moved as 32-bit words, so every bit pattern arrives unchanged.  A and T must not overlap (the
+ * operation is out of place); padding of T (columns rows..ldt-1) is never written.  rows == 0 or cols == 0:
+ * nothing is launched.  Pointers need only 4-byte alignment.  Conventions otherwise as for the products.
+ */
+int transpose_f32(int64_t rows, int64_t cols,
+                  const float *A, int64_t lda,
+                  float *T, int64_t ldt,
+                  void *stream);
+
+/* Name of the kernel variant transpose_f32 would launch (rules as for the queries above; "none" for an empty matrix). */
+const char *fsrgemm_kernel_for_transpose_f32(int64_t rows, int64_t cols,
+                                             const float *A, int64_t lda,
+                                             const float *T, int64_t ldt);
 
 /* Human-readable text for a status code; static storage, never NULL. */
 const char *fsrgemm_status_string(int status);

@@ -290,6 +290,30 @@ const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB, int64_t M, int64_
     return bf16_kernel_name(p.cfg, p.mode, a_lay, b_lay);
 }
 
+static bool transpose_args_ok(int64_t rows, int64_t cols, const float *A, int64_t lda, const float *T, int64_t ldt)
+{
+    const int64_t lim = (int64_t)1 << 31;
+    if (rows < 0 || cols < 0 || rows >= lim || cols >= lim || lda < cols || ldt < rows) return false;
+    if (rows == 0 || cols == 0) return true;
+    return A != nullptr && T != nullptr && ceil_div(rows, 64) * ceil_div(cols, 64) < lim;
+}
+
+const char *fsrgemm_kernel_for_transpose_f32(int64_t rows, int64_t cols, const float *A, int64_t lda, const float *T, int64_t ldt)
+{
+    if (!transpose_args_ok(rows, cols, A, lda, T, ldt)) return nullptr;
+    return rows == 0 || cols == 0 ? "none" : transpose_kernel_name((int)rows, (int)cols);
+}
+
+int transpose_f32(int64_t rows, int64_t cols, const float *A, int64_t lda, float *T, int64_t ldt, void *stream)
+{
+    if (!transpose_args_ok(rows, cols, A, lda, T, ldt)) return FSRGEMM_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0) return FSRGEMM_OK;
+    const int rc = device_ok();
+    if (rc != FSRGEMM_OK) return rc;
+    const hipError_t e = launch_transpose_f32(A, lda, T, ldt, (int)rows, (int)cols, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+}
+
 const char *fsrgemm_status_string(int status)
 {
     switch (status) {

@@ -100,4 +100,8 @@ hipError_t launch_bf16(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &
 const char *bf16_main_kernel_name(int a_lay, int b_lay);
 hipError_t launch_bf16_main(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 
+// fp32 transposition (transpose.hip)
+const char *transpose_kernel_name(int rows, int cols);
+hipError_t launch_transpose_f32(const float *A, int64_t lda, float *T, int64_t ldt, int rows, int cols, hipStream_t s);
+
 }  // namespace fsrgemm

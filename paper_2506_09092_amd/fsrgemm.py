@@ -13,7 +13,8 @@ import os
 __all__ = [
     "load", "library_path", "gemm_f32", "gemm_f32_ex", "gemm_bf16", "fsrgemm_kernel_for_f32",
     "fsrgemm_kernel_for_f32_ex", "fsrgemm_kernel_for_bf16", "gemm_bf16_ex", "fsrgemm_kernel_for_bf16_ex",
-    "gemm_f32_ws", "gemm_f32_workspace_bytes", "gemm_bf16_ws", "gemm_bf16_workspace_bytes",
+    "gemm_f32_ws", "gemm_f32_workspace_bytes", "gemm_bf16_ws", "gemm_bf16_workspace_bytes", "transpose_f32",
+    "fsrgemm_kernel_for_transpose_f32",
     "fsrgemm_status_string", "fsrgemm_version", "check", "FsrGemmError", "EXPORTS",
     "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
 ]
@@ -40,6 +41,8 @@ EXPORTS = {
     "fsrgemm_kernel_for_f32_ex": (ctypes.c_char_p, [ctypes.c_int, ctypes.c_int] + _QUERY),
     "fsrgemm_kernel_for_bf16": (ctypes.c_char_p, _QUERY),
     "fsrgemm_kernel_for_bf16_ex": (ctypes.c_char_p, [ctypes.c_int, ctypes.c_int] + _QUERY),
+    "transpose_f32": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _i64, _vp]),
+    "fsrgemm_kernel_for_transpose_f32": (ctypes.c_char_p, [_i64, _i64, _vp, _i64, _vp, _i64]),
     "fsrgemm_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "fsrgemm_version": (ctypes.c_int, []),
 }
@@ -138,6 +141,15 @@ def fsrgemm_kernel_for_bf16(M, N, K, A, lda, B, ldb, C, ldc):
 
 def fsrgemm_kernel_for_bf16_ex(transA, transB, M, N, K, A, lda, B, ldb, C, ldc):
     r = load().fsrgemm_kernel_for_bf16_ex(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc)
+    return None if r is None else r.decode()
+
+
+def transpose_f32(rows, cols, A, lda, T, ldt, stream=0) -> int:
+    return load().transpose_f32(rows, cols, _ptr(A), lda, _ptr(T), ldt, _ptr(stream) or None)
+
+
+def fsrgemm_kernel_for_transpose_f32(rows, cols, A, lda, T, ldt):
+    r = load().fsrgemm_kernel_for_transpose_f32(rows, cols, _ptr(A), lda, _ptr(T), ldt)
     return None if r is None else r.decode()
 
 

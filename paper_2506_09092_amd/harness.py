@@ -156,6 +156,26 @@ def run_bf16_ex(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, l
     return outs[0]
 
 
+def run_transpose(lib, A: np.ndarray, lda=None, ldt=None, offset=0, repeat=1):
+    """T = transpose of A (rows x cols float32) through transpose_f32 with padded, canaried buffers.
+    Returns the cols x rows result; checks that nothing outside it was written."""
+    rows, cols = A.shape
+    lda, ldt = lda or max(cols, 1), ldt or max(rows, 1)
+    a = _dev(inputs.embed(A, lda, np.float32(np.nan), offset))
+    t_host = np.full(offset + cols * ldt + 3, SENTINEL, dtype=np.float32)
+    outs = []
+    for _ in range(repeat):
+        t = _dev(t_host)
+        st = lib.transpose_f32(rows, cols, a.data_ptr() + 4 * offset, lda, t.data_ptr() + 4 * offset, ldt,
+                               torch.cuda.current_stream().cuda_stream)
+        lib.check(st)
+        torch.cuda.synchronize()
+        outs.append(_unpack(t.cpu().numpy(), cols, rows, ldt, offset))
+    for o in outs[1:]:
+        assert np.array_equal(o.view(np.uint32), outs[0].view(np.uint32)), "run-to-run results differ"
+    return outs[0]
+
+
 def _unpack(flat: np.ndarray, M: int, N: int, ldc: int, offset: int) -> np.ndarray:
     """Checks that everything outside the M x N block still holds the sentinel; returns the block."""
     assert np.all(flat[:offset] == SENTINEL), "wrote before C"

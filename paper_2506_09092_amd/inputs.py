@@ -89,6 +89,15 @@ def normal(seed: int, matrix_id: int, rows: int, cols: int) -> np.ndarray:
     return out
 
 
+def any_bits_f32(seed: int, matrix_id: int, rows: int, cols: int) -> np.ndarray:
+    """float32 whose 32 bits are the top half of the raw draw: every bit pattern can occur (NaNs with
+    payloads, infinities, denormals, both zeros).  For operations that only move data."""
+    out = np.empty((rows, cols), dtype=np.uint32)
+    for r0, r1 in _row_chunks(rows, cols):
+        out[r0:r1] = (raw_bits(seed, matrix_id, rows, cols, 0, r0, r1) >> np.uint64(32)).astype(np.uint32)
+    return out.view(np.float32)
+
+
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """Round to bfloat16 (nearest, ties to even) and return the uint16 bit patterns.
 

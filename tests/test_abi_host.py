@@ -142,6 +142,22 @@ def test_workspace_query_and_argument_checks():
     assert lib.gemm_f32_ws(0, 0, 0, 8, 4096, None, 4096, P, 8, None, 8, None, 0, 0) == lib.FSRGEMM_OK
 
 
+def test_transpose_argument_checks():
+    f, bad = lib.transpose_f32, lib.FSRGEMM_ERR_INVALID_ARG
+    assert f(-1, 4, P, 4, P, 4, 0) == bad and f(4, -1, P, 4, P, 4, 0) == bad
+    assert f(4, 8, P, 7, P, 4, 0) == bad and f(4, 8, P, 8, P, 3, 0) == bad        # lda < cols, ldt < rows
+    assert f(4, 8, None, 8, P, 4, 0) == bad and f(4, 8, P, 8, None, 4, 0) == bad
+    assert f(2 ** 31, 1, P, 1, P, 2 ** 31, 0) == bad
+    assert f(0, 8, None, 8, None, 0, 0) == lib.FSRGEMM_OK and f(4, 0, None, 0, None, 4, 0) == lib.FSRGEMM_OK
+    # <tile rows, tile columns, bounds-checked>: wide tiles from 128 columns on, checks only below 64 rows or columns
+    q = lib.fsrgemm_kernel_for_transpose_f32
+    assert q(4096, 4096, P, 4096, P, 4096) == "transpose_f32_kernel<64, 128, false>"
+    assert q(64, 128, P, 128, P, 64) == "transpose_f32_kernel<64, 128, false>"
+    assert q(5000, 127, P, 127, P, 5000) == "transpose_f32_kernel<64, 64, false>"
+    assert q(63, 4096, P, 4096, P, 63) == q(4096, 63, P, 63, P, 4096) == "transpose_f32_kernel<64, 64, true>"
+    assert q(0, 8, None, 8, None, 0) == "none" and q(4, 8, P, 7, P, 4) is None and q(4, 8, None, 8, P, 4) is None
+
+
 def test_build_refuses_spills_in_hand_scheduled_kernels():
     # the build parses the compiler's resource-usage remarks for the kernels that issue loads from
     # inline assembly; any spill (or missing remarks) must stop it

@@ -13,7 +13,8 @@ import pytest
 import oracle
 from paper_2506_09092_amd import inputs
 
-from paper_2506_09092_amd.harness import run_bf16, run_bf16_ex, run_bf16_ws, run_f32, run_f32_ex, run_f32_ws
+from paper_2506_09092_amd.harness import (run_bf16, run_bf16_ex, run_bf16_ws, run_f32, run_f32_ex, run_f32_ws,
+                                          run_transpose)
 
 pytestmark = pytest.mark.gpu
 TOL_F32 = 1e-5
@@ -489,3 +490,45 @@ def test_f32_paper_task2_shape(gpu):
     ref, S = oracle.gemm(A[rows], B)
     assert oracle.componentwise_error(got[rows], ref, S) <= TOL_F32
     assert oracle.freivalds_residual(A, B, got) <= TOL_F32
+
+
+# ---- transposition (the paper's Task 8): data movement, so every case is bit for bit ----
+
+def _check_transpose(gpu, A, **kw):
+    got = run_transpose(gpu, A, **kw)
+    assert np.array_equal(got.view(np.uint32), oracle.transpose(A).view(np.uint32))
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (1, 5000), (5000, 1), (63, 5), (64, 64), (65, 64), (64, 127), (100, 300),
+                                   (257, 255), (1000, 1000), (4097, 17), (17, 4097), (1023, 2049),
+                                   (64, 128), (64, 129), (70, 128), (129, 255), (200, 64), (63, 128), (3000, 127)])
+def test_transpose_shapes(gpu, shape):
+    rows, cols = shape
+    say("transpose %dx%d" % shape)
+    A = inputs.any_bits_f32(10, 1, rows, cols)          # every bit pattern: NaN payloads, infinities, denormals, -0
+    _check_transpose(gpu, A, repeat=2)
+    _check_transpose(gpu, A, lda=cols + 3, ldt=rows + 5, offset=1, repeat=2)        # padded, 4-byte aligned only
+    _check_transpose(gpu, A, lda=cols + (-cols) % 4 + 4, ldt=rows + (-rows) % 4)    # 16-byte aligned rows
+
+
+@pytest.mark.parametrize("n", [1 << 10, 1 << 11, 1 << 12, 1 << 13, 1 << 14])
+def test_transpose_paper_sizes(gpu, n):
+    # the paper's five Task-8 sizes, full comparison with the oracle
+    say("transpose %d^2 (paper size)" % n)
+    A = inputs.uniform_pm1(10, 2, n, n)
+    _check_transpose(gpu, A)
+
+
+def test_transpose_twice_is_the_identity(gpu):
+    A = inputs.any_bits_f32(10, 3, 777, 1234)
+    T = run_transpose(gpu, A)
+    assert np.array_equal(run_transpose(gpu, T).view(np.uint32), A.view(np.uint32))
+
+
+def test_transpose_empty(gpu):
+    import torch
+    t = torch.full((8,), 3.0, device="cuda")
+    gpu.check(gpu.transpose_f32(0, 5, None, 5, t, 0, 0))
+    gpu.check(gpu.transpose_f32(5, 0, None, 0, t, 5, 0))
+    torch.cuda.synchronize()
+    assert bool((t == 3.0).all())
