@@ -28,9 +28,13 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense MFMA peaks
 # profiles/gemm_f32_4096_bf16_8192_hbm_traffic.txt (scaled by a 1 GiB copy).  Each entry is tied to the
 # kernel sources it was measured on: once those change the figure is stale and the bench reports null.
 TRAFFIC = {
-    "f32_4096": {"bytes": 867974364, "sources": {"gemm_f32.hip": "d127afe349029bcd", "common.hpp": "60c60539401198d6"}},
-    "bf16_8192": {"bytes": 2109138032, "sources": {"gemm_bf16_main.hip": "d05c369947fc0d3a", "common.hpp": "60c60539401198d6"}},
+    "f32_4096": {"bytes": 866402533, "sources": {"gemm_f32.hip": "d127afe349029bcd", "common.hpp": "80f1879992596133"}},
+    "bf16_8192": {"bytes": 2111549247, "sources": {"gemm_bf16_main.hip": "68602cd09b71b81d", "common.hpp": "80f1879992596133"}},
 }
+# the same for the transposes (profiles/transpose_f32_paper_sizes.txt), by N
+_T8_SOURCES = {"transpose.hip": "0a882ffb3d2b7377", "common.hpp": "80f1879992596133"}
+TRAFFIC.update({"transpose_%d" % n: {"bytes": b, "sources": _T8_SOURCES}
+                for n, b in ((1024, 8433502), (2048, 33598846), (4096, 134260222), (8192, 536905727), (16384, 2147491840))})
 
 
 def measured_traffic(name):
@@ -277,7 +281,8 @@ def transpose_sizes(lib, torch, launches=9):
         byts = 8.0 * n * n
         out.append({"n": n, "ms": ms, "launches_per_timing": reps,
                     "roofline": {"bound": "hbm", "kernel": lib.fsrgemm_kernel_for_transpose_f32(n, n, a, n, t, n),
-                                 "achieved": byts / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s", "frac": byts / (ms * 1e-3) / 8e12}})
+                                 "achieved": byts / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s", "frac": byts / (ms * 1e-3) / 8e12,
+                                 "traffic": measured_traffic("transpose_%d" % n)}})
         del a, t
     return out
 
