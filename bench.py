@@ -130,7 +130,33 @@ def report(w, t, lib):
     )
 
 
-def paper_task2_sizes(lib, torch, launches=5):
+def steady_ms(torch, fn, samples=7, warm_ms=20.0, min_ms=0.5):
+    """Median time of one call of fn (a launch on the current stream) in ms, at steady clocks: fn first runs for
+    about warm_ms, then each of `samples` timings covers a run of calls that lasts about min_ms (at least one
+    call), so that neither the idle-clock ramp nor the gap between launches is part of the figure.  The calls
+    reuse their operands: problems that fit the caches are timed with warm caches."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    fn()
+    fn()
+    e1.record()
+    torch.cuda.synchronize()
+    one = max(e0.elapsed_time(e1) / 2, 1e-3)
+    for _ in range(int(min(512, warm_ms / one))):
+        fn()
+    reps = int(max(1, min(256, min_ms / one)))
+    times = []
+    for _ in range(samples):
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) / reps)
+    return sorted(times)[samples // 2]
+
+
+def paper_task2_sizes(lib, torch):
     """Latency of the paper's own Task 2 shapes (appendix input-size table): A (size, 4096), B (4096, 2048), fp32,
     size = 2^10 .. 2^18.  Profiler leg only; values are random normal (correctness of these shapes is a GPU test)."""
     out = []
@@ -141,23 +167,14 @@ def paper_task2_sizes(lib, torch, launches=5):
         M = 1 << e
         a = torch.randn(M, K, device="cuda")
         c = torch.empty(M, N, device="cuda")
-        for _ in range(2):
-            lib.check(lib.gemm_f32(M, N, K, a, K, b, N, c, N, stream))
-        torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
-        for e0, e1 in evs:
-            e0.record()
-            lib.check(lib.gemm_f32(M, N, K, a, K, b, N, c, N, stream))
-            e1.record()
-        torch.cuda.synchronize()
-        ms = sorted(x.elapsed_time(y) for x, y in evs)[launches // 2]
+        ms = steady_ms(torch, lambda: lib.check(lib.gemm_f32(M, N, K, a, K, b, N, c, N, stream)))
         out.append({"size": M, "kernel": lib.fsrgemm_kernel_for_f32(M, N, K, a, K, b, N, c, N), "ms": ms,
                     "tflops": 2.0 * M * N * K / (ms * 1e-3) / 1e12})
         del a, c
     return out
 
 
-def transposed_storage_4096(lib, torch, launches=7):
+def transposed_storage_4096(lib, torch):
     """fp32 4096^3 with A, B or both handed over in transposed storage (gemm_f32_ex): median launch time of each
     of the four storage pairs on the same random operands.  Profiler leg only; parity of these paths is a GPU test."""
     n = 4096
@@ -165,22 +182,13 @@ def transposed_storage_4096(lib, torch, launches=7):
     stream = torch.cuda.current_stream().cuda_stream
     out = []
     for ta, tb in ((0, 0), (0, 1), (1, 0), (1, 1)):
-        for _ in range(2):
-            lib.check(lib.gemm_f32_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream))
-        torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
-        for e0, e1 in evs:
-            e0.record()
-            lib.check(lib.gemm_f32_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream))
-            e1.record()
-        torch.cuda.synchronize()
-        ms = sorted(x.elapsed_time(y) for x, y in evs)[launches // 2]
+        ms = steady_ms(torch, lambda: lib.check(lib.gemm_f32_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream)))
         out.append({"transA": ta, "transB": tb, "kernel": lib.fsrgemm_kernel_for_f32_ex(ta, tb, n, n, n, a, n, b, n, c, n),
                     "ms": ms, "tflops": 2.0 * n ** 3 / (ms * 1e-3) / 1e12})
     return out
 
 
-def storage_orders_bf16_8192(lib, torch, launches=15):
+def storage_orders_bf16_8192(lib, torch):
     """bf16 8192^3 in the four storage pairs of gemm_bf16_ex: (0, 1) is the headline kernel's pair, the others
     take the general kernel.  Median launch time on random operands; parity of these paths is a GPU test."""
     import math
@@ -192,22 +200,13 @@ def storage_orders_bf16_8192(lib, torch, launches=15):
     stream = torch.cuda.current_stream().cuda_stream
     out = []
     for ta, tb in ((0, 1), (0, 0), (1, 1), (1, 0)):
-        for _ in range(8):
-            lib.check(lib.gemm_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream))
-        torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
-        for e0, e1 in evs:
-            e0.record()
-            lib.check(lib.gemm_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream))
-            e1.record()
-        torch.cuda.synchronize()
-        ms = sorted(x.elapsed_time(y) for x, y in evs)[launches // 2]
+        ms = steady_ms(torch, lambda: lib.check(lib.gemm_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream)))
         out.append({"transA": ta, "transB": tb, "kernel": lib.fsrgemm_kernel_for_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n),
                     "ms": ms, "tflops": 2.0 * n ** 3 / (ms * 1e-3) / 1e12})
     return out
 
 
-def split_k(lib, torch, kind, launches=9):
+def split_k(lib, torch, kind):
     """Shapes with few output tiles and a long K (row or column vector times matrix, a few rows against a large
     weight matrix, small squares of long dot products): the plain entry point against the workspace one with the
     workspace the library asks for.  These are HBM-bound: bytes = the operands and the result once, against the
@@ -219,16 +218,7 @@ def split_k(lib, torch, kind, launches=9):
     out = []
 
     def median_ms(fn):
-        for _ in range(3):
-            fn()
-        torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
-        for e0, e1 in evs:
-            e0.record()
-            fn()
-            e1.record()
-        torch.cuda.synchronize()
-        return sorted(x.elapsed_time(y) for x, y in evs)[launches // 2]
+        return steady_ms(torch, fn)
 
     shapes = (((1, 4096, 4096), (4096, 1, 4096), (1, 16384, 16384), (8, 8192, 8192), (64, 64, 4097), (256, 256, 65536),
                (512, 512, 16384)) if kind == "f32" else
@@ -255,35 +245,38 @@ def split_k(lib, torch, kind, launches=9):
     return out
 
 
-def transpose_sizes(lib, torch, launches=9):
-    """The paper's Task 8 (matrix transposition) on its five sizes N x N, N = 2^10 .. 2^14: median time per launch
-    and the HBM roofline (every element read once and written once against 8 TB/s).  The two smallest sizes are
-    timed as 16 launches in a row, since one of them is shorter than the gap between launches; they (and partly
-    4096^2) stay in the chip's caches between launches.  Parity is a GPU test."""
+def transpose_sizes(lib, torch):
+    """The paper's Task 8 (matrix transposition) on its five sizes N x N, N = 2^10 .. 2^14: time per launch and
+    the HBM roofline (every element read once and written once against 8 TB/s).  The smaller sizes stay in the
+    chip's caches between launches (up to 4096^2 at least partly).  Parity is a GPU test."""
     stream = torch.cuda.current_stream().cuda_stream
     out = []
     for e in (10, 11, 12, 13, 14):
         n = 1 << e
-        reps = 16 if n <= 2048 else 1
         a = torch.randn(n, n, device="cuda")
         t = torch.empty(n, n, device="cuda")
-        for _ in range(3):
-            lib.check(lib.transpose_f32(n, n, a, n, t, n, stream))
-        torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
-        for e0, e1 in evs:
-            e0.record()
-            for _ in range(reps):
-                lib.check(lib.transpose_f32(n, n, a, n, t, n, stream))
-            e1.record()
-        torch.cuda.synchronize()
-        ms = sorted(x.elapsed_time(y) for x, y in evs)[launches // 2] / reps
+        ms = steady_ms(torch, lambda: lib.check(lib.transpose_f32(n, n, a, n, t, n, stream)))
         byts = 8.0 * n * n
-        out.append({"n": n, "ms": ms, "launches_per_timing": reps,
+        out.append({"n": n, "ms": ms,
                     "roofline": {"bound": "hbm", "kernel": lib.fsrgemm_kernel_for_transpose_f32(n, n, a, n, t, n),
                                  "achieved": byts / (ms * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s", "frac": byts / (ms * 1e-3) / 8e12,
                                  "traffic": measured_traffic("transpose_%d" % n)}})
         del a, t
+    return out
+
+
+def selection_loop(lib, torch):
+    """The selection loop (Algorithm 1 over tile configurations, validator = the CPU oracle) on three problems:
+    where it starts (the dispatcher's choice), which candidates it visited, what it ends on, and the two timed
+    against each other.  The loop's code and its oracle-backed validator live in fsr_search.py / tests/."""
+    from paper_2506_09092_amd.fsr_search import Problem
+    from tests import tune_dispatch
+
+    out = []
+    for p in (Problem("f32", 0, 0, 3072, 3072, 3072), Problem("f32", 0, 0, 768, 768, 768), Problem("bf16", 0, 1, 512, 512, 16384)):
+        rows, rep = tune_dispatch.tune(lib, torch, p, 0.04, lambda msg: None)
+        rep["new_table_rows"] = [r.strip() for r in rows]
+        out.append(rep)
     return out
 
 
@@ -349,7 +342,7 @@ def main():
         del w
         torch.cuda.empty_cache()
 
-    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = None
+    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = None
     if not args.headline_only:
         task2 = paper_task2_sizes(lib, torch)
         layouts = transposed_storage_4096(lib, torch)
@@ -357,6 +350,9 @@ def main():
         skinny = split_k(lib, torch, "f32")
         skinny_bf16 = split_k(lib, torch, "bf16")
         task8 = transpose_sizes(lib, torch)
+        if not args.no_validate:
+            log("selection loop on three problems")
+            selection = selection_loop(lib, torch)
     torch.cuda.empty_cache()
 
     if args.copy_calibration:
@@ -385,6 +381,7 @@ def main():
         "split_k_f32": skinny,
         "split_k_bf16": skinny_bf16,
         "paper_task8_transpose": task8,
+        "selection_loop": selection,
         "paper_context": "paper reports only speedups over hand-written CUDA for the group holding Task 2: 5.95-68.3x (RTX 3090 Ti), 6.06-60.0x (GTX 1660 SUPER)",
     }
     print(json.dumps(out), flush=True)

@@ -150,6 +150,54 @@ int gemm_bf16_ws(int transA, int transB,
                  void *stream);
 
 /*
+ * The products with the configuration chosen by the caller instead of the dispatcher: the candidates of a
+ * selection loop shaped like the paper's Algorithm 1 (generate candidates, drop those that fail to build or to
+ * validate, keep the one with the least measured time), with tile configurations and K slices in the place of
+ * generated kernels.
+ *   tile: fp32  0 = 256 x 128, 1 = 128 x 128, 2 = 64 x 64 output tile per workgroup (fsrgemm_tile_count_f32() = 3);
+ *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64
+ *               (fsrgemm_tile_count_bf16() = 4).
+ *   k_slices: 1 = K in one piece; 2..64 = split along K as gemm_f32_ws does, which needs a workspace of
+ *         k_slices * M * N * 4 bytes (4-byte aligned, at most 16 MiB) and k_slices <= ceil(K / 16) (fp32) or
+ *         ceil(K / 64) (bf16).
+ * A candidate that cannot run this problem is FSRGEMM_ERR_INVALID_ARG and launches nothing: a tile or slice
+ * count out of range, a split without a fitting workspace, bf16 tile 0 with a split or where its kernel's
+ * conditions fail (M, N >= 256, K a multiple of 64, 16-byte aligned operands with leading dimensions that are
+ * multiples of 8 and below 2^25; M or N a multiple of 8 for an operand contiguous along it).  Every other
+ * candidate takes any shape and alignment.  All other arguments as for gemm_f32_ws / gemm_bf16_ws.
+ */
+int gemm_f32_cfg(int tile, int k_slices, int transA, int transB,
+                 int64_t M, int64_t N, int64_t K,
+                 const float *A, int64_t lda,
+                 const float *B, int64_t ldb,
+                 float *C, int64_t ldc,
+                 void *workspace, int64_t workspace_bytes,
+                 void *stream);
+int gemm_bf16_cfg(int tile, int k_slices, int transA, int transB,
+                  int64_t M, int64_t N, int64_t K,
+                  const uint16_t *A, int64_t lda,
+                  const uint16_t *B, int64_t ldb,
+                  float *C, int64_t ldc,
+                  void *workspace, int64_t workspace_bytes,
+                  void *stream);
+int fsrgemm_tile_count_f32(void);
+int fsrgemm_tile_count_bf16(void);
+
+/*
+ * What the dispatcher would choose for this problem, in the terms of the *_cfg calls: the starting point of a
+ * selection run.  with_workspace != 0: the choice of a *_ws call whose workspace is big enough.  A and B are
+ * looked at for their alignment only (no device access).  The answer comes from the rules built into the
+ * library, or from its table of earlier selection results when the problem (precision, storage orders, M, N,
+ * K) has a row there.  Returns FSRGEMM_OK and sets *tile, *k_slices, or FSRGEMM_ERR_INVALID_ARG.
+ */
+int fsrgemm_plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                     const float *A, int64_t lda, const float *B, int64_t ldb,
+                     int with_workspace, int *tile, int *k_slices);
+int fsrgemm_plan_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                      const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                      int with_workspace, int *tile, int *k_slices);
+
+/*
  * Name of the kernel variant the dispatcher would launch for this problem
  * (same argument checks as the gemm calls; launches nothing, touches no
  * device memory).  Returns a pointer to static storage, or NULL when the

@@ -11,8 +11,9 @@ using namespace fsrgemm;
 namespace {
 
 struct Plan {
-    int cfg;
-    int mode;
+    int cfg;        // tile configuration (F32Config / Bf16Config)
+    int mode;       // load mode, follows from the tile, the shape and the alignment
+    int slices;     // K slices of a call that brings a workspace; 1 = one piece
 };
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -32,39 +33,130 @@ int check_args(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, int6
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// The largest tile whose grid still fills the chip (256 compute units, two or more workgroups each for the
-// smaller tiles); the load mode follows from alignment and divisibility.  Grids beyond 2^31 - 1 workgroups are
-// rejected.
-int plan_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb, Plan *p)
+// Configurations that the selection loop found faster than the rules below, by exact problem: the incumbent
+// (k_best) of the paper's Algorithm 1 with tile configurations and K slices as the candidates.  A row with
+// ws == 0 serves calls without a workspace (its slices are 1), a row with ws == 1 calls that bring one.
+struct Tuned {
+    int kind;       // 0 = fp32, 1 = bf16
+    int transA, transB;
+    int M, N, K;
+    int ws;
+    int tile, slices;
+};
+constexpr Tuned kTuned[] = {
+#include "tuned_table.inc"
+    {-1, 0, 0, 0, 0, 0, 0, 0, 0}};
+
+const Tuned *find_tuned(int kind, int transA, int transB, int64_t M, int64_t N, int64_t K, bool ws)
 {
-    int bm, bn;
-    if (ceil_div(M, 256) * ceil_div(N, 128) >= 384) p->cfg = kF32_256x128, bm = 256, bn = 128;
-    else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kF32_128x128, bm = 128, bn = 128;
-    else p->cfg = kF32_64x64, bm = 64, bn = 64;
-    if (ceil_div(M, bm) * ceil_div(N, bn) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
+    for (const Tuned &t : kTuned)
+        if (t.kind == kind && t.M == M && t.N == N && t.K == K && t.transA == (transA != 0) && t.transB == (transB != 0) &&
+            t.ws == (int)ws)
+            return &t;
+    return nullptr;
+}
+
+constexpr int kF32TileM[kF32ConfigCount] = {256, 128, 64}, kF32TileN[kF32ConfigCount] = {128, 128, 64};
+constexpr int kBf16Tile[kBf16ConfigCount] = {256, 256, 128, 64};
+constexpr int kMaxSlices = 64;
+constexpr int64_t kMaxWorkspace = (int64_t)16 << 20;
+
+// Split-K rule: problems with few 64 x 64 output tiles and a long K are cut into K slices so that about 1024
+// workgroups stream the operands.  A slice keeps at least 256 k when the tiles alone leave half the compute
+// units idle, 1024 k when they would fill them once or twice; at most 64 slices, partial products within
+// 16 MiB.  Depends on the shape only, so the order of summation, and with it the result, is the same on every
+// call.  k_tile = 16 for fp32, 64 for bf16.  1 = do not split.
+int splitk_slices(int64_t M, int64_t N, int64_t K, int k_tile)
+{
+    const int64_t tiles = ceil_div(M, 64) * ceil_div(N, 64), nk = ceil_div(K, k_tile);
+    if (M == 0 || N == 0 || tiles > 512) return 1;
+    int64_t s = 1024 / tiles;
+    const int64_t longest = nk / ((tiles <= 128 ? 256 : 1024) / k_tile);
+    if (s > longest) s = longest;
+    if (s > kMaxSlices) s = kMaxSlices;
+    const int64_t cap = kMaxWorkspace / (M * N * 4);
+    if (s > cap) s = cap;
+    return s < 2 ? 1 : (int)s;
+}
+
+// Load mode of an fp32 tile configuration for this problem.  Unchecked loads and stores need whole K-tiles and a
+// matrix at least one tile wide and high (a ragged last tile is shifted back into the matrix).  Grids beyond
+// 2^31 - 1 workgroups are rejected.
+int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+             int *mode)
+{
+    const int bm = kF32TileM[cfg], bn = kF32TileN[cfg];
+    if (ceil_div(M, bm) * ceil_div(N, bn) * slices >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
     const bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
-    // unchecked loads and stores need whole K-tiles and a matrix at least one tile wide and high (a ragged last
-    // tile is shifted back into the matrix)
-    p->mode = !vec ? kScalar : (M >= bm && N >= bn && K % 16 == 0 && K > 0) ? kFast : kVecPred;
+    *mode = !vec ? kScalar : (M >= bm && N >= bn && K % 16 == 0 && K > 0) ? kFast : kVecPred;
+    return FSRGEMM_OK;
+}
+
+// Tile rule for fp32: the configuration with the least modelled time.  A compute unit works through its share
+// of the output tiles at a rate that depends on the tile only, so a launch takes ceil(tiles / 256) tile times
+// (256 compute units; a last round with few tiles costs a whole one), and never less than the time of one
+// workgroup running alone.  Times per tile and k step, in units of 0.1 ns, measured on square problems with
+// each configuration forced: 256 x 128: 1167, 128 x 128: 610, 64 x 64: 169 with four workgroups per compute
+// unit, 221 alone.  K cancels.  Equal costs go to the larger tile.
+int tile_rule_f32(int64_t M, int64_t N)
+{
+    constexpr int64_t kTileTime[kF32ConfigCount] = {1167, 610, 169}, kAlone[kF32ConfigCount] = {1167, 610, 221};
+    int best = 0;
+    int64_t best_cost = 0;
+    for (int c = 0; c < kF32ConfigCount; ++c) {
+        const int64_t rounds = ceil_div(ceil_div(M, kF32TileM[c]) * ceil_div(N, kF32TileN[c]), 256);
+        int64_t cost = rounds * kTileTime[c];
+        if (cost < kAlone[c]) cost = kAlone[c];
+        if (c == 0 || cost < best_cost) best = c, best_cost = cost;
+    }
+    return best;
+}
+
+// `split`: the call brings a workspace.
+int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+             int64_t ldb, bool split, Plan *p)
+{
+    const Tuned *t = find_tuned(0, transA, transB, M, N, K, split);
+    p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 16) : 1;
+    if (!t && p->slices == 1) t = find_tuned(0, transA, transB, M, N, K, false);
+    p->cfg = t ? t->tile : p->slices > 1 ? kF32_64x64 : tile_rule_f32(M, N);
+    return mode_f32(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
+}
+
+// The direct-to-LDS kernel needs unchecked 256 x 256 x 64 tiles, 32-bit lane offsets and, for an operand that
+// is contiguous along m (n), M (N) a multiple of 8: a shifted last tile must still start 16-byte aligned.
+bool main_kernel_fits(int a_lay, int b_lay, int64_t M, int64_t N, int mode, int64_t lda, int64_t ldb)
+{
+    return mode == kFast && lda < (1 << 25) && ldb < (1 << 25) && (a_lay == kKContig || M % 8 == 0) &&
+           (b_lay == kKContig || N % 8 == 0);
+}
+
+int mode_bf16(int cfg, int slices, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B,
+              int64_t ldb, int *mode)
+{
+    const int b = kBf16Tile[cfg];
+    if (ceil_div(M, b) * ceil_div(N, b) * slices >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
+    const bool vec = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0;
+    *mode = !vec ? kScalar : (M >= b && N >= b && K % 64 == 0 && K > 0) ? kFast : kVecPred;
     return FSRGEMM_OK;
 }
 
 int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B,
-              int64_t ldb, Plan *p)
+              int64_t ldb, bool split, Plan *p)
 {
-    int b;
-    if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) p->cfg = kBf16_256x256, b = 256;
-    else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kBf16_128x128, b = 128;
-    else p->cfg = kBf16_64x64, b = 64;
-    if (ceil_div(M, b) * ceil_div(N, b) >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
-    const bool vec = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0;
-    p->mode = !vec ? kScalar : (M >= b && N >= b && K % 64 == 0 && K > 0) ? kFast : kVecPred;
-    // the direct-to-LDS kernel needs unchecked 256 x 256 x 64 tiles, 32-bit lane offsets and, for an operand
-    // that is contiguous along m (n), M (N) a multiple of 8: a shifted last tile must still start 16-byte aligned
-    if (b == 256 && p->mode == kFast && lda < (1 << 25) && ldb < (1 << 25) && (a_lay == kKContig || M % 8 == 0) &&
-        (b_lay == kKContig || N % 8 == 0))
-        p->cfg = kBf16_Main;
-    return FSRGEMM_OK;
+    const int transA = a_lay == kMnContig, transB = b_lay == kKContig;
+    const Tuned *t = find_tuned(1, transA, transB, M, N, K, split);
+    p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 64) : 1;
+    if (!t && p->slices == 1) t = find_tuned(1, transA, transB, M, N, K, false);
+    if (t) p->cfg = t->tile;
+    else if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) p->cfg = kBf16_Main;
+    else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kBf16_128x128;
+    else p->cfg = kBf16_64x64;
+    int rc = mode_bf16(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
+    // where the direct-to-LDS kernel does not fit (alignment, ragged K, a split), the general kernel of its tile runs
+    if (rc == FSRGEMM_OK && p->cfg == kBf16_Main && (p->slices > 1 || !main_kernel_fits(a_lay, b_lay, M, N, p->mode, lda, ldb)))
+        p->cfg = kBf16_256x256;
+    return rc;
 }
 
 // gfx950 check for the current device, cached per device ordinal (racing first calls just repeat the query).
@@ -104,24 +196,6 @@ GemmArgs pack(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const
     return a;
 }
 
-// Split-K plan: problems with few 64 x 64 output tiles and a long K are cut into K slices so that about 1024
-// workgroups stream the operands.  A slice keeps at least 256 k when the tiles alone leave half the compute
-// units idle, 1024 k when they would fill them once or twice; at most 64 slices, partial products within
-// 16 MiB.  Depends on the shape only, so the order of summation, and with it the result, is the same on every
-// call.  k_tile = 16 for fp32, 64 for bf16.  1 = do not split.
-int splitk_slices(int64_t M, int64_t N, int64_t K, int k_tile)
-{
-    const int64_t tiles = ceil_div(M, 64) * ceil_div(N, 64), nk = ceil_div(K, k_tile);
-    if (M == 0 || N == 0 || tiles > 512) return 1;
-    int64_t s = 1024 / tiles;
-    const int64_t longest = nk / ((tiles <= 128 ? 256 : 1024) / k_tile);
-    if (s > longest) s = longest;
-    if (s > 64) s = 64;
-    const int64_t cap = ((int64_t)16 << 20) / (M * N * 4);
-    if (s > cap) s = cap;
-    return s < 2 ? 1 : (int)s;
-}
-
 }  // namespace
 
 namespace fsrgemm {
@@ -141,6 +215,65 @@ hipError_t ensure_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_
 
 }  // namespace fsrgemm
 
+namespace {
+
+// Launch of a planned product: in one piece into C, or (p.slices > 1) as partial products into the workspace
+// followed by the kernel that adds the slices in slice order.
+int run_f32(const Plan &p, int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+            const float *B, int64_t ldb, float *C, int64_t ldc, float *ws, hipStream_t s)
+{
+    const int rc = device_ok();
+    if (rc != FSRGEMM_OK) return rc;
+    const bool split = p.slices > 1;
+    GemmArgs a = pack(M, N, K, A, lda, B, ldb, split ? ws : C, split ? N : ldc);
+    a.k_slices = p.slices;
+    a.slice_stride = split ? M * N : 0;
+    hipError_t e = launch_f32(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, a, s);
+    if (e == hipSuccess && split) e = launch_splitk_reduce(ws, p.slices, M * N, C, (int)M, (int)N, ldc, s);
+    return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+}
+
+int run_bf16(const Plan &p, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
+             const uint16_t *B, int64_t ldb, float *C, int64_t ldc, float *ws, hipStream_t s)
+{
+    const bool split = p.slices > 1;
+    if (split && p.cfg == kBf16_Main) return FSRGEMM_ERR_INVALID_ARG;     // the planners never pair the two
+    const int rc = device_ok();
+    if (rc != FSRGEMM_OK) return rc;
+    GemmArgs a = pack(M, N, K, A, lda, B, ldb, split ? ws : C, split ? N : ldc);
+    a.k_slices = p.slices;
+    a.slice_stride = split ? M * N : 0;
+    hipError_t e = launch_bf16(p.cfg, p.mode, a_lay, b_lay, a, s);
+    if (e == hipSuccess && split) e = launch_splitk_reduce(ws, p.slices, M * N, C, (int)M, (int)N, ldc, s);
+    return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+}
+
+bool extents_ok(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t lim = (int64_t)1 << 31;
+    return M >= 0 && N >= 0 && K >= 0 && M < lim && N < lim && K < lim;
+}
+
+// a workspace a split can use: big enough and aligned for a float
+bool workspace_fits(const void *workspace, int64_t bytes, int slices, int64_t M, int64_t N)
+{
+    return workspace != nullptr && bytes >= (int64_t)slices * M * N * 4 && (reinterpret_cast<uintptr_t>(workspace) & 3u) == 0;
+}
+
+// Checks of a forced configuration that do not depend on the precision: the slice count, and for a split the
+// workspace and a K range that gives every slice at least one K-tile.
+bool forced_ok(int tile, int tile_count, int slices, int64_t M, int64_t N, int64_t K, int k_tile, const void *workspace,
+               int64_t workspace_bytes)
+{
+    if (tile < 0 || tile >= tile_count || slices < 1 || slices > kMaxSlices) return false;
+    if (workspace_bytes < 0 || (workspace_bytes > 0 && workspace == nullptr)) return false;
+    if (slices == 1) return true;
+    return M > 0 && N > 0 && slices <= ceil_div(K, k_tile) && (int64_t)slices * M * N * 4 <= kMaxWorkspace &&
+           workspace_fits(workspace, workspace_bytes, slices, M, N);
+}
+
+}  // namespace
+
 extern "C" {
 
 int gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb, float *C,
@@ -152,18 +285,61 @@ int gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const
 int gemm_f32_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
                 int64_t ldb, float *C, int64_t ldc, void *stream)
 {
+    return gemm_f32_ws(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, nullptr, 0, stream);
+}
+
+int64_t gemm_f32_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K)
+{
+    if (!extents_ok(M, N, K)) return 0;
+    const Tuned *t = find_tuned(0, transA, transB, M, N, K, true);
+    const int slices = t ? t->slices : splitk_slices(M, N, K, 16);
+    return slices > 1 ? (int64_t)slices * M * N * 4 : 0;
+}
+
+int gemm_f32_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                int64_t ldb, float *C, int64_t ldc, void *workspace, int64_t workspace_bytes, void *stream)
+{
     int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
     if (rc != FSRGEMM_OK) return rc;
+    if (workspace_bytes < 0 || (workspace_bytes > 0 && workspace == nullptr)) return FSRGEMM_ERR_INVALID_ARG;
     Plan p;
-    rc = plan_f32(M, N, K, A, lda, B, ldb, &p);
+    rc = plan_f32(transA, transB, M, N, K, A, lda, B, ldb, workspace != nullptr, &p);
+    if (rc == FSRGEMM_OK && p.slices > 1 && !workspace_fits(workspace, workspace_bytes, p.slices, M, N))
+        rc = plan_f32(transA, transB, M, N, K, A, lda, B, ldb, false, &p);
     if (rc != FSRGEMM_OK) return rc;
     if (M == 0 || N == 0) return FSRGEMM_OK;
-    rc = device_ok();
-    if (rc != FSRGEMM_OK) return rc;
-    const hipError_t e = launch_f32(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig,
-                                    pack(M, N, K, A, lda, B, ldb, C, ldc), static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+    return run_f32(p, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, static_cast<float *>(workspace),
+                   static_cast<hipStream_t>(stream));
 }
+
+int gemm_f32_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A,
+                 int64_t lda, const float *B, int64_t ldb, float *C, int64_t ldc, void *workspace, int64_t workspace_bytes,
+                 void *stream)
+{
+    int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
+    if (rc != FSRGEMM_OK) return rc;
+    if (!forced_ok(tile, kF32ConfigCount, k_slices, M, N, K, 16, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
+    Plan p = {tile, 0, k_slices};
+    rc = mode_f32(tile, k_slices, M, N, K, A, lda, B, ldb, &p.mode);
+    if (rc != FSRGEMM_OK) return rc;
+    if (M == 0 || N == 0) return FSRGEMM_OK;
+    return run_f32(p, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, static_cast<float *>(workspace),
+                   static_cast<hipStream_t>(stream));
+}
+
+int fsrgemm_plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                     int64_t ldb, int with_workspace, int *tile, int *k_slices)
+{
+    if (!extents_ok(M, N, K) || tile == nullptr || k_slices == nullptr) return FSRGEMM_ERR_INVALID_ARG;
+    Plan p;
+    const int rc = plan_f32(transA, transB, M, N, K, A, lda, B, ldb, with_workspace != 0, &p);
+    if (rc != FSRGEMM_OK) return rc;
+    *tile = p.cfg;
+    *k_slices = p.slices;
+    return FSRGEMM_OK;
+}
+
+int fsrgemm_tile_count_f32(void) { return kF32ConfigCount; }
 
 int gemm_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
               float *C, int64_t ldc, void *stream)
@@ -174,60 +350,14 @@ int gemm_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, c
 int gemm_bf16_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
                  const uint16_t *B, int64_t ldb, float *C, int64_t ldc, void *stream)
 {
-    int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
-    if (rc != FSRGEMM_OK) return rc;
-    const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
-    Plan p;
-    rc = plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, &p);
-    if (rc != FSRGEMM_OK) return rc;
-    if (M == 0 || N == 0) return FSRGEMM_OK;
-    rc = device_ok();
-    if (rc != FSRGEMM_OK) return rc;
-    const hipError_t e = launch_bf16(p.cfg, p.mode, a_lay, b_lay, pack(M, N, K, A, lda, B, ldb, C, ldc),
-                                     static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
-}
-
-int64_t gemm_f32_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K)
-{
-    (void)transA;
-    (void)transB;
-    if (M < 0 || N < 0 || K < 0 || M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31)) return 0;
-    const int slices = splitk_slices(M, N, K, 16);
-    return slices > 1 ? (int64_t)slices * M * N * 4 : 0;
-}
-
-int gemm_f32_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
-                int64_t ldb, float *C, int64_t ldc, void *workspace, int64_t workspace_bytes, void *stream)
-{
-    int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
-    if (rc != FSRGEMM_OK) return rc;
-    if (workspace_bytes < 0 || (workspace_bytes > 0 && workspace == nullptr)) return FSRGEMM_ERR_INVALID_ARG;
-    const int slices = splitk_slices(M, N, K, 16);
-    const int64_t need = (int64_t)slices * M * N * 4;
-    if (slices < 2 || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 3u))
-        return gemm_f32_ex(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, stream);
-    Plan p;
-    rc = plan_f32(M, N, K, A, lda, B, ldb, &p);
-    if (rc != FSRGEMM_OK) return rc;
-    rc = device_ok();
-    if (rc != FSRGEMM_OK) return rc;
-    float *ws = static_cast<float *>(workspace);
-    GemmArgs a = pack(M, N, K, A, lda, B, ldb, ws, N);
-    a.k_slices = slices;
-    a.slice_stride = M * N;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = launch_f32(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, a, s);
-    if (e == hipSuccess) e = launch_splitk_reduce(ws, slices, M * N, C, (int)M, (int)N, ldc, s);
-    return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+    return gemm_bf16_ws(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, nullptr, 0, stream);
 }
 
 int64_t gemm_bf16_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K)
 {
-    (void)transA;
-    (void)transB;
-    if (M < 0 || N < 0 || K < 0 || M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31)) return 0;
-    const int slices = splitk_slices(M, N, K, 64);
+    if (!extents_ok(M, N, K)) return 0;
+    const Tuned *t = find_tuned(1, transA, transB, M, N, K, true);
+    const int slices = t ? t->slices : splitk_slices(M, N, K, 64);
     return slices > 1 ? (int64_t)slices * M * N * 4 : 0;
 }
 
@@ -238,26 +368,49 @@ int gemm_bf16_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const 
     int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
     if (rc != FSRGEMM_OK) return rc;
     if (workspace_bytes < 0 || (workspace_bytes > 0 && workspace == nullptr)) return FSRGEMM_ERR_INVALID_ARG;
-    const int slices = splitk_slices(M, N, K, 64);
-    const int64_t need = (int64_t)slices * M * N * 4;
-    if (slices < 2 || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 3u))
-        return gemm_bf16_ex(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, stream);
     const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
     Plan p;
-    rc = plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, &p);
+    rc = plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, workspace != nullptr, &p);
+    if (rc == FSRGEMM_OK && p.slices > 1 && !workspace_fits(workspace, workspace_bytes, p.slices, M, N))
+        rc = plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, false, &p);
     if (rc != FSRGEMM_OK) return rc;
-    if (p.cfg == kBf16_Main) return FSRGEMM_ERR_LAUNCH;      // cannot happen: a split problem has at most 512 small tiles
-    rc = device_ok();
-    if (rc != FSRGEMM_OK) return rc;
-    float *ws = static_cast<float *>(workspace);
-    GemmArgs a = pack(M, N, K, A, lda, B, ldb, ws, N);
-    a.k_slices = slices;
-    a.slice_stride = M * N;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = launch_bf16(p.cfg, p.mode, a_lay, b_lay, a, s);
-    if (e == hipSuccess) e = launch_splitk_reduce(ws, slices, M * N, C, (int)M, (int)N, ldc, s);
-    return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+    if (M == 0 || N == 0) return FSRGEMM_OK;
+    return run_bf16(p, a_lay, b_lay, M, N, K, A, lda, B, ldb, C, ldc, static_cast<float *>(workspace),
+                    static_cast<hipStream_t>(stream));
 }
+
+int gemm_bf16_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A,
+                  int64_t lda, const uint16_t *B, int64_t ldb, float *C, int64_t ldc, void *workspace,
+                  int64_t workspace_bytes, void *stream)
+{
+    int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
+    if (rc != FSRGEMM_OK) return rc;
+    if (!forced_ok(tile, kBf16ConfigCount, k_slices, M, N, K, 64, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
+    const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
+    Plan p = {tile, 0, k_slices};
+    rc = mode_bf16(tile, k_slices, M, N, K, A, lda, B, ldb, &p.mode);
+    if (rc != FSRGEMM_OK) return rc;
+    // a forced direct-to-LDS kernel is an invalid candidate where it does not fit; nothing else is substituted
+    if (tile == kBf16_Main && (k_slices > 1 || !main_kernel_fits(a_lay, b_lay, M, N, p.mode, lda, ldb))) return FSRGEMM_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return FSRGEMM_OK;
+    return run_bf16(p, a_lay, b_lay, M, N, K, A, lda, B, ldb, C, ldc, static_cast<float *>(workspace),
+                    static_cast<hipStream_t>(stream));
+}
+
+int fsrgemm_plan_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
+                      const uint16_t *B, int64_t ldb, int with_workspace, int *tile, int *k_slices)
+{
+    if (!extents_ok(M, N, K) || tile == nullptr || k_slices == nullptr) return FSRGEMM_ERR_INVALID_ARG;
+    Plan p;
+    const int rc = plan_bf16(transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, A, lda, B, ldb,
+                             with_workspace != 0, &p);
+    if (rc != FSRGEMM_OK) return rc;
+    *tile = p.cfg;
+    *k_slices = p.slices;
+    return FSRGEMM_OK;
+}
+
+int fsrgemm_tile_count_bf16(void) { return kBf16ConfigCount; }
 
 const char *fsrgemm_kernel_for_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
                                    int64_t ldb, const float *C, int64_t ldc)
@@ -270,7 +423,7 @@ const char *fsrgemm_kernel_for_f32_ex(int transA, int transB, int64_t M, int64_t
 {
     Plan p;
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
-    if (plan_f32(M, N, K, A, lda, B, ldb, &p) != FSRGEMM_OK) return nullptr;
+    if (plan_f32(transA, transB, M, N, K, A, lda, B, ldb, false, &p) != FSRGEMM_OK) return nullptr;
     return f32_kernel_name(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig);
 }
 
@@ -286,7 +439,7 @@ const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB, int64_t M, int64_
     Plan p;
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
     const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
-    if (plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, &p) != FSRGEMM_OK) return nullptr;
+    if (plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, false, &p) != FSRGEMM_OK) return nullptr;
     return bf16_kernel_name(p.cfg, p.mode, a_lay, b_lay);
 }
 

@@ -14,7 +14,8 @@ __all__ = [
     "load", "library_path", "gemm_f32", "gemm_f32_ex", "gemm_bf16", "fsrgemm_kernel_for_f32",
     "fsrgemm_kernel_for_f32_ex", "fsrgemm_kernel_for_bf16", "gemm_bf16_ex", "fsrgemm_kernel_for_bf16_ex",
     "gemm_f32_ws", "gemm_f32_workspace_bytes", "gemm_bf16_ws", "gemm_bf16_workspace_bytes", "transpose_f32",
-    "fsrgemm_kernel_for_transpose_f32",
+    "fsrgemm_kernel_for_transpose_f32", "gemm_f32_cfg", "gemm_bf16_cfg", "fsrgemm_tile_count_f32",
+    "fsrgemm_tile_count_bf16", "fsrgemm_plan_f32", "fsrgemm_plan_bf16",
     "fsrgemm_status_string", "fsrgemm_version", "check", "FsrGemmError", "EXPORTS",
     "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
 ]
@@ -43,6 +44,14 @@ EXPORTS = {
     "fsrgemm_kernel_for_bf16_ex": (ctypes.c_char_p, [ctypes.c_int, ctypes.c_int] + _QUERY),
     "transpose_f32": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _i64, _vp]),
     "fsrgemm_kernel_for_transpose_f32": (ctypes.c_char_p, [_i64, _i64, _vp, _i64, _vp, _i64]),
+    "gemm_f32_cfg": (ctypes.c_int, [ctypes.c_int] * 4 + _GEMM[:-1] + [_vp, _i64, _vp]),
+    "gemm_bf16_cfg": (ctypes.c_int, [ctypes.c_int] * 4 + _GEMM[:-1] + [_vp, _i64, _vp]),
+    "fsrgemm_tile_count_f32": (ctypes.c_int, []),
+    "fsrgemm_tile_count_bf16": (ctypes.c_int, []),
+    "fsrgemm_plan_f32": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, ctypes.c_int,
+                                        ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
+    "fsrgemm_plan_bf16": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, ctypes.c_int,
+                                         ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
     "fsrgemm_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "fsrgemm_version": (ctypes.c_int, []),
 }
@@ -122,6 +131,40 @@ def gemm_bf16(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
 def gemm_bf16_ex(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
     return load().gemm_bf16_ex(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
                                _ptr(stream) or None)
+
+
+def gemm_f32_cfg(tile, k_slices, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, workspace=0, workspace_bytes=0, stream=0) -> int:
+    return load().gemm_f32_cfg(int(tile), int(k_slices), int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb,
+                               _ptr(C), ldc, _ptr(workspace), int(workspace_bytes), _ptr(stream) or None)
+
+
+def gemm_bf16_cfg(tile, k_slices, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, workspace=0, workspace_bytes=0, stream=0) -> int:
+    return load().gemm_bf16_cfg(int(tile), int(k_slices), int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb,
+                                _ptr(C), ldc, _ptr(workspace), int(workspace_bytes), _ptr(stream) or None)
+
+
+def fsrgemm_tile_count_f32() -> int:
+    return int(load().fsrgemm_tile_count_f32())
+
+
+def fsrgemm_tile_count_bf16() -> int:
+    return int(load().fsrgemm_tile_count_bf16())
+
+
+def _plan(fn, transA, transB, M, N, K, A, lda, B, ldb, with_workspace):
+    tile, slices = ctypes.c_int(-1), ctypes.c_int(-1)
+    rc = fn(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, int(bool(with_workspace)), ctypes.byref(tile),
+            ctypes.byref(slices))
+    return None if rc != FSRGEMM_OK else (tile.value, slices.value)
+
+
+def fsrgemm_plan_f32(transA, transB, M, N, K, A, lda, B, ldb, with_workspace=False):
+    """(tile, k_slices) the dispatcher would take, or None for invalid arguments."""
+    return _plan(load().fsrgemm_plan_f32, transA, transB, M, N, K, A, lda, B, ldb, with_workspace)
+
+
+def fsrgemm_plan_bf16(transA, transB, M, N, K, A, lda, B, ldb, with_workspace=False):
+    return _plan(load().fsrgemm_plan_bf16, transA, transB, M, N, K, A, lda, B, ldb, with_workspace)
 
 
 def fsrgemm_kernel_for_f32(M, N, K, A, lda, B, ldb, C, ldc):

@@ -63,7 +63,7 @@ def run_f32_ex(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, ld
     return outs[0]
 
 
-def _run_ws(lib, kind: str, transA, transB, A, B, workspace_bytes, lda, ldb, ldc, offset, repeat):
+def _run_ws(lib, kind: str, transA, transB, A, B, workspace_bytes, lda, ldb, ldc, offset, repeat, forced=None):
     M, K = A.shape
     N = B.shape[1]
     sa = np.ascontiguousarray(A.T) if transA else A
@@ -73,6 +73,10 @@ def _run_ws(lib, kind: str, transA, transB, A, B, workspace_bytes, lda, ldb, ldc
     gemm, query = (lib.gemm_f32_ws, lib.gemm_f32_workspace_bytes) if kind == "f32" else (lib.gemm_bf16_ws, lib.gemm_bf16_workspace_bytes)
     a = _dev(inputs.embed(sa, lda, fill, offset))
     b = _dev(inputs.embed(sb, ldb, fill, offset))
+    if forced is not None:          # (tile, k_slices): the *_cfg entry point with exactly the workspace its split needs
+        gemm_cfg = lib.gemm_f32_cfg if kind == "f32" else lib.gemm_bf16_cfg
+        gemm = lambda *args: gemm_cfg(forced[0], forced[1], *args)
+        workspace_bytes = forced[1] * M * N * 4 if forced[1] > 1 else 0
     if workspace_bytes is None:
         workspace_bytes = query(transA, transB, M, N, K)
     guard = 64
@@ -105,6 +109,14 @@ def run_bf16_ws(lib, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, w
                 ldc=None, offset=0, repeat=1):
     """The same through gemm_bf16_ws; operands are bf16 bit patterns."""
     return _run_ws(lib, "bf16", transA, transB, A, B, workspace_bytes, lda, ldb, ldc, offset, repeat)
+
+
+def run_cfg(lib, kind: str, tile: int, k_slices: int, transA: bool, transB: bool, A: np.ndarray, B: np.ndarray, lda=None,
+            ldb=None, ldc=None, offset=0, repeat=1):
+    """C = A.B through gemm_f32_cfg / gemm_bf16_cfg (kind "f32" / "bf16") with the given tile and K slices, and a
+    canaried workspace of exactly the size the split needs.  Raises FsrGemmError when the library rejects the
+    candidate."""
+    return _run_ws(lib, kind, transA, transB, A, B, None, lda, ldb, ldc, offset, repeat, forced=(tile, k_slices))
 
 
 def run_bf16(lib, A: np.ndarray, Bt: np.ndarray, lda=None, ldb=None, ldc=None, offset=0, repeat=1):

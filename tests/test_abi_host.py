@@ -68,7 +68,9 @@ def test_dispatch_query_names_variants():
     # 1 vectors + predicated edges, 2 scalar; row-major A is contiguous along k (0), row-major B along n (1)
     assert fast == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
     assert ragged == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>" and unaligned == "gemm_f32_kernel<1, 1, 4, 2, 0, 1>"
-    assert q(4097, 4097, 129, P, 132, P, 4100, P, 4097) == "gemm_f32_kernel<4, 2, 2, 1, 0, 1>"
+    assert q(4090, 4090, 129, P, 132, P, 4092, P, 4090) == "gemm_f32_kernel<4, 2, 2, 1, 0, 1>"
+    # one row and column beyond 4096 would cost the large tiles a whole further round: the small tile takes it
+    assert q(4097, 4097, 129, P, 132, P, 4100, P, 4097) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"
     assert q(64, 64, 0, P, 4, P, 64, P, 64) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"                    # K = 0 never takes the unchecked mode
     assert q(4, 4, 4, P, 3, P, 4, P, 4) is None
     qb = lib.fsrgemm_kernel_for_bf16
@@ -125,7 +127,7 @@ def test_workspace_query_and_argument_checks():
     wb = lib.gemm_f32_workspace_bytes
     assert wb(0, 0, 1, 4096, 4096) == 16 * 1 * 4096 * 4             # 64 tiles, 256 K-tiles -> 16 slices of 16 K-tiles
     assert wb(0, 0, 1, 16384, 16384) == 4 * 16384 * 4               # 256 tiles -> 4 slices
-    assert wb(0, 0, 1024, 1024, 1024) == 0                           # 256 tiles, but only 64 K-tiles
+    assert wb(0, 0, 1280, 1280, 1280) == 0                           # 400 tiles, but only 80 K-tiles
     assert wb(0, 0, 256, 256, 65536) == 64 * 256 * 256 * 4           # 16 tiles -> the cap of 64 slices: 16 MiB
     assert wb(1, 1, 256, 256, 65536) == wb(0, 0, 256, 256, 65536)
     assert wb(0, 0, 64, 64, 256) == 0                                 # K too short to cut
@@ -140,6 +142,65 @@ def test_workspace_query_and_argument_checks():
     assert lib.gemm_f32_ws(0, 0, 1, 8, 4096, P, 4096, P, 8, P, 8, P, -1, 0) == bad
     assert lib.gemm_f32_ws(0, 0, 1, 8, 4096, P, 4095, P, 8, P, 8, P, 1 << 20, 0) == bad    # lda < K
     assert lib.gemm_f32_ws(0, 0, 0, 8, 4096, None, 4096, P, 8, None, 8, None, 0, 0) == lib.FSRGEMM_OK
+
+
+def test_f32_tile_rule_follows_the_round_model():
+    # fewest rounds of 256 tiles, weighted by the tile's time; sizes where the three configurations win in turn
+    pf = lambda n: lib.fsrgemm_plan_f32(0, 0, n, n, n, P, n, P, n)[0]
+    assert [pf(n) for n in (1024, 2048, 3072, 4096, 6144, 8192)] == [2, 1, 2, 0, 1, 0]
+    assert lib.fsrgemm_plan_f32(0, 0, 10, 100000, 64, P, 64, P, 100000)[0] == 2          # a sliver: small tiles waste least
+    assert lib.fsrgemm_plan_f32(0, 0, 262144, 2048, 4096, P, 4096, P, 2048)[0] == 0        # the paper's largest Task-2 size
+
+
+def test_forced_configurations_and_plan_queries():
+    bad, ok = lib.FSRGEMM_ERR_INVALID_ARG, lib.FSRGEMM_OK
+    assert lib.fsrgemm_tile_count_f32() == 3 and lib.fsrgemm_tile_count_bf16() == 4
+    f = lambda tile, s, ws=None, wsb=0, M=64, N=64, K=4096: lib.gemm_f32_cfg(tile, s, 0, 0, M, N, K, P, K, P, N, P, N, ws, wsb, 0)
+    assert f(-1, 1) == bad and f(3, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
+    assert f(2, 4) == bad and f(2, 4, P, 4 * 64 * 64 * 4 - 1) == bad            # a split without / with too small a workspace
+    assert f(2, 4, P + 2, 1 << 20) == bad                                      # misaligned workspace
+    assert f(2, 2, P, 1 << 30, M=2048, N=2048) == bad                          # partial products beyond 16 MiB
+    assert f(2, 8, P, 1 << 24, K=100) == bad                                   # more slices than K-tiles (7)
+    assert f(2, 1, None, 8) == bad and f(2, 1, P, -1) == bad
+    assert lib.gemm_f32_cfg(1, 1, 0, 0, 0, 64, 64, None, 64, P, 64, None, 64, None, 0, 0) == ok      # empty: nothing to launch
+    assert lib.gemm_f32_cfg(1, 1, 0, 0, 8, 8, 8, P, 7, P, 8, P, 8, None, 0, 0) == bad                # the usual argument checks
+    g = lambda tile, s, M, N, K, a=P, lda=None, ws=None, wsb=0: lib.gemm_bf16_cfg(tile, s, 0, 1, M, N, K, a, lda or K, P, K, P, N, ws, wsb, 0)
+    # the direct-to-LDS candidate is rejected where its kernel's conditions fail, never replaced
+    assert g(0, 1, 255, 512, 512) == bad and g(0, 1, 512, 512, 96) == bad and g(0, 1, 512, 512, 512, a=P + 2) == bad
+    assert g(0, 1, 512, 512, 512, lda=516) == bad and g(0, 2, 512, 512, 512, ws=P, wsb=1 << 24) == bad
+    assert g(4, 1, 512, 512, 512) == bad and g(1, 1, 0, 512, 512) == ok
+    # plan queries: the rules, in the terms of the forced calls
+    pf, pb = lib.fsrgemm_plan_f32, lib.fsrgemm_plan_bf16
+    assert pf(0, 0, 4096, 4096, 4096, P, 4096, P, 4096) == (0, 1) and pf(0, 0, 200, 200, 200, P, 200, P, 200) == (2, 1)
+    assert pf(0, 0, 64, 64, 1 << 20, P, 1 << 20, P, 64, True)[0] == 2 and pf(0, 0, 64, 64, 1 << 20, P, 1 << 20, P, 64, True)[1] > 1
+    assert pf(0, 0, 64, 64, 1 << 20, P, 1 << 20, P, 64, False) == (2, 1)
+    assert pb(0, 1, 8192, 8192, 8192, P, 8192, P, 8192) == (0, 1)
+    assert pb(0, 1, 8192, 8192, 8200, P, 8200, P, 8200) == (1, 1)              # ragged K: the general kernel of that tile
+    assert pb(0, 1, 300, 300, 300, P, 300, P, 300) == (3, 1)
+    assert pf(0, 0, -1, 1, 1, P, 1, P, 1) is None
+    # the workspace query and the plan agree
+    for M, N, K in ((1, 4096, 4096), (64, 64, 4097), (256, 256, 65536), (4096, 4096, 4096)):
+        s = pf(0, 0, M, N, K, P, K, P, N, True)[1]
+        assert lib.gemm_f32_workspace_bytes(0, 0, M, N, K) == (s * M * N * 4 if s > 1 else 0)
+
+
+def test_tuned_table_rows_are_well_formed():
+    # every row of the table names a candidate the forced entry point would accept for its problem
+    import os
+    import re
+
+    path = os.path.join(os.path.dirname(lib.library_path()), "csrc", "tuned_table.inc")
+    rows = [tuple(int(x) for x in m.groups()) for m in re.finditer(r"^\s*\{(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+)\},", open(path).read(), re.M)]
+    assert len(set(r[:7] for r in rows)) == len(rows)                  # one row per (problem, workspace) pair
+    for kind, ta, tb, M, N, K, ws, tile, slices in rows:
+        assert kind in (0, 1) and ta in (0, 1) and tb in (0, 1) and ws in (0, 1) and M > 0 and N > 0 and K > 0
+        assert 0 <= tile < (lib.fsrgemm_tile_count_bf16() if kind else lib.fsrgemm_tile_count_f32())
+        assert 1 <= slices <= 64 and (ws == 1 or slices == 1) and slices * M * N * 4 <= (16 << 20 if slices > 1 else 1 << 62)
+        plan = (lib.fsrgemm_plan_bf16 if kind else lib.fsrgemm_plan_f32)(ta, tb, M, N, K, P, M if ta else K, P, K if tb else N, bool(ws))
+        assert plan == (tile, slices), (plan, (tile, slices))
+        if ws:
+            q = lib.gemm_bf16_workspace_bytes if kind else lib.gemm_f32_workspace_bytes
+            assert q(ta, tb, M, N, K) == (slices * M * N * 4 if slices > 1 else 0)
 
 
 def test_transpose_argument_checks():

@@ -13,7 +13,7 @@ import pytest
 import oracle
 from paper_2506_09092_amd import inputs
 
-from paper_2506_09092_amd.harness import (run_bf16, run_bf16_ex, run_bf16_ws, run_f32, run_f32_ex, run_f32_ws,
+from paper_2506_09092_amd.harness import (run_bf16, run_bf16_ex, run_bf16_ws, run_cfg, run_f32, run_f32_ex, run_f32_ws,
                                           run_transpose)
 
 pytestmark = pytest.mark.gpu
@@ -103,8 +103,8 @@ def test_f32_transposed_storage_sweep(gpu):
 def test_f32_transposed_storage_tile_configs(gpu, ta, tb):
     # every tile configuration in its unchecked-vector mode, small K included, and integers bit for bit
     for (M, N, K), name in (((2048, 2048, 48), "gemm_f32_kernel<2, 2, 3, 0, %d, %d>"),
-                            ((4096, 3072, 16), "gemm_f32_kernel<4, 2, 2, 0, %d, %d>"),
-                            ((4096, 3072, 112), "gemm_f32_kernel<4, 2, 2, 0, %d, %d>"),
+                            ((4096, 2048, 16), "gemm_f32_kernel<4, 2, 2, 0, %d, %d>"),
+                            ((4096, 2048, 112), "gemm_f32_kernel<4, 2, 2, 0, %d, %d>"),
                             ((1024, 1024, 1024), "gemm_f32_kernel<1, 1, 4, 0, %d, %d>")):
         say("transposed %d%d %dx%dx%d" % (ta, tb, M, N, K))
         lda, ldb = (M if ta else K), (K if tb else N)
@@ -287,8 +287,8 @@ def test_bf16_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
     assert np.array_equal(run_bf16(gpu, Ai, Bi).astype(np.float64), ref)
 
 
-@pytest.mark.parametrize("shape,kernel", [((4000, 3000, 64), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
-                                          ((2050, 2100, 48), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
+@pytest.mark.parametrize("shape,kernel", [((4000, 2040, 64), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+                                          ((2040, 2030, 48), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
                                           ((1000, 1000, 1008), "gemm_f32_kernel<1, 1, 4, 0, 0, 1>"),
                                           ((65, 129, 32), "gemm_f32_kernel<1, 1, 4, 0, 0, 1>")])
 def test_f32_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
@@ -309,9 +309,9 @@ def test_f32_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
 @pytest.mark.parametrize("shape,kernel", [((2048, 2048, 16), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
                                           ((2048, 2048, 32), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
                                           ((2048, 2048, 112), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
-                                          ((4096, 3072, 16), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
-                                          ((4096, 3072, 48), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
-                                          ((4096, 3072, 160), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")])
+                                          ((4096, 2048, 16), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+                                          ((4096, 2048, 48), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+                                          ((4096, 2048, 160), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")])
 def test_f32_tile_configs_small_k(gpu, shape, kernel):
     # prologue, odd/even K-tile tails and the clamped prefetch of the two large tile configurations; full oracle comparison
     M, N, K = shape
@@ -493,6 +493,89 @@ def test_f32_paper_task2_shape(gpu):
 
 
 # ---- transposition (the paper's Task 8): data movement, so every case is bit for bit ----
+
+# ---- forced configurations: every candidate of the selection loop is a correct product ----
+
+@pytest.mark.parametrize("shape,ta,tb", [((300, 520, 1000), 0, 0), ((512, 384, 2048), 0, 0), ((64, 64, 4097), 0, 0),
+                                         ((1, 700, 3000), 0, 0), ((257, 129, 640), 1, 1), ((40, 1000, 512), 0, 1)])
+def test_f32_every_candidate(gpu, shape, ta, tb):
+    M, N, K = shape
+    A, B = inputs.uniform_pm1(12, 1, M, K), inputs.uniform_pm1(12, 2, K, N)
+    ref, S = oracle.gemm(A, B)
+    for tile in range(gpu.fsrgemm_tile_count_f32()):
+        for slices in (1, 2, 5, 16, 64):
+            say("f32 candidate tile %d slices %d on %dx%dx%d %d%d" % (tile, slices, M, N, K, ta, tb))
+            if slices > 1 and (slices > -(-K // 16) or slices * M * N * 4 > 16 << 20):
+                continue
+            got = run_cfg(gpu, "f32", tile, slices, ta, tb, A, B, repeat=2)
+            assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+    # padded, offset operands through a split
+    got = run_cfg(gpu, "f32", 1, 3, ta, tb, A, B, lda=(M if ta else K) + 3, ldb=(K if tb else N) + 5, ldc=N + 7, offset=1)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+
+
+@pytest.mark.parametrize("shape,ta,tb", [((300, 520, 1000), 0, 1), ((512, 512, 2048), 0, 1), ((64, 64, 4160), 0, 1),
+                                         ((16, 1000, 4096), 0, 1), ((264, 256, 640), 1, 0), ((512, 768, 1024), 0, 0)])
+def test_bf16_every_candidate(gpu, shape, ta, tb):
+    M, N, K = shape
+    A, Bt = inputs.bf16_normal_scaled(12, 3, M, K, 1 / math.sqrt(K)), inputs.bf16_normal_scaled(12, 4, N, K, 1 / math.sqrt(K))
+    B = np.ascontiguousarray(Bt.T)
+    ref, S = oracle.gemm(A, B)
+    fits_main = M >= 256 and N >= 256 and K % 64 == 0 and (not ta or M % 8 == 0) and (tb or N % 8 == 0)
+    for tile in range(gpu.fsrgemm_tile_count_bf16()):
+        for slices in (1, 2, 5, 16, 64):
+            say("bf16 candidate tile %d slices %d on %dx%dx%d %d%d" % (tile, slices, M, N, K, ta, tb))
+            if slices > 1 and (slices > -(-K // 64) or slices * M * N * 4 > 16 << 20):
+                continue
+            if tile == 0 and (slices > 1 or not fits_main):
+                with pytest.raises(gpu.FsrGemmError):
+                    run_cfg(gpu, "bf16", tile, slices, ta, tb, A, B)
+                continue
+            got = run_cfg(gpu, "bf16", tile, slices, ta, tb, A, B, repeat=2)
+            assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+
+
+def test_forced_plan_equals_dispatch(gpu):
+    # the dispatcher's own choice, forced, gives the dispatcher's bits (fp32 and bf16, plain and with a workspace)
+    for M, N, K in ((300, 520, 1000), (64, 64, 4097), (1, 4096, 4096)):
+        A, B = inputs.uniform_pm1(12, 5, M, K), inputs.uniform_pm1(12, 6, K, N)
+        tile, slices = gpu.fsrgemm_plan_f32(0, 0, M, N, K, 0x1000, K, 0x1000, N, True)
+        assert np.array_equal(run_cfg(gpu, "f32", tile, slices, 0, 0, A, B).view(np.uint32), run_f32_ws(gpu, 0, 0, A, B).view(np.uint32))
+        tile, slices = gpu.fsrgemm_plan_f32(0, 0, M, N, K, 0x1000, K, 0x1000, N, False)
+        assert slices == 1
+        assert np.array_equal(run_cfg(gpu, "f32", tile, 1, 0, 0, A, B).view(np.uint32), run_f32(gpu, A, B).view(np.uint32))
+    for M, N, K in ((512, 512, 512), (16, 1024, 8192)):
+        A, Bt = inputs.bf16_normal_scaled(12, 7, M, K, 1 / math.sqrt(K)), inputs.bf16_normal_scaled(12, 8, N, K, 1 / math.sqrt(K))
+        B = np.ascontiguousarray(Bt.T)
+        tile, slices = gpu.fsrgemm_plan_bf16(0, 1, M, N, K, 0x1000, K, 0x1000, K, True)
+        assert np.array_equal(run_cfg(gpu, "bf16", tile, slices, 0, 1, A, B).view(np.uint32), run_bf16_ws(gpu, 0, 1, A, B).view(np.uint32))
+
+
+def test_tuned_table_rows_validate(gpu):
+    # every problem with a row in the dispatcher's table, through the public entry point that the row serves
+    import os
+    import re
+
+    path = os.path.join(os.path.dirname(gpu.library_path()), "csrc", "tuned_table.inc")
+    rows = [tuple(int(x) for x in m.groups()) for m in re.finditer(r"^\s*\{(\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+), (\d+)\},", open(path).read(), re.M)]
+    for kind, ta, tb, M, N, K, ws, tile, slices in rows:
+        say("table row %s" % ((kind, ta, tb, M, N, K, ws, tile, slices),))
+        if M * N * K > 1 << 34:
+            continue                                    # larger problems are covered by the full-size tests
+        if kind == 0:
+            A, B = inputs.uniform_pm1(13, 1, M, K), inputs.uniform_pm1(13, 2, K, N)
+            got = run_f32_ws(gpu, ta, tb, A, B, repeat=2) if ws else run_f32_ex(gpu, ta, tb, A, B, repeat=2)
+            tol = TOL_F32
+        else:
+            A = inputs.bf16_normal_scaled(13, 3, M, K, 1 / math.sqrt(K))
+            B = np.ascontiguousarray(inputs.bf16_normal_scaled(13, 4, N, K, 1 / math.sqrt(K)).T)
+            got = run_bf16_ws(gpu, ta, tb, A, B, repeat=2) if ws else run_bf16_ex(gpu, ta, tb, A, B, repeat=2)
+            tol = TOL_BF16
+        rng = np.random.default_rng(13)
+        ii, jj = rng.integers(0, M, 4096), rng.integers(0, N, 4096)
+        ref, S = oracle.gemm_entries(A, B, ii, jj)
+        assert np.all(np.isfinite(got)) and oracle.componentwise_error(got[ii, jj], ref, S) <= tol
+
 
 def _check_transpose(gpu, A, **kw):
     got = run_transpose(gpu, A, **kw)
