@@ -92,7 +92,7 @@ int gemm_f32_ex(int transA, int transB,
  * goes to the workspace and a second kernel adds the slices in slice order, so the result is still the same
  * on every call (it may differ in the last bits from gemm_f32_ex, which sums along K in one piece).
  *   gemm_f32_workspace_bytes: bytes that make the split possible for this shape, 0 when the problem is not
- *     split (the answer depends on M, N, K only; at most 16 MiB).
+ *     split (the answer depends on M, N, K and the storage orders only; at most 16 MiB).
  *   gemm_f32_ws: as gemm_f32_ex; `workspace` is device memory of `workspace_bytes` bytes, 4-byte aligned, not
  *     overlapping A, B or C, owned by the caller and free for reuse once the stream has passed the call.
  *     Its contents on entry are ignored, on exit unspecified.  With a NULL, misaligned or too small workspace
@@ -154,14 +154,16 @@ int gemm_bf16_ws(int transA, int transB,
  * selection loop shaped like the paper's Algorithm 1 (generate candidates, drop those that fail to build or to
  * validate, keep the one with the least measured time), with tile configurations and K slices in the place of
  * generated kernels.
- *   tile: fp32  0 = 256 x 128, 1 = 128 x 128, 2 = 64 x 64 output tile per workgroup (fsrgemm_tile_count_f32() = 3);
+ *   tile: fp32  0 = 256 x 128, 1 = 128 x 128, 2 = 64 x 64 output tile per workgroup, 3 = the streaming kernels for
+ *               M == 1 or N == 1 with K > 0, which use no matrix cores (fsrgemm_tile_count_f32() = 4);
  *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64
  *               (fsrgemm_tile_count_bf16() = 4).
  *   k_slices: 1 = K in one piece; 2..64 = split along K as gemm_f32_ws does, which needs a workspace of
  *         k_slices * M * N * 4 bytes (4-byte aligned, at most 16 MiB) and k_slices <= ceil(K / 16) (fp32) or
  *         ceil(K / 64) (bf16).
  * A candidate that cannot run this problem is FSRGEMM_ERR_INVALID_ARG and launches nothing: a tile or slice
- * count out of range, a split without a fitting workspace, bf16 tile 0 with a split or where its kernel's
+ * count out of range, a split without a fitting workspace, fp32 candidate 3 on a product without a vector,
+ * bf16 tile 0 with a split or where its kernel's
  * conditions fail (M, N >= 256, K a multiple of 64, 16-byte aligned operands with leading dimensions that are
  * multiples of 8 and below 2^25; M or N a multiple of 8 for an operand contiguous along it).  Every other
  * candidate takes any shape and alignment.  All other arguments as for gemm_f32_ws / gemm_bf16_ws.

@@ -85,6 +85,10 @@ int splitk_slices(int64_t M, int64_t N, int64_t K, int k_tile)
 int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
              int *mode)
 {
+    if (cfg == kF32_Vector) {           // the vector kernels look at alignment themselves
+        *mode = 0;
+        return ceil_div(M > N ? M : N, 4) * slices >= ((int64_t)1 << 31) ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_OK;
+    }
     const int bm = kF32TileM[cfg], bn = kF32TileN[cfg];
     if (ceil_div(M, bm) * ceil_div(N, bn) * slices >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
     const bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
@@ -112,14 +116,64 @@ int tile_rule_f32(int64_t M, int64_t N)
     return best;
 }
 
+// How a product with M == 1 or N == 1 maps onto the vector kernels: which operand is the matrix, how it is
+// walked, and the strides of the two vectors.
+struct VecMap {
+    int pattern;
+    VecArgs a;
+};
+VecMap vector_map(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                  int64_t ldb, float *C, int64_t ldc)
+{
+    VecMap v;
+    v.a.K = (int)K;
+    v.a.k_slices = 1;
+    v.a.slice_stride = 0;
+    v.a.xvec = false;
+    if (N == 1) {       // a matrix times a column: y = C's column, x = B's
+        v.pattern = transA ? kVecCols : kVecRows;
+        v.a.mat = A, v.a.ld = lda, v.a.len = (int)M;
+        v.a.x = B, v.a.incx = transB ? 1 : ldb;
+        v.a.y = C, v.a.incy = ldc;
+    } else {            // a row times a matrix: y = C's row, x = A's
+        v.pattern = transB ? kVecRows : kVecCols;
+        v.a.mat = B, v.a.ld = ldb, v.a.len = (int)N;
+        v.a.x = A, v.a.incx = transA ? lda : 1;
+        v.a.y = C, v.a.incy = 1;
+    }
+    return v;
+}
+
+// Workgroups of the vector kernels for an output of `len` elements, and the K slices of a call with a
+// workspace.  The kernels stream well from about 256 workgroups on, and a split costs a second launch, so K is
+// cut only to reach that many, and never finer than 2048 (measured: a 1 x 4096 x 4096 product gains 15 % from
+// two slices, a 1 x 1024 x 1024 one loses 40 % to any split).
+int64_t vector_groups(int pattern, int64_t len) { return pattern == kVecRows ? ceil_div(len, 4) : ceil_div(len, 32); }
+int vector_slices(int pattern, int64_t len, int64_t K)
+{
+    int64_t s = 256 / vector_groups(pattern, len);
+    if (s > K / 2048) s = K / 2048;
+    if (s > kMaxSlices) s = kMaxSlices;
+    return s < 2 ? 1 : (int)s;
+}
+
+bool vector_shape(int64_t M, int64_t N, int64_t K) { return (M == 1 || N == 1) && M > 0 && N > 0 && K > 0; }
+
 // `split`: the call brings a workspace.
 int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
              int64_t ldb, bool split, Plan *p)
 {
     const Tuned *t = find_tuned(0, transA, transB, M, N, K, split);
-    p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 16) : 1;
-    if (!t && p->slices == 1) t = find_tuned(0, transA, transB, M, N, K, false);
-    p->cfg = t ? t->tile : p->slices > 1 ? kF32_64x64 : tile_rule_f32(M, N);
+    const bool vector = vector_shape(M, N, K);
+    if (!t && vector) {
+        const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
+        p->cfg = kF32_Vector;
+        p->slices = split ? vector_slices(v.pattern, v.a.len, K) : 1;
+    } else {
+        p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 16) : 1;
+        if (!t && p->slices == 1) t = find_tuned(0, transA, transB, M, N, K, false);
+        p->cfg = t ? t->tile : p->slices > 1 ? kF32_64x64 : tile_rule_f32(M, N);
+    }
     return mode_f32(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
 }
 
@@ -225,10 +279,17 @@ int run_f32(const Plan &p, int transA, int transB, int64_t M, int64_t N, int64_t
     const int rc = device_ok();
     if (rc != FSRGEMM_OK) return rc;
     const bool split = p.slices > 1;
-    GemmArgs a = pack(M, N, K, A, lda, B, ldb, split ? ws : C, split ? N : ldc);
-    a.k_slices = p.slices;
-    a.slice_stride = split ? M * N : 0;
-    hipError_t e = launch_f32(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, a, s);
+    hipError_t e;
+    if (p.cfg == kF32_Vector) {
+        VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, C, ldc);
+        if (split) v.a.y = ws, v.a.incy = 1, v.a.k_slices = p.slices, v.a.slice_stride = v.a.len;
+        e = launch_gemv_f32(v.pattern, v.a, s);
+    } else {
+        GemmArgs a = pack(M, N, K, A, lda, B, ldb, split ? ws : C, split ? N : ldc);
+        a.k_slices = p.slices;
+        a.slice_stride = split ? M * N : 0;
+        e = launch_f32(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, a, s);
+    }
     if (e == hipSuccess && split) e = launch_splitk_reduce(ws, p.slices, M * N, C, (int)M, (int)N, ldc, s);
     return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
 }
@@ -291,9 +352,9 @@ int gemm_f32_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const f
 int64_t gemm_f32_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K)
 {
     if (!extents_ok(M, N, K)) return 0;
-    const Tuned *t = find_tuned(0, transA, transB, M, N, K, true);
-    const int slices = t ? t->slices : splitk_slices(M, N, K, 16);
-    return slices > 1 ? (int64_t)slices * M * N * 4 : 0;
+    Plan p;
+    if (plan_f32(transA, transB, M, N, K, nullptr, 4, nullptr, 4, true, &p) != FSRGEMM_OK) return 0;
+    return p.slices > 1 ? (int64_t)p.slices * M * N * 4 : 0;
 }
 
 int gemm_f32_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
@@ -318,7 +379,8 @@ int gemm_f32_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int6
 {
     int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
     if (rc != FSRGEMM_OK) return rc;
-    if (!forced_ok(tile, kF32ConfigCount, k_slices, M, N, K, 16, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
+    if (!forced_ok(tile, kF32_Vector + 1, k_slices, M, N, K, 16, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
+    if (tile == kF32_Vector && !vector_shape(M, N, K) && M > 0 && N > 0) return FSRGEMM_ERR_INVALID_ARG;
     Plan p = {tile, 0, k_slices};
     rc = mode_f32(tile, k_slices, M, N, K, A, lda, B, ldb, &p.mode);
     if (rc != FSRGEMM_OK) return rc;
@@ -339,7 +401,7 @@ int fsrgemm_plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, co
     return FSRGEMM_OK;
 }
 
-int fsrgemm_tile_count_f32(void) { return kF32ConfigCount; }
+int fsrgemm_tile_count_f32(void) { return kF32_Vector + 1; }
 
 int gemm_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
               float *C, int64_t ldc, void *stream)
@@ -424,6 +486,10 @@ const char *fsrgemm_kernel_for_f32_ex(int transA, int transB, int64_t M, int64_t
     Plan p;
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
     if (plan_f32(transA, transB, M, N, K, A, lda, B, ldb, false, &p) != FSRGEMM_OK) return nullptr;
+    if (p.cfg == kF32_Vector) {
+        const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
+        return gemv_kernel_name(v.pattern, gemv_takes_vectors(v.a));
+    }
     return f32_kernel_name(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig);
 }
 

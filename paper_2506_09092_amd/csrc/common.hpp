@@ -100,6 +100,27 @@ hipError_t launch_bf16(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &
 const char *bf16_main_kernel_name(int a_lay, int b_lay);
 hipError_t launch_bf16_main(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 
+// fp32 products with M == 1 or N == 1 (gemv_f32.hip): y[i * incy] = sum over k of mat(i, k) * x[k * incx] for
+// i < len, with mat(i, k) at mat[i * ld + k] (kVecRows) or mat[k * ld + i] (kVecCols).  With k_slices > 1 slice s
+// writes its partial y behind y + s * slice_stride.  xvec is filled in by the launcher.
+enum VecPattern { kVecRows = 0, kVecCols = 1 };
+constexpr int kF32_Vector = kF32ConfigCount;        // the candidate number of these kernels, after the tile configurations
+struct VecArgs {
+    const float *mat;
+    int64_t ld;
+    const float *x;
+    int64_t incx;
+    float *y;
+    int64_t incy;
+    int len, K;
+    int k_slices;
+    int64_t slice_stride;
+    bool xvec;
+};
+const char *gemv_kernel_name(int pattern, bool vec);
+bool gemv_takes_vectors(const VecArgs &a);
+hipError_t launch_gemv_f32(int pattern, VecArgs a, hipStream_t s);
+
 // fp32 transposition (transpose.hip)
 const char *transpose_kernel_name(int rows, int cols);
 hipError_t launch_transpose_f32(const float *A, int64_t lda, float *T, int64_t ldt, int rows, int cols, hipStream_t s);

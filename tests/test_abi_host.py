@@ -125,8 +125,10 @@ def test_transposed_storage_arguments(ta, tb):
 
 def test_workspace_query_and_argument_checks():
     wb = lib.gemm_f32_workspace_bytes
-    assert wb(0, 0, 1, 4096, 4096) == 16 * 1 * 4096 * 4             # 64 tiles, 256 K-tiles -> 16 slices of 16 K-tiles
-    assert wb(0, 0, 1, 16384, 16384) == 4 * 16384 * 4               # 256 tiles -> 4 slices
+    assert wb(0, 0, 8, 4096, 4096) == 16 * 8 * 4096 * 4             # 64 tiles, 256 K-tiles -> 16 slices of 16 K-tiles
+    assert wb(0, 0, 8, 16384, 16384) == 4 * 8 * 16384 * 4           # 256 tiles -> 4 slices
+    assert wb(0, 0, 1, 4096, 4096) == 2 * 4096 * 4                  # a row times a matrix: 128 workgroups of 32 columns -> 2 slices
+    assert wb(0, 0, 4096, 1, 4096) == 0                             # a matrix times a column: 1024 workgroups of 4 rows
     assert wb(0, 0, 1280, 1280, 1280) == 0                           # 400 tiles, but only 80 K-tiles
     assert wb(0, 0, 256, 256, 65536) == 64 * 256 * 256 * 4           # 16 tiles -> the cap of 64 slices: 16 MiB
     assert wb(1, 1, 256, 256, 65536) == wb(0, 0, 256, 256, 65536)
@@ -154,9 +156,10 @@ def test_f32_tile_rule_follows_the_round_model():
 
 def test_forced_configurations_and_plan_queries():
     bad, ok = lib.FSRGEMM_ERR_INVALID_ARG, lib.FSRGEMM_OK
-    assert lib.fsrgemm_tile_count_f32() == 3 and lib.fsrgemm_tile_count_bf16() == 4
+    assert lib.fsrgemm_tile_count_f32() == 4 and lib.fsrgemm_tile_count_bf16() == 4
     f = lambda tile, s, ws=None, wsb=0, M=64, N=64, K=4096: lib.gemm_f32_cfg(tile, s, 0, 0, M, N, K, P, K, P, N, P, N, ws, wsb, 0)
-    assert f(-1, 1) == bad and f(3, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
+    assert f(-1, 1) == bad and f(4, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
+    assert f(3, 1) == bad and f(3, 1, K=0, M=1) == bad                          # the vector kernels need M or N = 1 and K > 0
     assert f(2, 4) == bad and f(2, 4, P, 4 * 64 * 64 * 4 - 1) == bad            # a split without / with too small a workspace
     assert f(2, 4, P + 2, 1 << 20) == bad                                      # misaligned workspace
     assert f(2, 2, P, 1 << 30, M=2048, N=2048) == bad                          # partial products beyond 16 MiB
@@ -178,6 +181,19 @@ def test_forced_configurations_and_plan_queries():
     assert pb(0, 1, 8192, 8192, 8200, P, 8200, P, 8200) == (1, 1)              # ragged K: the general kernel of that tile
     assert pb(0, 1, 300, 300, 300, P, 300, P, 300) == (3, 1)
     assert pf(0, 0, -1, 1, 1, P, 1, P, 1) is None
+    # a vector on one side: the streaming kernels (candidate 3), split along K only where the output alone gives few workgroups
+    assert pf(0, 0, 1, 4096, 4096, P, 4096, P, 4096) == (3, 1) and pf(0, 0, 4096, 1, 4096, P, 4096, P, 1) == (3, 1)
+    assert pf(0, 0, 1, 4096, 4096, P, 4096, P, 4096, True) == (3, 2)            # 128 workgroups of 32 columns -> 2 slices
+    assert pf(0, 0, 4096, 1, 4096, P, 4096, P, 1, True) == (3, 1)               # 1024 workgroups of 4 rows already
+    assert pf(0, 0, 1, 1024, 1024, P, 1024, P, 1024, True) == (3, 1)            # too short to pay for a second launch
+    assert pf(0, 0, 1, 1, 1 << 20, P, 1 << 20, P, 1, True) == (3, 64) and pf(0, 0, 1, 4096, 0, P, 1, P, 4096) == (2, 1)
+    qv = lib.fsrgemm_kernel_for_f32_ex
+    assert qv(0, 0, 4096, 1, 4096, P, 4096, P, 1, P, 1) == "gemv_rows_f32_kernel<true>"
+    assert qv(0, 0, 1, 4096, 4096, P, 4096, P, 4096, P, 4096) == "gemv_cols_f32_kernel<true>"
+    assert qv(0, 1, 1, 4096, 4096, P, 4096, P, 4096, P, 4096) == "gemv_rows_f32_kernel<true>"
+    assert qv(1, 0, 4096, 1, 4096, P, 4096, P, 1, P, 1) == "gemv_cols_f32_kernel<true>"
+    assert qv(0, 0, 4096, 1, 4095, P, 4095, P, 1, P, 1) == "gemv_rows_f32_kernel<false>"        # rows not 16-byte aligned
+    assert qv(0, 0, 1, 4096, 4096, P, 4096, P + 4, 4096, P, 4096) == "gemv_cols_f32_kernel<false>"
     # the workspace query and the plan agree
     for M, N, K in ((1, 4096, 4096), (64, 64, 4097), (256, 256, 65536), (4096, 4096, 4096)):
         s = pf(0, 0, M, N, K, P, K, P, N, True)[1]

@@ -146,11 +146,12 @@ def test_f32_workspace_split_k(gpu, shape):
     M, N, K = shape
     need = gpu.gemm_f32_workspace_bytes(0, 0, M, N, K)
     say("split-K %dx%dx%d workspace %d bytes" % (M, N, K, need))
-    assert need > 0 and need % (4 * M * N) == 0 and need <= 16 << 20
+    vector = M == 1 or N == 1               # the streaming kernels: whether they split depends on the storage order
+    assert (need > 0 or vector) and need % (4 * M * N) == 0 and need <= 16 << 20
     A, B = inputs.uniform_pm1(7, 1, M, K), inputs.uniform_pm1(7, 2, K, N)
     ref, S = oracle.gemm(A, B)
     for ta, tb in ((0, 0), (0, 1), (1, 0), (1, 1)):
-        assert gpu.gemm_f32_workspace_bytes(ta, tb, M, N, K) == need
+        assert vector or gpu.gemm_f32_workspace_bytes(ta, tb, M, N, K) == need
         got = run_f32_ws(gpu, ta, tb, A, B, repeat=2)
         assert oracle.componentwise_error(got, ref, S) <= TOL_F32
     pad = 3 if (M + N) % 2 else 4
@@ -158,7 +159,8 @@ def test_f32_workspace_split_k(gpu, shape):
     assert oracle.componentwise_error(got, ref, S) <= TOL_F32
     # a workspace one float short, or none, must leave the call equal to gemm_f32_ex bit for bit
     plain = run_f32_ex(gpu, 0, 0, A, B)
-    assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=need - 4).view(np.uint32), plain.view(np.uint32))
+    if need:
+        assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=need - 4).view(np.uint32), plain.view(np.uint32))
     assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=0).view(np.uint32), plain.view(np.uint32))
 
 
@@ -494,6 +496,46 @@ def test_f32_paper_task2_shape(gpu):
 
 # ---- transposition (the paper's Task 8): data movement, so every case is bit for bit ----
 
+# ---- a vector on one side: the streaming kernels ----
+
+@pytest.mark.parametrize("M,N,K", [(1, 1000, 3000), (1000, 1, 3000), (1, 4096, 4096), (4096, 1, 4096), (1, 1, 100000),
+                                   (1, 33, 7), (31, 1, 1), (1, 5000, 1027), (4100, 1, 2050), (1, 64, 65536)])
+def test_f32_vector_shapes(gpu, M, N, K):
+    A, B = inputs.uniform_pm1(14, 1, M, K), inputs.uniform_pm1(14, 2, K, N)
+    ref, S = oracle.gemm(A, B)
+    for ta, tb in [(0, 0)] + LAYOUTS:
+        say("f32 vector %dx%dx%d storage %d%d" % (M, N, K, ta, tb))
+        assert gpu.fsrgemm_plan_f32(ta, tb, M, N, K, 0x1000, M if ta else K, 0x1000, K if tb else N)[0] == 3
+        got = run_f32_ex(gpu, ta, tb, A, B, repeat=2)                                        # tight: vector loads where rows are aligned
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        lda, ldb = (M if ta else K) + 3, (K if tb else N) + 5
+        got = run_f32_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 2, offset=1, repeat=2)  # padded, 4-byte aligned only
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        got = run_f32_ws(gpu, ta, tb, A, B, repeat=2)                                        # with the workspace the library asks for
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        lda, ldb = (M if ta else K), (K if tb else N)
+        got = run_f32_ws(gpu, ta, tb, A, B, lda=lda + (-lda) % 4 + 4, ldb=ldb + (-ldb) % 4 + 4, ldc=N + 1, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+    Ai, Bi = inputs.small_ints(0, 9, M, K), inputs.small_ints(0, 10, K, N)
+    if K <= 4097:
+        refi, _ = oracle.gemm(Ai, Bi)
+        for ta, tb in [(0, 0)] + LAYOUTS:
+            assert np.array_equal(run_f32_ws(gpu, ta, tb, Ai, Bi).astype(np.float64), refi)
+
+
+def test_f32_vector_every_slice_count(gpu):
+    M, N, K = 1, 700, 3000
+    A, B = inputs.uniform_pm1(14, 3, M, K), inputs.uniform_pm1(14, 4, K, N)
+    ref, S = oracle.gemm(A, B)
+    for ta, tb in [(0, 0)] + LAYOUTS:
+        for slices in (1, 2, 3, 7, 64):
+            say("f32 vector candidate, %d slices, storage %d%d" % (slices, ta, tb))
+            assert oracle.componentwise_error(run_cfg(gpu, "f32", 3, slices, ta, tb, A, B, repeat=2), ref, S) <= TOL_F32
+            assert oracle.componentwise_error(run_cfg(gpu, "f32", 3, slices, ta, tb, B.T.copy(), A.T.copy(), repeat=2), ref.T, S.T) <= TOL_F32
+    with pytest.raises(gpu.FsrGemmError):
+        run_cfg(gpu, "f32", 3, 1, 0, 0, inputs.uniform_pm1(14, 5, 2, 64), inputs.uniform_pm1(14, 6, 64, 2))
+
+
 # ---- forced configurations: every candidate of the selection loop is a correct product ----
 
 @pytest.mark.parametrize("shape,ta,tb", [((300, 520, 1000), 0, 0), ((512, 384, 2048), 0, 0), ((64, 64, 4097), 0, 0),
@@ -502,7 +544,7 @@ def test_f32_every_candidate(gpu, shape, ta, tb):
     M, N, K = shape
     A, B = inputs.uniform_pm1(12, 1, M, K), inputs.uniform_pm1(12, 2, K, N)
     ref, S = oracle.gemm(A, B)
-    for tile in range(gpu.fsrgemm_tile_count_f32()):
+    for tile in range(3 + (M == 1 or N == 1)):          # the three tile configurations, and the vector kernels where they apply
         for slices in (1, 2, 5, 16, 64):
             say("f32 candidate tile %d slices %d on %dx%dx%d %d%d" % (tile, slices, M, N, K, ta, tb))
             if slices > 1 and (slices > -(-K // 16) or slices * M * N * 4 > 16 << 20):
