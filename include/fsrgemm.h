@@ -187,17 +187,20 @@ int fsrgemm_tile_count_bf16(void);
 
 /*
  * What the dispatcher would choose for this problem, in the terms of the *_cfg calls: the starting point of a
- * selection run.  with_workspace != 0: the choice of a *_ws call whose workspace is big enough.  A and B are
- * looked at for their alignment only (no device access).  The answer comes from the rules built into the
- * library, or from its table of earlier selection results when the problem (precision, storage orders, M, N,
- * K) has a row there.  Returns FSRGEMM_OK and sets *tile, *k_slices, or FSRGEMM_ERR_INVALID_ARG.
+ * selection run.  flags: FSRGEMM_PLAN_WORKSPACE = the choice of a *_ws call whose workspace is big enough;
+ * FSRGEMM_PLAN_RULES_ONLY = the choice of the built-in rules alone, without the library's table of earlier
+ * selection results (which otherwise decides for a problem -- precision, storage orders, M, N, K -- that has a
+ * row there).  A and B are looked at for their alignment only (no device access).  Returns FSRGEMM_OK and sets
+ * *tile, *k_slices, or FSRGEMM_ERR_INVALID_ARG.
  */
+#define FSRGEMM_PLAN_WORKSPACE 1
+#define FSRGEMM_PLAN_RULES_ONLY 2
 int fsrgemm_plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
                      const float *A, int64_t lda, const float *B, int64_t ldb,
-                     int with_workspace, int *tile, int *k_slices);
+                     int flags, int *tile, int *k_slices);
 int fsrgemm_plan_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
                       const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
-                      int with_workspace, int *tile, int *k_slices);
+                      int flags, int *tile, int *k_slices);
 
 /*
  * Name of the kernel variant the dispatcher would launch for this problem

@@ -161,9 +161,9 @@ bool vector_shape(int64_t M, int64_t N, int64_t K) { return (M == 1 || N == 1) &
 
 // `split`: the call brings a workspace.
 int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
-             int64_t ldb, bool split, Plan *p)
+             int64_t ldb, bool split, Plan *p, bool use_table = true)
 {
-    const Tuned *t = find_tuned(0, transA, transB, M, N, K, split);
+    const Tuned *t = use_table ? find_tuned(0, transA, transB, M, N, K, split) : nullptr;
     const bool vector = vector_shape(M, N, K);
     if (!t && vector) {
         const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
@@ -171,7 +171,7 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
         p->slices = split ? vector_slices(v.pattern, v.a.len, K) : 1;
     } else {
         p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 16) : 1;
-        if (!t && p->slices == 1) t = find_tuned(0, transA, transB, M, N, K, false);
+        if (!t && p->slices == 1 && use_table) t = find_tuned(0, transA, transB, M, N, K, false);
         p->cfg = t ? t->tile : p->slices > 1 ? kF32_64x64 : tile_rule_f32(M, N);
     }
     return mode_f32(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
@@ -196,12 +196,12 @@ int mode_bf16(int cfg, int slices, int64_t M, int64_t N, int64_t K, const uint16
 }
 
 int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B,
-              int64_t ldb, bool split, Plan *p)
+              int64_t ldb, bool split, Plan *p, bool use_table = true)
 {
     const int transA = a_lay == kMnContig, transB = b_lay == kKContig;
-    const Tuned *t = find_tuned(1, transA, transB, M, N, K, split);
+    const Tuned *t = use_table ? find_tuned(1, transA, transB, M, N, K, split) : nullptr;
     p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 64) : 1;
-    if (!t && p->slices == 1) t = find_tuned(1, transA, transB, M, N, K, false);
+    if (!t && p->slices == 1 && use_table) t = find_tuned(1, transA, transB, M, N, K, false);
     if (t) p->cfg = t->tile;
     else if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) p->cfg = kBf16_Main;
     else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kBf16_128x128;
@@ -390,11 +390,11 @@ int gemm_f32_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int6
 }
 
 int fsrgemm_plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
-                     int64_t ldb, int with_workspace, int *tile, int *k_slices)
+                     int64_t ldb, int flags, int *tile, int *k_slices)
 {
-    if (!extents_ok(M, N, K) || tile == nullptr || k_slices == nullptr) return FSRGEMM_ERR_INVALID_ARG;
+    if (!extents_ok(M, N, K) || tile == nullptr || k_slices == nullptr || (flags & ~3)) return FSRGEMM_ERR_INVALID_ARG;
     Plan p;
-    const int rc = plan_f32(transA, transB, M, N, K, A, lda, B, ldb, with_workspace != 0, &p);
+    const int rc = plan_f32(transA, transB, M, N, K, A, lda, B, ldb, (flags & 1) != 0, &p, (flags & 2) == 0);
     if (rc != FSRGEMM_OK) return rc;
     *tile = p.cfg;
     *k_slices = p.slices;
@@ -460,12 +460,12 @@ int gemm_bf16_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int
 }
 
 int fsrgemm_plan_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
-                      const uint16_t *B, int64_t ldb, int with_workspace, int *tile, int *k_slices)
+                      const uint16_t *B, int64_t ldb, int flags, int *tile, int *k_slices)
 {
-    if (!extents_ok(M, N, K) || tile == nullptr || k_slices == nullptr) return FSRGEMM_ERR_INVALID_ARG;
+    if (!extents_ok(M, N, K) || tile == nullptr || k_slices == nullptr || (flags & ~3)) return FSRGEMM_ERR_INVALID_ARG;
     Plan p;
     const int rc = plan_bf16(transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, A, lda, B, ldb,
-                             with_workspace != 0, &p);
+                             (flags & 1) != 0, &p, (flags & 2) == 0);
     if (rc != FSRGEMM_OK) return rc;
     *tile = p.cfg;
     *k_slices = p.slices;

@@ -116,8 +116,10 @@ class DeviceBackend:
         self.fn = lib.gemm_f32_cfg if p.kind == "f32" else lib.gemm_bf16_cfg
         self.tile_count = lib.fsrgemm_tile_count_f32() if p.kind == "f32" else lib.fsrgemm_tile_count_bf16()
         plan = lib.fsrgemm_plan_f32 if p.kind == "f32" else lib.fsrgemm_plan_bf16
-        self.start = Candidate(*plan(p.transA, p.transB, p.M, p.N, p.K, a0, self.lda, b0, self.ldb, True))
-        self.start_unsplit = Candidate(*plan(p.transA, p.transB, p.M, p.N, p.K, a0, self.lda, b0, self.ldb, False))
+        args = (p.transA, p.transB, p.M, p.N, p.K, a0, self.lda, b0, self.ldb)
+        # the dispatcher's choice with / without a workspace, and what its rules alone would take
+        self.start, self.start_unsplit = Candidate(*plan(*args, True)), Candidate(*plan(*args, False))
+        self.rules, self.rules_unsplit = Candidate(*plan(*args, True, True)), Candidate(*plan(*args, False, True))
 
     def _call(self, c: Candidate, s: int) -> int:
         p, (a, b, out) = self.p, self.sets[s]

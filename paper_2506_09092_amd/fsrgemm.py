@@ -17,13 +17,15 @@ __all__ = [
     "fsrgemm_kernel_for_transpose_f32", "gemm_f32_cfg", "gemm_bf16_cfg", "fsrgemm_tile_count_f32",
     "fsrgemm_tile_count_bf16", "fsrgemm_plan_f32", "fsrgemm_plan_bf16",
     "fsrgemm_status_string", "fsrgemm_version", "check", "FsrGemmError", "EXPORTS",
-    "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
+    "FSRGEMM_PLAN_WORKSPACE", "FSRGEMM_PLAN_RULES_ONLY", "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
 ]
 
 FSRGEMM_OK = 0
 FSRGEMM_ERR_INVALID_ARG = -1
 FSRGEMM_ERR_LAUNCH = -2
 FSRGEMM_ERR_UNSUPPORTED_DEVICE = -3
+FSRGEMM_PLAN_WORKSPACE = 1
+FSRGEMM_PLAN_RULES_ONLY = 2
 
 _i64, _vp = ctypes.c_int64, ctypes.c_void_p
 _GEMM = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp]
@@ -151,20 +153,20 @@ def fsrgemm_tile_count_bf16() -> int:
     return int(load().fsrgemm_tile_count_bf16())
 
 
-def _plan(fn, transA, transB, M, N, K, A, lda, B, ldb, with_workspace):
+def _plan(fn, transA, transB, M, N, K, A, lda, B, ldb, with_workspace, rules_only):
     tile, slices = ctypes.c_int(-1), ctypes.c_int(-1)
-    rc = fn(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, int(bool(with_workspace)), ctypes.byref(tile),
-            ctypes.byref(slices))
+    flags = (FSRGEMM_PLAN_WORKSPACE if with_workspace else 0) | (FSRGEMM_PLAN_RULES_ONLY if rules_only else 0)
+    rc = fn(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, flags, ctypes.byref(tile), ctypes.byref(slices))
     return None if rc != FSRGEMM_OK else (tile.value, slices.value)
 
 
-def fsrgemm_plan_f32(transA, transB, M, N, K, A, lda, B, ldb, with_workspace=False):
+def fsrgemm_plan_f32(transA, transB, M, N, K, A, lda, B, ldb, with_workspace=False, rules_only=False):
     """(tile, k_slices) the dispatcher would take, or None for invalid arguments."""
-    return _plan(load().fsrgemm_plan_f32, transA, transB, M, N, K, A, lda, B, ldb, with_workspace)
+    return _plan(load().fsrgemm_plan_f32, transA, transB, M, N, K, A, lda, B, ldb, with_workspace, rules_only)
 
 
-def fsrgemm_plan_bf16(transA, transB, M, N, K, A, lda, B, ldb, with_workspace=False):
-    return _plan(load().fsrgemm_plan_bf16, transA, transB, M, N, K, A, lda, B, ldb, with_workspace)
+def fsrgemm_plan_bf16(transA, transB, M, N, K, A, lda, B, ldb, with_workspace=False, rules_only=False):
+    return _plan(load().fsrgemm_plan_bf16, transA, transB, M, N, K, A, lda, B, ldb, with_workspace, rules_only)
 
 
 def fsrgemm_kernel_for_f32(M, N, K, A, lda, B, ldb, C, ldc):

@@ -214,6 +214,8 @@ def test_tuned_table_rows_are_well_formed():
         assert 1 <= slices <= 64 and (ws == 1 or slices == 1) and slices * M * N * 4 <= (16 << 20 if slices > 1 else 1 << 62)
         plan = (lib.fsrgemm_plan_bf16 if kind else lib.fsrgemm_plan_f32)(ta, tb, M, N, K, P, M if ta else K, P, K if tb else N, bool(ws))
         assert plan == (tile, slices), (plan, (tile, slices))
+        rules = (lib.fsrgemm_plan_bf16 if kind else lib.fsrgemm_plan_f32)(ta, tb, M, N, K, P, M if ta else K, P, K if tb else N, bool(ws), True)
+        assert rules != plan                                              # a row that repeats the rules is never written
         if ws:
             q = lib.gemm_bf16_workspace_bytes if kind else lib.gemm_f32_workspace_bytes
             assert q(ta, tb, M, N, K) == (slices * M * N * 4 if slices > 1 else 0)

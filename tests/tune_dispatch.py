@@ -5,8 +5,8 @@ Lives under tests/ because it compares the HIP path with the oracle.
 
     python -m tests.tune_dispatch --out <file> [--log <file>] [--only f32|bf16]        (on an MI355X)
 
-A row is written only when the winner is at least `--gain` (default 4 %) faster than what the dispatcher takes
-today, measured twice; everything else stays with the rules.  After replacing the table, rebuild the library.
+A row is written only when the winner is at least `--gain` (default 4 %) faster than what the dispatcher's rules
+alone would take, measured twice; everything else stays with the rules.  After replacing the table, rebuild the library.
 """
 from __future__ import annotations
 
@@ -73,17 +73,17 @@ def tune(lib, torch, p: Problem, gain: float, log):
     validator = OracleValidator(p, A, B)
     rows, report = [], dict(problem=p._asdict())
     for with_ws in (False, True):
-        start = be.start if with_ws else be.start_unsplit
+        start, rules = (be.start, be.rules) if with_ws else (be.start_unsplit, be.rules_unsplit)
         r = fsr_search.search(start, be.tile_count, be.runs, lambda c: validator(be.output(c)), be.latency,
                               rounds=3, per_round=4, max_slices=fsr_search.MAX_SLICES if with_ws else 1, log=log)
         best = r["best"]
-        entry = dict(start=start, best=best, visited={"%d/%d" % k: v for k, v in r["visited"].items()})
-        if best is not None and best != start and r["visited"].get(start) == "valid":
-            # the incumbent against the dispatcher's choice, measured again, both ways round
-            t_start = min(be.latency(start), be.latency(start))
+        entry = dict(start=start, rules=rules, best=best, visited={"%d/%d" % k: v for k, v in r["visited"].items()})
+        if best is not None and best != rules and be.runs(rules) and validator(be.output(rules)):
+            # the incumbent against the choice of the rules, measured again, both ways round; a row only for a clear gain
+            t_rules = min(be.latency(rules), be.latency(rules))
             t_best = max(be.latency(best), be.latency(best))
-            entry.update(t_start=t_start, t_best=t_best)
-            if t_best < (1 - gain) * t_start:
+            entry.update(t_rules=t_rules, t_best=t_best)
+            if t_best < (1 - gain) * t_rules:
                 rows.append(fsr_search.table_row(p, with_ws, best))
         report["with_workspace" if with_ws else "plain"] = entry
     del be
