@@ -496,6 +496,73 @@ def test_f32_paper_task2_shape(gpu):
 
 # ---- transposition (the paper's Task 8): data movement, so every case is bit for bit ----
 
+# ---- infinities, NaNs, subnormal numbers ----
+
+def _same_class(got, ref):
+    """NaN where the oracle has NaN, the same infinity where it has one, finite elsewhere."""
+    return (np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(got == np.inf, ref == np.inf)
+            and np.array_equal(got == -np.inf, ref == -np.inf))
+
+
+def _plant_specials(X, seed, count):
+    rng = np.random.default_rng(seed)
+    X = X.copy()
+    for v in (np.inf, -np.inf, np.nan):
+        X[rng.integers(0, X.shape[0], count), rng.integers(0, X.shape[1], count)] = v
+    return X
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 260, 200), (512, 512, 128), (1, 300, 500), (300, 1, 500)])
+def test_f32_special_values(gpu, M, N, K):
+    # IEEE propagation does not depend on the order of summation: the class of every entry must match the oracle's
+    # in every candidate, and the finite entries must still be within the tolerance
+    Ai, Bi = inputs.small_ints(0, 11, M, K), inputs.small_ints(0, 12, K, N)
+    # a vector operand stays clean: one special value in it would reach every entry of the result
+    A, B = (Ai if M == 1 else _plant_specials(Ai, 1, 6)), (Bi if N == 1 else _plant_specials(Bi, 2, 6))
+    ref, S = oracle.gemm(A, B)
+    assert np.isnan(ref).any() and np.isfinite(ref).any()
+    fin = np.isfinite(ref)
+    for tile in range(3 + (M == 1 or N == 1)):
+        for slices in (1, 3):
+            say("f32 specials %dx%dx%d tile %d slices %d" % (M, N, K, tile, slices))
+            got = run_cfg(gpu, "f32", tile, slices, 0, 0, A, B)
+            assert _same_class(got, ref)
+            assert np.array_equal(got[fin].astype(np.float64), ref[fin])          # small integers: exact
+    assert _same_class(run_f32(gpu, A, B), ref)
+    # subnormal operands and subnormal results are kept, not flushed: scaled small integers stay exact
+    for sa, sb in ((2.0 ** -140, 1.0), (2.0 ** -75, 2.0 ** -70)):
+        As, Bs = (Ai * np.float32(sa)).astype(np.float32), (Bi * np.float32(sb)).astype(np.float32)
+        refs, _ = oracle.gemm(As, Bs)
+        assert np.array_equal(run_f32(gpu, As, Bs).astype(np.float64), refs) and np.count_nonzero(refs) > 0
+        assert np.array_equal(run_f32_ws(gpu, 0, 0, As, Bs).astype(np.float64), refs)
+
+
+def test_bf16_special_values(gpu):
+    M, N, K = 512, 520, 192
+    Ai, Bti = inputs.bf16_small_ints(4, 60, M, K), inputs.bf16_small_ints(4, 61, N, K)
+    A, Bt = Ai.copy(), Bti.copy()
+    rng = np.random.default_rng(3)
+    for X in (A, Bt):
+        for pattern in (0x7F80, 0xFF80, 0x7FC0):                # +inf, -inf, NaN
+            X[rng.integers(0, X.shape[0], 5), rng.integers(0, X.shape[1], 5)] = pattern
+    B = np.ascontiguousarray(Bt.T)
+    ref, _ = oracle.gemm(A, B)
+    assert np.isnan(ref).any() and np.isfinite(ref).any()
+    fin = np.isfinite(ref)
+    for tile in range(gpu.fsrgemm_tile_count_bf16()):
+        say("bf16 specials tile %d" % tile)
+        got = run_cfg(gpu, "bf16", tile, 1, 0, 1, A, B)
+        assert _same_class(got, ref) and np.array_equal(got[fin].astype(np.float64), ref[fin])
+    got = run_cfg(gpu, "bf16", 2, 3, 0, 1, A, B)
+    assert _same_class(got, ref) and np.array_equal(got[fin].astype(np.float64), ref[fin])
+    # subnormal bf16 operands (small integers times 2^-130) are kept
+    Af = (Ai.astype(np.uint32) << 16).view(np.float32)
+    Ad = ((Af * np.float32(2.0 ** -130)).view(np.uint32) >> 16).astype(np.uint16)
+    refd, _ = oracle.gemm(Ad, np.ascontiguousarray(Bti.T))
+    assert np.count_nonzero(refd) > 0
+    assert np.array_equal(run_bf16(gpu, Ad, Bti).astype(np.float64), refd)
+
+
 # ---- a vector on one side: the streaming kernels ----
 
 @pytest.mark.parametrize("M,N,K", [(1, 1000, 3000), (1000, 1, 3000), (1, 4096, 4096), (4096, 1, 4096), (1, 1, 100000),

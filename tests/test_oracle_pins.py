@@ -274,6 +274,29 @@ def _golden_transposes():
     return cases
 
 
+def test_ieee_special_values_follow_the_standard():
+    # what IEEE 754 fixes for sums of products with infinities, NaNs and subnormal numbers, worked by hand
+    inf, nan = np.inf, np.nan
+    A = np.array([[inf, 0, 1], [1, 2, 3], [inf, -inf, 0], [nan, 0, 0], [2.0 ** -149, 0, 0], [-inf, 1, 1]], dtype=np.float32)
+    B = np.array([[0, 1], [1, 1], [1, 1]], dtype=np.float32)
+    C, S = oracle.gemm(A, B)
+    assert np.isnan(C[0, 0]) and C[0, 1] == inf                  # inf * 0 is NaN; inf + finite is inf
+    assert list(C[1]) == [5.0, 6.0]                              # rows without special values are untouched by the others
+    assert np.isnan(C[2, 0]) and np.isnan(C[2, 1])               # (inf * 0) and (inf - inf)
+    assert np.isnan(C[3]).all()                                  # NaN times zero is NaN
+    assert C[4, 0] == 0.0 and C[4, 1] == 2.0 ** -149             # the smallest subnormal survives (fp64 holds it exactly)
+    assert np.isnan(C[5, 0]) and C[5, 1] == -inf
+    assert S[0, 1] == inf and S[5, 1] == inf and np.isnan(S[0, 0])
+    # products of subnormals are exact in fp64: 3 * 2^-149 times 5 * 2^-149
+    a, b = np.array([[3 * 2.0 ** -149]], dtype=np.float32), np.array([[5 * 2.0 ** -149]], dtype=np.float32)
+    assert oracle.gemm(a, b)[0][0, 0] == 15 * 2.0 ** -298
+    # bf16 patterns: 0x7F80 = +inf, 0xFF80 = -inf, 0x7FC0 = NaN, 0x0001 = 2^-133 (smallest subnormal)
+    Ab = np.array([[0x7F80, 0x3F80], [0xFF80, 0x0000], [0x7FC0, 0x3F80], [0x0001, 0x0000]], dtype=np.uint16)
+    Bb = np.array([[0x3F80], [0x3F80]], dtype=np.uint16)
+    Cb = oracle.gemm(Ab, Bb)[0][:, 0]
+    assert Cb[0] == inf and Cb[1] == -inf and np.isnan(Cb[2]) and Cb[3] == 2.0 ** -133
+
+
 def test_transpose_golden_worked_examples():
     cases = _golden_transposes()
     assert len(cases) == 3
