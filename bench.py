@@ -265,6 +265,41 @@ def transpose_sizes(lib, torch):
     return out
 
 
+def validator_pass_in_a_graph(lib, torch, passes=20):
+    """One validator pass = the 64 shapes of the fp32 sweep, launched back to back: issued call by call against
+    one replay of a HIP graph that captured the same 64 calls (the library allocates nothing and launches plain
+    kernels only, so its calls can be captured).  Time per pass in ms, operands random, tight leading dimensions."""
+    from paper_2506_09092_amd import inputs
+
+    calls = []
+    for c in inputs.sweep_cases(3, 64):
+        M, N, K = c["M"], c["N"], c["K"]
+        a, b, o = torch.randn(M, K, device="cuda"), torch.randn(K, N, device="cuda"), torch.empty(M, N, device="cuda")
+        calls.append(lambda a=a, b=b, o=o, M=M, N=N, K=K: lib.check(
+            lib.gemm_f32(M, N, K, a, K, b, N, o, N, torch.cuda.current_stream().cuda_stream)))
+
+    def one_pass():
+        for f in calls:
+            f()
+
+    one_pass()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_pass()
+    out = {}
+    for name, fn in (("eager_ms", one_pass), ("graph_ms", graph.replay)):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(passes):
+            fn()
+        torch.cuda.synchronize()
+        out[name] = (time.perf_counter() - t0) * 1e3 / passes
+    out["launches_per_pass"] = len(calls)
+    return out
+
+
 def selection_loop(lib, torch):
     """The selection loop (Algorithm 1 over tile configurations, validator = the CPU oracle) on three problems:
     where it starts (the dispatcher's choice), which candidates it visited, what it ends on, and the two timed
@@ -342,7 +377,7 @@ def main():
         del w
         torch.cuda.empty_cache()
 
-    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = None
+    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = None
     if not args.headline_only:
         task2 = paper_task2_sizes(lib, torch)
         layouts = transposed_storage_4096(lib, torch)
@@ -350,6 +385,7 @@ def main():
         skinny = split_k(lib, torch, "f32")
         skinny_bf16 = split_k(lib, torch, "bf16")
         task8 = transpose_sizes(lib, torch)
+        graph = validator_pass_in_a_graph(lib, torch)
         if not args.no_validate:
             log("selection loop on three problems")
             selection = selection_loop(lib, torch)
@@ -382,6 +418,7 @@ def main():
         "split_k_bf16": skinny_bf16,
         "paper_task8_transpose": task8,
         "selection_loop": selection,
+        "validator_pass_fp32_sweep": graph,
         "paper_context": "paper reports only speedups over hand-written CUDA for the group holding Task 2: 5.95-68.3x (RTX 3090 Ti), 6.06-60.0x (GTX 1660 SUPER)",
     }
     print(json.dumps(out), flush=True)

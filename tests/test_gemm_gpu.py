@@ -496,6 +496,58 @@ def test_f32_paper_task2_shape(gpu):
 
 # ---- transposition (the paper's Task 8): data movement, so every case is bit for bit ----
 
+# ---- the library under HIP graph capture ----
+
+def test_calls_captured_in_a_hip_graph_replay_bit_exact(gpu):
+    # the entry points allocate nothing and clear nothing with memset, so a validator pass (many launches on many
+    # shapes) can be captured once and replayed; every replay must give the eager bits
+    import torch
+
+    stream = lambda: torch.cuda.current_stream().cuda_stream
+    calls, outs = [], []
+    for c in inputs.sweep_cases(3, 64)[::3]:
+        M, N, K = c["M"], c["N"], c["K"]
+        a, b, o = torch.randn(M, K, device="cuda"), torch.randn(K, N, device="cuda"), torch.empty(M, N, device="cuda")
+        calls.append(lambda a=a, b=b, o=o, M=M, N=N, K=K: gpu.gemm_f32(M, N, K, a, K, b, N, o, N, stream()))
+        outs.append(o)
+    a, b, o = torch.randn(64, 8192, device="cuda"), torch.randn(8192, 64, device="cuda"), torch.empty(64, 64, device="cuda")
+    ws = torch.empty(gpu.gemm_f32_workspace_bytes(0, 0, 64, 64, 8192), dtype=torch.uint8, device="cuda")
+    assert ws.numel() > 0
+    calls.append(lambda a=a, b=b, o=o: gpu.gemm_f32_ws(0, 0, 64, 64, 8192, a, 8192, b, 64, o, 64, ws, ws.numel(), stream()))
+    outs.append(o)
+    ah = (torch.randn(512, 256, device="cuda") / 16).to(torch.bfloat16)
+    bh = (torch.randn(768, 256, device="cuda") / 16).to(torch.bfloat16)
+    oh = torch.empty(512, 768, device="cuda")
+    # tile 0: the direct-to-LDS kernel, whose loads are issued from inline assembly
+    calls.append(lambda: gpu.gemm_bf16_cfg(0, 1, 0, 1, 512, 768, 256, ah, 256, bh, 256, oh, 768, None, 0, stream()))
+    outs.append(oh)
+    t_in, t_out = torch.randn(300, 700, device="cuda"), torch.empty(700, 300, device="cuda")
+    calls.append(lambda: gpu.transpose_f32(300, 700, t_in, 700, t_out, 300, stream()))
+    outs.append(t_out)
+    v_in, v_out = torch.randn(1, 5000, device="cuda"), torch.empty(1, 300, device="cuda")
+    m_in = torch.randn(5000, 300, device="cuda")
+    calls.append(lambda: gpu.gemm_f32(1, 300, 5000, v_in, 5000, m_in, 300, v_out, 300, stream()))
+    outs.append(v_out)
+
+    for f in calls:                          # eager pass: also the first use of every kernel, outside the capture
+        gpu.check(f())
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for f in calls:
+            gpu.check(f())
+    for replay in range(3):
+        say("graph replay %d" % replay)
+        for o in outs:
+            o.fill_(float("nan"))            # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o.view(torch.int32), e.view(torch.int32))
+
+
 # ---- infinities, NaNs, subnormal numbers ----
 
 def _same_class(got, ref):
