@@ -28,11 +28,11 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense MFMA peaks
 # profiles/gemm_f32_4096_bf16_8192_hbm_traffic.txt (scaled by a 1 GiB copy).  Each entry is tied to the
 # kernel sources it was measured on: once those change the figure is stale and the bench reports null.
 TRAFFIC = {
-    "f32_4096": {"bytes": 866402533, "sources": {"gemm_f32.hip": "d127afe349029bcd", "common.hpp": "80f1879992596133"}},
-    "bf16_8192": {"bytes": 2111549247, "sources": {"gemm_bf16_main.hip": "68602cd09b71b81d", "common.hpp": "80f1879992596133"}},
+    "f32_4096": {"bytes": 866402533, "sources": {"gemm_f32.hip": "4defe3642b682f7b", "common.hpp": "fcd7c27e4bf90732"}},
+    "bf16_8192": {"bytes": 2111549247, "sources": {"gemm_bf16_main.hip": "13524cc455fec9d0", "common.hpp": "fcd7c27e4bf90732"}},
 }
 # the same for the transposes (profiles/transpose_f32_paper_sizes.txt), by N
-_T8_SOURCES = {"transpose.hip": "0a882ffb3d2b7377", "common.hpp": "80f1879992596133"}
+_T8_SOURCES = {"transpose.hip": "4a43b5ad193408de", "common.hpp": "fcd7c27e4bf90732"}
 TRAFFIC.update({"transpose_%d" % n: {"bytes": b, "sources": _T8_SOURCES}
                 for n, b in ((1024, 8433502), (2048, 33598846), (4096, 134260222), (8192, 536905727), (16384, 2147491840))})
 

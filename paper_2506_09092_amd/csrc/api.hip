@@ -4,7 +4,7 @@
 
 #include <string.h>
 
-#include "common.hpp"
+#include "launchers.hpp"
 
 using namespace fsrgemm;
 

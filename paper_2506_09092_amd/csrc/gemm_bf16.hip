@@ -39,7 +39,7 @@
 
 #include <type_traits>
 
-#include "common.hpp"
+#include "launchers.hpp"
 
 namespace fsrgemm {
 namespace {

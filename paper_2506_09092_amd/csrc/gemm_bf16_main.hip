@@ -77,7 +77,7 @@
 #include <type_traits>
 #include <utility>
 
-#include "common.hpp"
+#include "launchers.hpp"
 
 namespace fsrgemm {
 namespace {

@@ -14,7 +14,7 @@
 // With k_slices > 1 the K range is cut into slices, workgroup ids beyond the first round belong to further
 // slices and every slice writes its partial y to its own vector behind g.y (a workspace); the caller adds the
 // slices with the split-K reduction kernel.  All sums have a fixed order: results repeat bit for bit.
-#include "common.hpp"
+#include "launchers.hpp"
 
 namespace fsrgemm {
 

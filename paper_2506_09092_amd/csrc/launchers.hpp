@@ -1,0 +1,58 @@
+// Host-side interface between the C ABI (api.hip) and the kernel files: configuration numbers, kernel names as
+// a profiler prints them, and one launcher per kernel family.
+#pragma once
+#include <atomic>
+
+#include "common.hpp"
+
+namespace fsrgemm {
+
+// Raises a kernel's dynamic-LDS limit once per device (the attribute belongs to the device's copy of the
+// kernel).  `done` is the caller's per-kernel bitmap of devices already configured; safe to call concurrently.
+hipError_t ensure_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done);
+
+// fp32 tile configurations (gemm_f32.hip), each available in the three load modes and the four layout pairs
+enum F32Config { kF32_256x128 = 0, kF32_128x128 = 1, kF32_64x64 = 2, kF32ConfigCount };
+// Names are substrings of the kernel symbols as a profiler trace prints them.
+const char *f32_kernel_name(int cfg, int mode, int a_lay, int b_lay);
+hipError_t launch_f32(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
+// second half of a split-K product: C = sum over slices, in slice order
+const char *splitk_reduce_kernel_name();
+hipError_t launch_splitk_reduce(const float *ws, int slices, int64_t slice_stride, float *C, int M, int N, int64_t ldc,
+                                hipStream_t s);
+
+// bf16 configurations: the direct-to-LDS 256x256 kernel for large aligned problems (gemm_bf16_main.hip, the
+// four layout pairs) and three tile sizes of the general kernel (gemm_bf16.hip), each in the three load
+// modes and the four layout pairs
+enum Bf16Config { kBf16_Main = 0, kBf16_256x256 = 1, kBf16_128x128 = 2, kBf16_64x64 = 3, kBf16ConfigCount };
+const char *bf16_kernel_name(int cfg, int mode, int a_lay, int b_lay);
+hipError_t launch_bf16(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
+const char *bf16_main_kernel_name(int a_lay, int b_lay);
+hipError_t launch_bf16_main(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
+
+// fp32 products with M == 1 or N == 1 (gemv_f32.hip): y[i * incy] = sum over k of mat(i, k) * x[k * incx] for
+// i < len, with mat(i, k) at mat[i * ld + k] (kVecRows) or mat[k * ld + i] (kVecCols).  With k_slices > 1 slice s
+// writes its partial y behind y + s * slice_stride.  xvec is filled in by the launcher.
+enum VecPattern { kVecRows = 0, kVecCols = 1 };
+constexpr int kF32_Vector = kF32ConfigCount;        // the candidate number of these kernels, after the tile configurations
+struct VecArgs {
+    const float *mat;
+    int64_t ld;
+    const float *x;
+    int64_t incx;
+    float *y;
+    int64_t incy;
+    int len, K;
+    int k_slices;
+    int64_t slice_stride;
+    bool xvec;
+};
+const char *gemv_kernel_name(int pattern, bool vec);
+bool gemv_takes_vectors(const VecArgs &a);
+hipError_t launch_gemv_f32(int pattern, VecArgs a, hipStream_t s);
+
+// fp32 transposition (transpose.hip)
+const char *transpose_kernel_name(int rows, int cols);
+hipError_t launch_transpose_f32(const float *A, int64_t lda, float *T, int64_t ldt, int rows, int cols, hipStream_t s);
+
+}  // namespace fsrgemm

@@ -17,7 +17,7 @@
 // access of a full tile can leave the matrix.  Only matrices with fewer than 64 rows or columns take the
 // element-wise, bounds-checked path.  Global accesses are written as 16-byte copies: the compiler emits
 // 128-bit loads and stores, which this target allows at any address that is aligned for a float.
-#include "common.hpp"
+#include "launchers.hpp"
 
 namespace fsrgemm {
 namespace {
