@@ -334,7 +334,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed launches first: the clocks of an idle device settle only after 50-75 launches of the bf16 workload")
     ap.add_argument("--workload", default="f32_4096", choices=["f32_4096", "bf16_8192"],
                     help="which headline workload fills the top-level fields (both are always measured)")
     ap.add_argument("--no-validate", action="store_true", help="skip the oracle sweep (profiling runs)")
