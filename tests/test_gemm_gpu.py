@@ -696,6 +696,38 @@ def test_bf16_every_candidate(gpu, shape, ta, tb):
             assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
 
 
+@pytest.mark.parametrize("ta,tb", [(0, 0)] + LAYOUTS)
+def test_every_compiled_kernel_instance(gpu, ta, tb):
+    # every tile configuration in each of its three load modes (unchecked vectors / vectors with checked edges /
+    # element-wise), for this storage pair, both precisions: 9 fp32 and 9 bf16 general kernels plus the
+    # direct-to-LDS one per parametrisation
+    M, N = 520, 392                                     # not multiples of any tile: shifted last tiles everywhere
+    # unchecked: K a multiple of the K-tile (16 fp32, 64 bf16); checked edges: it is not, but rows stay 16-byte aligned
+    for K, aligned, mode in ((128, True, "unchecked"), (104, True, "checked edges"), (100, False, "element-wise")):
+        A, B = inputs.uniform_pm1(15, 1, M, K), inputs.uniform_pm1(15, 2, K, N)
+        ref, S = oracle.gemm(A, B)
+        Ah = inputs.bf16_normal_scaled(15, 3, M, K, 1 / math.sqrt(K))
+        Bh = np.ascontiguousarray(inputs.bf16_normal_scaled(15, 4, N, K, 1 / math.sqrt(K)).T)
+        refh, Sh = oracle.gemm(Ah, Bh)
+        lda, ldb = (M if ta else K), (K if tb else N)
+        kw = dict(lda=lda + 8, ldb=ldb + 8, ldc=N + 3, offset=0) if aligned else dict(lda=lda + 3, ldb=ldb + 1, ldc=N + 1, offset=1)
+        for tile in range(3):
+            say("f32 tile %d, %s, storage %d%d" % (tile, mode, ta, tb))
+            got = run_cfg(gpu, "f32", tile, 1, ta, tb, A, B, repeat=2, **kw)
+            assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        for tile in (1, 2, 3):
+            say("bf16 tile %d, %s, storage %d%d" % (tile, mode, ta, tb))
+            got = run_cfg(gpu, "bf16", tile, 1, ta, tb, Ah, Bh, repeat=2, **kw)
+            assert oracle.componentwise_error(got, refh, Sh) <= TOL_BF16
+    K = 128
+    Ah = inputs.bf16_normal_scaled(15, 5, M, K, 1 / math.sqrt(K))
+    Bh = np.ascontiguousarray(inputs.bf16_normal_scaled(15, 6, N, K, 1 / math.sqrt(K)).T)
+    refh, Sh = oracle.gemm(Ah, Bh)
+    say("bf16 tile 0, storage %d%d" % (ta, tb))
+    got = run_cfg(gpu, "bf16", 0, 1, ta, tb, Ah, Bh, ldc=N + 3, repeat=2)
+    assert oracle.componentwise_error(got, refh, Sh) <= TOL_BF16
+
+
 def test_forced_plan_equals_dispatch(gpu):
     # the dispatcher's own choice, forced, gives the dispatcher's bits (fp32 and bf16, plain and with a workspace)
     for M, N, K in ((300, 520, 1000), (64, 64, 4097), (1, 4096, 4096)):
