@@ -229,6 +229,18 @@ const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB,
                                        const uint16_t *B, int64_t ldb,
                                        const float *C, int64_t ldc);
 
+/* The kernel a *_cfg call with this tile would launch, or NULL where the call would reject the candidate. */
+const char *fsrgemm_kernel_for_f32_cfg(int tile, int transA, int transB,
+                                       int64_t M, int64_t N, int64_t K,
+                                       const float *A, int64_t lda,
+                                       const float *B, int64_t ldb,
+                                       const float *C, int64_t ldc);
+const char *fsrgemm_kernel_for_bf16_cfg(int tile, int transA, int transB,
+                                        int64_t M, int64_t N, int64_t K,
+                                        const uint16_t *A, int64_t lda,
+                                        const uint16_t *B, int64_t ldb,
+                                        const float *C, int64_t ldc);
+
 /*
  * Matrix transposition, the paper's Task 8 (task-prompt table: a rows x cols matrix of 32-bit floating point
  * numbers becomes a cols x rows one, all matrices row-major), the memory-bound counterpart of the product:

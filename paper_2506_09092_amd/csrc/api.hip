@@ -509,6 +509,33 @@ const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB, int64_t M, int64_
     return bf16_kernel_name(p.cfg, p.mode, a_lay, b_lay);
 }
 
+const char *fsrgemm_kernel_for_f32_cfg(int tile, int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A,
+                                       int64_t lda, const float *B, int64_t ldb, const float *C, int64_t ldc)
+{
+    if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
+    if (tile < 0 || tile > kF32_Vector || (tile == kF32_Vector && !vector_shape(M, N, K))) return nullptr;
+    int mode;
+    if (mode_f32(tile, 1, M, N, K, A, lda, B, ldb, &mode) != FSRGEMM_OK) return nullptr;
+    if (tile == kF32_Vector) {
+        const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
+        return gemv_kernel_name(v.pattern, gemv_takes_vectors(v.a));
+    }
+    return f32_kernel_name(tile, mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig);
+}
+
+const char *fsrgemm_kernel_for_bf16_cfg(int tile, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                                        const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, const float *C,
+                                        int64_t ldc)
+{
+    if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
+    if (tile < 0 || tile >= kBf16ConfigCount) return nullptr;
+    const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
+    int mode;
+    if (mode_bf16(tile, 1, M, N, K, A, lda, B, ldb, &mode) != FSRGEMM_OK) return nullptr;
+    if (tile == kBf16_Main && !main_kernel_fits(a_lay, b_lay, M, N, mode, lda, ldb)) return nullptr;
+    return bf16_kernel_name(tile, mode, a_lay, b_lay);
+}
+
 static bool transpose_args_ok(int64_t rows, int64_t cols, const float *A, int64_t lda, const float *T, int64_t ldt)
 {
     const int64_t lim = (int64_t)1 << 31;

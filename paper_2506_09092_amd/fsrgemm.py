@@ -15,7 +15,8 @@ __all__ = [
     "fsrgemm_kernel_for_f32_ex", "fsrgemm_kernel_for_bf16", "gemm_bf16_ex", "fsrgemm_kernel_for_bf16_ex",
     "gemm_f32_ws", "gemm_f32_workspace_bytes", "gemm_bf16_ws", "gemm_bf16_workspace_bytes", "transpose_f32",
     "fsrgemm_kernel_for_transpose_f32", "gemm_f32_cfg", "gemm_bf16_cfg", "fsrgemm_tile_count_f32",
-    "fsrgemm_tile_count_bf16", "fsrgemm_plan_f32", "fsrgemm_plan_bf16",
+    "fsrgemm_tile_count_bf16", "fsrgemm_plan_f32", "fsrgemm_plan_bf16", "fsrgemm_kernel_for_f32_cfg",
+    "fsrgemm_kernel_for_bf16_cfg",
     "fsrgemm_status_string", "fsrgemm_version", "check", "FsrGemmError", "EXPORTS",
     "FSRGEMM_PLAN_WORKSPACE", "FSRGEMM_PLAN_RULES_ONLY", "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
 ]
@@ -48,6 +49,8 @@ EXPORTS = {
     "fsrgemm_kernel_for_transpose_f32": (ctypes.c_char_p, [_i64, _i64, _vp, _i64, _vp, _i64]),
     "gemm_f32_cfg": (ctypes.c_int, [ctypes.c_int] * 4 + _GEMM[:-1] + [_vp, _i64, _vp]),
     "gemm_bf16_cfg": (ctypes.c_int, [ctypes.c_int] * 4 + _GEMM[:-1] + [_vp, _i64, _vp]),
+    "fsrgemm_kernel_for_f32_cfg": (ctypes.c_char_p, [ctypes.c_int] * 3 + _QUERY),
+    "fsrgemm_kernel_for_bf16_cfg": (ctypes.c_char_p, [ctypes.c_int] * 3 + _QUERY),
     "fsrgemm_tile_count_f32": (ctypes.c_int, []),
     "fsrgemm_tile_count_bf16": (ctypes.c_int, []),
     "fsrgemm_plan_f32": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, ctypes.c_int,
@@ -143,6 +146,16 @@ def gemm_f32_cfg(tile, k_slices, transA, transB, M, N, K, A, lda, B, ldb, C, ldc
 def gemm_bf16_cfg(tile, k_slices, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, workspace=0, workspace_bytes=0, stream=0) -> int:
     return load().gemm_bf16_cfg(int(tile), int(k_slices), int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb,
                                 _ptr(C), ldc, _ptr(workspace), int(workspace_bytes), _ptr(stream) or None)
+
+
+def fsrgemm_kernel_for_f32_cfg(tile, transA, transB, M, N, K, A, lda, B, ldb, C, ldc):
+    r = load().fsrgemm_kernel_for_f32_cfg(int(tile), int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc)
+    return None if r is None else r.decode()
+
+
+def fsrgemm_kernel_for_bf16_cfg(tile, transA, transB, M, N, K, A, lda, B, ldb, C, ldc):
+    r = load().fsrgemm_kernel_for_bf16_cfg(int(tile), int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc)
+    return None if r is None else r.decode()
 
 
 def fsrgemm_tile_count_f32() -> int:

@@ -172,6 +172,14 @@ def test_forced_configurations_and_plan_queries():
     assert g(0, 1, 255, 512, 512) == bad and g(0, 1, 512, 512, 96) == bad and g(0, 1, 512, 512, 512, a=P + 2) == bad
     assert g(0, 1, 512, 512, 512, lda=516) == bad and g(0, 2, 512, 512, 512, ws=P, wsb=1 << 24) == bad
     assert g(4, 1, 512, 512, 512) == bad and g(1, 1, 0, 512, 512) == ok
+    # names of forced candidates; None where the forced call would reject the candidate
+    qc, qh = lib.fsrgemm_kernel_for_f32_cfg, lib.fsrgemm_kernel_for_bf16_cfg
+    assert qc(0, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) == "gemm_f32_kernel<4, 2, 2, 2, 0, 1>"        # the largest tile on a tiny unaligned problem
+    assert qc(3, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) is None and qc(4, 0, 0, 1, 10, 10, P, 10, P, 10, P, 10) is None
+    assert qc(3, 0, 0, 1, 16, 16, P, 16, P, 16, P, 16) == "gemv_cols_f32_kernel<true>"
+    assert qh(0, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) == "gemm_bf16_main_kernel<0, 0>"
+    assert qh(0, 0, 1, 520, 392, 100, P, 104, P, 104, P, 392) is None and qh(4, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) is None
+    assert qh(1, 1, 0, 8, 8, 8, P, 8, P, 8, P, 8) == "gemm_bf16_kernel<4, 1, 1, 1, 1>"
     # plan queries: the rules, in the terms of the forced calls
     pf, pb = lib.fsrgemm_plan_f32, lib.fsrgemm_plan_bf16
     assert pf(0, 0, 4096, 4096, 4096, P, 4096, P, 4096) == (0, 1) and pf(0, 0, 200, 200, 200, P, 200, P, 200) == (2, 1)

@@ -711,6 +711,15 @@ def test_every_compiled_kernel_instance(gpu, ta, tb):
         refh, Sh = oracle.gemm(Ah, Bh)
         lda, ldb = (M if ta else K), (K if tb else N)
         kw = dict(lda=lda + 8, ldb=ldb + 8, ldc=N + 3, offset=0) if aligned else dict(lda=lda + 3, ldb=ldb + 1, ldc=N + 1, offset=1)
+        # the names the library gives these candidates: <.., load mode, A layout, B layout>
+        base, m = (0x1000 if aligned else 0x1004), ("unchecked", "checked edges", "element-wise").index(mode)
+        for tile, shape in enumerate(("4, 2, 2", "2, 2, 3", "1, 1, 4")):
+            assert gpu.fsrgemm_kernel_for_f32_cfg(tile, ta, tb, M, N, K, base, kw["lda"], base, kw["ldb"], 0x1000, kw["ldc"]) == \
+                "gemm_f32_kernel<%s, %d, %d, %d>" % (shape, m, ta, 1 - tb)
+        base = 0x1000 if aligned else 0x1002
+        for tile, shape in ((1, "4, 1"), (2, "2, 2"), (3, "1, 4")):
+            assert gpu.fsrgemm_kernel_for_bf16_cfg(tile, ta, tb, M, N, K, base, kw["lda"], base, kw["ldb"], 0x1000, kw["ldc"]) == \
+                "gemm_bf16_kernel<%s, %d, %d, %d>" % (shape, m, ta, 1 - tb)
         for tile in range(3):
             say("f32 tile %d, %s, storage %d%d" % (tile, mode, ta, tb))
             got = run_cfg(gpu, "f32", tile, 1, ta, tb, A, B, repeat=2, **kw)
