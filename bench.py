@@ -37,6 +37,11 @@ TRAFFIC.update({"transpose_%d" % n: {"bytes": b, "sources": _T8_SOURCES}
                 for n, b in ((1024, 8433502), (2048, 33598846), (4096, 134260222), (8192, 536905727), (16384, 2147491840))})
 
 
+# What a loop of nothing but the kernel's MFMA instruction sustains on this part (TFLOP/s; fp32 on any data,
+# bf16 16x16x32 on random operands, where the power limit holds it to 1.94-2.04 PFLOP/s).
+MEASURED_CEILING = {"f32": 155.0, "bf16": 2000.0}
+
+
 def measured_traffic(name):
     import hashlib
 
@@ -109,8 +114,10 @@ def time_workload(w, lib, torch, steps, warmup):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     per = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    # the other cache regime: the same operand set launch after launch (what fits the caches stays there)
+    warm = steady_ms(torch, lambda: call(0))
     return dict(wall_ms_per_step=wall_ms / steps, launch_ms_avg=sum(per) / len(per),
-                launch_ms_median=per[len(per) // 2], launch_ms_min=per[0])
+                launch_ms_median=per[len(per) // 2], launch_ms_min=per[0], launch_ms_same_buffers=warm)
 
 
 def report(w, t, lib):
@@ -122,9 +129,13 @@ def report(w, t, lib):
         workload=w["desc"],
         tflops=w["flops"] / (t["wall_ms_per_step"] * 1e-3) / 1e12,
         ms_per_step=t["wall_ms_per_step"],
-        launch_ms={"avg": t["launch_ms_avg"], "median": t["launch_ms_median"], "min": t["launch_ms_min"]},
+        launch_ms={"avg": t["launch_ms_avg"], "median": t["launch_ms_median"], "min": t["launch_ms_min"],
+                   "same_buffers_median": t["launch_ms_same_buffers"]},
         roofline={"bound": "mfma", "kernel": q(w["M"], w["N"], w["K"], a, w["lda"], b, w["ldb"], c, w["ldc"]),
                   "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                  # a register-only loop of the kernel's MFMA on the same kind of data, whole chip, measured once
+                  "register_only_mfma_loop": MEASURED_CEILING[w["kind"]],
+                  "frac_of_register_only_loop": achieved / MEASURED_CEILING[w["kind"]],
                   "traffic": measured_traffic(w["name"]),
                   "hbm_GBps_algorithmic": w["bytes"] / (t["launch_ms_avg"] * 1e-3) / 1e9},
     )
@@ -171,6 +182,19 @@ def paper_task2_sizes(lib, torch):
         out.append({"size": M, "kernel": lib.fsrgemm_kernel_for_f32(M, N, K, a, K, b, N, c, N), "ms": ms,
                     "tflops": 2.0 * M * N * K / (ms * 1e-3) / 1e12})
         del a, c
+    return out
+
+
+def small_fixed_configs(lib, torch):
+    """fp32 256^3 and 1024^3 (the small fixed configurations; parity is a GPU test): these are bound by launch
+    latency and by the number of tiles, so the figure of interest is microseconds per launch."""
+    stream = torch.cuda.current_stream().cuda_stream
+    out = []
+    for n in (256, 1024):
+        a, b, c = torch.randn(n, n, device="cuda"), torch.randn(n, n, device="cuda"), torch.empty(n, n, device="cuda")
+        ms = steady_ms(torch, lambda: lib.check(lib.gemm_f32(n, n, n, a, n, b, n, c, n, stream)))
+        out.append({"n": n, "kernel": lib.fsrgemm_kernel_for_f32(n, n, n, a, n, b, n, c, n), "us": ms * 1e3,
+                    "tflops": 2.0 * n ** 3 / (ms * 1e-3) / 1e12})
     return out
 
 
@@ -330,6 +354,38 @@ def cpu_baseline(w):
             "sample": "%s %d of %d rows of C for the %s workload (fp64 triple loop, OpenMP over rows)" % ("all" if rows == w["M"] else "first", rows, w["M"], w["name"])}
 
 
+def cpu_baseline_other_sizes(inputs):
+    """The oracle on the other configurations, as context for cpu_baseline: one thread on 256^3 and 1024^3, all
+    cores on 1024^3, and all cores on the first 512 rows of the bf16 8192^3 product (the whole product would
+    take 16 times as long: the last entry is an extrapolation and says so)."""
+    import math
+
+    import oracle
+
+    def timed(A, B, threads):
+        old = oracle.num_threads()
+        oracle.set_num_threads(threads)
+        try:
+            t0 = time.perf_counter()
+            oracle.gemm(A, B, want_scale=False)
+            return time.perf_counter() - t0
+        finally:
+            oracle.set_num_threads(old)
+
+    cores, out = oracle.num_threads(), []
+    for n, threads in ((256, 1), (1024, 1), (1024, cores)):
+        A, B = inputs.uniform_pm1(1, 1, n, n), inputs.uniform_pm1(1, 2, n, n)
+        dt = timed(A, B, threads)
+        out.append({"workload": "fp32 %d^3" % n, "cores": threads, "seconds": dt, "gflops": 2.0 * n ** 3 / dt / 1e9})
+    n, rows = 8192, 512
+    A = inputs.bf16_normal_scaled(4, 1, rows, n, 1 / math.sqrt(n))
+    B = inputs.bf16_normal_scaled(4, 2, n, n, 1 / math.sqrt(n)).T.copy()
+    dt = timed(A, B, cores)
+    out.append({"workload": "bf16 8192^3, first 512 rows of C", "cores": cores, "seconds": dt,
+                "gflops": 2.0 * rows * n * n / dt / 1e9, "whole_product_seconds_extrapolated": dt * n / rows})
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -378,8 +434,9 @@ def main():
         del w
         torch.cuda.empty_cache()
 
-    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = None
+    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = small = None
     if not args.headline_only:
+        small = small_fixed_configs(lib, torch)
         task2 = paper_task2_sizes(lib, torch)
         layouts = transposed_storage_4096(lib, torch)
         layouts_bf16 = storage_orders_bf16_8192(lib, torch)
@@ -410,6 +467,8 @@ def main():
         "config": {"workload": top["workload"], "buffers": "rotating operand/result sets", "timing": "wall clock over all steps; HIP events per launch"},
         "roofline": top["roofline"], "launch_ms": top["launch_ms"], "oracle_check": top["oracle_check"],
         "cpu_baseline": baselines.get(args.workload),
+        "cpu_baseline_other_sizes": None if args.no_cpu_baseline else cpu_baseline_other_sizes(inputs),
+        "small_fixed_configs_f32": small,
         "other_workload": other,
         "sweep": sweep,
         "paper_task2_shapes": task2,
