@@ -155,7 +155,11 @@ int gemm_bf16_ws(int transA, int transB,
  * validate, keep the one with the least measured time), with tile configurations and K slices in the place of
  * generated kernels.
  *   tile: fp32  0 = 256 x 128, 1 = 128 x 128, 2 = 64 x 64 output tile per workgroup, 3 = the streaming kernels for
- *               M == 1 or N == 1 with K > 0, which use no matrix cores (fsrgemm_tile_count_f32() = 4);
+ *               M == 1 or N == 1 with K > 0, which use no matrix cores, 4 = the kernel for small results of long
+ *               sums (transA != 0 and transB == 0, i.e. both operands stored with k as the row index; M, N <= 16 with
+ *               at most 144 entries after rounding both up to multiples of 4; K > 0), whose
+ *               k_slices are workgroups (1..256, at most K) that each keep a partial result in the workspace, so it
+ *               needs its workspace even for one (fsrgemm_tile_count_f32() = 5);
  *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64
  *               (fsrgemm_tile_count_bf16() = 4).
  *   k_slices: 1 = K in one piece; 2..64 = split along K as gemm_f32_ws does, which needs a workspace of
@@ -163,6 +167,7 @@ int gemm_bf16_ws(int transA, int transB,
  *         ceil(K / 64) (bf16).
  * A candidate that cannot run this problem is FSRGEMM_ERR_INVALID_ARG and launches nothing: a tile or slice
  * count out of range, a split without a fitting workspace, fp32 candidate 3 on a product without a vector,
+ * fp32 candidate 4 on a result that is too large,
  * bf16 tile 0 with a split or where its kernel's
  * conditions fail (M, N >= 256, K a multiple of 64, 16-byte aligned operands with leading dimensions that are
  * multiples of 8 and below 2^25; M or N a multiple of 8 for an operand contiguous along it).  Every other

@@ -85,6 +85,10 @@ int splitk_slices(int64_t M, int64_t N, int64_t K, int k_tile)
 int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
              int *mode)
 {
+    if (cfg == kF32_Skinny) {
+        *mode = 0;
+        return FSRGEMM_OK;
+    }
     if (cfg == kF32_Vector) {           // the vector kernels look at alignment themselves
         *mode = 0;
         return ceil_div(M > N ? M : N, 4) * slices >= ((int64_t)1 << 31) ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_OK;
@@ -165,7 +169,11 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
 {
     const Tuned *t = use_table ? find_tuned(0, transA, transB, M, N, K, split) : nullptr;
     const bool vector = vector_shape(M, N, K);
-    if (!t && vector) {
+    if (!t && split && transA && !transB && skinny_fits(M, N) && K >= 4096 && 2048 * lda < (1 << 29) && 2048 * ldb < (1 << 29)) {
+        // a small result of long sums: one workgroup per 2048 k, each with a partial result in the workspace
+        p->cfg = kF32_Skinny;
+        p->slices = (int)(K / 2048 < kSkinnyMaxParts ? K / 2048 : kSkinnyMaxParts);
+    } else if (!t && vector) {
         const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
         p->cfg = kF32_Vector;
         p->slices = split ? vector_slices(v.pattern, v.a.len, K) : 1;
@@ -278,6 +286,12 @@ int run_f32(const Plan &p, int transA, int transB, int64_t M, int64_t N, int64_t
 {
     const int rc = device_ok();
     if (rc != FSRGEMM_OK) return rc;
+    if (p.cfg == kF32_Skinny) {
+        SkinnyArgs a;
+        a.A = A, a.lda = lda, a.B = B, a.ldb = ldb;
+        a.M = (int)M, a.N = (int)N, a.K = (int)K, a.parts = p.slices, a.partial = ws;
+        return launch_skinny_f32(a, C, ldc, s) == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+    }
     const bool split = p.slices > 1;
     hipError_t e;
     if (p.cfg == kF32_Vector) {
@@ -354,7 +368,7 @@ int64_t gemm_f32_workspace_bytes(int transA, int transB, int64_t M, int64_t N, i
     if (!extents_ok(M, N, K)) return 0;
     Plan p;
     if (plan_f32(transA, transB, M, N, K, nullptr, 4, nullptr, 4, true, &p) != FSRGEMM_OK) return 0;
-    return p.slices > 1 ? (int64_t)p.slices * M * N * 4 : 0;
+    return p.slices > 1 || p.cfg == kF32_Skinny ? (int64_t)p.slices * M * N * 4 : 0;
 }
 
 int gemm_f32_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
@@ -365,7 +379,7 @@ int gemm_f32_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const f
     if (workspace_bytes < 0 || (workspace_bytes > 0 && workspace == nullptr)) return FSRGEMM_ERR_INVALID_ARG;
     Plan p;
     rc = plan_f32(transA, transB, M, N, K, A, lda, B, ldb, workspace != nullptr, &p);
-    if (rc == FSRGEMM_OK && p.slices > 1 && !workspace_fits(workspace, workspace_bytes, p.slices, M, N))
+    if (rc == FSRGEMM_OK && (p.slices > 1 || p.cfg == kF32_Skinny) && !workspace_fits(workspace, workspace_bytes, p.slices, M, N))
         rc = plan_f32(transA, transB, M, N, K, A, lda, B, ldb, false, &p);
     if (rc != FSRGEMM_OK) return rc;
     if (M == 0 || N == 0) return FSRGEMM_OK;
@@ -379,8 +393,18 @@ int gemm_f32_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int6
 {
     int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
     if (rc != FSRGEMM_OK) return rc;
-    if (!forced_ok(tile, kF32_Vector + 1, k_slices, M, N, K, 16, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
-    if (tile == kF32_Vector && !vector_shape(M, N, K) && M > 0 && N > 0) return FSRGEMM_ERR_INVALID_ARG;
+    if (tile == kF32_Skinny) {      // its k_slices are workgroups with a partial result each: up to 256, and a workspace even for one
+        if (M == 0 || N == 0) return FSRGEMM_OK;
+        if (!transA || transB || !skinny_fits(M, N) || K < 1 || k_slices < 1 || k_slices > kSkinnyMaxParts || k_slices > K ||
+            workspace_bytes < 0 || !workspace_fits(workspace, workspace_bytes, k_slices, M, N))
+            return FSRGEMM_ERR_INVALID_ARG;
+        SkinnyArgs probe;
+        probe.lda = lda, probe.ldb = ldb, probe.K = (int)K, probe.parts = k_slices;
+        if (!skinny_offsets_fit(probe)) return FSRGEMM_ERR_INVALID_ARG;
+    } else {
+        if (!forced_ok(tile, kF32_Vector + 1, k_slices, M, N, K, 16, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
+        if (tile == kF32_Vector && !vector_shape(M, N, K) && M > 0 && N > 0) return FSRGEMM_ERR_INVALID_ARG;
+    }
     Plan p = {tile, 0, k_slices};
     rc = mode_f32(tile, k_slices, M, N, K, A, lda, B, ldb, &p.mode);
     if (rc != FSRGEMM_OK) return rc;
@@ -401,7 +425,7 @@ int fsrgemm_plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, co
     return FSRGEMM_OK;
 }
 
-int fsrgemm_tile_count_f32(void) { return kF32_Vector + 1; }
+int fsrgemm_tile_count_f32(void) { return kF32_Skinny + 1; }
 
 int gemm_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
               float *C, int64_t ldc, void *stream)
@@ -513,6 +537,7 @@ const char *fsrgemm_kernel_for_f32_cfg(int tile, int transA, int transB, int64_t
                                        int64_t lda, const float *B, int64_t ldb, const float *C, int64_t ldc)
 {
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
+    if (tile == kF32_Skinny) return K >= 1 && transA && !transB ? skinny_kernel_name((int)(M < 17 ? M : 17), (int)(N < 17 ? N : 17)) : nullptr;
     if (tile < 0 || tile > kF32_Vector || (tile == kF32_Vector && !vector_shape(M, N, K))) return nullptr;
     int mode;
     if (mode_f32(tile, 1, M, N, K, A, lda, B, ldb, &mode) != FSRGEMM_OK) return nullptr;

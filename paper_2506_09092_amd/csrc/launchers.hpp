@@ -51,6 +51,25 @@ const char *gemv_kernel_name(int pattern, bool vec);
 bool gemv_takes_vectors(const VecArgs &a);
 hipError_t launch_gemv_f32(int pattern, VecArgs a, hipStream_t s);
 
+// fp32 products with M, N <= 16 and a long K, both operands stored with k as the row index (gemm_f32_skinny.hip):
+// element (i, k) of A at A[k * lda + i], element (k, j) of B at B[k * ldb + j]; K is cut into `parts` pieces whose
+// partial results go to partial[part][M][N] and are then added into C.
+constexpr int kF32_Skinny = kF32_Vector + 1;        // candidate number, after the vector kernels
+constexpr int kSkinnyMaxParts = 256;
+struct SkinnyArgs {
+    const float *A;
+    int64_t lda;
+    const float *B;
+    int64_t ldb;
+    int M, N, K;
+    int parts;
+    float *partial;
+};
+bool skinny_fits(int64_t M, int64_t N);
+bool skinny_offsets_fit(const SkinnyArgs &a);
+const char *skinny_kernel_name(int M, int N);
+hipError_t launch_skinny_f32(const SkinnyArgs &a, float *C, int64_t ldc, hipStream_t s);
+
 // fp32 transposition (transpose.hip)
 const char *transpose_kernel_name(int rows, int cols);
 hipError_t launch_transpose_f32(const float *A, int64_t lda, float *T, int64_t ldt, int rows, int cols, hipStream_t s);

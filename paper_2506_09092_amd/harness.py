@@ -76,7 +76,7 @@ def _run_ws(lib, kind: str, transA, transB, A, B, workspace_bytes, lda, ldb, ldc
     if forced is not None:          # (tile, k_slices): the *_cfg entry point with exactly the workspace its split needs
         gemm_cfg = lib.gemm_f32_cfg if kind == "f32" else lib.gemm_bf16_cfg
         gemm = lambda *args: gemm_cfg(forced[0], forced[1], *args)
-        workspace_bytes = forced[1] * M * N * 4 if forced[1] > 1 else 0
+        workspace_bytes = forced[1] * M * N * 4 if forced[1] > 1 or (kind == "f32" and forced[0] == 4) else 0
     if workspace_bytes is None:
         workspace_bytes = query(transA, transB, M, N, K)
     guard = 64

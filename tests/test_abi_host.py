@@ -156,9 +156,9 @@ def test_f32_tile_rule_follows_the_round_model():
 
 def test_forced_configurations_and_plan_queries():
     bad, ok = lib.FSRGEMM_ERR_INVALID_ARG, lib.FSRGEMM_OK
-    assert lib.fsrgemm_tile_count_f32() == 4 and lib.fsrgemm_tile_count_bf16() == 4
+    assert lib.fsrgemm_tile_count_f32() == 5 and lib.fsrgemm_tile_count_bf16() == 4
     f = lambda tile, s, ws=None, wsb=0, M=64, N=64, K=4096: lib.gemm_f32_cfg(tile, s, 0, 0, M, N, K, P, K, P, N, P, N, ws, wsb, 0)
-    assert f(-1, 1) == bad and f(4, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
+    assert f(-1, 1) == bad and f(5, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
     assert f(3, 1) == bad and f(3, 1, K=0, M=1) == bad                          # the vector kernels need M or N = 1 and K > 0
     assert f(2, 4) == bad and f(2, 4, P, 4 * 64 * 64 * 4 - 1) == bad            # a split without / with too small a workspace
     assert f(2, 4, P + 2, 1 << 20) == bad                                      # misaligned workspace
@@ -175,11 +175,28 @@ def test_forced_configurations_and_plan_queries():
     # names of forced candidates; None where the forced call would reject the candidate
     qc, qh = lib.fsrgemm_kernel_for_f32_cfg, lib.fsrgemm_kernel_for_bf16_cfg
     assert qc(0, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) == "gemm_f32_kernel<4, 2, 2, 2, 0, 1>"        # the largest tile on a tiny unaligned problem
-    assert qc(3, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) is None and qc(4, 0, 0, 1, 10, 10, P, 10, P, 10, P, 10) is None
+    assert qc(3, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) is None and qc(5, 0, 0, 1, 10, 10, P, 10, P, 10, P, 10) is None
     assert qc(3, 0, 0, 1, 16, 16, P, 16, P, 16, P, 16) == "gemv_cols_f32_kernel<true>"
     assert qh(0, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) == "gemm_bf16_main_kernel<0, 0>"
     assert qh(0, 0, 1, 520, 392, 100, P, 104, P, 104, P, 392) is None and qh(4, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) is None
     assert qh(1, 1, 0, 8, 8, 8, P, 8, P, 8, P, 8) == "gemm_bf16_kernel<4, 1, 1, 1, 1>"
+    # candidate 4: small results of long sums; its slices are workgroups, each with a partial result in the workspace
+    sk = lambda M, N, K, s, ws=P, wsb=1 << 20: lib.gemm_f32_cfg(4, s, 1, 0, M, N, K, P, M, P, N, P, N, ws, wsb, 0)
+    assert sk(17, 4, 4096, 4) == bad and sk(12, 16, 4096, 4) == bad and sk(64, 64, 4096, 4) == bad      # no register block that large
+    assert sk(10, 10, 4096, 0) == bad and sk(10, 10, 4096, 257) == bad and sk(10, 10, 8, 9) == bad       # parts: 1..256, at most K
+    assert sk(10, 10, 4096, 1, None, 0) == bad and sk(10, 10, 4096, 4, P, 4 * 100 * 4 - 1) == bad        # always needs its workspace
+    assert sk(0, 10, 4096, 4) == ok
+    assert qc(4, 1, 0, 10, 10, 1 << 20, P, 10, P, 10, P, 10) == "gemm_f32_skinny_kernel<12, 12>"
+    assert qc(4, 1, 0, 10, 1, 1 << 20, P, 10, P, 1, P, 1) == "gemm_f32_skinny_kernel<12, 4>"
+    assert qc(4, 1, 0, 16, 8, 64, P, 16, P, 8, P, 8) == "gemm_f32_skinny_kernel<16, 8>" and qc(4, 1, 0, 16, 9, 64, P, 16, P, 9, P, 9) is None
+    assert qc(4, 0, 0, 16, 8, 64, P, 64, P, 8, P, 8) is None                    # only for operands stored with k as the row index
+    assert lib.gemm_f32_cfg(4, 4, 0, 0, 10, 10, 4096, P, 4096, P, 10, P, 10, P, 1 << 20, 0) == bad
+    assert sk(10, 10, 1 << 30, 1, P, 1 << 20) == bad                            # one piece that long does not fit 32-bit lane offsets
+    # the dispatcher takes it for such shapes when the call brings a workspace: the normal equations of least squares
+    pfw = lambda M, N, K: lib.fsrgemm_plan_f32(1, 0, M, N, K, P, M, P, N, True)
+    assert pfw(10, 10, 1 << 22) == (4, 256) and pfw(10, 1, 1 << 14) == (4, 8) and pfw(10, 10, 4095)[0] != 4
+    assert lib.fsrgemm_plan_f32(1, 0, 10, 10, 1 << 22, P, 10, P, 10, False) == (2, 1)
+    assert lib.gemm_f32_workspace_bytes(1, 0, 10, 10, 1 << 22) == 256 * 100 * 4 and lib.gemm_f32_workspace_bytes(1, 0, 10, 1, 4096) == 2 * 10 * 4
     # plan queries: the rules, in the terms of the forced calls
     pf, pb = lib.fsrgemm_plan_f32, lib.fsrgemm_plan_bf16
     assert pf(0, 0, 4096, 4096, 4096, P, 4096, P, 4096) == (0, 1) and pf(0, 0, 200, 200, 200, P, 200, P, 200) == (2, 1)
@@ -195,6 +212,7 @@ def test_forced_configurations_and_plan_queries():
     assert pf(0, 0, 4096, 1, 4096, P, 4096, P, 1, True) == (3, 1)               # 1024 workgroups of 4 rows already
     assert pf(0, 0, 1, 1024, 1024, P, 1024, P, 1024, True) == (3, 1)            # too short to pay for a second launch
     assert pf(0, 0, 1, 1, 1 << 20, P, 1 << 20, P, 1, True) == (3, 64) and pf(0, 0, 1, 4096, 0, P, 1, P, 4096) == (2, 1)
+    assert pf(1, 0, 1, 1, 1 << 20, P, 1, P, 1, True) == (4, 256)                # both vectors stored as columns: the small-result kernel
     qv = lib.fsrgemm_kernel_for_f32_ex
     assert qv(0, 0, 4096, 1, 4096, P, 4096, P, 1, P, 1) == "gemv_rows_f32_kernel<true>"
     assert qv(0, 0, 1, 4096, 4096, P, 4096, P, 4096, P, 4096) == "gemv_cols_f32_kernel<true>"

@@ -655,6 +655,59 @@ def test_f32_vector_every_slice_count(gpu):
         run_cfg(gpu, "f32", 3, 1, 0, 0, inputs.uniform_pm1(14, 5, 2, 64), inputs.uniform_pm1(14, 6, 64, 2))
 
 
+# ---- small results of long sums (the normal equations of the paper's Task 20) ----
+
+@pytest.mark.parametrize("M,N,K", [(10, 10, 1 << 14), (10, 1, 1 << 16), (1, 1, 100003), (16, 8, 5000), (7, 16, 4097),
+                                   (12, 12, 8192), (3, 5, 70000), (4, 4, 4096)])
+def test_f32_small_result_long_sum(gpu, M, N, K):
+    A, B = inputs.uniform_pm1(16, 1, M, K), inputs.uniform_pm1(16, 2, K, N)
+    ref, S = oracle.gemm(A, B)
+    for ta, tb in [(0, 0)] + LAYOUTS:
+        say("f32 small result %dx%dx%d storage %d%d" % (M, N, K, ta, tb))
+        # the dedicated kernel takes operands stored with k as the row index (a transposed A, a row-major B)
+        tall = (ta, tb) == (1, 0)
+        assert (gpu.fsrgemm_plan_f32(ta, tb, M, N, K, 0x1000, M if ta else K, 0x1000, K if tb else N, True)[0] == 4) == tall
+        got = run_f32_ws(gpu, ta, tb, A, B, repeat=2)                   # the dispatcher's choice, canaried workspace of the size it asks for
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        lda, ldb = (M if ta else K) + 3, (K if tb else N) + 2
+        got = run_f32_ws(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 3, offset=1, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        for parts in (1, 3, 256):
+            if tall:
+                got = run_cfg(gpu, "f32", 4, parts, ta, tb, A, B, repeat=2)
+                assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+            else:
+                with pytest.raises(gpu.FsrGemmError):
+                    run_cfg(gpu, "f32", 4, parts, ta, tb, A, B)
+    if K <= 4097:
+        Ai, Bi = inputs.small_ints(0, 13, M, K), inputs.small_ints(0, 14, K, N)
+        assert np.array_equal(run_f32_ws(gpu, 1, 0, Ai, Bi).astype(np.float64), oracle.gemm(Ai, Bi)[0])
+    with pytest.raises(gpu.FsrGemmError):
+        run_cfg(gpu, "f32", 4, 4, 1, 0, inputs.uniform_pm1(16, 3, 17, 64), inputs.uniform_pm1(16, 4, 64, 4))
+
+
+def test_f32_normal_equations(gpu):
+    # X^T X and X^T y for a tall X (the paper's Task 20 at its smallest size), A and B the same buffer for the first
+    import torch
+
+    n, f = 1 << 14, 10
+    X, y = inputs.uniform_pm1(16, 5, n, f), inputs.uniform_pm1(16, 6, n, 1)
+    refG, SG = oracle.gemm(np.ascontiguousarray(X.T), X)
+    refg, Sg = oracle.gemm(np.ascontiguousarray(X.T), y)
+    xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    G, g = torch.full((f, f), float("nan"), device="cuda"), torch.full((f, 1), float("nan"), device="cuda")
+    need = max(gpu.gemm_f32_workspace_bytes(1, 0, f, f, n), gpu.gemm_f32_workspace_bytes(1, 0, f, 1, n))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    gpu.check(gpu.gemm_f32_ws(1, 0, f, f, n, xd, f, xd, f, G, f, ws, need, st))
+    gpu.check(gpu.gemm_f32_ws(1, 0, f, 1, n, xd, f, yd, 1, g, 1, ws, need, st))
+    torch.cuda.synchronize()
+    assert oracle.componentwise_error(G.cpu().numpy(), refG, SG) <= TOL_F32
+    assert oracle.componentwise_error(g.cpu().numpy(), refg, Sg) <= TOL_F32
+    assert np.array_equal(G.cpu().numpy(), G.cpu().numpy().T)            # the same sums in the same order on both sides of the diagonal
+    assert np.array_equal(run_f32_ws(gpu, 1, 0, np.ascontiguousarray(X.T), X).view(np.uint32), G.cpu().numpy().view(np.uint32))   # separate buffers: same bits
+
+
 # ---- forced configurations: every candidate of the selection loop is a correct product ----
 
 @pytest.mark.parametrize("shape,ta,tb", [((300, 520, 1000), 0, 0), ((512, 384, 2048), 0, 0), ((64, 64, 4097), 0, 0),
