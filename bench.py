@@ -289,6 +289,29 @@ def transpose_sizes(lib, torch):
     return out
 
 
+def normal_equations(lib, torch):
+    """The normal equations of the paper's Task 20 (ordinary least squares: X of n_samples x 10 features, sizes
+    2^14 .. 2^22 as in the appendix table): G = X^T X and g = X^T y as two calls of gemm_f32_ws with X as a
+    transposed A.  Both stream X from HBM once: 4 n f bytes for G (A and B are the same buffer), 4 n (f + 1) for g."""
+    stream = torch.cuda.current_stream().cuda_stream
+    f, out = 10, []
+    for e in (14, 16, 18, 20, 22):
+        n = 1 << e
+        X, y = torch.randn(n, f, device="cuda"), torch.randn(n, 1, device="cuda")
+        G, g = torch.empty(f, f, device="cuda"), torch.empty(f, 1, device="cuda")
+        need = max(lib.gemm_f32_workspace_bytes(1, 0, f, f, n), lib.gemm_f32_workspace_bytes(1, 0, f, 1, n))
+        ws = torch.empty(max(need, 4), dtype=torch.uint8, device="cuda")
+        t_gram = steady_ms(torch, lambda: lib.check(lib.gemm_f32_ws(1, 0, f, f, n, X, f, X, f, G, f, ws, need, stream)))
+        t_xty = steady_ms(torch, lambda: lib.check(lib.gemm_f32_ws(1, 0, f, 1, n, X, f, y, 1, g, 1, ws, need, stream)))
+        t_plain = steady_ms(torch, lambda: lib.check(lib.gemm_f32_ex(1, 0, f, f, n, X, f, X, f, G, f, stream)), samples=3, warm_ms=5.0)
+        out.append({"n_samples": n, "kernel": lib.fsrgemm_kernel_for_f32_cfg(4, 1, 0, f, f, n, X, f, X, f, G, f),
+                    "gram_ms": t_gram, "gram_GBps": 4.0 * n * f / t_gram / 1e6, "gram_frac_of_8TBps": 4.0 * n * f / t_gram / 8e9,
+                    "xty_ms": t_xty, "xty_GBps": 4.0 * n * (f + 1) / t_xty / 1e6, "xty_frac_of_8TBps": 4.0 * n * (f + 1) / t_xty / 8e9,
+                    "gram_ms_without_workspace": t_plain})
+        del X, y
+    return out
+
+
 def validator_pass_in_a_graph(lib, torch, passes=20):
     """One validator pass = the 64 shapes of the fp32 sweep, launched back to back: issued call by call against
     one replay of a HIP graph that captured the same 64 calls (the library allocates nothing and launches plain
@@ -434,7 +457,7 @@ def main():
         del w
         torch.cuda.empty_cache()
 
-    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = small = None
+    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = small = task20 = None
     if not args.headline_only:
         small = small_fixed_configs(lib, torch)
         task2 = paper_task2_sizes(lib, torch)
@@ -443,6 +466,7 @@ def main():
         skinny = split_k(lib, torch, "f32")
         skinny_bf16 = split_k(lib, torch, "bf16")
         task8 = transpose_sizes(lib, torch)
+        task20 = normal_equations(lib, torch)
         graph = validator_pass_in_a_graph(lib, torch)
         if not args.no_validate:
             log("selection loop on three problems")
@@ -477,6 +501,7 @@ def main():
         "split_k_f32": skinny,
         "split_k_bf16": skinny_bf16,
         "paper_task8_transpose": task8,
+        "paper_task20_normal_equations": task20,
         "selection_loop": selection,
         "validator_pass_fp32_sweep": graph,
         "paper_context": "paper reports only speedups over hand-written CUDA for the group holding Task 2: 5.95-68.3x (RTX 3090 Ti), 6.06-60.0x (GTX 1660 SUPER)",

@@ -15,6 +15,8 @@
 // B stored K x N, i.e. a transposed A and a row-major B).  Along k the lanes of a wavefront read consecutive rows,
 // 64 rows being one contiguous run of memory for a tightly packed operand.  Other storage orders of such shapes
 // stay with the split tile kernels.
+#include <stdio.h>
+
 #include "launchers.hpp"
 
 namespace fsrgemm {
@@ -23,7 +25,10 @@ namespace {
 
 constexpr int kThreads = 256;
 
-template <int MB, int NB>
+bool skinny_reads_pairs(const SkinnyArgs &a) { return (reinterpret_cast<uintptr_t>(a.A) & 7u) == 0 && a.lda % 2 == 0; }
+
+// APAIR: A's rows start 8-byte aligned (base and leading dimension even), so a row is read as pairs
+template <int MB, int NB, bool APAIR>
 __global__ __launch_bounds__(kThreads) void gemm_f32_skinny_kernel(SkinnyArgs g)
 {
     constexpr int V = MB * NB;                      // private sums per lane
@@ -52,10 +57,21 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_skinny_kernel(SkinnyArgs g)
     auto row = [&](int kk, float (&a)[MB], float (&b)[NB]) {
         const float *__restrict__ ar = A + (uint32_t)kk * lda;
         const float *__restrict__ br = B + (uint32_t)kk * ldb;
+        if constexpr (APAIR) {
+            // an odd M reads one element of the row's padding (the leading dimension is even, so it is there)
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            const float v = ar[min(i, g.M - 1)];
-            a[i] = i < g.M ? v : 0.f;
+            for (int i = 0; i < MB; i += 2) {
+                const f32x2 v = *reinterpret_cast<const f32x2 *>(ar + min(i, (g.M - 1) & ~1));
+                a[i] = i < g.M ? v[0] : 0.f;
+                a[i + 1] = i + 1 < g.M ? v[1] : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                const float v = ar[min(i, g.M - 1)];
+                a[i] = i < g.M ? v : 0.f;
+            }
         }
         if constexpr (MB == NB) {
             if (gram) {
@@ -132,7 +148,8 @@ __global__ __launch_bounds__(64) void skinny_reduce_kernel(const float *__restri
 template <int MB, int NB>
 hipError_t launch(const SkinnyArgs &a, hipStream_t s)
 {
-    hipLaunchKernelGGL((gemm_f32_skinny_kernel<MB, NB>), dim3((unsigned)a.parts), dim3(kThreads), 0, s, a);
+    if (skinny_reads_pairs(a)) hipLaunchKernelGGL((gemm_f32_skinny_kernel<MB, NB, true>), dim3((unsigned)a.parts), dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((gemm_f32_skinny_kernel<MB, NB, false>), dim3((unsigned)a.parts), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
@@ -162,15 +179,25 @@ bool skinny_fits(int64_t M, int64_t N)
     return M >= 1 && N >= 1 && M <= 16 && N <= 16 && round4((int)M) * round4((int)N) <= 144;
 }
 
-// <MB, NB> as a profiler trace prints the kernel
-const char *skinny_kernel_name(int M, int N)
+// <MB, NB, A read as pairs> as a profiler trace prints the kernel
+const char *skinny_kernel_name(int M, int N, const float *A, int64_t lda)
 {
-    static const char *names[4][4] = {
-        {"gemm_f32_skinny_kernel<4, 4>", "gemm_f32_skinny_kernel<4, 8>", "gemm_f32_skinny_kernel<4, 12>", "gemm_f32_skinny_kernel<4, 16>"},
-        {"gemm_f32_skinny_kernel<8, 4>", "gemm_f32_skinny_kernel<8, 8>", "gemm_f32_skinny_kernel<8, 12>", "gemm_f32_skinny_kernel<8, 16>"},
-        {"gemm_f32_skinny_kernel<12, 4>", "gemm_f32_skinny_kernel<12, 8>", "gemm_f32_skinny_kernel<12, 12>", nullptr},
-        {"gemm_f32_skinny_kernel<16, 4>", "gemm_f32_skinny_kernel<16, 8>", nullptr, nullptr}};
-    return skinny_fits(M, N) ? names[round4(M) / 4 - 1][round4(N) / 4 - 1] : nullptr;
+    struct Names {
+        char text[4][4][2][48];
+        Names()
+        {
+            for (int i = 0; i < 4; ++i)
+                for (int j = 0; j < 4; ++j)
+                    for (int p = 0; p < 2; ++p)
+                        snprintf(text[i][j][p], sizeof text[i][j][p], "gemm_f32_skinny_kernel<%d, %d, %s>", 4 * i + 4, 4 * j + 4,
+                                 p ? "true" : "false");
+        }
+    };
+    static const Names names;
+    if (!skinny_fits(M, N)) return nullptr;
+    SkinnyArgs a;
+    a.A = A, a.lda = lda;
+    return names.text[round4(M) / 4 - 1][round4(N) / 4 - 1][skinny_reads_pairs(a)];
 }
 
 // the lane offsets inside one piece of K are 32-bit: the farthest element of a piece must stay below 2^29
