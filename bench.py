@@ -312,30 +312,45 @@ def normal_equations(lib, torch):
     return out
 
 
-def validator_pass_in_a_graph(lib, torch, passes=20):
-    """One validator pass = the 64 shapes of the fp32 sweep, launched back to back: issued call by call against
-    one replay of a HIP graph that captured the same 64 calls (the library allocates nothing and launches plain
-    kernels only, so its calls can be captured).  Time per pass in ms, operands random, tight leading dimensions."""
+def validator_pass_in_a_graph(lib, torch, passes=20, n_streams=4):
+    """One validator pass = the 64 shapes of the fp32 sweep, each launched once (operands random, tight leading
+    dimensions).  Four ways to issue it, time per pass in ms: call by call on one stream; call by call dealt
+    round-robin to four streams (the cases are independent, and most are too small to fill the device); one
+    replay of a HIP graph that captured the one-stream pass; one replay of a graph that captured the four-stream
+    pass (the library allocates nothing and launches plain kernels only, so its calls can be captured)."""
     from paper_2506_09092_amd import inputs
 
-    calls = []
+    cases = []
     for c in inputs.sweep_cases(3, 64):
         M, N, K = c["M"], c["N"], c["K"]
-        a, b, o = torch.randn(M, K, device="cuda"), torch.randn(K, N, device="cuda"), torch.empty(M, N, device="cuda")
-        calls.append(lambda a=a, b=b, o=o, M=M, N=N, K=K: lib.check(
-            lib.gemm_f32(M, N, K, a, K, b, N, o, N, torch.cuda.current_stream().cuda_stream)))
+        cases.append((M, N, K, torch.randn(M, K, device="cuda"), torch.randn(K, N, device="cuda"), torch.empty(M, N, device="cuda")))
+    side = [torch.cuda.Stream() for _ in range(n_streams)]       # default priority
 
-    def one_pass():
-        for f in calls:
-            f()
+    def one_stream():
+        st = torch.cuda.current_stream().cuda_stream
+        for M, N, K, a, b, o in cases:
+            lib.check(lib.gemm_f32(M, N, K, a, K, b, N, o, N, st))
 
-    one_pass()
-    torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        one_pass()
+    def four_streams():
+        main = torch.cuda.current_stream()
+        for s in side:
+            s.wait_stream(main)
+        for i, (M, N, K, a, b, o) in enumerate(cases):
+            lib.check(lib.gemm_f32(M, N, K, a, K, b, N, o, N, side[i % n_streams].cuda_stream))
+        for s in side:
+            main.wait_stream(s)
+
+    def captured(fn):
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g.replay
+
     out = {}
-    for name, fn in (("eager_ms", one_pass), ("graph_ms", graph.replay)):
+    for name, fn in (("one_stream_ms", one_stream), ("four_streams_ms", four_streams),
+                     ("graph_one_stream_ms", captured(one_stream)), ("graph_four_streams_ms", captured(four_streams))):
         fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -343,7 +358,7 @@ def validator_pass_in_a_graph(lib, torch, passes=20):
             fn()
         torch.cuda.synchronize()
         out[name] = (time.perf_counter() - t0) * 1e3 / passes
-    out["launches_per_pass"] = len(calls)
+    out["launches_per_pass"] = len(cases)
     return out
 
 

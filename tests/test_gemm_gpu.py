@@ -537,15 +537,29 @@ def test_calls_captured_in_a_hip_graph_replay_bit_exact(gpu):
     with torch.cuda.graph(graph):
         for f in calls:
             gpu.check(f())
-    for replay in range(3):
-        say("graph replay %d" % replay)
-        for o in outs:
-            o.fill_(float("nan"))            # eager work between the replays
-        torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
-        for o, e in zip(outs, eager):
-            assert torch.equal(o.view(torch.int32), e.view(torch.int32))
+    # the same calls dealt to four streams and captured as parallel branches of one graph
+    side = [torch.cuda.Stream() for _ in range(4)]
+    forked = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(forked):
+        main = torch.cuda.current_stream()
+        for s_ in side:
+            s_.wait_stream(main)
+        for i, f in enumerate(calls[:-1]):
+            with torch.cuda.stream(side[i % 4]):
+                gpu.check(f())
+        for s_ in side:
+            main.wait_stream(s_)
+        gpu.check(calls[-1]())
+    for g, name in ((graph, "one stream"), (forked, "four streams")):
+        for replay in range(3):
+            say("graph (%s) replay %d" % (name, replay))
+            for o in outs:
+                o.fill_(float("nan"))            # eager work between the replays
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for o, e in zip(outs, eager):
+                assert torch.equal(o.view(torch.int32), e.view(torch.int32))
 
 
 # ---- infinities, NaNs, subnormal numbers ----
