@@ -537,7 +537,7 @@ const char *fsrgemm_kernel_for_f32_cfg(int tile, int transA, int transB, int64_t
                                        int64_t lda, const float *B, int64_t ldb, const float *C, int64_t ldc)
 {
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
-    if (tile == kF32_Skinny) return K >= 1 && transA && !transB ? skinny_kernel_name((int)(M < 17 ? M : 17), (int)(N < 17 ? N : 17), A, lda) : nullptr;
+    if (tile == kF32_Skinny) return K >= 1 && transA && !transB ? skinny_kernel_name((int)(M < 17 ? M : 17), (int)(N < 17 ? N : 17), A, lda, B, ldb) : nullptr;
     if (tile < 0 || tile > kF32_Vector || (tile == kF32_Vector && !vector_shape(M, N, K))) return nullptr;
     int mode;
     if (mode_f32(tile, 1, M, N, K, A, lda, B, ldb, &mode) != FSRGEMM_OK) return nullptr;

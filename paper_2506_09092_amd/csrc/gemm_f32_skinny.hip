@@ -26,9 +26,13 @@ namespace {
 constexpr int kThreads = 256;
 
 bool skinny_reads_pairs(const SkinnyArgs &a) { return (reinterpret_cast<uintptr_t>(a.A) & 7u) == 0 && a.lda % 2 == 0; }
+bool skinny_is_gram(const SkinnyArgs &a) { return a.A == a.B && a.M == a.N && a.lda == a.ldb; }
 
-// APAIR: A's rows start 8-byte aligned (base and leading dimension even), so a row is read as pairs
-template <int MB, int NB, bool APAIR>
+// APAIR: A's rows start 8-byte aligned (base and leading dimension even), so a row is read as pairs.
+// GRAM: X^T X -- A and B are the same matrix, so one set of loads serves both, and the result is symmetric, so only
+// j >= i is summed and the rest copied over at the end (the same products in the same order: the copy has the
+// bits the sum would have had).
+template <int MB, int NB, bool APAIR, bool GRAM>
 __global__ __launch_bounds__(kThreads) void gemm_f32_skinny_kernel(SkinnyArgs g)
 {
     constexpr int V = MB * NB;                      // private sums per lane
@@ -44,8 +48,6 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_skinny_kernel(SkinnyArgs g)
     const float *__restrict__ A = g.A + k0 * g.lda;
     const float *__restrict__ B = g.B + k0 * g.ldb;
     const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
-    // X^T X: both operands are the same matrix, so one set of loads serves both
-    const bool gram = MB == NB && g.A == g.B && g.M == g.N && g.lda == g.ldb;
     float acc[MB][NB];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
@@ -73,17 +75,12 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_skinny_kernel(SkinnyArgs g)
                 a[i] = i < g.M ? v : 0.f;
             }
         }
-        if constexpr (MB == NB) {
-            if (gram) {
+        if constexpr (!GRAM) {
 #pragma unroll
-                for (int j = 0; j < NB; ++j) b[j] = a[j];
-                return;
+            for (int j = 0; j < NB; ++j) {
+                const float v = br[min(j, g.N - 1)];
+                b[j] = j < g.N ? v : 0.f;
             }
-        }
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const float v = br[min(j, g.N - 1)];
-            b[j] = j < g.N ? v : 0.f;
         }
     };
     // Whole batches of U rows per lane: all loads of a batch are issued, then its rows are added to the private
@@ -94,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_skinny_kernel(SkinnyArgs g)
 #pragma unroll
         for (int i = 0; i < MB; ++i)
 #pragma unroll
-            for (int j = 0; j < NB; ++j) acc[i][j] = __builtin_fmaf(ar[i], br[j], acc[i][j]);
+            for (int j = GRAM ? i : 0; j < NB; ++j) acc[i][j] = __builtin_fmaf(ar[i], GRAM ? ar[j] : br[j], acc[i][j]);
     };
     int kk = tid;
     for (; kk + (U - 1) * kThreads < len; kk += kBatch) {
@@ -108,6 +105,13 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_skinny_kernel(SkinnyArgs g)
         float ar[MB], br[NB];
         row(kk, ar, br);
         add_row(ar, br);
+    }
+
+    if constexpr (GRAM) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < i; ++j) acc[i][j] = acc[j][i];
     }
 
     // 256 private results -> 1, in a fixed order: CH values at a time every lane parks its sums in LDS, then one
@@ -148,8 +152,16 @@ __global__ __launch_bounds__(64) void skinny_reduce_kernel(const float *__restri
 template <int MB, int NB>
 hipError_t launch(const SkinnyArgs &a, hipStream_t s)
 {
-    if (skinny_reads_pairs(a)) hipLaunchKernelGGL((gemm_f32_skinny_kernel<MB, NB, true>), dim3((unsigned)a.parts), dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((gemm_f32_skinny_kernel<MB, NB, false>), dim3((unsigned)a.parts), dim3(kThreads), 0, s, a);
+    const dim3 grid((unsigned)a.parts), block(kThreads);
+    if constexpr (MB == NB) {
+        if (skinny_is_gram(a)) {
+            if (skinny_reads_pairs(a)) hipLaunchKernelGGL((gemm_f32_skinny_kernel<MB, NB, true, true>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((gemm_f32_skinny_kernel<MB, NB, false, true>), grid, block, 0, s, a);
+            return hipGetLastError();
+        }
+    }
+    if (skinny_reads_pairs(a)) hipLaunchKernelGGL((gemm_f32_skinny_kernel<MB, NB, true, false>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((gemm_f32_skinny_kernel<MB, NB, false, false>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
@@ -179,25 +191,26 @@ bool skinny_fits(int64_t M, int64_t N)
     return M >= 1 && N >= 1 && M <= 16 && N <= 16 && round4((int)M) * round4((int)N) <= 144;
 }
 
-// <MB, NB, A read as pairs> as a profiler trace prints the kernel
-const char *skinny_kernel_name(int M, int N, const float *A, int64_t lda)
+// <MB, NB, A read as pairs, X^T X> as a profiler trace prints the kernel
+const char *skinny_kernel_name(int M, int N, const float *A, int64_t lda, const float *B, int64_t ldb)
 {
     struct Names {
-        char text[4][4][2][48];
+        char text[4][4][2][2][56];
         Names()
         {
             for (int i = 0; i < 4; ++i)
                 for (int j = 0; j < 4; ++j)
                     for (int p = 0; p < 2; ++p)
-                        snprintf(text[i][j][p], sizeof text[i][j][p], "gemm_f32_skinny_kernel<%d, %d, %s>", 4 * i + 4, 4 * j + 4,
-                                 p ? "true" : "false");
+                        for (int q = 0; q < 2; ++q)
+                            snprintf(text[i][j][p][q], sizeof text[i][j][p][q], "gemm_f32_skinny_kernel<%d, %d, %s, %s>", 4 * i + 4,
+                                     4 * j + 4, p ? "true" : "false", q ? "true" : "false");
         }
     };
     static const Names names;
     if (!skinny_fits(M, N)) return nullptr;
     SkinnyArgs a;
-    a.A = A, a.lda = lda;
-    return names.text[round4(M) / 4 - 1][round4(N) / 4 - 1][skinny_reads_pairs(a)];
+    a.A = A, a.lda = lda, a.B = B, a.ldb = ldb, a.M = M, a.N = N;
+    return names.text[round4(M) / 4 - 1][round4(N) / 4 - 1][skinny_reads_pairs(a)][skinny_is_gram(a)];
 }
 
 // the lane offsets inside one piece of K are 32-bit: the farthest element of a piece must stay below 2^29

@@ -67,7 +67,7 @@ struct SkinnyArgs {
 };
 bool skinny_fits(int64_t M, int64_t N);
 bool skinny_offsets_fit(const SkinnyArgs &a);
-const char *skinny_kernel_name(int M, int N, const float *A, int64_t lda);
+const char *skinny_kernel_name(int M, int N, const float *A, int64_t lda, const float *B, int64_t ldb);
 hipError_t launch_skinny_f32(const SkinnyArgs &a, float *C, int64_t ldc, hipStream_t s);
 
 // fp32 transposition (transpose.hip)

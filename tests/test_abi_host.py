@@ -186,10 +186,11 @@ def test_forced_configurations_and_plan_queries():
     assert sk(10, 10, 4096, 0) == bad and sk(10, 10, 4096, 257) == bad and sk(10, 10, 8, 9) == bad       # parts: 1..256, at most K
     assert sk(10, 10, 4096, 1, None, 0) == bad and sk(10, 10, 4096, 4, P, 4 * 100 * 4 - 1) == bad        # always needs its workspace
     assert sk(0, 10, 4096, 4) == ok
-    assert qc(4, 1, 0, 10, 10, 1 << 20, P, 10, P, 10, P, 10) == "gemm_f32_skinny_kernel<12, 12, true>"
-    assert qc(4, 1, 0, 10, 1, 1 << 20, P, 10, P, 1, P, 1) == "gemm_f32_skinny_kernel<12, 4, true>"
-    assert qc(4, 1, 0, 16, 8, 64, P, 16, P, 8, P, 8) == "gemm_f32_skinny_kernel<16, 8, true>" and qc(4, 1, 0, 16, 9, 64, P, 16, P, 9, P, 9) is None
-    assert qc(4, 1, 0, 9, 8, 64, P, 9, P, 8, P, 8) == "gemm_f32_skinny_kernel<12, 8, false>"            # odd leading dimension
+    assert qc(4, 1, 0, 10, 10, 1 << 20, P, 10, P, 10, P, 10) == "gemm_f32_skinny_kernel<12, 12, true, true>"
+    assert qc(4, 1, 0, 10, 1, 1 << 20, P, 10, P, 1, P, 1) == "gemm_f32_skinny_kernel<12, 4, true, false>"
+    assert qc(4, 1, 0, 16, 8, 64, P, 16, P, 8, P, 8) == "gemm_f32_skinny_kernel<16, 8, true, false>" and qc(4, 1, 0, 16, 9, 64, P, 16, P, 9, P, 9) is None
+    assert qc(4, 1, 0, 10, 10, 1 << 20, P, 10, P + 64, 10, P, 10) == "gemm_f32_skinny_kernel<12, 12, true, false>"      # two different matrices
+    assert qc(4, 1, 0, 9, 8, 64, P, 9, P, 8, P, 8) == "gemm_f32_skinny_kernel<12, 8, false, false>"            # odd leading dimension
     assert qc(4, 0, 0, 16, 8, 64, P, 64, P, 8, P, 8) is None                    # only for operands stored with k as the row index
     assert lib.gemm_f32_cfg(4, 4, 0, 0, 10, 10, 4096, P, 4096, P, 10, P, 10, P, 1 << 20, 0) == bad
     assert sk(10, 10, 1 << 30, 1, P, 1 << 20) == bad                            # one piece that long does not fit 32-bit lane offsets
