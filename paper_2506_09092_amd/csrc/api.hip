@@ -50,7 +50,8 @@ constexpr Tuned kTuned[] = {
 const Tuned *find_tuned(int kind, int transA, int transB, int64_t M, int64_t N, int64_t K, bool ws)
 {
     for (const Tuned &t : kTuned)
-        if (t.kind == kind && t.M == M && t.N == N && t.K == K && t.transA == (transA != 0) && t.transB == (transB != 0) &&
+        if (t.kind == kind && (ws || t.slices == 1) && (ws || kind != 0 || t.tile != kF32_Skinny) &&      // never a row that needs a workspace for a call without one
+             t.M == M && t.N == N && t.K == K && t.transA == (transA != 0) && t.transB == (transB != 0) &&
             t.ws == (int)ws)
             return &t;
     return nullptr;
@@ -170,9 +171,10 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
     const Tuned *t = use_table ? find_tuned(0, transA, transB, M, N, K, split) : nullptr;
     const bool vector = vector_shape(M, N, K);
     if (!t && split && transA && !transB && skinny_fits(M, N) && K >= 4096 && 2048 * lda < (1 << 29) && 2048 * ldb < (1 << 29)) {
-        // a small result of long sums: one workgroup per 2048 k, each with a partial result in the workspace
+        // a small result of long sums: one workgroup per 256 k (a row per lane) up to one per compute unit, each
+        // with a partial result in the workspace
         p->cfg = kF32_Skinny;
-        p->slices = (int)(K / 2048 < kSkinnyMaxParts ? K / 2048 : kSkinnyMaxParts);
+        p->slices = (int)(K / 256 < kSkinnyMaxParts ? K / 256 : kSkinnyMaxParts);
     } else if (!t && vector) {
         const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
         p->cfg = kF32_Vector;

@@ -113,6 +113,9 @@ class DeviceBackend:
             self.sets.append((a0.clone(), b0.clone(), torch.empty(p.M, p.N, device="cuda")))
         self.lda, self.ldb = hostA.shape[1], hostB.shape[1]
         self.ws = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
+        # set for a search on behalf of callers that bring a workspace: then every candidate is offered it (one
+        # that needs none ignores it), otherwise only the split ones, which cannot run without
+        self.offer_workspace = False
         self.fn = lib.gemm_f32_cfg if p.kind == "f32" else lib.gemm_bf16_cfg
         self.tile_count = lib.fsrgemm_tile_count_f32() if p.kind == "f32" else lib.fsrgemm_tile_count_bf16()
         plan = lib.fsrgemm_plan_f32 if p.kind == "f32" else lib.fsrgemm_plan_bf16
@@ -124,7 +127,7 @@ class DeviceBackend:
     def _call(self, c: Candidate, s: int) -> int:
         p, (a, b, out) = self.p, self.sets[s]
         return self.fn(c.tile, c.slices, p.transA, p.transB, p.M, p.N, p.K, a, self.lda, b, self.ldb, out, p.N,
-                       self.ws if c.slices > 1 else None, self.ws.numel() if c.slices > 1 else 0,
+                       *((self.ws, self.ws.numel()) if self.offer_workspace or c.slices > 1 else (None, 0)),
                        self.torch.cuda.current_stream().cuda_stream)
 
     def runs(self, c: Candidate) -> bool:

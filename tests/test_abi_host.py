@@ -196,9 +196,9 @@ def test_forced_configurations_and_plan_queries():
     assert sk(10, 10, 1 << 30, 1, P, 1 << 20) == bad                            # one piece that long does not fit 32-bit lane offsets
     # the dispatcher takes it for such shapes when the call brings a workspace: the normal equations of least squares
     pfw = lambda M, N, K: lib.fsrgemm_plan_f32(1, 0, M, N, K, P, M, P, N, True)
-    assert pfw(10, 10, 1 << 22) == (4, 256) and pfw(10, 1, 1 << 14) == (4, 8) and pfw(10, 10, 4095)[0] != 4
+    assert pfw(10, 10, 1 << 22) == (4, 256) and pfw(10, 1, 1 << 14) == (4, 64) and pfw(10, 10, 4095)[0] != 4
     assert lib.fsrgemm_plan_f32(1, 0, 10, 10, 1 << 22, P, 10, P, 10, False) == (2, 1)
-    assert lib.gemm_f32_workspace_bytes(1, 0, 10, 10, 1 << 22) == 256 * 100 * 4 and lib.gemm_f32_workspace_bytes(1, 0, 10, 1, 4096) == 2 * 10 * 4
+    assert lib.gemm_f32_workspace_bytes(1, 0, 10, 10, 1 << 22) == 256 * 100 * 4 and lib.gemm_f32_workspace_bytes(1, 0, 10, 1, 4096) == 16 * 10 * 4
     # plan queries: the rules, in the terms of the forced calls
     pf, pb = lib.fsrgemm_plan_f32, lib.fsrgemm_plan_bf16
     assert pf(0, 0, 4096, 4096, 4096, P, 4096, P, 4096) == (0, 1) and pf(0, 0, 200, 200, 200, P, 200, P, 200) == (2, 1)
@@ -239,7 +239,8 @@ def test_tuned_table_rows_are_well_formed():
     for kind, ta, tb, M, N, K, ws, tile, slices in rows:
         assert kind in (0, 1) and ta in (0, 1) and tb in (0, 1) and ws in (0, 1) and M > 0 and N > 0 and K > 0
         assert 0 <= tile < (lib.fsrgemm_tile_count_bf16() if kind else lib.fsrgemm_tile_count_f32())
-        assert 1 <= slices <= 64 and (ws == 1 or slices == 1) and slices * M * N * 4 <= (16 << 20 if slices > 1 else 1 << 62)
+        assert 1 <= slices <= 256 and (ws == 1 or slices == 1) and slices * M * N * 4 <= (16 << 20 if slices > 1 else 1 << 62)
+        assert ws == 1 or not (kind == 0 and tile == 4)                   # the small-result kernel cannot serve a call without a workspace
         plan = (lib.fsrgemm_plan_bf16 if kind else lib.fsrgemm_plan_f32)(ta, tb, M, N, K, P, M if ta else K, P, K if tb else N, bool(ws))
         assert plan == (tile, slices), (plan, (tile, slices))
         rules = (lib.fsrgemm_plan_bf16 if kind else lib.fsrgemm_plan_f32)(ta, tb, M, N, K, P, M if ta else K, P, K if tb else N, bool(ws), True)

@@ -37,6 +37,10 @@ BF16 = [(n, n, n) for n in (512, 1024, 1536, 2048, 2560, 3072, 3584, 4096, 5120,
        [(1, 8192, 8192), (16, 8192, 8192), (256, 256, 65536), (512, 512, 16384)]
 
 
+# the normal equations of the paper's Task 20: X^T X and X^T y for X of n x 10 (a transposed A against a row-major B)
+F32_TALL = [(10, 10, 1 << e) for e in (14, 18, 22)] + [(10, 1, 1 << e) for e in (14, 18, 22)]
+
+
 def host_operands(p: Problem, seed: int):
     if p.kind == "f32":
         A, B = inputs.uniform_pm1(seed, 1, p.M, p.K), inputs.uniform_pm1(seed, 2, p.K, p.N)
@@ -74,6 +78,7 @@ def tune(lib, torch, p: Problem, gain: float, log):
     rows, report = [], dict(problem=p._asdict())
     for with_ws in (False, True):
         start, rules = (be.start, be.rules) if with_ws else (be.start_unsplit, be.rules_unsplit)
+        be.offer_workspace = with_ws
         r = fsr_search.search(start, be.tile_count, be.runs, lambda c: validator(be.output(c)), be.latency,
                               rounds=3, per_round=4, max_slices=fsr_search.MAX_SLICES if with_ws else 1, log=log)
         best = r["best"]
@@ -111,6 +116,7 @@ def main():
         print(msg, flush=True)
 
     problems = [Problem("f32", 0, 0, *s) for s in F32 if args.only in (None, "f32")] + \
+               [Problem("f32", 1, 0, *s) for s in F32_TALL if args.only in (None, "f32")] + \
                [Problem("bf16", 0, 1, *s) for s in BF16 if args.only in (None, "bf16")]
     rows, reports = [], []
     for p in problems:
