@@ -156,7 +156,7 @@ int gemm_bf16_ws(int transA, int transB,
  * generated kernels.
  *   tile: fp32  0 = 256 x 128, 1 = 128 x 128, 2 = 64 x 64 output tile per workgroup, 3 = the streaming kernels for
  *               M == 1 or N == 1 with K > 0, which use no matrix cores, 4 = the kernel for small results of long
- *               sums (transA != 0 and transB == 0, i.e. both operands stored with k as the row index; M, N <= 16 with
+ *               sums (both operands stored with k as the row index: transA != 0 or M == 1, transB == 0 or N == 1; M, N <= 16 with
  *               at most 144 entries after rounding both up to multiples of 4; K > 0), whose
  *               k_slices are workgroups (1..256, at most K) that each keep a partial result in the workspace, so it
  *               needs its workspace even for one (fsrgemm_tile_count_f32() = 5);

@@ -164,13 +164,26 @@ int vector_slices(int pattern, int64_t len, int64_t K)
 
 bool vector_shape(int64_t M, int64_t N, int64_t K) { return (M == 1 || N == 1) && M > 0 && N > 0 && K > 0; }
 
+// The small-result kernel wants both operands stored with k as the row index: a transposed A (K x M) and a
+// row-major B (K x N).  A vector is that in either storage order: a 1 x K row is a K x 1 column with leading
+// dimension 1.  Sets the leading dimensions the kernel is to use.
+bool tall_storage(int transA, int transB, int64_t M, int64_t N, int64_t lda, int64_t ldb, int64_t *lda_t, int64_t *ldb_t)
+{
+    if (!(transA || M == 1) || !(!transB || N == 1)) return false;
+    *lda_t = transA ? lda : 1;
+    *ldb_t = !transB ? ldb : 1;
+    return true;
+}
+
 // `split`: the call brings a workspace.
 int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
              int64_t ldb, bool split, Plan *p, bool use_table = true)
 {
     const Tuned *t = use_table ? find_tuned(0, transA, transB, M, N, K, split) : nullptr;
     const bool vector = vector_shape(M, N, K);
-    if (!t && split && transA && !transB && skinny_fits(M, N) && K >= 4096 && 2048 * lda < (1 << 29) && 2048 * ldb < (1 << 29)) {
+    int64_t lda_t = 0, ldb_t = 0;
+    if (!t && split && skinny_fits(M, N) && K >= 4096 && tall_storage(transA, transB, M, N, lda, ldb, &lda_t, &ldb_t) &&
+        2048 * lda_t < (1 << 29) && 2048 * ldb_t < (1 << 29)) {
         // a small result of long sums: one workgroup per 256 k (a row per lane) up to one per compute unit, each
         // with a partial result in the workspace
         p->cfg = kF32_Skinny;
@@ -290,7 +303,8 @@ int run_f32(const Plan &p, int transA, int transB, int64_t M, int64_t N, int64_t
     if (rc != FSRGEMM_OK) return rc;
     if (p.cfg == kF32_Skinny) {
         SkinnyArgs a;
-        a.A = A, a.lda = lda, a.B = B, a.ldb = ldb;
+        a.A = A, a.B = B;
+        if (!tall_storage(transA, transB, M, N, lda, ldb, &a.lda, &a.ldb)) return FSRGEMM_ERR_INVALID_ARG;
         a.M = (int)M, a.N = (int)N, a.K = (int)K, a.parts = p.slices, a.partial = ws;
         return launch_skinny_f32(a, C, ldc, s) == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
     }
@@ -397,11 +411,11 @@ int gemm_f32_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int6
     if (rc != FSRGEMM_OK) return rc;
     if (tile == kF32_Skinny) {      // its k_slices are workgroups with a partial result each: up to 256, and a workspace even for one
         if (M == 0 || N == 0) return FSRGEMM_OK;
-        if (!transA || transB || !skinny_fits(M, N) || K < 1 || k_slices < 1 || k_slices > kSkinnyMaxParts || k_slices > K ||
-            workspace_bytes < 0 || !workspace_fits(workspace, workspace_bytes, k_slices, M, N))
-            return FSRGEMM_ERR_INVALID_ARG;
         SkinnyArgs probe;
-        probe.lda = lda, probe.ldb = ldb, probe.K = (int)K, probe.parts = k_slices;
+        if (!tall_storage(transA, transB, M, N, lda, ldb, &probe.lda, &probe.ldb) || !skinny_fits(M, N) || K < 1 || k_slices < 1 ||
+            k_slices > kSkinnyMaxParts || k_slices > K || workspace_bytes < 0 || !workspace_fits(workspace, workspace_bytes, k_slices, M, N))
+            return FSRGEMM_ERR_INVALID_ARG;
+        probe.K = (int)K, probe.parts = k_slices;
         if (!skinny_offsets_fit(probe)) return FSRGEMM_ERR_INVALID_ARG;
     } else {
         if (!forced_ok(tile, kF32_Vector + 1, k_slices, M, N, K, 16, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
@@ -539,7 +553,11 @@ const char *fsrgemm_kernel_for_f32_cfg(int tile, int transA, int transB, int64_t
                                        int64_t lda, const float *B, int64_t ldb, const float *C, int64_t ldc)
 {
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
-    if (tile == kF32_Skinny) return K >= 1 && transA && !transB ? skinny_kernel_name((int)(M < 17 ? M : 17), (int)(N < 17 ? N : 17), A, lda, B, ldb) : nullptr;
+    if (tile == kF32_Skinny) {
+        int64_t lda_t, ldb_t;
+        if (K < 1 || !tall_storage(transA, transB, M, N, lda, ldb, &lda_t, &ldb_t)) return nullptr;
+        return skinny_kernel_name((int)(M < 17 ? M : 17), (int)(N < 17 ? N : 17), A, lda_t, B, ldb_t);
+    }
     if (tile < 0 || tile > kF32_Vector || (tile == kF32_Vector && !vector_shape(M, N, K))) return nullptr;
     int mode;
     if (mode_f32(tile, 1, M, N, K, A, lda, B, ldb, &mode) != FSRGEMM_OK) return nullptr;

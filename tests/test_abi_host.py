@@ -191,6 +191,7 @@ def test_forced_configurations_and_plan_queries():
     assert qc(4, 1, 0, 16, 8, 64, P, 16, P, 8, P, 8) == "gemm_f32_skinny_kernel<16, 8, true, false>" and qc(4, 1, 0, 16, 9, 64, P, 16, P, 9, P, 9) is None
     assert qc(4, 1, 0, 10, 10, 1 << 20, P, 10, P + 64, 10, P, 10) == "gemm_f32_skinny_kernel<12, 12, true, false>"      # two different matrices
     assert qc(4, 1, 0, 9, 8, 64, P, 9, P, 8, P, 8) == "gemm_f32_skinny_kernel<12, 8, false, false>"            # odd leading dimension
+    assert qc(4, 0, 0, 1, 8, 64, P, 64, P, 8, P, 8) == "gemm_f32_skinny_kernel<4, 8, false, false>"    # a row vector is tall with leading dimension 1
     assert qc(4, 0, 0, 16, 8, 64, P, 64, P, 8, P, 8) is None                    # only for operands stored with k as the row index
     assert lib.gemm_f32_cfg(4, 4, 0, 0, 10, 10, 4096, P, 4096, P, 10, P, 10, P, 1 << 20, 0) == bad
     assert sk(10, 10, 1 << 30, 1, P, 1 << 20) == bad                            # one piece that long does not fit 32-bit lane offsets
@@ -213,8 +214,10 @@ def test_forced_configurations_and_plan_queries():
     assert pf(0, 0, 1, 4096, 4096, P, 4096, P, 4096, True) == (3, 2)            # 128 workgroups of 32 columns -> 2 slices
     assert pf(0, 0, 4096, 1, 4096, P, 4096, P, 1, True) == (3, 1)               # 1024 workgroups of 4 rows already
     assert pf(0, 0, 1, 1024, 1024, P, 1024, P, 1024, True) == (3, 1)            # too short to pay for a second launch
-    assert pf(0, 0, 1, 1, 1 << 20, P, 1 << 20, P, 1, True) == (3, 64) and pf(0, 0, 1, 4096, 0, P, 1, P, 4096) == (2, 1)
-    assert pf(1, 0, 1, 1, 1 << 20, P, 1, P, 1, True) == (4, 256)                # both vectors stored as columns: the small-result kernel
+    assert pf(0, 0, 1, 17, 1 << 20, P, 1 << 20, P, 17, True) == (3, 64) and pf(0, 0, 1, 4096, 0, P, 1, P, 4096) == (2, 1)
+    # a dot product in any storage order (a vector is tall either way), a row times a tall matrix: the small-result kernel
+    assert pf(0, 0, 1, 1, 1 << 20, P, 1 << 20, P, 1, True) == pf(1, 1, 1, 1, 1 << 20, P, 1, P, 1 << 20, True) == (4, 256)
+    assert pf(0, 0, 1, 10, 1 << 20, P, 1 << 20, P, 10, True) == (4, 256) and pf(0, 1, 1, 10, 1 << 20, P, 1 << 20, P, 1 << 20, True)[0] == 3
     qv = lib.fsrgemm_kernel_for_f32_ex
     assert qv(0, 0, 4096, 1, 4096, P, 4096, P, 1, P, 1) == "gemv_rows_f32_kernel<true>"
     assert qv(0, 0, 1, 4096, 4096, P, 4096, P, 4096, P, 4096) == "gemv_cols_f32_kernel<true>"

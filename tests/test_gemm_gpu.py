@@ -678,8 +678,9 @@ def test_f32_small_result_long_sum(gpu, M, N, K):
     ref, S = oracle.gemm(A, B)
     for ta, tb in [(0, 0)] + LAYOUTS:
         say("f32 small result %dx%dx%d storage %d%d" % (M, N, K, ta, tb))
-        # the dedicated kernel takes operands stored with k as the row index (a transposed A, a row-major B)
-        tall = (ta, tb) == (1, 0)
+        # the dedicated kernel takes operands stored with k as the row index (a transposed A, a row-major B; a vector
+        # is that in either order)
+        tall = bool((ta or M == 1) and (not tb or N == 1))
         assert (gpu.fsrgemm_plan_f32(ta, tb, M, N, K, 0x1000, M if ta else K, 0x1000, K if tb else N, True)[0] == 4) == tall
         got = run_f32_ws(gpu, ta, tb, A, B, repeat=2)                   # the dispatcher's choice, canaried workspace of the size it asks for
         assert oracle.componentwise_error(got, ref, S) <= TOL_F32
