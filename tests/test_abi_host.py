@@ -253,6 +253,23 @@ def test_tuned_table_rows_are_well_formed():
             assert q(ta, tb, M, N, K) == (slices * M * N * 4 if slices > 1 else 0)
 
 
+def test_header_is_plain_c_and_declares_what_the_binding_loads(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 on its own, and every function it declares must be one
+    # the binding knows (and the other way round)
+    import os
+    import re
+    import subprocess
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    header = os.path.join(root, "include", "fsrgemm.h")
+    src = tmp_path / "use.c"
+    src.write_text('#include "fsrgemm.h"\nint main(void) { return gemm_f32(0, 0, 0, 0, 1, 0, 1, 0, 1, 0) == FSRGEMM_OK && fsrgemm_version() > 0 ? 0 : 1; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.dirname(header), "-fsyntax-only", str(src)])
+    text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+    declared = set(re.findall(r"\b(\w+)\s*\(", text)) - {"defined"}
+    assert declared == set(lib.EXPORTS), declared ^ set(lib.EXPORTS)
+
+
 def test_transpose_argument_checks():
     f, bad = lib.transpose_f32, lib.FSRGEMM_ERR_INVALID_ARG
     assert f(-1, 4, P, 4, P, 4, 0) == bad and f(4, -1, P, 4, P, 4, 0) == bad
