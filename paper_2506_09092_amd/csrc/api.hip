@@ -162,7 +162,8 @@ int vector_slices(int pattern, int64_t len, int64_t K)
     return s < 2 ? 1 : (int)s;
 }
 
-bool vector_shape(int64_t M, int64_t N, int64_t K) { return (M == 1 || N == 1) && M > 0 && N > 0 && K > 0; }
+// (K beyond 2^30 stays with the tile kernels: the vector kernels count k in 32-bit steps of up to 1024)
+bool vector_shape(int64_t M, int64_t N, int64_t K) { return (M == 1 || N == 1) && M > 0 && N > 0 && K > 0 && K <= ((int64_t)1 << 30); }
 
 // The small-result kernel wants both operands stored with k as the row index: a transposed A (K x M) and a
 // row-major B (K x N).  A vector is that in either storage order: a 1 x K row is a K x 1 column with leading

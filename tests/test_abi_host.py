@@ -218,6 +218,7 @@ def test_forced_configurations_and_plan_queries():
     # a dot product in any storage order (a vector is tall either way), a row times a tall matrix: the small-result kernel
     assert pf(0, 0, 1, 1, 1 << 20, P, 1 << 20, P, 1, True) == pf(1, 1, 1, 1, 1 << 20, P, 1, P, 1 << 20, True) == (4, 256)
     assert pf(0, 0, 1, 10, 1 << 20, P, 1 << 20, P, 10, True) == (4, 256) and pf(0, 1, 1, 10, 1 << 20, P, 1 << 20, P, 1 << 20, True)[0] == 3
+    assert pf(0, 0, 1, 64, (1 << 30) + 16, P, (1 << 30) + 16, P, 64)[0] == 2        # beyond the vector kernels' 32-bit k arithmetic
     qv = lib.fsrgemm_kernel_for_f32_ex
     assert qv(0, 0, 4096, 1, 4096, P, 4096, P, 1, P, 1) == "gemv_rows_f32_kernel<true>"
     assert qv(0, 0, 1, 4096, 4096, P, 4096, P, 4096, P, 4096) == "gemv_cols_f32_kernel<true>"
