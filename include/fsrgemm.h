@@ -160,13 +160,14 @@ int gemm_bf16_ws(int transA, int transB,
  *               at most 144 entries after rounding both up to multiples of 4; K > 0), whose
  *               k_slices are workgroups (1..256, at most K) that each keep a partial result in the workspace, so it
  *               needs its workspace even for one (fsrgemm_tile_count_f32() = 5);
- *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64
- *               (fsrgemm_tile_count_bf16() = 4).
+ *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64, 4 = the streaming
+ *               kernels for M == 1 or N == 1 with K > 0 (fsrgemm_tile_count_bf16() = 5).
  *   k_slices: 1 = K in one piece; 2..64 = split along K as gemm_f32_ws does, which needs a workspace of
  *         k_slices * M * N * 4 bytes (4-byte aligned, at most 16 MiB) and k_slices <= ceil(K / 16) (fp32) or
  *         ceil(K / 64) (bf16).
  * A candidate that cannot run this problem is FSRGEMM_ERR_INVALID_ARG and launches nothing: a tile or slice
- * count out of range, a split without a fitting workspace, fp32 candidate 3 on a product without a vector,
+ * count out of range, a split without a fitting workspace, fp32 candidate 3 or bf16 candidate 4 on a product
+ * without a vector,
  * fp32 candidate 4 on a result that is too large,
  * bf16 tile 0 with a split or where its kernel's
  * conditions fail (M, N >= 256, K a multiple of 64, 16-byte aligned operands with leading dimensions that are

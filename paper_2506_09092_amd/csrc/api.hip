@@ -122,15 +122,17 @@ int tile_rule_f32(int64_t M, int64_t N)
 }
 
 // How a product with M == 1 or N == 1 maps onto the vector kernels: which operand is the matrix, how it is
-// walked, and the strides of the two vectors.
-struct VecMap {
+// walked, and the strides of the two vectors.  ARGS: VecArgs (fp32) or VecArgs16 (bf16); T the element type.
+template <class ARGS, class T>
+struct VecMapT {
     int pattern;
-    VecArgs a;
+    ARGS a;
 };
-VecMap vector_map(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
-                  int64_t ldb, float *C, int64_t ldc)
+template <class ARGS, class T>
+VecMapT<ARGS, T> vector_map_t(int transA, int transB, int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
+                              int64_t ldb, float *C, int64_t ldc)
 {
-    VecMap v;
+    VecMapT<ARGS, T> v;
     v.a.K = (int)K;
     v.a.k_slices = 1;
     v.a.slice_stride = 0;
@@ -148,16 +150,32 @@ VecMap vector_map(int transA, int transB, int64_t M, int64_t N, int64_t K, const
     }
     return v;
 }
+using VecMap = VecMapT<VecArgs, float>;
+VecMap vector_map(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                  int64_t ldb, float *C, int64_t ldc)
+{
+    return vector_map_t<VecArgs, float>(transA, transB, M, N, K, A, lda, B, ldb, C, ldc);
+}
+using VecMap16 = VecMapT<VecArgs16, uint16_t>;
+VecMap16 vector_map16(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
+                      const uint16_t *B, int64_t ldb, float *C, int64_t ldc)
+{
+    return vector_map_t<VecArgs16, uint16_t>(transA, transB, M, N, K, A, lda, B, ldb, C, ldc);
+}
 
 // Workgroups of the vector kernels for an output of `len` elements, and the K slices of a call with a
-// workspace.  The kernels stream well from about 256 workgroups on, and a split costs a second launch, so K is
-// cut only to reach that many, and never finer than 2048 (measured: a 1 x 4096 x 4096 product gains 15 % from
-// two slices, a 1 x 1024 x 1024 one loses 40 % to any split).
-int64_t vector_groups(int pattern, int64_t len) { return pattern == kVecRows ? ceil_div(len, 4) : ceil_div(len, 32); }
-int vector_slices(int pattern, int64_t len, int64_t K)
+// workspace.  A split costs a second launch, so K is cut only to reach enough workgroups to keep the memory
+// system busy, and never finer than 2048 (1024 for the column pattern): 256 workgroups, or 512 (fp32) / 1024 (bf16)
+// for the column pattern on a matrix of 128 MiB and more, whose workgroups each keep 32 KB in flight (measured: fp32 1 x 4096 x 4096 gains 15 % from two
+// slices, 1 x 1024 x 1024 loses 40 % to any split; bf16 1 x 16384 x 16384 with a row-major B gains 35 % from four).
+int64_t vector_groups(int pattern, int64_t len, int cols_per_group) { return pattern == kVecRows ? ceil_div(len, 4) : ceil_div(len, cols_per_group); }
+int vector_slices(int pattern, int64_t len, int64_t K, int cols_per_group = 32)
 {
-    int64_t s = 256 / vector_groups(pattern, len);
-    if (s > K / 2048) s = K / 2048;
+    const int64_t matrix_bytes = len * K * (cols_per_group == 32 ? 4 : 2);
+    const int64_t target = pattern == kVecCols && matrix_bytes >= ((int64_t)128 << 20) ? (cols_per_group == 64 ? 1024 : 512) : 256;
+    int64_t s = target / vector_groups(pattern, len, cols_per_group);
+    const int64_t shortest = pattern == kVecCols ? 1024 : 2048;
+    if (s > K / shortest) s = K / shortest;
     if (s > kMaxSlices) s = kMaxSlices;
     return s < 2 ? 1 : (int)s;
 }
@@ -224,12 +242,23 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
 {
     const int transA = a_lay == kMnContig, transB = b_lay == kKContig;
     const Tuned *t = use_table ? find_tuned(1, transA, transB, M, N, K, split) : nullptr;
+    if (!t && vector_shape(M, N, K)) {
+        const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
+        p->cfg = kBf16_Vector;
+        p->slices = split ? vector_slices(v.pattern, v.a.len, K, 64) : 1;
+        p->mode = 0;
+        return ceil_div(M > N ? M : N, 4) * p->slices >= ((int64_t)1 << 31) ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_OK;
+    }
     p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 64) : 1;
     if (!t && p->slices == 1 && use_table) t = find_tuned(1, transA, transB, M, N, K, false);
     if (t) p->cfg = t->tile;
     else if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) p->cfg = kBf16_Main;
     else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kBf16_128x128;
     else p->cfg = kBf16_64x64;
+    if (p->cfg == kBf16_Vector) {       // a row of the selection table
+        p->mode = 0;
+        return vector_shape(M, N, K) ? FSRGEMM_OK : FSRGEMM_ERR_INVALID_ARG;
+    }
     int rc = mode_bf16(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
     // where the direct-to-LDS kernel does not fit (alignment, ragged K, a split), the general kernel of its tile runs
     if (rc == FSRGEMM_OK && p->cfg == kBf16_Main && (p->slices > 1 || !main_kernel_fits(a_lay, b_lay, M, N, p->mode, lda, ldb)))
@@ -332,10 +361,17 @@ int run_bf16(const Plan &p, int a_lay, int b_lay, int64_t M, int64_t N, int64_t 
     if (split && p.cfg == kBf16_Main) return FSRGEMM_ERR_INVALID_ARG;     // the planners never pair the two
     const int rc = device_ok();
     if (rc != FSRGEMM_OK) return rc;
-    GemmArgs a = pack(M, N, K, A, lda, B, ldb, split ? ws : C, split ? N : ldc);
-    a.k_slices = p.slices;
-    a.slice_stride = split ? M * N : 0;
-    hipError_t e = launch_bf16(p.cfg, p.mode, a_lay, b_lay, a, s);
+    hipError_t e;
+    if (p.cfg == kBf16_Vector) {
+        VecMap16 v = vector_map16(a_lay == kMnContig, b_lay == kKContig, M, N, K, A, lda, B, ldb, C, ldc);
+        if (split) v.a.y = ws, v.a.incy = 1, v.a.k_slices = p.slices, v.a.slice_stride = v.a.len;
+        e = launch_gemv_bf16(v.pattern, v.a, s);
+    } else {
+        GemmArgs a = pack(M, N, K, A, lda, B, ldb, split ? ws : C, split ? N : ldc);
+        a.k_slices = p.slices;
+        a.slice_stride = split ? M * N : 0;
+        e = launch_bf16(p.cfg, p.mode, a_lay, b_lay, a, s);
+    }
     if (e == hipSuccess && split) e = launch_splitk_reduce(ws, p.slices, M * N, C, (int)M, (int)N, ldc, s);
     return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
 }
@@ -459,9 +495,9 @@ int gemm_bf16_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const 
 int64_t gemm_bf16_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K)
 {
     if (!extents_ok(M, N, K)) return 0;
-    const Tuned *t = find_tuned(1, transA, transB, M, N, K, true);
-    const int slices = t ? t->slices : splitk_slices(M, N, K, 64);
-    return slices > 1 ? (int64_t)slices * M * N * 4 : 0;
+    Plan p;
+    if (plan_bf16(transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, nullptr, 8, nullptr, 8, true, &p) != FSRGEMM_OK) return 0;
+    return p.slices > 1 ? (int64_t)p.slices * M * N * 4 : 0;
 }
 
 int gemm_bf16_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
@@ -488,9 +524,14 @@ int gemm_bf16_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int
 {
     int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
     if (rc != FSRGEMM_OK) return rc;
-    if (!forced_ok(tile, kBf16ConfigCount, k_slices, M, N, K, 64, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
+    if (!forced_ok(tile, kBf16_Vector + 1, k_slices, M, N, K, 64, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
     const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
     Plan p = {tile, 0, k_slices};
+    if (tile == kBf16_Vector) {
+        if (M == 0 || N == 0) return FSRGEMM_OK;
+        if (!vector_shape(M, N, K) || ceil_div(M > N ? M : N, 4) * k_slices >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
+        return run_bf16(p, a_lay, b_lay, M, N, K, A, lda, B, ldb, C, ldc, static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
+    }
     rc = mode_bf16(tile, k_slices, M, N, K, A, lda, B, ldb, &p.mode);
     if (rc != FSRGEMM_OK) return rc;
     // a forced direct-to-LDS kernel is an invalid candidate where it does not fit; nothing else is substituted
@@ -513,7 +554,7 @@ int fsrgemm_plan_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, c
     return FSRGEMM_OK;
 }
 
-int fsrgemm_tile_count_bf16(void) { return kBf16ConfigCount; }
+int fsrgemm_tile_count_bf16(void) { return kBf16_Vector + 1; }
 
 const char *fsrgemm_kernel_for_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
                                    int64_t ldb, const float *C, int64_t ldc)
@@ -547,6 +588,10 @@ const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB, int64_t M, int64_
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
     const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
     if (plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, false, &p) != FSRGEMM_OK) return nullptr;
+    if (p.cfg == kBf16_Vector) {
+        const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
+        return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a));
+    }
     return bf16_kernel_name(p.cfg, p.mode, a_lay, b_lay);
 }
 
@@ -574,6 +619,11 @@ const char *fsrgemm_kernel_for_bf16_cfg(int tile, int transA, int transB, int64_
                                         int64_t ldc)
 {
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
+    if (tile == kBf16_Vector) {
+        if (!vector_shape(M, N, K)) return nullptr;
+        const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
+        return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a));
+    }
     if (tile < 0 || tile >= kBf16ConfigCount) return nullptr;
     const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
     int mode;

@@ -51,6 +51,24 @@ const char *gemv_kernel_name(int pattern, bool vec);
 bool gemv_takes_vectors(const VecArgs &a);
 hipError_t launch_gemv_f32(int pattern, VecArgs a, hipStream_t s);
 
+// the same for bf16 operands (gemv_bf16.hip); y is fp32
+constexpr int kBf16_Vector = kBf16ConfigCount;      // the candidate number of these kernels, after the tile configurations
+struct VecArgs16 {
+    const uint16_t *mat;
+    int64_t ld;
+    const uint16_t *x;
+    int64_t incx;
+    float *y;
+    int64_t incy;
+    int len, K;
+    int k_slices;
+    int64_t slice_stride;
+    bool xvec;
+};
+const char *gemv_bf16_kernel_name(int pattern, bool vec);
+bool gemv_bf16_takes_vectors(const VecArgs16 &a);
+hipError_t launch_gemv_bf16(int pattern, VecArgs16 a, hipStream_t s);
+
 // fp32 products with M, N <= 16 and a long K, both operands stored with k as the row index (gemm_f32_skinny.hip):
 // element (i, k) of A at A[k * lda + i], element (k, j) of B at B[k * ldb + j]; K is cut into `parts` pieces whose
 // partial results go to partial[part][M][N] and are then added into C.

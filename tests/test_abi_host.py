@@ -135,8 +135,18 @@ def test_workspace_query_and_argument_checks():
     assert wb(0, 0, 64, 64, 256) == 0                                 # K too short to cut
     assert wb(0, 0, 4096, 4096, 4096) == 0 and wb(0, 0, 0, 5, 4096) == 0 and wb(0, 0, -1, 5, 4096) == 0
     wh = lib.gemm_bf16_workspace_bytes
-    assert wh(0, 1, 1, 4096, 4096) == 16 * 4096 * 4 and wh(0, 1, 64, 64, 256) == 0 and wh(0, 1, 8192, 8192, 8192) == 0
-    assert wh(0, 1, 1, 16384, 16384) == 4 * 16384 * 4
+    assert wh(0, 1, 8, 4096, 4096) == 16 * 8 * 4096 * 4 and wh(0, 1, 64, 64, 256) == 0 and wh(0, 1, 8192, 8192, 8192) == 0
+    assert wh(0, 1, 8, 16384, 16384) == 4 * 8 * 16384 * 4
+    # a vector on one side: the streaming kernels; one wavefront per matrix row needs no split, 64 columns per workgroup do
+    assert wh(0, 1, 1, 4096, 4096) == 0 and wh(0, 0, 1, 4096, 4096) == 4 * 4096 * 4
+    pb = lib.fsrgemm_plan_bf16
+    assert pb(0, 1, 1, 8192, 8192, P, 8192, P, 8192) == (4, 1) and pb(0, 0, 1, 8192, 8192, P, 8192, P, 8192, True) == (4, 8) and pb(0, 0, 1, 4096, 4096, P, 4096, P, 4096, True) == (4, 4)
+    qb = lib.fsrgemm_kernel_for_bf16_ex
+    assert qb(0, 1, 1, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemv_rows_bf16_kernel<true>"
+    assert qb(0, 0, 1, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemv_cols_bf16_kernel<true>"
+    assert qb(0, 1, 1, 8192, 8196, P, 8196, P, 8196, P, 8192) == "gemv_rows_bf16_kernel<false>"         # rows not 16-byte aligned
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 1, 8192, P, 8192, P, 8192, P, 1) == "gemv_rows_bf16_kernel<true>"
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 2, 8192, P, 8192, P, 8192, P, 2) is None
     bad = lib.FSRGEMM_ERR_INVALID_ARG
     assert lib.gemm_bf16_ws(0, 1, 1, 8, 4096, P, 4096, P, 4096, P, 8, None, 64, 0) == bad
     assert lib.gemm_bf16_ws(0, 1, 1, 8, 4096, P, 4096, P, 4095, P, 8, P, 1 << 20, 0) == bad   # ldb < K
@@ -156,7 +166,7 @@ def test_f32_tile_rule_follows_the_round_model():
 
 def test_forced_configurations_and_plan_queries():
     bad, ok = lib.FSRGEMM_ERR_INVALID_ARG, lib.FSRGEMM_OK
-    assert lib.fsrgemm_tile_count_f32() == 5 and lib.fsrgemm_tile_count_bf16() == 4
+    assert lib.fsrgemm_tile_count_f32() == 5 and lib.fsrgemm_tile_count_bf16() == 5
     f = lambda tile, s, ws=None, wsb=0, M=64, N=64, K=4096: lib.gemm_f32_cfg(tile, s, 0, 0, M, N, K, P, K, P, N, P, N, ws, wsb, 0)
     assert f(-1, 1) == bad and f(5, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
     assert f(3, 1) == bad and f(3, 1, K=0, M=1) == bad                          # the vector kernels need M or N = 1 and K > 0
@@ -171,7 +181,7 @@ def test_forced_configurations_and_plan_queries():
     # the direct-to-LDS candidate is rejected where its kernel's conditions fail, never replaced
     assert g(0, 1, 255, 512, 512) == bad and g(0, 1, 512, 512, 96) == bad and g(0, 1, 512, 512, 512, a=P + 2) == bad
     assert g(0, 1, 512, 512, 512, lda=516) == bad and g(0, 2, 512, 512, 512, ws=P, wsb=1 << 24) == bad
-    assert g(4, 1, 512, 512, 512) == bad and g(1, 1, 0, 512, 512) == ok
+    assert g(4, 1, 512, 512, 512) == bad and g(5, 1, 1, 512, 512) == bad and g(1, 1, 0, 512, 512) == ok     # candidate 4: vector shapes only
     # names of forced candidates; None where the forced call would reject the candidate
     qc, qh = lib.fsrgemm_kernel_for_f32_cfg, lib.fsrgemm_kernel_for_bf16_cfg
     assert qc(0, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) == "gemm_f32_kernel<4, 2, 2, 2, 0, 1>"        # the largest tile on a tiny unaligned problem

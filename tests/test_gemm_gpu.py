@@ -181,7 +181,8 @@ def test_bf16_workspace_split_k(gpu, shape):
     M, N, K = shape
     need = gpu.gemm_bf16_workspace_bytes(0, 1, M, N, K)
     say("bf16 split-K %dx%dx%d workspace %d bytes" % (M, N, K, need))
-    assert need > 0 and need % (4 * M * N) == 0 and need <= 16 << 20
+    vector = M == 1 or N == 1               # the streaming kernels: whether they split depends on the storage order
+    assert (need > 0 or vector) and need % (4 * M * N) == 0 and need <= 16 << 20
     A = inputs.bf16_normal_scaled(4, 50, M, K, 1 / math.sqrt(K))
     B = inputs.bf16_normal_scaled(4, 51, K, N, 1 / math.sqrt(K))
     ref, S = oracle.gemm(A, B)
@@ -191,7 +192,8 @@ def test_bf16_workspace_split_k(gpu, shape):
     got = run_bf16_ws(gpu, 0, 1, A, B, lda=K + 3, ldb=K + 3, ldc=N + 1, offset=1, repeat=2)
     assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
     plain = run_bf16_ex(gpu, 0, 1, A, B)
-    assert np.array_equal(run_bf16_ws(gpu, 0, 1, A, B, workspace_bytes=need - 4).view(np.uint32), plain.view(np.uint32))
+    if need:
+        assert np.array_equal(run_bf16_ws(gpu, 0, 1, A, B, workspace_bytes=need - 4).view(np.uint32), plain.view(np.uint32))
     Ai, Bi = inputs.bf16_small_ints(4, 52, M, K), inputs.bf16_small_ints(4, 53, K, N)
     refi, _ = oracle.gemm(Ai, Bi)
     assert np.array_equal(run_bf16_ws(gpu, 0, 1, Ai, Bi).astype(np.float64), refi)
@@ -615,7 +617,7 @@ def test_bf16_special_values(gpu):
     ref, _ = oracle.gemm(A, B)
     assert np.isnan(ref).any() and np.isfinite(ref).any()
     fin = np.isfinite(ref)
-    for tile in range(gpu.fsrgemm_tile_count_bf16()):
+    for tile in range(4):
         say("bf16 specials tile %d" % tile)
         got = run_cfg(gpu, "bf16", tile, 1, 0, 1, A, B)
         assert _same_class(got, ref) and np.array_equal(got[fin].astype(np.float64), ref[fin])
@@ -654,6 +656,38 @@ def test_f32_vector_shapes(gpu, M, N, K):
         refi, _ = oracle.gemm(Ai, Bi)
         for ta, tb in [(0, 0)] + LAYOUTS:
             assert np.array_equal(run_f32_ws(gpu, ta, tb, Ai, Bi).astype(np.float64), refi)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1000, 3000), (1000, 1, 3000), (1, 4096, 4096), (4096, 1, 4096), (1, 1, 100000),
+                                   (1, 70, 9), (31, 1, 1), (1, 5000, 1032), (4104, 1, 2051), (1, 128, 65536)])
+def test_bf16_vector_shapes(gpu, M, N, K):
+    A = inputs.bf16_normal_scaled(17, 1, M, K, 1 / math.sqrt(K))
+    B = inputs.bf16_normal_scaled(17, 2, K, N, 1 / math.sqrt(K))
+    ref, S = oracle.gemm(A, B)
+    for ta, tb in [(0, 0)] + LAYOUTS:
+        say("bf16 vector %dx%dx%d storage %d%d" % (M, N, K, ta, tb))
+        assert gpu.fsrgemm_plan_bf16(ta, tb, M, N, K, 0x1000, M if ta else K, 0x1000, K if tb else N)[0] == 4
+        got = run_bf16_ex(gpu, ta, tb, A, B, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+        lda, ldb = (M if ta else K) + 3, (K if tb else N) + 5
+        got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 2, offset=1, repeat=2)      # 2-byte aligned only
+        assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+        got = run_bf16_ws(gpu, ta, tb, A, B, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+        lda, ldb = (M if ta else K), (K if tb else N)
+        got = run_bf16_ws(gpu, ta, tb, A, B, lda=lda + (-lda) % 8 + 8, ldb=ldb + (-ldb) % 8 + 8, ldc=N + 1, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+        for slices in (2, 7, 64):
+            if slices <= -(-K // 64):
+                got = run_cfg(gpu, "bf16", 4, slices, ta, tb, A, B, repeat=2)
+                assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+    if K <= 4097:
+        Ai, Bi = inputs.bf16_small_ints(4, 70, M, K), inputs.bf16_small_ints(4, 71, K, N)
+        refi, _ = oracle.gemm(Ai, Bi)
+        for ta, tb in [(0, 0)] + LAYOUTS:
+            assert np.array_equal(run_bf16_ws(gpu, ta, tb, Ai, Bi).astype(np.float64), refi)
+    with pytest.raises(gpu.FsrGemmError):
+        run_cfg(gpu, "bf16", 4, 1, 0, 1, inputs.bf16_small_ints(4, 72, 2, 64), inputs.bf16_small_ints(4, 73, 64, 2))
 
 
 def test_f32_vector_every_slice_count(gpu):
@@ -751,7 +785,7 @@ def test_bf16_every_candidate(gpu, shape, ta, tb):
     B = np.ascontiguousarray(Bt.T)
     ref, S = oracle.gemm(A, B)
     fits_main = M >= 256 and N >= 256 and K % 64 == 0 and (not ta or M % 8 == 0) and (tb or N % 8 == 0)
-    for tile in range(gpu.fsrgemm_tile_count_bf16()):
+    for tile in range(4):
         for slices in (1, 2, 5, 16, 64):
             say("bf16 candidate tile %d slices %d on %dx%dx%d %d%d" % (tile, slices, M, N, K, ta, tb))
             if slices > 1 and (slices > -(-K // 64) or slices * M * N * 4 > 16 << 20):
