@@ -312,6 +312,23 @@ def normal_equations(lib, torch):
     return out
 
 
+def dot_products(lib, torch):
+    """The paper's Task 15 (dot product of two fp32 vectors, N = 2^16 .. 2^20, appendix table) as the product of a
+    1 x N row and an N x 1 column through gemm_f32_ws: at most 8 MB of operands, so what is timed is two small
+    launches (the streaming kernel over up to 256 workgroups, then the sum of their partial results)."""
+    stream = torch.cuda.current_stream().cuda_stream
+    out = []
+    for e in (16, 17, 18, 19, 20):
+        n = 1 << e
+        a, b, c = torch.randn(1, n, device="cuda"), torch.randn(n, 1, device="cuda"), torch.empty(1, 1, device="cuda")
+        need = lib.gemm_f32_workspace_bytes(0, 0, 1, 1, n)
+        ws = torch.empty(max(need, 4), dtype=torch.uint8, device="cuda")
+        ms = steady_ms(torch, lambda: lib.check(lib.gemm_f32_ws(0, 0, 1, 1, n, a, n, b, 1, c, 1, ws, need, stream)))
+        out.append({"n": n, "kernel": lib.fsrgemm_kernel_for_f32_cfg(4, 0, 0, 1, 1, n, a, n, b, 1, c, 1), "us": ms * 1e3,
+                    "GBps": 8.0 * n / ms / 1e6})
+    return out
+
+
 def validator_pass_in_a_graph(lib, torch, passes=20, n_streams=4):
     """One validator pass = the 64 shapes of the fp32 sweep, each launched once (operands random, tight leading
     dimensions).  Four ways to issue it, time per pass in ms: call by call on one stream; call by call dealt
@@ -472,7 +489,7 @@ def main():
         del w
         torch.cuda.empty_cache()
 
-    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = small = task20 = None
+    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = small = task20 = task15 = None
     if not args.headline_only:
         small = small_fixed_configs(lib, torch)
         task2 = paper_task2_sizes(lib, torch)
@@ -482,6 +499,7 @@ def main():
         skinny_bf16 = split_k(lib, torch, "bf16")
         task8 = transpose_sizes(lib, torch)
         task20 = normal_equations(lib, torch)
+        task15 = dot_products(lib, torch)
         graph = validator_pass_in_a_graph(lib, torch)
         if not args.no_validate:
             log("selection loop on three problems")
@@ -517,6 +535,7 @@ def main():
         "split_k_bf16": skinny_bf16,
         "paper_task8_transpose": task8,
         "paper_task20_normal_equations": task20,
+        "paper_task15_dot_product": task15,
         "selection_loop": selection,
         "validator_pass_fp32_sweep": graph,
         "paper_context": "paper reports only speedups over hand-written CUDA for the group holding Task 2: 5.95-68.3x (RTX 3090 Ti), 6.06-60.0x (GTX 1660 SUPER)",
