@@ -242,6 +242,45 @@ def test_forced_configurations_and_plan_queries():
         assert lib.gemm_f32_workspace_bytes(0, 0, M, N, K) == (s * M * N * 4 if s > 1 else 0)
 
 
+def test_dispatcher_only_plans_candidates_that_the_forced_calls_accept():
+    # a seeded sweep over shapes, storage orders, paddings and alignments: whatever the dispatcher plans must be a
+    # candidate its own forced entry point would run, within the documented limits
+    import random
+
+    rng = random.Random(20)
+    dims = [1, 2, 7, 10, 16, 17, 63, 64, 65, 255, 256, 257, 1000, 4096, 4097, 8192, 1 << 16, 1 << 20, (1 << 22) + 3]
+    for case in range(4000):
+        kind = rng.choice(("f32", "bf16"))
+        ta, tb = rng.randint(0, 1), rng.randint(0, 1)
+        M, N, K = rng.choice(dims), rng.choice(dims), rng.choice(dims)
+        if M * N > 1 << 28:
+            N = 16
+        lda, ldb = (M if ta else K) + rng.choice((0, 0, 1, 3, 4, 8)), (K if tb else N) + rng.choice((0, 0, 1, 3, 4, 8))
+        esize = 4 if kind == "f32" else 2
+        a, b = P + esize * rng.choice((0, 0, 1, 2, 4)), P + esize * rng.choice((0, 0, 1, 2, 4))
+        plan, named = ((lib.fsrgemm_plan_f32, lib.fsrgemm_kernel_for_f32_cfg) if kind == "f32" else
+                       (lib.fsrgemm_plan_bf16, lib.fsrgemm_kernel_for_bf16_cfg))
+        count = lib.fsrgemm_tile_count_f32() if kind == "f32" else lib.fsrgemm_tile_count_bf16()
+        query = lib.gemm_f32_workspace_bytes if kind == "f32" else lib.gemm_bf16_workspace_bytes
+        for with_ws in (False, True):
+            got = plan(ta, tb, M, N, K, a, lda, b, ldb, with_ws)
+            assert got is not None, (kind, ta, tb, M, N, K)
+            tile, slices = got
+            ctx = (kind, ta, tb, M, N, K, lda, ldb, with_ws, tile, slices)
+            small_result = kind == "f32" and tile == 4
+            assert 0 <= tile < count and 1 <= slices <= (256 if small_result else 64), ctx
+            assert named(tile, ta, tb, M, N, K, a, lda, b, ldb, P, N) is not None, ctx
+            if not with_ws:
+                assert slices == 1 and not small_result, ctx
+            elif slices > 1 or small_result:
+                assert slices * M * N * 4 <= 16 << 20 and slices <= K, ctx
+                assert query(ta, tb, M, N, K) == slices * M * N * 4, ctx
+            else:
+                assert query(ta, tb, M, N, K) == 0, ctx
+            if kind == "bf16" and tile == 0:
+                assert slices == 1, ctx
+
+
 def test_tuned_table_rows_are_well_formed():
     # every row of the table names a candidate the forced entry point would accept for its problem
     import os
