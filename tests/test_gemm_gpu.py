@@ -498,6 +498,50 @@ def test_f32_paper_task2_shape(gpu):
 
 # ---- transposition (the paper's Task 8): data movement, so every case is bit for bit ----
 
+# ---- a seeded mix of everything ----
+
+def test_random_shapes_through_every_entry_point(gpu):
+    # 160 seeded cases: precision, storage orders, shape (log-uniform, with vectors and long K mixed in), paddings,
+    # offsets, with and without a workspace, dispatcher's choice or a random valid candidate
+    import random
+
+    rng = random.Random(31)
+    draw = lambda hi: max(1, int(2 ** (rng.random() * math.log2(hi))))
+    for case in range(160):
+        kind = rng.choice(("f32", "bf16"))
+        ta, tb = rng.randint(0, 1), rng.randint(0, 1)
+        M, N, K = draw(600), draw(600), draw(5000)
+        if rng.random() < 0.2:
+            M = 1
+        if rng.random() < 0.2:
+            N = rng.choice((1, 10))
+        pad = 8 if rng.random() < 0.5 else rng.choice((1, 3, 5))
+        off = 0 if pad == 8 and rng.random() < 0.7 else 1
+        lda, ldb = (M if ta else K) + (pad if pad != 8 else (-(M if ta else K)) % 8), (K if tb else N) + (pad if pad != 8 else (-(K if tb else N)) % 8)
+        say("random case %d: %s %d%d %dx%dx%d lda %d ldb %d offset %d" % (case, kind, ta, tb, M, N, K, lda, ldb, off))
+        if kind == "f32":
+            A, B = inputs.uniform_pm1(18, 2 * case, M, K), inputs.uniform_pm1(18, 2 * case + 1, K, N)
+            tol, run_ws, run_ex, count = TOL_F32, run_f32_ws, run_f32_ex, gpu.fsrgemm_tile_count_f32()
+        else:
+            A = inputs.bf16_normal_scaled(18, 2 * case, M, K, 1 / math.sqrt(K))
+            B = inputs.bf16_normal_scaled(18, 2 * case + 1, K, N, 1 / math.sqrt(K))
+            tol, run_ws, run_ex, count = TOL_BF16, run_bf16_ws, run_bf16_ex, gpu.fsrgemm_tile_count_bf16()
+        ref, S = oracle.gemm(A, B)
+        kw = dict(lda=lda, ldb=ldb, ldc=N + rng.choice((0, 1, 4)), offset=off, repeat=2)
+        mode = rng.choice(("plain", "workspace", "forced"))
+        if mode == "plain":
+            got = run_ex(gpu, ta, tb, A, B, **kw)
+        elif mode == "workspace":
+            got = run_ws(gpu, ta, tb, A, B, **kw)
+        else:
+            tile, slices = rng.randrange(count), rng.choice((1, 1, 2, 3, 8))
+            try:
+                got = run_cfg(gpu, kind, tile, slices, ta, tb, A, B, **kw)
+            except gpu.FsrGemmError:
+                continue                        # a candidate that cannot run this problem is rejected, never launched
+        assert oracle.componentwise_error(got, ref, S) <= tol, (case, kind, ta, tb, M, N, K, mode)
+
+
 # ---- the library under HIP graph capture ----
 
 def test_calls_captured_in_a_hip_graph_replay_bit_exact(gpu):
