@@ -88,6 +88,12 @@ bool skinny_offsets_fit(const SkinnyArgs &a);
 const char *skinny_kernel_name(int M, int N, const float *A, int64_t lda, const float *B, int64_t ldb);
 hipError_t launch_skinny_f32(const SkinnyArgs &a, float *C, int64_t ldc, hipStream_t s);
 
+// fp32 256 x 256 direct-to-LDS kernel for large aligned problems (gemm_f32_main.hip), the four layout pairs, no K slices
+constexpr int kF32_Main = kF32_Skinny + 1;          // candidate number, after the small-result kernel
+bool f32_main_fits(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb);
+const char *f32_main_kernel_name(int a_lay, int b_lay);
+hipError_t launch_f32_main(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
+
 // fp32 transposition (transpose.hip)
 const char *transpose_kernel_name(int rows, int cols);
 hipError_t launch_transpose_f32(const float *A, int64_t lda, float *T, int64_t ldt, int rows, int cols, hipStream_t s);

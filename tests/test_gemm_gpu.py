@@ -330,6 +330,51 @@ def test_f32_tile_configs_small_k(gpu, shape, kernel):
         assert np.array_equal(run_f32(gpu, Ai, Bi).astype(np.float64), oracle.gemm(Ai, Bi)[0])
 
 
+@pytest.mark.parametrize("ta,tb", [(0, 0)] + LAYOUTS)
+@pytest.mark.parametrize("shape", [(512, 768, 32), (512, 512, 64), (768, 512, 96), (256, 256, 224),     # whole tiles, 1 / 2 / 3 / 7 K-tiles
+                                   (520, 392, 128), (264, 1284, 64), (1000, 260, 160)])                 # shifted last tiles
+def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
+    # the 256 x 256 direct-to-LDS fp32 kernel, forced: prologue, odd / even tails, the clamped loads two K-tiles ahead,
+    # operands contiguous along k and along m / n, padded leading dimensions, small integers
+    M, N, K = shape
+    say("f32 main kernel storage %d%d %dx%dx%d" % (ta, tb, M, N, K))
+    lda, ldb = (M if ta else K), (K if tb else N)
+    name = "gemm_f32_main_kernel<%d, %d>" % (ta, 1 - tb)
+    assert gpu.fsrgemm_kernel_for_f32_cfg(5, ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name
+    A, B = inputs.uniform_pm1(19, 1, M, K), inputs.uniform_pm1(19, 2, K, N)
+    ref, S = oracle.gemm(A, B)
+    got = run_cfg(gpu, "f32", 5, 1, ta, tb, A, B, repeat=2)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+    assert gpu.fsrgemm_kernel_for_f32_cfg(5, ta, tb, M, N, K, 0x1000, lda + 4, 0x1000, ldb + 36, 0x1000, N + 3) == name
+    got = run_cfg(gpu, "f32", 5, 1, ta, tb, A, B, lda=lda + 4, ldb=ldb + 36, ldc=N + 3, repeat=2)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+    Ai, Bi = inputs.small_ints(0, 19, M, K), inputs.small_ints(0, 20, K, N)
+    refi, _ = oracle.gemm(Ai, Bi)
+    assert np.array_equal(run_cfg(gpu, "f32", 5, 1, ta, tb, Ai, Bi).astype(np.float64), refi)
+    # where the candidate does not fit it is rejected: a split, a misaligned base, rows that are not whole pieces
+    for kw, slices in ((dict(), 2), (dict(offset=1), 1), (dict(lda=lda + 2), 1)):
+        with pytest.raises(gpu.FsrGemmError):
+            run_cfg(gpu, "f32", 5, slices, ta, tb, A, B, **kw)
+
+
+def test_f32_main_kernel_is_the_dispatchers_choice(gpu):
+    # 16 x 16 tiles of 256 fill the compute units exactly once: the dispatcher takes the direct-to-LDS kernel, and
+    # forcing it gives the same bits; a K that is not whole tiles of 32 goes to the general kernel
+    M = N = 4096
+    for K, kernel in ((64, "gemm_f32_main_kernel<0, 1>"), (48, "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")):
+        say("f32 4096x4096x%d through the dispatcher" % K)
+        assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == kernel
+        A, B = inputs.uniform_pm1(19, 3, M, K), inputs.uniform_pm1(19, 4, K, N)
+        got = run_f32(gpu, A, B, repeat=2)
+        rng = np.random.default_rng(19)
+        ii, jj = rng.integers(0, M, 8192), rng.integers(0, N, 8192)
+        ref, S = oracle.gemm_entries(A, B, ii, jj)
+        assert np.all(np.isfinite(got)) and oracle.componentwise_error(got[ii, jj], ref, S) <= TOL_F32
+        if K == 64:
+            assert gpu.fsrgemm_plan_f32(0, 0, M, N, K, 0x1000, K, 0x1000, N, False) == (5, 1)
+            assert np.array_equal(run_cfg(gpu, "f32", 5, 1, 0, 0, A, B).view(np.uint32), got.view(np.uint32))
+
+
 @pytest.mark.parametrize("K", [64, 128, 192, 448])
 def test_bf16_main_kernel_small_k(gpu, K):
     # the scheduled 256x256 kernel with 1, 2, 3 and 7 K-tiles: prologue, odd/even tails, clamped prefetch
@@ -415,7 +460,7 @@ def test_f32_4096_normal_full_size(gpu):
     say("fp32 4096^3 normal seed 2 (sampled rows, columns, entries + Freivalds)")
     n = 4096
     A, B = inputs.normal(2, 1, n, n), inputs.normal(2, 2, n, n)
-    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
+    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_main_kernel<0, 1>"
     got = run_f32(gpu, A, B)
     rng = np.random.default_rng(2)
     rows, cols = np.sort(rng.choice(n, 64, replace=False)), np.sort(rng.choice(n, 64, replace=False))
@@ -468,7 +513,7 @@ def test_f32_paper_task2_largest_size(gpu):
     A = np.empty((M, K), dtype=np.float32)
     for b in range(64):
         A[b * 4096:(b + 1) * 4096] = block * np.float32(2.0 ** ((b % 5) - 2))
-    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
+    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == "gemm_f32_main_kernel<0, 1>"
     a, b_, c = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), torch.full((M, N), float("nan"), device="cuda")
     gpu.check(gpu.gemm_f32(M, N, K, a, K, b_, N, c, N, torch.cuda.current_stream().cuda_stream))
     torch.cuda.synchronize()
@@ -846,7 +891,7 @@ def test_bf16_every_candidate(gpu, shape, ta, tb):
 def test_every_compiled_kernel_instance(gpu, ta, tb):
     # every tile configuration in each of its three load modes (unchecked vectors / vectors with checked edges /
     # element-wise), for this storage pair, both precisions: 9 fp32 and 9 bf16 general kernels plus the
-    # direct-to-LDS one per parametrisation
+    # two direct-to-LDS ones per parametrisation
     M, N = 520, 392                                     # not multiples of any tile: shifted last tiles everywhere
     # unchecked: K a multiple of the K-tile (16 fp32, 64 bf16); checked edges: it is not, but rows stay 16-byte aligned
     for K, aligned, mode in ((128, True, "unchecked"), (104, True, "checked edges"), (100, False, "element-wise")):
@@ -875,6 +920,11 @@ def test_every_compiled_kernel_instance(gpu, ta, tb):
             got = run_cfg(gpu, "bf16", tile, 1, ta, tb, Ah, Bh, repeat=2, **kw)
             assert oracle.componentwise_error(got, refh, Sh) <= TOL_BF16
     K = 128
+    A, B = inputs.uniform_pm1(15, 7, M, K), inputs.uniform_pm1(15, 8, K, N)
+    ref, S = oracle.gemm(A, B)
+    say("f32 tile 5, storage %d%d" % (ta, tb))
+    got = run_cfg(gpu, "f32", 5, 1, ta, tb, A, B, ldc=N + 3, repeat=2)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_F32
     Ah = inputs.bf16_normal_scaled(15, 5, M, K, 1 / math.sqrt(K))
     Bh = np.ascontiguousarray(inputs.bf16_normal_scaled(15, 6, N, K, 1 / math.sqrt(K)).T)
     refh, Sh = oracle.gemm(Ah, Bh)
