@@ -107,12 +107,12 @@ int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *
 // workgroup running alone.  Times per tile and k step, in units of 0.1 ns, measured on square problems with
 // each configuration forced: 256 x 128: 1167, 128 x 128: 610, 64 x 64: 169 with four workgroups per compute
 // unit, 221 alone.  K cancels.  Equal costs go to the larger tile.  The 256 x 256 direct-to-LDS kernel
-// (main_fits: it can take the problem) runs one workgroup per compute unit at 2280 per tile and wins where
+// (main_fits: it can take the problem) runs one workgroup per compute unit at 2230 per tile and wins where
 // its tiles fill whole rounds.
 int tile_rule_f32(int64_t M, int64_t N, bool main_fits)
 {
     constexpr int64_t kTileTime[kF32ConfigCount] = {1167, 610, 169}, kAlone[kF32ConfigCount] = {1167, 610, 221};
-    constexpr int64_t kMainTime = 2280;
+    constexpr int64_t kMainTime = 2230;
     int best = 0;
     int64_t best_cost = 0;
     for (int c = 0; c < kF32ConfigCount; ++c) {
