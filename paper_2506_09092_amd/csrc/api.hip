@@ -97,7 +97,8 @@ int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *
     const int bm = kF32TileM[cfg], bn = kF32TileN[cfg];
     if (ceil_div(M, bm) * ceil_div(N, bn) * slices >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
     const bool vec = aligned16(A) && aligned16(B) && lda % 4 == 0 && ldb % 4 == 0;
-    *mode = !vec ? kScalar : (M >= bm && N >= bn && K % 16 == 0 && K > 0) ? kFast : kVecPred;
+    const bool near = lda < kF32MaxLdUnchecked && ldb < kF32MaxLdUnchecked;      // 32-bit lane offsets of the unchecked loads
+    *mode = !vec ? kScalar : (M >= bm && N >= bn && K % 16 == 0 && K > 0 && near) ? kFast : kVecPred;
     return FSRGEMM_OK;
 }
 
@@ -105,13 +106,13 @@ int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *
 // of the output tiles at a rate that depends on the tile only, so a launch takes ceil(tiles / 256) tile times
 // (256 compute units; a last round with few tiles costs a whole one), and never less than the time of one
 // workgroup running alone.  Times per tile and k step, in units of 0.1 ns, measured on square problems with
-// each configuration forced: 256 x 128: 1167, 128 x 128: 610, 64 x 64: 169 with four workgroups per compute
+// each configuration forced: 256 x 128: 1137, 128 x 128: 569, 64 x 64: 169 with four workgroups per compute
 // unit, 221 alone.  K cancels.  Equal costs go to the larger tile.  The 256 x 256 direct-to-LDS kernel
 // (main_fits: it can take the problem) runs one workgroup per compute unit at 2230 per tile and wins where
 // its tiles fill whole rounds.
 int tile_rule_f32(int64_t M, int64_t N, bool main_fits)
 {
-    constexpr int64_t kTileTime[kF32ConfigCount] = {1167, 610, 169}, kAlone[kF32ConfigCount] = {1167, 610, 221};
+    constexpr int64_t kTileTime[kF32ConfigCount] = {1137, 569, 169}, kAlone[kF32ConfigCount] = {1137, 569, 221};
     constexpr int64_t kMainTime = 2230;
     int best = 0;
     int64_t best_cost = 0;

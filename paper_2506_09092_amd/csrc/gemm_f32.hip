@@ -49,6 +49,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kBK = 16;
 constexpr int kPadA = 4;    // As row = 20 floats: 16-byte aligned; 16 consecutive rows hit distinct bank quads
+constexpr int64_t kMaxLdUnchecked = kF32MaxLdUnchecked;
 constexpr int kPadB = 8;    // Bs row = BN + 8 floats: rows 4 apart land 32 banks apart
 
 template <int MODE>
@@ -107,6 +108,39 @@ struct Operand {
             return load4<MODE>(base + (int64_t)(r0 + r) * ld + k0 + k, r0 + r < rows, k0 + k, K);
         else
             return load4<MODE>(base + (int64_t)(k0 + k) * ld + r0 + r, k0 + k < K, r0 + r, rows);
+    }
+    // Unchecked loads take their address as a wavefront-uniform 64-bit base (the tile's origin, the K position and
+    // vector s: scalar registers, computed by the scalar unit) plus a 32-bit byte offset per lane that is the same for
+    // every vector and K-tile.  In that form a load reads one address register per lane instead of two and needs no
+    // vector arithmetic; with 64-bit lane addresses each load held the matrix pipe up for some 40 cycles.
+    // Needs ld < 2^24 (kMaxLdUnchecked): the offset reaches (63 ld + 15) * 4 bytes.
+    static __device__ __forceinline__ uint32_t lane_offset(int tid, int64_t ld)
+    {
+        if constexpr (LAY == kKContig) return (uint32_t)(((tid >> 2) * ld + (tid & 3) * 4) * 4);
+        else return (uint32_t)(((tid / (EXT / 4)) * ld + (tid % (EXT / 4)) * 4) * 4);
+    }
+    // the uniform part for vector s of the K-tile that starts at k0, and what one K-tile further adds to it (bytes)
+    static __device__ __forceinline__ const char *vector_base(const float *__restrict__ base, int64_t ld, int r0, int k0, int s)
+    {
+        static_assert(256 % (EXT / 4) == 0, "vector s of a lane must start a whole number of k-rows behind vector 0");
+        if constexpr (LAY == kKContig) return reinterpret_cast<const char *>(base + (int64_t)(r0 + 64 * s) * ld + k0);
+        else return reinterpret_cast<const char *>(base + (int64_t)(k0 + s * (1024 / EXT)) * ld + r0);
+    }
+    static __device__ __forceinline__ int64_t k_tile_step(int64_t ld) { return LAY == kKContig ? kBK * 4 : kBK * 4 * ld; }
+    template <int MODE>
+    static __device__ __forceinline__ f32x4 gload_unchecked(const char *u, uint32_t lane_off)
+    {
+        static_assert(MODE == kFast || MODE == kUnalignedVec, "checked loads go through gload");
+        // opaque to the optimiser, so that base and offset reach instruction selection as they are written here
+        // (it would otherwise fold the offset into a 64-bit address per lane outside the loop)
+        asm volatile("" : "+s"(u), "+v"(lane_off));
+        const __attribute__((address_space(1))) char *p = (const __attribute__((address_space(1))) char *)u + lane_off;
+        if constexpr (MODE == kFast) {
+            return *reinterpret_cast<const __attribute__((address_space(1))) f32x4 *>(p);
+        } else {
+            typedef f32x4 f32x4_elem_aligned __attribute__((aligned(4)));
+            return *reinterpret_cast<const __attribute__((address_space(1))) f32x4_elem_aligned *>(p);
+        }
     }
     static __device__ __forceinline__ int lds_store_at(int tid, int s)
     {
@@ -171,13 +205,38 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
 
     // A workgroup whose tile lies inside the matrix needs no check on whole K-tiles even when the problem as a
     // whole is ragged: `unchecked` counts the leading K-tiles it may load like the unchecked mode does.
-    const int unchecked = MODE == kFast ? nk : (m0 + BM <= M && n0 + BN <= N) ? max(0, min(nk, K / kBK - t0)) : 0;
+    const bool offsets_fit = g.lda < kMaxLdUnchecked && g.ldb < kMaxLdUnchecked;     // the unchecked mode is only launched if so
+    const int unchecked = MODE == kFast ? nk : (offsets_fit && m0 + BM <= M && n0 + BN <= N) ? max(0, min(nk, K / kBK - t0)) : 0;
+    const uint32_t a_lane = OpA::lane_offset(tid, g.lda), b_lane = OpB::lane_offset(tid, g.ldb);
+    // Uniform bases of the unchecked loads, one per vector, for the K-tile such a load fetches next: they walk K one
+    // tile per use (unchecked loads fetch K-tiles in order, starting with the slice's first) and stop at the last.
+    const char *ua[NA], *ub[NB];
+#pragma unroll
+    for (int s = 0; s < NA; ++s) ua[s] = OpA::vector_base(A, g.lda, m0, t0 * kBK, s);
+#pragma unroll
+    for (int s = 0; s < NB; ++s) ub[s] = OpB::vector_base(B, g.ldb, n0, t0 * kBK, s);
+    const int64_t a_step = OpA::k_tile_step(g.lda), b_step = OpB::k_tile_step(g.ldb);
     f32x4 rg[NG];
     auto gload = [&](auto load_mode, int idx, int t) {      // K-tiles past the end are clamped: loaded again, never consumed
         constexpr int LM = decltype(load_mode)::value;
         const int k0 = (t0 + (t < nk ? t : nk - 1)) * kBK;
-        if (idx < NA) rg[idx] = OpA::template gload<LM>(A, g.lda, m0, M, k0, K, tid, idx);
-        else rg[idx] = OpB::template gload<LM>(B, g.ldb, n0, N, k0, K, tid, idx - NA);
+        // The smallest tile keeps an address per lane for its unchecked loads too: it has a single accumulator block,
+        // so its MFMAs form one dependent chain and a workgroup alone is bound by load latency; with few workgroups
+        // per compute unit the scalar-base form (whose base is computed on the wavefront's own instruction stream)
+        // measured 7-9 % slower there (1024 x 2048 x 4096, 3072^2), though 8 % faster with many (5120^2).
+        if constexpr ((LM == kFast || LM == kUnalignedVec) && TM * TN > 1) {
+            const bool more = t + 1 < nk;
+            if (idx < NA) {
+                rg[idx] = OpA::template gload_unchecked<LM>(ua[idx], a_lane);
+                ua[idx] += more ? a_step : 0;
+            } else {
+                rg[idx] = OpB::template gload_unchecked<LM>(ub[idx - NA], b_lane);
+                ub[idx - NA] += more ? b_step : 0;
+            }
+        } else {
+            if (idx < NA) rg[idx] = OpA::template gload<LM>(A, g.lda, m0, M, k0, K, tid, idx);
+            else rg[idx] = OpB::template gload<LM>(B, g.ldb, n0, N, k0, K, tid, idx - NA);
+        }
     };
     using Checked = std::integral_constant<int, MODE>;
     using Unchecked = std::integral_constant<int, MODE == kScalar ? kUnalignedVec : kFast>;
@@ -283,9 +342,10 @@ __global__ __launch_bounds__(kThreads, MIN_WAVES) void gemm_f32_kernel(GemmArgs 
 }
 
 template <int TM, int TN, int MIN_WAVES, int ALAY, int BLAY>
-hipError_t launch_lay(int mode, const GemmArgs &a, hipStream_t s)
+hipError_t launch_lay(int mode, const GemmArgs &args, hipStream_t s)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
+    const GemmArgs &a = args;
     const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n * a.k_slices)), block(kThreads);
     switch (mode) {
@@ -358,6 +418,7 @@ const char *f32_kernel_name(int cfg, int mode, int a_lay, int b_lay)
 
 hipError_t launch_f32(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
+    if (mode == kFast && (a.lda >= kMaxLdUnchecked || a.ldb >= kMaxLdUnchecked)) return hipErrorInvalidValue;
     switch (cfg) {
     case kF32_256x128: return launch_cfg<4, 2, 2>(mode, a_lay, b_lay, a, s);
     case kF32_128x128: return launch_cfg<2, 2, 3>(mode, a_lay, b_lay, a, s);

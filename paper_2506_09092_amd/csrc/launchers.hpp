@@ -13,6 +13,8 @@ hipError_t ensure_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_
 
 // fp32 tile configurations (gemm_f32.hip), each available in the three load modes and the four layout pairs
 enum F32Config { kF32_256x128 = 0, kF32_128x128 = 1, kF32_64x64 = 2, kF32ConfigCount };
+// the unchecked load mode addresses a lane's vectors with 32-bit byte offsets: leading dimensions below this
+constexpr int64_t kF32MaxLdUnchecked = (int64_t)1 << 24;
 // Names are substrings of the kernel symbols as a profiler trace prints them.
 const char *f32_kernel_name(int cfg, int mode, int a_lay, int b_lay);
 hipError_t launch_f32(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);

@@ -72,8 +72,8 @@ def test_dispatch_query_names_variants():
     assert q(4096, 4096, 4112, P, 4112, P, 4096, P, 4096) == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
     assert ragged == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>" and unaligned == "gemm_f32_kernel<1, 1, 4, 2, 0, 1>"
     assert q(4090, 4090, 129, P, 132, P, 4092, P, 4090) == "gemm_f32_kernel<4, 2, 2, 1, 0, 1>"
-    # one row and column beyond 4096 would cost the large tiles a whole further round: the small tile takes it
-    assert q(4097, 4097, 129, P, 132, P, 4100, P, 4097) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"
+    # one row and column beyond 4096 would cost the largest tile a whole further round: a smaller one takes it
+    assert q(4097, 4097, 129, P, 132, P, 4100, P, 4097) == "gemm_f32_kernel<2, 2, 3, 1, 0, 1>"
     assert q(64, 64, 0, P, 4, P, 64, P, 64) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"                    # K = 0 never takes the unchecked mode
     assert q(4, 4, 4, P, 3, P, 4, P, 4) is None
     qb = lib.fsrgemm_kernel_for_bf16
