@@ -86,7 +86,7 @@ int splitk_slices(int64_t M, int64_t N, int64_t K, int k_tile)
 int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
              int *mode)
 {
-    if (cfg == kF32_Skinny || cfg == kF32_Main) {      // whether they fit the problem is their own check
+    if (cfg == kF32_Skinny || cfg >= kF32_Main) {      // whether they fit the problem is their own check
         *mode = 0;
         return FSRGEMM_OK;
     }
@@ -107,13 +107,13 @@ int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *
 // (256 compute units; a last round with few tiles costs a whole one), and never less than the time of one
 // workgroup running alone.  Times per tile and k step, in units of 0.1 ns, measured on square problems with
 // each configuration forced: 256 x 128: 1137, 128 x 128: 569, 64 x 64: 169 with four workgroups per compute
-// unit, 221 alone.  K cancels.  Equal costs go to the larger tile.  The 256 x 256 direct-to-LDS kernel
-// (main_fits: it can take the problem) runs one workgroup per compute unit at 2230 per tile and wins where
-// its tiles fill whole rounds.
-int tile_rule_f32(int64_t M, int64_t N, bool main_fits)
+// unit, 221 alone.  K cancels.  Equal costs go to the larger tile.  The direct-to-LDS kernel runs one workgroup
+// per compute unit; its shapes (main_fits: bit s set if shape s can take the problem) enter with their own tile
+// times and win where their tiles fill whole rounds.
+constexpr int64_t kMainTileTime[kF32MainShapes] = {2230, 1710, 1120, 1120, 838, 566};   // 256x256, 192x256, 128x256, 256x128, 192x128, 128x128
+int tile_rule_f32(int64_t M, int64_t N, unsigned main_fits)
 {
     constexpr int64_t kTileTime[kF32ConfigCount] = {1137, 569, 169}, kAlone[kF32ConfigCount] = {1137, 569, 221};
-    constexpr int64_t kMainTime = 2230;
     int best = 0;
     int64_t best_cost = 0;
     for (int c = 0; c < kF32ConfigCount; ++c) {
@@ -122,7 +122,11 @@ int tile_rule_f32(int64_t M, int64_t N, bool main_fits)
         if (cost < kAlone[c]) cost = kAlone[c];
         if (c == 0 || cost < best_cost) best = c, best_cost = cost;
     }
-    if (main_fits && ceil_div(ceil_div(M, 256) * ceil_div(N, 256), 256) * kMainTime < best_cost) best = kF32_Main;
+    for (int sh = 0; sh < kF32MainShapes; ++sh) {
+        if (!(main_fits >> sh & 1)) continue;
+        const int64_t cost = ceil_div(ceil_div(M, f32_main_tile_m(sh)) * ceil_div(N, f32_main_tile_n(sh)), 256) * kMainTileTime[sh];
+        if (cost < best_cost) best = kF32_Main + sh, best_cost = cost;
+    }
     return best;
 }
 
@@ -219,8 +223,10 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
     } else {
         p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 16) : 1;
         if (!t && p->slices == 1 && use_table) t = find_tuned(0, transA, transB, M, N, K, false);
-        const bool main_fits = f32_main_fits(transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, A, lda, B, ldb);
-        if (t && t->tile == kF32_Main && (!main_fits || t->slices > 1)) t = nullptr;    // a row for operands aligned otherwise
+        unsigned main_fits = 0;
+        for (int sh = 0; sh < kF32MainShapes; ++sh)
+            main_fits |= (unsigned)f32_main_fits(sh, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, A, lda, B, ldb) << sh;
+        if (t && t->tile >= kF32_Main && (!(main_fits >> (t->tile - kF32_Main) & 1) || t->slices > 1)) t = nullptr;    // a row for operands aligned otherwise
         p->cfg = t ? t->tile : p->slices > 1 ? kF32_64x64 : tile_rule_f32(M, N, main_fits);
     }
     return mode_f32(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
@@ -347,10 +353,10 @@ int run_f32(const Plan &p, int transA, int transB, int64_t M, int64_t N, int64_t
     }
     const bool split = p.slices > 1;
     hipError_t e;
-    if (p.cfg == kF32_Main) {
+    if (p.cfg >= kF32_Main) {
         if (split) return FSRGEMM_ERR_INVALID_ARG;      // the planners never pair the two
         const GemmArgs a = pack(M, N, K, A, lda, B, ldb, C, ldc);
-        e = launch_f32_main(transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, a, s);
+        e = launch_f32_main(p.cfg - kF32_Main, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, a, s);
         return e == hipSuccess ? FSRGEMM_OK : e == hipErrorInvalidValue ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_ERR_LAUNCH;
     }
     if (p.cfg == kF32_Vector) {
@@ -467,10 +473,10 @@ int gemm_f32_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int6
             return FSRGEMM_ERR_INVALID_ARG;
         probe.K = (int)K, probe.parts = k_slices;
         if (!skinny_offsets_fit(probe)) return FSRGEMM_ERR_INVALID_ARG;
-    } else if (tile == kF32_Main) {     // unsplit, and only problems it fits
+    } else if (tile >= kF32_Main && tile < kF32_Main + kF32MainShapes) {     // unsplit, and only problems it fits
         if (k_slices != 1 || workspace_bytes < 0 || (workspace_bytes > 0 && workspace == nullptr)) return FSRGEMM_ERR_INVALID_ARG;
         if (M == 0 || N == 0) return FSRGEMM_OK;
-        if (!f32_main_fits(transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, A, lda, B, ldb))
+        if (!f32_main_fits(tile - kF32_Main, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, A, lda, B, ldb))
             return FSRGEMM_ERR_INVALID_ARG;
     } else {
         if (!forced_ok(tile, kF32_Vector + 1, k_slices, M, N, K, 16, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
@@ -496,7 +502,7 @@ int fsrgemm_plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, co
     return FSRGEMM_OK;
 }
 
-int fsrgemm_tile_count_f32(void) { return kF32_Main + 1; }
+int fsrgemm_tile_count_f32(void) { return kF32_Main + kF32MainShapes; }
 
 int gemm_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
               float *C, int64_t ldc, void *stream)
@@ -586,7 +592,7 @@ const char *fsrgemm_kernel_for_f32_ex(int transA, int transB, int64_t M, int64_t
     Plan p;
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
     if (plan_f32(transA, transB, M, N, K, A, lda, B, ldb, false, &p) != FSRGEMM_OK) return nullptr;
-    if (p.cfg == kF32_Main) return f32_main_kernel_name(transA ? kMnContig : kKContig, transB ? kKContig : kMnContig);
+    if (p.cfg >= kF32_Main) return f32_main_kernel_name(p.cfg - kF32_Main, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig);
     if (p.cfg == kF32_Vector) {
         const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
         return gemv_kernel_name(v.pattern, gemv_takes_vectors(v.a));
@@ -623,9 +629,9 @@ const char *fsrgemm_kernel_for_f32_cfg(int tile, int transA, int transB, int64_t
         if (K < 1 || !tall_storage(transA, transB, M, N, lda, ldb, &lda_t, &ldb_t)) return nullptr;
         return skinny_kernel_name((int)(M < 17 ? M : 17), (int)(N < 17 ? N : 17), A, lda_t, B, ldb_t);
     }
-    if (tile == kF32_Main) {
+    if (tile >= kF32_Main && tile < kF32_Main + kF32MainShapes) {
         const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
-        return f32_main_fits(a_lay, b_lay, M, N, K, A, lda, B, ldb) ? f32_main_kernel_name(a_lay, b_lay) : nullptr;
+        return f32_main_fits(tile - kF32_Main, a_lay, b_lay, M, N, K, A, lda, B, ldb) ? f32_main_kernel_name(tile - kF32_Main, a_lay, b_lay) : nullptr;
     }
     if (tile < 0 || tile > kF32_Vector || (tile == kF32_Vector && !vector_shape(M, N, K))) return nullptr;
     int mode;

@@ -1,10 +1,11 @@
 // fp32 kernel for large, aligned problems: C[M x N] = A . B with fp32 operands, accumulation and output (the
-// paper's Task 2 at its own precision), one 256 x 256 tile of C per workgroup and direct global->LDS loads.
+// paper's Task 2 at its own precision), one 256 x 256 tile of C per workgroup -- or a smaller one, see "Tile
+// shapes" -- and direct global->LDS loads.
 // Either operand may be contiguous along k (a row-major A, a B stored transposed: a tile row is 128 bytes of
 // 32 k) or along m / n (an A stored transposed, a row-major B: a tile row is a k-row of 1 KB); LDS keeps the
 // memory order and the fragment reads do the rest.
 //
-// Shape of the computation
+// Shape of the computation (for the 256 x 256 tile)
 //   workgroup : 256 lanes = 4 wavefronts, one per SIMD
 //   wavefront : 128 x 128 of the tile = 4 x 4 blocks of V_MFMA_F32_32X32X2_F32, 256 accumulator registers (the
 //               whole AccVGPR file)
@@ -35,13 +36,21 @@
 // the loop's back edge; the compiler does not know they are MFMAs, so the wait before the accumulators are
 // read at the end is written out.
 //
-// LDS layout of an operand's 32 KB:
-//   contiguous along k   : 256 rows of 128 bytes; the 16-byte piece c of row r sits at position
-//                          c ^ ((r >> 1) & 7), which makes the 16-byte fragment reads (32 rows x 2 pieces per
-//                          wavefront) conflict-free
-//   contiguous along m/n : 32 k-rows of 1 KB; piece c of k-row k sits at position c ^ (8 * (k & 1))
+// LDS layout of an operand's tile (32 KB for 256 rows or columns):
+//   contiguous along k   : rows of 128 bytes; the 16-byte piece c of row r sits at position c ^ ((r >> 1) & 7),
+//                          which makes the 16-byte fragment reads (32 rows x 2 pieces per wavefront) conflict-free
+//   contiguous along m/n : 32 k-rows as in memory (1 KB for 256 columns); the 4-byte fragment reads take 32
+//                          consecutive words per half wavefront and need no permutation
 // A global->LDS load writes its 64 lanes' 16 bytes to consecutive LDS addresses, so the permutation is applied
 // on the global side: the lane that fills position p fetches the piece that belongs there.
+//
+// Tile shapes.  A launch lasts as long as the compute unit with the most tiles, so a problem whose 256 x 256 tiles
+// do not fill whole rounds of the 256 compute units is better off with a smaller tile that does: the kernel is a
+// template over the blocks per wavefront, WM x WN of 32 x 32 (tile 64 WM x 64 WN), instantiated for 256 x 256,
+// 192 x 256, 128 x 256, 256 x 128, 192 x 128 and 128 x 128.  A side of 192 needs that operand contiguous along k
+// (its k-rows would be 768 bytes, which a 1 KB load does not divide).  Loads per wavefront and K-tile: 2 WM + 2 WN.
+#include <stdio.h>
+
 #include <type_traits>
 
 #include "launchers.hpp"
@@ -50,61 +59,92 @@ namespace fsrgemm {
 
 namespace {
 
-constexpr int kBM = 256, kBN = 256, kBK = 32, kThreads = 256;
-constexpr int kOperandBytes = 256 * kBK * 4;                // 32 KB, either layout
-constexpr int kStageBytes = 2 * kOperandBytes;
-constexpr int kLdsBytes = 2 * kStageBytes;                  // 128 KB
+constexpr int kBK = 32, kThreads = 256;
 
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
-#define GLOBAL_PTR __attribute__((address_space(1)))
 #define LDS_PTR __attribute__((address_space(3)))
 
-template <int ALAY, int BLAY>
+// M0 is on a clobber list below on purpose (the loads take their LDS address from it); clang warns that it is a
+// reserved register.  Nothing the compiler emits for this kernel uses M0.
+#pragma clang diagnostic ignored "-Winline-asm"
+
+template <int WM, int WN, int ALAY, int BLAY>
 __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, int tiles_m, int tiles_n)
 {
+    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int kBytesA = BM * kBK * 4, kBytesB = BN * kBK * 4, kStageBytes = kBytesA + kBytesB;
+    constexpr int kLoadsA = 2 * WM, kLoadsB = 2 * WN, kLoads = kLoadsA + kLoadsB;     // 1 KB each, per wavefront and K-tile
+    constexpr int kMfmas = 4 * WM * WN;                                               // per chunk of 8 k
+    static_assert(ALAY == kKContig || WM != 3, "k-rows of 768 bytes are not built");
+    static_assert(BLAY == kKContig || WN != 3, "k-rows of 768 bytes are not built");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     int tile_m, tile_n;
     tile_coords(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_origin(tile_m, kBM, g.M), n0 = tile_origin(tile_n, kBN, g.N);
+    const int m0 = tile_origin(tile_m, BM, g.M), n0 = tile_origin(tile_n, BN, g.N);
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+    const int wm0 = (wave >> 1) * 32 * WM, wn0 = (wave & 1) * 32 * WN;
     const int li = lane & 31, lh = lane >> 5;
     const int nk = g.K / kBK;
     const float *__restrict__ A = static_cast<const float *>(g.A);
     const float *__restrict__ B = static_cast<const float *>(g.B);
 
-    // Load q (0..7) of wavefront w for an operand fills the LDS bytes [(8 w + q) KB, +1 KB) of the operand:
-    //   along k   : rows 64 w + 8 q + lane / 8, position lane % 8, which holds piece
-    //               (lane % 8) ^ ((row >> 1) & 7) with (row >> 1) & 7 = 4 (q & 1) + (lane >> 4)
-    //   along m/n : k-row 8 w + q, position lane, which holds piece lane ^ (8 * (q & 1))
-    // K-tiles beyond the last one (the pipeline asks for two ahead) repeat the last: in bounds and never read.
+    // Load q of wavefront w for an operand of EXT rows / columns (q < EXT / 32) fills the LDS bytes
+    // [(w EXT / 32 + q) KB, +1 KB) of the operand's tile:
+    //   along k   : rows w EXT / 4 + 8 q + lane / 8, position lane % 8, which holds piece
+    //               (lane % 8) ^ ((row >> 1) & 7) with (row >> 1) & 7 = (4 q + (lane >> 4)) & 7
+    //   along m/n : k-rows of 4 EXT bytes, 1 or 2 per load: k-row (w EXT / 32 + q) (256 / EXT) + lane / (EXT / 4),
+    //               piece lane % (EXT / 4)
     // The address of a load is a wavefront-uniform pointer (scalar arithmetic, free beside the MFMAs) plus a 32-bit
-    // lane offset that is fixed for the whole kernel: two per operand, by the parity of q.
-    auto lane_offset = [&](auto layout, int64_t ld, int odd) -> uint32_t {
-        constexpr int LAY = decltype(layout)::value;
+    // lane offset that is fixed for the whole kernel: two per operand, by the parity of q (equal along m/n).
+    // K-tiles beyond the last one (the pipeline asks for two ahead) repeat the last: in bounds and never read.
+    auto lane_offset = [&](auto layout, auto extent, int64_t ld, int odd) -> uint32_t {
+        constexpr int LAY = decltype(layout)::value, EXT = decltype(extent)::value;
         if constexpr (LAY == kKContig) return (uint32_t)(((lane >> 3) * ld + (((lane & 7) ^ ((4 * odd + (lane >> 4)) & 7)) << 2)) << 2);
-        else return (uint32_t)((lane ^ (8 * odd)) << 4);
+        else return (uint32_t)(((lane / (EXT / 4)) * ld + (lane % (EXT / 4)) * 4) << 2);
     };
-    const uint32_t a_off[2] = {lane_offset(std::integral_constant<int, ALAY>{}, g.lda, 0), lane_offset(std::integral_constant<int, ALAY>{}, g.lda, 1)};
-    const uint32_t b_off[2] = {lane_offset(std::integral_constant<int, BLAY>{}, g.ldb, 0), lane_offset(std::integral_constant<int, BLAY>{}, g.ldb, 1)};
+    using LayA = std::integral_constant<int, ALAY>;
+    using LayB = std::integral_constant<int, BLAY>;
+    using ExtA = std::integral_constant<int, BM>;
+    using ExtB = std::integral_constant<int, BN>;
+    const uint32_t a_off[2] = {lane_offset(LayA{}, ExtA{}, g.lda, 0), lane_offset(LayA{}, ExtA{}, g.lda, 1)};
+    const uint32_t b_off[2] = {lane_offset(LayB{}, ExtB{}, g.ldb, 0), lane_offset(LayB{}, ExtB{}, g.ldb, 1)};
+    // The loads of a K-tile in issue order: A's and B's alternate while both last.  -> operand (0 A, 1 B) and q
+    auto which = [](int idx, int &operand, int &q) {
+        constexpr int kBoth = 2 * (kLoadsA < kLoadsB ? kLoadsA : kLoadsB);
+        if (idx < kBoth) operand = idx & 1, q = idx >> 1;
+        else operand = kLoadsA < kLoadsB ? 1 : 0, q = idx - kBoth / 2;
+    };
     // A load is issued by hand in two steps: M0 <- its LDS address, then, at least one instruction later (M0 needs a
     // wait state before a load reads it), the load in its scalar-base form.
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(LDS_PTR char *)lds);
-    auto load_m0 = [&](int stage, int idx) {       // idx 0..15: A and B loads alternate, q = idx / 2
-        const uint32_t dst = lds0 + stage * kStageBytes + (idx & 1) * kOperandBytes + (wave * 8 + (idx >> 1)) * 1024;
+    auto load_m0 = [&](int stage, int idx) {
+        int operand, q;
+        which(idx, operand, q);
+        // (worked out anew each time, like the bases below: see there)
+        uint32_t dst = lds0 + wave * ((operand ? kLoadsB : kLoadsA) * 1024);
+        asm volatile("" : "+s"(dst));
+        dst += stage * kStageBytes + operand * kBytesA + q * 1024;
         asm volatile("s_mov_b32 m0, %0" ::"s"(dst) : "m0");
     };
-    auto dma = [&](auto layout, const float *__restrict__ P, int64_t ld, int origin, const uint32_t (&off)[2], int q, int t) {
-        constexpr int LAY = decltype(layout)::value;
+    auto dma = [&](auto layout, auto extent, const float *__restrict__ P, int64_t ld, int origin, const uint32_t (&off)[2], int q, int t) {
+        constexpr int LAY = decltype(layout)::value, EXT = decltype(extent)::value;
         const int tc = t < nk ? t : nk - 1;
+        // The base is worked out anew for every load (a handful of scalar instructions): kept across the loop, the
+        // bases of all loads would not fit the scalar registers, and a spilled one would come back through a lane
+        // read right in front of a hand-issued load, which the compiler does not know to keep apart.  The zero
+        // below is opaque to it, so nothing that contains it is loop-invariant.
+        int zero = 0;
+        asm volatile("" : "+s"(zero));
         const float *row;       // uniform
-        if constexpr (LAY == kKContig) row = P + (int64_t)(origin + wave * 64 + 8 * q) * ld + tc * kBK;
-        else row = P + (int64_t)(tc * kBK + wave * 8 + q) * ld + origin;
+        if constexpr (LAY == kKContig) row = P + (int64_t)(origin + wave * (EXT / 4) + 8 * q + zero) * ld + tc * kBK;
+        else row = P + (int64_t)(tc * kBK + (wave * (EXT / 32) + q) * (256 / EXT)) * ld + origin;
         asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(off[q & 1]), "s"(row) : "memory");
     };
     auto load_go = [&](int idx, int t) {
-        if (idx & 1) dma(std::integral_constant<int, BLAY>{}, B, g.ldb, n0, b_off, idx >> 1, t);
-        else dma(std::integral_constant<int, ALAY>{}, A, g.lda, m0, a_off, idx >> 1, t);
+        int operand, q;
+        which(idx, operand, q);
+        if (operand) dma(LayB{}, ExtB{}, B, g.ldb, n0, b_off, q, t);
+        else dma(LayA{}, ExtA{}, A, g.lda, m0, a_off, q, t);
     };
     auto load = [&](int stage, int idx, int t) {    // outside the MFMA loop
         load_m0(stage, idx);
@@ -115,32 +155,34 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     // Fragments of chunk c (8 k): the lane with row / column x = offset + 32 block + lane % 32 holds
     // k = 8 c + 4 (lane / 32) + s for the four steps s of the chunk -- one 16-byte read along k, four 4-byte
     // reads along m / n.
-    float fa[2][4][4], fb[2][4][4];         // [register buffer][block][step]
-    constexpr int kReadsA = ALAY == kKContig ? 4 : 16, kReadsB = BLAY == kKContig ? 4 : 16;
-    auto fragment = [&](auto layout, int operand, int offset, int stage, int c, float (&f)[4][4], int idx) {
-        constexpr int LAY = decltype(layout)::value;
-        const char *st = lds + stage * kStageBytes + operand * kOperandBytes;
+    float fa[2][WM][4], fb[2][WN][4];       // [register buffer][block][step]
+    constexpr int kReadsA = ALAY == kKContig ? WM : 4 * WM, kReadsB = BLAY == kKContig ? WN : 4 * WN;
+    constexpr int kReads = kReadsA + kReadsB;
+    static_assert(kReads <= kMfmas && 2 * kLoads <= kMfmas, "a chunk has a slot per fragment read and two per load");
+    auto fragment = [&](auto layout, auto extent, auto blocks, const char *st, int offset, int c, auto &f, int idx) {
+        constexpr int LAY = decltype(layout)::value, EXT = decltype(extent)::value, W = decltype(blocks)::value;
         if constexpr (LAY == kKContig) {
             const int b = idx;
             const f32x4 v = *reinterpret_cast<const f32x4 *>(st + (offset + 32 * b + li) * 128 + (((2 * c + lh) ^ ((li >> 1) & 7)) << 4));
 #pragma unroll
             for (int s = 0; s < 4; ++s) f[b][s] = v[s];
         } else {
-            const int b = idx & 3, s = idx >> 2;
+            const int b = idx % W, s = idx / W;
             const int k = 8 * c + 4 * lh + s, x = offset + 32 * b + li;
-            f[b][s] = *reinterpret_cast<const float *>(st + k * 1024 + ((((x >> 2) ^ (8 * (k & 1))) << 4) | ((x & 3) << 2)));
+            f[b][s] = *reinterpret_cast<const float *>(st + k * (4 * EXT) + 4 * x);
         }
     };
-    auto read = [&](int stage, int c, int buf, int idx) {   // idx 0 .. kReadsA + kReadsB - 1
-        if (idx < kReadsA) fragment(std::integral_constant<int, ALAY>{}, 0, wm0, stage, c, fa[buf], idx);
-        else fragment(std::integral_constant<int, BLAY>{}, 1, wn0, stage, c, fb[buf], idx - kReadsA);
+    auto read = [&](int stage, int c, int buf, int idx) {   // idx 0 .. kReads - 1
+        const char *st = lds + stage * kStageBytes;
+        if (idx < kReadsA) fragment(LayA{}, ExtA{}, std::integral_constant<int, WM>{}, st, wm0, c, fa[buf], idx);
+        else fragment(LayB{}, ExtB{}, std::integral_constant<int, WN>{}, st + kBytesA, wn0, c, fb[buf], idx - kReadsA);
     };
 
-    f32x16 acc[4][4];
+    f32x16 acc[WM][WN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < WN; ++j) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
             asm volatile("" : "+a"(acc[i][j]));
@@ -148,32 +190,33 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
 
     // K-tiles 0 and 1 into stages 0 and 1, then the first fragments
 #pragma unroll
-    for (int idx = 0; idx < 16; ++idx) load(0, idx, 0);
+    for (int idx = 0; idx < kLoads; ++idx) load(0, idx, 0);
 #pragma unroll
-    for (int idx = 0; idx < 16; ++idx) load(1, idx, 1);
+    for (int idx = 0; idx < kLoads; ++idx) load(1, idx, 1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     FENCE();
 #pragma unroll
-    for (int idx = 0; idx < kReadsA + kReadsB; ++idx) read(0, 0, 0, idx);
+    for (int idx = 0; idx < kReads; ++idx) read(0, 0, 0, idx);
     FENCE();
 
     auto k_tile = [&](auto parity, int t) {
         constexpr int X = decltype(parity)::value, Y = 1 - X;
+        constexpr int kFirstLoadSlot = kMfmas - 2 * kLoads;         // the loads sit behind every second MFMA at the end of chunk 3
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int cur = c & 1, nxt = cur ^ 1;
 #pragma unroll
-            for (int m = 0; m < 64; ++m) {
-                const int s = m >> 4, i = (m >> 2) & 3, j = m & 3;
-                const bool loads = c == 3 && m >= 32 && !(m & 1);
-                if (loads) load_m0(X, (m - 32) >> 1);
+            for (int m = 0; m < kMfmas; ++m) {
+                const int s = m / (WM * WN), i = (m / WN) % WM, j = m % WN;
+                const bool loads = c == 3 && m >= kFirstLoadSlot && !((m - kFirstLoadSlot) & 1);
+                if (loads) load_m0(X, (m - kFirstLoadSlot) >> 1);
                 {
                     const float av = fa[cur][i][s], bv = fb[cur][j][s];
                     asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(av), "v"(bv));
                 }
-                if (loads) load_go((m - 32) >> 1, t + 2);
-                if (m < kReadsA + kReadsB) {
+                if (loads) load_go((m - kFirstLoadSlot) >> 1, t + 2);
+                if (m < kReads) {
                     if (c < 3) read(X, c + 1, nxt, m);
                     else read(Y, 0, nxt, m);
                 }
@@ -197,9 +240,9 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     // unknown to the compiler as such) have written their accumulators before these are read.
     asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < WN; ++j) {
             const int col = n0 + wn0 + j * 32 + li;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -210,44 +253,80 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
         }
 }
 
-template <int ALAY, int BLAY>
+template <int WM, int WN, int ALAY, int BLAY>
 hipError_t launch_main(const GemmArgs &a, hipStream_t s)
 {
-    auto kern = gemm_f32_main_kernel<ALAY, BLAY>;
+    constexpr int kLdsBytes = 2 * (64 * WM + 64 * WN) * kBK * 4;
+    auto kern = gemm_f32_main_kernel<WM, WN, ALAY, BLAY>;
     static std::atomic<uint64_t> configured{0};
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kLdsBytes, configured);
     if (e != hipSuccess) return e;
-    const int tiles_m = (a.M + kBM - 1) / kBM, tiles_n = (a.N + kBN - 1) / kBN;
+    const int tiles_m = (a.M + 64 * WM - 1) / (64 * WM), tiles_n = (a.N + 64 * WN - 1) / (64 * WN);
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLdsBytes, s, a, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
-}  // namespace
-
-// <A layout, B layout> with 0 = contiguous along k, 1 = along m / n; as a profiler trace prints the kernel
-const char *f32_main_kernel_name(int a_lay, int b_lay)
+template <int WM, int WN>
+hipError_t launch_shape(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
-    static const char *names[2][2] = {{"gemm_f32_main_kernel<0, 0>", "gemm_f32_main_kernel<0, 1>"},
-                                      {"gemm_f32_main_kernel<1, 0>", "gemm_f32_main_kernel<1, 1>"}};
-    return names[a_lay][b_lay];
+    if constexpr (WM == 3) {        // 192 rows: A contiguous along k only
+        if (a_lay != kKContig) return hipErrorInvalidValue;
+        return b_lay == kKContig ? launch_main<WM, WN, kKContig, kKContig>(a, s) : launch_main<WM, WN, kKContig, kMnContig>(a, s);
+    } else {
+        if (a_lay == kKContig) return b_lay == kKContig ? launch_main<WM, WN, kKContig, kKContig>(a, s) : launch_main<WM, WN, kKContig, kMnContig>(a, s);
+        return b_lay == kKContig ? launch_main<WM, WN, kMnContig, kKContig>(a, s) : launch_main<WM, WN, kMnContig, kMnContig>(a, s);
+    }
 }
 
-// Whole unchecked 256 x 256 x 32 tiles of 16-byte pieces: a matrix at least one tile high and wide (a ragged
-// last tile is shifted back into it), whole K-tiles, 16-byte aligned bases and rows, and, for an operand that is
-// contiguous along m (n), M (N) a multiple of 4 so that a shifted tile still starts on a piece.
-bool f32_main_fits(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb)
+constexpr int kShapeM[kF32MainShapes] = {256, 192, 128, 256, 192, 128}, kShapeN[kF32MainShapes] = {256, 256, 256, 128, 128, 128};
+
+}  // namespace
+
+int f32_main_tile_m(int shape) { return kShapeM[shape]; }
+int f32_main_tile_n(int shape) { return kShapeN[shape]; }
+
+// <blocks of 32 rows per wavefront, blocks of 32 columns, A layout, B layout> with 0 = contiguous along k, 1 = along
+// m / n; as a profiler trace prints the kernel
+const char *f32_main_kernel_name(int shape, int a_lay, int b_lay)
 {
+    struct Names {
+        char text[kF32MainShapes][2][2][40];
+        Names()
+        {
+            for (int sh = 0; sh < kF32MainShapes; ++sh)
+                for (int a = 0; a < 2; ++a)
+                    for (int b = 0; b < 2; ++b)
+                        snprintf(text[sh][a][b], sizeof text[sh][a][b], "gemm_f32_main_kernel<%d, %d, %d, %d>", kShapeM[sh] / 64, kShapeN[sh] / 64, a, b);
+        }
+    };
+    static const Names names;
+    return names.text[shape][a_lay][b_lay];
+}
+
+// Whole unchecked tiles of 16-byte pieces: a matrix at least one tile high and wide (a ragged last tile is shifted
+// back into it), whole K-tiles of 32, 16-byte aligned bases and rows, for an operand that is contiguous along
+// m (n) M (N) a multiple of 4 so that a shifted tile still starts on a piece, and no side of 192 along such an operand.
+bool f32_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb)
+{
+    if (shape < 0 || shape >= kF32MainShapes) return false;
+    const int bm = kShapeM[shape], bn = kShapeN[shape];
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) == 0 && lda % 4 == 0 && ldb % 4 == 0;
-    return aligned && M >= kBM && N >= kBN && K >= kBK && K % kBK == 0 && (a_lay == kKContig || M % 4 == 0) &&
-           (b_lay == kKContig || N % 4 == 0) && ((M + kBM - 1) / kBM) * ((N + kBN - 1) / kBN) < ((int64_t)1 << 31);
+    return aligned && M >= bm && N >= bn && K >= kBK && K % kBK == 0 && (a_lay == kKContig || (M % 4 == 0 && bm != 192)) &&
+           (b_lay == kKContig || (N % 4 == 0 && bn != 192)) && ((M + bm - 1) / bm) * ((N + bn - 1) / bn) < ((int64_t)1 << 31);
 }
 
 // requires f32_main_fits(...) and a.k_slices == 1
-hipError_t launch_f32_main(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
+hipError_t launch_f32_main(int shape, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
-    if (!f32_main_fits(a_lay, b_lay, a.M, a.N, a.K, a.A, a.lda, a.B, a.ldb) || a.k_slices != 1) return hipErrorInvalidValue;
-    if (a_lay == kKContig) return b_lay == kKContig ? launch_main<kKContig, kKContig>(a, s) : launch_main<kKContig, kMnContig>(a, s);
-    return b_lay == kKContig ? launch_main<kMnContig, kKContig>(a, s) : launch_main<kMnContig, kMnContig>(a, s);
+    if (!f32_main_fits(shape, a_lay, b_lay, a.M, a.N, a.K, a.A, a.lda, a.B, a.ldb) || a.k_slices != 1) return hipErrorInvalidValue;
+    switch (shape) {
+    case 0: return launch_shape<4, 4>(a_lay, b_lay, a, s);
+    case 1: return launch_shape<3, 4>(a_lay, b_lay, a, s);
+    case 2: return launch_shape<2, 4>(a_lay, b_lay, a, s);
+    case 3: return launch_shape<4, 2>(a_lay, b_lay, a, s);
+    case 4: return launch_shape<3, 2>(a_lay, b_lay, a, s);
+    default: return launch_shape<2, 2>(a_lay, b_lay, a, s);
+    }
 }
 
 }  // namespace fsrgemm

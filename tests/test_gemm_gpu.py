@@ -291,7 +291,8 @@ def test_bf16_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
     assert np.array_equal(run_bf16(gpu, Ai, Bi).astype(np.float64), ref)
 
 
-@pytest.mark.parametrize("shape,kernel", [((4000, 2040, 64), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+@pytest.mark.parametrize("shape,kernel", [((4000, 2040, 64), "gemm_f32_main_kernel<2, 4, 0, 1>"),
+                                          ((4000, 2040, 80), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
                                           ((2040, 2030, 48), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
                                           ((1000, 1000, 1008), "gemm_f32_kernel<1, 1, 4, 0, 0, 1>"),
                                           ((65, 129, 32), "gemm_f32_kernel<1, 1, 4, 0, 0, 1>")])
@@ -311,11 +312,13 @@ def test_f32_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
 
 
 @pytest.mark.parametrize("shape,kernel", [((2048, 2048, 16), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
-                                          ((2048, 2048, 32), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
+                                          ((2048, 2048, 32), "gemm_f32_main_kernel<2, 2, 0, 1>"),        # whole K-tiles of 32: the direct-to-LDS kernel
+                                          ((2048, 2048, 48), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
                                           ((2048, 2048, 112), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
                                           ((4096, 2048, 16), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
                                           ((4096, 2048, 48), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
-                                          ((4096, 2048, 160), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")])
+                                          ((4096, 2048, 176), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+                                          ((4096, 2048, 160), "gemm_f32_main_kernel<2, 4, 0, 1>")])
 def test_f32_tile_configs_small_k(gpu, shape, kernel):
     # prologue, odd/even K-tile tails and the clamped prefetch of the two large tile configurations; full oracle comparison
     M, N, K = shape
@@ -323,45 +326,55 @@ def test_f32_tile_configs_small_k(gpu, shape, kernel):
     assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == kernel
     A, B = inputs.uniform_pm1(6, K, M, K), inputs.uniform_pm1(6, K + 1, K, N)
     check_f32(gpu, A, B, repeat=2)
-    if K in (112, 160):
+    if K in (112, 160, 176):
         assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K + 4, 0x1000, N + 12, 0x1000, N + 1) == kernel
         check_f32(gpu, A, B, lda=K + 4, ldb=N + 12, ldc=N + 1)
         Ai, Bi = inputs.small_ints(6, 90, M, K), inputs.small_ints(6, 91, K, N)
         assert np.array_equal(run_f32(gpu, Ai, Bi).astype(np.float64), oracle.gemm(Ai, Bi)[0])
 
 
+MAIN_SHAPES = {5: (256, 256), 6: (192, 256), 7: (128, 256), 8: (256, 128), 9: (192, 128), 10: (128, 128)}     # fp32 candidates 5..10
+
+
 @pytest.mark.parametrize("ta,tb", [(0, 0)] + LAYOUTS)
 @pytest.mark.parametrize("shape", [(512, 768, 32), (512, 512, 64), (768, 512, 96), (256, 256, 224),     # whole tiles, 1 / 2 / 3 / 7 K-tiles
                                    (520, 392, 128), (264, 1284, 64), (1000, 260, 160)])                 # shifted last tiles
 def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
-    # the 256 x 256 direct-to-LDS fp32 kernel, forced: prologue, odd / even tails, the clamped loads two K-tiles ahead,
-    # operands contiguous along k and along m / n, padded leading dimensions, small integers
+    # the direct-to-LDS fp32 kernel in its six tile shapes, forced: prologue, odd / even tails, the clamped loads two
+    # K-tiles ahead, operands contiguous along k and along m / n, padded leading dimensions, small integers
     M, N, K = shape
-    say("f32 main kernel storage %d%d %dx%dx%d" % (ta, tb, M, N, K))
     lda, ldb = (M if ta else K), (K if tb else N)
-    name = "gemm_f32_main_kernel<%d, %d>" % (ta, 1 - tb)
-    assert gpu.fsrgemm_kernel_for_f32_cfg(5, ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name
     A, B = inputs.uniform_pm1(19, 1, M, K), inputs.uniform_pm1(19, 2, K, N)
     ref, S = oracle.gemm(A, B)
-    got = run_cfg(gpu, "f32", 5, 1, ta, tb, A, B, repeat=2)
-    assert oracle.componentwise_error(got, ref, S) <= TOL_F32
-    assert gpu.fsrgemm_kernel_for_f32_cfg(5, ta, tb, M, N, K, 0x1000, lda + 4, 0x1000, ldb + 36, 0x1000, N + 3) == name
-    got = run_cfg(gpu, "f32", 5, 1, ta, tb, A, B, lda=lda + 4, ldb=ldb + 36, ldc=N + 3, repeat=2)
-    assert oracle.componentwise_error(got, ref, S) <= TOL_F32
     Ai, Bi = inputs.small_ints(0, 19, M, K), inputs.small_ints(0, 20, K, N)
     refi, _ = oracle.gemm(Ai, Bi)
-    assert np.array_equal(run_cfg(gpu, "f32", 5, 1, ta, tb, Ai, Bi).astype(np.float64), refi)
-    # where the candidate does not fit it is rejected: a split, a misaligned base, rows that are not whole pieces
-    for kw, slices in ((dict(), 2), (dict(offset=1), 1), (dict(lda=lda + 2), 1)):
-        with pytest.raises(gpu.FsrGemmError):
-            run_cfg(gpu, "f32", 5, slices, ta, tb, A, B, **kw)
+    for tile, (bm, bn) in MAIN_SHAPES.items():
+        say("f32 main kernel %dx%d storage %d%d %dx%dx%d" % (bm, bn, ta, tb, M, N, K))
+        # a side of 192 only along an operand that is contiguous along k
+        fits = M >= bm and N >= bn and not (ta and bm == 192) and not (not tb and bn == 192)
+        name = "gemm_f32_main_kernel<%d, %d, %d, %d>" % (bm // 64, bn // 64, ta, 1 - tb) if fits else None
+        assert gpu.fsrgemm_kernel_for_f32_cfg(tile, ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name
+        if not fits:
+            with pytest.raises(gpu.FsrGemmError):
+                run_cfg(gpu, "f32", tile, 1, ta, tb, A, B)
+            continue
+        got = run_cfg(gpu, "f32", tile, 1, ta, tb, A, B, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        assert gpu.fsrgemm_kernel_for_f32_cfg(tile, ta, tb, M, N, K, 0x1000, lda + 4, 0x1000, ldb + 36, 0x1000, N + 3) == name
+        got = run_cfg(gpu, "f32", tile, 1, ta, tb, A, B, lda=lda + 4, ldb=ldb + 36, ldc=N + 3, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        assert np.array_equal(run_cfg(gpu, "f32", tile, 1, ta, tb, Ai, Bi).astype(np.float64), refi)
+        # where the candidate does not fit it is rejected: a split, a misaligned base, rows that are not whole pieces
+        for kw, slices in ((dict(), 2), (dict(offset=1), 1), (dict(lda=lda + 2), 1)):
+            with pytest.raises(gpu.FsrGemmError):
+                run_cfg(gpu, "f32", tile, slices, ta, tb, A, B, **kw)
 
 
 def test_f32_main_kernel_is_the_dispatchers_choice(gpu):
     # 16 x 16 tiles of 256 fill the compute units exactly once: the dispatcher takes the direct-to-LDS kernel, and
     # forcing it gives the same bits; a K that is not whole tiles of 32 goes to the general kernel
     M = N = 4096
-    for K, kernel in ((64, "gemm_f32_main_kernel<0, 1>"), (48, "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")):
+    for K, kernel in ((64, "gemm_f32_main_kernel<4, 4, 0, 1>"), (48, "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")):
         say("f32 4096x4096x%d through the dispatcher" % K)
         assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == kernel
         A, B = inputs.uniform_pm1(19, 3, M, K), inputs.uniform_pm1(19, 4, K, N)
@@ -460,7 +473,7 @@ def test_f32_4096_normal_full_size(gpu):
     say("fp32 4096^3 normal seed 2 (sampled rows, columns, entries + Freivalds)")
     n = 4096
     A, B = inputs.normal(2, 1, n, n), inputs.normal(2, 2, n, n)
-    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_main_kernel<0, 1>"
+    assert gpu.fsrgemm_kernel_for_f32(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_f32_main_kernel<4, 4, 0, 1>"
     got = run_f32(gpu, A, B)
     rng = np.random.default_rng(2)
     rows, cols = np.sort(rng.choice(n, 64, replace=False)), np.sort(rng.choice(n, 64, replace=False))
@@ -513,7 +526,7 @@ def test_f32_paper_task2_largest_size(gpu):
     A = np.empty((M, K), dtype=np.float32)
     for b in range(64):
         A[b * 4096:(b + 1) * 4096] = block * np.float32(2.0 ** ((b % 5) - 2))
-    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == "gemm_f32_main_kernel<0, 1>"
+    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == "gemm_f32_main_kernel<4, 4, 0, 1>"
     a, b_, c = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), torch.full((M, N), float("nan"), device="cuda")
     gpu.check(gpu.gemm_f32(M, N, K, a, K, b_, N, c, N, torch.cuda.current_stream().cuda_stream))
     torch.cuda.synchronize()
