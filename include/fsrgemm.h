@@ -159,8 +159,9 @@ int gemm_bf16_ws(int transA, int transB,
  *               sums (both operands stored with k as the row index: transA != 0 or M == 1, transB == 0 or N == 1; M, N <= 16 with
  *               at most 144 entries after rounding both up to multiples of 4; K > 0), whose
  *               k_slices are workgroups (1..256, at most K) that each keep a partial result in the workspace, so it
- *               needs its workspace even for one, 5..10 = the direct-to-LDS kernel with tiles 256 x 256, 192 x 256,
- *               128 x 256, 256 x 128, 192 x 128, 128 x 128 (fsrgemm_tile_count_f32() = 11);
+ *               needs its workspace even for one, 5..13 = the direct-to-LDS kernel with tiles 256 x 256, 192 x 256,
+ *               128 x 256, 256 x 128, 192 x 128, 128 x 128, 256 x 192, 192 x 192, 128 x 192
+ *               (fsrgemm_tile_count_f32() = 14);
  *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64, 4 = the streaming
  *               kernels for M == 1 or N == 1 with K > 0 (fsrgemm_tile_count_bf16() = 5).
  *   k_slices: 1 = K in one piece; 2..64 = split along K as gemm_f32_ws does, which needs a workspace of
@@ -170,9 +171,9 @@ int gemm_bf16_ws(int transA, int transB,
  * count out of range, a split without a fitting workspace, fp32 candidate 3 or bf16 candidate 4 on a product
  * without a vector,
  * fp32 candidate 4 on a result that is too large,
- * fp32 tiles 5..10 with a split or where their kernel's conditions fail (M, N at least one tile, K a positive
+ * fp32 tiles 5..13 with a split or where their kernel's conditions fail (M, N at least one tile, K a positive
  * multiple of 32, 16-byte aligned operands with leading dimensions that are multiples of 4; M or N a multiple of 4
- * for an operand contiguous along it, and no tile side of 192 along such an operand),
+ * for an operand contiguous along it),
  * bf16 tile 0 with a split or where its kernel's
  * conditions fail (M, N >= 256, K a multiple of 64, 16-byte aligned operands with leading dimensions that are
  * multiples of 8 and below 2^25; M or N a multiple of 8 for an operand contiguous along it).  Every other

@@ -110,7 +110,7 @@ int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *
 // unit, 221 alone.  K cancels.  Equal costs go to the larger tile.  The direct-to-LDS kernel runs one workgroup
 // per compute unit; its shapes (main_fits: bit s set if shape s can take the problem) enter with their own tile
 // times and win where their tiles fill whole rounds.
-constexpr int64_t kMainTileTime[kF32MainShapes] = {2230, 1710, 1120, 1120, 838, 566};   // 256x256, 192x256, 128x256, 256x128, 192x128, 128x128
+constexpr int64_t kMainTileTime[kF32MainShapes] = {2230, 1710, 1120, 1120, 838, 566, 1715, 1286, 845};   // in the order of the shapes
 int tile_rule_f32(int64_t M, int64_t N, unsigned main_fits)
 {
     constexpr int64_t kTileTime[kF32ConfigCount] = {1137, 569, 169}, kAlone[kF32ConfigCount] = {1137, 569, 221};

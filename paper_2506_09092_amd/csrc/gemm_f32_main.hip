@@ -46,9 +46,8 @@
 //
 // Tile shapes.  A launch lasts as long as the compute unit with the most tiles, so a problem whose 256 x 256 tiles
 // do not fill whole rounds of the 256 compute units is better off with a smaller tile that does: the kernel is a
-// template over the blocks per wavefront, WM x WN of 32 x 32 (tile 64 WM x 64 WN), instantiated for 256 x 256,
-// 192 x 256, 128 x 256, 256 x 128, 192 x 128 and 128 x 128.  A side of 192 needs that operand contiguous along k
-// (its k-rows would be 768 bytes, which a 1 KB load does not divide).  Loads per wavefront and K-tile: 2 WM + 2 WN.
+// template over the blocks per wavefront, WM x WN of 32 x 32 (tile 64 WM x 64 WN), instantiated for the nine shapes
+// with sides of 256, 192 and 128.  Loads per wavefront and K-tile: 2 WM + 2 WN.
 #include <stdio.h>
 
 #include <type_traits>
@@ -75,8 +74,6 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     constexpr int kBytesA = BM * kBK * 4, kBytesB = BN * kBK * 4, kStageBytes = kBytesA + kBytesB;
     constexpr int kLoadsA = 2 * WM, kLoadsB = 2 * WN, kLoads = kLoadsA + kLoadsB;     // 1 KB each, per wavefront and K-tile
     constexpr int kMfmas = 4 * WM * WN;                                               // per chunk of 8 k
-    static_assert(ALAY == kKContig || WM != 3, "k-rows of 768 bytes are not built");
-    static_assert(BLAY == kKContig || WN != 3, "k-rows of 768 bytes are not built");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     int tile_m, tile_n;
     tile_coords(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -92,22 +89,28 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     // [(w EXT / 32 + q) KB, +1 KB) of the operand's tile:
     //   along k   : rows w EXT / 4 + 8 q + lane / 8, position lane % 8, which holds piece
     //               (lane % 8) ^ ((row >> 1) & 7) with (row >> 1) & 7 = (4 q + (lane >> 4)) & 7
-    //   along m/n : k-rows of 4 EXT bytes, 1 or 2 per load: k-row (w EXT / 32 + q) (256 / EXT) + lane / (EXT / 4),
-    //               piece lane % (EXT / 4)
+    //   along m/n : k-rows of 4 EXT bytes, stored back to back.  The load starts (1024 q) mod (4 EXT) bytes into k-row
+    //               (w EXT / 32 + q) 256 / EXT (rounded down) and runs on into the next k-row where that one ends:
+    //               1 KB is one k-row of 256 columns, two of 128, and one and a third of 192, where the start
+    //               takes three values in turn
     // The address of a load is a wavefront-uniform pointer (scalar arithmetic, free beside the MFMAs) plus a 32-bit
-    // lane offset that is fixed for the whole kernel: two per operand, by the parity of q (equal along m/n).
+    // lane offset that is fixed for the whole kernel: up to three per operand, by q mod 2 (along k) or q mod 3.
     // K-tiles beyond the last one (the pipeline asks for two ahead) repeat the last: in bounds and never read.
-    auto lane_offset = [&](auto layout, auto extent, int64_t ld, int odd) -> uint32_t {
+    auto lane_offset = [&](auto layout, auto extent, int64_t ld, int q) -> uint32_t {
         constexpr int LAY = decltype(layout)::value, EXT = decltype(extent)::value;
-        if constexpr (LAY == kKContig) return (uint32_t)(((lane >> 3) * ld + (((lane & 7) ^ ((4 * odd + (lane >> 4)) & 7)) << 2)) << 2);
-        else return (uint32_t)(((lane / (EXT / 4)) * ld + (lane % (EXT / 4)) * 4) << 2);
+        if constexpr (LAY == kKContig) {
+            return (uint32_t)(((lane >> 3) * ld + (((lane & 7) ^ ((4 * (q & 1) + (lane >> 4)) & 7)) << 2)) << 2);
+        } else {
+            const int pos = (1024 * q) % (4 * EXT) + 16 * lane;
+            return (uint32_t)((pos / (4 * EXT)) * ld * 4 + pos % (4 * EXT));
+        }
     };
     using LayA = std::integral_constant<int, ALAY>;
     using LayB = std::integral_constant<int, BLAY>;
     using ExtA = std::integral_constant<int, BM>;
     using ExtB = std::integral_constant<int, BN>;
-    const uint32_t a_off[2] = {lane_offset(LayA{}, ExtA{}, g.lda, 0), lane_offset(LayA{}, ExtA{}, g.lda, 1)};
-    const uint32_t b_off[2] = {lane_offset(LayB{}, ExtB{}, g.ldb, 0), lane_offset(LayB{}, ExtB{}, g.ldb, 1)};
+    const uint32_t a_off[3] = {lane_offset(LayA{}, ExtA{}, g.lda, 0), lane_offset(LayA{}, ExtA{}, g.lda, 1), lane_offset(LayA{}, ExtA{}, g.lda, 2)};
+    const uint32_t b_off[3] = {lane_offset(LayB{}, ExtB{}, g.ldb, 0), lane_offset(LayB{}, ExtB{}, g.ldb, 1), lane_offset(LayB{}, ExtB{}, g.ldb, 2)};
     // The loads of a K-tile in issue order: A's and B's alternate while both last.  -> operand (0 A, 1 B) and q
     auto which = [](int idx, int &operand, int &q) {
         constexpr int kBoth = 2 * (kLoadsA < kLoadsB ? kLoadsA : kLoadsB);
@@ -126,7 +129,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
         dst += stage * kStageBytes + operand * kBytesA + q * 1024;
         asm volatile("s_mov_b32 m0, %0" ::"s"(dst) : "m0");
     };
-    auto dma = [&](auto layout, auto extent, const float *__restrict__ P, int64_t ld, int origin, const uint32_t (&off)[2], int q, int t) {
+    auto dma = [&](auto layout, auto extent, const float *__restrict__ P, int64_t ld, int origin, const uint32_t (&off)[3], int q, int t) {
         constexpr int LAY = decltype(layout)::value, EXT = decltype(extent)::value;
         const int tc = t < nk ? t : nk - 1;
         // The base is worked out anew for every load (a handful of scalar instructions): kept across the loop, the
@@ -137,8 +140,9 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
         asm volatile("" : "+s"(zero));
         const float *row;       // uniform
         if constexpr (LAY == kKContig) row = P + (int64_t)(origin + wave * (EXT / 4) + 8 * q + zero) * ld + tc * kBK;
-        else row = P + (int64_t)(tc * kBK + (wave * (EXT / 32) + q) * (256 / EXT)) * ld + origin;
-        asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(off[q & 1]), "s"(row) : "memory");
+        else row = P + (int64_t)(tc * kBK + (wave * (EXT / 32) + q) * 256 / EXT) * ld + origin;
+        const int variant = LAY == kKContig ? q & 1 : EXT == 192 ? q % 3 : 0;      // which of the operand's lane offsets
+        asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(off[variant]), "s"(row) : "memory");
     };
     auto load_go = [&](int idx, int t) {
         int operand, q;
@@ -269,16 +273,12 @@ hipError_t launch_main(const GemmArgs &a, hipStream_t s)
 template <int WM, int WN>
 hipError_t launch_shape(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
-    if constexpr (WM == 3) {        // 192 rows: A contiguous along k only
-        if (a_lay != kKContig) return hipErrorInvalidValue;
-        return b_lay == kKContig ? launch_main<WM, WN, kKContig, kKContig>(a, s) : launch_main<WM, WN, kKContig, kMnContig>(a, s);
-    } else {
-        if (a_lay == kKContig) return b_lay == kKContig ? launch_main<WM, WN, kKContig, kKContig>(a, s) : launch_main<WM, WN, kKContig, kMnContig>(a, s);
-        return b_lay == kKContig ? launch_main<WM, WN, kMnContig, kKContig>(a, s) : launch_main<WM, WN, kMnContig, kMnContig>(a, s);
-    }
+    if (a_lay == kKContig) return b_lay == kKContig ? launch_main<WM, WN, kKContig, kKContig>(a, s) : launch_main<WM, WN, kKContig, kMnContig>(a, s);
+    return b_lay == kKContig ? launch_main<WM, WN, kMnContig, kKContig>(a, s) : launch_main<WM, WN, kMnContig, kMnContig>(a, s);
 }
 
-constexpr int kShapeM[kF32MainShapes] = {256, 192, 128, 256, 192, 128}, kShapeN[kF32MainShapes] = {256, 256, 256, 128, 128, 128};
+// in the order of the candidate numbers: the first six were there first
+constexpr int kShapeM[kF32MainShapes] = {256, 192, 128, 256, 192, 128, 256, 192, 128}, kShapeN[kF32MainShapes] = {256, 256, 256, 128, 128, 128, 192, 192, 192};
 
 }  // namespace
 
@@ -305,14 +305,14 @@ const char *f32_main_kernel_name(int shape, int a_lay, int b_lay)
 
 // Whole unchecked tiles of 16-byte pieces: a matrix at least one tile high and wide (a ragged last tile is shifted
 // back into it), whole K-tiles of 32, 16-byte aligned bases and rows, for an operand that is contiguous along
-// m (n) M (N) a multiple of 4 so that a shifted tile still starts on a piece, and no side of 192 along such an operand.
+// m (n) M (N) a multiple of 4 so that a shifted tile still starts on a piece.
 bool f32_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb)
 {
     if (shape < 0 || shape >= kF32MainShapes) return false;
     const int bm = kShapeM[shape], bn = kShapeN[shape];
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) == 0 && lda % 4 == 0 && ldb % 4 == 0;
-    return aligned && M >= bm && N >= bn && K >= kBK && K % kBK == 0 && (a_lay == kKContig || (M % 4 == 0 && bm != 192)) &&
-           (b_lay == kKContig || (N % 4 == 0 && bn != 192)) && ((M + bm - 1) / bm) * ((N + bn - 1) / bn) < ((int64_t)1 << 31);
+    return aligned && M >= bm && N >= bn && K >= kBK && K % kBK == 0 && (a_lay == kKContig || M % 4 == 0) &&
+           (b_lay == kKContig || N % 4 == 0) && ((M + bm - 1) / bm) * ((N + bn - 1) / bn) < ((int64_t)1 << 31);
 }
 
 // requires f32_main_fits(...) and a.k_slices == 1
@@ -325,7 +325,10 @@ hipError_t launch_f32_main(int shape, int a_lay, int b_lay, const GemmArgs &a, h
     case 2: return launch_shape<2, 4>(a_lay, b_lay, a, s);
     case 3: return launch_shape<4, 2>(a_lay, b_lay, a, s);
     case 4: return launch_shape<3, 2>(a_lay, b_lay, a, s);
-    default: return launch_shape<2, 2>(a_lay, b_lay, a, s);
+    case 5: return launch_shape<2, 2>(a_lay, b_lay, a, s);
+    case 6: return launch_shape<4, 3>(a_lay, b_lay, a, s);
+    case 7: return launch_shape<3, 3>(a_lay, b_lay, a, s);
+    default: return launch_shape<2, 3>(a_lay, b_lay, a, s);
     }
 }
 

@@ -164,10 +164,10 @@ def test_workspace_query_and_argument_checks():
 
 def test_f32_tile_rule_follows_the_round_model():
     # fewest rounds of 256 tiles, weighted by the tile's time; sizes where the configurations win in turn.  The
-    # direct-to-LDS kernel (5..10: 256 x 256, 192 x 256, 128 x 256, 256 x 128, 192 x 128, 128 x 128) enters where it fits
+    # direct-to-LDS kernel (5..13: tiles with sides of 256, 192 and 128) enters where it fits
     # (aligned operands, whole K-tiles of 32) with the shape whose tiles fill whole rounds
     pf = lambda n, a=P, K=None: lib.fsrgemm_plan_f32(0, 0, n, n, K or n, a, K or n, P, n)[0]
-    assert [pf(n) for n in (1024, 2048, 3072, 4096, 6144, 8192)] == [2, 10, 2, 5, 9, 5]
+    assert [pf(n) for n in (1024, 2048, 3072, 4096, 6144, 8192)] == [2, 10, 12, 5, 9, 5]
     assert [pf(n, P + 4) for n in (4096, 8192)] == [0, 0] and pf(4096, K=4112) == 0      # misaligned A / a ragged K: the general kernel
     assert lib.fsrgemm_plan_f32(0, 0, 10, 100000, 64, P, 64, P, 100000)[0] == 2          # a sliver: small tiles waste least
     assert lib.fsrgemm_plan_f32(0, 0, 262144, 2048, 4096, P, 4096, P, 2048)[0] == 5        # the paper's largest Task-2 size
@@ -175,9 +175,9 @@ def test_f32_tile_rule_follows_the_round_model():
 
 def test_forced_configurations_and_plan_queries():
     bad, ok = lib.FSRGEMM_ERR_INVALID_ARG, lib.FSRGEMM_OK
-    assert lib.fsrgemm_tile_count_f32() == 11 and lib.fsrgemm_tile_count_bf16() == 5
+    assert lib.fsrgemm_tile_count_f32() == 14 and lib.fsrgemm_tile_count_bf16() == 5
     f = lambda tile, s, ws=None, wsb=0, M=64, N=64, K=4096: lib.gemm_f32_cfg(tile, s, 0, 0, M, N, K, P, K, P, N, P, N, ws, wsb, 0)
-    assert f(-1, 1) == bad and f(11, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
+    assert f(-1, 1) == bad and f(14, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
     assert f(3, 1) == bad and f(3, 1, K=0, M=1) == bad                          # the vector kernels need M or N = 1 and K > 0
     assert f(2, 4) == bad and f(2, 4, P, 4 * 64 * 64 * 4 - 1) == bad            # a split without / with too small a workspace
     assert f(2, 4, P + 2, 1 << 20) == bad                                      # misaligned workspace
@@ -194,7 +194,7 @@ def test_forced_configurations_and_plan_queries():
     # names of forced candidates; None where the forced call would reject the candidate
     qc, qh = lib.fsrgemm_kernel_for_f32_cfg, lib.fsrgemm_kernel_for_bf16_cfg
     assert qc(0, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) == "gemm_f32_kernel<4, 2, 2, 2, 0, 1>"        # the largest tile on a tiny unaligned problem
-    assert qc(3, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) is None and qc(11, 0, 0, 1, 10, 10, P, 10, P, 10, P, 10) is None
+    assert qc(3, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) is None and qc(14, 0, 0, 1, 10, 10, P, 10, P, 10, P, 10) is None
     assert qc(3, 0, 0, 1, 16, 16, P, 16, P, 16, P, 16) == "gemv_cols_f32_kernel<true>"
     assert qh(0, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) == "gemm_bf16_main_kernel<0, 0>"
     assert qh(0, 0, 1, 520, 392, 100, P, 104, P, 104, P, 392) is None and qh(4, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) is None
@@ -219,7 +219,8 @@ def test_forced_configurations_and_plan_queries():
     assert pfw(10, 10, 1 << 22) == (4, 256) and pfw(10, 1, 1 << 14) == (4, 64) and pfw(10, 10, 4095)[0] != 4
     assert lib.fsrgemm_plan_f32(1, 0, 10, 10, 1 << 22, P, 10, P, 10, False) == (2, 1)
     assert lib.gemm_f32_workspace_bytes(1, 0, 10, 10, 1 << 22) == 256 * 100 * 4 and lib.gemm_f32_workspace_bytes(1, 0, 10, 1, 4096) == 16 * 10 * 4
-    # candidates 5..10: the direct-to-LDS kernel with tiles 256 x 256, 192 x 256, 128 x 256, 256 x 128, 192 x 128, 128 x 128;
+    # candidates 5..13: the direct-to-LDS kernel with tiles 256 x 256, 192 x 256, 128 x 256, 256 x 128, 192 x 128, 128 x 128,
+    # 256 x 192, 192 x 192, 128 x 192;
     # rejected where its conditions fail, never replaced, never split
     mk = lambda M, N, K, ta=0, tb=0, a=P, lda=None, s=1, ws=None, wsb=0: lib.gemm_f32_cfg(
         5, s, ta, tb, M, N, K, a, lda or (M if ta else K), P, K if tb else N, P, N, ws, wsb, 0)
@@ -230,7 +231,8 @@ def test_forced_configurations_and_plan_queries():
     assert qc(5, 0, 0, 510, 512, 64, P, 64, P, 512, P, 512) == "gemm_f32_main_kernel<4, 4, 0, 1>"
     assert qc(5, 1, 1, 512, 510, 64, P, 512, P, 64, P, 510) == "gemm_f32_main_kernel<4, 4, 1, 0>"
     assert qc(6, 0, 0, 192, 256, 64, P, 64, P, 256, P, 256) == "gemm_f32_main_kernel<3, 4, 0, 1>" and qc(6, 0, 0, 191, 256, 64, P, 64, P, 256, P, 256) is None
-    assert qc(6, 1, 0, 192, 256, 64, P, 192, P, 256, P, 256) is None                  # 192 rows of an A stored transposed: not built
+    assert qc(6, 1, 0, 192, 256, 64, P, 192, P, 256, P, 256) == "gemm_f32_main_kernel<3, 4, 1, 1>"
+    assert qc(12, 0, 0, 192, 192, 64, P, 64, P, 192, P, 192) == "gemm_f32_main_kernel<3, 3, 0, 1>" and qc(13, 0, 0, 128, 191, 64, P, 64, P, 192, P, 191) is None
     assert qc(10, 1, 0, 128, 128, 32, P, 128, P, 128, P, 128) == "gemm_f32_main_kernel<2, 2, 1, 1>" and qc(10, 0, 0, 128, 127, 32, P, 32, P, 128, P, 127) is None
     assert qc(9, 0, 1, 200, 130, 96, P, 96, P, 96, P, 130) == "gemm_f32_main_kernel<3, 2, 0, 0>"
     assert qc(5, 0, 0, 512, 512, 48, P, 48, P, 512, P, 512) is None

@@ -333,14 +333,15 @@ def test_f32_tile_configs_small_k(gpu, shape, kernel):
         assert np.array_equal(run_f32(gpu, Ai, Bi).astype(np.float64), oracle.gemm(Ai, Bi)[0])
 
 
-MAIN_SHAPES = {5: (256, 256), 6: (192, 256), 7: (128, 256), 8: (256, 128), 9: (192, 128), 10: (128, 128)}     # fp32 candidates 5..10
+MAIN_SHAPES = {5: (256, 256), 6: (192, 256), 7: (128, 256), 8: (256, 128), 9: (192, 128), 10: (128, 128),        # fp32 candidates 5..13
+               11: (256, 192), 12: (192, 192), 13: (128, 192)}
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0)] + LAYOUTS)
 @pytest.mark.parametrize("shape", [(512, 768, 32), (512, 512, 64), (768, 512, 96), (256, 256, 224),     # whole tiles, 1 / 2 / 3 / 7 K-tiles
                                    (520, 392, 128), (264, 1284, 64), (1000, 260, 160)])                 # shifted last tiles
 def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
-    # the direct-to-LDS fp32 kernel in its six tile shapes, forced: prologue, odd / even tails, the clamped loads two
+    # the direct-to-LDS fp32 kernel in its nine tile shapes, forced: prologue, odd / even tails, the clamped loads two
     # K-tiles ahead, operands contiguous along k and along m / n, padded leading dimensions, small integers
     M, N, K = shape
     lda, ldb = (M if ta else K), (K if tb else N)
@@ -350,8 +351,7 @@ def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
     refi, _ = oracle.gemm(Ai, Bi)
     for tile, (bm, bn) in MAIN_SHAPES.items():
         say("f32 main kernel %dx%d storage %d%d %dx%dx%d" % (bm, bn, ta, tb, M, N, K))
-        # a side of 192 only along an operand that is contiguous along k
-        fits = M >= bm and N >= bn and not (ta and bm == 192) and not (not tb and bn == 192)
+        fits = M >= bm and N >= bn
         name = "gemm_f32_main_kernel<%d, %d, %d, %d>" % (bm // 64, bn // 64, ta, 1 - tb) if fits else None
         assert gpu.fsrgemm_kernel_for_f32_cfg(tile, ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name
         if not fits:
