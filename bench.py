@@ -185,6 +185,23 @@ def paper_task2_sizes(lib, torch):
     return out
 
 
+def mid_sizes_f32(lib, torch):
+    """fp32 problems between the small fixed configurations and the headline size, where the number of output tiles
+    per compute unit decides: the kernel and tile shape the dispatcher takes, its rate, and torch.matmul (the vendor
+    library) on the same buffers for scale.  Profiler leg only; these shapes' parity is covered by the GPU tests."""
+    stream = torch.cuda.current_stream().cuda_stream
+    out = []
+    for M, N, K in ((2048, 2048, 2048), (3072, 3072, 3072), (4096, 2048, 4096), (5120, 5120, 2048), (6144, 6144, 2048),
+                    (7168, 7168, 2048), (8192, 8192, 2048), (4096, 4096, 4112)):
+        a, b, c = torch.randn(M, K, device="cuda"), torch.randn(K, N, device="cuda"), torch.empty(M, N, device="cuda")
+        ms = steady_ms(torch, lambda: lib.check(lib.gemm_f32(M, N, K, a, K, b, N, c, N, stream)), samples=5)
+        vendor = steady_ms(torch, lambda: torch.matmul(a, b, out=c), samples=5)
+        out.append({"M": M, "N": N, "K": K, "kernel": lib.fsrgemm_kernel_for_f32(M, N, K, a, K, b, N, c, N), "ms": ms,
+                    "tflops": 2.0 * M * N * K / (ms * 1e-3) / 1e12, "torch_matmul_tflops": 2.0 * M * N * K / (vendor * 1e-3) / 1e12})
+        del a, b, c
+    return out
+
+
 def small_fixed_configs(lib, torch):
     """fp32 256^3 and 1024^3 (the small fixed configurations; parity is a GPU test): these are bound by launch
     latency and by the number of tiles, so the figure of interest is microseconds per launch."""
@@ -489,10 +506,11 @@ def main():
         del w
         torch.cuda.empty_cache()
 
-    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = small = task20 = task15 = None
+    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = small = task20 = task15 = mid = None
     if not args.headline_only:
         small = small_fixed_configs(lib, torch)
         task2 = paper_task2_sizes(lib, torch)
+        mid = mid_sizes_f32(lib, torch)
         layouts = transposed_storage_4096(lib, torch)
         layouts_bf16 = storage_orders_bf16_8192(lib, torch)
         skinny = split_k(lib, torch, "f32")
@@ -529,6 +547,7 @@ def main():
         "other_workload": other,
         "sweep": sweep,
         "paper_task2_shapes": task2,
+        "mid_sizes_f32": mid,
         "transposed_storage_f32_4096": layouts,
         "storage_orders_bf16_8192": layouts_bf16,
         "split_k_f32": skinny,
