@@ -106,7 +106,7 @@ int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *
 // of the output tiles at a rate that depends on the tile only, so a launch takes ceil(tiles / 256) tile times
 // (256 compute units; a last round with few tiles costs a whole one), and never less than the time of one
 // workgroup running alone.  Times per tile and k step, in units of 0.1 ns, measured on square problems with
-// each configuration forced: 256 x 128: 1137, 128 x 128: 569, 64 x 64: 169 with four workgroups per compute
+// each configuration forced: 256 x 128: 1137, 128 x 128: 569, 64 x 64: 169 with several workgroups per compute
 // unit, 221 alone.  K cancels.  Equal costs go to the larger tile.  The direct-to-LDS kernel runs one workgroup
 // per compute unit; its shapes (main_fits: bit s set if shape s can take the problem) enter with their own tile
 // times and win where their tiles fill whole rounds.
