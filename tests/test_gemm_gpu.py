@@ -625,6 +625,11 @@ def test_calls_captured_in_a_hip_graph_replay_bit_exact(gpu):
     # tile 0: the direct-to-LDS kernel, whose loads are issued from inline assembly
     calls.append(lambda: gpu.gemm_bf16_cfg(0, 1, 0, 1, 512, 768, 256, ah, 256, bh, 256, oh, 768, None, 0, stream()))
     outs.append(oh)
+    # fp32 candidates 12 and 9: the fp32 direct-to-LDS kernel (192 x 192 and 192 x 128 tiles), hand-issued loads as well
+    am, bm_, om = torch.randn(400, 96, device="cuda"), torch.randn(96, 388, device="cuda"), torch.empty(2, 400, 388, device="cuda")
+    calls.append(lambda: gpu.gemm_f32_cfg(12, 1, 0, 0, 400, 388, 96, am, 96, bm_, 388, om[0], 388, None, 0, stream()))
+    calls.append(lambda: gpu.gemm_f32_cfg(9, 1, 0, 0, 400, 388, 96, am, 96, bm_, 388, om[1], 388, None, 0, stream()))
+    outs.append(om)
     t_in, t_out = torch.randn(300, 700, device="cuda"), torch.empty(700, 300, device="cuda")
     calls.append(lambda: gpu.transpose_f32(300, 700, t_in, 700, t_out, 300, stream()))
     outs.append(t_out)
@@ -699,12 +704,20 @@ def test_f32_special_values(gpu, M, N, K):
             assert _same_class(got, ref)
             assert np.array_equal(got[fin].astype(np.float64), ref[fin])          # small integers: exact
     assert _same_class(run_f32(gpu, A, B), ref)
+    main_tiles = [t for t, (bm, bn) in MAIN_SHAPES.items() if M >= bm and N >= bn and K % 32 == 0]      # the direct-to-LDS shapes that fit
+    for tile in main_tiles:
+        say("f32 specials %dx%dx%d tile %d" % (M, N, K, tile))
+        got = run_cfg(gpu, "f32", tile, 1, 0, 0, A, B)
+        assert _same_class(got, ref)
+        assert np.array_equal(got[fin].astype(np.float64), ref[fin])
     # subnormal operands and subnormal results are kept, not flushed: scaled small integers stay exact
     for sa, sb in ((2.0 ** -140, 1.0), (2.0 ** -75, 2.0 ** -70)):
         As, Bs = (Ai * np.float32(sa)).astype(np.float32), (Bi * np.float32(sb)).astype(np.float32)
         refs, _ = oracle.gemm(As, Bs)
         assert np.array_equal(run_f32(gpu, As, Bs).astype(np.float64), refs) and np.count_nonzero(refs) > 0
         assert np.array_equal(run_f32_ws(gpu, 0, 0, As, Bs).astype(np.float64), refs)
+        for tile in main_tiles[:2]:
+            assert np.array_equal(run_cfg(gpu, "f32", tile, 1, 0, 0, As, Bs).astype(np.float64), refs)
 
 
 def test_bf16_special_values(gpu):
