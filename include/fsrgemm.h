@@ -171,9 +171,9 @@ int gemm_bf16_ws(int transA, int transB,
  * count out of range, a split without a fitting workspace, fp32 candidate 3 or bf16 candidate 4 on a product
  * without a vector,
  * fp32 candidate 4 on a result that is too large,
- * fp32 tiles 5..13 with a split or where their kernel's conditions fail (M, N at least one tile, K a positive
- * multiple of 32, 16-byte aligned operands with leading dimensions that are multiples of 4; M or N a multiple of 4
- * for an operand contiguous along it),
+ * fp32 tiles 5..13 with a split or where their kernel's conditions fail (M, N at least one tile, K >= 32 and a
+ * multiple of 4 -- of 32 for tile 5 --, 16-byte aligned operands with leading dimensions that are multiples of 4;
+ * M or N a multiple of 4 for an operand contiguous along it),
  * bf16 tile 0 with a split or where its kernel's
  * conditions fail (M, N >= 256, K a multiple of 64, 16-byte aligned operands with leading dimensions that are
  * multiples of 8 and below 2^25; M or N a multiple of 8 for an operand contiguous along it).  Every other

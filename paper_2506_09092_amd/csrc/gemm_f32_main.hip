@@ -62,6 +62,10 @@ constexpr int kBK = 32, kThreads = 256;
 
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
 #define LDS_PTR __attribute__((address_space(3)))
+#define GLOBAL_PTR __attribute__((address_space(1)))
+
+// where the loads of the last, partial K-tile fetch the pieces that lie beyond K
+__device__ __attribute__((aligned(16))) const float kZeroPiece[4] = {0.f, 0.f, 0.f, 0.f};
 
 // M0 is on a clobber list below on purpose (the loads take their LDS address from it); clang warns that it is a
 // reserved register.  Nothing the compiler emits for this kernel uses M0.
@@ -74,6 +78,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     constexpr int kBytesA = BM * kBK * 4, kBytesB = BN * kBK * 4, kStageBytes = kBytesA + kBytesB;
     constexpr int kLoadsA = 2 * WM, kLoadsB = 2 * WN, kLoads = kLoadsA + kLoadsB;     // 1 KB each, per wavefront and K-tile
     constexpr int kMfmas = 4 * WM * WN;                                               // per chunk of 8 k
+    constexpr bool kTakesRestOfK = WM * WN < 16;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     int tile_m, tile_n;
     tile_coords(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -240,6 +245,56 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     }
     if (t < nk) k_tile(std::integral_constant<int, 0>{}, t);
 
+    // The rest of K when K is not whole K-tiles (it is a multiple of 4, so a piece lies inside K or beyond it): one
+    // more K-tile whose pieces beyond K come from a zero piece.  It runs outside the pipeline, once per tile of C: its
+    // loads (one address per lane, through the compiler's builtin) are waited for, then its chunks run with their
+    // fragment reads in front of them.  Not for the 256 x 256 tile, which has no registers to spare for it: that
+    // shape is only launched on whole K-tiles.
+    const int k_rest = kTakesRestOfK ? g.K - nk * kBK : 0;
+    if (k_rest > 0) {
+        auto tail_src = [&](auto layout, auto extent, const float *__restrict__ P, int64_t ld, int origin, int q) -> const float * {
+            constexpr int LAY = decltype(layout)::value, EXT = decltype(extent)::value;
+            if constexpr (LAY == kKContig) {
+                const int piece = (lane & 7) ^ ((4 * (q & 1) + (lane >> 4)) & 7);
+                const int row = origin + wave * (EXT / 4) + 8 * q + (lane >> 3);
+                return 4 * piece < k_rest ? P + (int64_t)row * ld + nk * kBK + 4 * piece : kZeroPiece;
+            } else {
+                const int pos = (1024 * q) % (4 * EXT) + 16 * lane;
+                const int k_row = (wave * (EXT / 32) + q) * 256 / EXT + pos / (4 * EXT);
+                return k_row < k_rest ? P + (int64_t)(nk * kBK + k_row) * ld + origin + (pos % (4 * EXT)) / 4 : kZeroPiece;
+            }
+        };
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();       // every load has landed and every wavefront is done with both stages
+        FENCE();
+#pragma unroll
+        for (int idx = 0; idx < kLoads; ++idx) {
+            int operand, q;
+            which(idx, operand, q);
+            char *dst = lds + operand * kBytesA + (wave * (operand ? kLoadsB : kLoadsA) + q) * 1024;       // stage 0
+            const float *src = operand ? tail_src(LayB{}, ExtB{}, B, g.ldb, n0, q) : tail_src(LayA{}, ExtA{}, A, g.lda, m0, q);
+            __builtin_amdgcn_global_load_lds((const GLOBAL_PTR void *)src, (LDS_PTR void *)dst, 16, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        FENCE();
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (8 * c < k_rest) {
+#pragma unroll
+                for (int idx = 0; idx < kReads; ++idx) read(0, c, 0, idx);
+                FENCE();
+#pragma unroll
+                for (int m = 0; m < kMfmas; ++m) {
+                    const int s = m / (WM * WN), i = (m / WN) % WM, j = m % WN;
+                    const float av = fa[0][i][s], bv = fb[0][j][s];
+                    asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(av), "v"(bv));
+                }
+                FENCE();
+            }
+        }
+    }
+
     // Every global->LDS load has landed before the workgroup gives up its LDS, and the last MFMAs (64 cycles each,
     // unknown to the compiler as such) have written their accumulators before these are read.
     asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
@@ -304,14 +359,15 @@ const char *f32_main_kernel_name(int shape, int a_lay, int b_lay)
 }
 
 // Whole unchecked tiles of 16-byte pieces: a matrix at least one tile high and wide (a ragged last tile is shifted
-// back into it), whole K-tiles of 32, 16-byte aligned bases and rows, for an operand that is contiguous along
+// back into it), at least one K-tile of 32 and K a multiple of 4 (of 32 for the 256 x 256 tile), 16-byte aligned bases and rows,
+// for an operand that is contiguous along
 // m (n) M (N) a multiple of 4 so that a shifted tile still starts on a piece.
 bool f32_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb)
 {
     if (shape < 0 || shape >= kF32MainShapes) return false;
     const int bm = kShapeM[shape], bn = kShapeN[shape];
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) == 0 && lda % 4 == 0 && ldb % 4 == 0;
-    return aligned && M >= bm && N >= bn && K >= kBK && K % kBK == 0 && (a_lay == kKContig || M % 4 == 0) &&
+    return aligned && M >= bm && N >= bn && K >= kBK && K % (bm * bn == 256 * 256 ? kBK : 4) == 0 && (a_lay == kKContig || M % 4 == 0) &&
            (b_lay == kKContig || N % 4 == 0) && ((M + bm - 1) / bm) * ((N + bn - 1) / bn) < ((int64_t)1 << 31);
 }
 

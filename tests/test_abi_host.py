@@ -66,10 +66,11 @@ def test_dispatch_query_names_variants():
     unaligned = q(123, 5, 8, P + 4, 8, P + 4, 5, P, 5)
     # <TM, TN, min waves, load mode, A layout, B layout>: tile (64 TM) x (64 TN); mode 0 unchecked vectors,
     # 1 vectors + predicated edges, 2 scalar; row-major A is contiguous along k (0), row-major B along n (1)
-    # the 256 x 256 direct-to-LDS kernel <A layout, B layout> where it fits and fills whole rounds; K = 4112 is
-    # whole K-tiles of 16 but not of 32
+    # the direct-to-LDS kernel <blocks per wavefront, A layout, B layout> where it fits, in the shape that fills whole
+    # rounds; its 256 x 256 tile takes whole K-tiles of 32 only, and no shape takes a K below 32
     assert fast == "gemm_f32_main_kernel<4, 4, 0, 1>"
-    assert q(4096, 4096, 4112, P, 4112, P, 4096, P, 4096) == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
+    assert q(4096, 4096, 4112, P, 4112, P, 4096, P, 4096) == "gemm_f32_main_kernel<2, 4, 0, 1>"
+    assert q(4096, 4096, 16, P, 16, P, 4096, P, 4096) == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
     assert ragged == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>" and unaligned == "gemm_f32_kernel<1, 1, 4, 2, 0, 1>"
     assert q(4090, 4090, 129, P, 132, P, 4092, P, 4090) == "gemm_f32_kernel<4, 2, 2, 1, 0, 1>"
     # one row and column beyond 4096 would cost the largest tile a whole further round: a smaller one takes it
@@ -91,7 +92,8 @@ def test_dispatch_query_names_variants():
     assert qb(8000, 8000, 8008, P, 8008, P, 8008, P, 8000) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"
     assert qb(255, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_kernel<1, 4, 0, 0, 0>"          # 4 x 128 tiles of 64
     assert q(4000, 4000, 4000, P, 4000, P, 4000, P, 4000) == "gemm_f32_main_kernel<4, 4, 0, 1>"
-    assert q(4000, 4000, 4008, P, 4008, P, 4000, P, 4000) == "gemm_f32_kernel<4, 2, 2, 1, 0, 1>"
+    assert q(4000, 4000, 4008, P, 4008, P, 4000, P, 4000) == "gemm_f32_main_kernel<2, 4, 0, 1>"          # a rest of K: not the 256 x 256 tile
+    assert q(4000, 4000, 4010, P, 4012, P, 4000, P, 4000) == "gemm_f32_kernel<4, 2, 2, 1, 0, 1>"          # K not a multiple of 4
     assert q(63, 4000, 4000, P, 4000, P, 4000, P, 4000) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"            # narrower than a tile
     # other storage orders: <.., A layout, B layout> with 0 = contiguous along k, 1 = along m / n
     qx = lib.fsrgemm_kernel_for_bf16_ex
@@ -124,7 +126,7 @@ def test_transposed_storage_arguments(ta, tb):
     # <TM, TN, min waves, load mode, A layout, B layout>: layout 0 = contiguous along k, 1 = along m / n
     assert q(ta, tb, 4096, 4096, 4096, P, 4096, P, 4096, P, 4096) == "gemm_f32_main_kernel<4, 4, %d, %d>" % (ta, 1 - tb)
     assert q(ta, tb, 4096, 2048, 4096, P, 4096, P, 4096, P, 2048) == "gemm_f32_main_kernel<2, 4, %d, %d>" % (ta, 1 - tb)
-    assert q(ta, tb, 4096, 2048, 4112, P, 4112, P, 4112, P, 2048) == "gemm_f32_kernel<4, 2, 2, 0, %d, %d>" % (ta, 1 - tb)
+    assert q(ta, tb, 4096, 2048, 16, P, 4096, P, 2048, P, 2048) == "gemm_f32_kernel<4, 2, 2, 0, %d, %d>" % (ta, 1 - tb)     # K below a K-tile of 32
     assert q(ta, tb, M, N, K, P, lda_min - 1, P, ldb_min, P, N) is None
     assert lib.fsrgemm_kernel_for_f32(4096, 4096, 4096, P, 4096, P, 4096, P, 4096) == q(0, 0, 4096, 4096, 4096, P, 4096, P, 4096, P, 4096)
 
@@ -168,7 +170,8 @@ def test_f32_tile_rule_follows_the_round_model():
     # (aligned operands, whole K-tiles of 32) with the shape whose tiles fill whole rounds
     pf = lambda n, a=P, K=None: lib.fsrgemm_plan_f32(0, 0, n, n, K or n, a, K or n, P, n)[0]
     assert [pf(n) for n in (1024, 2048, 3072, 4096, 6144, 8192)] == [2, 10, 12, 5, 9, 5]
-    assert [pf(n, P + 4) for n in (4096, 8192)] == [0, 0] and pf(4096, K=4112) == 0      # misaligned A / a ragged K: the general kernel
+    assert [pf(n, P + 4) for n in (4096, 8192)] == [0, 0] and pf(4096, K=4112) == 7      # misaligned A: the general kernel; a rest of K: not the 256 x 256 tile
+    assert lib.fsrgemm_plan_f32(0, 0, 4096, 4096, 4110, P, 4112, P, 4096)[0] == 0 and pf(4096, K=16) == 0     # K not a multiple of 4, K below a K-tile
     assert lib.fsrgemm_plan_f32(0, 0, 10, 100000, 64, P, 64, P, 100000)[0] == 2          # a sliver: small tiles waste least
     assert lib.fsrgemm_plan_f32(0, 0, 262144, 2048, 4096, P, 4096, P, 2048)[0] == 5        # the paper's largest Task-2 size
 

@@ -102,15 +102,16 @@ def test_f32_transposed_storage_sweep(gpu):
 @pytest.mark.parametrize("ta,tb", LAYOUTS)
 def test_f32_transposed_storage_tile_configs(gpu, ta, tb):
     # every tile configuration in its unchecked-vector mode, small K included, and integers bit for bit
-    for (M, N, K), name in (((2048, 2048, 48), "gemm_f32_kernel<2, 2, 3, 0, %d, %d>"),
-                            ((4096, 2048, 16), "gemm_f32_kernel<4, 2, 2, 0, %d, %d>"),
-                            ((4096, 2048, 112), "gemm_f32_kernel<4, 2, 2, 0, %d, %d>"),
-                            ((1024, 1024, 1024), "gemm_f32_kernel<1, 1, 4, 0, %d, %d>")):
+    # (forced: the dispatcher gives most of these shapes to the direct-to-LDS kernel)
+    for (M, N, K), tile, name in (((2048, 2048, 48), 1, "gemm_f32_kernel<2, 2, 3, 0, %d, %d>"),
+                                  ((4096, 2048, 16), 0, "gemm_f32_kernel<4, 2, 2, 0, %d, %d>"),
+                                  ((4096, 2048, 112), 0, "gemm_f32_kernel<4, 2, 2, 0, %d, %d>"),
+                                  ((1024, 1024, 1024), 2, "gemm_f32_kernel<1, 1, 4, 0, %d, %d>")):
         say("transposed %d%d %dx%dx%d" % (ta, tb, M, N, K))
         lda, ldb = (M if ta else K), (K if tb else N)
-        assert gpu.fsrgemm_kernel_for_f32_ex(ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name % (ta, 1 - tb)
+        assert gpu.fsrgemm_kernel_for_f32_cfg(tile, ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name % (ta, 1 - tb)
         A, B = inputs.uniform_pm1(6, 1, M, K), inputs.uniform_pm1(6, 2, K, N)
-        got = run_f32_ex(gpu, ta, tb, A, B, repeat=2)
+        got = run_cfg(gpu, "f32", tile, 1, ta, tb, A, B, repeat=2)
         ref, S = oracle.gemm(A, B)
         assert oracle.componentwise_error(got, ref, S) <= TOL_F32
     A, B = inputs.small_ints(0, 3, 256, 256), inputs.small_ints(0, 4, 256, 256)
@@ -292,7 +293,7 @@ def test_bf16_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
 
 
 @pytest.mark.parametrize("shape,kernel", [((4000, 2040, 64), "gemm_f32_main_kernel<2, 4, 0, 1>"),
-                                          ((4000, 2040, 80), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+                                          ((4000, 2040, 80), "gemm_f32_main_kernel<2, 4, 0, 1>"),          # and a rest of K
                                           ((2040, 2030, 48), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
                                           ((1000, 1000, 1008), "gemm_f32_kernel<1, 1, 4, 0, 0, 1>"),
                                           ((65, 129, 32), "gemm_f32_kernel<1, 1, 4, 0, 0, 1>")])
@@ -311,26 +312,27 @@ def test_f32_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
     assert np.array_equal(run_f32(gpu, Ai, Bi, lda=K, ldb=N + (-N) % 4).astype(np.float64), refi)
 
 
-@pytest.mark.parametrize("shape,kernel", [((2048, 2048, 16), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
-                                          ((2048, 2048, 32), "gemm_f32_main_kernel<2, 2, 0, 1>"),        # whole K-tiles of 32: the direct-to-LDS kernel
-                                          ((2048, 2048, 48), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
-                                          ((2048, 2048, 112), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
-                                          ((4096, 2048, 16), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
-                                          ((4096, 2048, 48), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
-                                          ((4096, 2048, 176), "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
-                                          ((4096, 2048, 160), "gemm_f32_main_kernel<2, 4, 0, 1>")])
-def test_f32_tile_configs_small_k(gpu, shape, kernel):
-    # prologue, odd/even K-tile tails and the clamped prefetch of the two large tile configurations; full oracle comparison
+@pytest.mark.parametrize("shape,tile,kernel", [((2048, 2048, 16), 1, "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
+                                               ((2048, 2048, 32), 1, "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
+                                               ((2048, 2048, 48), 1, "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
+                                               ((2048, 2048, 112), 1, "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
+                                               ((4096, 2048, 16), 0, "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+                                               ((4096, 2048, 48), 0, "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"),
+                                               ((4096, 2048, 160), 0, "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")])
+def test_f32_tile_configs_small_k(gpu, shape, tile, kernel):
+    # prologue, odd/even K-tile tails and the clamped prefetch of the two large tile configurations of the general kernel,
+    # forced (the dispatcher gives these shapes to the direct-to-LDS kernel once K reaches 32); full oracle comparison
     M, N, K = shape
-    say("fp32 %dx%dx%d" % shape)
-    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == kernel
+    say("fp32 %dx%dx%d tile %d" % (M, N, K, tile))
+    assert gpu.fsrgemm_kernel_for_f32_cfg(tile, 0, 0, M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == kernel
     A, B = inputs.uniform_pm1(6, K, M, K), inputs.uniform_pm1(6, K + 1, K, N)
-    check_f32(gpu, A, B, repeat=2)
-    if K in (112, 160, 176):
-        assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K + 4, 0x1000, N + 12, 0x1000, N + 1) == kernel
-        check_f32(gpu, A, B, lda=K + 4, ldb=N + 12, ldc=N + 1)
+    ref, S = oracle.gemm(A, B)
+    assert oracle.componentwise_error(run_cfg(gpu, "f32", tile, 1, 0, 0, A, B, repeat=2), ref, S) <= TOL_F32
+    if K in (112, 160):
+        assert gpu.fsrgemm_kernel_for_f32_cfg(tile, 0, 0, M, N, K, 0x1000, K + 4, 0x1000, N + 12, 0x1000, N + 1) == kernel
+        assert oracle.componentwise_error(run_cfg(gpu, "f32", tile, 1, 0, 0, A, B, lda=K + 4, ldb=N + 12, ldc=N + 1), ref, S) <= TOL_F32
         Ai, Bi = inputs.small_ints(6, 90, M, K), inputs.small_ints(6, 91, K, N)
-        assert np.array_equal(run_f32(gpu, Ai, Bi).astype(np.float64), oracle.gemm(Ai, Bi)[0])
+        assert np.array_equal(run_cfg(gpu, "f32", tile, 1, 0, 0, Ai, Bi).astype(np.float64), oracle.gemm(Ai, Bi)[0])
 
 
 MAIN_SHAPES = {5: (256, 256), 6: (192, 256), 7: (128, 256), 8: (256, 128), 9: (192, 128), 10: (128, 128),        # fp32 candidates 5..13
@@ -339,7 +341,8 @@ MAIN_SHAPES = {5: (256, 256), 6: (192, 256), 7: (128, 256), 8: (256, 128), 9: (1
 
 @pytest.mark.parametrize("ta,tb", [(0, 0)] + LAYOUTS)
 @pytest.mark.parametrize("shape", [(512, 768, 32), (512, 512, 64), (768, 512, 96), (256, 256, 224),     # whole tiles, 1 / 2 / 3 / 7 K-tiles
-                                   (520, 392, 128), (264, 1284, 64), (1000, 260, 160)])                 # shifted last tiles
+                                   (520, 392, 128), (264, 1284, 64), (1000, 260, 160),                  # shifted last tiles
+                                   (512, 512, 44), (520, 392, 100), (384, 388, 60), (256, 512, 36)])    # a rest of K behind 1 / 3 / 1 / 1 K-tiles
 def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
     # the direct-to-LDS fp32 kernel in its nine tile shapes, forced: prologue, odd / even tails, the clamped loads two
     # K-tiles ahead, operands contiguous along k and along m / n, padded leading dimensions, small integers
@@ -351,7 +354,7 @@ def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
     refi, _ = oracle.gemm(Ai, Bi)
     for tile, (bm, bn) in MAIN_SHAPES.items():
         say("f32 main kernel %dx%d storage %d%d %dx%dx%d" % (bm, bn, ta, tb, M, N, K))
-        fits = M >= bm and N >= bn
+        fits = M >= bm and N >= bn and K % (32 if tile == 5 else 4) == 0      # the 256 x 256 tile takes whole K-tiles only
         name = "gemm_f32_main_kernel<%d, %d, %d, %d>" % (bm // 64, bn // 64, ta, 1 - tb) if fits else None
         assert gpu.fsrgemm_kernel_for_f32_cfg(tile, ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name
         if not fits:
@@ -372,9 +375,10 @@ def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
 
 def test_f32_main_kernel_is_the_dispatchers_choice(gpu):
     # 16 x 16 tiles of 256 fill the compute units exactly once: the dispatcher takes the direct-to-LDS kernel, and
-    # forcing it gives the same bits; a K that is not whole tiles of 32 goes to the general kernel
+    # forcing it gives the same bits; a K that is not whole tiles of 32 takes another shape of it (the 256 x 256 one
+    # has no rest-of-K step), and a K below 32 the general kernel
     M = N = 4096
-    for K, kernel in ((64, "gemm_f32_main_kernel<4, 4, 0, 1>"), (48, "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")):
+    for K, kernel in ((64, "gemm_f32_main_kernel<4, 4, 0, 1>"), (48, "gemm_f32_main_kernel<2, 4, 0, 1>"), (16, "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")):
         say("f32 4096x4096x%d through the dispatcher" % K)
         assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == kernel
         A, B = inputs.uniform_pm1(19, 3, M, K), inputs.uniform_pm1(19, 4, K, N)
@@ -704,7 +708,7 @@ def test_f32_special_values(gpu, M, N, K):
             assert _same_class(got, ref)
             assert np.array_equal(got[fin].astype(np.float64), ref[fin])          # small integers: exact
     assert _same_class(run_f32(gpu, A, B), ref)
-    main_tiles = [t for t, (bm, bn) in MAIN_SHAPES.items() if M >= bm and N >= bn and K % 32 == 0]      # the direct-to-LDS shapes that fit
+    main_tiles = [t for t, (bm, bn) in MAIN_SHAPES.items() if M >= bm and N >= bn and K % (32 if t == 5 else 4) == 0 and K >= 32]      # the direct-to-LDS shapes that fit
     for tile in main_tiles:
         say("f32 specials %dx%dx%d tile %d" % (M, N, K, tile))
         got = run_cfg(gpu, "f32", tile, 1, 0, 0, A, B)
