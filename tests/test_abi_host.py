@@ -176,6 +176,18 @@ def test_f32_tile_rule_follows_the_round_model():
     assert lib.fsrgemm_plan_f32(0, 0, 262144, 2048, 4096, P, 4096, P, 2048)[0] == 5        # the paper's largest Task-2 size
 
 
+def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
+    # with a workspace: the slices from the shape, then 128 x 128 tiles if tiles x slices reaches 240 workgroups (fp32: and a
+    # slice keeps 1024 k), else 64 x 64 tiles.  fp32 tiles: 1 = 128 x 128, 2 = 64 x 64; bf16: 2 = 128 x 128, 3 = 64 x 64
+    pf = lambda M, N, K: lib.fsrgemm_plan_f32(0, 0, M, N, K, P, K, P, N, True, True)
+    pb = lambda M, N, K: lib.fsrgemm_plan_bf16(0, 1, M, N, K, P, K, P, K, True, True)
+    assert pf(512, 512, 65536) == (1, 16) and pf(384, 384, 65536) == (1, 28) and pf(1024, 1024, 4096) == (1, 4)
+    assert pf(768, 768, 4096) == (2, 4)             # 36 tiles x 4 slices: too few workgroups
+    assert pf(256, 256, 16384) == (2, 64)           # slices of 256 k: too short
+    assert pb(512, 512, 65536) == (2, 16) and pb(256, 256, 16384) == (2, 64) and pb(768, 768, 4096) == (3, 4)
+    assert lib.gemm_f32_workspace_bytes(0, 0, 512, 512, 65536) == 16 * 512 * 512 * 4
+
+
 def test_forced_configurations_and_plan_queries():
     bad, ok = lib.FSRGEMM_ERR_INVALID_ARG, lib.FSRGEMM_OK
     assert lib.fsrgemm_tile_count_f32() == 14 and lib.fsrgemm_tile_count_bf16() == 5
