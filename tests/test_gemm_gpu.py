@@ -165,6 +165,32 @@ def test_f32_workspace_split_k(gpu, shape):
     assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=0).view(np.uint32), plain.view(np.uint32))
 
 
+@pytest.mark.parametrize("shape", [(512, 512, 16384), (256, 1024, 16384), (384, 388, 28672)])
+def test_splits_on_the_larger_tile(gpu, shape):
+    # long-K splits that still fill the compute units with 128 x 128 tiles take those (fp32 candidate 1, bf16 candidate 2):
+    # sampled entries against the oracle, and the dispatcher's bits are the forced candidate's
+    M, N, K = shape
+    rng = np.random.default_rng(23)
+    ii, jj = rng.integers(0, M, 4096), rng.integers(0, N, 4096)
+    say("split on 128 x 128 tiles, fp32 %dx%dx%d" % shape)
+    tile, slices = gpu.fsrgemm_plan_f32(0, 0, M, N, K, 0x1000, K, 0x1000, N, True)
+    assert tile == 1 and slices > 1
+    A, B = inputs.uniform_pm1(23, 1, M, K), inputs.uniform_pm1(23, 2, K, N)
+    got = run_f32_ws(gpu, 0, 0, A, B, repeat=2)
+    ref, S = oracle.gemm_entries(A, B, ii, jj)
+    assert np.all(np.isfinite(got)) and oracle.componentwise_error(got[ii, jj], ref, S) <= TOL_F32
+    assert np.array_equal(run_cfg(gpu, "f32", tile, slices, 0, 0, A, B).view(np.uint32), got.view(np.uint32))
+    say("split on 128 x 128 tiles, bf16 %dx%dx%d" % shape)
+    tile, slices = gpu.fsrgemm_plan_bf16(0, 1, M, N, K, 0x1000, K, 0x1000, K, True)
+    assert tile == 2 and slices > 1
+    Ah = inputs.bf16_normal_scaled(23, 3, M, K, 1 / math.sqrt(K))
+    Bh = np.ascontiguousarray(inputs.bf16_normal_scaled(23, 4, N, K, 1 / math.sqrt(K)).T)
+    got = run_bf16_ws(gpu, 0, 1, Ah, Bh, repeat=2)
+    ref, S = oracle.gemm_entries(Ah, Bh, ii, jj)
+    assert np.all(np.isfinite(got)) and oracle.componentwise_error(got[ii, jj], ref, S) <= TOL_BF16
+    assert np.array_equal(run_cfg(gpu, "bf16", tile, slices, 0, 1, Ah, Bh).view(np.uint32), got.view(np.uint32))
+
+
 def test_f32_workspace_integers_bit_exact_and_large_problem_unsplit(gpu):
     A, B = inputs.small_ints(0, 5, 48, 4000), inputs.small_ints(0, 6, 4000, 200)
     assert gpu.gemm_f32_workspace_bytes(0, 0, 48, 200, 4000) > 0
