@@ -18,7 +18,7 @@ HIPCC_FLAGS = (
 # Sources whose kernels issue loads or MFMAs from inline assembly.  The compiler cannot place hazard wait
 # states around those, which is safe only while it reloads no spilled register next to them: such kernels
 # must compile without spills (checked below from the compiler's own resource-usage remarks).
-NO_SPILL_SOURCES = ("gemm_bf16_main.hip", "gemm_f32_main.hip")
+NO_SPILL_SOURCES = ("gemm_bf16_main.hip", "gemm_f32_main.hip", "gemm_bf16.hip")
 # Every other kernel must at least stay out of scratch memory: a loop the compiler failed to unroll puts a
 # kernel's register arrays there, which is correct but many times slower.
 KERNEL_SOURCES = ("gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_main.hip", "transpose.hip", "gemv_f32.hip", "gemm_f32_skinny.hip", "gemv_bf16.hip", "gemm_f32_main.hip")

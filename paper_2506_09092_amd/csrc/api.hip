@@ -209,13 +209,15 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
 {
     const Tuned *t = use_table ? find_tuned(0, transA, transB, M, N, K, split) : nullptr;
     const bool vector = vector_shape(M, N, K);
-    int64_t lda_t = 0, ldb_t = 0;
-    if (!t && split && skinny_fits(M, N) && K >= 4096 && tall_storage(transA, transB, M, N, lda, ldb, &lda_t, &ldb_t) &&
-        2048 * lda_t < (1 << 29) && 2048 * ldb_t < (1 << 29)) {
+    SkinnyArgs sk;
+    sk.K = (int)K;
+    sk.parts = (int)(K / 256 < kSkinnyMaxParts ? K / 256 : kSkinnyMaxParts);
+    if (!t && split && skinny_fits(M, N) && K >= 4096 && tall_storage(transA, transB, M, N, lda, ldb, &sk.lda, &sk.ldb) &&
+        skinny_offsets_fit(sk)) {
         // a small result of long sums: one workgroup per 256 k (a row per lane) up to one per compute unit, each
-        // with a partial result in the workspace
+        // with a partial result in the workspace; the pieces' lane offsets must fit, as the launcher checks them
         p->cfg = kF32_Skinny;
-        p->slices = (int)(K / 256 < kSkinnyMaxParts ? K / 256 : kSkinnyMaxParts);
+        p->slices = sk.parts;
     } else if (!t && vector) {
         const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
         p->cfg = kF32_Vector;
@@ -631,9 +633,12 @@ const char *fsrgemm_kernel_for_f32_cfg(int tile, int transA, int transB, int64_t
 {
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
     if (tile == kF32_Skinny) {
-        int64_t lda_t, ldb_t;
-        if (K < 1 || !tall_storage(transA, transB, M, N, lda, ldb, &lda_t, &ldb_t)) return nullptr;
-        return skinny_kernel_name((int)(M < 17 ? M : 17), (int)(N < 17 ? N : 17), A, lda_t, B, ldb_t);
+        // no kernel where no piece count gemm_f32_cfg accepts keeps the lane offsets of a piece in range
+        SkinnyArgs sk;
+        if (K < 1 || !tall_storage(transA, transB, M, N, lda, ldb, &sk.lda, &sk.ldb)) return nullptr;
+        sk.K = (int)K, sk.parts = (int)(K < kSkinnyMaxParts ? K : kSkinnyMaxParts);
+        if (!skinny_offsets_fit(sk)) return nullptr;
+        return skinny_kernel_name((int)(M < 17 ? M : 17), (int)(N < 17 ? N : 17), A, sk.lda, B, sk.ldb);
     }
     if (tile >= kF32_Main && tile < kF32_Main + kF32MainShapes) {
         const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;

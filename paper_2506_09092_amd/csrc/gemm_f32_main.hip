@@ -361,13 +361,15 @@ const char *f32_main_kernel_name(int shape, int a_lay, int b_lay)
 // Whole unchecked tiles of 16-byte pieces: a matrix at least one tile high and wide (a ragged last tile is shifted
 // back into it), at least one K-tile of 32 and K a multiple of 4 (of 32 for the 256 x 256 tile), 16-byte aligned bases and rows,
 // for an operand that is contiguous along
-// m (n) M (N) a multiple of 4 so that a shifted tile still starts on a piece.
+// m (n) M (N) a multiple of 4 so that a shifted tile still starts on a piece; leading dimensions below 2^24 elements,
+// because a lane's offset from its load's uniform base (up to 7 rows and 28 elements along k, up to 2 k-rows along
+// m / n) is a 32-bit number of bytes.
 bool f32_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb)
 {
     if (shape < 0 || shape >= kF32MainShapes) return false;
     const int bm = kShapeM[shape], bn = kShapeN[shape];
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) == 0 && lda % 4 == 0 && ldb % 4 == 0;
-    return aligned && M >= bm && N >= bn && K >= kBK && K % (bm * bn == 256 * 256 ? kBK : 4) == 0 && (a_lay == kKContig || M % 4 == 0) &&
+    return aligned && lda < kF32MaxLdUnchecked && ldb < kF32MaxLdUnchecked && M >= bm && N >= bn && K >= kBK && K % (bm * bn == 256 * 256 ? kBK : 4) == 0 && (a_lay == kKContig || M % 4 == 0) &&
            (b_lay == kKContig || N % 4 == 0) && ((M + bm - 1) / bm) * ((N + bn - 1) / bn) < ((int64_t)1 << 31);
 }
 

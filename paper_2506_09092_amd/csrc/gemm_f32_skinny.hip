@@ -25,10 +25,11 @@ namespace {
 
 constexpr int kThreads = 256;
 
-bool skinny_reads_pairs(const SkinnyArgs &a) { return (reinterpret_cast<uintptr_t>(a.A) & 7u) == 0 && a.lda % 2 == 0; }
+// (an even M only: the pair that holds the last element of an odd M would reach one element into the row's padding)
+bool skinny_reads_pairs(const SkinnyArgs &a) { return (reinterpret_cast<uintptr_t>(a.A) & 7u) == 0 && a.lda % 2 == 0 && a.M % 2 == 0; }
 bool skinny_is_gram(const SkinnyArgs &a) { return a.A == a.B && a.M == a.N && a.lda == a.ldb; }
 
-// APAIR: A's rows start 8-byte aligned (base and leading dimension even), so a row is read as pairs.
+// APAIR: A's rows start 8-byte aligned (base and leading dimension even) and M is even, so a row is read as pairs.
 // GRAM: X^T X -- A and B are the same matrix, so one set of loads serves both, and the result is symmetric, so only
 // j >= i is summed and the rest copied over at the end (the same products in the same order: the copy has the
 // bits the sum would have had).
@@ -60,11 +61,10 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_skinny_kernel(SkinnyArgs g)
         const float *__restrict__ ar = A + (uint32_t)kk * lda;
         const float *__restrict__ br = B + (uint32_t)kk * ldb;
         if constexpr (APAIR) {
-            // an odd M reads one element of the row's padding (the leading dimension is even, so it is there)
             typedef float f32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
             for (int i = 0; i < MB; i += 2) {
-                const f32x2 v = *reinterpret_cast<const f32x2 *>(ar + min(i, (g.M - 1) & ~1));
+                const f32x2 v = *reinterpret_cast<const f32x2 *>(ar + min(i, g.M - 2));
                 a[i] = i < g.M ? v[0] : 0.f;
                 a[i + 1] = i + 1 < g.M ? v[1] : 0.f;
             }

@@ -398,3 +398,41 @@ def test_build_refuses_spills_in_hand_scheduled_kernels():
     with pytest.raises(RuntimeError):
         build.check_no_spills("x.hip", ok.replace("ScratchSize [bytes/lane]: 0", "ScratchSize [bytes/lane]: 64"), scratch_only=True)
     assert "gemm_bf16_main.hip" in build.NO_SPILL_SOURCES
+
+
+def test_f32_direct_to_lds_kernel_is_not_planned_beyond_its_32_bit_lane_offsets():
+    # the kernel adds a 32-bit byte offset per lane (up to 7 rows and 28 elements along k, up to 2 k-rows along m / n)
+    # to a uniform base: leading dimensions of 2^24 elements and more take the general tiles in their checked mode
+    q, qx = lib.fsrgemm_kernel_for_f32, lib.fsrgemm_kernel_for_f32_ex
+    n, big = 4096, 1 << 24
+    assert q(n, n, n, P, big - 4, P, n, P, n) == "gemm_f32_main_kernel<4, 4, 0, 1>"
+    for lda, ldb in ((big, n), (n, big), (160000000, n), (1 << 30, n), (n, 1 << 30)):
+        name = q(n, n, n, P, lda, P, ldb, P, n)
+        assert name.startswith("gemm_f32_kernel<") and name.split(", ")[3] == "1", (lda, ldb, name)      # load mode 1: checked
+    assert qx(1, 0, n, n, n, P, big, P, n, P, n).startswith("gemm_f32_kernel<")
+    assert qx(1, 1, n, n, n, P, n, P, big, P, n).startswith("gemm_f32_kernel<")
+    # forced: rejected, not replaced
+    for tile in range(5, 14):       # (rejected before any launch: the addresses are fake)
+        assert lib.gemm_f32_cfg(tile, 1, 0, 0, n, n, n, P, big, P, n, P, n, None, 0, 0) == lib.FSRGEMM_ERR_INVALID_ARG
+        assert lib.fsrgemm_kernel_for_f32_cfg(tile, 0, 0, n, n, n, P, n, P, big, P, n) is None
+    assert lib.fsrgemm_plan_f32(0, 0, n, n, n, P, big, P, n)[0] < 3
+
+
+def test_small_result_kernel_is_planned_only_where_its_launcher_accepts_the_pieces():
+    # normal equations with a widely padded X: 2^22 rows in 256 pieces are 16384 rows a piece, and 16384 * 40000
+    # elements do not fit the kernel's 32-bit lane offsets -- the plan must fall back to the split tile kernels, and
+    # whatever it names must be what the forced entry point accepts for the same arguments
+    bad = lib.FSRGEMM_ERR_INVALID_ARG
+    K = 1 << 22
+    assert lib.fsrgemm_plan_f32(1, 0, 10, 10, K, P, 10, P, 10, True) == (4, 256)
+    for lda in (10, 1024, 32766, 32768, 40000, 1 << 20):
+        tile, slices = lib.fsrgemm_plan_f32(1, 0, 10, 10, K, P, lda, P, 10, True)
+        fits = (K // 256) * lda < 1 << 29
+        assert (tile == 4) == fits, (lda, tile, slices)
+        assert (lib.fsrgemm_kernel_for_f32_cfg(4, 1, 0, 10, 10, K, P, lda, P, 10, P, 10) is None) == (not fits)
+        if not fits:        # (only rejected calls are made here: the addresses are fake)
+            assert lib.gemm_f32_cfg(4, 256, 1, 0, 10, 10, K, P, lda, P, 10, P, 10, P, 256 * 100 * 4, 0) == bad
+            assert tile == 2 and slices > 1
+    # the same on B's side, and for a dot product of two strided vectors
+    assert lib.fsrgemm_plan_f32(1, 0, 10, 10, K, P, 10, P, 40000, True)[0] == 2
+    assert lib.fsrgemm_plan_f32(1, 1, 1, 1, K, P, 1, P, K, True) == (4, 256)

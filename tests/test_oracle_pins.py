@@ -257,6 +257,78 @@ def test_error_metric_and_freivalds_detect_planted_mistakes():
     assert oracle.componentwise_error(np.zeros((0, 3)), np.zeros((0, 3)), np.zeros((0, 3))) == 0.0
 
 
+def test_bf16_widening_matches_the_format():
+    # bfloat16 is the upper half of an IEEE binary32: 1 sign, 8 exponent, 7 fraction bits.  Known patterns, worked by
+    # hand from the format, then every one of the 65536 patterns against a decoder written out from that definition.
+    known = {0x3F80: 1.0, 0xC000: -2.0, 0x4040: 3.0, 0x3F00: 0.5, 0x0001: 2.0 ** -133, 0x0080: 2.0 ** -126, 0x7F7F: (2 - 2.0 ** -7) * 2.0 ** 127,
+             0x3FC0: 1.5, 0xBF81: -(1 + 2.0 ** -7), 0x0000: 0.0, 0x4049: 3.140625}
+    bits = np.array(sorted(known), dtype=np.uint16)
+    assert list(oracle.bf16_bits_to_f64(bits)) == [known[int(b)] for b in bits]
+    assert oracle.bf16_bits_to_f64(np.array([0x8000], dtype=np.uint16))[0] == 0.0 and np.signbit(oracle.bf16_bits_to_f64(np.array([0x8000], dtype=np.uint16))[0])
+    assert oracle.bf16_bits_to_f64(np.array([0x7F80], dtype=np.uint16))[0] == np.inf and np.isnan(oracle.bf16_bits_to_f64(np.array([0x7FC1], dtype=np.uint16))[0])
+
+    def decode(b):
+        sign, e, f = -1.0 if b >> 15 else 1.0, (b >> 7) & 0xFF, b & 0x7F
+        if e == 0xFF:
+            return sign * np.inf if f == 0 else np.nan
+        return sign * (f * 2.0 ** -7 * 2.0 ** -126 if e == 0 else (1 + f * 2.0 ** -7) * 2.0 ** (e - 127))
+
+    every = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    want = np.array([decode(int(b)) for b in every])
+    with np.errstate(invalid="ignore"):         # signalling NaN patterns are among the 65536
+        got = oracle.bf16_bits_to_f64(every)
+    assert np.array_equal(np.isnan(got), np.isnan(want)) and np.array_equal(got[~np.isnan(got)], want[~np.isnan(want)])
+    assert np.array_equal(np.signbit(got[~np.isnan(got)]), np.signbit(want[~np.isnan(want)]))
+    # a matrix keeps its shape, and the widening agrees with the C routine's (a 1 x 1 product with 1.0)
+    m = every[:4096].reshape(64, 64)
+    assert oracle.bf16_bits_to_f64(m).shape == (64, 64)
+    one = np.array([[0x3F80]], dtype=np.uint16)
+    finite = every[(every & 0x7F80) != 0x7F80][::97]
+    via_c = np.array([oracle.gemm(np.array([[b]], dtype=np.uint16), one)[0][0, 0] for b in finite])
+    assert np.array_equal(via_c, oracle.bf16_bits_to_f64(finite))
+
+
+def test_freivalds_on_bf16_bit_patterns_detects_planted_mistakes():
+    # the residual check is what covers all entries of the bf16 8192^3 product, so its bf16 branch is pinned on its
+    # own: operands are uint16 bit patterns, B is handed over as the K x N view of a column-major (N x K) array
+    import math
+
+    M, N, K = 48, 80, 96
+    A = inputs.bf16_normal_scaled(16, 1, M, K, 1 / math.sqrt(K))
+    Bt = inputs.bf16_normal_scaled(16, 2, N, K, 1 / math.sqrt(K))
+    C, S = oracle.gemm(A, Bt.T)
+    good = C.astype(np.float32)
+    # exact arithmetic on the widened values (Python integers scaled by 2^-300 would do as well; fractions are plainer)
+    from fractions import Fraction
+    x = np.ones(N)
+    Af, Bf = oracle.bf16_bits_to_f64(A), oracle.bf16_bits_to_f64(Bt.T)
+    row0 = sum(Fraction(float(Af[0, k])) * sum(Fraction(float(Bf[k, j])) for j in range(N)) for k in range(K))
+    assert abs(float(row0) - float(C[0] @ x)) <= 1e-12
+    base = oracle.freivalds_residual(A, Bt.T, good)
+    assert base <= 2.0 ** -24                    # fp32 rounding of each entry, averaged down by the random signs
+    assert oracle.freivalds_residual(A, Bt.T, C) <= 1e-14
+    # a dropped k term; B taken row-major instead of column-major (same bytes); one corrupted entry; a wrong 16 x 16
+    # block; operands widened as if they were integers; a NaN
+    drop, _ = oracle.gemm(A[:, :-1], Bt.T[:-1])
+    assert oracle.freivalds_residual(A, Bt.T, drop) > 1e-4
+    sq = inputs.bf16_normal_scaled(16, 3, K, K, 1 / math.sqrt(K))
+    Ct, _ = oracle.gemm(A, sq)
+    assert oracle.freivalds_residual(A, sq.T, Ct) > 1e-3
+    bad = good.copy()
+    bad[17, 23] += np.float32(1e-2) * np.float32(S[17, 23])
+    assert oracle.freivalds_residual(A, Bt.T, bad) > 1e-2 / N / 2
+    blk = good.copy()
+    blk[16:32, 32:48] = 0.0
+    assert oracle.freivalds_residual(A, Bt.T, blk) > 1e-3
+    as_ints = A.astype(np.float32) @ Bt.T.astype(np.float32)
+    assert oracle.freivalds_residual(A, Bt.T, as_ints) > 1.0
+    bad[3, 3] = np.nan
+    assert oracle.freivalds_residual(A, Bt.T, bad) == float("inf")
+    # the fp32 branch on the same values (bf16 widened to fp32 exactly) gives the same number: same vectors, same sums
+    A32, B32 = Af.astype(np.float32), Bf.astype(np.float32)
+    assert oracle.freivalds_residual(A32, B32, good) == base
+
+
 # ---- transposition (Task 8) ----
 
 def _golden_transposes():
