@@ -271,6 +271,27 @@ const char *fsrgemm_kernel_for_transpose_f32(int64_t rows, int64_t cols,
                                              const float *T, int64_t ldt);
 
 /* Human-readable text for a status code; static storage, never NULL. */
+/*
+ * Measurement aid for the Performance Profiler leg (Section 3.2: candidates are ranked by measured execution time;
+ * this gives the time a scale): a loop of nothing but the matrix-core instruction of the product kernels, one
+ * wavefront per SIMD with all 256 accumulator registers in use, operands held in registers.  What it sustains is
+ * the ceiling of the contraction step on this part for operands of this kind; it depends on the operand VALUES
+ * (the clock follows the power drawn), which is why the caller supplies them.
+ *   kind        0: V_MFMA_F32_32X32X2_F32 (the fp32 kernels), 1: V_MFMA_F32_16X16X32_BF16 (the bf16 kernels)
+ *   passes      1 .. 2^24 loop iterations of 64 MFMAs per wavefront
+ *   operands    device pointer, 16-byte aligned, to 8 KB (kind 0: 2048 floats) or 16 KB (kind 1: 8192 bf16 bit
+ *               patterns); read once per lane, any finite values
+ *   sink        device pointer to workgroups * 256 floats, overwritten with sums nobody needs
+ *   workgroups  1 .. 65536 workgroups of 256 lanes; one per compute unit (256 on MI355X) loads the whole chip once
+ *   flop        if not NULL, receives the floating-point operations of the launch:
+ *               workgroups * 4 * passes * 64 * (4096 for kind 0, 16384 for kind 1)
+ * Errors: FSRGEMM_ERR_INVALID_ARG for anything outside these ranges or a NULL / misaligned pointer, before any HIP call.
+ */
+int fsrgemm_mfma_ceiling(int kind, int passes, const void *operands, float *sink, int workgroups, double *flop,
+                         void *stream);
+/* Name of that kernel as a profiler trace prints it; NULL for an unknown kind. */
+const char *fsrgemm_kernel_for_mfma_ceiling(int kind);
+
 const char *fsrgemm_status_string(int status);
 
 /* Library version as major*10000 + minor*100 + patch. */

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libfsrgemm.so")
-SOURCES = ("api.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_main.hip", "transpose.hip", "gemv_f32.hip", "gemm_f32_skinny.hip", "gemv_bf16.hip", "gemm_f32_main.hip")
+SOURCES = ("api.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_main.hip", "transpose.hip", "gemv_f32.hip", "gemm_f32_skinny.hip", "gemv_bf16.hip", "gemm_f32_main.hip", "mfma_ceiling.hip")
 HIPCC_FLAGS = (
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-fp32 code generation is switched off for every device compile
@@ -18,10 +18,10 @@ HIPCC_FLAGS = (
 # Sources whose kernels issue loads or MFMAs from inline assembly.  The compiler cannot place hazard wait
 # states around those, which is safe only while it reloads no spilled register next to them: such kernels
 # must compile without spills (checked below from the compiler's own resource-usage remarks).
-NO_SPILL_SOURCES = ("gemm_bf16_main.hip", "gemm_f32_main.hip", "gemm_bf16.hip")
+NO_SPILL_SOURCES = ("gemm_bf16_main.hip", "gemm_f32_main.hip", "gemm_bf16.hip", "mfma_ceiling.hip")
 # Every other kernel must at least stay out of scratch memory: a loop the compiler failed to unroll puts a
 # kernel's register arrays there, which is correct but many times slower.
-KERNEL_SOURCES = ("gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_main.hip", "transpose.hip", "gemv_f32.hip", "gemm_f32_skinny.hip", "gemv_bf16.hip", "gemm_f32_main.hip")
+KERNEL_SOURCES = ("gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_main.hip", "transpose.hip", "gemv_f32.hip", "gemm_f32_skinny.hip", "gemv_bf16.hip", "gemm_f32_main.hip", "mfma_ceiling.hip")
 
 
 def check_no_spills(src: str, remarks: str, scratch_only: bool = False) -> str:

@@ -696,6 +696,18 @@ int transpose_f32(int64_t rows, int64_t cols, const float *A, int64_t lda, float
     return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
 }
 
+int fsrgemm_mfma_ceiling(int kind, int passes, const void *operands, float *sink, int workgroups, double *flop, void *stream)
+{
+    if (kind < 0 || kind > 1 || passes < 1 || passes > (1 << 24) || workgroups < 1 || workgroups > (1 << 16)) return FSRGEMM_ERR_INVALID_ARG;
+    if (operands == nullptr || sink == nullptr || !aligned16(operands)) return FSRGEMM_ERR_INVALID_ARG;
+    if (flop != nullptr) *flop = mfma_ceiling_flop(kind, passes, workgroups);
+    const int rc = device_ok();
+    if (rc != FSRGEMM_OK) return rc;
+    return launch_mfma_ceiling(kind, passes, operands, sink, workgroups, static_cast<hipStream_t>(stream)) == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
+}
+
+const char *fsrgemm_kernel_for_mfma_ceiling(int kind) { return kind == 0 || kind == 1 ? mfma_ceiling_kernel_name(kind) : nullptr; }
+
 const char *fsrgemm_status_string(int status)
 {
     switch (status) {
@@ -707,6 +719,6 @@ const char *fsrgemm_status_string(int status)
     }
 }
 
-int fsrgemm_version(void) { return 100; }
+int fsrgemm_version(void) { return 200; }
 
 }  // extern "C"

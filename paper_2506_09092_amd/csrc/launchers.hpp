@@ -100,6 +100,11 @@ bool f32_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_
 const char *f32_main_kernel_name(int shape, int a_lay, int b_lay);
 hipError_t launch_f32_main(int shape, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 
+// register-only MFMA loops (mfma_ceiling.hip): kind 0 = the fp32 kernels' instruction, 1 = the bf16 kernels'
+const char *mfma_ceiling_kernel_name(int kind);
+double mfma_ceiling_flop(int kind, int passes, int workgroups);
+hipError_t launch_mfma_ceiling(int kind, int passes, const void *operands, float *sink, int workgroups, hipStream_t s);
+
 // fp32 transposition (transpose.hip)
 const char *transpose_kernel_name(int rows, int cols);
 hipError_t launch_transpose_f32(const float *A, int64_t lda, float *T, int64_t ldt, int rows, int cols, hipStream_t s);

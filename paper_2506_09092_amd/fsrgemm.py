@@ -16,7 +16,7 @@ __all__ = [
     "gemm_f32_ws", "gemm_f32_workspace_bytes", "gemm_bf16_ws", "gemm_bf16_workspace_bytes", "transpose_f32",
     "fsrgemm_kernel_for_transpose_f32", "gemm_f32_cfg", "gemm_bf16_cfg", "fsrgemm_tile_count_f32",
     "fsrgemm_tile_count_bf16", "fsrgemm_plan_f32", "fsrgemm_plan_bf16", "fsrgemm_kernel_for_f32_cfg",
-    "fsrgemm_kernel_for_bf16_cfg",
+    "fsrgemm_kernel_for_bf16_cfg", "fsrgemm_mfma_ceiling", "fsrgemm_kernel_for_mfma_ceiling",
     "fsrgemm_status_string", "fsrgemm_version", "check", "FsrGemmError", "EXPORTS",
     "FSRGEMM_PLAN_WORKSPACE", "FSRGEMM_PLAN_RULES_ONLY", "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
 ]
@@ -57,6 +57,8 @@ EXPORTS = {
                                         ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
     "fsrgemm_plan_bf16": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, ctypes.c_int,
                                          ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
+    "fsrgemm_mfma_ceiling": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, _vp, _vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), _vp]),
+    "fsrgemm_kernel_for_mfma_ceiling": (ctypes.c_char_p, [ctypes.c_int]),
     "fsrgemm_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "fsrgemm_version": (ctypes.c_int, []),
 }
@@ -208,6 +210,19 @@ def transpose_f32(rows, cols, A, lda, T, ldt, stream=0) -> int:
 
 def fsrgemm_kernel_for_transpose_f32(rows, cols, A, lda, T, ldt):
     r = load().fsrgemm_kernel_for_transpose_f32(rows, cols, _ptr(A), lda, _ptr(T), ldt)
+    return None if r is None else r.decode()
+
+
+def fsrgemm_mfma_ceiling(kind, passes, operands, sink, workgroups, stream=0):
+    """(status, flop of the launch)."""
+    flop = ctypes.c_double(0.0)
+    rc = load().fsrgemm_mfma_ceiling(int(kind), int(passes), _ptr(operands), _ptr(sink), int(workgroups), ctypes.byref(flop),
+                                     _ptr(stream) or None)
+    return rc, flop.value
+
+
+def fsrgemm_kernel_for_mfma_ceiling(kind):
+    r = load().fsrgemm_kernel_for_mfma_ceiling(int(kind))
     return None if r is None else r.decode()
 
 

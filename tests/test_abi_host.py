@@ -225,6 +225,9 @@ def test_forced_configurations_and_plan_queries():
     assert qc(4, 1, 0, 16, 8, 64, P, 16, P, 8, P, 8) == "gemm_f32_skinny_kernel<16, 8, true, false>" and qc(4, 1, 0, 16, 9, 64, P, 16, P, 9, P, 9) is None
     assert qc(4, 1, 0, 10, 10, 1 << 20, P, 10, P + 64, 10, P, 10) == "gemm_f32_skinny_kernel<12, 12, true, false>"      # two different matrices
     assert qc(4, 1, 0, 9, 8, 64, P, 9, P, 8, P, 8) == "gemm_f32_skinny_kernel<12, 8, false, false>"            # odd leading dimension
+    # an odd M is read element by element even where rows start 8-byte aligned: its last pair would reach into the padding
+    assert qc(4, 1, 0, 9, 8, 64, P, 10, P, 8, P, 8) == "gemm_f32_skinny_kernel<12, 8, false, false>"
+    assert qc(4, 1, 0, 10, 8, 64, P, 10, P, 8, P, 8) == "gemm_f32_skinny_kernel<12, 8, true, false>"
     assert qc(4, 0, 0, 1, 8, 64, P, 64, P, 8, P, 8) == "gemm_f32_skinny_kernel<4, 8, false, false>"    # a row vector is tall with leading dimension 1
     assert qc(4, 0, 0, 16, 8, 64, P, 64, P, 8, P, 8) is None                    # only for operands stored with k as the row index
     assert lib.gemm_f32_cfg(4, 4, 0, 0, 10, 10, 4096, P, 4096, P, 10, P, 10, P, 1 << 20, 0) == bad
@@ -436,3 +439,13 @@ def test_small_result_kernel_is_planned_only_where_its_launcher_accepts_the_piec
     # the same on B's side, and for a dot product of two strided vectors
     assert lib.fsrgemm_plan_f32(1, 0, 10, 10, K, P, 10, P, 40000, True)[0] == 2
     assert lib.fsrgemm_plan_f32(1, 1, 1, 1, K, P, 1, P, K, True) == (4, 256)
+
+
+def test_mfma_ceiling_arguments():
+    # the register-only MFMA loop of the profiler leg: argument errors come before any HIP call
+    bad = lib.FSRGEMM_ERR_INVALID_ARG
+    f = lambda kind=1, passes=10, ops=P, sink=P, groups=256: lib.fsrgemm_mfma_ceiling(kind, passes, ops, sink, groups)[0]
+    assert f(kind=2) == bad and f(kind=-1) == bad and f(passes=0) == bad and f(passes=(1 << 24) + 1) == bad
+    assert f(groups=0) == bad and f(groups=(1 << 16) + 1) == bad and f(ops=None) == bad and f(sink=None) == bad and f(ops=P + 4) == bad
+    assert lib.fsrgemm_kernel_for_mfma_ceiling(0) == "mfma_ceiling_kernel<0>" and lib.fsrgemm_kernel_for_mfma_ceiling(1) == "mfma_ceiling_kernel<1>"
+    assert lib.fsrgemm_kernel_for_mfma_ceiling(2) is None
