@@ -50,7 +50,10 @@ typedef enum {
      * "output mismatch", Appendix B) */
     FSRGEMM_ERR_LAUNCH = -2,
     /* current device is not gfx950 */
-    FSRGEMM_ERR_UNSUPPORTED_DEVICE = -3
+    FSRGEMM_ERR_UNSUPPORTED_DEVICE = -3,
+    /* gemm_f32_noalloc only: the K split planned for the problem needs more
+     * scratch memory than the library's fixed buffer holds */
+    FSRGEMM_ERR_SCRATCH_LIMIT = -4
 } fsrgemm_status;
 
 /*
@@ -107,6 +110,30 @@ int gemm_f32_ws(int transA, int transB,
                 float *C, int64_t ldc,
                 void *workspace, int64_t workspace_bytes,
                 void *stream);
+
+/*
+ * gemm_f32_ws for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Arguments and result are gemm_f32_ws's with a workspace of the size
+ * gemm_f32_workspace_bytes names (bit for bit the same C), but the workspace is a fixed array of
+ * FSRGEMM_NOALLOC_SCRATCH_BYTES inside the library's device image: each GPU the library runs on holds its own
+ * copy until the process ends.  The call allocates and frees nothing (no hipMalloc, hipFree or allocating library
+ * routine); the array's address is looked up on the first call on each device.
+ *   - The array is as large as the largest workspace gemm_f32_workspace_bytes ever names (16 MiB), so every problem
+ *     gemm_f32_ws can split is split here in the same way.  Should a plan ever need more than the array holds, the
+ *     call returns FSRGEMM_ERR_SCRATCH_LIMIT before anything is launched (gemm_f32_ex computes any problem unsplit).
+ *     Problems that are not split (gemm_f32_workspace_bytes == 0) never touch the array.
+ *   - Every call on one GPU shares that GPU's array, whatever its stream or host thread.  Nothing in it has to start
+ *     at zero (every partial product is written before it is read), so calls need no clearing between them, but
+ *     calls that overlap in time on one GPU race on it: order them (one stream, or events) as calls that share a
+ *     workspace must be ordered.
+ */
+#define FSRGEMM_NOALLOC_SCRATCH_BYTES 16777216 /* 16 MiB */
+int gemm_f32_noalloc(int transA, int transB,
+                     int64_t M, int64_t N, int64_t K,
+                     const float *A, int64_t lda,
+                     const float *B, int64_t ldb,
+                     float *C, int64_t ldc,
+                     void *stream);
 
 /*
  * bf16 inputs, fp32 accumulation and fp32 output.

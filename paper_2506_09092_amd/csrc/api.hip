@@ -403,6 +403,29 @@ int run_bf16(const Plan &p, int a_lay, int b_lay, int64_t M, int64_t N, int64_t 
     return e == hipSuccess ? FSRGEMM_OK : FSRGEMM_ERR_LAUNCH;
 }
 
+// Scratch memory of gemm_f32_noalloc: one array per device that holds the library, there until the process ends.
+// In host code the array's name is not a device address: the address is looked up once per device, with that device
+// current, and only that pointer is handed to kernels.
+constexpr int64_t kStaticScratchBytes = FSRGEMM_NOALLOC_SCRATCH_BYTES;
+static_assert(kStaticScratchBytes >= kMaxWorkspace, "every split the planner makes fits the array");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int static_scratch(float **out)
+{
+    constexpr int kMaxDev = 64;
+    static std::atomic<void *> known[kMaxDev];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return FSRGEMM_ERR_UNSUPPORTED_DEVICE;
+    const bool cached = dev >= 0 && dev < kMaxDev;
+    void *ptr = cached ? known[dev].load(std::memory_order_acquire) : nullptr;
+    if (ptr == nullptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return FSRGEMM_ERR_LAUNCH;
+        if (cached) known[dev].store(ptr, std::memory_order_release);
+    }
+    *out = static_cast<float *>(ptr);
+    return FSRGEMM_OK;
+}
+
 bool extents_ok(int64_t M, int64_t N, int64_t K)
 {
     const int64_t lim = (int64_t)1 << 31;
@@ -441,6 +464,25 @@ int gemm_f32_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const f
                 int64_t ldb, float *C, int64_t ldc, void *stream)
 {
     return gemm_f32_ws(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, nullptr, 0, stream);
+}
+
+int gemm_f32_noalloc(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                     int64_t ldb, float *C, int64_t ldc, void *stream)
+{
+    int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
+    if (rc != FSRGEMM_OK) return rc;
+    Plan p;
+    rc = plan_f32(transA, transB, M, N, K, A, lda, B, ldb, true, &p);
+    if (rc != FSRGEMM_OK) return rc;
+    const bool needs = p.slices > 1 || p.cfg == kF32_Skinny;
+    if (needs && (int64_t)p.slices * M * N * 4 > kStaticScratchBytes) return FSRGEMM_ERR_SCRATCH_LIMIT;
+    if (M == 0 || N == 0) return FSRGEMM_OK;
+    float *ws = nullptr;
+    if (needs) {
+        rc = static_scratch(&ws);
+        if (rc != FSRGEMM_OK) return rc;
+    }
+    return run_f32(p, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, ws, static_cast<hipStream_t>(stream));
 }
 
 int64_t gemm_f32_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K)
@@ -715,6 +757,7 @@ const char *fsrgemm_status_string(int status)
     case FSRGEMM_ERR_INVALID_ARG: return "invalid argument";
     case FSRGEMM_ERR_LAUNCH: return "kernel launch failed";
     case FSRGEMM_ERR_UNSUPPORTED_DEVICE: return "current device is not gfx950";
+    case FSRGEMM_ERR_SCRATCH_LIMIT: return "the problem's K split needs more scratch memory than the library's fixed buffer holds";
     default: return "unknown status";
     }
 }

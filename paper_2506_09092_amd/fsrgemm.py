@@ -13,18 +13,21 @@ import os
 __all__ = [
     "load", "library_path", "gemm_f32", "gemm_f32_ex", "gemm_bf16", "fsrgemm_kernel_for_f32",
     "fsrgemm_kernel_for_f32_ex", "fsrgemm_kernel_for_bf16", "gemm_bf16_ex", "fsrgemm_kernel_for_bf16_ex",
-    "gemm_f32_ws", "gemm_f32_workspace_bytes", "gemm_bf16_ws", "gemm_bf16_workspace_bytes", "transpose_f32",
+    "gemm_f32_ws", "gemm_f32_noalloc", "gemm_f32_workspace_bytes", "gemm_bf16_ws", "gemm_bf16_workspace_bytes", "transpose_f32",
     "fsrgemm_kernel_for_transpose_f32", "gemm_f32_cfg", "gemm_bf16_cfg", "fsrgemm_tile_count_f32",
     "fsrgemm_tile_count_bf16", "fsrgemm_plan_f32", "fsrgemm_plan_bf16", "fsrgemm_kernel_for_f32_cfg",
     "fsrgemm_kernel_for_bf16_cfg", "fsrgemm_mfma_ceiling", "fsrgemm_kernel_for_mfma_ceiling",
     "fsrgemm_status_string", "fsrgemm_version", "check", "FsrGemmError", "EXPORTS",
     "FSRGEMM_PLAN_WORKSPACE", "FSRGEMM_PLAN_RULES_ONLY", "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
+    "FSRGEMM_ERR_SCRATCH_LIMIT", "FSRGEMM_NOALLOC_SCRATCH_BYTES",
 ]
 
 FSRGEMM_OK = 0
 FSRGEMM_ERR_INVALID_ARG = -1
 FSRGEMM_ERR_LAUNCH = -2
 FSRGEMM_ERR_UNSUPPORTED_DEVICE = -3
+FSRGEMM_ERR_SCRATCH_LIMIT = -4
+FSRGEMM_NOALLOC_SCRATCH_BYTES = 16 * 1024 * 1024
 FSRGEMM_PLAN_WORKSPACE = 1
 FSRGEMM_PLAN_RULES_ONLY = 2
 
@@ -35,6 +38,7 @@ _QUERY = [_i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64]
 EXPORTS = {
     "gemm_f32": (ctypes.c_int, _GEMM),
     "gemm_f32_ex": (ctypes.c_int, [ctypes.c_int, ctypes.c_int] + _GEMM),
+    "gemm_f32_noalloc": (ctypes.c_int, [ctypes.c_int, ctypes.c_int] + _GEMM),
     "gemm_f32_workspace_bytes": (_i64, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64]),
     "gemm_f32_ws": (ctypes.c_int, [ctypes.c_int, ctypes.c_int] + _GEMM[:-1] + [_vp, _i64, _vp]),
     "gemm_bf16_workspace_bytes": (_i64, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64]),
@@ -111,6 +115,11 @@ def gemm_f32(M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
 def gemm_f32_ex(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
     return load().gemm_f32_ex(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
                               _ptr(stream) or None)
+
+
+def gemm_f32_noalloc(transA, transB, M, N, K, A, lda, B, ldb, C, ldc, stream=0) -> int:
+    return load().gemm_f32_noalloc(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
+                                   _ptr(stream) or None)
 
 
 def gemm_f32_workspace_bytes(transA, transB, M, N, K) -> int:
