@@ -239,6 +239,28 @@ def mid_sizes_f32(lib, torch):
     return out
 
 
+def mid_sizes_bf16(lib, torch):
+    """bf16 problems (A row-major, B column-major) whose 256 x 256 tiles do not fill whole rounds of the compute units, or
+    whose K is not whole K-tiles: the tile shape of the direct-to-LDS kernel the dispatcher took, its rate, and
+    torch.matmul (the vendor library, bf16 output) on the same buffers for scale.  Profiler leg only; parity of every
+    shape and of the rest-of-K step is covered by the GPU tests."""
+    import math
+
+    stream = torch.cuda.current_stream().cuda_stream
+    out = []
+    for M, N, K in ((4096, 4096, 4096), (5120, 5120, 5120), (6144, 6144, 6144), (7168, 7168, 7168), (3072, 8192, 4096),
+                    (8192, 8192, 8200), (8000, 8000, 8000)):
+        a = (torch.randn(M, K, device="cuda") / math.sqrt(K)).to(torch.bfloat16)
+        b = (torch.randn(N, K, device="cuda") / math.sqrt(K)).to(torch.bfloat16)
+        c, cb = torch.empty(M, N, device="cuda"), torch.empty(M, N, device="cuda", dtype=torch.bfloat16)
+        ms = steady_ms(torch, lambda: lib.check(lib.gemm_bf16(M, N, K, a, K, b, K, c, N, stream)), samples=5)
+        vendor = steady_ms(torch, lambda: torch.matmul(a, b.t(), out=cb), samples=5)
+        out.append({"M": M, "N": N, "K": K, "kernel": lib.fsrgemm_kernel_for_bf16(M, N, K, a, K, b, K, c, N), "ms": ms,
+                    "tflops": 2.0 * M * N * K / (ms * 1e-3) / 1e12, "torch_matmul_bf16_out_tflops": 2.0 * M * N * K / (vendor * 1e-3) / 1e12})
+        del a, b, c, cb
+    return out
+
+
 def small_fixed_configs(lib, torch):
     """fp32 256^3 and 1024^3 (the small fixed configurations; parity is a GPU test): these are bound by launch
     latency and by the number of tiles, so the figure of interest is microseconds per launch."""
@@ -528,11 +550,12 @@ def main():
         del w
         torch.cuda.empty_cache()
 
-    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = small = task20 = mid = None
+    task2 = layouts = layouts_bf16 = skinny = skinny_bf16 = task8 = selection = graph = small = task20 = mid = mid16 = None
     if not args.headline_only:
         small = small_fixed_configs(lib, torch)
         task2 = paper_task2_sizes(lib, torch)
         mid = mid_sizes_f32(lib, torch)
+        mid16 = mid_sizes_bf16(lib, torch)
         layouts = transposed_storage_4096(lib, torch)
         layouts_bf16 = storage_orders_bf16_8192(lib, torch)
         skinny = split_k(lib, torch, "f32")
@@ -573,6 +596,7 @@ def main():
         "sweep": sweep,
         "paper_task2_shapes": task2,
         "mid_sizes_f32": mid,
+        "mid_sizes_bf16": mid16,
         "transposed_storage_f32_4096": layouts,
         "storage_orders_bf16_8192": layouts_bf16,
         "split_k_f32": skinny,

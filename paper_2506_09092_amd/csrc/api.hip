@@ -237,17 +237,34 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
     return mode_f32(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
 }
 
-// The direct-to-LDS kernel needs unchecked 256 x 256 x 64 tiles, 32-bit lane offsets and, for an operand that
-// is contiguous along m (n), M (N) a multiple of 8: a shifted last tile must still start 16-byte aligned.
-bool main_kernel_fits(int a_lay, int b_lay, int64_t M, int64_t N, int mode, int64_t lda, int64_t ldb)
+// Tile rule for the bf16 direct-to-LDS kernel: the shape with the least modelled time.  A launch takes as many rounds
+// as the compute unit with the most tiles, a round takes b ns per K-tile plus a ns around them (prologue, result
+// written out), and -- unlike fp32 -- a last round that fills only part of the 256 compute units is shorter than a
+// full one, down to three quarters: this kernel runs against the power limit, and with compute units idle the others
+// clock higher.  b and a per shape are a least-squares fit to launches of every shape forced on 18 problems (4096^3 ...
+// 10240^2 x 4096, 16384 x 4096 x 4096); the fit picks the measured winner or a shape within 3 % of it on all of them.
+// Returns the shape, or -1 when none fits the problem (fits: bit s set if shape s can take it).
+constexpr int64_t kBf16MainPerKTile[kBf16MainShapes] = {1333, 1073, 780, 1037, 907, 808};      // in the order of the shapes
+constexpr int64_t kBf16MainPerRound[kBf16MainShapes] = {8700, 5800, 4700, 7700, 3700, 5200};
+int tile_rule_bf16_main(int64_t M, int64_t N, int64_t K, unsigned fits)
 {
-    return mode == kFast && lda < (1 << 25) && ldb < (1 << 25) && (a_lay == kKContig || M % 8 == 0) &&
-           (b_lay == kKContig || N % 8 == 0);
+    int best = -1;
+    int64_t best_cost = 0;
+    for (int sh = 0; sh < kBf16MainShapes; ++sh) {
+        if (!(fits >> sh & 1)) continue;
+        const int64_t tiles = ceil_div(M, bf16_main_tile_m(sh)) * ceil_div(N, bf16_main_tile_n(sh)), rest = tiles % 256;
+        const int64_t rounds256 = tiles / 256 * 256 + (rest == 0 ? 0 : rest < 192 ? 192 : rest);       // in 1/256 of a round
+        const int64_t cost = rounds256 * (kBf16MainPerKTile[sh] * ceil_div(K, 64) + kBf16MainPerRound[sh]);
+        if (best < 0 || cost < best_cost) best = sh, best_cost = cost;
+    }
+    return best;
 }
 
 int mode_bf16(int cfg, int slices, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B,
               int64_t ldb, int *mode)
 {
+    *mode = 0;
+    if (bf16_main_shape(cfg) >= 0) return FSRGEMM_OK;       // whether it fits the problem is its own check
     const int b = kBf16Tile[cfg];
     if (ceil_div(M, b) * ceil_div(N, b) * slices >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
     const bool vec = aligned16(A) && aligned16(B) && lda % 8 == 0 && ldb % 8 == 0;
@@ -269,22 +286,24 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     }
     p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 64) : 1;
     if (!t && p->slices == 1 && use_table) t = find_tuned(1, transA, transB, M, N, K, false);
+    unsigned main_fits = 0;
+    for (int sh = 0; sh < kBf16MainShapes; ++sh) main_fits |= (unsigned)bf16_main_fits(sh, a_lay, b_lay, M, N, K, A, lda, B, ldb) << sh;
+    if (t && bf16_main_shape(t->tile) >= 0 && (!(main_fits >> bf16_main_shape(t->tile) & 1) || t->slices > 1)) t = nullptr;  // a row for operands aligned otherwise
     if (t) p->cfg = t->tile;
     // a split runs on 128 x 128 tiles where those still give every compute unit a workgroup (up to 30 % faster than
     // 64 x 64 ones there, measured on 256^2 ... 1024^2 with K up to 65536), else on 64 x 64 tiles
     else if (p->slices > 1) p->cfg = ceil_div(M, 128) * ceil_div(N, 128) * p->slices >= 240 ? kBf16_128x128 : kBf16_64x64;
-    else if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) p->cfg = kBf16_Main;
+    // where 256 x 256 tiles give at least half the compute units one each: the direct-to-LDS kernel in the shape that
+    // fills whole rounds, or, where it does not fit (alignment, a K that is not whole 16-byte pieces), the general
+    // kernel of that tile
+    else if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) p->cfg = main_fits ? bf16_main_candidate(tile_rule_bf16_main(M, N, K, main_fits)) : (int)kBf16_256x256;
     else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kBf16_128x128;
     else p->cfg = kBf16_64x64;
     if (p->cfg == kBf16_Vector) {       // a row of the selection table
         p->mode = 0;
         return vector_shape(M, N, K) ? FSRGEMM_OK : FSRGEMM_ERR_INVALID_ARG;
     }
-    int rc = mode_bf16(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
-    // where the direct-to-LDS kernel does not fit (alignment, ragged K, a split), the general kernel of its tile runs
-    if (rc == FSRGEMM_OK && p->cfg == kBf16_Main && (p->slices > 1 || !main_kernel_fits(a_lay, b_lay, M, N, p->mode, lda, ldb)))
-        p->cfg = kBf16_256x256;
-    return rc;
+    return mode_bf16(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
 }
 
 // gfx950 check for the current device, cached per device ordinal (racing first calls just repeat the query).
@@ -385,10 +404,14 @@ int run_bf16(const Plan &p, int a_lay, int b_lay, int64_t M, int64_t N, int64_t 
              const uint16_t *B, int64_t ldb, float *C, int64_t ldc, float *ws, hipStream_t s)
 {
     const bool split = p.slices > 1;
-    if (split && p.cfg == kBf16_Main) return FSRGEMM_ERR_INVALID_ARG;     // the planners never pair the two
+    if (split && bf16_main_shape(p.cfg) >= 0) return FSRGEMM_ERR_INVALID_ARG;     // the planners never pair the two
     const int rc = device_ok();
     if (rc != FSRGEMM_OK) return rc;
     hipError_t e;
+    if (bf16_main_shape(p.cfg) >= 0) {
+        e = launch_bf16_main(bf16_main_shape(p.cfg), a_lay, b_lay, pack(M, N, K, A, lda, B, ldb, C, ldc), s);
+        return e == hipSuccess ? FSRGEMM_OK : e == hipErrorInvalidValue ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_ERR_LAUNCH;
+    }
     if (p.cfg == kBf16_Vector) {
         VecMap16 v = vector_map16(a_lay == kMnContig, b_lay == kKContig, M, N, K, A, lda, B, ldb, C, ldc);
         if (split) v.a.y = ws, v.a.incy = 1, v.a.k_slices = p.slices, v.a.slice_stride = v.a.len;
@@ -598,7 +621,7 @@ int gemm_bf16_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int
 {
     int rc = check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc);
     if (rc != FSRGEMM_OK) return rc;
-    if (!forced_ok(tile, kBf16_Vector + 1, k_slices, M, N, K, 64, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
+    if (!forced_ok(tile, kBf16_MainMore + kBf16MainShapes - 1, k_slices, M, N, K, 64, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
     const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
     Plan p = {tile, 0, k_slices};
     if (tile == kBf16_Vector) {
@@ -609,7 +632,9 @@ int gemm_bf16_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int
     rc = mode_bf16(tile, k_slices, M, N, K, A, lda, B, ldb, &p.mode);
     if (rc != FSRGEMM_OK) return rc;
     // a forced direct-to-LDS kernel is an invalid candidate where it does not fit; nothing else is substituted
-    if (tile == kBf16_Main && (k_slices > 1 || !main_kernel_fits(a_lay, b_lay, M, N, p.mode, lda, ldb))) return FSRGEMM_ERR_INVALID_ARG;
+    if (bf16_main_shape(tile) >= 0 && M > 0 && N > 0 &&
+        (k_slices > 1 || !bf16_main_fits(bf16_main_shape(tile), a_lay, b_lay, M, N, K, A, lda, B, ldb)))
+        return FSRGEMM_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return FSRGEMM_OK;
     return run_bf16(p, a_lay, b_lay, M, N, K, A, lda, B, ldb, C, ldc, static_cast<float *>(workspace),
                     static_cast<hipStream_t>(stream));
@@ -628,7 +653,7 @@ int fsrgemm_plan_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, c
     return FSRGEMM_OK;
 }
 
-int fsrgemm_tile_count_bf16(void) { return kBf16_Vector + 1; }
+int fsrgemm_tile_count_bf16(void) { return kBf16_MainMore + kBf16MainShapes - 1; }
 
 const char *fsrgemm_kernel_for_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
                                    int64_t ldb, const float *C, int64_t ldc)
@@ -706,11 +731,11 @@ const char *fsrgemm_kernel_for_bf16_cfg(int tile, int transA, int transB, int64_
         const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
         return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a));
     }
-    if (tile < 0 || tile >= kBf16ConfigCount) return nullptr;
+    if (tile < 0 || tile >= kBf16_MainMore + kBf16MainShapes - 1) return nullptr;
     const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
     int mode;
     if (mode_bf16(tile, 1, M, N, K, A, lda, B, ldb, &mode) != FSRGEMM_OK) return nullptr;
-    if (tile == kBf16_Main && !main_kernel_fits(a_lay, b_lay, M, N, mode, lda, ldb)) return nullptr;
+    if (bf16_main_shape(tile) >= 0 && !bf16_main_fits(bf16_main_shape(tile), a_lay, b_lay, M, N, K, A, lda, B, ldb)) return nullptr;
     return bf16_kernel_name(tile, mode, a_lay, b_lay);
 }
 

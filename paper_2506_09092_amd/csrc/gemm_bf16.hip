@@ -340,13 +340,13 @@ const char *bf16_kernel_name(int cfg, int mode, int a_lay, int b_lay)
         }
     };
     static const Names names;
-    return cfg == kBf16_Main ? bf16_main_kernel_name(a_lay, b_lay) : names.text[cfg - 1][mode][a_lay][b_lay];
+    return bf16_main_shape(cfg) >= 0 ? bf16_main_kernel_name(bf16_main_shape(cfg), a_lay, b_lay) : names.text[cfg - 1][mode][a_lay][b_lay];
 }
 
 hipError_t launch_bf16(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
+    if (bf16_main_shape(cfg) >= 0) return launch_bf16_main(bf16_main_shape(cfg), a_lay, b_lay, a, s);
     switch (cfg) {
-    case kBf16_Main: return launch_bf16_main(a_lay, b_lay, a, s);
     case kBf16_256x256: return launch_cfg<4, 1>(mode, a_lay, b_lay, a, s);
     case kBf16_128x128: return launch_cfg<2, 2>(mode, a_lay, b_lay, a, s);
     default: return launch_cfg<1, 4>(mode, a_lay, b_lay, a, s);

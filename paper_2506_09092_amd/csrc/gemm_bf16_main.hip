@@ -5,7 +5,7 @@
 // row-major B: the tile's rows are k-rows of 512 bytes); LDS keeps the memory
 // order and the fragment reads do the rest (see "Fragments" below).
 //
-// Shape of the computation
+// Shape of the computation (for the 256 x 256 tile; "Tile shapes" below)
 //   workgroup  : 256 lanes = 4 wavefronts, one per SIMD, 256 x 256 tile of C
 //   wavefront  : 128 x 128 of that tile = 8 x 8 blocks of V_MFMA_F32_16X16X32_BF16,
 //                256 accumulator registers (the whole AccVGPR file)
@@ -74,6 +74,20 @@
 // block's reads differ by an XOR in address bits 5-7, so a lane keeps one
 // address per block (8 registers per such operand) and reaches k-step, half
 // and stage through immediate offsets.
+//
+// Tile shapes.  A launch lasts as long as the compute unit with the most tiles, so a problem whose 256 x 256
+// tiles do not fill whole rounds of the compute units is better off with a tile that does: the kernel is a
+// template over the blocks per wavefront, IM x JN of 16 x 16 (tile 32 IM x 32 JN), built for sides of 256, 192
+// and 128 (a 128 x 128 tile asks the L2 for more bytes per cycle than a compute unit gets, and is left out).
+// Everything scales: IM + JN loads per wavefront and K-tile, IM + JN fragment reads and IM JN MFMAs per
+// k-step.  An operand that is contiguous along m / n keeps its side at 256.
+//
+// Rest of K.  When K is not whole K-tiles (it is a multiple of 8, so a 16-byte piece lies inside K or beyond
+// it), one more K-tile follows the pipeline, once per tile of C: its loads take an address per lane through the
+// compiler's builtin, pieces beyond K come from a zero piece in device memory, the loads are waited for, then
+// the k-steps that contain k < K run with their fragment reads in front.
+#include <stdio.h>
+
 #include <type_traits>
 #include <utility>
 
@@ -88,21 +102,21 @@ namespace {
 // that it is a reserved register.  Nothing the compiler emits for this kernel uses M0.
 #pragma clang diagnostic ignored "-Winline-asm"
 
-constexpr int kBM = 256, kBN = 256, kBK = 64;
-constexpr int kTileBytes = kBM * kBK * 2;       // one operand tile: 32 KB
-constexpr int kStageBytes = 2 * kTileBytes;     // A + B: 64 KB
+constexpr int kBK = 64;
 constexpr int kScratchBytes = 1024;             // landing zone of the prefetch touches (256 B per wavefront)
-constexpr int kLdsBytes = 2 * kStageBytes + kScratchBytes;
 constexpr int kThreads = 256;
-constexpr int kEarly = 12;       // loads of K-tile t+2 issued in k-step 1 of K-tile t; the other 4 in k-step 0 of t+1
-constexpr int kTouchAhead = 3;   // K-tiles between a prefetch touch and the loads it serves: 2 is too late, 4 and
-                                 // more let touched lines be evicted before use (more fabric reads, same time)
-constexpr int kReadEvery = 3;    // a fragment read behind every third MFMA: the 16 reads of a k-step are done by slot 45
+constexpr int kLate = 4;         // loads of K-tile t+1 issued in k-step 0 of K-tile t; the others earlier, in k-step 1 of t-1
 constexpr int kLoadEvery = 4;    // a load behind every fourth MFMA (slots 2, 6, ...): denser loads stall the matrix pipe
 
+// where the loads of the last, partial K-tile fetch the pieces that lie beyond K
+__device__ __attribute__((aligned(16))) const uint16_t kZeroPiece[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+
+#define FSR_AS1 __attribute__((address_space(1)))
+
+template <int IM, int JN>
 struct Frag {
-    bf16x8 a[8];
-    bf16x8 b[8];
+    bf16x8 a[IM];
+    bf16x8 b[JN];
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -126,10 +140,22 @@ __device__ __forceinline__ void static_for(F &&f)
 // chunk swizzle of a tile whose rows are k-rows (operand contiguous along m / n)
 __device__ __forceinline__ int kswz(int k) { return ((k & 3) << 1) | (((k >> 3) & 1) << 3); }
 
-template <int ALAY, int BLAY>
+template <int IM, int JN, int ALAY, int BLAY>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, int tiles_m, int tiles_n)
 {
     constexpr bool AMC = ALAY == kMnContig, BMC = BLAY == kMnContig;
+    static_assert((!AMC || IM == 8) && (!BMC || JN == 8), "an operand contiguous along m / n keeps its side at 256");
+    constexpr int kBM = 32 * IM, kBN = 32 * JN;
+    constexpr int kTileA = kBM * kBK * 2, kTileB = kBN * kBK * 2;       // operand tiles: 128 bytes per row
+    constexpr int kStageBytes = kTileA + kTileB;
+    constexpr int kLoadsA = IM, kLoadsB = JN, kLoads = IM + JN;        // 1 KB each, per wavefront and K-tile
+    constexpr int kMfmas = IM * JN;                                    // per k-step
+    constexpr int kReads = IM + JN;                                    // fragment reads per k-step
+    constexpr int kEarly = kLoads - kLate;
+    constexpr int kReadEvery = kMfmas >= 36 ? 3 : 2;                   // a fragment read behind every third (second) MFMA
+    // K-tiles between a prefetch touch and the loads it serves: with 64 MFMAs per k-step 2 is too late, 4 and more
+    // let touched lines be evicted before use (more fabric reads, same time); shorter K-tiles look one further ahead
+    constexpr int kTouchAhead = kMfmas == 64 ? 3 : 4;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     int tile_m, tile_n;
@@ -137,18 +163,18 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     const int m0 = tile_origin(tile_m, kBM, g.M), n0 = tile_origin(tile_n, kBN, g.N);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+    const int wm0 = (wave >> 1) * (16 * IM), wn0 = (wave & 1) * (16 * JN);
     const int l16 = lane & 15, lq = lane >> 4;
     const int nk = g.K / kBK;
     const uint16_t *A = static_cast<const uint16_t *>(g.A);
     const uint16_t *B = static_cast<const uint16_t *>(g.B);
 
-    // Global -> LDS.  A load instruction moves 64 x 16 bytes to 1 KB of contiguous LDS; a wavefront fills 8 KB
-    // of each operand tile with 8 loads (index q = 0..7 for A, 8 + q for B).
-    //   contiguous along k    : 8 tile rows per load: rows 64 w + 8 q + lane / 8; the lane fetches the chunk that
-    //                           belongs at its position, (lane % 8) ^ ((row >> 1) & 7), and
-    //                           ((64 w + 8 q + lane / 8) >> 1) & 7 = 4 (q & 1) + (lane / 8 >> 1): one lane offset for
-    //                           even q, one for odd q.  The lane offsets also carry the K position.
+    // Global -> LDS.  A load instruction moves 64 x 16 bytes to 1 KB of contiguous LDS; a wavefront fills its
+    // quarter of each operand tile (8 IM KB of A, 8 JN KB of B) with IM + JN loads (index q < IM for A, IM + q for B).
+    //   contiguous along k    : 8 tile rows per load: rows 8 IM w + 8 q + lane / 8 (8 JN w + .. for B); the lane fetches
+    //                           the chunk that belongs at its position, (lane % 8) ^ ((row >> 1) & 7), and
+    //                           ((8 IM w + 8 q + lane / 8) >> 1) & 7 = 4 (q & 1) + (lane / 8 >> 1) for even IM: one lane
+    //                           offset for even q, one for odd q.  The lane offsets also carry the K position.
     //   contiguous along m / n: 2 k-rows per load: k-rows 16 w + 2 q + lane / 32; chunk (lane % 32) ^ kswz(k-row),
     //                           k-row % 4 = 2 (q & 1) + lane / 32 and (k-row / 8) % 2 = q / 4: four lane offsets,
     //                           index (q & 1) + 2 (q >> 2).  The K position is carried by the scalar row bases.
@@ -163,33 +189,34 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         voff_a[v] = AMC ? (uint32_t)(hrow * g.lda * 2 + (hpos ^ kswz(kr)) * 16) : (uint32_t)(lrow * g.lda + kc_chunk * 8) * 2u;
         voff_b[v] = BMC ? (uint32_t)(hrow * g.ldb * 2 + (hpos ^ kswz(kr)) * 16) : (uint32_t)(lrow * g.ldb + kc_chunk * 8) * 2u;
     }
-    const char *rbase[16];          // row-group bases: uniform; fixed for the tile unless they carry the K position
+    const char *rbase[kLoads];      // row-group bases: uniform; fixed for the tile unless they carry the K position
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < kLoadsA; ++q)
         rbase[q] = AMC ? reinterpret_cast<const char *>(A + (int64_t)(wave * 16 + q * 2) * g.lda + m0)
-                       : reinterpret_cast<const char *>(A + (int64_t)(m0 + wave * 64 + q * 8) * g.lda);
-        rbase[8 + q] = BMC ? reinterpret_cast<const char *>(B + (int64_t)(wave * 16 + q * 2) * g.ldb + n0)
-                           : reinterpret_cast<const char *>(B + (int64_t)(n0 + wave * 64 + q * 8) * g.ldb);
-    }
+                       : reinterpret_cast<const char *>(A + (int64_t)(m0 + wave * (8 * IM) + q * 8) * g.lda);
+#pragma unroll
+    for (int q = 0; q < kLoadsB; ++q)
+        rbase[kLoadsA + q] = BMC ? reinterpret_cast<const char *>(B + (int64_t)(wave * 16 + q * 2) * g.ldb + n0)
+                                 : reinterpret_cast<const char *>(B + (int64_t)(n0 + wave * (8 * JN) + q * 8) * g.ldb);
     const int64_t kstep_a = 64 * g.lda * 2, kstep_b = 64 * g.ldb * 2;       // one K-tile of k-rows, in bytes
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(FSR_AS3 char *)smem);
-    const uint32_t wave_lds = lds0 + wave * (64 * 128);
+    const uint32_t wave_lds_a = lds0 + wave * (kLoadsA * 1024), wave_lds_b = lds0 + kTileA + wave * (kLoadsB * 1024);
     // M0 <- LDS address of load `idx` in `stage`; at least one instruction must follow before the load
     auto load_m0 = [&](auto stage, auto idx) {
-        constexpr int kOff = decltype(stage)::value * kStageBytes + (decltype(idx)::value < 8 ? 0 : kTileBytes) +
-                             (decltype(idx)::value & 7) * 1024;
-        const uint32_t w = wave_lds;
+        constexpr int I = decltype(idx)::value;
+        constexpr int kOff = decltype(stage)::value * kStageBytes + (I < kLoadsA ? I : I - kLoadsA) * 1024;
+        const uint32_t w = I < kLoadsA ? wave_lds_a : wave_lds_b;
         asm volatile("s_add_u32 m0, %0, %1" ::"s"(w), "n"(kOff) : "m0", "scc");
     };
     bool more = 1 < nk;     // the K-tile after the one now being loaded lies inside K (else the last one is loaded again)
     auto load_go = [&](auto idx) {
-        constexpr int I = decltype(idx)::value, q = I & 7;
-        constexpr bool mc = I < 8 ? AMC : BMC;
+        constexpr int I = decltype(idx)::value, q = I < kLoadsA ? I : I - kLoadsA;
+        constexpr bool mc = I < kLoadsA ? AMC : BMC;
         constexpr int v = mc ? (q & 1) + 2 * (q >> 2) : (q & 1);
-        const uint32_t vo = I < 8 ? voff_a[v] : voff_b[v];
+        const uint32_t vo = I < kLoadsA ? voff_a[v] : voff_b[v];
         const char *rb = rbase[I];
         asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(vo), "s"(rb) : "memory");
-        if constexpr (mc) rbase[I] += more ? (I < 8 ? kstep_a : kstep_b) : 0;      // its next use is the next K-tile
+        if constexpr (mc) rbase[I] += more ? (I < kLoadsA ? kstep_a : kstep_b) : 0;      // its next use is the next K-tile
     };
     // after the last load of a K-tile: the following loads fetch K-tile `next`; past the end they stay on
     // the last K-tile, whose data then lands once more in a stage that is never read again
@@ -200,22 +227,25 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         if (!BMC) voff_b[0] += step, voff_b[1] += step;
     };
 
-    // Prefetch touches, one 128-byte line per lane.  Contiguous along k: lanes 0-15 take A rows
-    // 64 (tile_n % 4) + 16 w + lane, lanes 16-23 take B rows 32 (tile_m % 8) + 8 w + (lane - 16).  Contiguous
-    // along m / n (a K-tile is 64 k-rows of 4 lines): lanes 0-15 take A k-rows 16 (tile_n % 4) + 4 w + lane / 4,
-    // line lane % 4; lanes 16-23 take B k-rows 8 (tile_m % 8) + 2 w + (lane - 16) / 4, line (lane - 16) % 4.
-    // The remaining lanes repeat lane 0 and coalesce with it.
+    // Prefetch touches, one 128-byte line per lane: the workgroup's quarter of its A panel's rows (the 4 tiles
+    // beside it along n read the same panel) and its eighth of its B panel's rows (8 tiles along m).  Contiguous
+    // along k: lanes 0 .. 2 IM - 1 take A rows 8 IM (tile_n % 4) + 2 IM w + lane, the next JN lanes take B rows
+    // 4 JN (tile_m % 8) + JN w + (lane - 2 IM).  Contiguous along m / n (a K-tile is 64 k-rows of 4 lines): lanes
+    // 0-15 take A k-rows 16 (tile_n % 4) + 4 w + lane / 4, line lane % 4; lanes 16-23 take B k-rows
+    // 8 (tile_m % 8) + 2 w + (lane - 16) / 4, line (lane - 16) % 4.  The remaining lanes repeat lane 0 and coalesce
+    // with it.
     const char *touch_ptr;
     int64_t touch_step;
     {
-        const int tl = lane < 24 ? lane : 0, u = tl - 16;
-        if (tl < 16) {
+        constexpr int kTouchA = 2 * IM, kTouchB = JN;
+        const int tl = lane < kTouchA + kTouchB ? lane : 0, u = tl - kTouchA;
+        if (tl < kTouchA) {
             touch_ptr = AMC ? reinterpret_cast<const char *>(A + (int64_t)((tile_n & 3) * 16 + wave * 4 + (tl >> 2)) * g.lda + m0 + (tl & 3) * 64)
-                            : reinterpret_cast<const char *>(A + (int64_t)(m0 + (tile_n & 3) * 64 + wave * 16 + tl) * g.lda);
+                            : reinterpret_cast<const char *>(A + (int64_t)(m0 + (tile_n & 3) * (8 * IM) + wave * (2 * IM) + tl) * g.lda);
             touch_step = AMC ? kstep_a : kBK * 2;
         } else {
             touch_ptr = BMC ? reinterpret_cast<const char *>(B + (int64_t)((tile_m & 7) * 8 + wave * 2 + (u >> 2)) * g.ldb + n0 + (u & 3) * 64)
-                            : reinterpret_cast<const char *>(B + (int64_t)(n0 + (tile_m & 7) * 32 + wave * 8 + u) * g.ldb);
+                            : reinterpret_cast<const char *>(B + (int64_t)(n0 + (tile_m & 7) * (4 * JN) + wave * JN + u) * g.ldb);
             touch_step = BMC ? kstep_b : kBK * 2;
         }
     }
@@ -234,56 +264,55 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     // Contiguous along m / n: as the source of a transposing read the lane points at k-row
     // 32 kk + 8 lq + 4 h + l16 / 4 (h = 0, 1: the two reads), rows 16 b + 4 (l16 % 4) .. + 3 of the wavefront's
     // part; block b flips address bits 5-7 with b, k-step and half add 16 KB and 2 KB.
-    int ra_off[2], rb_off[2], ra_blk[8], rb_blk[8];
+    int ra_off[2], rb_off[2], ra_blk[AMC ? 8 : 1], rb_blk[BMC ? 8 : 1];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
         const int pos = (4 * kk + lq) ^ ((l16 >> 1) & 7);
         ra_off[kk] = (wm0 + l16) * 128 + pos * 16;
-        rb_off[kk] = kTileBytes + (wn0 + l16) * 128 + pos * 16;
+        rb_off[kk] = kTileA + (wn0 + l16) * 128 + pos * 16;
     }
     {
         const int fk = kswz((l16 >> 2) + 8 * lq), half = (l16 >> 1) & 1;
         const int row_part = (8 * lq + (l16 >> 2)) * 512 + (l16 & 1) * 8;
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
-            ra_blk[b] = (row_part + ((wm0 / 8) | fk | half) * 16) ^ (b << 5);
-            rb_blk[b] = kTileBytes + ((row_part + ((wn0 / 8) | fk | half) * 16) ^ (b << 5));
+            if constexpr (AMC) ra_blk[b] = (row_part + ((wm0 / 8) | fk | half) * 16) ^ (b << 5);
+            if constexpr (BMC) rb_blk[b] = kTileA + ((row_part + ((wn0 / 8) | fk | half) * 16) ^ (b << 5));
         }
     }
-    Frag F[2];
+    Frag<IM, JN> F[2];
     auto tr_read = [&](const char *p) {
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)p);
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)(p + 2048));
         return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    // idx orders the sixteen fragments as the next k-step consumes them: a0, b0..b7, a1..a7
+    // idx orders the IM + JN fragments as the next k-step consumes them: a0, b0 .. b(JN-1), a1 .. a(IM-1)
     auto lread = [&](int stage, int kk, int fi, int idx) {
         const char *s = smem + stage * kStageBytes;
-        if (idx == 0 || idx > 8) {
-            const int i = idx == 0 ? 0 : idx - 8;
-            if (AMC) F[fi].a[i] = tr_read(s + ra_blk[i] + kk * 16384);
+        if (idx == 0 || idx > JN) {
+            const int i = idx == 0 ? 0 : idx - JN;
+            if constexpr (AMC) F[fi].a[i] = tr_read(s + ra_blk[i] + kk * 16384);
             else F[fi].a[i] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk] + i * 2048);
         } else {
             const int j = idx - 1;
-            if (BMC) F[fi].b[j] = tr_read(s + rb_blk[j] + kk * 16384);
+            if constexpr (BMC) F[fi].b[j] = tr_read(s + rb_blk[j] + kk * 16384);
             else F[fi].b[j] = *reinterpret_cast<const bf16x8 *>(s + rb_off[kk] + j * 2048);
         }
     };
 
-    f32x4 acc[8][8];
+    f32x4 acc[IM][JN];
 
-    constexpr int kLate = 16 - kEarly;
     constexpr int kTouchSlot = kLoadEvery * kLate + 1;      // behind the late loads, so the touch is the youngest load at the barrier
-    static_assert(kLoadEvery * 16 <= 64 && kReadEvery * 15 < 64 && kTouchSlot + 2 < 64, "slots of one k-step");
+    static_assert(kLoadEvery * (kEarly - 1) + 2 < kMfmas && kReadEvery * (kReads - 1) < kMfmas && kTouchSlot + 2 < kMfmas, "slots of one k-step");
 
     auto k_tile = [&](auto parity, int t) {
         constexpr int P = decltype(parity)::value;
         constexpr int X = P, Y = 1 - P;
         static_for<2>([&](auto kkc) {
             constexpr int kk = decltype(kkc)::value;
-            static_for<64>([&](auto mc) {
+            static_for<kMfmas>([&](auto mc) {
                 constexpr int m = decltype(mc)::value;
-                constexpr int i = m >> 3, j = m & 7;
+                constexpr int i = m / JN, j = m % JN;
                 constexpr int c = m / kLoadEvery;               // load of this group of slots
                 constexpr bool has_load = kk == 1 ? c < kEarly : c < kLate;
                 if constexpr (m % kLoadEvery == 1 && has_load) {
@@ -292,7 +321,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
                 }
                 if constexpr (kk == 0 && m == kTouchSlot) touch_m0();
                 asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(F[kk].a[i]), "v"(F[kk].b[j]));
-                if constexpr (m % kReadEvery == 0 && m / kReadEvery < 16) {
+                if constexpr (m % kReadEvery == 0 && m / kReadEvery < kReads) {
                     // fragments of the next k-step (the next K-tile's first, from Y, once the barrier is passed)
                     if constexpr (kk == 0) lread(X, 1, 1, m / kReadEvery);
                     else lread(Y, 0, 0, m / kReadEvery);
@@ -322,7 +351,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
 
     // Prologue: K-tile 0 into stage 0 and touches for the K-tiles the loop's own touches come too late for;
     // only K-tile 0 is waited for (the touches are the youngest kTouchAhead - 1 loads).
-    static_for<16>([&](auto ic) {
+    static_for<kLoads>([&](auto ic) {
         load_m0(Int<0>{}, ic);
         asm volatile("s_nop 0");
         load_go(ic);
@@ -334,16 +363,17 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     advance(1);
     // the accumulators are cleared while K-tile 0 is on its way
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < IM; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < JN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < IM; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) asm volatile("" : "+a"(acc[i][j]));      // pins the clears here
+        for (int j = 0; j < JN; ++j) asm volatile("" : "+a"(acc[i][j]));      // pins the clears here
     __builtin_amdgcn_sched_barrier(0);
-    static_assert(kTouchAhead == 3, "the wait below skips kTouchAhead - 1 touches");
-    asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    static_assert(kTouchAhead == 3 || kTouchAhead == 4, "the wait below skips the kTouchAhead - 1 touches");
+    if constexpr (kTouchAhead == 3) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     // then the early loads of K-tile 1 into stage 1 and the first fragments
@@ -353,7 +383,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         load_go(ic);
     });
 #pragma unroll
-    for (int idx = 0; idx < 16; ++idx) lread(0, 0, 0, idx);
+    for (int idx = 0; idx < kReads; ++idx) lread(0, 0, 0, idx);
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_sched_barrier(0);
 
@@ -363,20 +393,68 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         k_tile(Int<1>{}, t + 1);
     }
     if (t < nk) k_tile(Int<0>{}, t);
+
+    // The rest of K: one more K-tile into stage 0, outside the pipeline.  The lane that fills position p of a row
+    // fetches the piece that belongs there if it lies inside K, else the zero piece.
+    const int k_rest = g.K - nk * kBK;
+    if (k_rest > 0) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();       // every load has landed and every wavefront is done with both stages
+        __builtin_amdgcn_sched_barrier(0);
+        // (the lane id is taken afresh from the hardware: nothing of this step is to be worked out, and kept in registers, ahead of the loop)
+        int ln = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        asm volatile("" : "+v"(ln));
+        auto rest_src = [&](auto mcc, const uint16_t *P, int64_t ld, int origin, int rows_per_wave, int q) -> const uint16_t * {
+            if constexpr (decltype(mcc)::value) {
+                const int kr = wave * 16 + q * 2 + (ln >> 5);       // k-row of the K-tile; chunk = 8 rows / columns
+                return kr < k_rest ? P + (int64_t)(nk * kBK + kr) * ld + origin + 8 * ((ln & 31) ^ kswz(kr)) : kZeroPiece;
+            } else {
+                const int row = ln >> 3, chunk = (ln & 7) ^ (((row >> 1) & 3) | ((q & 1) << 2));
+                return 8 * chunk < k_rest ? P + (int64_t)(origin + wave * rows_per_wave + q * 8 + row) * ld + nk * kBK + 8 * chunk : kZeroPiece;
+            }
+        };
+#pragma unroll
+        for (int idx = 0; idx < kLoads; ++idx) {
+            const bool is_a = idx < kLoadsA;
+            const int q = is_a ? idx : idx - kLoadsA;
+            char *dst = smem + (is_a ? wave * (kLoadsA * 1024) : kTileA + wave * (kLoadsB * 1024)) + q * 1024;
+            const uint16_t *src = is_a ? rest_src(std::integral_constant<bool, AMC>{}, A, g.lda, m0, 8 * IM, q)
+                                       : rest_src(std::integral_constant<bool, BMC>{}, B, g.ldb, n0, 8 * JN, q);
+            __builtin_amdgcn_global_load_lds((const FSR_AS1 void *)src, (FSR_AS3 void *)dst, 16, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            if (32 * kk < k_rest) {
+#pragma unroll
+                for (int idx = 0; idx < kReads; ++idx) lread(0, kk, 0, idx);
+                __builtin_amdgcn_s_waitcnt(0xC07F);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int m = 0; m < kMfmas; ++m)
+                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[m / JN][m % JN]) : "v"(F[0].a[m / JN]), "v"(F[0].b[m % JN]));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
     // no load may still be writing LDS when the wavefront ends, and the last MFMAs must have retired
     // before the accumulators are read (the compiler does not know what wrote them)
     asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
-    // Register r of a 16x16 block holds row 4 (lane / 16) + r, column lane % 16.  The lane ids are taken
-    // afresh so that no store address is kept in a register across the loop; blocks are fenced so that the
+    // Register r of a 16x16 block holds row 4 (lane / 16) + r, column lane % 16.  The lane id is taken
+    // afresh from the hardware so that no store address is kept in a register across the loop; blocks are fenced so that the
     // accumulators are copied out a block at a time.
     float *__restrict__ C = g.C;
-    int l16e = lane & 15, lqe = lane >> 4;
-    asm volatile("" : "+v"(l16e), "+v"(lqe));
+    int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));      // the lane's number within its wavefront
+    asm volatile("" : "+v"(lane_e));
+    const int l16e = lane_e & 15, lqe = lane_e >> 4;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < IM; ++i)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < JN; ++j) {
             const int col = n0 + wn0 + j * 16 + l16e;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -389,37 +467,90 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
 
 }  // namespace
 
-// <A layout, B layout> with 0 = contiguous along k, 1 = along m / n; as a profiler trace prints the kernel
-const char *bf16_main_kernel_name(int a_lay, int b_lay)
+// in the order of the candidate numbers: 256 x 256 was there first
+constexpr int kShapeM[kBf16MainShapes] = {256, 192, 128, 256, 192, 256}, kShapeN[kBf16MainShapes] = {256, 256, 256, 192, 192, 128};
+
+int bf16_main_tile_m(int shape) { return kShapeM[shape]; }
+int bf16_main_tile_n(int shape) { return kShapeN[shape]; }
+
+// <blocks of 16 rows per wavefront, blocks of 16 columns, A layout, B layout> with 0 = contiguous along k, 1 = along
+// m / n; as a profiler trace prints the kernel
+const char *bf16_main_kernel_name(int shape, int a_lay, int b_lay)
 {
-    static const char *names[2][2] = {{"gemm_bf16_main_kernel<0, 0>", "gemm_bf16_main_kernel<0, 1>"},
-                                      {"gemm_bf16_main_kernel<1, 0>", "gemm_bf16_main_kernel<1, 1>"}};
-    return names[a_lay][b_lay];
+    struct Names {
+        char text[kBf16MainShapes][2][2][40];
+        Names()
+        {
+            for (int sh = 0; sh < kBf16MainShapes; ++sh)
+                for (int a = 0; a < 2; ++a)
+                    for (int b = 0; b < 2; ++b)
+                        snprintf(text[sh][a][b], sizeof text[sh][a][b], "gemm_bf16_main_kernel<%d, %d, %d, %d>", kShapeM[sh] / 32, kShapeN[sh] / 32, a, b);
+        }
+    };
+    static const Names names;
+    return names.text[shape][a_lay][b_lay];
+}
+
+// Whole unchecked tiles of 16-byte pieces: a matrix at least one tile high and wide (a ragged last tile is shifted
+// back into it), at least one whole K-tile of 64 and K a multiple of 8 (the rest of K is whole pieces), 16-byte aligned
+// bases and rows, leading dimensions below 2^25 (32-bit lane offsets); an operand that is contiguous along m (n) needs
+// its side of the tile at 256 and M (N) a multiple of 8, so that a shifted tile still starts on a piece.
+bool bf16_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb)
+{
+    if (shape < 0 || shape >= kBf16MainShapes) return false;
+    const int bm = kShapeM[shape], bn = kShapeN[shape];
+    const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) == 0 && lda % 8 == 0 && ldb % 8 == 0;
+    return aligned && lda < (1 << 25) && ldb < (1 << 25) && M >= bm && N >= bn && K >= kBK && K % 8 == 0 &&
+           (a_lay == kKContig || (bm == 256 && M % 8 == 0)) && (b_lay == kKContig || (bn == 256 && N % 8 == 0)) &&
+           ((M + bm - 1) / bm) * ((N + bn - 1) / bn) < ((int64_t)1 << 31);
 }
 
 namespace {
 
-template <int ALAY, int BLAY>
+template <int IM, int JN, int ALAY, int BLAY>
 hipError_t launch_main(const GemmArgs &a, hipStream_t s)
 {
-    auto kern = gemm_bf16_main_kernel<ALAY, BLAY>;
+    constexpr int kLdsBytes = 2 * (32 * IM + 32 * JN) * kBK * 2 + kScratchBytes;
+    auto kern = gemm_bf16_main_kernel<IM, JN, ALAY, BLAY>;
     static std::atomic<uint64_t> configured{0};
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kLdsBytes, configured);
     if (e != hipSuccess) return e;
-    const int tiles_m = (a.M + kBM - 1) / kBM, tiles_n = (a.N + kBN - 1) / kBN;
+    const int tiles_m = (a.M + 32 * IM - 1) / (32 * IM), tiles_n = (a.N + 32 * JN - 1) / (32 * JN);
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLdsBytes, s, a, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
+// the layouts a shape is built for: an operand contiguous along m / n only with its side at 256
+template <int IM, int JN>
+hipError_t launch_shape(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
+{
+    if (a_lay == kKContig && b_lay == kKContig) return launch_main<IM, JN, kKContig, kKContig>(a, s);
+    if constexpr (IM == 8) {
+        if (a_lay == kMnContig && b_lay == kKContig) return launch_main<IM, JN, kMnContig, kKContig>(a, s);
+    }
+    if constexpr (JN == 8) {
+        if (a_lay == kKContig && b_lay == kMnContig) return launch_main<IM, JN, kKContig, kMnContig>(a, s);
+    }
+    if constexpr (IM == 8 && JN == 8) {
+        if (a_lay == kMnContig && b_lay == kMnContig) return launch_main<IM, JN, kMnContig, kMnContig>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
 }  // namespace
 
-// Requires M >= 256, N >= 256, K % 64 == 0, K >= 64, 16-byte aligned bases, lda % 8 == 0, ldb % 8 == 0 and
-// leading dimensions below 2^25 (32-bit lane offsets).  M and N need not be multiples of 256 (tile_origin), but an
-// operand contiguous along m (n) needs M % 8 == 0 (N % 8 == 0) so that a shifted tile still starts 16-byte aligned.
-hipError_t launch_bf16_main(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
+// requires bf16_main_fits(...) and a.k_slices == 1
+hipError_t launch_bf16_main(int shape, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
-    if (a_lay == kKContig) return b_lay == kKContig ? launch_main<kKContig, kKContig>(a, s) : launch_main<kKContig, kMnContig>(a, s);
-    return b_lay == kKContig ? launch_main<kMnContig, kKContig>(a, s) : launch_main<kMnContig, kMnContig>(a, s);
+    if (!bf16_main_fits(shape, a_lay, b_lay, a.M, a.N, a.K, a.A, a.lda, a.B, a.ldb) || a.k_slices != 1) return hipErrorInvalidValue;
+    switch (shape) {
+    case 0: return launch_shape<8, 8>(a_lay, b_lay, a, s);
+    case 1: return launch_shape<6, 8>(a_lay, b_lay, a, s);
+    case 2: return launch_shape<4, 8>(a_lay, b_lay, a, s);
+    case 3: return launch_shape<8, 6>(a_lay, b_lay, a, s);
+    case 4: return launch_shape<6, 6>(a_lay, b_lay, a, s);
+    default: return launch_shape<8, 4>(a_lay, b_lay, a, s);
+    }
 }
 
 }  // namespace fsrgemm

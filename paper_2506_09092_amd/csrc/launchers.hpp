@@ -29,8 +29,14 @@ hipError_t launch_splitk_reduce(const float *ws, int slices, int64_t slice_strid
 enum Bf16Config { kBf16_Main = 0, kBf16_256x256 = 1, kBf16_128x128 = 2, kBf16_64x64 = 3, kBf16ConfigCount };
 const char *bf16_kernel_name(int cfg, int mode, int a_lay, int b_lay);
 hipError_t launch_bf16(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
-const char *bf16_main_kernel_name(int a_lay, int b_lay);
-hipError_t launch_bf16_main(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
+// the direct-to-LDS kernel's tile shapes: 256 x 256 (candidate kBf16_Main), then 192 x 256, 128 x 256, 256 x 192,
+// 192 x 192, 256 x 128 (candidates kBf16_MainMore ..., after the vector kernels); no K slices
+constexpr int kBf16MainShapes = 6;
+int bf16_main_tile_m(int shape);
+int bf16_main_tile_n(int shape);
+bool bf16_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb);
+const char *bf16_main_kernel_name(int shape, int a_lay, int b_lay);
+hipError_t launch_bf16_main(int shape, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 
 // fp32 products with M == 1 or N == 1 (gemv_f32.hip): y[i * incy] = sum over k of mat(i, k) * x[k * incx] for
 // i < len, with mat(i, k) at mat[i * ld + k] (kVecRows) or mat[k * ld + i] (kVecCols).  With k_slices > 1 slice s
@@ -55,6 +61,13 @@ hipError_t launch_gemv_f32(int pattern, VecArgs a, hipStream_t s);
 
 // the same for bf16 operands (gemv_bf16.hip); y is fp32
 constexpr int kBf16_Vector = kBf16ConfigCount;      // the candidate number of these kernels, after the tile configurations
+constexpr int kBf16_MainMore = kBf16_Vector + 1;    // candidate number of the direct-to-LDS kernel's second shape
+// shape of the direct-to-LDS kernel a bf16 candidate number stands for, -1 if none
+inline int bf16_main_shape(int cfg)
+{
+    return cfg == kBf16_Main ? 0 : cfg >= kBf16_MainMore && cfg < kBf16_MainMore + kBf16MainShapes - 1 ? cfg - kBf16_MainMore + 1 : -1;
+}
+inline int bf16_main_candidate(int shape) { return shape == 0 ? (int)kBf16_Main : kBf16_MainMore + shape - 1; }
 struct VecArgs16 {
     const uint16_t *mat;
     int64_t ld;

@@ -78,18 +78,24 @@ def test_dispatch_query_names_variants():
     assert q(64, 64, 0, P, 4, P, 64, P, 64) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"                    # K = 0 never takes the unchecked mode
     assert q(4, 4, 4, P, 3, P, 4, P, 4) is None
     qb = lib.fsrgemm_kernel_for_bf16
-    assert qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<0, 0>"
+    assert qb(8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<8, 8, 0, 0>"
     # general kernel <T, min waves, load mode>: tile (64 T) x (64 T)
-    assert qb(8192, 8192, 8200, P, 8200, P, 8200, P, 8192) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"   # K not a multiple of 64
+    # <blocks of 16 rows per wavefront, of 16 columns, A layout, B layout>: tile (32 IM) x (32 JN), in the shape that fills
+    # whole rounds; a K that is not whole K-tiles of 64 but whole 16-byte pieces stays (one more K-tile with zero pieces)
+    assert qb(8192, 8192, 8200, P, 8200, P, 8200, P, 8192) == "gemm_bf16_main_kernel<8, 8, 0, 0>"
+    assert qb(8192, 8192, 8196, P, 8200, P, 8200, P, 8192) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"   # K not a multiple of 8
+    assert qb(6144, 6144, 6144, P, 6144, P, 6144, P, 6144) == "gemm_bf16_main_kernel<8, 6, 0, 0>"   # 768 tiles of 256 x 192: 3 whole rounds
+    assert qb(8192, 8192, 56, P, 56, P, 56, P, 8192) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"           # under one K-tile
     assert qb(2048, 2048, 512, P, 512, P, 512, P, 2048) == "gemm_bf16_kernel<2, 2, 0, 0, 0>"
     assert qb(100, 100, 100, P, 100, P, 100, P, 100) == "gemm_bf16_kernel<1, 4, 2, 0, 0>"         # ld not a multiple of 8
     assert qb(100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1, 0, 0>"
     # leading dimensions of 2^25 elements and more do not fit the main kernel's 32-bit lane offsets
     assert qb(8192, 8192, 8192, P, 1 << 25, P, 8192, P, 8192) == "gemm_bf16_kernel<4, 1, 0, 0, 0>"
-    assert qb(8192, 8192, 8192, P, (1 << 25) - 8, P, 8192, P, 8192) == "gemm_bf16_main_kernel<0, 0>"
+    assert qb(8192, 8192, 8192, P, (1 << 25) - 8, P, 8192, P, 8192) == "gemm_bf16_main_kernel<8, 8, 0, 0>"
     # ragged M and N still take the unchecked kernels (last tiles are shifted back); a ragged K does not
-    assert qb(8000, 8000, 8000, P, 8000, P, 8000, P, 8000) == "gemm_bf16_main_kernel<0, 0>"
-    assert qb(8000, 8000, 8008, P, 8008, P, 8008, P, 8000) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"
+    assert qb(8000, 8000, 8000, P, 8000, P, 8000, P, 8000) == "gemm_bf16_main_kernel<8, 8, 0, 0>"
+    assert qb(8000, 8000, 8008, P, 8008, P, 8008, P, 8000) == "gemm_bf16_main_kernel<8, 8, 0, 0>"
+    assert qb(8000, 8000, 8004, P, 8008, P, 8008, P, 8000) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"
     assert qb(255, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_kernel<1, 4, 0, 0, 0>"          # 4 x 128 tiles of 64
     assert q(4000, 4000, 4000, P, 4000, P, 4000, P, 4000) == "gemm_f32_main_kernel<4, 4, 0, 1>"
     assert q(4000, 4000, 4008, P, 4008, P, 4000, P, 4000) == "gemm_f32_main_kernel<2, 4, 0, 1>"          # a rest of K: not the 256 x 256 tile
@@ -97,15 +103,15 @@ def test_dispatch_query_names_variants():
     assert q(63, 4000, 4000, P, 4000, P, 4000, P, 4000) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"            # narrower than a tile
     # other storage orders: <.., A layout, B layout> with 0 = contiguous along k, 1 = along m / n
     qx = lib.fsrgemm_kernel_for_bf16_ex
-    assert qx(0, 1, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<0, 0>"
-    assert qx(0, 0, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<0, 1>"
-    assert qx(1, 1, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<1, 0>"
-    assert qx(1, 0, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<1, 1>"
+    assert qx(0, 1, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<8, 8, 0, 0>"
+    assert qx(0, 0, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<8, 8, 0, 1>"
+    assert qx(1, 1, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<8, 8, 1, 0>"
+    assert qx(1, 0, 8192, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_main_kernel<8, 8, 1, 1>"
     # an operand contiguous along m (n) keeps the main kernel only if M (N) is a multiple of 8
-    assert qx(1, 0, 8000, 4008, 512, P, 8000, P, 4008, P, 4008) == "gemm_bf16_main_kernel<1, 1>"
+    assert qx(1, 0, 8000, 4008, 512, P, 8000, P, 4008, P, 4008) == "gemm_bf16_main_kernel<8, 8, 1, 1>"
     assert qx(1, 1, 8004, 8000, 512, P, 8008, P, 512, P, 8000) == "gemm_bf16_kernel<4, 1, 0, 1, 0>"
     assert qx(0, 0, 8004, 8004, 512, P, 512, P, 8008, P, 8004) == "gemm_bf16_kernel<4, 1, 0, 0, 1>"
-    assert qx(0, 1, 8004, 8004, 512, P, 512, P, 512, P, 8004) == "gemm_bf16_main_kernel<0, 0>"
+    assert qx(0, 1, 8004, 8004, 512, P, 512, P, 512, P, 8004) == "gemm_bf16_main_kernel<6, 6, 0, 0>"
     assert qx(1, 0, 100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1, 1, 1>"
     assert qx(1, 0, 100, 90, 80, P, 99, P, 90, P, 90) is None                                 # lda < M for a transposed A
 
@@ -190,7 +196,7 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
 
 def test_forced_configurations_and_plan_queries():
     bad, ok = lib.FSRGEMM_ERR_INVALID_ARG, lib.FSRGEMM_OK
-    assert lib.fsrgemm_tile_count_f32() == 14 and lib.fsrgemm_tile_count_bf16() == 5
+    assert lib.fsrgemm_tile_count_f32() == 14 and lib.fsrgemm_tile_count_bf16() == 10
     f = lambda tile, s, ws=None, wsb=0, M=64, N=64, K=4096: lib.gemm_f32_cfg(tile, s, 0, 0, M, N, K, P, K, P, N, P, N, ws, wsb, 0)
     assert f(-1, 1) == bad and f(14, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
     assert f(3, 1) == bad and f(3, 1, K=0, M=1) == bad                          # the vector kernels need M or N = 1 and K > 0
@@ -203,7 +209,7 @@ def test_forced_configurations_and_plan_queries():
     assert lib.gemm_f32_cfg(1, 1, 0, 0, 8, 8, 8, P, 7, P, 8, P, 8, None, 0, 0) == bad                # the usual argument checks
     g = lambda tile, s, M, N, K, a=P, lda=None, ws=None, wsb=0: lib.gemm_bf16_cfg(tile, s, 0, 1, M, N, K, a, lda or K, P, K, P, N, ws, wsb, 0)
     # the direct-to-LDS candidate is rejected where its kernel's conditions fail, never replaced
-    assert g(0, 1, 255, 512, 512) == bad and g(0, 1, 512, 512, 96) == bad and g(0, 1, 512, 512, 512, a=P + 2) == bad
+    assert g(0, 1, 255, 512, 512) == bad and g(0, 1, 512, 512, 100) == bad and g(0, 1, 512, 512, 56) == bad and g(0, 1, 512, 512, 512, a=P + 2) == bad
     assert g(0, 1, 512, 512, 512, lda=516) == bad and g(0, 2, 512, 512, 512, ws=P, wsb=1 << 24) == bad
     assert g(4, 1, 512, 512, 512) == bad and g(5, 1, 1, 512, 512) == bad and g(1, 1, 0, 512, 512) == ok     # candidate 4: vector shapes only
     # names of forced candidates; None where the forced call would reject the candidate
@@ -211,7 +217,7 @@ def test_forced_configurations_and_plan_queries():
     assert qc(0, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) == "gemm_f32_kernel<4, 2, 2, 2, 0, 1>"        # the largest tile on a tiny unaligned problem
     assert qc(3, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) is None and qc(14, 0, 0, 1, 10, 10, P, 10, P, 10, P, 10) is None
     assert qc(3, 0, 0, 1, 16, 16, P, 16, P, 16, P, 16) == "gemv_cols_f32_kernel<true>"
-    assert qh(0, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) == "gemm_bf16_main_kernel<0, 0>"
+    assert qh(0, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) == "gemm_bf16_main_kernel<8, 8, 0, 0>"
     assert qh(0, 0, 1, 520, 392, 100, P, 104, P, 104, P, 392) is None and qh(4, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) is None
     assert qh(1, 1, 0, 8, 8, 8, P, 8, P, 8, P, 8) == "gemm_bf16_kernel<4, 1, 1, 1, 1>"
     # candidate 4: small results of long sums; its slices are workgroups, each with a partial result in the workspace
@@ -261,7 +267,10 @@ def test_forced_configurations_and_plan_queries():
     assert pf(0, 0, 64, 64, 1 << 20, P, 1 << 20, P, 64, True)[0] == 2 and pf(0, 0, 64, 64, 1 << 20, P, 1 << 20, P, 64, True)[1] > 1
     assert pf(0, 0, 64, 64, 1 << 20, P, 1 << 20, P, 64, False) == (2, 1)
     assert pb(0, 1, 8192, 8192, 8192, P, 8192, P, 8192) == (0, 1)
-    assert pb(0, 1, 8192, 8192, 8200, P, 8200, P, 8200) == (1, 1)              # ragged K: the general kernel of that tile
+    assert pb(0, 1, 8192, 8192, 8200, P, 8200, P, 8200) == (0, 1)              # a rest of K in whole 16-byte pieces: still the direct-to-LDS kernel
+    assert pb(0, 1, 8192, 8192, 8196, P, 8200, P, 8200) == (1, 1)              # otherwise the general kernel of that tile
+    assert pb(0, 1, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1) and pb(0, 0, 6144, 6144, 6144, P, 6144, P, 6144) == (5, 1)   # 256 x 192; with B along n, 192 x 256
+    assert pb(0, 1, 4096, 4096, 4096, P, 4096, P, 4096, False, True) == (0, 1) and pb(0, 1, 4096, 4096, 4096, P, 4096, P, 4096) == (6, 1)   # the rules; a row of the selection table
     assert pb(0, 1, 300, 300, 300, P, 300, P, 300) == (3, 1)
     assert pf(0, 0, -1, 1, 1, P, 1, P, 1) is None
     # a vector on one side: the streaming kernels (candidate 3), split along K only where the output alone gives few workgroups

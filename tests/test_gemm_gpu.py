@@ -5,6 +5,7 @@ e <= 1e-5 for fp32, e <= 1e-2 for bf16 inputs; bit-exact on small-integer
 operands, where every summation order is exact.
 """
 import math
+import re
 import sys
 
 import numpy as np
@@ -257,14 +258,14 @@ def test_bf16_main_kernel_storage_orders(gpu, shape, ta, tb):
     M, N, K = shape
     say("bf16 main kernel storage %d%d %dx%dx%d" % (ta, tb, M, N, K))
     lda, ldb = (M if ta else K), (K if tb else N)
-    name = "gemm_bf16_main_kernel<%d, %d>" % (ta, 1 - tb)
-    assert gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name
+    is_main = lambda name: re.fullmatch(r"gemm_bf16_main_kernel<[468], [468], %d, %d>" % (ta, 1 - tb), name) is not None     # in whatever tile shape
+    assert is_main(gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N))
     A = inputs.bf16_normal_scaled(4, 70, M, K, 1 / math.sqrt(K))
     B = inputs.bf16_normal_scaled(4, 71, K, N, 1 / math.sqrt(K))
     ref, S = oracle.gemm(A, B)
     got = run_bf16_ex(gpu, ta, tb, A, B, repeat=2)
     assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
-    assert gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, 0x1000, lda + 8, 0x1000, ldb + 40, 0x1000, N + 3) == name
+    assert is_main(gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, 0x1000, lda + 8, 0x1000, ldb + 40, 0x1000, N + 3))
     got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda + 8, ldb=ldb + 40, ldc=N + 3, repeat=2)
     assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
     Ai, Bi = inputs.bf16_small_ints(4, 72, M, K), inputs.bf16_small_ints(4, 73, K, N)
@@ -295,13 +296,17 @@ def test_bf16_big_tile_config_ragged(gpu):
     say("bf16 %dx%dx%d (256-tile, ragged)" % (M, N, K))
     A = inputs.bf16_normal_scaled(4, 40, M, K, 1 / math.sqrt(K))
     Bt = inputs.bf16_normal_scaled(4, 41, N, K, 1 / math.sqrt(K))
-    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N).startswith("gemm_bf16_main_kernel<")    # with a rest of K
     check_bf16(gpu, A, Bt)
+    A2, Bt2 = inputs.bf16_normal_scaled(4, 42, M, K + 4, 1 / math.sqrt(K)), inputs.bf16_normal_scaled(4, 43, N, K + 4, 1 / math.sqrt(K))
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K + 4, 0x1000, K + 8, 0x1000, K + 8, 0x1000, N) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"    # K not whole 16-byte pieces
+    check_bf16(gpu, A2, Bt2, lda=K + 8, ldb=K + 8)
 
 
-@pytest.mark.parametrize("shape,kernel", [((4000, 2100, 256), "gemm_bf16_main_kernel<0, 0>"),           # 16 x 9 tiles of 256, both ragged
-                                          ((2304, 4090, 64), "gemm_bf16_main_kernel<0, 0>"),            # one K-tile, ragged N
-                                          ((257, 33000, 128), "gemm_bf16_main_kernel<0, 0>"),           # second tile row overlaps all but one row
+@pytest.mark.parametrize("shape,kernel", [((4000, 2100, 256), "gemm_bf16_main_kernel<"),           # the direct-to-LDS kernel in whatever shape, both sides ragged
+                                          ((2304, 4090, 64), "gemm_bf16_main_kernel<"),            # one K-tile, ragged N
+                                          ((257, 33000, 128), "gemm_bf16_main_kernel<"),           # the last tile row overlaps all but one row
+                                          ((8200, 8400, 128), "gemm_bf16_main_kernel<"),           # more than 1024 tiles, both ragged
                                           ((2000, 2100, 128), "gemm_bf16_kernel<2, 2, 0, 0, 0>"),  # 128 x 128 tiles, unchecked
                                           ((300, 520, 64), "gemm_bf16_kernel<1, 4, 0, 0, 0>")])    # 64 x 64 tiles, unchecked
 def test_bf16_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
@@ -309,7 +314,7 @@ def test_bf16_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
     # column start early enough to end with the matrix
     M, N, K = shape
     say("bf16 %dx%dx%d (shifted last tiles)" % shape)
-    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == kernel
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N).startswith(kernel)
     A = inputs.bf16_normal_scaled(4, 60, M, K, 1 / math.sqrt(K))
     Bt = inputs.bf16_normal_scaled(4, 61, N, K, 1 / math.sqrt(K))
     check_bf16(gpu, A, Bt, repeat=2)
@@ -419,17 +424,71 @@ def test_f32_main_kernel_is_the_dispatchers_choice(gpu):
             assert np.array_equal(run_cfg(gpu, "f32", 5, 1, 0, 0, A, B).view(np.uint32), got.view(np.uint32))
 
 
+BF16_MAIN_SHAPES = {0: (256, 256), 5: (192, 256), 6: (128, 256), 7: (256, 192), 8: (192, 192), 9: (256, 128)}      # candidate -> tile
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 1)] + BF16_STORAGE)
+@pytest.mark.parametrize("shape", [(512, 768, 64), (512, 512, 128), (768, 512, 192), (256, 256, 448),     # whole tiles, 1 / 2 / 3 / 7 K-tiles
+                                   (520, 392, 128), (264, 1288, 64), (1000, 264, 192),                    # shifted last tiles
+                                   (512, 512, 72), (520, 392, 232), (384, 392, 120), (256, 512, 104)])    # a rest of K behind 1 / 3 / 1 / 1 K-tiles
+def test_bf16_main_kernel_every_shape(gpu, shape, ta, tb):
+    # the direct-to-LDS bf16 kernel in its six tile shapes, forced: prologue, odd / even tails, the clamped loads two
+    # K-tiles ahead, the rest of K (one and two k-steps of it), operands contiguous along k and (side 256 only) along
+    # m / n, padded leading dimensions, small integers
+    M, N, K = shape
+    lda, ldb = (M if ta else K), (K if tb else N)
+    A = inputs.bf16_normal_scaled(4, 80, M, K, 1 / math.sqrt(K))
+    B = inputs.bf16_normal_scaled(4, 81, K, N, 1 / math.sqrt(K))
+    ref, S = oracle.gemm(A, B)
+    Ai, Bi = inputs.bf16_small_ints(4, 82, M, K), inputs.bf16_small_ints(4, 83, K, N)
+    refi, _ = oracle.gemm(Ai, Bi)
+    for tile, (bm, bn) in BF16_MAIN_SHAPES.items():
+        say("bf16 main kernel %dx%d storage %d%d %dx%dx%d" % (bm, bn, ta, tb, M, N, K))
+        fits = M >= bm and N >= bn and (not ta or bm == 256) and (tb or bn == 256)     # an operand along m / n keeps its side at 256
+        name = "gemm_bf16_main_kernel<%d, %d, %d, %d>" % (bm // 32, bn // 32, ta, 1 - tb) if fits else None
+        assert gpu.fsrgemm_kernel_for_bf16_cfg(tile, ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name
+        if not fits:
+            with pytest.raises(gpu.FsrGemmError):
+                run_cfg(gpu, "bf16", tile, 1, ta, tb, A, B)
+            continue
+        got = run_cfg(gpu, "bf16", tile, 1, ta, tb, A, B, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+        assert gpu.fsrgemm_kernel_for_bf16_cfg(tile, ta, tb, M, N, K, 0x1000, lda + 8, 0x1000, ldb + 40, 0x1000, N + 3) == name
+        got = run_cfg(gpu, "bf16", tile, 1, ta, tb, A, B, lda=lda + 8, ldb=ldb + 40, ldc=N + 3, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+        assert np.array_equal(run_cfg(gpu, "bf16", tile, 1, ta, tb, Ai, Bi).astype(np.float64), refi)
+        # where the candidate does not fit it is rejected: a split, a misaligned base, rows that are not whole pieces
+        for kw, slices in ((dict(), 2), (dict(offset=1), 1), (dict(lda=lda + 4), 1)):
+            with pytest.raises(gpu.FsrGemmError):
+                run_cfg(gpu, "bf16", tile, slices, ta, tb, A, B, **kw)
+
+
+def test_bf16_rest_of_k_at_full_width(gpu):
+    # 8192 x 8192 with K = 1032 = 16 K-tiles and one piece: every tile of the headline grid runs the rest-of-K step
+    M = N = 8192
+    K = 1032
+    say("bf16 %dx%dx%d (rest of K)" % (M, N, K))
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_main_kernel<8, 8, 0, 0>"
+    A = inputs.bf16_normal_scaled(4, 84, M, K, 1 / math.sqrt(K))
+    Bt = inputs.bf16_normal_scaled(4, 85, N, K, 1 / math.sqrt(K))
+    got = run_bf16(gpu, A, Bt, repeat=2)
+    ii, jj = one_entry_per_block(M, N, 16, 84)
+    c, s = oracle.gemm_entries(A, Bt.T, ii, jj)
+    assert oracle.componentwise_error(got[ii, jj], c, s) <= TOL_BF16
+    assert oracle.freivalds_residual(A, Bt.T, got) <= freivalds_gate(N, K)
+
+
 @pytest.mark.parametrize("K", [64, 128, 192, 448])
 def test_bf16_main_kernel_small_k(gpu, K):
-    # the scheduled 256x256 kernel with 1, 2, 3 and 7 K-tiles: prologue, odd/even tails, clamped prefetch
-    M, N = 2048, 4096
+    # the direct-to-LDS kernel through the dispatcher with 1, 2, 3 and 7 K-tiles: prologue, odd/even tails, clamped prefetch
+    M, N = 4096, 4096
     say("bf16 main kernel %dx%dx%d" % (M, N, K))
-    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == "gemm_bf16_main_kernel<0, 0>"
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N).startswith("gemm_bf16_main_kernel<")
     A = inputs.bf16_normal_scaled(4, 50 + K, M, K, 1 / math.sqrt(K))
     Bt = inputs.bf16_normal_scaled(4, 51 + K, N, K, 1 / math.sqrt(K))
     check_bf16(gpu, A, Bt, repeat=2)
     if K == 192:                                            # padded leading dimensions stay on the same kernel
-        assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K + 8, 0x1000, K + 72, 0x1000, N + 3) == "gemm_bf16_main_kernel<0, 0>"
+        assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K + 8, 0x1000, K + 72, 0x1000, N + 3).startswith("gemm_bf16_main_kernel<")
         check_bf16(gpu, A, Bt, lda=K + 8, ldb=K + 72, ldc=N + 3)
         Ai, Bi = inputs.bf16_small_ints(4, 60, M, K), inputs.bf16_small_ints(4, 61, N, K)
         got = run_bf16(gpu, Ai, Bi)
@@ -530,7 +589,7 @@ def test_bf16_8192_full_size(gpu):
     n = 8192
     A = inputs.bf16_normal_scaled(4, 1, n, n, 1 / math.sqrt(n))
     Bt = inputs.bf16_normal_scaled(4, 2, n, n, 1 / math.sqrt(n))
-    assert gpu.fsrgemm_kernel_for_bf16(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_bf16_main_kernel<0, 0>"
+    assert gpu.fsrgemm_kernel_for_bf16(n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == "gemm_bf16_main_kernel<8, 8, 0, 0>"
     got = run_bf16(gpu, A, Bt)
     say("  GPU done; oracle on samples")
     rng = np.random.default_rng(4)
@@ -944,7 +1003,7 @@ def test_bf16_every_candidate(gpu, shape, ta, tb):
     A, Bt = inputs.bf16_normal_scaled(12, 3, M, K, 1 / math.sqrt(K)), inputs.bf16_normal_scaled(12, 4, N, K, 1 / math.sqrt(K))
     B = np.ascontiguousarray(Bt.T)
     ref, S = oracle.gemm(A, B)
-    fits_main = M >= 256 and N >= 256 and K % 64 == 0 and (not ta or M % 8 == 0) and (tb or N % 8 == 0)
+    fits_main = M >= 256 and N >= 256 and K >= 64 and K % 8 == 0 and (not ta or M % 8 == 0) and (tb or N % 8 == 0)
     for tile in range(4):
         for slices in (1, 2, 5, 16, 64):
             say("bf16 candidate tile %d slices %d on %dx%dx%d %d%d" % (tile, slices, M, N, K, ta, tb))
