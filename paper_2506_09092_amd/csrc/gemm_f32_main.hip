@@ -78,7 +78,6 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     constexpr int kBytesA = BM * kBK * 4, kBytesB = BN * kBK * 4, kStageBytes = kBytesA + kBytesB;
     constexpr int kLoadsA = 2 * WM, kLoadsB = 2 * WN, kLoads = kLoadsA + kLoadsB;     // 1 KB each, per wavefront and K-tile
     constexpr int kMfmas = 4 * WM * WN;                                               // per chunk of 8 k
-    constexpr bool kTakesRestOfK = WM * WN < 16;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     int tile_m, tile_n;
     tile_coords(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -248,18 +247,22 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     // The rest of K when K is not whole K-tiles (it is a multiple of 4, so a piece lies inside K or beyond it): one
     // more K-tile whose pieces beyond K come from a zero piece.  It runs outside the pipeline, once per tile of C: its
     // loads (one address per lane, through the compiler's builtin) are waited for, then its chunks run with their
-    // fragment reads in front of them.  Not for the 256 x 256 tile, which has no registers to spare for it: that
-    // shape is only launched on whole K-tiles.
-    const int k_rest = kTakesRestOfK ? g.K - nk * kBK : 0;
+    // fragment reads in front of them.  Nothing of it may be kept in registers across the loop (the 256 x 256 tile has
+    // none to spare): the lane's number is read again from the hardware here and in the epilogue.
+    const int k_rest = g.K - nk * kBK;
     if (k_rest > 0) {
+        // (the lane's number is taken afresh from the hardware: nothing of this step is to be worked out, and kept in
+        // registers, ahead of the loop)
+        int ln = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        asm volatile("" : "+v"(ln));
         auto tail_src = [&](auto layout, auto extent, const float *__restrict__ P, int64_t ld, int origin, int q) -> const float * {
             constexpr int LAY = decltype(layout)::value, EXT = decltype(extent)::value;
             if constexpr (LAY == kKContig) {
-                const int piece = (lane & 7) ^ ((4 * (q & 1) + (lane >> 4)) & 7);
-                const int row = origin + wave * (EXT / 4) + 8 * q + (lane >> 3);
+                const int piece = (ln & 7) ^ ((4 * (q & 1) + (ln >> 4)) & 7);
+                const int row = origin + wave * (EXT / 4) + 8 * q + (ln >> 3);
                 return 4 * piece < k_rest ? P + (int64_t)row * ld + nk * kBK + 4 * piece : kZeroPiece;
             } else {
-                const int pos = (1024 * q) % (4 * EXT) + 16 * lane;
+                const int pos = (1024 * q) % (4 * EXT) + 16 * ln;
                 const int k_row = (wave * (EXT / 32) + q) * 256 / EXT + pos / (4 * EXT);
                 return k_row < k_rest ? P + (int64_t)(nk * kBK + k_row) * ld + origin + (pos % (4 * EXT)) / 4 : kZeroPiece;
             }
@@ -298,14 +301,18 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     // Every global->LDS load has landed before the workgroup gives up its LDS, and the last MFMAs (64 cycles each,
     // unknown to the compiler as such) have written their accumulators before these are read.
     asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    // (the lane's number is taken afresh from the hardware, so that no store address is kept in a register across the loop)
+    int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    asm volatile("" : "+v"(lane_e));
+    const int li_e = lane_e & 31, lh_e = lane_e >> 5;
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
-            const int col = n0 + wn0 + j * 32 + li;
+            const int col = n0 + wn0 + j * 32 + li_e;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
+                const int row = m0 + wm0 + i * 32 + (r / 4) * 8 + lh_e * 4 + (r % 4);
                 g.C[(int64_t)row * g.ldc + col] = acc[i][j][r];
             }
             FENCE();
@@ -359,7 +366,7 @@ const char *f32_main_kernel_name(int shape, int a_lay, int b_lay)
 }
 
 // Whole unchecked tiles of 16-byte pieces: a matrix at least one tile high and wide (a ragged last tile is shifted
-// back into it), at least one K-tile of 32 and K a multiple of 4 (of 32 for the 256 x 256 tile), 16-byte aligned bases and rows,
+// back into it), at least one K-tile of 32 and K a multiple of 4, 16-byte aligned bases and rows,
 // for an operand that is contiguous along
 // m (n) M (N) a multiple of 4 so that a shifted tile still starts on a piece; leading dimensions below 2^24 elements,
 // because a lane's offset from its load's uniform base (up to 7 rows and 28 elements along k, up to 2 k-rows along
@@ -369,7 +376,7 @@ bool f32_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_
     if (shape < 0 || shape >= kF32MainShapes) return false;
     const int bm = kShapeM[shape], bn = kShapeN[shape];
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) == 0 && lda % 4 == 0 && ldb % 4 == 0;
-    return aligned && lda < kF32MaxLdUnchecked && ldb < kF32MaxLdUnchecked && M >= bm && N >= bn && K >= kBK && K % (bm * bn == 256 * 256 ? kBK : 4) == 0 && (a_lay == kKContig || M % 4 == 0) &&
+    return aligned && lda < kF32MaxLdUnchecked && ldb < kF32MaxLdUnchecked && M >= bm && N >= bn && K >= kBK && K % 4 == 0 && (a_lay == kKContig || M % 4 == 0) &&
            (b_lay == kKContig || N % 4 == 0) && ((M + bm - 1) / bm) * ((N + bn - 1) / bn) < ((int64_t)1 << 31);
 }
 

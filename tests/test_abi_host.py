@@ -67,9 +67,9 @@ def test_dispatch_query_names_variants():
     # <TM, TN, min waves, load mode, A layout, B layout>: tile (64 TM) x (64 TN); mode 0 unchecked vectors,
     # 1 vectors + predicated edges, 2 scalar; row-major A is contiguous along k (0), row-major B along n (1)
     # the direct-to-LDS kernel <blocks per wavefront, A layout, B layout> where it fits, in the shape that fills whole
-    # rounds; its 256 x 256 tile takes whole K-tiles of 32 only, and no shape takes a K below 32
+    # rounds; a rest of K in whole 16-byte pieces stays (one more K-tile with zero pieces), and no shape takes a K below 32
     assert fast == "gemm_f32_main_kernel<4, 4, 0, 1>"
-    assert q(4096, 4096, 4112, P, 4112, P, 4096, P, 4096) == "gemm_f32_main_kernel<2, 4, 0, 1>"
+    assert q(4096, 4096, 4112, P, 4112, P, 4096, P, 4096) == "gemm_f32_main_kernel<4, 4, 0, 1>"
     assert q(4096, 4096, 16, P, 16, P, 4096, P, 4096) == "gemm_f32_kernel<4, 2, 2, 0, 0, 1>"
     assert ragged == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>" and unaligned == "gemm_f32_kernel<1, 1, 4, 2, 0, 1>"
     assert q(4090, 4090, 129, P, 132, P, 4092, P, 4090) == "gemm_f32_kernel<4, 2, 2, 1, 0, 1>"
@@ -98,7 +98,7 @@ def test_dispatch_query_names_variants():
     assert qb(8000, 8000, 8004, P, 8008, P, 8008, P, 8000) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"
     assert qb(255, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemm_bf16_kernel<1, 4, 0, 0, 0>"          # 4 x 128 tiles of 64
     assert q(4000, 4000, 4000, P, 4000, P, 4000, P, 4000) == "gemm_f32_main_kernel<4, 4, 0, 1>"
-    assert q(4000, 4000, 4008, P, 4008, P, 4000, P, 4000) == "gemm_f32_main_kernel<2, 4, 0, 1>"          # a rest of K: not the 256 x 256 tile
+    assert q(4000, 4000, 4008, P, 4008, P, 4000, P, 4000) == "gemm_f32_main_kernel<4, 4, 0, 1>"          # a rest of K
     assert q(4000, 4000, 4010, P, 4012, P, 4000, P, 4000) == "gemm_f32_kernel<4, 2, 2, 1, 0, 1>"          # K not a multiple of 4
     assert q(63, 4000, 4000, P, 4000, P, 4000, P, 4000) == "gemm_f32_kernel<1, 1, 4, 1, 0, 1>"            # narrower than a tile
     # other storage orders: <.., A layout, B layout> with 0 = contiguous along k, 1 = along m / n
@@ -176,7 +176,7 @@ def test_f32_tile_rule_follows_the_round_model():
     # (aligned operands, whole K-tiles of 32) with the shape whose tiles fill whole rounds
     pf = lambda n, a=P, K=None: lib.fsrgemm_plan_f32(0, 0, n, n, K or n, a, K or n, P, n)[0]
     assert [pf(n) for n in (1024, 2048, 3072, 4096, 6144, 8192)] == [2, 10, 12, 5, 9, 5]
-    assert [pf(n, P + 4) for n in (4096, 8192)] == [0, 0] and pf(4096, K=4112) == 7      # misaligned A: the general kernel; a rest of K: not the 256 x 256 tile
+    assert [pf(n, P + 4) for n in (4096, 8192)] == [0, 0] and pf(4096, K=4112) == 5      # misaligned A: the general kernel; a rest of K: the same tile
     assert lib.fsrgemm_plan_f32(0, 0, 4096, 4096, 4110, P, 4112, P, 4096)[0] == 0 and pf(4096, K=16) == 0     # K not a multiple of 4, K below a K-tile
     assert lib.fsrgemm_plan_f32(0, 0, 10, 100000, 64, P, 64, P, 100000)[0] == 2          # a sliver: small tiles waste least
     assert lib.fsrgemm_plan_f32(0, 0, 262144, 2048, 4096, P, 4096, P, 2048)[0] == 5        # the paper's largest Task-2 size
@@ -248,7 +248,7 @@ def test_forced_configurations_and_plan_queries():
     # rejected where its conditions fail, never replaced, never split
     mk = lambda M, N, K, ta=0, tb=0, a=P, lda=None, s=1, ws=None, wsb=0: lib.gemm_f32_cfg(
         5, s, ta, tb, M, N, K, a, lda or (M if ta else K), P, K if tb else N, P, N, ws, wsb, 0)
-    assert mk(255, 512, 512) == bad and mk(512, 255, 512) == bad and mk(512, 512, 48) == bad and mk(512, 512, 0) == bad
+    assert mk(255, 512, 512) == bad and mk(512, 255, 512) == bad and mk(512, 512, 50) == bad and mk(512, 512, 28) == bad and mk(512, 512, 0) == bad
     assert mk(512, 512, 512, a=P + 4) == bad and mk(512, 512, 512, lda=514) == bad and mk(512, 512, 512, s=2, ws=P, wsb=1 << 24) == bad
     assert mk(510, 512, 512, ta=1) == bad and mk(512, 510, 512) == bad            # a shifted last tile would start off a 16-byte piece
     assert mk(0, 512, 512) == ok and mk(512, 512, 512, ws=None, wsb=8) == bad
@@ -259,7 +259,7 @@ def test_forced_configurations_and_plan_queries():
     assert qc(12, 0, 0, 192, 192, 64, P, 64, P, 192, P, 192) == "gemm_f32_main_kernel<3, 3, 0, 1>" and qc(13, 0, 0, 128, 191, 64, P, 64, P, 192, P, 191) is None
     assert qc(10, 1, 0, 128, 128, 32, P, 128, P, 128, P, 128) == "gemm_f32_main_kernel<2, 2, 1, 1>" and qc(10, 0, 0, 128, 127, 32, P, 32, P, 128, P, 127) is None
     assert qc(9, 0, 1, 200, 130, 96, P, 96, P, 96, P, 130) == "gemm_f32_main_kernel<3, 2, 0, 0>"
-    assert qc(5, 0, 0, 512, 512, 48, P, 48, P, 512, P, 512) is None
+    assert qc(5, 0, 0, 512, 512, 48, P, 48, P, 512, P, 512) == "gemm_f32_main_kernel<4, 4, 0, 1>" and qc(5, 0, 0, 512, 512, 28, P, 28, P, 512, P, 512) is None
     assert lib.fsrgemm_kernel_for_f32(4096, 4096, 4096, P, 4096, P, 4096, P, 4096) == "gemm_f32_main_kernel<4, 4, 0, 1>"
     # plan queries: the rules, in the terms of the forced calls
     pf, pb = lib.fsrgemm_plan_f32, lib.fsrgemm_plan_bf16

@@ -386,7 +386,7 @@ def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
     refi, _ = oracle.gemm(Ai, Bi)
     for tile, (bm, bn) in MAIN_SHAPES.items():
         say("f32 main kernel %dx%d storage %d%d %dx%dx%d" % (bm, bn, ta, tb, M, N, K))
-        fits = M >= bm and N >= bn and K % (32 if tile == 5 else 4) == 0      # the 256 x 256 tile takes whole K-tiles only
+        fits = M >= bm and N >= bn and K % 4 == 0
         name = "gemm_f32_main_kernel<%d, %d, %d, %d>" % (bm // 64, bn // 64, ta, 1 - tb) if fits else None
         assert gpu.fsrgemm_kernel_for_f32_cfg(tile, ta, tb, M, N, K, 0x1000, lda, 0x1000, ldb, 0x1000, N) == name
         if not fits:
@@ -407,10 +407,10 @@ def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
 
 def test_f32_main_kernel_is_the_dispatchers_choice(gpu):
     # 16 x 16 tiles of 256 fill the compute units exactly once: the dispatcher takes the direct-to-LDS kernel, and
-    # forcing it gives the same bits; a K that is not whole tiles of 32 takes another shape of it (the 256 x 256 one
-    # has no rest-of-K step), and a K below 32 the general kernel
+    # forcing it gives the same bits; a K that is not whole tiles of 32 stays on it (the rest-of-K step), and a K below 32
+    # takes the general kernel
     M = N = 4096
-    for K, kernel in ((64, "gemm_f32_main_kernel<4, 4, 0, 1>"), (48, "gemm_f32_main_kernel<2, 4, 0, 1>"), (16, "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")):
+    for K, kernel in ((64, "gemm_f32_main_kernel<4, 4, 0, 1>"), (48, "gemm_f32_main_kernel<4, 4, 0, 1>"), (16, "gemm_f32_kernel<4, 2, 2, 0, 0, 1>")):
         say("f32 4096x4096x%d through the dispatcher" % K)
         assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == kernel
         A, B = inputs.uniform_pm1(19, 3, M, K), inputs.uniform_pm1(19, 4, K, N)
