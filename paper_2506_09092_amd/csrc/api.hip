@@ -242,7 +242,8 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
 // written out), and -- unlike fp32 -- a last round that fills only part of the 256 compute units is shorter than a
 // full one, down to three quarters: this kernel runs against the power limit, and with compute units idle the others
 // clock higher.  b and a per shape are a least-squares fit to launches of every shape forced on 18 problems (4096^3 ...
-// 10240^2 x 4096, 16384 x 4096 x 4096); the fit picks the measured winner or a shape within 3 % of it on all of them.
+// 10240^2 x 4096, 16384 x 4096 x 4096); on a second sweep of 22 problems the rule's choice was the measured winner or
+// within 2 % of it on 20 (the others: 5 % on 7168^2 x 2048, 1.6 us on 4096^2 x 128).
 // Returns the shape, or -1 when none fits the problem (fits: bit s set if shape s can take it).
 constexpr int64_t kBf16MainPerKTile[kBf16MainShapes] = {1333, 1073, 780, 1037, 907, 808};      // in the order of the shapes
 constexpr int64_t kBf16MainPerRound[kBf16MainShapes] = {8700, 5800, 4700, 7700, 3700, 5200};

@@ -19,12 +19,24 @@ Candidate = collections.namedtuple("Candidate", "tile slices")
 MAX_SLICES = 64
 
 
-def neighbours(c: Candidate, tile_count: int, max_slices: int = MAX_SLICES):
+# Candidate numbers are handed out in the order the kernels were written, not by likeness: for bf16 the 256 x 256 tile of
+# the direct-to-LDS kernel is candidate 0, its other shapes 5 .. 9, the general tiles 1 .. 3, the vector kernels 4.
+# "One tile size up or down" walks this chain instead (general 256 x 256, then the direct-to-LDS shapes by falling area,
+# then the smaller general tiles, then the vector kernels).
+TILE_CHAIN = {"bf16": (1, 0, 5, 7, 8, 6, 9, 2, 3, 4)}
+
+
+def neighbours(c: Candidate, tile_count: int, max_slices: int = MAX_SLICES, chain=None):
     """The refinement step: one tile size up or down with the same slices, half or twice the slices with the same
     tile (max_slices = 1: the search for callers without a workspace).  Nearest first; the order is part of the
-    result's determinism."""
+    result's determinism.  chain: the candidate numbers in order of likeness (default: their own order)."""
     out = []
-    for t in (c.tile + 1, c.tile - 1):
+    if chain is not None and c.tile in chain:
+        at = chain.index(c.tile)
+        near = [chain[i] for i in (at + 1, at - 1) if 0 <= i < len(chain)]
+    else:
+        near = [c.tile + 1, c.tile - 1]
+    for t in near:
         if 0 <= t < tile_count:
             out.append(Candidate(t, c.slices))
     if c.slices * 2 <= max_slices:
@@ -35,7 +47,7 @@ def neighbours(c: Candidate, tile_count: int, max_slices: int = MAX_SLICES):
 
 
 def search(start: Candidate, tile_count: int, runs, validates, latency, rounds: int = 3, per_round: int = 4,
-           max_slices: int = MAX_SLICES, log=None):
+           max_slices: int = MAX_SLICES, log=None, chain=None):
     """Algorithm 1 over configurations.
 
     start            the dispatcher's current choice: round 0 proposes it and its neighbours
@@ -52,7 +64,7 @@ def search(start: Candidate, tile_count: int, runs, validates, latency, rounds: 
     left to propose, which a finite configuration space, unlike a language model, runs into.
     """
     visited, history = {}, []
-    queue = [start] + neighbours(start, tile_count, max_slices)
+    queue = [start] + neighbours(start, tile_count, max_slices, chain)
     best, best_t, d = None, float("inf"), 0
     while d < rounds:
         batch = []
@@ -71,7 +83,7 @@ def search(start: Candidate, tile_count: int, runs, validates, latency, rounds: 
         if not valid:
             history.append(dict(candidates=batch, valid=[], winner=None, latency=None))
             for c in batch:                          # feedback of a failed round: look around what failed
-                queue.extend(n for n in neighbours(c, tile_count, max_slices) if n not in visited)
+                queue.extend(n for n in neighbours(c, tile_count, max_slices, chain) if n not in visited)
             if log:
                 log("round without a valid candidate: %s" % (batch,))
             continue
@@ -85,9 +97,9 @@ def search(start: Candidate, tile_count: int, runs, validates, latency, rounds: 
         d += 1
         # refine around the round's winner first, then around the incumbent, then around the round's other
         # valid candidates, fastest first
-        near = [n for c in (winner, best) for n in neighbours(c, tile_count, max_slices)]
+        near = [n for c in (winner, best) for n in neighbours(c, tile_count, max_slices, chain)]
         others = sorted((c for c in valid if c != winner), key=lambda c: (times[c], c))
-        far = [n for c in others for n in neighbours(c, tile_count, max_slices)]
+        far = [n for c in others for n in neighbours(c, tile_count, max_slices, chain)]
         queue = [n for n in near + queue + far if n not in visited]
     return dict(best=best, best_latency=best_t, rounds=history, visited=visited)
 
@@ -118,6 +130,7 @@ class DeviceBackend:
         self.offer_workspace = False
         self.fn = lib.gemm_f32_cfg if p.kind == "f32" else lib.gemm_bf16_cfg
         self.tile_count = lib.fsrgemm_tile_count_f32() if p.kind == "f32" else lib.fsrgemm_tile_count_bf16()
+        self.chain = TILE_CHAIN.get(p.kind)
         plan = lib.fsrgemm_plan_f32 if p.kind == "f32" else lib.fsrgemm_plan_bf16
         args = (p.transA, p.transB, p.M, p.N, p.K, a0, self.lda, b0, self.ldb)
         # the dispatcher's choice with / without a workspace, and what its rules alone would take

@@ -270,7 +270,7 @@ def test_forced_configurations_and_plan_queries():
     assert pb(0, 1, 8192, 8192, 8200, P, 8200, P, 8200) == (0, 1)              # a rest of K in whole 16-byte pieces: still the direct-to-LDS kernel
     assert pb(0, 1, 8192, 8192, 8196, P, 8200, P, 8200) == (1, 1)              # otherwise the general kernel of that tile
     assert pb(0, 1, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1) and pb(0, 0, 6144, 6144, 6144, P, 6144, P, 6144) == (5, 1)   # 256 x 192; with B along n, 192 x 256
-    assert pb(0, 1, 4096, 4096, 4096, P, 4096, P, 4096, False, True) == (0, 1) and pb(0, 1, 4096, 4096, 4096, P, 4096, P, 4096) == (6, 1)   # the rules; a row of the selection table
+    assert pb(0, 1, 3072, 3072, 3072, P, 3072, P, 3072, False, True) == (5, 1) and pb(0, 1, 3072, 3072, 3072, P, 3072, P, 3072) == (8, 1)   # the rules; a row of the selection table
     assert pb(0, 1, 300, 300, 300, P, 300, P, 300) == (3, 1)
     assert pf(0, 0, -1, 1, 1, P, 1, P, 1) is None
     # a vector on one side: the streaming kernels (candidate 3), split along K only where the output alone gives few workgroups

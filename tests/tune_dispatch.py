@@ -80,7 +80,7 @@ def tune(lib, torch, p: Problem, gain: float, log):
         start, rules = (be.start, be.rules) if with_ws else (be.start_unsplit, be.rules_unsplit)
         be.offer_workspace = with_ws
         r = fsr_search.search(start, be.tile_count, be.runs, lambda c: validator(be.output(c)), be.latency,
-                              rounds=3, per_round=4, max_slices=fsr_search.MAX_SLICES if with_ws else 1, log=log)
+                              rounds=3, per_round=4, max_slices=fsr_search.MAX_SLICES if with_ws else 1, log=log, chain=be.chain)
         best = r["best"]
         entry = dict(start=start, rules=rules, best=best, visited={"%d/%d" % k: v for k, v in r["visited"].items()})
         if best is not None and best != rules and be.runs(rules) and validator(be.output(rules)):
