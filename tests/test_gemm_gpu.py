@@ -616,6 +616,45 @@ def test_bf16_8192_full_size(gpu):
     assert r <= freivalds_gate(n, n)
 
 
+@pytest.mark.parametrize("shape,kernel", [((6144, 6144, 6144), "gemm_bf16_main_kernel<8, 6, 0, 0>"),       # 768 tiles of 256 x 192: three whole rounds
+                                          ((3072, 8192, 4096), "gemm_bf16_main_kernel<6, 8, 0, 0>"),       # 512 tiles of 192 x 256
+                                          ((8192, 8192, 8200), "gemm_bf16_main_kernel<8, 8, 0, 0>"),       # a rest of K, rows that straddle cache lines
+                                          ((3072, 3072, 3072), "gemm_bf16_main_kernel<6, 6, 0, 0>")])      # a row of the selection table: 192 x 192
+def test_bf16_mid_sizes_in_the_timed_configuration(gpu, shape, kernel):
+    # the problems the bench's mid_sizes_bf16 section times, in the tile shape the dispatcher takes for them: an entry in
+    # every 16 x 16 block against the oracle, and the Freivalds residual over all entries
+    M, N, K = shape
+    say("bf16 %dx%dx%d (%s)" % (M, N, K, kernel))
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N) == kernel
+    A = inputs.bf16_normal_scaled(4, 90, M, K, 1 / math.sqrt(K))
+    Bt = inputs.bf16_normal_scaled(4, 91, N, K, 1 / math.sqrt(K))
+    got = run_bf16(gpu, A, Bt)
+    ii, jj = one_entry_per_block(M, N, 16, 90)
+    c, s = oracle.gemm_entries(A, Bt.T, ii, jj)
+    e = oracle.componentwise_error(got[ii, jj], c, s)
+    r = oracle.freivalds_residual(A, Bt.T, got)
+    say("  %d entries: componentwise error %.3e; Freivalds residual %.3e (gate %.3e)" % (ii.size, e, r, freivalds_gate(N, K)))
+    assert e <= TOL_BF16 and r <= freivalds_gate(N, K)
+
+
+def test_f32_rest_of_k_on_the_largest_tile(gpu):
+    # 4096 x 4096 x 4112 (the bench's mid-size case with a K that is not whole K-tiles): the 256 x 256 tile with its
+    # rest-of-K step, every tile of the headline grid; whole rows and columns, an entry per 32 x 32 block, Freivalds
+    M = N = 4096
+    K = 4112
+    say("fp32 %dx%dx%d (rest of K on 256 x 256 tiles)" % (M, N, K))
+    assert gpu.fsrgemm_kernel_for_f32(M, N, K, 0x1000, K, 0x1000, N, 0x1000, N) == "gemm_f32_main_kernel<4, 4, 0, 1>"
+    A, B = inputs.normal(2, 5, M, K), inputs.normal(2, 6, K, N)
+    got = run_f32(gpu, A, B, repeat=2)
+    rows = np.arange(7, M, 131)
+    ref, S = oracle.gemm(A[rows], B)
+    assert oracle.componentwise_error(got[rows], ref, S) <= TOL_F32
+    ii, jj = one_entry_per_block(M, N, 32, 5)
+    c, s = oracle.gemm_entries(A, B, ii, jj)
+    assert oracle.componentwise_error(got[ii, jj], c, s) <= TOL_F32
+    assert oracle.freivalds_residual(A, B, got) <= freivalds_gate(N, K)
+
+
 def test_f32_paper_task2_largest_size(gpu):
     # the paper's largest Task 2 input (input-size table): A (2^18, 4096), B (4096, 2048).  A is 4 GiB, so element
     # offsets reach 2^30 and byte offsets 2^32: this is the 64-bit indexing case.  A is built from one seeded
