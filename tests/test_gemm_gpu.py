@@ -685,6 +685,38 @@ def test_f32_paper_task2_largest_size(gpu):
     assert oracle.componentwise_error(got_cols, ref, S) <= TOL_F32
 
 
+def test_bf16_operand_beyond_4_gib(gpu):
+    # A of 2^18 x 8192 bf16 is 4 GiB: row offsets pass 2^32 bytes inside the direct-to-LDS kernel (64-bit scalar row
+    # bases, 32-bit lane offsets).  As in the fp32 case above, A is one seeded 4096-row block repeated 64 times with
+    # a different power-of-two scale per copy (exact in bf16), so a row fetched from the wrong copy would not pass.
+    import torch
+
+    M, N, K = 1 << 18, 256, 8192
+    say("bf16 %dx%dx%d (A of 4 GiB)" % (M, N, K))
+    block = inputs.bf16_normal_scaled(5, 21, 4096, K, 1 / math.sqrt(K))
+    Bt = inputs.bf16_normal_scaled(5, 22, N, K, 1 / math.sqrt(K))
+    A = np.empty((M, K), dtype=np.uint16)
+    for b in range(64):
+        # scaling by 2^e adds e to the exponent field (bits 7..14); the block's values are far from overflow and underflow
+        A[b * 4096:(b + 1) * 4096] = block + np.uint16((((b % 5) - 2) << 7) & 0xFFFF) if (b % 5) >= 2 else block - np.uint16((2 - (b % 5)) << 7)
+    assert gpu.fsrgemm_kernel_for_bf16(M, N, K, 0x1000, K, 0x1000, K, 0x1000, N).startswith("gemm_bf16_main_kernel<")
+    a = torch.from_numpy(A.view(np.int16)).cuda()
+    b_ = torch.from_numpy(Bt.view(np.int16)).cuda()
+    c = torch.full((M, N), float("nan"), device="cuda")
+    gpu.check(gpu.gemm_bf16(M, N, K, a, K, b_, K, c, N, torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(19)
+    rows = np.unique(np.concatenate([rng.integers(0, M, 96), np.arange(0, M, 4096), np.arange(4095, M, 4096), [M - 1]]))
+    got = c[torch.from_numpy(rows).cuda()].cpu().numpy()
+    ref, S = oracle.gemm(A[rows], Bt.T)
+    assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+    cols = np.sort(rng.choice(N, 4, replace=False))
+    got_cols = c[:, torch.from_numpy(cols).cuda()].cpu().numpy()
+    assert np.all(np.isfinite(got_cols))
+    ref, S = oracle.gemm(A, np.ascontiguousarray(Bt[cols].T))
+    assert oracle.componentwise_error(got_cols, ref, S) <= TOL_BF16
+
+
 def test_f32_paper_task2_shape(gpu):
     # the paper's own Task 2 operand shapes (input-size table): A (size, 4096), B (4096, 2048); smallest size
     say("fp32 1024x2048x4096 (paper Task 2, size 2^10)")
