@@ -33,10 +33,11 @@ def test_host_dispatch_under_sanitizers(tmp_path):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     if not os.path.exists(hipcc):
         pytest.skip("no hipcc here")
-    objs = [o for o in glob.glob(os.path.join(build.CSRC, "..", "_build", "*.o")) if os.path.basename(o) != "api.o"]
-    if len(objs) != len(build.SOURCES) - 1:         # the library's other objects: built once, beside the library
+    # the library's other objects, as the build leaves them beside the library
+    objs = [os.path.join(os.path.dirname(build.CSRC), "_build", src.replace(".hip", ".o")) for src in build.SOURCES if src != "api.hip"]
+    newest_source = max(os.path.getmtime(p) for p in glob.glob(os.path.join(build.CSRC, "*")))
+    if not all(os.path.exists(o) and os.path.getmtime(o) >= newest_source for o in objs):
         build.build_library()
-        objs = [o for o in glob.glob(os.path.join(build.CSRC, "..", "_build", "*.o")) if os.path.basename(o) != "api.o"]
     host_san = [x for f in SAN for x in ("-Xarch_host", f)]          # the sanitizers instrument the host pass only
     api, drv, exe = str(tmp_path / "api_san.o"), str(tmp_path / "host_driver.o"), str(tmp_path / "host_driver")
     subprocess.check_call([hipcc, *build.HIPCC_FLAGS, "-O1", "-g", *host_san, "-c", os.path.join(build.CSRC, "api.hip"), "-o", api],
