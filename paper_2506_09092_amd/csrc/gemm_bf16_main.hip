@@ -113,10 +113,91 @@ __device__ __attribute__((aligned(16))) const uint16_t kZeroPiece[8] = {0, 0, 0,
 
 #define FSR_AS1 __attribute__((address_space(1)))
 
-template <int IM, int JN>
-struct Frag {
-    bf16x8 a[IM];
-    bf16x8 b[JN];
+// Order of the MFMAs and of the fragment reads of one K-tile.
+//
+// Every 16 x 16 block of the wavefront's part takes its two MFMAs of a K-tile (k-steps 0 and 1) directly one
+// after the other: the second then takes the first one's result as its addend without that result passing through
+// the register file, which draws measurably less power (register-only loops on random operands: 2.03 PFLOP/s with
+// a block's MFMAs 64 apart, 2.15 in pairs), and power is what bounds this kernel.  A K-tile therefore needs all
+// 2 (IM + JN) fragments of both k-steps, and each fragment register is filled again with the next K-tile's
+// fragment once its last MFMA of this K-tile has been issued.  For that to leave every read time, the walk over
+// the blocks alternates: K-tiles of stage 0 go row by row (fragment a_i is free after row i, the b_j only in the
+// last row), K-tiles of stage 1 column by column (b_j free after column j) -- the fragments that become free last
+// in one walk are those the other walk needs last.  "Slot" s = 2 p + kk is the MFMA of k-step kk on the p-th
+// block of the walk; the barrier sits after slot H - 1 (H = IM JN, half the slots), and a K-tile's fragments are
+// read between the barrier of the K-tile before and its own barrier, the only time its stage is complete and not
+// yet being overwritten.  The plan below places these reads at compile time: at every slot that may carry a read
+// (not those behind which a global load or the touch is issued, at most every second slot) the free register
+// whose fragment is needed first is filled; the static_asserts check that every read has a lead of kMinLead slots
+// on its first use and that the last reads are issued well ahead of the barrier that waits for them.
+template <int IM, int JN, int LATE, int EARLY, int LOAD_EVERY, int TOUCH_SLOT>
+struct ChainPlan {
+    static constexpr int H = IM * JN, S = 2 * H, NF = 2 * (IM + JN);
+    static constexpr int kMinLead = 6, kReadGap = 2;
+    // fragment f < NF: k-step f / (IM + JN); r = f % (IM + JN) < IM is a_r, else b_(r - IM)
+    static constexpr int kk_of(int f) { return f / (IM + JN); }
+    static constexpr bool is_a(int f) { return f % (IM + JN) < IM; }
+    static constexpr int idx_of(int f) { return is_a(f) ? f % (IM + JN) : f % (IM + JN) - IM; }
+    // walk 0: row by row, walk 1: column by column; p-th block
+    static constexpr int blk_i(int walk, int p) { return walk == 0 ? p / JN : p % IM; }
+    static constexpr int blk_j(int walk, int p) { return walk == 0 ? p % JN : p / IM; }
+    static constexpr int first_slot(int walk, int f)
+    {
+        const int x = idx_of(f), p = walk == 0 ? (is_a(f) ? x * JN : x) : (is_a(f) ? x : x * IM);
+        return 2 * p + kk_of(f);
+    }
+    static constexpr int last_slot(int walk, int f)
+    {
+        const int x = idx_of(f), p = walk == 0 ? (is_a(f) ? x * JN + JN - 1 : (IM - 1) * JN + x) : (is_a(f) ? (JN - 1) * IM + x : x * IM + IM - 1);
+        return 2 * p + kk_of(f);
+    }
+    // may a fragment read follow the MFMA of slot m of half h?  Not where a global load or the touch follows it.
+    static constexpr bool read_slot(int h, int m)
+    {
+        const int c = m / LOAD_EVERY;
+        const bool has_load = h == 1 ? c < EARLY : c < LATE;
+        if (m % LOAD_EVERY == 2 && has_load) return false;
+        if (h == 0 && m == TOUCH_SLOT + 1) return false;
+        return true;
+    }
+    struct Plan {
+        int frag[S];        // [u - H] for u in [H, H + S): the fragment read behind slot u of the timeline below, or -1
+        int min_lead, last_read;
+        bool complete;
+    };
+    // Reads that take the fragments from a K-tile walked as `from` to the next (walked the other way).  Timeline u:
+    // slots of the first K-tile are u = 0 .. S - 1, of the second S + 0 ..; reads may be issued for u in [H, H + S).
+    static constexpr Plan make(int from)
+    {
+        Plan pl{};
+        for (int u = 0; u < S; ++u) pl.frag[u] = -1;
+        bool done[NF] = {};
+        int placed = 0, last = -kReadGap;
+        pl.min_lead = S;
+        pl.last_read = 0;
+        for (int u = H; u < H + S; ++u) {
+            if (!read_slot((u / H) % 2, u % H) || u - last < kReadGap) continue;
+            int best = -1, best_need = 0;
+            for (int f = 0; f < NF; ++f) {
+                if (done[f] || last_slot(from, f) + 1 > u) continue;
+                const int need = S + first_slot(1 - from, f);
+                if (best < 0 || need < best_need) best = f, best_need = need;
+            }
+            if (best < 0) continue;
+            done[best] = true;
+            pl.frag[u - H] = best;
+            last = u;
+            ++placed;
+            if (best_need - u < pl.min_lead) pl.min_lead = best_need - u;
+            pl.last_read = u;
+        }
+        pl.complete = placed == NF;
+        return pl;
+    }
+    static constexpr Plan kPlan[2] = {make(0), make(1)};
+    static_assert(kPlan[0].complete && kPlan[1].complete, "every fragment register is filled again");
+    static_assert(kPlan[0].min_lead >= kMinLead && kPlan[1].min_lead >= kMinLead, "a read is issued kMinLead MFMAs ahead of its first use");
+    static_assert(kPlan[0].last_read + kMinLead <= H + S && kPlan[1].last_read + kMinLead <= H + S, "the last reads are issued well ahead of the barrier");
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -152,7 +233,6 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     constexpr int kMfmas = IM * JN;                                    // per k-step
     constexpr int kReads = IM + JN;                                    // fragment reads per k-step
     constexpr int kEarly = kLoads - kLate;
-    constexpr int kReadEvery = kMfmas >= 36 ? 3 : 2;                   // a fragment read behind every third (second) MFMA
     // K-tiles between a prefetch touch and the loads it serves: with 64 MFMAs per k-step 2 is too late, 4 and more
     // let touched lines be evicted before use (more fabric reads, same time); shorter K-tiles look one further ahead
     constexpr int kTouchAhead = kMfmas == 64 ? 3 : 4;
@@ -280,70 +360,69 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
             if constexpr (BMC) rb_blk[b] = kTileA + ((row_part + ((wn0 / 8) | fk | half) * 16) ^ (b << 5));
         }
     }
-    Frag<IM, JN> F[2];
+    bf16x8 Fa[2][IM], Fb[2][JN];        // [k-step][block row / column]
     auto tr_read = [&](const char *p) {
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)p);
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)(p + 2048));
         return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    // idx orders the IM + JN fragments as the next k-step consumes them: a0, b0 .. b(JN-1), a1 .. a(IM-1)
-    auto lread = [&](int stage, int kk, int fi, int idx) {
+    // fragment r of k-step kk of the K-tile in `stage` (r < IM: a_r, else b_(r - IM)) into the registers of k-step kd
+    auto lread = [&](int stage, int kk, int kd, int r) {
         const char *s = smem + stage * kStageBytes;
-        if (idx == 0 || idx > JN) {
-            const int i = idx == 0 ? 0 : idx - JN;
-            if constexpr (AMC) F[fi].a[i] = tr_read(s + ra_blk[i] + kk * 16384);
-            else F[fi].a[i] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk] + i * 2048);
+        if (r < IM) {
+            if constexpr (AMC) Fa[kd][r] = tr_read(s + ra_blk[r] + kk * 16384);
+            else Fa[kd][r] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk] + r * 2048);
         } else {
-            const int j = idx - 1;
-            if constexpr (BMC) F[fi].b[j] = tr_read(s + rb_blk[j] + kk * 16384);
-            else F[fi].b[j] = *reinterpret_cast<const bf16x8 *>(s + rb_off[kk] + j * 2048);
+            const int j = r - IM;
+            if constexpr (BMC) Fb[kd][j] = tr_read(s + rb_blk[j] + kk * 16384);
+            else Fb[kd][j] = *reinterpret_cast<const bf16x8 *>(s + rb_off[kk] + j * 2048);
         }
     };
 
     f32x4 acc[IM][JN];
 
     constexpr int kTouchSlot = kLoadEvery * kLate + 1;      // behind the late loads, so the touch is the youngest load at the barrier
-    static_assert(kLoadEvery * (kEarly - 1) + 2 < kMfmas && kReadEvery * (kReads - 1) < kMfmas && kTouchSlot + 2 < kMfmas, "slots of one k-step");
+    static_assert(kLoadEvery * (kEarly - 1) + 2 < kMfmas && kTouchSlot + 2 < kMfmas, "slots of one half");
+    using Chain = ChainPlan<IM, JN, kLate, kEarly, kLoadEvery, kTouchSlot>;
 
+    // K-tile t in stage P: its walk is P's (0 row by row, 1 column by column); half 0 is slots 0 .. kMfmas - 1
     auto k_tile = [&](auto parity, int t) {
         constexpr int P = decltype(parity)::value;
         constexpr int X = P, Y = 1 - P;
-        static_for<2>([&](auto kkc) {
-            constexpr int kk = decltype(kkc)::value;
+        static_for<2>([&](auto hc) {
+            constexpr int h = decltype(hc)::value;
             static_for<kMfmas>([&](auto mc) {
                 constexpr int m = decltype(mc)::value;
-                constexpr int i = m / JN, j = m % JN;
+                constexpr int slot = h * kMfmas + m, blk = slot / 2, kk = slot % 2;
+                constexpr int i = Chain::blk_i(P, blk), j = Chain::blk_j(P, blk);
                 constexpr int c = m / kLoadEvery;               // load of this group of slots
-                constexpr bool has_load = kk == 1 ? c < kEarly : c < kLate;
+                constexpr bool has_load = h == 1 ? c < kEarly : c < kLate;
                 if constexpr (m % kLoadEvery == 1 && has_load) {
-                    if constexpr (kk == 1) load_m0(Int<X>{}, Int<c>{});
+                    if constexpr (h == 1) load_m0(Int<X>{}, Int<c>{});
                     else load_m0(Int<Y>{}, Int<kEarly + c>{});
                 }
-                if constexpr (kk == 0 && m == kTouchSlot) touch_m0();
-                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(F[kk].a[i]), "v"(F[kk].b[j]));
-                if constexpr (m % kReadEvery == 0 && m / kReadEvery < kReads) {
-                    // fragments of the next k-step (the next K-tile's first, from Y, once the barrier is passed)
-                    if constexpr (kk == 0) lread(X, 1, 1, m / kReadEvery);
-                    else lread(Y, 0, 0, m / kReadEvery);
-                }
+                if constexpr (h == 0 && m == kTouchSlot) touch_m0();
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(Fa[kk][i]), "v"(Fb[kk][j]));
+                // half 0: the last fragments of this K-tile (from X, into registers the K-tile before has freed);
+                // half 1: the first fragments of the next K-tile (from Y, complete since the barrier)
+                constexpr int f = h == 0 ? Chain::kPlan[1 - P].frag[kMfmas + m] : Chain::kPlan[P].frag[m];
+                if constexpr (f >= 0) lread(h == 0 ? X : Y, Chain::kk_of(f), Chain::kk_of(f), f % (IM + JN));
                 if constexpr (m % kLoadEvery == 2 && has_load) {
-                    if constexpr (kk == 1) load_go(Int<c>{});
+                    if constexpr (h == 1) load_go(Int<c>{});
                     else load_go(Int<kEarly + c>{});
                 }
-                if constexpr (kk == 0 && m == kTouchSlot + 1) touch_go(t + kTouchAhead);
-                if constexpr (kk == 0 && m == kTouchSlot + 2) advance(t + 2);
+                if constexpr (h == 0 && m == kTouchSlot + 1) touch_go(t + kTouchAhead);
+                if constexpr (h == 0 && m == kTouchSlot + 2) advance(t + 2);
                 __builtin_amdgcn_sched_barrier(0);
             });
-            if constexpr (kk == 0) {
+            if constexpr (h == 0) {
                 // All loads but the youngest (the touch) have landed: K-tile t+1 is complete in Y.  Every
-                // wavefront also has its last fragments of X in registers, so after the barrier Y may be
-                // read and X overwritten.  The LDS counter is drained through the builtin so that the
-                // compiler knows it and adds no waits of its own in front of the MFMAs.
+                // wavefront also has all fragments of X in registers, so after the barrier Y may be read and X
+                // overwritten.  The LDS counter is drained through the builtin so that the compiler, which
+                // places the waits in front of the MFMAs that use a fragment, knows it.
                 asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
                 __builtin_amdgcn_s_waitcnt(0xC07F);             // lgkmcnt(0)
                 __builtin_amdgcn_s_barrier();
-            } else {
-                __builtin_amdgcn_s_waitcnt(0xC07F);             // lgkmcnt(0): the next K-tile's first fragments
             }
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -376,14 +455,16 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     else asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    // then the early loads of K-tile 1 into stage 1 and the first fragments
+    // then the early loads of K-tile 1 into stage 1 and all fragments of K-tile 0 (its first half reads some again)
     static_for<kEarly>([&](auto ic) {
         load_m0(Int<1>{}, ic);
         asm volatile("s_nop 0");
         load_go(ic);
     });
 #pragma unroll
-    for (int idx = 0; idx < kReads; ++idx) lread(0, 0, 0, idx);
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int r = 0; r < kReads; ++r) lread(0, kk, kk, r);
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_sched_barrier(0);
 
@@ -430,12 +511,12 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         for (int kk = 0; kk < 2; ++kk) {
             if (32 * kk < k_rest) {
 #pragma unroll
-                for (int idx = 0; idx < kReads; ++idx) lread(0, kk, 0, idx);
+                for (int r = 0; r < kReads; ++r) lread(0, kk, 0, r);
                 __builtin_amdgcn_s_waitcnt(0xC07F);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int m = 0; m < kMfmas; ++m)
-                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[m / JN][m % JN]) : "v"(F[0].a[m / JN]), "v"(F[0].b[m % JN]));
+                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[m / JN][m % JN]) : "v"(Fa[0][m / JN]), "v"(Fb[0][m % JN]));
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
