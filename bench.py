@@ -96,10 +96,10 @@ def mfma_ceiling(w, lib, torch, inputs, launches=120):
     if kind == 0:
         ops = torch.from_numpy(inputs.normal(2, 40, 1, 2048)).cuda()
     else:
-        ops = torch.from_numpy(inputs.bf16_normal_scaled(4, 40, 1, 8192, 1 / math.sqrt(w["K"])).view(np.int16)).cuda()
+        ops = torch.from_numpy(inputs.bf16_normal_scaled(4, 40, 1, 16384, 1 / math.sqrt(w["K"])).view(np.int16)).cuda()
     groups = torch.cuda.get_device_properties(0).multi_processor_count
     sink = torch.empty(groups * 256, device="cuda", dtype=torch.float32)
-    passes = 500 if kind == 0 else 2000
+    passes = 500 if kind == 0 else 1000
     stream = torch.cuda.current_stream().cuda_stream
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
     flop = 0.0

@@ -231,7 +231,8 @@ int fsrgemm_tile_count_bf16(void);
  * FSRGEMM_PLAN_RULES_ONLY = the choice of the built-in rules alone, without the library's table of earlier
  * selection results (which otherwise decides for a problem -- precision, storage orders, M, N, K -- that has a
  * row there).  A and B are looked at for their alignment only (no device access).  Returns FSRGEMM_OK and sets
- * *tile, *k_slices, or FSRGEMM_ERR_INVALID_ARG.
+ * *tile, *k_slices, or FSRGEMM_ERR_INVALID_ARG.  Where the product runs as two bands (below), *tile is the
+ * first band's.
  */
 #define FSRGEMM_PLAN_WORKSPACE 1
 #define FSRGEMM_PLAN_RULES_ONLY 2
@@ -243,10 +244,33 @@ int fsrgemm_plan_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
                       int flags, int *tile, int *k_slices);
 
 /*
+ * Two bands.  A launch lasts as long as the compute unit with the most output tiles, so a problem whose tiles do
+ * not fill whole rounds of the 256 compute units in any tile shape wastes part of its last round.  For such a
+ * problem (large, aligned, not in the selection table, no K slices) the dispatcher may cut C once, along its rows or
+ * its columns, and run each band as a product of its own, in the tile shape that suits that band's tile count:
+ * two launches on the caller's stream, every entry of C still computed by one workgroup, the result the same bits
+ * as in one launch (part of the tile configuration of Section 3.2's candidates: what is chosen, not what is computed).
+ * These queries report that choice for the plain entry points (flags as for fsrgemm_plan_*):
+ *   *dim          0: one launch; 1: rows [0, *at) and [*at, M); 2: columns [0, *at) and [*at, N)
+ *   *at           the cut, a multiple of 64 (0 when *dim is 0)
+ *   *tile_first, *tile_second   candidate numbers of the two bands' configurations (equal when *dim is 0)
+ * A band of its own is exactly the forced call gemm_*_cfg(tile, 1, ...) on that band's rows or columns.
+ * Returns FSRGEMM_OK or FSRGEMM_ERR_INVALID_ARG (NULL result pointers, extents out of range, unknown flags).
+ */
+int fsrgemm_bands_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                      const float *A, int64_t lda, const float *B, int64_t ldb,
+                      int flags, int *dim, int64_t *at, int *tile_first, int *tile_second);
+int fsrgemm_bands_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                       const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                       int flags, int *dim, int64_t *at, int *tile_first, int *tile_second);
+
+/*
  * Name of the kernel variant the dispatcher would launch for this problem
  * (same argument checks as the gemm calls; launches nothing, touches no
  * device memory).  Returns a pointer to static storage, or NULL when the
- * arguments are invalid.  The Performance-Profiler side of the bench uses it
+ * arguments are invalid; for a product that runs as two bands the text is
+ * "<first kernel> + <second kernel> (rows | columns from <cut>)" in a buffer
+ * of the calling thread, valid until that thread's next such query.  The Performance-Profiler side of the bench uses it
  * to label timings and to find the kernel in a profiler trace.
  */
 const char *fsrgemm_kernel_for_f32(int64_t M, int64_t N, int64_t K,
@@ -306,14 +330,15 @@ const char *fsrgemm_kernel_for_transpose_f32(int64_t rows, int64_t cols,
  * wavefront per SIMD with all 256 accumulator registers in use, operands held in registers.  What it sustains is
  * the ceiling of the contraction step on this part for operands of this kind; it depends on the operand VALUES
  * (the clock follows the power drawn), which is why the caller supplies them.
- *   kind        0: V_MFMA_F32_32X32X2_F32 (the fp32 kernels), 1: V_MFMA_F32_16X16X32_BF16 (the bf16 kernels)
- *   passes      1 .. 2^24 loop iterations of 64 MFMAs per wavefront
- *   operands    device pointer, 16-byte aligned, to 8 KB (kind 0: 2048 floats) or 16 KB (kind 1: 8192 bf16 bit
+ *   kind        0: V_MFMA_F32_32X32X2_F32 (the fp32 kernels), 1: V_MFMA_F32_16X16X32_BF16 (the bf16 kernels), issued
+ *               in the order the product kernels issue them (kind 1: the two k-steps of a block back to back)
+ *   passes      1 .. 2^24 loop iterations of 64 (kind 0) or 128 (kind 1) MFMAs per wavefront
+ *   operands    device pointer, 16-byte aligned, to 8 KB (kind 0: 2048 floats) or 32 KB (kind 1: 16384 bf16 bit
  *               patterns); read once per lane, any finite values
  *   sink        device pointer to workgroups * 256 floats, overwritten with sums nobody needs
  *   workgroups  1 .. 65536 workgroups of 256 lanes; one per compute unit (256 on MI355X) loads the whole chip once
  *   flop        if not NULL, receives the floating-point operations of the launch:
- *               workgroups * 4 * passes * 64 * (4096 for kind 0, 16384 for kind 1)
+ *               workgroups * 4 * passes * (64 * 4096 for kind 0, 128 * 16384 for kind 1)
  * Errors: FSRGEMM_ERR_INVALID_ARG for anything outside these ranges or a NULL / misaligned pointer, before any HIP call.
  */
 int fsrgemm_mfma_ceiling(int kind, int passes, const void *operands, float *sink, int workgroups, double *flop,

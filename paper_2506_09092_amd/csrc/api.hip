@@ -2,6 +2,7 @@
 // choice of tile configuration and load mode, launch on the caller's stream.
 #include "../../include/fsrgemm.h"
 
+#include <stdio.h>
 #include <string.h>
 
 #include "launchers.hpp"
@@ -14,6 +15,11 @@ struct Plan {
     int cfg;        // tile configuration (F32Config / Bf16Config)
     int mode;       // load mode, follows from the tile, the shape and the alignment
     int slices;     // K slices of a call that brings a workspace; 1 = one piece
+    // Two bands (direct-to-LDS shapes only): rows (band_dim 1) or columns (2) [0, band_at) of C run as configuration
+    // cfg, the rest as cfg2, one launch each on the caller's stream; 0 = one launch
+    int band_dim = 0;
+    int64_t band_at = 0;
+    int cfg2 = 0;
 };
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -111,7 +117,7 @@ int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *
 // per compute unit; its shapes (main_fits: bit s set if shape s can take the problem) enter with their own tile
 // times and win where their tiles fill whole rounds.
 constexpr int64_t kMainTileTime[kF32MainShapes] = {2230, 1710, 1120, 1120, 838, 566, 1715, 1286, 845};   // in the order of the shapes
-int tile_rule_f32(int64_t M, int64_t N, unsigned main_fits)
+int tile_rule_f32(int64_t M, int64_t N, unsigned main_fits, int64_t *cost_out = nullptr)
 {
     constexpr int64_t kTileTime[kF32ConfigCount] = {1137, 569, 169}, kAlone[kF32ConfigCount] = {1137, 569, 221};
     int best = 0;
@@ -127,7 +133,56 @@ int tile_rule_f32(int64_t M, int64_t N, unsigned main_fits)
         const int64_t cost = ceil_div(ceil_div(M, f32_main_tile_m(sh)) * ceil_div(N, f32_main_tile_n(sh)), 256) * kMainTileTime[sh];
         if (cost < best_cost) best = kF32_Main + sh, best_cost = cost;
     }
+    if (cost_out) *cost_out = best_cost;
     return best;
+}
+
+// Two bands.  Where no tile shape fills whole rounds of the compute units, two launches often do: C is cut once, along
+// its rows or its columns, and each band takes the shape that suits its own tile count (5120^2: 729 tiles of 192 x 192
+// are 2.85 rounds; rows 0 .. 1471 as 240 tiles of 128 x 256 and the rest as 760 tiles of 192 x 128 are 1 + 3 rounds that
+// take 6 % less time).  The bands are independent products on shifted pointers, so nothing changes in a kernel and every
+// entry of C is still computed by one workgroup in the same order of summation.  cost(shape, m, n) is the modelled
+// time of an m x n band in that shape, negative where the shape cannot take it; cuts are multiples of 64 (every tile
+// side is one, and a cut then keeps the operands' alignment), at most 256 per direction.
+struct Bands {
+    int dim = 0;
+    int64_t at = 0;
+    int sh1 = -1, sh2 = -1;
+    int64_t cost = 0;
+};
+template <class Cost>
+Bands best_bands(int64_t M, int64_t N, int shapes, Cost cost, int64_t launch_gap)
+{
+    Bands best;
+    for (int dim = 1; dim <= 2; ++dim) {
+        const int64_t ext = dim == 1 ? M : N;
+        const int64_t step = 64 * ceil_div(ext, 64 * 256);
+        for (int64_t at = 128; at + 128 <= ext; at += step) {
+            int s1 = -1, s2 = -1;
+            int64_t c1 = 0, c2 = 0;
+            for (int sh = 0; sh < shapes; ++sh) {
+                const int64_t a = dim == 1 ? cost(sh, at, N) : cost(sh, M, at), b = dim == 1 ? cost(sh, ext - at, N) : cost(sh, M, ext - at);
+                if (a >= 0 && (s1 < 0 || a < c1)) s1 = sh, c1 = a;
+                if (b >= 0 && (s2 < 0 || b < c2)) s2 = sh, c2 = b;
+            }
+            if (s1 < 0 || s2 < 0) continue;
+            const int64_t c = c1 + c2 + launch_gap;
+            if (best.dim == 0 || c < best.cost) best.dim = dim, best.at = at, best.sh1 = s1, best.sh2 = s2, best.cost = c;
+        }
+    }
+    return best;
+}
+
+// Operands and result of the band that starts at row (dim 1) or column (dim 2) `at` of C.  The planners call this with
+// whatever they were given for A and B (possibly NULL: only the alignment is looked at), hence addresses as integers.
+template <class T>
+void shift_to_band(int dim, int64_t at, int a_lay, int b_lay, const T *&A, int64_t lda, const T *&B, int64_t ldb, float *&C, int64_t ldc)
+{
+    const int64_t off_a = dim == 1 ? (a_lay == kKContig ? at * lda : at) : 0, off_b = dim == 2 ? (b_lay == kKContig ? at * ldb : at) : 0;
+    const int64_t off_c = dim == 1 ? at * ldc : at;
+    A = reinterpret_cast<const T *>(reinterpret_cast<uintptr_t>(A) + (uintptr_t)off_a * sizeof(T));
+    B = reinterpret_cast<const T *>(reinterpret_cast<uintptr_t>(B) + (uintptr_t)off_b * sizeof(T));
+    C = reinterpret_cast<float *>(reinterpret_cast<uintptr_t>(C) + (uintptr_t)off_c * sizeof(float));
 }
 
 // How a product with M == 1 or N == 1 maps onto the vector kernels: which operand is the matrix, how it is
@@ -232,7 +287,26 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
         // a split runs on 64 x 64 tiles, or on 128 x 128 ones where those still give every compute unit a workgroup
         // and a slice keeps at least 1024 k (10-17 % faster there, measured on 256^2 ... 1024^2 with K up to 65536)
         const bool split128 = p->slices > 1 && ceil_div(M, 128) * ceil_div(N, 128) * p->slices >= 240 && K / p->slices >= 1024;
-        p->cfg = t ? t->tile : p->slices > 1 ? (split128 ? kF32_128x128 : kF32_64x64) : tile_rule_f32(M, N, main_fits);
+        int64_t one_cost = 0;
+        p->cfg = t ? t->tile : p->slices > 1 ? (split128 ? kF32_128x128 : kF32_64x64) : tile_rule_f32(M, N, main_fits, &one_cost);
+        // one launch leaves compute units idle in its last round: try two bands of direct-to-LDS shapes (tile times in
+        // 0.1 ns per k; 4 us for the second launch); taken for a modelled gain of 3 % and more
+        if (!t && p->slices == 1 && main_fits && (double)one_cost * 256.0 * 65536.0 > 1.03 * (double)M * (double)N * (double)kMainTileTime[0]) {
+            const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
+            const Bands b = best_bands(M, N, kF32MainShapes, [&](int sh, int64_t m, int64_t n) -> int64_t {
+                if (!(main_fits >> sh & 1) || m < f32_main_tile_m(sh) || n < f32_main_tile_n(sh)) return -1;
+                return ceil_div(ceil_div(m, f32_main_tile_m(sh)) * ceil_div(n, f32_main_tile_n(sh)), 256) * kMainTileTime[sh];
+            }, 40000 / K);
+            if (b.dim && b.cost * 100 <= one_cost * 97) {
+                const float *A2 = A, *B2 = B;
+                float *none = nullptr;
+                shift_to_band(b.dim, b.at, a_lay, b_lay, A2, lda, B2, ldb, none, 0);
+                const int64_t m1 = b.dim == 1 ? b.at : M, n1 = b.dim == 2 ? b.at : N;
+                if (f32_main_fits(b.sh1, a_lay, b_lay, m1, n1, K, A, lda, B, ldb) &&
+                    f32_main_fits(b.sh2, a_lay, b_lay, b.dim == 1 ? M - b.at : M, b.dim == 2 ? N - b.at : N, K, A2, lda, B2, ldb))
+                    p->cfg = kF32_Main + b.sh1, p->cfg2 = kF32_Main + b.sh2, p->band_dim = b.dim, p->band_at = b.at;
+            }
+        }
     }
     return mode_f32(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
 }
@@ -247,17 +321,22 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
 // Returns the shape, or -1 when none fits the problem (fits: bit s set if shape s can take it).
 constexpr int64_t kBf16MainPerKTile[kBf16MainShapes] = {1333, 1073, 780, 1037, 907, 808};      // in the order of the shapes
 constexpr int64_t kBf16MainPerRound[kBf16MainShapes] = {8700, 5800, 4700, 7700, 3700, 5200};
-int tile_rule_bf16_main(int64_t M, int64_t N, int64_t K, unsigned fits)
+int64_t bf16_main_cost(int sh, int64_t M, int64_t N, int64_t K)       // in 1/256 ns
+{
+    const int64_t tiles = ceil_div(M, bf16_main_tile_m(sh)) * ceil_div(N, bf16_main_tile_n(sh)), rest = tiles % 256;
+    const int64_t rounds256 = tiles / 256 * 256 + (rest == 0 ? 0 : rest < 192 ? 192 : rest);       // in 1/256 of a round
+    return rounds256 * (kBf16MainPerKTile[sh] * ceil_div(K, 64) + kBf16MainPerRound[sh]);
+}
+int tile_rule_bf16_main(int64_t M, int64_t N, int64_t K, unsigned fits, int64_t *cost_out = nullptr)
 {
     int best = -1;
     int64_t best_cost = 0;
     for (int sh = 0; sh < kBf16MainShapes; ++sh) {
         if (!(fits >> sh & 1)) continue;
-        const int64_t tiles = ceil_div(M, bf16_main_tile_m(sh)) * ceil_div(N, bf16_main_tile_n(sh)), rest = tiles % 256;
-        const int64_t rounds256 = tiles / 256 * 256 + (rest == 0 ? 0 : rest < 192 ? 192 : rest);       // in 1/256 of a round
-        const int64_t cost = rounds256 * (kBf16MainPerKTile[sh] * ceil_div(K, 64) + kBf16MainPerRound[sh]);
+        const int64_t cost = bf16_main_cost(sh, M, N, K);
         if (best < 0 || cost < best_cost) best = sh, best_cost = cost;
     }
+    if (cost_out) *cost_out = best_cost;
     return best;
 }
 
@@ -297,7 +376,25 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     // where 256 x 256 tiles give at least half the compute units one each: the direct-to-LDS kernel in the shape that
     // fills whole rounds, or, where it does not fit (alignment, a K that is not whole 16-byte pieces), the general
     // kernel of that tile
-    else if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) p->cfg = main_fits ? bf16_main_candidate(tile_rule_bf16_main(M, N, K, main_fits)) : (int)kBf16_256x256;
+    else if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) {
+        int64_t one_cost = 0;
+        p->cfg = main_fits ? bf16_main_candidate(tile_rule_bf16_main(M, N, K, main_fits, &one_cost)) : (int)kBf16_256x256;
+        // two bands, as for fp32 (costs in 1/256 ns; 4 us for the second launch; taken for a modelled gain of 4 % and more)
+        if (main_fits && ceil_div(M, 64) * ceil_div(N, 64) <= ((int64_t)1 << 20)) {
+            const Bands b = best_bands(M, N, kBf16MainShapes, [&](int sh, int64_t m, int64_t n) -> int64_t {
+                if (!(main_fits >> sh & 1) || m < bf16_main_tile_m(sh) || n < bf16_main_tile_n(sh)) return -1;
+                return bf16_main_cost(sh, m, n, K);
+            }, (int64_t)4000 * 256);
+            if (b.dim && b.cost * 100 <= one_cost * 96) {
+                const uint16_t *A2 = A, *B2 = B;
+                float *none = nullptr;
+                shift_to_band(b.dim, b.at, a_lay, b_lay, A2, lda, B2, ldb, none, 0);
+                if (bf16_main_fits(b.sh1, a_lay, b_lay, b.dim == 1 ? b.at : M, b.dim == 2 ? b.at : N, K, A, lda, B, ldb) &&
+                    bf16_main_fits(b.sh2, a_lay, b_lay, b.dim == 1 ? M - b.at : M, b.dim == 2 ? N - b.at : N, K, A2, lda, B2, ldb))
+                    p->cfg = bf16_main_candidate(b.sh1), p->cfg2 = bf16_main_candidate(b.sh2), p->band_dim = b.dim, p->band_at = b.at;
+            }
+        }
+    }
     else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kBf16_128x128;
     else p->cfg = kBf16_64x64;
     if (p->cfg == kBf16_Vector) {       // a row of the selection table
@@ -383,8 +480,17 @@ int run_f32(const Plan &p, int transA, int transB, int64_t M, int64_t N, int64_t
     hipError_t e;
     if (p.cfg >= kF32_Main) {
         if (split) return FSRGEMM_ERR_INVALID_ARG;      // the planners never pair the two
-        const GemmArgs a = pack(M, N, K, A, lda, B, ldb, C, ldc);
-        e = launch_f32_main(p.cfg - kF32_Main, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, a, s);
+        const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
+        if (p.band_dim == 0) {
+            e = launch_f32_main(p.cfg - kF32_Main, a_lay, b_lay, pack(M, N, K, A, lda, B, ldb, C, ldc), s);
+        } else {
+            const int64_t m1 = p.band_dim == 1 ? p.band_at : M, n1 = p.band_dim == 2 ? p.band_at : N;
+            e = launch_f32_main(p.cfg - kF32_Main, a_lay, b_lay, pack(m1, n1, K, A, lda, B, ldb, C, ldc), s);
+            if (e == hipSuccess) {
+                shift_to_band(p.band_dim, p.band_at, a_lay, b_lay, A, lda, B, ldb, C, ldc);
+                e = launch_f32_main(p.cfg2 - kF32_Main, a_lay, b_lay, pack(p.band_dim == 1 ? M - m1 : M, p.band_dim == 2 ? N - n1 : N, K, A, lda, B, ldb, C, ldc), s);
+            }
+        }
         return e == hipSuccess ? FSRGEMM_OK : e == hipErrorInvalidValue ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_ERR_LAUNCH;
     }
     if (p.cfg == kF32_Vector) {
@@ -410,7 +516,16 @@ int run_bf16(const Plan &p, int a_lay, int b_lay, int64_t M, int64_t N, int64_t 
     if (rc != FSRGEMM_OK) return rc;
     hipError_t e;
     if (bf16_main_shape(p.cfg) >= 0) {
-        e = launch_bf16_main(bf16_main_shape(p.cfg), a_lay, b_lay, pack(M, N, K, A, lda, B, ldb, C, ldc), s);
+        if (p.band_dim == 0) {
+            e = launch_bf16_main(bf16_main_shape(p.cfg), a_lay, b_lay, pack(M, N, K, A, lda, B, ldb, C, ldc), s);
+        } else {
+            const int64_t m1 = p.band_dim == 1 ? p.band_at : M, n1 = p.band_dim == 2 ? p.band_at : N;
+            e = launch_bf16_main(bf16_main_shape(p.cfg), a_lay, b_lay, pack(m1, n1, K, A, lda, B, ldb, C, ldc), s);
+            if (e == hipSuccess) {
+                shift_to_band(p.band_dim, p.band_at, a_lay, b_lay, A, lda, B, ldb, C, ldc);
+                e = launch_bf16_main(bf16_main_shape(p.cfg2), a_lay, b_lay, pack(p.band_dim == 1 ? M - m1 : M, p.band_dim == 2 ? N - n1 : N, K, A, lda, B, ldb, C, ldc), s);
+            }
+        }
         return e == hipSuccess ? FSRGEMM_OK : e == hipErrorInvalidValue ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_ERR_LAUNCH;
     }
     if (p.cfg == kBf16_Vector) {
@@ -448,6 +563,15 @@ int static_scratch(float **out)
     }
     *out = static_cast<float *>(ptr);
     return FSRGEMM_OK;
+}
+
+// "first kernel + second kernel (rows | columns from <cut>)" of a product that runs as two bands; the text lives in a
+// buffer of the calling thread until its next such query
+const char *two_band_name(const Plan &p, const char *first, const char *second)
+{
+    static thread_local char text[192];
+    snprintf(text, sizeof text, "%s + %s (%s from %lld)", first, second, p.band_dim == 1 ? "rows" : "columns", (long long)p.band_at);
+    return text;
 }
 
 bool extents_ok(int64_t M, int64_t N, int64_t K)
@@ -578,6 +702,17 @@ int fsrgemm_plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, co
 
 int fsrgemm_tile_count_f32(void) { return kF32_Main + kF32MainShapes; }
 
+int fsrgemm_bands_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                      int64_t ldb, int flags, int *dim, int64_t *at, int *tile_first, int *tile_second)
+{
+    if (!extents_ok(M, N, K) || dim == nullptr || at == nullptr || tile_first == nullptr || tile_second == nullptr || (flags & ~3)) return FSRGEMM_ERR_INVALID_ARG;
+    Plan p;
+    const int rc = plan_f32(transA, transB, M, N, K, A, lda, B, ldb, (flags & 1) != 0, &p, (flags & 2) == 0);
+    if (rc != FSRGEMM_OK) return rc;
+    *dim = p.band_dim, *at = p.band_at, *tile_first = p.cfg, *tile_second = p.band_dim ? p.cfg2 : p.cfg;
+    return FSRGEMM_OK;
+}
+
 int gemm_bf16(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
               float *C, int64_t ldc, void *stream)
 {
@@ -656,6 +791,18 @@ int fsrgemm_plan_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, c
 
 int fsrgemm_tile_count_bf16(void) { return kBf16_MainMore + kBf16MainShapes - 1; }
 
+int fsrgemm_bands_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
+                       const uint16_t *B, int64_t ldb, int flags, int *dim, int64_t *at, int *tile_first, int *tile_second)
+{
+    if (!extents_ok(M, N, K) || dim == nullptr || at == nullptr || tile_first == nullptr || tile_second == nullptr || (flags & ~3)) return FSRGEMM_ERR_INVALID_ARG;
+    Plan p;
+    const int rc = plan_bf16(transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, A, lda, B, ldb,
+                             (flags & 1) != 0, &p, (flags & 2) == 0);
+    if (rc != FSRGEMM_OK) return rc;
+    *dim = p.band_dim, *at = p.band_at, *tile_first = p.cfg, *tile_second = p.band_dim ? p.cfg2 : p.cfg;
+    return FSRGEMM_OK;
+}
+
 const char *fsrgemm_kernel_for_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
                                    int64_t ldb, const float *C, int64_t ldc)
 {
@@ -668,7 +815,11 @@ const char *fsrgemm_kernel_for_f32_ex(int transA, int transB, int64_t M, int64_t
     Plan p;
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
     if (plan_f32(transA, transB, M, N, K, A, lda, B, ldb, false, &p) != FSRGEMM_OK) return nullptr;
-    if (p.cfg >= kF32_Main) return f32_main_kernel_name(p.cfg - kF32_Main, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig);
+    if (p.cfg >= kF32_Main) {
+        const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
+        const char *first = f32_main_kernel_name(p.cfg - kF32_Main, a_lay, b_lay);
+        return p.band_dim == 0 ? first : two_band_name(p, first, f32_main_kernel_name(p.cfg2 - kF32_Main, a_lay, b_lay));
+    }
     if (p.cfg == kF32_Vector) {
         const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
         return gemv_kernel_name(v.pattern, gemv_takes_vectors(v.a));
@@ -693,7 +844,8 @@ const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB, int64_t M, int64_
         const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
         return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a));
     }
-    return bf16_kernel_name(p.cfg, p.mode, a_lay, b_lay);
+    const char *first = bf16_kernel_name(p.cfg, p.mode, a_lay, b_lay);
+    return p.band_dim == 0 ? first : two_band_name(p, first, bf16_kernel_name(p.cfg2, 0, a_lay, b_lay));
 }
 
 const char *fsrgemm_kernel_for_f32_cfg(int tile, int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A,

@@ -15,7 +15,7 @@ __all__ = [
     "fsrgemm_kernel_for_f32_ex", "fsrgemm_kernel_for_bf16", "gemm_bf16_ex", "fsrgemm_kernel_for_bf16_ex",
     "gemm_f32_ws", "gemm_f32_noalloc", "gemm_f32_workspace_bytes", "gemm_bf16_ws", "gemm_bf16_workspace_bytes", "transpose_f32",
     "fsrgemm_kernel_for_transpose_f32", "gemm_f32_cfg", "gemm_bf16_cfg", "fsrgemm_tile_count_f32",
-    "fsrgemm_tile_count_bf16", "fsrgemm_plan_f32", "fsrgemm_plan_bf16", "fsrgemm_kernel_for_f32_cfg",
+    "fsrgemm_tile_count_bf16", "fsrgemm_plan_f32", "fsrgemm_plan_bf16", "fsrgemm_bands_f32", "fsrgemm_bands_bf16", "fsrgemm_kernel_for_f32_cfg",
     "fsrgemm_kernel_for_bf16_cfg", "fsrgemm_mfma_ceiling", "fsrgemm_kernel_for_mfma_ceiling",
     "fsrgemm_status_string", "fsrgemm_version", "check", "FsrGemmError", "EXPORTS",
     "FSRGEMM_PLAN_WORKSPACE", "FSRGEMM_PLAN_RULES_ONLY", "FSRGEMM_OK", "FSRGEMM_ERR_INVALID_ARG", "FSRGEMM_ERR_LAUNCH", "FSRGEMM_ERR_UNSUPPORTED_DEVICE",
@@ -61,6 +61,10 @@ EXPORTS = {
                                         ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
     "fsrgemm_plan_bf16": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, ctypes.c_int,
                                          ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
+    "fsrgemm_bands_f32": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, ctypes.c_int,
+                                         ctypes.POINTER(ctypes.c_int), ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
+    "fsrgemm_bands_bf16": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, ctypes.c_int,
+                                          ctypes.POINTER(ctypes.c_int), ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
     "fsrgemm_mfma_ceiling": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, _vp, _vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), _vp]),
     "fsrgemm_kernel_for_mfma_ceiling": (ctypes.c_char_p, [ctypes.c_int]),
     "fsrgemm_status_string": (ctypes.c_char_p, [ctypes.c_int]),
@@ -191,6 +195,23 @@ def fsrgemm_plan_f32(transA, transB, M, N, K, A, lda, B, ldb, with_workspace=Fal
 
 def fsrgemm_plan_bf16(transA, transB, M, N, K, A, lda, B, ldb, with_workspace=False, rules_only=False):
     return _plan(load().fsrgemm_plan_bf16, transA, transB, M, N, K, A, lda, B, ldb, with_workspace, rules_only)
+
+
+def _bands(fn, transA, transB, M, N, K, A, lda, B, ldb, with_workspace, rules_only):
+    dim, at, first, second = ctypes.c_int(-1), _i64(-1), ctypes.c_int(-1), ctypes.c_int(-1)
+    flags = (FSRGEMM_PLAN_WORKSPACE if with_workspace else 0) | (FSRGEMM_PLAN_RULES_ONLY if rules_only else 0)
+    rc = fn(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, flags, ctypes.byref(dim), ctypes.byref(at),
+            ctypes.byref(first), ctypes.byref(second))
+    return None if rc != FSRGEMM_OK else (dim.value, at.value, first.value, second.value)
+
+
+def fsrgemm_bands_f32(transA, transB, M, N, K, A, lda, B, ldb, with_workspace=False, rules_only=False):
+    """(dim, at, tile_first, tile_second): dim 0 = one launch, 1 = cut along the rows of C at `at`, 2 = along its columns."""
+    return _bands(load().fsrgemm_bands_f32, transA, transB, M, N, K, A, lda, B, ldb, with_workspace, rules_only)
+
+
+def fsrgemm_bands_bf16(transA, transB, M, N, K, A, lda, B, ldb, with_workspace=False, rules_only=False):
+    return _bands(load().fsrgemm_bands_bf16, transA, transB, M, N, K, A, lda, B, ldb, with_workspace, rules_only)
 
 
 def fsrgemm_kernel_for_f32(M, N, K, A, lda, B, ldb, C, ldc):

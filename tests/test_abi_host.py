@@ -458,3 +458,68 @@ def test_mfma_ceiling_arguments():
     assert f(groups=0) == bad and f(groups=(1 << 16) + 1) == bad and f(ops=None) == bad and f(sink=None) == bad and f(ops=P + 4) == bad
     assert lib.fsrgemm_kernel_for_mfma_ceiling(0) == "mfma_ceiling_kernel<0>" and lib.fsrgemm_kernel_for_mfma_ceiling(1) == "mfma_ceiling_kernel<1>"
     assert lib.fsrgemm_kernel_for_mfma_ceiling(2) is None
+
+
+def _band_problems(kind, ta, tb, M, N, K, a, lda, b, ldb, dim, at):
+    """The two products a cut at row (dim 1) or column (dim 2) `at` of C leaves: (M, N, A, B) of each band."""
+    esize = 4 if kind == "f32" else 2
+    if dim == 1:
+        a2 = a + esize * (at if ta else at * lda)
+        return (at, N, a, b), (M - at, N, a2, b)
+    b2 = b + esize * (at * ldb if tb else at)
+    return (M, at, a, b), (M, N - at, a, b2)
+
+
+def test_two_band_plans():
+    # where no tile shape fills whole rounds of the 256 compute units the dispatcher cuts C once and gives each band its own
+    # shape: 5120^2 as rows 0..1471 in 128 x 256 tiles (240 = one round) + the rest in 192 x 128 tiles (760 = three rounds)
+    # instead of 729 tiles of 192 x 192 (2.85 -> 3 rounds of a larger tile); fp32 candidates: 5 + shape
+    bf = lambda M, N, K, a=P, **kw: lib.fsrgemm_bands_f32(0, 0, M, N, K, a, K, P, N, **kw)
+    assert bf(5120, 5120, 2048) == (1, 1472, 7, 9)
+    assert lib.fsrgemm_plan_f32(0, 0, 5120, 5120, 2048, P, 2048, P, 5120) == (7, 1)            # the first band's tile
+    name = lib.fsrgemm_kernel_for_f32(5120, 5120, 2048, P, 2048, P, 5120, P, 5120)
+    assert name == "gemm_f32_main_kernel<2, 4, 0, 1> + gemm_f32_main_kernel<3, 2, 0, 1> (rows from 1472)"
+    # whole rounds in one launch stay one launch; so do misaligned operands (no direct-to-LDS kernel), table rows and splits
+    assert bf(4096, 4096, 4096) == (0, 0, 5, 5) and bf(6144, 6144, 2048) == (0, 0, 9, 9) and bf(1024, 1024, 1024)[0] == 0
+    assert bf(5120, 5120, 2048, a=P + 4)[0] == 0
+    assert lib.fsrgemm_bands_f32(0, 0, 512, 512, 65536, P, 65536, P, 512, with_workspace=True)[0] == 0
+    # bf16: 7168^3 in 256 x 192 tiles is 4.16 rounds
+    got = lib.fsrgemm_bands_bf16(0, 1, 7168, 7168, 7168, P, 7168, P, 7168)
+    assert got[0] in (1, 2) and got[1] % 64 == 0 and 0 < got[1] < 7168
+    assert lib.fsrgemm_bands_bf16(0, 1, 8192, 8192, 8192, P, 8192, P, 8192) == (0, 0, 0, 0)
+    # argument errors
+    assert lib.fsrgemm_bands_f32(0, 0, -1, 8, 8, P, 8, P, 8) is None and lib.fsrgemm_bands_bf16(0, 1, 8, 8, 1 << 31, P, 8, P, 8) is None
+
+
+def test_each_band_is_a_problem_the_forced_call_accepts():
+    # over a seeded sweep of large problems in every storage order, with padded leading dimensions and ragged extents: a cut is
+    # a multiple of 64 strictly inside the matrix, and each band, on its shifted operands, is a problem the forced entry point of
+    # its tile accepts (same alignment rules, extents at least one tile)
+    import random
+
+    rng = random.Random(21)
+    cut = 0
+    for case in range(1500):
+        kind = rng.choice(("f32", "bf16"))
+        ta, tb = rng.randint(0, 1), rng.randint(0, 1)
+        M, N = rng.choice((2048, 2560, 3000, 3584, 4000, 4608, 5000, 5120, 7168, 9000, 11111, 12288)), rng.choice((2048, 2304, 3584, 4608, 5120, 6656, 7000, 7168, 10000))
+        M, N = M - M % 8, N - N % 8
+        K = rng.choice((64, 128, 2048, 4104, 8192))
+        pad = 8 * rng.choice((0, 0, 1, 5))
+        lda, ldb = (M if ta else K) + pad, (K if tb else N) + pad
+        bands, named = ((lib.fsrgemm_bands_f32, lib.fsrgemm_kernel_for_f32_cfg) if kind == "f32" else (lib.fsrgemm_bands_bf16, lib.fsrgemm_kernel_for_bf16_cfg))
+        plan = lib.fsrgemm_plan_f32 if kind == "f32" else lib.fsrgemm_plan_bf16
+        got = bands(ta, tb, M, N, K, P, lda, P, ldb)
+        assert got is not None
+        dim, at, first, second = got
+        ctx = (kind, ta, tb, M, N, K, lda, ldb, got)
+        assert plan(ta, tb, M, N, K, P, lda, P, ldb) == (first, 1), ctx
+        if dim == 0:
+            assert at == 0 and first == second, ctx
+            continue
+        cut += 1
+        assert dim in (1, 2) and at % 64 == 0 and 0 < at < (M if dim == 1 else N), ctx
+        for tile, (m, n, a, b) in zip((first, second), _band_problems(kind, ta, tb, M, N, K, P, lda, P, ldb, dim, at)):
+            name = named(tile, ta, tb, m, n, K, a, lda, b, ldb, P, N)
+            assert name is not None and "main_kernel" in name, ctx
+    assert cut > 100        # the sweep does exercise the two-band path

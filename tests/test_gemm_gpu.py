@@ -1214,3 +1214,75 @@ def test_transpose_empty(gpu):
     gpu.check(gpu.transpose_f32(5, 0, None, 0, t, 5, 0))
     torch.cuda.synchronize()
     assert bool((t == 3.0).all())
+
+
+@pytest.mark.parametrize("kind", [0, 1])
+def test_mfma_ceiling_loop_computes_what_its_operands_define(gpu, kind):
+    # The register-only MFMA loop behind the bench's ceiling figure is a measurement aid, but it must still be the MFMAs
+    # it claims to be: with every operand 1.0 each accumulator entry ends at passes x (k of one pass), so a lane's sum over
+    # its 256 accumulator registers is 256 x that: kind 0, fp32 32x32x2, 4 MFMAs per block and pass = 8 k;
+    # kind 1, bf16 16x16x32, 2 MFMAs per block and pass = 64 k.  Exact in fp32 for these sizes.
+    import torch
+    say("mfma ceiling kind %d" % kind)
+    passes, groups = 7, 3
+    ops = (torch.ones(2048, device="cuda", dtype=torch.float32) if kind == 0
+           else torch.full((16384,), 0x3F80, device="cuda", dtype=torch.int16))
+    sink = torch.zeros(groups * 256, device="cuda", dtype=torch.float32)
+    rc, flop = gpu.fsrgemm_mfma_ceiling(kind, passes, ops, sink, groups, torch.cuda.current_stream().cuda_stream)
+    gpu.check(rc)
+    torch.cuda.synchronize()
+    assert flop == groups * 4 * passes * (64 * 4096 if kind == 0 else 128 * 16384)
+    assert bool((sink == 256.0 * passes * (8 if kind == 0 else 64)).all())
+
+
+P_FAKE = 0x1000      # an aligned address for the plan queries (never dereferenced)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("shape", [(5120, 5120, 512), (3584, 3592, 772), (7168, 7168, 512)])
+def test_f32_two_band_products(gpu, shape, ta, tb):
+    # problems the dispatcher runs as two bands of C, each in its own tile shape (a cut along the rows, one along the
+    # columns, a ragged N and a rest of K among them): the whole result against the oracle, bit for bit against the
+    # same product forced into one launch of the first band's tile (every shape of this kernel sums in the same order),
+    # padding untouched, two runs identical
+    M, N, K = shape
+    say("fp32 two bands %dx%dx%d transA=%d transB=%d" % (M, N, K, ta, tb))
+    lda, ldb = (M if ta else K) + 8, (K if tb else N) + 4
+    dim, at, first, second = gpu.fsrgemm_bands_f32(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb)
+    assert dim in (1, 2), "this case is meant to take the two-band path"
+    A, B = inputs.uniform_pm1(30, 1, M, K), inputs.uniform_pm1(30, 2, K, N)
+    got = run_f32_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 4, repeat=2)
+    ref, S = oracle.gemm(A, B)
+    e = oracle.componentwise_error(got, ref, S)
+    assert e <= TOL_F32, "componentwise error %.3e" % e
+    one = run_cfg(gpu, "f32", first, 1, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 4)
+    assert np.array_equal(got.view(np.uint32), one.view(np.uint32))
+
+
+def test_f32_two_band_product_of_integers_is_exact(gpu):
+    M, N, K = 4608, 4608, 1024
+    say("fp32 two bands %dx%dx%d integers" % (M, N, K))
+    assert gpu.fsrgemm_bands_f32(0, 0, M, N, K, P_FAKE, K, P_FAKE, N)[0] != 0
+    A, B = inputs.small_ints(31, 1, M, K), inputs.small_ints(31, 2, K, N)
+    got = run_f32(gpu, A, B)
+    ref, _ = oracle.gemm(A, B)
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("shape,ta,tb", [((7168, 7168, 2056), 0, 1), ((7168, 7168, 512), 0, 0), ((7000, 7168, 520), 1, 1), ((7168, 7168, 512), 1, 0)])
+def test_bf16_two_band_products(gpu, shape, ta, tb):
+    # the same for bf16 operands; storage orders whose plan is one launch are checked all the same
+    M, N, K = shape
+    say("bf16 two bands %dx%dx%d transA=%d transB=%d" % (M, N, K, ta, tb))
+    lda, ldb = (M if ta else K) + 8, (K if tb else N) + 16
+    dim, at, first, second = gpu.fsrgemm_bands_bf16(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb)
+    assert (dim != 0) == ((ta, tb) != (1, 0)), "which of these cases take the two-band path"
+    A = inputs.bf16_normal_scaled(32, 1, M, K, 1 / math.sqrt(K))
+    B = inputs.bf16_normal_scaled(32, 2, K, N, 1 / math.sqrt(K))
+    got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 4, repeat=2)
+    ref, S = oracle.gemm(A, B)
+    e = oracle.componentwise_error(got, ref, S)
+    assert e <= TOL_BF16, "componentwise error %.3e" % e
+    assert e <= 1e-5, "fp32 accumulation of exact products stays far inside the bf16 tolerance: %.3e" % e
+    one = run_cfg(gpu, "bf16", first, 1, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 4)
+    assert np.array_equal(got.view(np.uint32), one.view(np.uint32))
