@@ -150,9 +150,28 @@ struct Bands {
     int sh1 = -1, sh2 = -1;
     int64_t cost = 0;
 };
+// The search is a few thousand cost evaluations (tens of microseconds), and callers repeat their problems: the last
+// results are kept per thread, keyed by everything the search depends on (precision and storage orders, extents, which
+// shapes fit the problem).
+struct BandsKey {
+    int kind, lays;
+    int64_t M, N, K;
+    unsigned fits;
+    bool operator==(const BandsKey &o) const { return kind == o.kind && lays == o.lays && M == o.M && N == o.N && K == o.K && fits == o.fits; }
+};
 template <class Cost>
-Bands best_bands(int64_t M, int64_t N, int shapes, Cost cost, int64_t launch_gap)
+Bands best_bands(const BandsKey &key, int shapes, Cost cost, int64_t launch_gap)
 {
+    constexpr int kSlots = 16;
+    struct Slot {
+        bool used = false;
+        BandsKey key;
+        Bands bands;
+    };
+    static thread_local Slot cache[kSlots];
+    Slot &slot = cache[(uint64_t)(key.M * 31 + key.N * 17 + key.K * 7 + key.kind * 3 + key.lays) % kSlots];
+    if (slot.used && slot.key == key) return slot.bands;
+    const int64_t M = key.M, N = key.N;
     Bands best;
     for (int dim = 1; dim <= 2; ++dim) {
         const int64_t ext = dim == 1 ? M : N;
@@ -165,11 +184,12 @@ Bands best_bands(int64_t M, int64_t N, int shapes, Cost cost, int64_t launch_gap
                 if (a >= 0 && (s1 < 0 || a < c1)) s1 = sh, c1 = a;
                 if (b >= 0 && (s2 < 0 || b < c2)) s2 = sh, c2 = b;
             }
-            if (s1 < 0 || s2 < 0) continue;
+            if (s1 < 0 || s2 < 0 || s1 == s2) continue;      // two bands of one shape are the one launch cut in two
             const int64_t c = c1 + c2 + launch_gap;
             if (best.dim == 0 || c < best.cost) best.dim = dim, best.at = at, best.sh1 = s1, best.sh2 = s2, best.cost = c;
         }
     }
+    slot.used = true, slot.key = key, slot.bands = best;
     return best;
 }
 
@@ -293,7 +313,7 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
         // 0.1 ns per k; 4 us for the second launch); taken for a modelled gain of 3 % and more
         if (!t && p->slices == 1 && main_fits && (double)one_cost * 256.0 * 65536.0 > 1.03 * (double)M * (double)N * (double)kMainTileTime[0]) {
             const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
-            const Bands b = best_bands(M, N, kF32MainShapes, [&](int sh, int64_t m, int64_t n) -> int64_t {
+            const Bands b = best_bands(BandsKey{0, a_lay * 2 + b_lay, M, N, K, main_fits}, kF32MainShapes, [&](int sh, int64_t m, int64_t n) -> int64_t {
                 if (!(main_fits >> sh & 1) || m < f32_main_tile_m(sh) || n < f32_main_tile_n(sh)) return -1;
                 return ceil_div(ceil_div(m, f32_main_tile_m(sh)) * ceil_div(n, f32_main_tile_n(sh)), 256) * kMainTileTime[sh];
             }, 40000 / K);
@@ -380,8 +400,9 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
         int64_t one_cost = 0;
         p->cfg = main_fits ? bf16_main_candidate(tile_rule_bf16_main(M, N, K, main_fits, &one_cost)) : (int)kBf16_256x256;
         // two bands, as for fp32 (costs in 1/256 ns; 4 us for the second launch; taken for a modelled gain of 4 % and more)
-        if (main_fits && ceil_div(M, 64) * ceil_div(N, 64) <= ((int64_t)1 << 20)) {
-            const Bands b = best_bands(M, N, kBf16MainShapes, [&](int sh, int64_t m, int64_t n) -> int64_t {
+        // (not where the one launch is within 3 % of 256 x 256 tiles in whole rounds, the best any plan can do)
+        if (main_fits && (double)one_cost * 65536.0 > 1.03 * (double)M * (double)N * (double)(kBf16MainPerKTile[0] * ceil_div(K, 64) + kBf16MainPerRound[0])) {
+            const Bands b = best_bands(BandsKey{1, a_lay * 2 + b_lay, M, N, K, main_fits}, kBf16MainShapes, [&](int sh, int64_t m, int64_t n) -> int64_t {
                 if (!(main_fits >> sh & 1) || m < bf16_main_tile_m(sh) || n < bf16_main_tile_n(sh)) return -1;
                 return bf16_main_cost(sh, m, n, K);
             }, (int64_t)4000 * 256);
