@@ -117,8 +117,8 @@ def mfma_ceiling(w, lib, torch, inputs, launches=120):
             "ms_median": tail[len(tail) // 2]}
 
 
-def time_workload(w, lib, torch, steps, warmup):
-    """Warm up, then time exactly `steps` calls: wall clock around the whole region
+def time_workload(w, lib, torch, steps, warmup, settle=True):
+    """Let the clocks settle, warm up, then time exactly `steps` calls: wall clock around the whole region
     (synchronised on both sides) and a HIP event pair around every launch."""
     fn = lib.gemm_f32 if w["kind"] == "f32" else lib.gemm_bf16
     stream = torch.cuda.current_stream().cuda_stream
@@ -128,6 +128,21 @@ def time_workload(w, lib, torch, steps, warmup):
         a, b, c = sets[i % len(sets)]
         lib.check(fn(w["M"], w["N"], w["K"], a, w["lda"], b, w["ldb"], c, w["ldc"], stream))
 
+    # The device has idled while the host prepared operands and checked results, and its clocks take tens of launches to
+    # come back (a cold device's first launches of the bf16 workload are 20 % slower).  Untimed launches of the workload
+    # itself, in blocks of 10, until a block is no faster than the one before (within 0.5 %), at most 20 blocks: what
+    # follows -- the warm-up the caller asked for and the timed steps -- then runs at the clocks this workload sustains.
+    settle_blocks = []
+    while settle and len(settle_blocks) < 20:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(10):
+            call(i)
+        e1.record()
+        torch.cuda.synchronize()
+        settle_blocks.append(e0.elapsed_time(e1) / 10)
+        if len(settle_blocks) >= 2 and settle_blocks[-1] >= 0.995 * settle_blocks[-2]:
+            break
     for i in range(warmup):
         call(i)
     torch.cuda.synchronize()
@@ -147,7 +162,8 @@ def time_workload(w, lib, torch, steps, warmup):
     warm = steady_ms(torch, lambda: call(0))
     return dict(wall_ms_per_step=wall_ms / steps, launch_ms_avg=sum(per) / len(per),
                 launch_ms_median=per[len(per) // 2], launch_ms_min=per[0], launch_ms_max=per[-1],
-                launch_ms_first_5=sum(head) / len(head), launch_ms_last_5=sum(tail) / len(tail), launch_ms_same_buffers=warm)
+                launch_ms_first_5=sum(head) / len(head), launch_ms_last_5=sum(tail) / len(tail), launch_ms_same_buffers=warm,
+                settle_ms_per_launch_by_block=settle_blocks)
 
 
 def report(w, t, lib, ceiling):
@@ -162,7 +178,10 @@ def report(w, t, lib, ceiling):
         # the timed launches in order: a device that was still ramping its clocks shows first_5 above last_5
         launch_ms={"avg": t["launch_ms_avg"], "median": t["launch_ms_median"], "min": t["launch_ms_min"], "max": t["launch_ms_max"],
                    "first_5": t["launch_ms_first_5"], "last_5": t["launch_ms_last_5"],
-                   "same_buffers_median": t["launch_ms_same_buffers"]},
+                   "same_buffers_median": t["launch_ms_same_buffers"],
+                   # untimed launches in front of the warm-up, in blocks of 10 (ms per launch of each block), that bring an
+                   # idle device's clocks to what this workload sustains
+                   "settle_blocks_of_10": t["settle_ms_per_launch_by_block"]},
         roofline={"bound": "mfma", "kernel": q(w["M"], w["N"], w["K"], a, w["lda"], b, w["ldb"], c, w["ldc"]),
                   "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                   # a register-only loop of the kernel's MFMA on the same kind of data, whole chip, measured in this
@@ -508,8 +527,9 @@ def main():
                     help="which headline workload fills the top-level fields (both are always measured)")
     ap.add_argument("--no-validate", action="store_true", help="skip the oracle sweep (profiling runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-ceiling", action="store_true",
-                    help="skip the register-only MFMA loops that run around each headline workload (a short one in front, which brings an idle device's clocks up, the measured one behind)")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the register-only MFMA loop that is measured behind each headline workload")
+    ap.add_argument("--no-settle", action="store_true",
+                    help="skip the untimed launches in front of the warm-up that bring an idle device's clocks up (counter runs: fewer dispatches)")
     ap.add_argument("--headline-only", action="store_true",
                     help="time the two headline workloads only (profiling runs: keeps other shapes out of the kernel trace)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -540,13 +560,9 @@ def main():
         log("profiler: %s" % name)
         w = make_workload(name, torch, inputs)
         chk = None if args.no_validate else validator.check_headline(w, lib, torch)
-        # The device has idled while the host prepared operands and checked results: a short run of the register-only
-        # MFMA loop brings its clocks up (30 launches, about 30 ms), then the workload's own warm-up and the timed
-        # steps follow at once.  The loop's own rate is measured after the timed region, over 120 launches: run in
-        # front, that long a stretch at the chip's highest power draw leaves the next 20 ms measurably slower.
-        if not args.no_ceiling:
-            mfma_ceiling(w, lib, torch, inputs, launches=30)
-        t = time_workload(w, lib, torch, args.steps, args.warmup)
+        # The register-only MFMA loop's rate is measured after the timed region, over 120 launches: run in front, that
+        # long a stretch at the chip's highest power draw leaves the next 20 ms measurably slower.
+        t = time_workload(w, lib, torch, args.steps, args.warmup, settle=not args.no_settle)
         ceiling = None if args.no_ceiling else mfma_ceiling(w, lib, torch, inputs)
         results[name] = report(w, t, lib, ceiling)
         results[name]["oracle_check"] = chk
