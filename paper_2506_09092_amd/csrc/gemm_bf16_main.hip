@@ -39,16 +39,20 @@
 // loop's back edge and fills the loop with hundreds of accumulator moves.  With
 // "+a" operands every block stays where it is.  The compiler cannot see that
 // these statements are MFMAs, so the hazards it would cover are kept away by
-// construction: a block is touched again only 64 MFMAs later, and the epilogue
-// starts behind explicit wait states.
+// construction: a block's two MFMAs of a K-tile follow each other directly with
+// the same accumulator registers as result and addend (the one dependence the
+// matrix core resolves itself; see ChainPlan below for why they are paired),
+// the block is touched again only a K-tile later, and the epilogue starts
+// behind explicit wait states.
 //
-// Per K-tile t of parity P (stage X = P holds t, Y = 1 - P receives t+1):
-//   k-step 0 : MFMAs on X's first half; fragment reads of X's second half; the
-//              late loads of K-tile t+1 into Y; the prefetch touch
+// Per K-tile t of parity P (stage X = P holds t, Y = 1 - P receives t+1), all
+// fragments of t being in registers or on their way when it starts:
+//   first half : MFMAs; the last fragment reads of X (into registers K-tile t-1
+//              has freed); the late loads of K-tile t+1 into Y; the prefetch touch
 //   barrier  : all loads but the touch have landed (Y complete), every
-//              wavefront has its last fragments of X in registers
-//   k-step 1 : MFMAs on X's second half; fragment reads of Y's first half; the
-//              early loads of K-tile t+2 into X
+//              wavefront has all fragments of X in registers
+//   second half : MFMAs; fragment reads of Y (K-tile t+1) into the registers this
+//              K-tile has freed; the early loads of K-tile t+2 into X
 // A load thus has at least half a K-tile (about 1000 cycles) to arrive: enough
 // for an L2 hit, not for a first touch that has to come over the fabric.  Each
 // workgroup therefore also touches, three K-tiles ahead, its share of the
