@@ -186,9 +186,9 @@ int gemm_bf16_ws(int transA, int transB,
  *               sums (both operands stored with k as the row index: transA != 0 or M == 1, transB == 0 or N == 1; M, N <= 16 with
  *               at most 144 entries after rounding both up to multiples of 4; K > 0), whose
  *               k_slices are workgroups (1..256, at most K) that each keep a partial result in the workspace, so it
- *               needs its workspace even for one, 5..13 = the direct-to-LDS kernel with tiles 256 x 256, 192 x 256,
- *               128 x 256, 256 x 128, 192 x 128, 128 x 128, 256 x 192, 192 x 192, 128 x 192
- *               (fsrgemm_tile_count_f32() = 14);
+ *               needs its workspace even for one, 5..16 = the direct-to-LDS kernel with tiles 256 x 256, 192 x 256,
+ *               128 x 256, 256 x 128, 192 x 128, 128 x 128, 256 x 192, 192 x 192, 128 x 192, 64 x 64, 128 x 64,
+ *               64 x 128 (fsrgemm_tile_count_f32() = 17);
  *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64, 4 = the streaming
  *               kernels for M == 1 or N == 1 with K > 0, 5..9 = the direct-to-LDS kernel with tiles 192 x 256,
  *               128 x 256, 256 x 192, 192 x 192, 256 x 128 (fsrgemm_tile_count_bf16() = 10).
@@ -199,7 +199,7 @@ int gemm_bf16_ws(int transA, int transB,
  * count out of range, a split without a fitting workspace, fp32 candidate 3 or bf16 candidate 4 on a product
  * without a vector,
  * fp32 candidate 4 on a result that is too large,
- * fp32 tiles 5..13 with a split or where their kernel's conditions fail (M, N at least one tile, K >= 32 and a
+ * fp32 tiles 5..16 with a split or where their kernel's conditions fail (M, N at least one tile, K >= 32 and a
  * multiple of 4, 16-byte aligned operands with leading dimensions that are multiples of 4 and below 2^24;
  * M or N a multiple of 4 for an operand contiguous along it),
  * bf16 tiles 0 and 5..9 with a split or where their kernel's

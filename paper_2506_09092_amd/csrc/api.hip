@@ -113,10 +113,12 @@ int mode_f32(int cfg, int slices, int64_t M, int64_t N, int64_t K, const float *
 // (256 compute units; a last round with few tiles costs a whole one), and never less than the time of one
 // workgroup running alone.  Times per tile and k step, in units of 0.1 ns, measured on square problems with
 // each configuration forced: 256 x 128: 1137, 128 x 128: 569, 64 x 64: 169 with several workgroups per compute
-// unit, 221 alone.  K cancels.  Equal costs go to the larger tile.  The direct-to-LDS kernel runs one workgroup
-// per compute unit; its shapes (main_fits: bit s set if shape s can take the problem) enter with their own tile
-// times and win where their tiles fill whole rounds.
-constexpr int64_t kMainTileTime[kF32MainShapes] = {2230, 1710, 1120, 1120, 838, 566, 1715, 1286, 845};   // in the order of the shapes
+// unit, 221 alone.  K cancels.  Equal costs go to the larger tile.  The shapes of the direct-to-LDS kernel (main_fits:
+// bit s set if shape s can take the problem) enter with their own tile times and win where their tiles fill whole
+// rounds; its tiles with a side of 64 (148 / 290 / 300 for 64 x 64, 128 x 64, 64 x 128: within 7 % of the 256 x 256
+// tile's time per flop, several workgroups sharing a compute unit) take the problems of 1024 ... 2560 rows that the
+// general 64 x 64 tile ran before.
+constexpr int64_t kMainTileTime[kF32MainShapes] = {2230, 1710, 1120, 1120, 838, 566, 1715, 1286, 845, 148, 290, 300};   // in the order of the shapes
 int tile_rule_f32(int64_t M, int64_t N, unsigned main_fits, int64_t *cost_out = nullptr)
 {
     constexpr int64_t kTileTime[kF32ConfigCount] = {1137, 569, 169}, kAlone[kF32ConfigCount] = {1137, 569, 221};
@@ -176,7 +178,7 @@ Bands best_bands(const BandsKey &key, int shapes, Cost cost, int64_t launch_gap)
     for (int dim = 1; dim <= 2; ++dim) {
         const int64_t ext = dim == 1 ? M : N;
         const int64_t step = 64 * ceil_div(ext, 64 * 256);
-        for (int64_t at = 128; at + 128 <= ext; at += step) {
+        for (int64_t at = 64; at + 64 <= ext; at += step) {
             int s1 = -1, s2 = -1;
             int64_t c1 = 0, c2 = 0;
             for (int sh = 0; sh < shapes; ++sh) {

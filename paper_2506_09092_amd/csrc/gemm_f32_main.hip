@@ -47,7 +47,9 @@
 // Tile shapes.  A launch lasts as long as the compute unit with the most tiles, so a problem whose 256 x 256 tiles
 // do not fill whole rounds of the 256 compute units is better off with a smaller tile that does: the kernel is a
 // template over the blocks per wavefront, WM x WN of 32 x 32 (tile 64 WM x 64 WN), instantiated for the nine shapes
-// with sides of 256, 192 and 128.  Loads per wavefront and K-tile: 2 WM + 2 WN.
+// with sides of 256, 192 and 128 and for 64 x 64, 128 x 64 and 64 x 128, which small problems need to give every
+// compute unit a tile (several of these small workgroups share a compute unit: 32 to 48 KB of LDS and under 100
+// registers each).  Loads per wavefront and K-tile: 2 WM + 2 WN.
 #include <stdio.h>
 
 #include <type_traits>
@@ -166,7 +168,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     float fa[2][WM][4], fb[2][WN][4];       // [register buffer][block][step]
     constexpr int kReadsA = ALAY == kKContig ? WM : 4 * WM, kReadsB = BLAY == kKContig ? WN : 4 * WN;
     constexpr int kReads = kReadsA + kReadsB;
-    static_assert(kReads <= kMfmas && 2 * kLoads <= kMfmas, "a chunk has a slot per fragment read and two per load");
+    // A chunk has a slot behind each MFMA.  The larger shapes put one fragment read behind an MFMA and the loads behind
+    // every second MFMA at the end of chunk 3; tiles with a side of 64 have 4 to 8 MFMAs per chunk, so they take up to
+    // two reads behind one MFMA and a load behind every MFMA (a 64-cycle MFMA still covers them).
+    constexpr int kReadsPerSlot = (kReads + kMfmas - 1) / kMfmas, kLoadStride = 2 * kLoads <= kMfmas ? 2 : 1;
+    static_assert(kReadsPerSlot <= 2 && kLoadStride * kLoads <= kMfmas, "slots of a chunk");
     auto fragment = [&](auto layout, auto extent, auto blocks, const char *st, int offset, int c, auto &f, int idx) {
         constexpr int LAY = decltype(layout)::value, EXT = decltype(extent)::value, W = decltype(blocks)::value;
         if constexpr (LAY == kKContig) {
@@ -210,23 +216,24 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
 
     auto k_tile = [&](auto parity, int t) {
         constexpr int X = decltype(parity)::value, Y = 1 - X;
-        constexpr int kFirstLoadSlot = kMfmas - 2 * kLoads;         // the loads sit behind every second MFMA at the end of chunk 3
+        constexpr int kFirstLoadSlot = kMfmas - kLoadStride * kLoads;         // the loads sit behind every second MFMA (every MFMA) at the end of chunk 3
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int cur = c & 1, nxt = cur ^ 1;
 #pragma unroll
             for (int m = 0; m < kMfmas; ++m) {
                 const int s = m / (WM * WN), i = (m / WN) % WM, j = m % WN;
-                const bool loads = c == 3 && m >= kFirstLoadSlot && !((m - kFirstLoadSlot) & 1);
-                if (loads) load_m0(X, (m - kFirstLoadSlot) >> 1);
+                const bool loads = c == 3 && m >= kFirstLoadSlot && (m - kFirstLoadSlot) % kLoadStride == 0;
+                if (loads) load_m0(X, (m - kFirstLoadSlot) / kLoadStride);
                 {
                     const float av = fa[cur][i][s], bv = fb[cur][j][s];
                     asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(av), "v"(bv));
                 }
-                if (loads) load_go((m - kFirstLoadSlot) >> 1, t + 2);
-                if (m < kReads) {
-                    if (c < 3) read(X, c + 1, nxt, m);
-                    else read(Y, 0, nxt, m);
+                if (loads) load_go((m - kFirstLoadSlot) / kLoadStride, t + 2);
+#pragma unroll
+                for (int r = kReadsPerSlot * m; r < kReadsPerSlot * (m + 1) && r < kReads; ++r) {
+                    if (c < 3) read(X, c + 1, nxt, r);
+                    else read(Y, 0, nxt, r);
                 }
                 FENCE();
             }
@@ -339,8 +346,8 @@ hipError_t launch_shape(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
     return b_lay == kKContig ? launch_main<WM, WN, kMnContig, kKContig>(a, s) : launch_main<WM, WN, kMnContig, kMnContig>(a, s);
 }
 
-// in the order of the candidate numbers: the first six were there first
-constexpr int kShapeM[kF32MainShapes] = {256, 192, 128, 256, 192, 128, 256, 192, 128}, kShapeN[kF32MainShapes] = {256, 256, 256, 128, 128, 128, 192, 192, 192};
+// in the order of the candidate numbers, which is the order the shapes were added in
+constexpr int kShapeM[kF32MainShapes] = {256, 192, 128, 256, 192, 128, 256, 192, 128, 64, 128, 64}, kShapeN[kF32MainShapes] = {256, 256, 256, 128, 128, 128, 192, 192, 192, 64, 64, 128};
 
 }  // namespace
 
@@ -393,7 +400,10 @@ hipError_t launch_f32_main(int shape, int a_lay, int b_lay, const GemmArgs &a, h
     case 5: return launch_shape<2, 2>(a_lay, b_lay, a, s);
     case 6: return launch_shape<4, 3>(a_lay, b_lay, a, s);
     case 7: return launch_shape<3, 3>(a_lay, b_lay, a, s);
-    default: return launch_shape<2, 3>(a_lay, b_lay, a, s);
+    case 8: return launch_shape<2, 3>(a_lay, b_lay, a, s);
+    case 9: return launch_shape<1, 1>(a_lay, b_lay, a, s);
+    case 10: return launch_shape<2, 1>(a_lay, b_lay, a, s);
+    default: return launch_shape<1, 2>(a_lay, b_lay, a, s);
     }
 }
 

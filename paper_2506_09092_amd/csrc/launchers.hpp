@@ -103,10 +103,11 @@ bool skinny_offsets_fit(const SkinnyArgs &a);
 const char *skinny_kernel_name(int M, int N, const float *A, int64_t lda, const float *B, int64_t ldb);
 hipError_t launch_skinny_f32(const SkinnyArgs &a, float *C, int64_t ldc, hipStream_t s);
 
-// fp32 direct-to-LDS kernel for large aligned problems (gemm_f32_main.hip), no K slices: nine tile shapes -- 256 x 256,
-// 192 x 256, 128 x 256, 256 x 128, 192 x 128, 128 x 128, 256 x 192, 192 x 192, 128 x 192 -- in the four layout pairs
+// fp32 direct-to-LDS kernel for aligned problems (gemm_f32_main.hip), no K slices: twelve tile shapes -- 256 x 256,
+// 192 x 256, 128 x 256, 256 x 128, 192 x 128, 128 x 128, 256 x 192, 192 x 192, 128 x 192, 64 x 64, 128 x 64, 64 x 128 -- in
+// the four layout pairs
 constexpr int kF32_Main = kF32_Skinny + 1;          // candidate number of the first shape, after the small-result kernel
-constexpr int kF32MainShapes = 9;
+constexpr int kF32MainShapes = 12;
 int f32_main_tile_m(int shape);
 int f32_main_tile_n(int shape);
 bool f32_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb);

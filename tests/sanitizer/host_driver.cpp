@@ -22,7 +22,7 @@ int main()
     const uintptr_t offs[] = {0, 0, 1, 2, 4};
     const uintptr_t P = 0x1000;
     const int n32 = fsrgemm_tile_count_f32(), n16 = fsrgemm_tile_count_bf16();
-    CHECK(n32 == 14 && n16 == 10 && fsrgemm_version() >= 200);
+    CHECK(n32 == 17 && n16 == 10 && fsrgemm_version() >= 200);
     long plans = 0, names = 0;
     for (int c = 0; c < 20000; ++c) {
         const int ta = (int)(next() & 1), tb = (int)(next() & 1);
@@ -39,6 +39,13 @@ int main()
                 if (rc != FSRGEMM_OK) continue;
                 ++plans;
                 CHECK(tile >= 0 && tile < (bf16 ? n16 : n32) && slices >= 1 && slices <= 256);
+                // the same plan in terms of bands: one launch, or a cut at a multiple of 64 strictly inside C
+                int dim = -7, first = -7, second = -7;
+                int64_t at = -7;
+                CHECK((bf16 ? fsrgemm_bands_bf16(ta, tb, M, N, K, (const uint16_t *)a, lda, (const uint16_t *)b, ldb, flags, &dim, &at, &first, &second)
+                            : fsrgemm_bands_f32(ta, tb, M, N, K, (const float *)a, lda, (const float *)b, ldb, flags, &dim, &at, &first, &second)) == FSRGEMM_OK);
+                CHECK(first == tile && second >= 0 && second < (bf16 ? n16 : n32));
+                CHECK(dim == 0 ? (at == 0 && second == first) : ((dim == 1 || dim == 2) && at % 64 == 0 && at > 0 && at < (dim == 1 ? M : N) && slices == 1));
                 if (M > 0 && N > 0 && M * N < (1ll << 40)) {
                     const char *nm = bf16 ? fsrgemm_kernel_for_bf16_cfg(tile, ta, tb, M, N, K, (const uint16_t *)a, lda, (const uint16_t *)b, ldb, cptr, ldc)
                                           : fsrgemm_kernel_for_f32_cfg(tile, ta, tb, M, N, K, (const float *)a, lda, (const float *)b, ldb, cptr, ldc);

@@ -172,10 +172,11 @@ def test_workspace_query_and_argument_checks():
 
 def test_f32_tile_rule_follows_the_round_model():
     # fewest rounds of 256 tiles, weighted by the tile's time; sizes where the configurations win in turn.  The
-    # direct-to-LDS kernel (5..13: tiles with sides of 256, 192 and 128) enters where it fits
+    # direct-to-LDS kernel (5..16: tiles with sides of 256, 192, 128 and 64) enters where it fits
     # (aligned operands, whole K-tiles of 32) with the shape whose tiles fill whole rounds
     pf = lambda n, a=P, K=None: lib.fsrgemm_plan_f32(0, 0, n, n, K or n, a, K or n, P, n)[0]
-    assert [pf(n) for n in (1024, 2048, 3072, 4096, 6144, 8192)] == [2, 10, 12, 5, 9, 5]
+    assert [pf(n) for n in (1024, 2048, 3072, 4096, 6144, 8192)] == [14, 10, 12, 5, 9, 5]
+    assert pf(1024, P + 4) == 2 and pf(2560) == 14 and lib.fsrgemm_plan_f32(0, 0, 1024, 2048, 4096, P, 4096, P, 2048)[0] == 15
     assert [pf(n, P + 4) for n in (4096, 8192)] == [0, 0] and pf(4096, K=4112) == 5      # misaligned A: the general kernel; a rest of K: the same tile
     assert lib.fsrgemm_plan_f32(0, 0, 4096, 4096, 4110, P, 4112, P, 4096)[0] == 0 and pf(4096, K=16) == 0     # K not a multiple of 4, K below a K-tile
     assert lib.fsrgemm_plan_f32(0, 0, 10, 100000, 64, P, 64, P, 100000)[0] == 2          # a sliver: small tiles waste least
@@ -196,9 +197,9 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
 
 def test_forced_configurations_and_plan_queries():
     bad, ok = lib.FSRGEMM_ERR_INVALID_ARG, lib.FSRGEMM_OK
-    assert lib.fsrgemm_tile_count_f32() == 14 and lib.fsrgemm_tile_count_bf16() == 10
+    assert lib.fsrgemm_tile_count_f32() == 17 and lib.fsrgemm_tile_count_bf16() == 10
     f = lambda tile, s, ws=None, wsb=0, M=64, N=64, K=4096: lib.gemm_f32_cfg(tile, s, 0, 0, M, N, K, P, K, P, N, P, N, ws, wsb, 0)
-    assert f(-1, 1) == bad and f(14, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
+    assert f(-1, 1) == bad and f(17, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
     assert f(3, 1) == bad and f(3, 1, K=0, M=1) == bad                          # the vector kernels need M or N = 1 and K > 0
     assert f(2, 4) == bad and f(2, 4, P, 4 * 64 * 64 * 4 - 1) == bad            # a split without / with too small a workspace
     assert f(2, 4, P + 2, 1 << 20) == bad                                      # misaligned workspace
@@ -263,9 +264,9 @@ def test_forced_configurations_and_plan_queries():
     assert lib.fsrgemm_kernel_for_f32(4096, 4096, 4096, P, 4096, P, 4096, P, 4096) == "gemm_f32_main_kernel<4, 4, 0, 1>"
     # plan queries: the rules, in the terms of the forced calls
     pf, pb = lib.fsrgemm_plan_f32, lib.fsrgemm_plan_bf16
-    assert pf(0, 0, 4096, 4096, 4096, P, 4096, P, 4096) == (5, 1) and pf(0, 0, 200, 200, 200, P, 200, P, 200) == (2, 1)
+    assert pf(0, 0, 4096, 4096, 4096, P, 4096, P, 4096) == (5, 1) and pf(0, 0, 200, 200, 200, P, 200, P, 200) == (14, 1) and pf(0, 0, 200, 200, 202, P, 202, P, 200) == (2, 1)
     assert pf(0, 0, 64, 64, 1 << 20, P, 1 << 20, P, 64, True)[0] == 2 and pf(0, 0, 64, 64, 1 << 20, P, 1 << 20, P, 64, True)[1] > 1
-    assert pf(0, 0, 64, 64, 1 << 20, P, 1 << 20, P, 64, False) == (2, 1)
+    assert pf(0, 0, 64, 64, 1 << 20, P, 1 << 20, P, 64, False) == (14, 1)
     assert pb(0, 1, 8192, 8192, 8192, P, 8192, P, 8192) == (0, 1)
     assert pb(0, 1, 8192, 8192, 8200, P, 8200, P, 8200) == (0, 1)              # a rest of K in whole 16-byte pieces: still the direct-to-LDS kernel
     assert pb(0, 1, 8192, 8192, 8196, P, 8200, P, 8200) == (1, 1)              # otherwise the general kernel of that tile
@@ -424,7 +425,7 @@ def test_f32_direct_to_lds_kernel_is_not_planned_beyond_its_32_bit_lane_offsets(
     assert qx(1, 0, n, n, n, P, big, P, n, P, n).startswith("gemm_f32_kernel<")
     assert qx(1, 1, n, n, n, P, n, P, big, P, n).startswith("gemm_f32_kernel<")
     # forced: rejected, not replaced
-    for tile in range(5, 14):       # (rejected before any launch: the addresses are fake)
+    for tile in range(5, 17):       # (rejected before any launch: the addresses are fake)
         assert lib.gemm_f32_cfg(tile, 1, 0, 0, n, n, n, P, big, P, n, P, n, None, 0, 0) == lib.FSRGEMM_ERR_INVALID_ARG
         assert lib.fsrgemm_kernel_for_f32_cfg(tile, 0, 0, n, n, n, P, n, P, big, P, n) is None
     assert lib.fsrgemm_plan_f32(0, 0, n, n, n, P, big, P, n)[0] < 3
@@ -472,13 +473,13 @@ def _band_problems(kind, ta, tb, M, N, K, a, lda, b, ldb, dim, at):
 
 def test_two_band_plans():
     # where no tile shape fills whole rounds of the 256 compute units the dispatcher cuts C once and gives each band its own
-    # shape: 5120^2 as rows 0..1471 in 128 x 256 tiles (240 = one round) + the rest in 192 x 128 tiles (760 = three rounds)
-    # instead of 729 tiles of 192 x 192 (2.85 -> 3 rounds of a larger tile); fp32 candidates: 5 + shape
+    # shape: 5120^2 as rows 0..1023 in 64 x 64 tiles (1280 = five rounds) + the rest in 128 x 128 tiles (1280 = five rounds of
+    # a tile of four times the work) instead of 729 tiles of 192 x 192 (2.85 -> 3 rounds); fp32 candidates: 5 + shape
     bf = lambda M, N, K, a=P, **kw: lib.fsrgemm_bands_f32(0, 0, M, N, K, a, K, P, N, **kw)
-    assert bf(5120, 5120, 2048) == (1, 1472, 7, 9)
-    assert lib.fsrgemm_plan_f32(0, 0, 5120, 5120, 2048, P, 2048, P, 5120) == (7, 1)            # the first band's tile
+    assert bf(5120, 5120, 2048) == (1, 1024, 14, 10)
+    assert lib.fsrgemm_plan_f32(0, 0, 5120, 5120, 2048, P, 2048, P, 5120) == (14, 1)            # the first band's tile
     name = lib.fsrgemm_kernel_for_f32(5120, 5120, 2048, P, 2048, P, 5120, P, 5120)
-    assert name == "gemm_f32_main_kernel<2, 4, 0, 1> + gemm_f32_main_kernel<3, 2, 0, 1> (rows from 1472)"
+    assert name == "gemm_f32_main_kernel<1, 1, 0, 1> + gemm_f32_main_kernel<2, 2, 0, 1> (rows from 1024)"
     # whole rounds in one launch stay one launch; so do misaligned operands (no direct-to-LDS kernel), table rows and splits
     assert bf(4096, 4096, 4096) == (0, 0, 5, 5) and bf(6144, 6144, 2048) == (0, 0, 9, 9) and bf(1024, 1024, 1024)[0] == 0
     assert bf(5120, 5120, 2048, a=P + 4)[0] == 0

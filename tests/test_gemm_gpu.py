@@ -327,7 +327,8 @@ def test_bf16_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
 @pytest.mark.parametrize("shape,kernel", [((4000, 2040, 64), "gemm_f32_main_kernel<2, 4, 0, 1>"),
                                           ((4000, 2040, 80), "gemm_f32_main_kernel<2, 4, 0, 1>"),          # and a rest of K
                                           ((2040, 2030, 48), "gemm_f32_kernel<2, 2, 3, 0, 0, 1>"),
-                                          ((1000, 1000, 1008), "gemm_f32_kernel<1, 1, 4, 0, 0, 1>"),
+                                          ((1000, 1000, 1008), "gemm_f32_main_kernel<1, 1, 0, 1>"),
+                                          ((1000, 1000, 1010), "gemm_f32_kernel<1, 1, 4, 2, 0, 1>"),          # rows of A that are not whole pieces: the general tile
                                           ((65, 129, 32), "gemm_f32_kernel<1, 1, 4, 0, 0, 1>")])
 def test_f32_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
     M, N, K = shape
@@ -367,16 +368,17 @@ def test_f32_tile_configs_small_k(gpu, shape, tile, kernel):
         assert np.array_equal(run_cfg(gpu, "f32", tile, 1, 0, 0, Ai, Bi).astype(np.float64), oracle.gemm(Ai, Bi)[0])
 
 
-MAIN_SHAPES = {5: (256, 256), 6: (192, 256), 7: (128, 256), 8: (256, 128), 9: (192, 128), 10: (128, 128),        # fp32 candidates 5..13
-               11: (256, 192), 12: (192, 192), 13: (128, 192)}
+MAIN_SHAPES = {5: (256, 256), 6: (192, 256), 7: (128, 256), 8: (256, 128), 9: (192, 128), 10: (128, 128),        # fp32 candidates 5..16
+               11: (256, 192), 12: (192, 192), 13: (128, 192), 14: (64, 64), 15: (128, 64), 16: (64, 128)}
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0)] + LAYOUTS)
 @pytest.mark.parametrize("shape", [(512, 768, 32), (512, 512, 64), (768, 512, 96), (256, 256, 224),     # whole tiles, 1 / 2 / 3 / 7 K-tiles
                                    (520, 392, 128), (264, 1284, 64), (1000, 260, 160),                  # shifted last tiles
-                                   (512, 512, 44), (520, 392, 100), (384, 388, 60), (256, 512, 36)])    # a rest of K behind 1 / 3 / 1 / 1 K-tiles
+                                   (512, 512, 44), (520, 392, 100), (384, 388, 60), (256, 512, 36),     # a rest of K behind 1 / 3 / 1 / 1 K-tiles
+                                   (64, 64, 32), (68, 132, 72), (196, 64, 164)])                        # the tiles with a side of 64 only
 def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
-    # the direct-to-LDS fp32 kernel in its nine tile shapes, forced: prologue, odd / even tails, the clamped loads two
+    # the direct-to-LDS fp32 kernel in its twelve tile shapes, forced: prologue, odd / even tails, the clamped loads two
     # K-tiles ahead, operands contiguous along k and along m / n, padded leading dimensions, small integers
     M, N, K = shape
     lda, ldb = (M if ta else K), (K if tb else N)
@@ -805,6 +807,11 @@ def test_calls_captured_in_a_hip_graph_replay_bit_exact(gpu):
     calls.append(lambda: gpu.gemm_f32_cfg(12, 1, 0, 0, 400, 388, 96, am, 96, bm_, 388, om[0], 388, None, 0, stream()))
     calls.append(lambda: gpu.gemm_f32_cfg(9, 1, 0, 0, 400, 388, 96, am, 96, bm_, 388, om[1], 388, None, 0, stream()))
     outs.append(om)
+    # a product the dispatcher runs as two bands of C: two launches behind one call
+    ab, bb, ob = torch.randn(3584, 1024, device="cuda"), torch.randn(1024, 3584, device="cuda"), torch.empty(3584, 3584, device="cuda")
+    assert gpu.fsrgemm_bands_f32(0, 0, 3584, 3584, 1024, ab, 1024, bb, 3584)[0] != 0
+    calls.append(lambda: gpu.gemm_f32(3584, 3584, 1024, ab, 1024, bb, 3584, ob, 3584, stream()))
+    outs.append(ob)
     t_in, t_out = torch.randn(300, 700, device="cuda"), torch.empty(700, 300, device="cuda")
     calls.append(lambda: gpu.transpose_f32(300, 700, t_in, 700, t_out, 300, stream()))
     outs.append(t_out)
@@ -1239,7 +1246,7 @@ P_FAKE = 0x1000      # an aligned address for the plan queries (never dereferenc
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
-@pytest.mark.parametrize("shape", [(5120, 5120, 512), (3584, 3592, 772), (7168, 7168, 512)])
+@pytest.mark.parametrize("shape", [(5000, 5120, 512), (5120, 5000, 512), (3000, 7168, 772), (7168, 7168, 512)])
 def test_f32_two_band_products(gpu, shape, ta, tb):
     # problems the dispatcher runs as two bands of C, each in its own tile shape (a cut along the rows, one along the
     # columns, a ragged N and a rest of K among them): the whole result against the oracle, bit for bit against the
