@@ -308,7 +308,9 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
         if (t && t->tile >= kF32_Main && (!(main_fits >> (t->tile - kF32_Main) & 1) || t->slices > 1)) t = nullptr;    // a row for operands aligned otherwise
         // a split runs on 64 x 64 tiles, or on 128 x 128 ones where those still give every compute unit a workgroup
         // and a slice keeps at least 1024 k (10-17 % faster there, measured on 256^2 ... 1024^2 with K up to 65536)
-        const bool split128 = p->slices > 1 && ceil_div(M, 128) * ceil_div(N, 128) * p->slices >= 240 && K / p->slices >= 1024;
+        // (not for a sliver of a few rows or columns, most of whose 128-wide tile would be padding: 8 x 8192 x 8192 runs 57 %
+        // faster on 64 x 64 tiles)
+        const bool split128 = p->slices > 1 && ceil_div(M, 128) * ceil_div(N, 128) * p->slices >= 240 && K / p->slices >= 1024 && M >= 96 && N >= 96;
         int64_t one_cost = 0;
         p->cfg = t ? t->tile : p->slices > 1 ? (split128 ? kF32_128x128 : kF32_64x64) : tile_rule_f32(M, N, main_fits, &one_cost);
         // one launch leaves compute units idle in its last round: try two bands of direct-to-LDS shapes (tile times in

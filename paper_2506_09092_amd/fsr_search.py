@@ -15,6 +15,7 @@ import collections
 
 Problem = collections.namedtuple("Problem", "kind transA transB M N K")          # kind: "f32" | "bf16"
 Candidate = collections.namedtuple("Candidate", "tile slices")
+Bands = collections.namedtuple("Bands", "dim at first second")     # a two-band plan of the dispatcher (fsrgemm_bands_*)
 
 MAX_SLICES = 64
 
@@ -136,8 +137,32 @@ class DeviceBackend:
         # the dispatcher's choice with / without a workspace, and what its rules alone would take
         self.start, self.start_unsplit = Candidate(*plan(*args, True)), Candidate(*plan(*args, False))
         self.rules, self.rules_unsplit = Candidate(*plan(*args, True, True)), Candidate(*plan(*args, False, True))
+        # where the rules run the product as two bands of C (one forced call each), that plan: (dim, at, first tile,
+        # second tile) with dim 1 = rows, 2 = columns, at = the cut; None where they launch once
+        bands = lib.fsrgemm_bands_f32 if p.kind == "f32" else lib.fsrgemm_bands_bf16
+        two = lambda with_ws: (lambda b: Bands(*b) if b[0] else None)(bands(*args, with_ws, True))
+        self.rules_bands, self.rules_bands_unsplit = two(True), two(False)
 
-    def _call(self, c: Candidate, s: int) -> int:
+    def _call_bands(self, bd: "Bands", s: int) -> int:
+        """The two forced calls of a two-band plan: each band is a product of its own on shifted operands."""
+        p, (a, b, out) = self.p, self.sets[s]
+        es = 4 if p.kind == "f32" else 2
+        pa, pb, pc = a.data_ptr(), b.data_ptr(), out.data_ptr()
+        stream = self.torch.cuda.current_stream().cuda_stream
+        if bd.dim == 1:
+            pa2, pb2, pc2 = pa + es * (bd.at if p.transA else bd.at * self.lda), pb, pc + 4 * bd.at * p.N
+            shapes = ((bd.at, p.N), (p.M - bd.at, p.N))
+        else:
+            pa2, pb2, pc2 = pa, pb + es * (bd.at * self.ldb if p.transB else bd.at), pc + 4 * bd.at
+            shapes = ((p.M, bd.at), (p.M, p.N - bd.at))
+        rc = self.fn(bd.first, 1, p.transA, p.transB, shapes[0][0], shapes[0][1], p.K, pa, self.lda, pb, self.ldb, pc, p.N, None, 0, stream)
+        if rc != self.lib.FSRGEMM_OK:
+            return rc
+        return self.fn(bd.second, 1, p.transA, p.transB, shapes[1][0], shapes[1][1], p.K, pa2, self.lda, pb2, self.ldb, pc2, p.N, None, 0, stream)
+
+    def _call(self, c, s: int) -> int:
+        if isinstance(c, Bands):
+            return self._call_bands(c, s)
         p, (a, b, out) = self.p, self.sets[s]
         return self.fn(c.tile, c.slices, p.transA, p.transB, p.M, p.N, p.K, a, self.lda, b, self.ldb, out, p.N,
                        *((self.ws, self.ws.numel()) if self.offer_workspace or c.slices > 1 else (None, 0)),
@@ -156,8 +181,8 @@ class DeviceBackend:
         self.torch.cuda.synchronize()
         return self.sets[0][2].cpu().numpy()
 
-    def latency(self, c: Candidate, samples: int = 7, min_ms: float = 0.2, warm_ms: float = 20.0) -> float:
-        """Median over `samples` timings of one launch in ms.  Short launches are timed as a run of launches that
+    def latency(self, c, samples: int = 7, min_ms: float = 0.2, warm_ms: float = 20.0) -> float:
+        """Median over `samples` timings of one call (a candidate, or a two-band plan) in ms.  Short launches are timed as a run of launches that
         lasts about min_ms, so that the gap between launches does not decide the ranking, and every candidate
         first runs for about warm_ms, so that the one measured first is not the one measured at idle clocks."""
         torch = self.torch

@@ -84,8 +84,11 @@ def tune(lib, torch, p: Problem, gain: float, log):
         best = r["best"]
         entry = dict(start=start, rules=rules, best=best, visited={"%d/%d" % k: v for k, v in r["visited"].items()})
         if best is not None and best != rules and be.runs(rules) and validator(be.output(rules)):
-            # the incumbent against the choice of the rules, measured again, both ways round; a row only for a clear gain
-            t_rules = min(be.latency(rules), be.latency(rules))
+            # the incumbent against the choice of the rules (their two-band plan where they make one), measured again,
+            # both ways round; a row only for a clear gain
+            as_run = (be.rules_bands if with_ws else be.rules_bands_unsplit) or rules
+            entry["rules_as_run"] = as_run
+            t_rules = min(be.latency(as_run), be.latency(as_run))
             t_best = max(be.latency(best), be.latency(best))
             entry.update(t_rules=t_rules, t_best=t_best)
             if t_best < (1 - gain) * t_rules:
