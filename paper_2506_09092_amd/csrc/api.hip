@@ -140,9 +140,9 @@ int tile_rule_f32(int64_t M, int64_t N, unsigned main_fits, int64_t *cost_out = 
 }
 
 // Two bands.  Where no tile shape fills whole rounds of the compute units, two launches often do: C is cut once, along
-// its rows or its columns, and each band takes the shape that suits its own tile count (5120^2: 729 tiles of 192 x 192
-// are 2.85 rounds; rows 0 .. 1471 as 240 tiles of 128 x 256 and the rest as 760 tiles of 192 x 128 are 1 + 3 rounds that
-// take 6 % less time).  The bands are independent products on shifted pointers, so nothing changes in a kernel and every
+// its rows or its columns, and each band takes the shape that suits its own tile count (fp32 5120^2: 729 tiles of
+// 192 x 192 are 2.85 rounds; rows 0 .. 1023 as 1280 tiles of 64 x 64 and the rest as 1280 tiles of 128 x 128 are five whole
+// rounds each and take 9 % less time).  The bands are independent products on shifted pointers, so nothing changes in a kernel and every
 // entry of C is still computed by one workgroup in the same order of summation.  cost(shape, m, n) is the modelled
 // time of an m x n band in that shape, negative where the shape cannot take it; cuts are multiples of 64 (every tile
 // side is one, and a cut then keeps the operands' alignment), at most 256 per direction.
