@@ -190,8 +190,8 @@ int gemm_bf16_ws(int transA, int transB,
  *               128 x 256, 256 x 128, 192 x 128, 128 x 128, 256 x 192, 192 x 192, 128 x 192, 64 x 64, 128 x 64,
  *               64 x 128 (fsrgemm_tile_count_f32() = 17);
  *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64, 4 = the streaming
- *               kernels for M == 1 or N == 1 with K > 0, 5..9 = the direct-to-LDS kernel with tiles 192 x 256,
- *               128 x 256, 256 x 192, 192 x 192, 256 x 128 (fsrgemm_tile_count_bf16() = 10).
+ *               kernels for M == 1 or N == 1 with K > 0, 5..10 = the direct-to-LDS kernel with tiles 192 x 256,
+ *               128 x 256, 256 x 192, 192 x 192, 256 x 128, 128 x 128 (fsrgemm_tile_count_bf16() = 11).
  *   k_slices: 1 = K in one piece; 2..64 = split along K as gemm_f32_ws does, which needs a workspace of
  *         k_slices * M * N * 4 bytes (4-byte aligned, at most 16 MiB) and k_slices <= ceil(K / 16) (fp32) or
  *         ceil(K / 64) (bf16).
@@ -202,7 +202,7 @@ int gemm_bf16_ws(int transA, int transB,
  * fp32 tiles 5..16 with a split or where their kernel's conditions fail (M, N at least one tile, K >= 32 and a
  * multiple of 4, 16-byte aligned operands with leading dimensions that are multiples of 4 and below 2^24;
  * M or N a multiple of 4 for an operand contiguous along it),
- * bf16 tiles 0 and 5..9 with a split or where their kernel's
+ * bf16 tiles 0 and 5..10 with a split or where their kernel's
  * conditions fail (M, N at least one tile, K >= 64 and a multiple of 8, 16-byte aligned operands with leading
  * dimensions that are multiples of 8 and below 2^25; an operand contiguous along m or n only with its side of the
  * tile at 256 and M or N a multiple of 8).  Every other

@@ -343,8 +343,9 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
 // 10240^2 x 4096, 16384 x 4096 x 4096); on a second sweep of 22 problems the rule's choice was the measured winner or
 // within 2 % of it on 20 (the others: 5 % on 7168^2 x 2048, 1.6 us on 4096^2 x 128).
 // Returns the shape, or -1 when none fits the problem (fits: bit s set if shape s can take it).
-constexpr int64_t kBf16MainPerKTile[kBf16MainShapes] = {1333, 1073, 780, 1037, 907, 808};      // in the order of the shapes
-constexpr int64_t kBf16MainPerRound[kBf16MainShapes] = {8700, 5800, 4700, 7700, 3700, 5200};
+constexpr int kBf16MainLarge = 6;        // the shapes this rule covers: those with a side of 256 or 192
+constexpr int64_t kBf16MainPerKTile[kBf16MainLarge] = {1333, 1073, 780, 1037, 907, 808};      // in the order of the shapes
+constexpr int64_t kBf16MainPerRound[kBf16MainLarge] = {8700, 5800, 4700, 7700, 3700, 5200};
 int64_t bf16_main_cost(int sh, int64_t M, int64_t N, int64_t K)       // in 1/256 ns
 {
     const int64_t tiles = ceil_div(M, bf16_main_tile_m(sh)) * ceil_div(N, bf16_main_tile_n(sh)), rest = tiles % 256;
@@ -355,7 +356,7 @@ int tile_rule_bf16_main(int64_t M, int64_t N, int64_t K, unsigned fits, int64_t 
 {
     int best = -1;
     int64_t best_cost = 0;
-    for (int sh = 0; sh < kBf16MainShapes; ++sh) {
+    for (int sh = 0; sh < kBf16MainLarge; ++sh) {
         if (!(fits >> sh & 1)) continue;
         const int64_t cost = bf16_main_cost(sh, M, N, K);
         if (best < 0 || cost < best_cost) best = sh, best_cost = cost;
@@ -402,11 +403,12 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     // kernel of that tile
     else if (ceil_div(M, 256) * ceil_div(N, 256) >= 128) {
         int64_t one_cost = 0;
+        main_fits &= (1u << kBf16MainLarge) - 1;        // the shapes the cost rule covers
         p->cfg = main_fits ? bf16_main_candidate(tile_rule_bf16_main(M, N, K, main_fits, &one_cost)) : (int)kBf16_256x256;
         // two bands, as for fp32 (costs in 1/256 ns; 4 us for the second launch; taken for a modelled gain of 4 % and more)
         // (not where the one launch is within 3 % of 256 x 256 tiles in whole rounds, the best any plan can do)
         if (main_fits && (double)one_cost * 65536.0 > 1.03 * (double)M * (double)N * (double)(kBf16MainPerKTile[0] * ceil_div(K, 64) + kBf16MainPerRound[0])) {
-            const Bands b = best_bands(BandsKey{1, a_lay * 2 + b_lay, M, N, K, main_fits}, kBf16MainShapes, [&](int sh, int64_t m, int64_t n) -> int64_t {
+            const Bands b = best_bands(BandsKey{1, a_lay * 2 + b_lay, M, N, K, main_fits}, kBf16MainLarge, [&](int sh, int64_t m, int64_t n) -> int64_t {
                 if (!(main_fits >> sh & 1) || m < bf16_main_tile_m(sh) || n < bf16_main_tile_n(sh)) return -1;
                 return bf16_main_cost(sh, m, n, K);
             }, (int64_t)4000 * 256);
@@ -420,6 +422,11 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
             }
         }
     }
+    // smaller problems: the direct-to-LDS kernel's 128 x 128 tile where it fits and gives three quarters of the compute
+    // units a workgroup (up to two share a unit; 2048^3 653 -> 807 TFLOP/s, 1024 x 4096 x 4096 771 -> 973, 1536 x 2048^2
+    // 542 -> 581 against the general tiles; with 144 tiles, 1536^3, it is level with the general 64 x 64 tile), else the
+    // general kernel's 128 x 128 tile where that fills the units, else its 64 x 64 tile
+    else if ((main_fits >> kBf16MainLarge & 1) && ceil_div(M, 128) * ceil_div(N, 128) >= 192) p->cfg = bf16_main_candidate(kBf16MainLarge);
     else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kBf16_128x128;
     else p->cfg = kBf16_64x64;
     if (p->cfg == kBf16_Vector) {       // a row of the selection table

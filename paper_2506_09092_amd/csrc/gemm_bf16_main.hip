@@ -82,9 +82,11 @@
 // Tile shapes.  A launch lasts as long as the compute unit with the most tiles, so a problem whose 256 x 256
 // tiles do not fill whole rounds of the compute units is better off with a tile that does: the kernel is a
 // template over the blocks per wavefront, IM x JN of 16 x 16 (tile 32 IM x 32 JN), built for sides of 256, 192
-// and 128 (a 128 x 128 tile asks the L2 for more bytes per cycle than a compute unit gets, and is left out).
+// and 128.  (A 128 x 128 tile asks the L2 for more bytes per cycle than a compute unit gets; it is there for problems
+// too small to give every compute unit a larger tile, where two such workgroups share a unit.)
 // Everything scales: IM + JN loads per wavefront and K-tile, IM + JN fragment reads and IM JN MFMAs per
-// k-step.  An operand that is contiguous along m / n keeps its side at 256.
+// k-step.  An operand that is contiguous along m / n keeps its side at 256.  The 128 x 128 tile has 16 MFMAs per half of
+// a K-tile: its loads sit behind every third MFMA and its fragment reads behind consecutive ones.
 //
 // Rest of K.  When K is not whole K-tiles (it is a multiple of 8, so a 16-byte piece lies inside K or beyond
 // it), one more K-tile follows the pipeline, once per tile of C: its loads take an address per lane through the
@@ -110,7 +112,9 @@ constexpr int kBK = 64;
 constexpr int kScratchBytes = 1024;             // landing zone of the prefetch touches (256 B per wavefront)
 constexpr int kThreads = 256;
 constexpr int kLate = 4;         // loads of K-tile t+1 issued in k-step 0 of K-tile t; the others earlier, in k-step 1 of t-1
-constexpr int kLoadEvery = 4;    // a load behind every fourth MFMA (slots 2, 6, ...): denser loads stall the matrix pipe
+// a load behind every fourth MFMA (slots 2, 6, ...): denser loads stall the matrix pipe; every third where a half has
+// fewer than 32 slots (tiles with both sides below 256)
+constexpr int load_every(int mfmas_per_half) { return mfmas_per_half >= 32 ? 4 : 3; }
 
 // where the loads of the last, partial K-tile fetch the pieces that lie beyond K
 __device__ __attribute__((aligned(16))) const uint16_t kZeroPiece[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -137,7 +141,7 @@ __device__ __attribute__((aligned(16))) const uint16_t kZeroPiece[8] = {0, 0, 0,
 template <int IM, int JN, int LATE, int EARLY, int LOAD_EVERY, int TOUCH_SLOT>
 struct ChainPlan {
     static constexpr int H = IM * JN, S = 2 * H, NF = 2 * (IM + JN);
-    static constexpr int kMinLead = 6, kReadGap = 2;
+    static constexpr int kMinLead = 6, kReadGap = H >= 32 ? 2 : 1;
     // fragment f < NF: k-step f / (IM + JN); r = f % (IM + JN) < IM is a_r, else b_(r - IM)
     static constexpr int kk_of(int f) { return f / (IM + JN); }
     static constexpr bool is_a(int f) { return f % (IM + JN) < IM; }
@@ -237,6 +241,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     constexpr int kMfmas = IM * JN;                                    // per k-step
     constexpr int kReads = IM + JN;                                    // fragment reads per k-step
     constexpr int kEarly = kLoads - kLate;
+    constexpr int kLoadEvery = load_every(kMfmas);
     // K-tiles between a prefetch touch and the loads it serves: with 64 MFMAs per k-step 2 is too late, 4 and more
     // let touched lines be evicted before use (more fabric reads, same time); shorter K-tiles look one further ahead
     constexpr int kTouchAhead = kMfmas == 64 ? 3 : 4;
@@ -553,7 +558,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
 }  // namespace
 
 // in the order of the candidate numbers: 256 x 256 was there first
-constexpr int kShapeM[kBf16MainShapes] = {256, 192, 128, 256, 192, 256}, kShapeN[kBf16MainShapes] = {256, 256, 256, 192, 192, 128};
+constexpr int kShapeM[kBf16MainShapes] = {256, 192, 128, 256, 192, 256, 128}, kShapeN[kBf16MainShapes] = {256, 256, 256, 192, 192, 128, 128};
 
 int bf16_main_tile_m(int shape) { return kShapeM[shape]; }
 int bf16_main_tile_n(int shape) { return kShapeN[shape]; }
@@ -634,7 +639,8 @@ hipError_t launch_bf16_main(int shape, int a_lay, int b_lay, const GemmArgs &a, 
     case 2: return launch_shape<4, 8>(a_lay, b_lay, a, s);
     case 3: return launch_shape<8, 6>(a_lay, b_lay, a, s);
     case 4: return launch_shape<6, 6>(a_lay, b_lay, a, s);
-    default: return launch_shape<8, 4>(a_lay, b_lay, a, s);
+    case 5: return launch_shape<8, 4>(a_lay, b_lay, a, s);
+    default: return launch_shape<4, 4>(a_lay, b_lay, a, s);
     }
 }
 

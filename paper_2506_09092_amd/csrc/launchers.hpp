@@ -30,8 +30,8 @@ enum Bf16Config { kBf16_Main = 0, kBf16_256x256 = 1, kBf16_128x128 = 2, kBf16_64
 const char *bf16_kernel_name(int cfg, int mode, int a_lay, int b_lay);
 hipError_t launch_bf16(int cfg, int mode, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 // the direct-to-LDS kernel's tile shapes: 256 x 256 (candidate kBf16_Main), then 192 x 256, 128 x 256, 256 x 192,
-// 192 x 192, 256 x 128 (candidates kBf16_MainMore ..., after the vector kernels); no K slices
-constexpr int kBf16MainShapes = 6;
+// 192 x 192, 256 x 128, 128 x 128 (candidates kBf16_MainMore ..., after the vector kernels); no K slices
+constexpr int kBf16MainShapes = 7;
 int bf16_main_tile_m(int shape);
 int bf16_main_tile_n(int shape);
 bool bf16_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb);

@@ -24,7 +24,7 @@ MAX_SLICES = 64
 # the direct-to-LDS kernel is candidate 0, its other shapes 5 .. 9, the general tiles 1 .. 3, the vector kernels 4.
 # "One tile size up or down" walks this chain instead (general 256 x 256, then the direct-to-LDS shapes by falling area,
 # then the smaller general tiles, then the vector kernels).
-TILE_CHAIN = {"bf16": (1, 0, 5, 7, 8, 6, 9, 2, 3, 4)}
+TILE_CHAIN = {"bf16": (1, 0, 5, 7, 8, 6, 9, 10, 2, 3, 4)}
 
 
 def neighbours(c: Candidate, tile_count: int, max_slices: int = MAX_SLICES, chain=None):

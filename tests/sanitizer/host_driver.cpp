@@ -22,7 +22,7 @@ int main()
     const uintptr_t offs[] = {0, 0, 1, 2, 4};
     const uintptr_t P = 0x1000;
     const int n32 = fsrgemm_tile_count_f32(), n16 = fsrgemm_tile_count_bf16();
-    CHECK(n32 == 17 && n16 == 10 && fsrgemm_version() >= 200);
+    CHECK(n32 == 17 && n16 == 11 && fsrgemm_version() >= 200);
     long plans = 0, names = 0;
     for (int c = 0; c < 20000; ++c) {
         const int ta = (int)(next() & 1), tb = (int)(next() & 1);

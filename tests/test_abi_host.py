@@ -86,7 +86,8 @@ def test_dispatch_query_names_variants():
     assert qb(8192, 8192, 8196, P, 8200, P, 8200, P, 8192) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"   # K not a multiple of 8
     assert qb(6144, 6144, 6144, P, 6144, P, 6144, P, 6144) == "gemm_bf16_main_kernel<8, 6, 0, 0>"   # 768 tiles of 256 x 192: 3 whole rounds
     assert qb(8192, 8192, 56, P, 56, P, 56, P, 8192) == "gemm_bf16_kernel<4, 1, 1, 0, 0>"           # under one K-tile
-    assert qb(2048, 2048, 512, P, 512, P, 512, P, 2048) == "gemm_bf16_kernel<2, 2, 0, 0, 0>"
+    assert qb(2048, 2048, 512, P, 512, P, 512, P, 2048) == "gemm_bf16_main_kernel<4, 4, 0, 0>"      # 256 tiles of 128 x 128, two to a compute unit
+    assert qb(2048, 2048, 516, P, 516, P, 516, P, 2048) == "gemm_bf16_kernel<2, 2, 2, 0, 0>"       # rows that are not whole pieces: the general tile
     assert qb(100, 100, 100, P, 100, P, 100, P, 100) == "gemm_bf16_kernel<1, 4, 2, 0, 0>"         # ld not a multiple of 8
     assert qb(100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1, 0, 0>"
     # leading dimensions of 2^25 elements and more do not fit the main kernel's 32-bit lane offsets
@@ -197,7 +198,7 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
 
 def test_forced_configurations_and_plan_queries():
     bad, ok = lib.FSRGEMM_ERR_INVALID_ARG, lib.FSRGEMM_OK
-    assert lib.fsrgemm_tile_count_f32() == 17 and lib.fsrgemm_tile_count_bf16() == 10
+    assert lib.fsrgemm_tile_count_f32() == 17 and lib.fsrgemm_tile_count_bf16() == 11
     f = lambda tile, s, ws=None, wsb=0, M=64, N=64, K=4096: lib.gemm_f32_cfg(tile, s, 0, 0, M, N, K, P, K, P, N, P, N, ws, wsb, 0)
     assert f(-1, 1) == bad and f(17, 1) == bad and f(0, 0) == bad and f(0, 65) == bad
     assert f(3, 1) == bad and f(3, 1, K=0, M=1) == bad                          # the vector kernels need M or N = 1 and K > 0

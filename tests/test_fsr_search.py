@@ -32,15 +32,16 @@ def test_neighbours_stay_in_range():
 def test_neighbours_follow_a_chain_of_likeness():
     # bf16 candidate numbers are not in order of tile size: the chain is; a tile that is not on it falls back to +-1
     chain = fsr_search.TILE_CHAIN["bf16"]
-    assert sorted(chain) == list(range(10))
-    assert neighbours(Candidate(0, 1), 10, 1, chain) == [Candidate(5, 1), Candidate(1, 1)]       # 256 x 256: 192 x 256, general 256 x 256
-    assert neighbours(Candidate(8, 1), 10, 1, chain) == [Candidate(6, 1), Candidate(7, 1)]       # 192 x 192: 128 x 256, 256 x 192
-    assert neighbours(Candidate(4, 1), 10, 1, chain) == [Candidate(3, 1)] and neighbours(Candidate(1, 1), 10, 1, chain) == [Candidate(0, 1)]
+    assert sorted(chain) == list(range(11))
+    assert neighbours(Candidate(0, 1), 11, 1, chain) == [Candidate(5, 1), Candidate(1, 1)]       # 256 x 256: 192 x 256, general 256 x 256
+    assert neighbours(Candidate(8, 1), 11, 1, chain) == [Candidate(6, 1), Candidate(7, 1)]       # 192 x 192: 128 x 256, 256 x 192
+    assert neighbours(Candidate(4, 1), 11, 1, chain) == [Candidate(3, 1)] and neighbours(Candidate(1, 1), 11, 1, chain) == [Candidate(0, 1)]
+    assert neighbours(Candidate(10, 1), 11, 1, chain) == [Candidate(2, 1), Candidate(9, 1)]     # direct-to-LDS 128 x 128: the general 128 x 128, 256 x 128
     assert neighbours(Candidate(2, 1), 3, 1, (5, 6)) == [Candidate(1, 1)]
     # the search reaches a minimum that plain numbering would need many rounds for: 0 -> 5 -> 7
     lat = lambda c: {7: 1.0, 5: 2.0, 0: 3.0}.get(c.tile, 9.0)
     runs, validates, latency, _ = scripted(lat)
-    assert search(Candidate(0, 1), 10, runs, validates, latency, rounds=3, per_round=4, max_slices=1, chain=chain)["best"] == Candidate(7, 1)
+    assert search(Candidate(0, 1), 11, runs, validates, latency, rounds=3, per_round=4, max_slices=1, chain=chain)["best"] == Candidate(7, 1)
 
 
 def test_walks_downhill_to_the_minimum():

@@ -307,7 +307,8 @@ def test_bf16_big_tile_config_ragged(gpu):
                                           ((2304, 4090, 64), "gemm_bf16_main_kernel<"),            # one K-tile, ragged N
                                           ((257, 33000, 128), "gemm_bf16_main_kernel<"),           # the last tile row overlaps all but one row
                                           ((8200, 8400, 128), "gemm_bf16_main_kernel<"),           # more than 1024 tiles, both ragged
-                                          ((2000, 2100, 128), "gemm_bf16_kernel<2, 2, 0, 0, 0>"),  # 128 x 128 tiles, unchecked
+                                          ((2000, 2100, 128), "gemm_bf16_main_kernel<4, 4, 0, 0>"),  # 128 x 128 tiles of the direct-to-LDS kernel
+                                          ((1000, 1100, 128), "gemm_bf16_kernel<1, 4, 0, 0, 0>"),  # too few of those: 64 x 64 tiles, unchecked
                                           ((300, 520, 64), "gemm_bf16_kernel<1, 4, 0, 0, 0>")])    # 64 x 64 tiles, unchecked
 def test_bf16_ragged_last_tiles_are_shifted_back(gpu, shape, kernel):
     # aligned problems that are not a whole number of tiles run the unchecked kernels: the last tile row and
@@ -426,15 +427,16 @@ def test_f32_main_kernel_is_the_dispatchers_choice(gpu):
             assert np.array_equal(run_cfg(gpu, "f32", 5, 1, 0, 0, A, B).view(np.uint32), got.view(np.uint32))
 
 
-BF16_MAIN_SHAPES = {0: (256, 256), 5: (192, 256), 6: (128, 256), 7: (256, 192), 8: (192, 192), 9: (256, 128)}      # candidate -> tile
+BF16_MAIN_SHAPES = {0: (256, 256), 5: (192, 256), 6: (128, 256), 7: (256, 192), 8: (192, 192), 9: (256, 128), 10: (128, 128)}      # candidate -> tile
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 1)] + BF16_STORAGE)
 @pytest.mark.parametrize("shape", [(512, 768, 64), (512, 512, 128), (768, 512, 192), (256, 256, 448),     # whole tiles, 1 / 2 / 3 / 7 K-tiles
                                    (520, 392, 128), (264, 1288, 64), (1000, 264, 192),                    # shifted last tiles
-                                   (512, 512, 72), (520, 392, 232), (384, 392, 120), (256, 512, 104)])    # a rest of K behind 1 / 3 / 1 / 1 K-tiles
+                                   (512, 512, 72), (520, 392, 232), (384, 392, 120), (256, 512, 104),     # a rest of K behind 1 / 3 / 1 / 1 K-tiles
+                                   (128, 128, 64), (136, 200, 328)])                                      # the 128 x 128 tile only
 def test_bf16_main_kernel_every_shape(gpu, shape, ta, tb):
-    # the direct-to-LDS bf16 kernel in its six tile shapes, forced: prologue, odd / even tails, the clamped loads two
+    # the direct-to-LDS bf16 kernel in its seven tile shapes, forced: prologue, odd / even tails, the clamped loads two
     # K-tiles ahead, the rest of K (one and two k-steps of it), operands contiguous along k and (side 256 only) along
     # m / n, padded leading dimensions, small integers
     M, N, K = shape
