@@ -28,8 +28,8 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense MFMA peaks
 # profiles/gemm_f32_4096_bf16_8192_hbm_traffic.txt (scaled by a 1 GiB copy).  Each entry is tied to the
 # kernel sources it was measured on: once those change the figure is stale and the bench reports null.
 TRAFFIC = {
-    "f32_4096": {"bytes": 470089626, "sources": {"gemm_f32_main.hip": "de51751b875e6a09", "common.hpp": "fcd7c27e4bf90732"}},
-    "bf16_8192": {"bytes": 2108098026, "sources": {"gemm_bf16_main.hip": "1afe631bec2fb829", "common.hpp": "fcd7c27e4bf90732"}},
+    "f32_4096": {"bytes": 470090268, "sources": {"gemm_f32_main.hip": "de51751b875e6a09", "common.hpp": "fcd7c27e4bf90732"}},
+    "bf16_8192": {"bytes": 2106284238, "sources": {"gemm_bf16_main.hip": "c142e6e0a7bd6985", "common.hpp": "fcd7c27e4bf90732"}},
 }
 # the same for the transposes (profiles/transpose_f32_paper_sizes.txt), by N
 _T8_SOURCES = {"transpose.hip": "4a43b5ad193408de", "common.hpp": "fcd7c27e4bf90732"}
@@ -258,15 +258,15 @@ def mid_sizes_f32(lib, torch):
 
 
 def mid_sizes_bf16(lib, torch):
-    """bf16 problems (A row-major, B column-major) whose 256 x 256 tiles do not fill whole rounds of the compute units, or
-    whose K is not whole K-tiles: the tile shape of the direct-to-LDS kernel the dispatcher took, its rate, and
+    """bf16 problems (A row-major, B column-major) whose 256 x 256 tiles do not fill whole rounds of the compute units (or,
+    2048^3, do not give every unit one), or whose K is not whole K-tiles: the tile shape of the direct-to-LDS kernel the dispatcher took, its rate, and
     torch.matmul (the vendor library, bf16 output) on the same buffers for scale.  Profiler leg only; parity of every
     shape and of the rest-of-K step is covered by the GPU tests."""
     import math
 
     stream = torch.cuda.current_stream().cuda_stream
     out = []
-    for M, N, K in ((4096, 4096, 4096), (5120, 5120, 5120), (6144, 6144, 6144), (7168, 7168, 7168), (3072, 8192, 4096),
+    for M, N, K in ((2048, 2048, 2048), (4096, 4096, 4096), (5120, 5120, 5120), (6144, 6144, 6144), (7168, 7168, 7168), (3072, 8192, 4096),
                     (8192, 8192, 8200), (8000, 8000, 8000)):
         a = (torch.randn(M, K, device="cuda") / math.sqrt(K)).to(torch.bfloat16)
         b = (torch.randn(N, K, device="cuda") / math.sqrt(K)).to(torch.bfloat16)
