@@ -779,6 +779,44 @@ def test_random_shapes_through_every_entry_point(gpu):
         assert oracle.componentwise_error(got, ref, S) <= tol, (case, kind, ta, tb, M, N, K, mode)
 
 
+def test_random_larger_aligned_shapes_through_the_plain_entry_points(gpu):
+    # 28 seeded cases of 1024 .. 6000 rows and columns, aligned, every storage order, ragged against every tile: what the
+    # dispatcher makes of them (tiles of every size, two bands, a rest of K) against the oracle's whole product
+    import random
+
+    rng = random.Random(33)
+    seen = set()
+    for case in range(28):
+        kind = rng.choice(("f32", "bf16"))
+        ta, tb = rng.randint(0, 1), rng.randint(0, 1)
+        M, N = 8 * rng.randint(128, 750), 8 * rng.randint(128, 750)
+        K = (4 if kind == "f32" else 8) * rng.randint(32, 280)
+        while M * N * K > 2.4e10:
+            M = max(1024, M // 2 // 8 * 8)
+        if case % 7 == 3:           # shapes whose tiles fill no whole rounds in any one shape: the two-band plans
+            kind, (M, N), K = "f32", rng.choice(((5000, 5120), (5120, 5000), (6656, 5000), (3000, 7168))), rng.choice((512, 772))
+        pad = 8 * rng.choice((0, 0, 1, 3))
+        lda, ldb = (M if ta else K) + pad, (K if tb else N) + pad
+        if kind == "f32":
+            A, B = inputs.uniform_pm1(33, 2 * case, M, K), inputs.uniform_pm1(33, 2 * case + 1, K, N)
+            tol, run_ex, bands, named = TOL_F32, run_f32_ex, gpu.fsrgemm_bands_f32, gpu.fsrgemm_kernel_for_f32_ex
+        else:
+            A = inputs.bf16_normal_scaled(33, 2 * case, M, K, 1 / math.sqrt(K))
+            B = inputs.bf16_normal_scaled(33, 2 * case + 1, K, N, 1 / math.sqrt(K))
+            tol, run_ex, bands, named = 1e-5, run_bf16_ex, gpu.fsrgemm_bands_bf16, gpu.fsrgemm_kernel_for_bf16_ex
+        dim, at, first, second = bands(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb)
+        name = named(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N)
+        say("larger case %d: %s %d%d %dx%dx%d lda %d ldb %d -> %s" % (case, kind, ta, tb, M, N, K, lda, ldb, name))
+        seen.add((kind, dim != 0))
+        seen.add((kind, first))
+        ref, S = oracle.gemm(A, B)
+        got = run_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + rng.choice((0, 4)), repeat=2)
+        e = oracle.componentwise_error(got, ref, S)
+        assert e <= tol, (case, kind, ta, tb, M, N, K, name, e)
+    # the draw does reach the paths it is there for: two-band plans and one launch in both precisions, several tile shapes
+    assert {("f32", True), ("f32", False), ("bf16", False)} <= seen and len([x for x in seen if not isinstance(x[1], bool)]) >= 6, seen
+
+
 # ---- the library under HIP graph capture ----
 
 def test_calls_captured_in_a_hip_graph_replay_bit_exact(gpu):
