@@ -972,6 +972,6 @@ const char *fsrgemm_status_string(int status)
     }
 }
 
-int fsrgemm_version(void) { return 200; }
+int fsrgemm_version(void) { return 300; }
 
 }  // extern "C"
