@@ -459,12 +459,14 @@ def validator_pass_in_a_graph(lib, torch, passes=20, n_streams=4):
 def selection_loop(lib, torch):
     """The selection loop (Algorithm 1 over tile configurations, validator = the CPU oracle) on three problems:
     where it starts (the dispatcher's choice), which candidates it visited, what it ends on, and the two timed
-    against each other.  The loop's code and its oracle-backed validator live in fsr_search.py / tests/."""
+    against each other (for 3584^3 the dispatcher's rules run the product as two bands of C, and that plan, two
+    launches, is what the loop's winner is timed against).  The loop's code and its oracle-backed validator live in
+    fsr_search.py / tests/."""
     from paper_2506_09092_amd.fsr_search import Problem
     from tests import tune_dispatch
 
     out = []
-    for p in (Problem("f32", 0, 0, 3072, 3072, 3072), Problem("f32", 0, 0, 768, 768, 768), Problem("bf16", 0, 1, 512, 512, 16384)):
+    for p in (Problem("f32", 0, 0, 3584, 3584, 3584), Problem("f32", 0, 0, 768, 768, 768), Problem("bf16", 0, 1, 512, 512, 16384)):
         rows, rep = tune_dispatch.tune(lib, torch, p, 0.04, lambda msg: None)
         rep["new_table_rows"] = [r.strip() for r in rows]
         out.append(rep)

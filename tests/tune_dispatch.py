@@ -83,10 +83,10 @@ def tune(lib, torch, p: Problem, gain: float, log):
                               rounds=3, per_round=4, max_slices=fsr_search.MAX_SLICES if with_ws else 1, log=log, chain=be.chain)
         best = r["best"]
         entry = dict(start=start, rules=rules, best=best, visited={"%d/%d" % k: v for k, v in r["visited"].items()})
-        if best is not None and best != rules and be.runs(rules) and validator(be.output(rules)):
+        as_run = (be.rules_bands if with_ws else be.rules_bands_unsplit) or rules
+        if best is not None and best != as_run and be.runs(rules) and validator(be.output(rules)):
             # the incumbent against the choice of the rules (their two-band plan where they make one), measured again,
             # both ways round; a row only for a clear gain
-            as_run = (be.rules_bands if with_ws else be.rules_bands_unsplit) or rules
             entry["rules_as_run"] = as_run
             t_rules = min(be.latency(as_run), be.latency(as_run))
             t_best = max(be.latency(best), be.latency(best))
