@@ -308,9 +308,9 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
         if (t && t->tile >= kF32_Main && (!(main_fits >> (t->tile - kF32_Main) & 1) || t->slices > 1)) t = nullptr;    // a row for operands aligned otherwise
         // a split runs on 64 x 64 tiles, or on 128 x 128 ones where those still give every compute unit a workgroup
         // and a slice keeps at least 1024 k (10-17 % faster there, measured on 256^2 ... 1024^2 with K up to 65536)
-        // (not for a sliver of a few rows or columns, most of whose 128-wide tile would be padding: 8 x 8192 x 8192 runs 57 %
+        // (not for a sliver under 128 rows or columns, part of whose 128-wide tile would be padding: 8 x 8192 x 8192 runs 57 %
         // faster on 64 x 64 tiles)
-        const bool split128 = p->slices > 1 && ceil_div(M, 128) * ceil_div(N, 128) * p->slices >= 240 && K / p->slices >= 1024 && M >= 96 && N >= 96;
+        const bool split128 = p->slices > 1 && ceil_div(M, 128) * ceil_div(N, 128) * p->slices >= 240 && K / p->slices >= 1024 && M >= 128 && N >= 128;
         int64_t one_cost = 0;
         p->cfg = t ? t->tile : p->slices > 1 ? (split128 ? kF32_128x128 : kF32_64x64) : tile_rule_f32(M, N, main_fits, &one_cost);
         // one launch leaves compute units idle in its last round: try two bands of direct-to-LDS shapes (tile times in
@@ -397,7 +397,9 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     if (t) p->cfg = t->tile;
     // a split runs on 128 x 128 tiles where those still give every compute unit a workgroup (up to 30 % faster than
     // 64 x 64 ones there, measured on 256^2 ... 1024^2 with K up to 65536), else on 64 x 64 tiles
-    else if (p->slices > 1) p->cfg = ceil_div(M, 128) * ceil_div(N, 128) * p->slices >= 240 ? kBf16_128x128 : kBf16_64x64;
+    // (and, as for fp32, not for a sliver most of whose 128-wide tile would be padding: 32 x 28672 x 8192 takes 0.129 ms on
+    // 128 x 128 tiles and 0.121 on 64 x 64 ones, 96 x 8192 x 8192 0.047 and 0.039)
+    else if (p->slices > 1) p->cfg = ceil_div(M, 128) * ceil_div(N, 128) * p->slices >= 240 && M >= 128 && N >= 128 ? kBf16_128x128 : kBf16_64x64;
     // where 256 x 256 tiles give at least half the compute units one each: the direct-to-LDS kernel in the shape that
     // fills whole rounds, or, where it does not fit (alignment, a K that is not whole 16-byte pieces), the general
     // kernel of that tile
