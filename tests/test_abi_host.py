@@ -194,6 +194,8 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
     assert pf(256, 256, 16384) == (2, 64)           # slices of 256 k: too short
     assert pb(512, 512, 65536) == (2, 16) and pb(256, 256, 16384) == (2, 64) and pb(768, 768, 4096) == (3, 4)
     assert lib.gemm_f32_workspace_bytes(0, 0, 512, 512, 65536) == 16 * 512 * 512 * 4
+    # a problem under 128 rows or columns keeps 64 x 64 tiles: most of a 128-wide tile would be padding
+    assert pf(8, 8192, 8192) == (2, 8) and pb(32, 28672, 8192) == (3, 2) and pb(96, 8192, 8192)[0] == 3 and pb(128, 8192, 8192)[0] == 2
 
 
 def test_forced_configurations_and_plan_queries():
