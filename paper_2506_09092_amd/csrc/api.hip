@@ -428,7 +428,11 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     // units a workgroup (up to two share a unit; 2048^3 653 -> 807 TFLOP/s, 1024 x 4096 x 4096 771 -> 973, 1536 x 2048^2
     // 542 -> 581 against the general tiles; with 144 tiles, 1536^3, it is level with the general 64 x 64 tile), else the
     // general kernel's 128 x 128 tile where that fills the units, else its 64 x 64 tile
-    else if ((main_fits >> kBf16MainLarge & 1) && ceil_div(M, 128) * ceil_div(N, 128) >= 192) p->cfg = bf16_main_candidate(kBf16MainLarge);
+    // (with an operand contiguous along m / n the general kernel stages through registers and is slower: there the
+    // 128 x 128 tile wins from 4 tiles on -- level at 256^3 and 512^3, 768^3 83-105 -> 107-112, 1024^3 156-198 -> 212-222,
+    // 1536^3 194-290 -> 392-405, 256^2 x 65536 0.69-0.87 -> 0.59-0.60 ms)
+    else if ((main_fits >> kBf16MainLarge & 1) && ceil_div(M, 128) * ceil_div(N, 128) >= (a_lay == kKContig && b_lay == kKContig ? 192 : 4))
+        p->cfg = bf16_main_candidate(kBf16MainLarge);
     else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kBf16_128x128;
     else p->cfg = kBf16_64x64;
     if (p->cfg == kBf16_Vector) {       // a row of the selection table

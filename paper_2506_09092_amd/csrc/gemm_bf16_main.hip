@@ -2,7 +2,7 @@
 // accumulate and output -- the Task 2 product at matrix-core input precision.
 // Either operand may be contiguous along k (a row-major A, a column-major B:
 // the tile's rows are 128 bytes of 64 k) or along m / n (a transposed A, a
-// row-major B: the tile's rows are k-rows of 512 bytes); LDS keeps the memory
+// row-major B: the tile's rows are k-rows of 512 or 256 bytes); LDS keeps the memory
 // order and the fragment reads do the rest (see "Fragments" below).
 //
 // Shape of the computation (for the 256 x 256 tile; "Tile shapes" below)
@@ -72,12 +72,13 @@
 // 8 + i / 4 and 12 + i / 4 point at.  Lane s therefore points at k-row
 // k0 + s / 4, rows 4 (s % 4) .. + 3 of the block, and lane i ends up with
 // k0 .. k0 + 3 of row i; k0 = 8 (l / 16) for the first read, + 4 for the second.
-// Such a tile's k-rows are 512 bytes; 16-byte chunk c of k-row k is stored at
-// c ^ f(k), f(k) = 2 (k % 4) + 8 ((k / 8) % 2): the 32 lanes one pass of the
-// read serves (4 + 4 k-rows, 32 bytes each) then cover all 64 banks once.  A
-// block's reads differ by an XOR in address bits 5-7, so a lane keeps one
-// address per block (8 registers per such operand) and reaches k-step, half
-// and stage through immediate offsets.
+// Such a tile's k-rows are 512 bytes (side 256) or 256 bytes (side 128), a
+// whole number of trips round the 64 banks either way; 16-byte chunk c of
+// k-row k is stored at c ^ f(k), f(k) = 2 (k % 4) + 8 ((k / 8) % 2): the 32
+// lanes one pass of the read serves (4 + 4 k-rows, 32 bytes each) then cover
+// all 64 banks once.  A block's reads differ by an XOR in address bits 5-7,
+// so a lane keeps one address per block (one register per block and such
+// operand) and reaches k-step, half and stage through immediate offsets.
 //
 // Tile shapes.  A launch lasts as long as the compute unit with the most tiles, so a problem whose 256 x 256
 // tiles do not fill whole rounds of the compute units is better off with a tile that does: the kernel is a
@@ -85,7 +86,8 @@
 // and 128.  (A 128 x 128 tile asks the L2 for more bytes per cycle than a compute unit gets; it is there for problems
 // too small to give every compute unit a larger tile, where two such workgroups share a unit.)
 // Everything scales: IM + JN loads per wavefront and K-tile, IM + JN fragment reads and IM JN MFMAs per
-// k-step.  An operand that is contiguous along m / n keeps its side at 256.  The 128 x 128 tile has 16 MFMAs per half of
+// k-step.  An operand that is contiguous along m / n needs its side at 256 or 128 (the swizzle above wants a k-row
+// that is a power of two long; 192 keeps such operands out).  The 128 x 128 tile has 16 MFMAs per half of
 // a K-tile: its loads sit behind every third MFMA and its fragment reads behind consecutive ones.
 //
 // Rest of K.  When K is not whole K-tiles (it is a multiple of 8, so a 16-byte piece lies inside K or beyond
@@ -233,7 +235,7 @@ template <int IM, int JN, int ALAY, int BLAY>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, int tiles_m, int tiles_n)
 {
     constexpr bool AMC = ALAY == kMnContig, BMC = BLAY == kMnContig;
-    static_assert((!AMC || IM == 8) && (!BMC || JN == 8), "an operand contiguous along m / n keeps its side at 256");
+    static_assert((!AMC || IM == 8 || IM == 4) && (!BMC || JN == 8 || JN == 4), "an operand contiguous along m / n has a side of 256 or 128");
     constexpr int kBM = 32 * IM, kBN = 32 * JN;
     constexpr int kTileA = kBM * kBK * 2, kTileB = kBN * kBK * 2;       // operand tiles: 128 bytes per row
     constexpr int kStageBytes = kTileA + kTileB;
@@ -264,28 +266,33 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     //                           the chunk that belongs at its position, (lane % 8) ^ ((row >> 1) & 7), and
     //                           ((8 IM w + 8 q + lane / 8) >> 1) & 7 = 4 (q & 1) + (lane / 8 >> 1) for even IM: one lane
     //                           offset for even q, one for odd q.  The lane offsets also carry the K position.
-    //   contiguous along m / n: 2 k-rows per load: k-rows 16 w + 2 q + lane / 32; chunk (lane % 32) ^ kswz(k-row),
-    //                           k-row % 4 = 2 (q & 1) + lane / 32 and (k-row / 8) % 2 = q / 4: four lane offsets,
-    //                           index (q & 1) + 2 (q >> 2).  The K position is carried by the scalar row bases.
+    //   contiguous along m / n: a k-row of the tile is 64 IM bytes = 4 IM chunks, so a load takes 16 / IM k-rows:
+    //                           k-rows 16 w + (16 / IM) q + lane / (4 IM); chunk (lane % (4 IM)) ^ kswz(k-row).
+    //                           Side 256: k-row % 4 = 2 (q & 1) + lane / 32 and (k-row / 8) % 2 = q / 4, four lane
+    //                           offsets, index (q & 1) + 2 (q >> 2).  Side 128: k-row % 4 = lane / 16 and
+    //                           (k-row / 8) % 2 = q / 2, two lane offsets, index 2 (q >> 1).  The K position is
+    //                           carried by the scalar row bases.
     const int lrow = lane >> 3, lpos = lane & 7;
     const int sw_even = (lrow >> 1) & 3, sw_odd = sw_even ^ 4;
-    const int hrow = lane >> 5, hpos = lane & 31;
+    constexpr int kChunksA = 4 * IM, kChunksB = 4 * JN;         // 16-byte chunks of a k-row
+    constexpr int kRowsPerLoadA = 64 / kChunksA, kRowsPerLoadB = 64 / kChunksB;        // (of use for sides of 256 and 128 only)
+    const int hrow_a = lane / kChunksA, hpos_a = lane % kChunksA, hrow_b = lane / kChunksB, hpos_b = lane % kChunksB;
     uint32_t voff_a[4], voff_b[4];      // bytes
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        const int kr = 2 * (v & 1) + hrow + 8 * (v >> 1);
+        const int kr_a = (IM == 8 ? 2 * (v & 1) : 0) + hrow_a + 8 * (v >> 1), kr_b = (JN == 8 ? 2 * (v & 1) : 0) + hrow_b + 8 * (v >> 1);
         const int kc_chunk = lpos ^ ((v & 1) ? sw_odd : sw_even);
-        voff_a[v] = AMC ? (uint32_t)(hrow * g.lda * 2 + (hpos ^ kswz(kr)) * 16) : (uint32_t)(lrow * g.lda + kc_chunk * 8) * 2u;
-        voff_b[v] = BMC ? (uint32_t)(hrow * g.ldb * 2 + (hpos ^ kswz(kr)) * 16) : (uint32_t)(lrow * g.ldb + kc_chunk * 8) * 2u;
+        voff_a[v] = AMC ? (uint32_t)(hrow_a * g.lda * 2 + (hpos_a ^ kswz(kr_a)) * 16) : (uint32_t)(lrow * g.lda + kc_chunk * 8) * 2u;
+        voff_b[v] = BMC ? (uint32_t)(hrow_b * g.ldb * 2 + (hpos_b ^ kswz(kr_b)) * 16) : (uint32_t)(lrow * g.ldb + kc_chunk * 8) * 2u;
     }
     const char *rbase[kLoads];      // row-group bases: uniform; fixed for the tile unless they carry the K position
 #pragma unroll
     for (int q = 0; q < kLoadsA; ++q)
-        rbase[q] = AMC ? reinterpret_cast<const char *>(A + (int64_t)(wave * 16 + q * 2) * g.lda + m0)
+        rbase[q] = AMC ? reinterpret_cast<const char *>(A + (int64_t)(wave * 16 + q * kRowsPerLoadA) * g.lda + m0)
                        : reinterpret_cast<const char *>(A + (int64_t)(m0 + wave * (8 * IM) + q * 8) * g.lda);
 #pragma unroll
     for (int q = 0; q < kLoadsB; ++q)
-        rbase[kLoadsA + q] = BMC ? reinterpret_cast<const char *>(B + (int64_t)(wave * 16 + q * 2) * g.ldb + n0)
+        rbase[kLoadsA + q] = BMC ? reinterpret_cast<const char *>(B + (int64_t)(wave * 16 + q * kRowsPerLoadB) * g.ldb + n0)
                                  : reinterpret_cast<const char *>(B + (int64_t)(n0 + wave * (8 * JN) + q * 8) * g.ldb);
     const int64_t kstep_a = 64 * g.lda * 2, kstep_b = 64 * g.ldb * 2;       // one K-tile of k-rows, in bytes
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(FSR_AS3 char *)smem);
@@ -301,7 +308,8 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     auto load_go = [&](auto idx) {
         constexpr int I = decltype(idx)::value, q = I < kLoadsA ? I : I - kLoadsA;
         constexpr bool mc = I < kLoadsA ? AMC : BMC;
-        constexpr int v = mc ? (q & 1) + 2 * (q >> 2) : (q & 1);
+        constexpr int side = I < kLoadsA ? IM : JN;
+        constexpr int v = !mc ? (q & 1) : side == 8 ? (q & 1) + 2 * (q >> 2) : 2 * (q >> 1);
         const uint32_t vo = I < kLoadsA ? voff_a[v] : voff_b[v];
         const char *rb = rbase[I];
         asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(vo), "s"(rb) : "memory");
@@ -319,21 +327,21 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     // Prefetch touches, one 128-byte line per lane: the workgroup's quarter of its A panel's rows (the 4 tiles
     // beside it along n read the same panel) and its eighth of its B panel's rows (8 tiles along m).  Contiguous
     // along k: lanes 0 .. 2 IM - 1 take A rows 8 IM (tile_n % 4) + 2 IM w + lane, the next JN lanes take B rows
-    // 4 JN (tile_m % 8) + JN w + (lane - 2 IM).  Contiguous along m / n (a K-tile is 64 k-rows of 4 lines): lanes
-    // 0-15 take A k-rows 16 (tile_n % 4) + 4 w + lane / 4, line lane % 4; lanes 16-23 take B k-rows
-    // 8 (tile_m % 8) + 2 w + (lane - 16) / 4, line (lane - 16) % 4.  The remaining lanes repeat lane 0 and coalesce
-    // with it.
+    // 4 JN (tile_m % 8) + JN w + (lane - 2 IM).  Contiguous along m / n (a K-tile is 64 k-rows of IM / 2 lines, JN / 2
+    // for B): the same number of lanes take A k-rows 16 (tile_n % 4) + 4 w + lane / (IM / 2), line lane % (IM / 2),
+    // and B k-rows 8 (tile_m % 8) + 2 w + u / (JN / 2), line u % (JN / 2), u = lane - 2 IM.  The remaining lanes repeat
+    // lane 0 and coalesce with it.
     const char *touch_ptr;
     int64_t touch_step;
     {
         constexpr int kTouchA = 2 * IM, kTouchB = JN;
         const int tl = lane < kTouchA + kTouchB ? lane : 0, u = tl - kTouchA;
         if (tl < kTouchA) {
-            touch_ptr = AMC ? reinterpret_cast<const char *>(A + (int64_t)((tile_n & 3) * 16 + wave * 4 + (tl >> 2)) * g.lda + m0 + (tl & 3) * 64)
+            touch_ptr = AMC ? reinterpret_cast<const char *>(A + (int64_t)((tile_n & 3) * 16 + wave * 4 + tl / (IM / 2)) * g.lda + m0 + (tl % (IM / 2)) * 64)
                             : reinterpret_cast<const char *>(A + (int64_t)(m0 + (tile_n & 3) * (8 * IM) + wave * (2 * IM) + tl) * g.lda);
             touch_step = AMC ? kstep_a : kBK * 2;
         } else {
-            touch_ptr = BMC ? reinterpret_cast<const char *>(B + (int64_t)((tile_m & 7) * 8 + wave * 2 + (u >> 2)) * g.ldb + n0 + (u & 3) * 64)
+            touch_ptr = BMC ? reinterpret_cast<const char *>(B + (int64_t)((tile_m & 7) * 8 + wave * 2 + u / (JN / 2)) * g.ldb + n0 + (u % (JN / 2)) * 64)
                             : reinterpret_cast<const char *>(B + (int64_t)(n0 + (tile_m & 7) * (4 * JN) + wave * JN + u) * g.ldb);
             touch_step = BMC ? kstep_b : kBK * 2;
         }
@@ -352,8 +360,9 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     // Fragment addresses.  Contiguous along k: row l16 of the block, chunk 4 kk + lq; blocks are 2 KB apart.
     // Contiguous along m / n: as the source of a transposing read the lane points at k-row
     // 32 kk + 8 lq + 4 h + l16 / 4 (h = 0, 1: the two reads), rows 16 b + 4 (l16 % 4) .. + 3 of the wavefront's
-    // part; block b flips address bits 5-7 with b, k-step and half add 16 KB and 2 KB.
-    int ra_off[2], rb_off[2], ra_blk[AMC ? 8 : 1], rb_blk[BMC ? 8 : 1];
+    // part; block b flips address bits 5-7 (5-6 for a side of 128) with b, k-step and half add 32 and 4 k-rows.
+    constexpr int kRowBytesA = 64 * IM, kRowBytesB = 64 * JN;       // a k-row of such a tile
+    int ra_off[2], rb_off[2], ra_blk[AMC ? IM : 1], rb_blk[BMC ? JN : 1];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
         const int pos = (4 * kk + lq) ^ ((l16 >> 1) & 7);
@@ -362,28 +371,32 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     }
     {
         const int fk = kswz((l16 >> 2) + 8 * lq), half = (l16 >> 1) & 1;
-        const int row_part = (8 * lq + (l16 >> 2)) * 512 + (l16 & 1) * 8;
+        const int krow = 8 * lq + (l16 >> 2), in_chunk = (l16 & 1) * 8;
+        // (the wavefront's first chunk, 2 IM or 0, and the swizzle may share a bit for a side of 128: XOR, not OR)
+        if constexpr (AMC) {
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            if constexpr (AMC) ra_blk[b] = (row_part + ((wm0 / 8) | fk | half) * 16) ^ (b << 5);
-            if constexpr (BMC) rb_blk[b] = kTileA + ((row_part + ((wn0 / 8) | fk | half) * 16) ^ (b << 5));
+            for (int b = 0; b < IM; ++b) ra_blk[b] = (krow * kRowBytesA + in_chunk + ((((wm0 / 8) ^ fk) | half) * 16)) ^ (b << 5);
+        }
+        if constexpr (BMC) {
+#pragma unroll
+            for (int b = 0; b < JN; ++b) rb_blk[b] = kTileA + ((krow * kRowBytesB + in_chunk + ((((wn0 / 8) ^ fk) | half) * 16)) ^ (b << 5));
         }
     }
     bf16x8 Fa[2][IM], Fb[2][JN];        // [k-step][block row / column]
-    auto tr_read = [&](const char *p) {
+    auto tr_read = [&](const char *p, int row_bytes) {
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)p);
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)(p + 2048));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)(p + 4 * row_bytes));
         return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
     // fragment r of k-step kk of the K-tile in `stage` (r < IM: a_r, else b_(r - IM)) into the registers of k-step kd
     auto lread = [&](int stage, int kk, int kd, int r) {
         const char *s = smem + stage * kStageBytes;
         if (r < IM) {
-            if constexpr (AMC) Fa[kd][r] = tr_read(s + ra_blk[r] + kk * 16384);
+            if constexpr (AMC) Fa[kd][r] = tr_read(s + ra_blk[r] + kk * (32 * kRowBytesA), kRowBytesA);
             else Fa[kd][r] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk] + r * 2048);
         } else {
             const int j = r - IM;
-            if constexpr (BMC) Fb[kd][j] = tr_read(s + rb_blk[j] + kk * 16384);
+            if constexpr (BMC) Fb[kd][j] = tr_read(s + rb_blk[j] + kk * (32 * kRowBytesB), kRowBytesB);
             else Fb[kd][j] = *reinterpret_cast<const bf16x8 *>(s + rb_off[kk] + j * 2048);
         }
     };
@@ -495,10 +508,11 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         // (the lane id is taken afresh from the hardware: nothing of this step is to be worked out, and kept in registers, ahead of the loop)
         int ln = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
         asm volatile("" : "+v"(ln));
-        auto rest_src = [&](auto mcc, const uint16_t *P, int64_t ld, int origin, int rows_per_wave, int q) -> const uint16_t * {
+        auto rest_src = [&](auto mcc, auto blocks, const uint16_t *P, int64_t ld, int origin, int rows_per_wave, int q) -> const uint16_t * {
             if constexpr (decltype(mcc)::value) {
-                const int kr = wave * 16 + q * 2 + (ln >> 5);       // k-row of the K-tile; chunk = 8 rows / columns
-                return kr < k_rest ? P + (int64_t)(nk * kBK + kr) * ld + origin + 8 * ((ln & 31) ^ kswz(kr)) : kZeroPiece;
+                constexpr int chunks = 4 * decltype(blocks)::value;      // of a k-row; chunk = 8 rows / columns
+                const int kr = wave * 16 + q * (64 / chunks) + ln / chunks;       // k-row of the K-tile
+                return kr < k_rest ? P + (int64_t)(nk * kBK + kr) * ld + origin + 8 * ((ln % chunks) ^ kswz(kr)) : kZeroPiece;
             } else {
                 const int row = ln >> 3, chunk = (ln & 7) ^ (((row >> 1) & 3) | ((q & 1) << 2));
                 return 8 * chunk < k_rest ? P + (int64_t)(origin + wave * rows_per_wave + q * 8 + row) * ld + nk * kBK + 8 * chunk : kZeroPiece;
@@ -509,8 +523,8 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
             const bool is_a = idx < kLoadsA;
             const int q = is_a ? idx : idx - kLoadsA;
             char *dst = smem + (is_a ? wave * (kLoadsA * 1024) : kTileA + wave * (kLoadsB * 1024)) + q * 1024;
-            const uint16_t *src = is_a ? rest_src(std::integral_constant<bool, AMC>{}, A, g.lda, m0, 8 * IM, q)
-                                       : rest_src(std::integral_constant<bool, BMC>{}, B, g.ldb, n0, 8 * JN, q);
+            const uint16_t *src = is_a ? rest_src(std::integral_constant<bool, AMC>{}, Int<IM>{}, A, g.lda, m0, 8 * IM, q)
+                                       : rest_src(std::integral_constant<bool, BMC>{}, Int<JN>{}, B, g.ldb, n0, 8 * JN, q);
             __builtin_amdgcn_global_load_lds((const FSR_AS1 void *)src, (FSR_AS3 void *)dst, 16, 0, 0);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -584,14 +598,14 @@ const char *bf16_main_kernel_name(int shape, int a_lay, int b_lay)
 // Whole unchecked tiles of 16-byte pieces: a matrix at least one tile high and wide (a ragged last tile is shifted
 // back into it), at least one whole K-tile of 64 and K a multiple of 8 (the rest of K is whole pieces), 16-byte aligned
 // bases and rows, leading dimensions below 2^25 (32-bit lane offsets); an operand that is contiguous along m (n) needs
-// its side of the tile at 256 and M (N) a multiple of 8, so that a shifted tile still starts on a piece.
+// its side of the tile at 256 or 128 and M (N) a multiple of 8, so that a shifted tile still starts on a piece.
 bool bf16_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb)
 {
     if (shape < 0 || shape >= kBf16MainShapes) return false;
     const int bm = kShapeM[shape], bn = kShapeN[shape];
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) == 0 && lda % 8 == 0 && ldb % 8 == 0;
     return aligned && lda < (1 << 25) && ldb < (1 << 25) && M >= bm && N >= bn && K >= kBK && K % 8 == 0 &&
-           (a_lay == kKContig || (bm == 256 && M % 8 == 0)) && (b_lay == kKContig || (bn == 256 && N % 8 == 0)) &&
+           (a_lay == kKContig || (bm != 192 && M % 8 == 0)) && (b_lay == kKContig || (bn != 192 && N % 8 == 0)) &&
            ((M + bm - 1) / bm) * ((N + bn - 1) / bn) < ((int64_t)1 << 31);
 }
 
@@ -610,18 +624,18 @@ hipError_t launch_main(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
-// the layouts a shape is built for: an operand contiguous along m / n only with its side at 256
+// the layouts a shape is built for: an operand contiguous along m / n only with its side at 256 or 128
 template <int IM, int JN>
 hipError_t launch_shape(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
     if (a_lay == kKContig && b_lay == kKContig) return launch_main<IM, JN, kKContig, kKContig>(a, s);
-    if constexpr (IM == 8) {
+    if constexpr (IM != 6) {
         if (a_lay == kMnContig && b_lay == kKContig) return launch_main<IM, JN, kMnContig, kKContig>(a, s);
     }
-    if constexpr (JN == 8) {
+    if constexpr (JN != 6) {
         if (a_lay == kKContig && b_lay == kMnContig) return launch_main<IM, JN, kKContig, kMnContig>(a, s);
     }
-    if constexpr (IM == 8 && JN == 8) {
+    if constexpr (IM != 6 && JN != 6) {
         if (a_lay == kMnContig && b_lay == kMnContig) return launch_main<IM, JN, kMnContig, kMnContig>(a, s);
     }
     return hipErrorInvalidValue;

@@ -114,6 +114,18 @@ def test_dispatch_query_names_variants():
     assert qx(0, 0, 8004, 8004, 512, P, 512, P, 8008, P, 8004) == "gemm_bf16_kernel<4, 1, 0, 0, 1>"
     assert qx(0, 1, 8004, 8004, 512, P, 512, P, 512, P, 8004) == "gemm_bf16_main_kernel<6, 6, 0, 0>"
     assert qx(1, 0, 100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1, 1, 1>"
+    # such an operand takes tile sides of 256 and 128, not 192; the 128 x 128 tile from 4 tiles on (with both operands
+    # along k: from 192 tiles on, the general 64 x 64 tile below)
+    assert qx(0, 0, 1024, 1024, 1024, P, 1024, P, 1024, P, 1024) == "gemm_bf16_main_kernel<4, 4, 0, 1>"
+    assert qx(1, 1, 256, 256, 4096, P, 256, P, 4096, P, 256) == "gemm_bf16_main_kernel<4, 4, 1, 0>"
+    assert qx(1, 0, 2048, 2048, 2048, P, 2048, P, 2048, P, 2048) == "gemm_bf16_main_kernel<4, 4, 1, 1>"
+    assert qx(1, 0, 128, 256, 512, P, 128, P, 256, P, 256) == "gemm_bf16_kernel<1, 4, 0, 1, 1>"         # 2 tiles
+    assert qx(0, 1, 1024, 1024, 1024, P, 1024, P, 1024, P, 1024) == "gemm_bf16_kernel<1, 4, 0, 0, 0>"
+    qh = lib.fsrgemm_kernel_for_bf16_cfg
+    for tile, (im, jn) in {0: (8, 8), 5: (6, 8), 6: (4, 8), 7: (8, 6), 8: (6, 6), 9: (8, 4), 10: (4, 4)}.items():
+        for ta, tb in ((0, 1), (0, 0), (1, 1), (1, 0)):
+            name = "gemm_bf16_main_kernel<%d, %d, %d, %d>" % (im, jn, ta, 1 - tb) if (not ta or im != 6) and (tb or jn != 6) else None
+            assert qh(tile, ta, tb, 512, 512, 512, P, 512, P, 512, P, 512) == name
     assert qx(1, 0, 100, 90, 80, P, 99, P, 90, P, 90) is None                                 # lda < M for a transposed A
 
 
