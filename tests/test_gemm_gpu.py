@@ -252,7 +252,8 @@ def test_bf16_storage_orders(gpu, shape, ta, tb):
 
 @pytest.mark.parametrize("ta,tb", BF16_STORAGE)
 @pytest.mark.parametrize("shape", [(4096, 2048, 64), (4096, 2048, 192), (2304, 4096, 448),      # whole tiles, 1 / 3 / 7 K-tiles
-                                   (4000, 2104, 256), (2312, 3992, 128), (264, 33000, 64)])       # shifted last tiles
+                                   (4000, 2104, 256), (2312, 3992, 128), (264, 33000, 64),        # shifted last tiles
+                                   (1024, 768, 192), (256, 256, 1024), (264, 520, 328)])          # 128 x 128 tiles: k-rows of 256 bytes
 def test_bf16_main_kernel_storage_orders(gpu, shape, ta, tb):
     # operands contiguous along m / n in the direct-to-LDS kernel: k-row tiles and transposing fragment reads
     M, N, K = shape
@@ -1318,12 +1319,12 @@ def test_f32_two_band_product_of_integers_is_exact(gpu):
 
 @pytest.mark.parametrize("shape,ta,tb", [((7168, 7168, 2056), 0, 1), ((7168, 7168, 512), 0, 0), ((7000, 7168, 520), 1, 1), ((7168, 7168, 512), 1, 0)])
 def test_bf16_two_band_products(gpu, shape, ta, tb):
-    # the same for bf16 operands; storage orders whose plan is one launch are checked all the same
+    # the same for bf16 operands, in every storage order (with both operands contiguous along m / n: a 128-wide band)
     M, N, K = shape
     say("bf16 two bands %dx%dx%d transA=%d transB=%d" % (M, N, K, ta, tb))
     lda, ldb = (M if ta else K) + 8, (K if tb else N) + 16
     dim, at, first, second = gpu.fsrgemm_bands_bf16(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb)
-    assert (dim != 0) == ((ta, tb) != (1, 0)), "which of these cases take the two-band path"
+    assert dim != 0, "these cases take the two-band path"
     A = inputs.bf16_normal_scaled(32, 1, M, K, 1 / math.sqrt(K))
     B = inputs.bf16_normal_scaled(32, 2, K, N, 1 / math.sqrt(K))
     got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 4, repeat=2)
