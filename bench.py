@@ -28,8 +28,8 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense MFMA peaks
 # profiles/gemm_f32_4096_bf16_8192_hbm_traffic.txt (scaled by a 1 GiB copy).  Each entry is tied to the
 # kernel sources it was measured on: once those change the figure is stale and the bench reports null.
 TRAFFIC = {
-    "f32_4096": {"bytes": 470090268, "sources": {"gemm_f32_main.hip": "de51751b875e6a09", "common.hpp": "fcd7c27e4bf90732"}},
-    "bf16_8192": {"bytes": 2106284238, "sources": {"gemm_bf16_main.hip": "c142e6e0a7bd6985", "common.hpp": "fcd7c27e4bf90732"}},
+    "f32_4096": {"bytes": 470094957, "sources": {"gemm_f32_main.hip": "de51751b875e6a09", "common.hpp": "fcd7c27e4bf90732"}},
+    "bf16_8192": {"bytes": 2086171205, "sources": {"gemm_bf16_main.hip": "cdcef45d647db565", "common.hpp": "fcd7c27e4bf90732"}},
 }
 # the same for the transposes (profiles/transpose_f32_paper_sizes.txt), by N
 _T8_SOURCES = {"transpose.hip": "4a43b5ad193408de", "common.hpp": "fcd7c27e4bf90732"}
