@@ -204,8 +204,8 @@ int gemm_bf16_ws(int transA, int transB,
  * M or N a multiple of 4 for an operand contiguous along it),
  * bf16 tiles 0 and 5..10 with a split or where their kernel's
  * conditions fail (M, N at least one tile, K >= 64 and a multiple of 8, 16-byte aligned operands with leading
- * dimensions that are multiples of 8 and below 2^25; an operand contiguous along m or n only with its side of the
- * tile at 256 or 128 and M or N a multiple of 8).  Every other
+ * dimensions that are multiples of 8 and below 2^25; with an operand contiguous along m or n, M or N a multiple
+ * of 8).  Every other
  * candidate takes any shape and alignment.  All other arguments as for gemm_f32_ws / gemm_bf16_ws.
  */
 int gemm_f32_cfg(int tile, int k_slices, int transA, int transB,

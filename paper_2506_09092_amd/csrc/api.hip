@@ -349,7 +349,10 @@ constexpr int64_t kBf16MainPerRound[kBf16MainLarge] = {8700, 5800, 4700, 7700, 3
 int64_t bf16_main_cost(int sh, int64_t M, int64_t N, int64_t K)       // in 1/256 ns
 {
     const int64_t tiles = ceil_div(M, bf16_main_tile_m(sh)) * ceil_div(N, bf16_main_tile_n(sh)), rest = tiles % 256;
-    const int64_t rounds256 = tiles / 256 * 256 + (rest == 0 ? 0 : rest < 192 ? 192 : rest);       // in 1/256 of a round
+    // (a launch that is one partial round gains less from its idle compute units than a last round behind full ones:
+    // 192 tiles of 256 x 256 take 0.84 of a full round on 3072 x 4096 x 4096, 192 of 192 x 256 take 0.86 on 3072^3)
+    const int64_t least = tiles < 256 ? 220 : 192;
+    const int64_t rounds256 = tiles / 256 * 256 + (rest == 0 ? 0 : rest < least ? least : rest);       // in 1/256 of a round
     return rounds256 * (kBf16MainPerKTile[sh] * ceil_div(K, 64) + kBf16MainPerRound[sh]);
 }
 int tile_rule_bf16_main(int64_t M, int64_t N, int64_t K, unsigned fits, int64_t *cost_out = nullptr)

@@ -2,8 +2,8 @@
 // accumulate and output -- the Task 2 product at matrix-core input precision.
 // Either operand may be contiguous along k (a row-major A, a column-major B:
 // the tile's rows are 128 bytes of 64 k) or along m / n (a transposed A, a
-// row-major B: the tile's rows are k-rows of 512 or 256 bytes); LDS keeps the memory
-// order and the fragment reads do the rest (see "Fragments" below).
+// row-major B: the tile is kept as k-rows, 128 bytes of 64 m or n each); LDS keeps the
+// memory order and the fragment reads do the rest (see "Fragments" below).
 //
 // Shape of the computation (for the 256 x 256 tile; "Tile shapes" below)
 //   workgroup  : 256 lanes = 4 wavefronts, one per SIMD, 256 x 256 tile of C
@@ -72,13 +72,17 @@
 // 8 + i / 4 and 12 + i / 4 point at.  Lane s therefore points at k-row
 // k0 + s / 4, rows 4 (s % 4) .. + 3 of the block, and lane i ends up with
 // k0 .. k0 + 3 of row i; k0 = 8 (l / 16) for the first read, + 4 for the second.
-// Such a tile's k-rows are 512 bytes (side 256) or 256 bytes (side 128), a
-// whole number of trips round the 64 banks either way; 16-byte chunk c of
-// k-row k is stored at c ^ f(k), f(k) = 2 (k % 4) + 8 ((k / 8) % 2): the 32
-// lanes one pass of the read serves (4 + 4 k-rows, 32 bytes each) then cover
-// all 64 banks once.  A block's reads differ by an XOR in address bits 5-7,
-// so a lane keeps one address per block (one register per block and such
-// operand) and reaches k-step, half and stage through immediate offsets.
+// Such a tile is kept in LDS as sub-tiles of 64 rows (4 blocks), whatever
+// its side (256, 192 or 128: a k-row of 384 bytes would fit no power-of-two
+// scheme): a load places 8 k-rows of 128 bytes of one sub-tile, 16-byte chunk
+// c of k-row k at c ^ f(k), f(k) = 2 ((k / 2) % 2) + 4 ((k / 8) % 2).  The 32
+// lanes one pass of the read serves (4 + 4 k-rows, 32 bytes each; odd k-rows
+// start 128 bytes into the 256 the banks span) then cover all 64 banks once.
+// The blocks of a sub-tile differ by an XOR in address bits 5-6, so a lane
+// keeps one address per block (one register per block and such operand) and
+// reaches k-step, half and stage through immediate offsets.  (Whole k-rows
+// of 512 and 256 bytes with their own swizzle, the first design for sides of
+// 256 and 128, ran level with this on every size tried and were dropped.)
 //
 // Tile shapes.  A launch lasts as long as the compute unit with the most tiles, so a problem whose 256 x 256
 // tiles do not fill whole rounds of the compute units is better off with a tile that does: the kernel is a
@@ -86,8 +90,7 @@
 // and 128.  (A 128 x 128 tile asks the L2 for more bytes per cycle than a compute unit gets; it is there for problems
 // too small to give every compute unit a larger tile, where two such workgroups share a unit.)
 // Everything scales: IM + JN loads per wavefront and K-tile, IM + JN fragment reads and IM JN MFMAs per
-// k-step.  An operand that is contiguous along m / n needs its side at 256 or 128 (the swizzle above wants a k-row
-// that is a power of two long; 192 keeps such operands out).  The 128 x 128 tile has 16 MFMAs per half of
+// k-step.  The 128 x 128 tile has 16 MFMAs per half of
 // a K-tile: its loads sit behind every third MFMA and its fragment reads behind consecutive ones.
 //
 // Rest of K.  When K is not whole K-tiles (it is a multiple of 8, so a 16-byte piece lies inside K or beyond
@@ -228,14 +231,13 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// chunk swizzle of a tile whose rows are k-rows (operand contiguous along m / n)
-__device__ __forceinline__ int kswz(int k) { return ((k & 3) << 1) | (((k >> 3) & 1) << 3); }
+// chunk swizzle of k-row k of an operand that is contiguous along m / n (in units of 16-byte chunks)
+__device__ __forceinline__ int kswz(int k) { return (((k >> 1) & 1) | (((k >> 3) & 1) << 1)) << 1; }
 
 template <int IM, int JN, int ALAY, int BLAY>
 __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, int tiles_m, int tiles_n)
 {
     constexpr bool AMC = ALAY == kMnContig, BMC = BLAY == kMnContig;
-    static_assert((!AMC || IM == 8 || IM == 4) && (!BMC || JN == 8 || JN == 4), "an operand contiguous along m / n has a side of 256 or 128");
     constexpr int kBM = 32 * IM, kBN = 32 * JN;
     constexpr int kTileA = kBM * kBK * 2, kTileB = kBN * kBK * 2;       // operand tiles: 128 bytes per row
     constexpr int kStageBytes = kTileA + kTileB;
@@ -266,33 +268,27 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     //                           the chunk that belongs at its position, (lane % 8) ^ ((row >> 1) & 7), and
     //                           ((8 IM w + 8 q + lane / 8) >> 1) & 7 = 4 (q & 1) + (lane / 8 >> 1) for even IM: one lane
     //                           offset for even q, one for odd q.  The lane offsets also carry the K position.
-    //   contiguous along m / n: a k-row of the tile is 64 IM bytes = 4 IM chunks, so a load takes 16 / IM k-rows:
-    //                           k-rows 16 w + (16 / IM) q + lane / (4 IM); chunk (lane % (4 IM)) ^ kswz(k-row).
-    //                           Side 256: k-row % 4 = 2 (q & 1) + lane / 32 and (k-row / 8) % 2 = q / 4, four lane
-    //                           offsets, index (q & 1) + 2 (q >> 2).  Side 128: k-row % 4 = lane / 16 and
-    //                           (k-row / 8) % 2 = q / 2, two lane offsets, index 2 (q >> 1).  The K position is
-    //                           carried by the scalar row bases.
+    //   contiguous along m / n: 8 k-rows of one 64-row sub-tile per load, 128 bytes each: sub-tile q / 2, k-rows
+    //                           16 w + 8 (q & 1) + lane / 8, chunk (lane % 8) ^ kswz(k-row), and of the k-row only
+    //                           (k / 2) % 2 = (lane / 16) % 2 and (k / 8) % 2 = q & 1 enter kswz: one lane offset for
+    //                           even q, one for odd q.  The K position is carried by the scalar row bases.
     const int lrow = lane >> 3, lpos = lane & 7;
     const int sw_even = (lrow >> 1) & 3, sw_odd = sw_even ^ 4;
-    constexpr int kChunksA = 4 * IM, kChunksB = 4 * JN;         // 16-byte chunks of a k-row
-    constexpr int kRowsPerLoadA = 64 / kChunksA, kRowsPerLoadB = 64 / kChunksB;        // (of use for sides of 256 and 128 only)
-    const int hrow_a = lane / kChunksA, hpos_a = lane % kChunksA, hrow_b = lane / kChunksB, hpos_b = lane % kChunksB;
-    uint32_t voff_a[4], voff_b[4];      // bytes
+    uint32_t voff_a[2], voff_b[2];      // bytes
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const int kr_a = (IM == 8 ? 2 * (v & 1) : 0) + hrow_a + 8 * (v >> 1), kr_b = (JN == 8 ? 2 * (v & 1) : 0) + hrow_b + 8 * (v >> 1);
-        const int kc_chunk = lpos ^ ((v & 1) ? sw_odd : sw_even);
-        voff_a[v] = AMC ? (uint32_t)(hrow_a * g.lda * 2 + (hpos_a ^ kswz(kr_a)) * 16) : (uint32_t)(lrow * g.lda + kc_chunk * 8) * 2u;
-        voff_b[v] = BMC ? (uint32_t)(hrow_b * g.ldb * 2 + (hpos_b ^ kswz(kr_b)) * 16) : (uint32_t)(lrow * g.ldb + kc_chunk * 8) * 2u;
+    for (int v = 0; v < 2; ++v) {
+        const int kc_chunk = lpos ^ (v ? sw_odd : sw_even), mn_chunk = lpos ^ kswz(lrow + 8 * v);
+        voff_a[v] = AMC ? (uint32_t)(lrow * g.lda * 2 + mn_chunk * 16) : (uint32_t)(lrow * g.lda + kc_chunk * 8) * 2u;
+        voff_b[v] = BMC ? (uint32_t)(lrow * g.ldb * 2 + mn_chunk * 16) : (uint32_t)(lrow * g.ldb + kc_chunk * 8) * 2u;
     }
     const char *rbase[kLoads];      // row-group bases: uniform; fixed for the tile unless they carry the K position
 #pragma unroll
     for (int q = 0; q < kLoadsA; ++q)
-        rbase[q] = AMC ? reinterpret_cast<const char *>(A + (int64_t)(wave * 16 + q * kRowsPerLoadA) * g.lda + m0)
+        rbase[q] = AMC ? reinterpret_cast<const char *>(A + (int64_t)(wave * 16 + (q & 1) * 8) * g.lda + m0 + 64 * (q >> 1))
                        : reinterpret_cast<const char *>(A + (int64_t)(m0 + wave * (8 * IM) + q * 8) * g.lda);
 #pragma unroll
     for (int q = 0; q < kLoadsB; ++q)
-        rbase[kLoadsA + q] = BMC ? reinterpret_cast<const char *>(B + (int64_t)(wave * 16 + q * kRowsPerLoadB) * g.ldb + n0)
+        rbase[kLoadsA + q] = BMC ? reinterpret_cast<const char *>(B + (int64_t)(wave * 16 + (q & 1) * 8) * g.ldb + n0 + 64 * (q >> 1))
                                  : reinterpret_cast<const char *>(B + (int64_t)(n0 + wave * (8 * JN) + q * 8) * g.ldb);
     const int64_t kstep_a = 64 * g.lda * 2, kstep_b = 64 * g.ldb * 2;       // one K-tile of k-rows, in bytes
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(FSR_AS3 char *)smem);
@@ -308,9 +304,7 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     auto load_go = [&](auto idx) {
         constexpr int I = decltype(idx)::value, q = I < kLoadsA ? I : I - kLoadsA;
         constexpr bool mc = I < kLoadsA ? AMC : BMC;
-        constexpr int side = I < kLoadsA ? IM : JN;
-        constexpr int v = !mc ? (q & 1) : side == 8 ? (q & 1) + 2 * (q >> 2) : 2 * (q >> 1);
-        const uint32_t vo = I < kLoadsA ? voff_a[v] : voff_b[v];
+        const uint32_t vo = I < kLoadsA ? voff_a[q & 1] : voff_b[q & 1];
         const char *rb = rbase[I];
         asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(vo), "s"(rb) : "memory");
         if constexpr (mc) rbase[I] += more ? (I < kLoadsA ? kstep_a : kstep_b) : 0;      // its next use is the next K-tile
@@ -359,9 +353,10 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
 
     // Fragment addresses.  Contiguous along k: row l16 of the block, chunk 4 kk + lq; blocks are 2 KB apart.
     // Contiguous along m / n: as the source of a transposing read the lane points at k-row
-    // 32 kk + 8 lq + 4 h + l16 / 4 (h = 0, 1: the two reads), rows 16 b + 4 (l16 % 4) .. + 3 of the wavefront's
-    // part; block b flips address bits 5-7 (5-6 for a side of 128) with b, k-step and half add 32 and 4 k-rows.
-    constexpr int kRowBytesA = 64 * IM, kRowBytesB = 64 * JN;       // a k-row of such a tile
+    // k = 32 kk + 8 lq + 4 h + l16 / 4 (h = 0, 1: the two reads), rows 16 b + 4 (l16 % 4) .. + 3 of the wavefront's
+    // part.  K-row k of sub-tile u lies in the KB that wavefront k / 16 filled with its load 2 u + (k / 8) % 2, 128
+    // bytes per k-row, chunks swizzled by kswz(k) (which 4 h and 32 kk leave alone); block g of the tile's 2 IM is
+    // chunks 2 (g % 4), + 1 of sub-tile g / 4.  One address per lane and block; k-step and half add 2 IM KB and 512.
     int ra_off[2], rb_off[2], ra_blk[AMC ? IM : 1], rb_blk[BMC ? JN : 1];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
@@ -370,33 +365,38 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         rb_off[kk] = kTileA + (wn0 + l16) * 128 + pos * 16;
     }
     {
-        const int fk = kswz((l16 >> 2) + 8 * lq), half = (l16 >> 1) & 1;
-        const int krow = 8 * lq + (l16 >> 2), in_chunk = (l16 & 1) * 8;
-        // (the wavefront's first chunk, 2 IM or 0, and the swizzle may share a bit for a side of 128: XOR, not OR)
+        const int krow = 8 * lq + (l16 >> 2), half = (l16 >> 1) & 1;
+        const int in_kb = (krow & 7) * 128 + ((half ^ kswz(krow)) * 16) + (l16 & 1) * 8;
         if constexpr (AMC) {
 #pragma unroll
-            for (int b = 0; b < IM; ++b) ra_blk[b] = (krow * kRowBytesA + in_chunk + ((((wm0 / 8) ^ fk) | half) * 16)) ^ (b << 5);
+            for (int b = 0; b < IM; ++b) {
+                const int gb = wm0 / 16 + b;
+                ra_blk[b] = ((krow >> 4) * IM + 2 * (gb >> 2) + ((krow >> 3) & 1)) * 1024 + (in_kb ^ ((gb & 3) << 5));
+            }
         }
         if constexpr (BMC) {
 #pragma unroll
-            for (int b = 0; b < JN; ++b) rb_blk[b] = kTileA + ((krow * kRowBytesB + in_chunk + ((((wn0 / 8) ^ fk) | half) * 16)) ^ (b << 5));
+            for (int b = 0; b < JN; ++b) {
+                const int gb = wn0 / 16 + b;
+                rb_blk[b] = kTileA + ((krow >> 4) * JN + 2 * (gb >> 2) + ((krow >> 3) & 1)) * 1024 + (in_kb ^ ((gb & 3) << 5));
+            }
         }
     }
     bf16x8 Fa[2][IM], Fb[2][JN];        // [k-step][block row / column]
-    auto tr_read = [&](const char *p, int row_bytes) {
+    auto tr_read = [&](const char *p) {
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)p);
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)(p + 4 * row_bytes));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FSR_AS3 s16x4 *)(FSR_AS3 char *)(p + 512));
         return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
     // fragment r of k-step kk of the K-tile in `stage` (r < IM: a_r, else b_(r - IM)) into the registers of k-step kd
     auto lread = [&](int stage, int kk, int kd, int r) {
         const char *s = smem + stage * kStageBytes;
         if (r < IM) {
-            if constexpr (AMC) Fa[kd][r] = tr_read(s + ra_blk[r] + kk * (32 * kRowBytesA), kRowBytesA);
+            if constexpr (AMC) Fa[kd][r] = tr_read(s + ra_blk[r] + kk * (2048 * IM));
             else Fa[kd][r] = *reinterpret_cast<const bf16x8 *>(s + ra_off[kk] + r * 2048);
         } else {
             const int j = r - IM;
-            if constexpr (BMC) Fb[kd][j] = tr_read(s + rb_blk[j] + kk * (32 * kRowBytesB), kRowBytesB);
+            if constexpr (BMC) Fb[kd][j] = tr_read(s + rb_blk[j] + kk * (2048 * JN));
             else Fb[kd][j] = *reinterpret_cast<const bf16x8 *>(s + rb_off[kk] + j * 2048);
         }
     };
@@ -508,11 +508,10 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
         // (the lane id is taken afresh from the hardware: nothing of this step is to be worked out, and kept in registers, ahead of the loop)
         int ln = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
         asm volatile("" : "+v"(ln));
-        auto rest_src = [&](auto mcc, auto blocks, const uint16_t *P, int64_t ld, int origin, int rows_per_wave, int q) -> const uint16_t * {
+        auto rest_src = [&](auto mcc, const uint16_t *P, int64_t ld, int origin, int rows_per_wave, int q) -> const uint16_t * {
             if constexpr (decltype(mcc)::value) {
-                constexpr int chunks = 4 * decltype(blocks)::value;      // of a k-row; chunk = 8 rows / columns
-                const int kr = wave * 16 + q * (64 / chunks) + ln / chunks;       // k-row of the K-tile
-                return kr < k_rest ? P + (int64_t)(nk * kBK + kr) * ld + origin + 8 * ((ln % chunks) ^ kswz(kr)) : kZeroPiece;
+                const int kr = wave * 16 + (q & 1) * 8 + (ln >> 3);       // k-row of the K-tile, in sub-tile q / 2
+                return kr < k_rest ? P + (int64_t)(nk * kBK + kr) * ld + origin + 64 * (q >> 1) + 8 * ((ln & 7) ^ kswz(kr)) : kZeroPiece;
             } else {
                 const int row = ln >> 3, chunk = (ln & 7) ^ (((row >> 1) & 3) | ((q & 1) << 2));
                 return 8 * chunk < k_rest ? P + (int64_t)(origin + wave * rows_per_wave + q * 8 + row) * ld + nk * kBK + 8 * chunk : kZeroPiece;
@@ -523,8 +522,8 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
             const bool is_a = idx < kLoadsA;
             const int q = is_a ? idx : idx - kLoadsA;
             char *dst = smem + (is_a ? wave * (kLoadsA * 1024) : kTileA + wave * (kLoadsB * 1024)) + q * 1024;
-            const uint16_t *src = is_a ? rest_src(std::integral_constant<bool, AMC>{}, Int<IM>{}, A, g.lda, m0, 8 * IM, q)
-                                       : rest_src(std::integral_constant<bool, BMC>{}, Int<JN>{}, B, g.ldb, n0, 8 * JN, q);
+            const uint16_t *src = is_a ? rest_src(std::integral_constant<bool, AMC>{}, A, g.lda, m0, 8 * IM, q)
+                                       : rest_src(std::integral_constant<bool, BMC>{}, B, g.ldb, n0, 8 * JN, q);
             __builtin_amdgcn_global_load_lds((const FSR_AS1 void *)src, (FSR_AS3 void *)dst, 16, 0, 0);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -598,14 +597,14 @@ const char *bf16_main_kernel_name(int shape, int a_lay, int b_lay)
 // Whole unchecked tiles of 16-byte pieces: a matrix at least one tile high and wide (a ragged last tile is shifted
 // back into it), at least one whole K-tile of 64 and K a multiple of 8 (the rest of K is whole pieces), 16-byte aligned
 // bases and rows, leading dimensions below 2^25 (32-bit lane offsets); an operand that is contiguous along m (n) needs
-// its side of the tile at 256 or 128 and M (N) a multiple of 8, so that a shifted tile still starts on a piece.
+// M (N) a multiple of 8, so that a shifted tile still starts on a piece.
 bool bf16_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb)
 {
     if (shape < 0 || shape >= kBf16MainShapes) return false;
     const int bm = kShapeM[shape], bn = kShapeN[shape];
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15u) == 0 && lda % 8 == 0 && ldb % 8 == 0;
     return aligned && lda < (1 << 25) && ldb < (1 << 25) && M >= bm && N >= bn && K >= kBK && K % 8 == 0 &&
-           (a_lay == kKContig || (bm != 192 && M % 8 == 0)) && (b_lay == kKContig || (bn != 192 && N % 8 == 0)) &&
+           (a_lay == kKContig || M % 8 == 0) && (b_lay == kKContig || N % 8 == 0) &&
            ((M + bm - 1) / bm) * ((N + bn - 1) / bn) < ((int64_t)1 << 31);
 }
 
@@ -624,20 +623,13 @@ hipError_t launch_main(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
-// the layouts a shape is built for: an operand contiguous along m / n only with its side at 256 or 128
 template <int IM, int JN>
 hipError_t launch_shape(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
     if (a_lay == kKContig && b_lay == kKContig) return launch_main<IM, JN, kKContig, kKContig>(a, s);
-    if constexpr (IM != 6) {
-        if (a_lay == kMnContig && b_lay == kKContig) return launch_main<IM, JN, kMnContig, kKContig>(a, s);
-    }
-    if constexpr (JN != 6) {
-        if (a_lay == kKContig && b_lay == kMnContig) return launch_main<IM, JN, kKContig, kMnContig>(a, s);
-    }
-    if constexpr (IM != 6 && JN != 6) {
-        if (a_lay == kMnContig && b_lay == kMnContig) return launch_main<IM, JN, kMnContig, kMnContig>(a, s);
-    }
+    if (a_lay == kMnContig && b_lay == kKContig) return launch_main<IM, JN, kMnContig, kKContig>(a, s);
+    if (a_lay == kKContig && b_lay == kMnContig) return launch_main<IM, JN, kKContig, kMnContig>(a, s);
+    if (a_lay == kMnContig && b_lay == kMnContig) return launch_main<IM, JN, kMnContig, kMnContig>(a, s);
     return hipErrorInvalidValue;
 }
 

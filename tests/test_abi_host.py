@@ -114,8 +114,8 @@ def test_dispatch_query_names_variants():
     assert qx(0, 0, 8004, 8004, 512, P, 512, P, 8008, P, 8004) == "gemm_bf16_kernel<4, 1, 0, 0, 1>"
     assert qx(0, 1, 8004, 8004, 512, P, 512, P, 512, P, 8004) == "gemm_bf16_main_kernel<6, 6, 0, 0>"
     assert qx(1, 0, 100, 100, 100, P, 104, P, 104, P, 100) == "gemm_bf16_kernel<1, 4, 1, 1, 1>"
-    # such an operand takes tile sides of 256 and 128, not 192; the 128 x 128 tile from 4 tiles on (with both operands
-    # along k: from 192 tiles on, the general 64 x 64 tile below)
+    # with such an operand the 128 x 128 tile runs from 4 tiles on (with both operands along k: from 192 tiles on, the
+    # general 64 x 64 tile below)
     assert qx(0, 0, 1024, 1024, 1024, P, 1024, P, 1024, P, 1024) == "gemm_bf16_main_kernel<4, 4, 0, 1>"
     assert qx(1, 1, 256, 256, 4096, P, 256, P, 4096, P, 256) == "gemm_bf16_main_kernel<4, 4, 1, 0>"
     assert qx(1, 0, 2048, 2048, 2048, P, 2048, P, 2048, P, 2048) == "gemm_bf16_main_kernel<4, 4, 1, 1>"
@@ -124,8 +124,7 @@ def test_dispatch_query_names_variants():
     qh = lib.fsrgemm_kernel_for_bf16_cfg
     for tile, (im, jn) in {0: (8, 8), 5: (6, 8), 6: (4, 8), 7: (8, 6), 8: (6, 6), 9: (8, 4), 10: (4, 4)}.items():
         for ta, tb in ((0, 1), (0, 0), (1, 1), (1, 0)):
-            name = "gemm_bf16_main_kernel<%d, %d, %d, %d>" % (im, jn, ta, 1 - tb) if (not ta or im != 6) and (tb or jn != 6) else None
-            assert qh(tile, ta, tb, 512, 512, 512, P, 512, P, 512, P, 512) == name
+            assert qh(tile, ta, tb, 512, 512, 512, P, 512, P, 512, P, 512) == "gemm_bf16_main_kernel<%d, %d, %d, %d>" % (im, jn, ta, 1 - tb)
     assert qx(1, 0, 100, 90, 80, P, 99, P, 90, P, 90) is None                                 # lda < M for a transposed A
 
 
@@ -285,8 +284,11 @@ def test_forced_configurations_and_plan_queries():
     assert pb(0, 1, 8192, 8192, 8192, P, 8192, P, 8192) == (0, 1)
     assert pb(0, 1, 8192, 8192, 8200, P, 8200, P, 8200) == (0, 1)              # a rest of K in whole 16-byte pieces: still the direct-to-LDS kernel
     assert pb(0, 1, 8192, 8192, 8196, P, 8200, P, 8200) == (1, 1)              # otherwise the general kernel of that tile
-    assert pb(0, 1, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1) and pb(0, 0, 6144, 6144, 6144, P, 6144, P, 6144) == (5, 1)   # 256 x 192; with B along n, 192 x 256
-    assert pb(0, 1, 3072, 3072, 3072, P, 3072, P, 3072, False, True) == (5, 1) and pb(0, 1, 3072, 3072, 3072, P, 3072, P, 3072) == (8, 1)   # the rules; a row of the selection table
+    assert pb(0, 1, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1) and pb(0, 0, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1)   # 256 x 192, in every storage order
+    assert pb(0, 1, 2560, 2560, 2560, P, 2560, P, 2560, False, True) == (10, 1) and pb(0, 1, 2560, 2560, 2560, P, 2560, P, 2560) == (8, 1)   # the rules; a row of the selection table
+    for ta, tb in ((0, 1), (0, 0), (1, 1), (1, 0)):      # one round of 256 tiles of 192 x 192 rather than 192 of 192 x 256
+        assert pb(ta, tb, 3072, 3072, 3072, P, 3072, P, 3072) == (8, 1)
+    assert pb(0, 1, 3072, 4096, 4096, P, 4096, P, 4096) == (5, 1)                    # 256 tiles of 192 x 256 rather than 192 of 256 x 256
     assert pb(0, 1, 300, 300, 300, P, 300, P, 300) == (3, 1)
     assert pf(0, 0, -1, 1, 1, P, 1, P, 1) is None
     # a vector on one side: the streaming kernels (candidate 3), split along K only where the output alone gives few workgroups

@@ -36,6 +36,10 @@ F32 = [(n, n, n) for n in (256, 512, 768, 1024, 1536, 2048, 2560, 3072, 3584, 40
 BF16 = [(n, n, n) for n in (512, 1024, 1536, 2048, 2560, 3072, 3584, 4096, 5120, 6144, 7168, 8192)] + \
        [(1, 8192, 8192), (16, 8192, 8192), (256, 256, 65536), (512, 512, 16384)]
 
+# bf16 cubes in the other three storage orders (an operand contiguous along m / n takes the transposing LDS reads of the
+# direct-to-LDS kernel): (transA, transB) x size
+BF16_ORDERS = [(ta, tb, n) for n in (1024, 1536, 2048, 2560, 3072, 3584, 4096, 5120, 6144) for ta, tb in ((0, 0), (1, 1), (1, 0))]
+
 
 # the normal equations of the paper's Task 20: X^T X and X^T y for X of n x 10 (a transposed A against a row-major B)
 F32_TALL = [(10, 10, 1 << e) for e in (14, 18, 22)] + [(10, 1, 1 << e) for e in (14, 18, 22)]
@@ -103,7 +107,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", required=True)
     ap.add_argument("--log", default=None)
-    ap.add_argument("--only", choices=["f32", "bf16"], default=None)
+    ap.add_argument("--only", choices=["f32", "bf16", "bf16-orders"], default=None)
     ap.add_argument("--gain", type=float, default=0.04)
     args = ap.parse_args()
 
@@ -120,7 +124,8 @@ def main():
 
     problems = [Problem("f32", 0, 0, *s) for s in F32 if args.only in (None, "f32")] + \
                [Problem("f32", 1, 0, *s) for s in F32_TALL if args.only in (None, "f32")] + \
-               [Problem("bf16", 0, 1, *s) for s in BF16 if args.only in (None, "bf16")]
+               [Problem("bf16", 0, 1, *s) for s in BF16 if args.only in (None, "bf16")] + \
+               [Problem("bf16", ta, tb, n, n, n) for ta, tb, n in BF16_ORDERS if args.only in (None, "bf16-orders")]
     rows, reports = [], []
     for p in problems:
         log("== %s" % (p,))
