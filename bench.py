@@ -28,8 +28,8 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense MFMA peaks
 # profiles/gemm_f32_4096_bf16_8192_hbm_traffic.txt (scaled by a 1 GiB copy).  Each entry is tied to the
 # kernel sources it was measured on: once those change the figure is stale and the bench reports null.
 TRAFFIC = {
-    "f32_4096": {"bytes": 470094957, "sources": {"gemm_f32_main.hip": "de51751b875e6a09", "common.hpp": "fcd7c27e4bf90732"}},
-    "bf16_8192": {"bytes": 2086171205, "sources": {"gemm_bf16_main.hip": "cdcef45d647db565", "common.hpp": "fcd7c27e4bf90732"}},
+    "f32_4096": {"bytes": 470091089, "sources": {"gemm_f32_main.hip": "de51751b875e6a09", "common.hpp": "fcd7c27e4bf90732"}},
+    "bf16_8192": {"bytes": 2103968485, "sources": {"gemm_bf16_main.hip": "947b2a1ff8a60ba1", "common.hpp": "fcd7c27e4bf90732"}},
 }
 # the same for the transposes (profiles/transpose_f32_paper_sizes.txt), by N
 _T8_SOURCES = {"transpose.hip": "4a43b5ad193408de", "common.hpp": "fcd7c27e4bf90732"}
@@ -306,21 +306,23 @@ def transposed_storage_4096(lib, torch):
     return out
 
 
-def storage_orders_bf16_8192(lib, torch):
-    """bf16 8192^3 in the four storage pairs of gemm_bf16_ex: (0, 1) is the headline kernel's pair, the others
-    take the general kernel.  Median launch time on random operands; parity of these paths is a GPU test."""
+def storage_orders_bf16(lib, torch):
+    """bf16 cubes in the four storage pairs of gemm_bf16_ex: (0, 1) is the headline kernel's pair; an operand that
+    is contiguous along m / n goes through the transposing LDS reads of the same kernel, in every tile shape.
+    Median launch time on random operands; parity of these paths is a GPU test."""
     import math
 
-    n = 8192
-    a = (torch.randn(n, n, device="cuda") / math.sqrt(n)).to(torch.bfloat16)
-    b = (torch.randn(n, n, device="cuda") / math.sqrt(n)).to(torch.bfloat16)
-    c = torch.empty(n, n, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     out = []
-    for ta, tb in ((0, 1), (0, 0), (1, 1), (1, 0)):
-        ms = steady_ms(torch, lambda: lib.check(lib.gemm_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream)))
-        out.append({"transA": ta, "transB": tb, "kernel": lib.fsrgemm_kernel_for_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n),
-                    "ms": ms, "tflops": 2.0 * n ** 3 / (ms * 1e-3) / 1e12})
+    for n in (8192, 6144, 3072, 2048):
+        a = (torch.randn(n, n, device="cuda") / math.sqrt(n)).to(torch.bfloat16)
+        b = (torch.randn(n, n, device="cuda") / math.sqrt(n)).to(torch.bfloat16)
+        c = torch.empty(n, n, device="cuda")
+        for ta, tb in ((0, 1), (0, 0), (1, 1), (1, 0)):
+            ms = steady_ms(torch, lambda: lib.check(lib.gemm_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n, stream)))
+            out.append({"n": n, "transA": ta, "transB": tb, "kernel": lib.fsrgemm_kernel_for_bf16_ex(ta, tb, n, n, n, a, n, b, n, c, n),
+                        "ms": ms, "tflops": 2.0 * n ** 3 / (ms * 1e-3) / 1e12})
+        del a, b, c
     return out
 
 
@@ -580,7 +582,7 @@ def main():
         mid = mid_sizes_f32(lib, torch)
         mid16 = mid_sizes_bf16(lib, torch)
         layouts = transposed_storage_4096(lib, torch)
-        layouts_bf16 = storage_orders_bf16_8192(lib, torch)
+        layouts_bf16 = storage_orders_bf16(lib, torch)
         skinny = split_k(lib, torch, "f32")
         skinny_bf16 = split_k(lib, torch, "bf16")
         task8 = transpose_sizes(lib, torch)
@@ -621,7 +623,7 @@ def main():
         "mid_sizes_f32": mid,
         "mid_sizes_bf16": mid16,
         "transposed_storage_f32_4096": layouts,
-        "storage_orders_bf16_8192": layouts_bf16,
+        "storage_orders_bf16": layouts_bf16,
         "split_k_f32": skinny,
         "split_k_bf16": skinny_bf16,
         "paper_task8_transpose": task8,
