@@ -355,6 +355,15 @@ int64_t bf16_main_cost(int sh, int64_t M, int64_t N, int64_t K)       // in 1/25
     const int64_t rounds256 = tiles / 256 * 256 + (rest == 0 ? 0 : rest < least ? least : rest);       // in 1/256 of a round
     return rounds256 * (kBf16MainPerKTile[sh] * ceil_div(K, 64) + kBf16MainPerRound[sh]);
 }
+// The same for the 128 x 128 tile, in the same units: up to 256 tiles run one to a compute unit (450 ns per K-tile),
+// beyond that two share a unit and its L2 path (780 ns: 2048^2 and 2048 x 4096 with K = 128 ... 8192); the time around
+// the K-tiles is taken as that of the 128 x 256 shape, so that a short K does not decide between the two by it.
+int64_t bf16_main128_cost(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128), nk = ceil_div(K, 64), rest = tiles % 512;
+    const int64_t one = 450 * nk + 4700, two = 780 * nk + 5400;
+    return tiles / 512 * 256 * two + (rest == 0 ? 0 : rest <= 256 ? (rest < 220 ? 220 : rest) * one : 256 * two);
+}
 int tile_rule_bf16_main(int64_t M, int64_t N, int64_t K, unsigned fits, int64_t *cost_out = nullptr)
 {
     int best = -1;
@@ -434,8 +443,17 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     // (with an operand contiguous along m / n the general kernel stages through registers and is slower: there the
     // 128 x 128 tile wins from 4 tiles on -- level at 256^3 and 512^3, 768^3 83-105 -> 107-112, 1024^3 156-198 -> 212-222,
     // 1536^3 194-290 -> 392-405, 256^2 x 65536 0.69-0.87 -> 0.59-0.60 ms)
-    else if ((main_fits >> kBf16MainLarge & 1) && ceil_div(M, 128) * ceil_div(N, 128) >= (a_lay == kKContig && b_lay == kKContig ? 192 : 4))
+    else if ((main_fits >> kBf16MainLarge & 1) && ceil_div(M, 128) * ceil_div(N, 128) >= (a_lay == kKContig && b_lay == kKContig ? 192 : 4)) {
         p->cfg = bf16_main_candidate(kBf16MainLarge);
+        // between 64 and 127 tiles of 256 x 256 a larger shape in one round can beat two 128 x 128 tiles to a compute unit
+        // (2048 x 2560 x 8192 852 -> 956 TFLOP/s on 128 x 256, 1792 x 4096 x 4096 1022 -> 1063): by the modelled times, where
+        // K is long enough for them to be about the K-tiles (with K = 256 the shapes' fitted constants would decide)
+        if (ceil_div(M, 256) * ceil_div(N, 256) >= 64 && K >= 1024) {
+            int64_t cost = 0;
+            const int sh = tile_rule_bf16_main(M, N, K, main_fits & ((1u << kBf16MainLarge) - 1), &cost);
+            if (sh >= 0 && cost < bf16_main128_cost(M, N, K)) p->cfg = bf16_main_candidate(sh);
+        }
+    }
     else if (ceil_div(M, 128) * ceil_div(N, 128) >= 256) p->cfg = kBf16_128x128;
     else p->cfg = kBf16_64x64;
     if (p->cfg == kBf16_Vector) {       // a row of the selection table
