@@ -624,7 +624,7 @@ def test_bf16_8192_full_size(gpu):
 @pytest.mark.parametrize("shape,kernel", [((6144, 6144, 6144), "gemm_bf16_main_kernel<8, 6, 0, 0>"),       # 768 tiles of 256 x 192: three whole rounds
                                           ((3072, 8192, 4096), "gemm_bf16_main_kernel<6, 8, 0, 0>"),       # 512 tiles of 192 x 256
                                           ((8192, 8192, 8200), "gemm_bf16_main_kernel<8, 8, 0, 0>"),       # a rest of K, rows that straddle cache lines
-                                          ((3072, 3072, 3072), "gemm_bf16_main_kernel<6, 6, 0, 0>")])      # a row of the selection table: 192 x 192
+                                          ((3072, 3072, 3072), "gemm_bf16_main_kernel<6, 6, 0, 0>")])      # one round of 256 tiles of 192 x 192
 def test_bf16_mid_sizes_in_the_timed_configuration(gpu, shape, kernel):
     # the problems the bench's mid_sizes_bf16 section times, in the tile shape the dispatcher takes for them: an entry in
     # every 16 x 16 block against the oracle, and the Freivalds residual over all entries
@@ -640,6 +640,24 @@ def test_bf16_mid_sizes_in_the_timed_configuration(gpu, shape, kernel):
     r = oracle.freivalds_residual(A, Bt.T, got)
     say("  %d entries: componentwise error %.3e; Freivalds residual %.3e (gate %.3e)" % (ii.size, e, r, freivalds_gate(N, K)))
     assert e <= TOL_BF16 and r <= freivalds_gate(N, K)
+
+
+@pytest.mark.parametrize("n,ta,tb,kernel", [(8192, 1, 0, "gemm_bf16_main_kernel<8, 8, 1, 1>"), (6144, 0, 0, "gemm_bf16_main_kernel<8, 6, 0, 1>"),
+                                            (3072, 1, 1, "gemm_bf16_main_kernel<6, 6, 1, 0>"), (2048, 1, 0, "gemm_bf16_main_kernel<4, 4, 1, 1>")])
+def test_bf16_storage_orders_in_the_timed_configuration(gpu, n, ta, tb, kernel):
+    # cubes the bench's storage_orders_bf16 section times, with operands contiguous along m / n, in the tile shape the
+    # dispatcher takes: an entry in every 16 x 16 block against the oracle, and the Freivalds residual over all entries
+    say("bf16 %d^3 transA=%d transB=%d (%s)" % (n, ta, tb, kernel))
+    assert gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, n, n, n, 0x1000, n, 0x1000, n, 0x1000, n) == kernel
+    A = inputs.bf16_normal_scaled(4, 92, n, n, 1 / math.sqrt(n))
+    B = inputs.bf16_normal_scaled(4, 93, n, n, 1 / math.sqrt(n))
+    got = run_bf16_ex(gpu, ta, tb, A, B)
+    ii, jj = one_entry_per_block(n, n, 16, 92)
+    c, s = oracle.gemm_entries(A, B, ii, jj)
+    e = oracle.componentwise_error(got[ii, jj], c, s)
+    r = oracle.freivalds_residual(A, B, got)
+    say("  %d entries: componentwise error %.3e; Freivalds residual %.3e (gate %.3e)" % (ii.size, e, r, freivalds_gate(n, n)))
+    assert e <= TOL_BF16 and r <= freivalds_gate(n, n)
 
 
 def test_f32_rest_of_k_on_the_largest_tile(gpu):
