@@ -836,6 +836,31 @@ def test_random_larger_aligned_shapes_through_the_plain_entry_points(gpu):
     assert {("f32", True), ("f32", False), ("bf16", False)} <= seen and len([x for x in seen if not isinstance(x[1], bool)]) >= 6, seen
 
 
+def test_random_small_bf16_shapes_in_every_storage_order(gpu):
+    # 32 seeded bf16 cases of 128 .. 1280 rows and columns (multiples of 8, ragged against the 128 x 128 tile) in the
+    # four storage orders with padded leading dimensions: with an operand contiguous along m / n the dispatcher takes the
+    # direct-to-LDS kernel's 128 x 128 tile from four tiles on, below that (and for K < 64) the general kernel
+    import random
+
+    rng = random.Random(34)
+    main = 0
+    for case in range(32):
+        ta, tb = ((0, 0), (1, 1), (1, 0), (0, 1))[case % 4]
+        M, N, K = 8 * rng.randint(16, 160), 8 * rng.randint(16, 160), 8 * rng.randint(4, 200)
+        pad = 8 * rng.choice((0, 1, 5))
+        lda, ldb = (M if ta else K) + pad, (K if tb else N) + pad
+        A = inputs.bf16_normal_scaled(34, 2 * case, M, K, 1 / math.sqrt(K))
+        B = inputs.bf16_normal_scaled(34, 2 * case + 1, K, N, 1 / math.sqrt(K))
+        name = gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N)
+        say("small case %d: bf16 %d%d %dx%dx%d lda %d ldb %d -> %s" % (case, ta, tb, M, N, K, lda, ldb, name))
+        main += name.startswith("gemm_bf16_main_kernel<4, 4")
+        ref, S = oracle.gemm(A, B)
+        got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + rng.choice((0, 4)), repeat=2)
+        e = oracle.componentwise_error(got, ref, S)
+        assert e <= 1e-5, (case, ta, tb, M, N, K, name, e)
+    assert main >= 12, main
+
+
 # ---- the library under HIP graph capture ----
 
 def test_calls_captured_in_a_hip_graph_replay_bit_exact(gpu):
