@@ -32,9 +32,9 @@ TRAFFIC = {
     "bf16_8192": {"bytes": 2103968485, "sources": {"gemm_bf16_main.hip": "947b2a1ff8a60ba1", "common.hpp": "fcd7c27e4bf90732"}},
 }
 # the same for the transposes (profiles/transpose_f32_paper_sizes.txt), by N
-_T8_SOURCES = {"transpose.hip": "4a43b5ad193408de", "common.hpp": "fcd7c27e4bf90732"}
+_T8_SOURCES = {"transpose.hip": "98f5436f921534d2", "common.hpp": "fcd7c27e4bf90732"}
 TRAFFIC.update({"transpose_%d" % n: {"bytes": b, "sources": _T8_SOURCES}
-                for n, b in ((1024, 8433502), (2048, 33598846), (4096, 134260222), (8192, 536905727), (16384, 2147491840))})
+                for n, b in ((1024, 8417187), (2048, 33582523), (4096, 134260464), (8192, 536906752), (16384, 2147493058))})
 
 
 def measured_traffic(name):

@@ -3,7 +3,7 @@
 // writes coalesced, the exchange done in on-chip memory without bank conflicts).
 //
 // The operation moves every element once in and once out, so HBM bandwidth bounds it.  One workgroup of 256
-// lanes moves a TR x TC tile (64 x 128, or 64 x 64 for matrices with fewer than 128 columns) through LDS:
+// lanes moves a TR x TC tile (64 x 128; 64 x 64 for matrices with fewer than 128 columns; 32 x 64 for small ones) through LDS:
 // TC / 4 lanes read a contiguous piece of an input row (16 bytes each), the values are written to LDS
 // transposed, and after a barrier TR / 4 lanes write a contiguous piece of an output row.  The LDS tile has
 // rows of TR + 1 words: both the transposed writes and the row reads hit 64 different banks.
@@ -80,10 +80,16 @@ hipError_t launch(const float *A, int64_t lda, float *T, int64_t ldt, int rows, 
 
 }  // namespace
 
+// A matrix that gives the 64 x 128 tile no more than two workgroups per compute unit is moved in 32 x 64 tiles: such a
+// launch is a few microseconds of latency, not of bandwidth, and four times the workgroups hide more of it (1024^2
+// 8.0 -> 3.9 us, 2048^2 5.8 -> 4.9; level at 4096^2, 8 % slower at 8192^2 and beyond).
+static bool small_matrix(int rows, int cols) { return (int64_t)((rows + 63) / 64) * ((cols + 127) / 128) <= 512; }
+
 // <tile rows, tile columns, checked>: as a profiler trace prints the kernel
 const char *transpose_kernel_name(int rows, int cols)
 {
     if (rows < 64 || cols < 64) return "transpose_f32_kernel<64, 64, true>";
+    if (small_matrix(rows, cols)) return "transpose_f32_kernel<32, 64, false>";
     return cols >= 128 ? "transpose_f32_kernel<64, 128, false>" : "transpose_f32_kernel<64, 64, false>";
 }
 
@@ -91,6 +97,7 @@ const char *transpose_kernel_name(int rows, int cols)
 hipError_t launch_transpose_f32(const float *A, int64_t lda, float *T, int64_t ldt, int rows, int cols, hipStream_t s)
 {
     if (rows < 64 || cols < 64) return launch<64, 64, true>(A, lda, T, ldt, rows, cols, s);
+    if (small_matrix(rows, cols)) return launch<32, 64, false>(A, lda, T, ldt, rows, cols, s);
     if (cols >= 128) return launch<64, 128, false>(A, lda, T, ldt, rows, cols, s);
     return launch<64, 64, false>(A, lda, T, ldt, rows, cols, s);
 }

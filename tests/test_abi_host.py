@@ -405,8 +405,10 @@ def test_transpose_argument_checks():
     # <tile rows, tile columns, bounds-checked>: wide tiles from 128 columns on, checks only below 64 rows or columns
     q = lib.fsrgemm_kernel_for_transpose_f32
     assert q(4096, 4096, P, 4096, P, 4096) == "transpose_f32_kernel<64, 128, false>"
-    assert q(64, 128, P, 128, P, 64) == "transpose_f32_kernel<64, 128, false>"
-    assert q(5000, 127, P, 127, P, 5000) == "transpose_f32_kernel<64, 64, false>"
+    assert q(2048, 2176, P, 2176, P, 2048) == "transpose_f32_kernel<64, 128, false>"
+    # up to 512 tiles of 64 x 128 (two to a compute unit): 32 x 64 tiles
+    assert q(64, 128, P, 128, P, 64) == q(2048, 2048, P, 2048, P, 2048) == q(5000, 127, P, 127, P, 5000) == "transpose_f32_kernel<32, 64, false>"
+    assert q(40000, 127, P, 127, P, 40000) == "transpose_f32_kernel<64, 64, false>"
     assert q(63, 4096, P, 4096, P, 63) == q(4096, 63, P, 63, P, 4096) == "transpose_f32_kernel<64, 64, true>"
     assert q(0, 8, None, 8, None, 0) == "none" and q(4, 8, P, 7, P, 4) is None and q(4, 8, None, 8, P, 4) is None
 

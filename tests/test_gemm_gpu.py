@@ -1274,7 +1274,8 @@ def _check_transpose(gpu, A, **kw):
 
 @pytest.mark.parametrize("shape", [(1, 1), (1, 5000), (5000, 1), (63, 5), (64, 64), (65, 64), (64, 127), (100, 300),
                                    (257, 255), (1000, 1000), (4097, 17), (17, 4097), (1023, 2049),
-                                   (64, 128), (64, 129), (70, 128), (129, 255), (200, 64), (63, 128), (3000, 127)])
+                                   (64, 128), (64, 129), (70, 128), (129, 255), (200, 64), (63, 128), (3000, 127),
+                                   (2100, 2300), (1100, 7777), (40000, 100), (33000, 127)])     # beyond the small-matrix tile: 64 x 128, 64 x 64
 def test_transpose_shapes(gpu, shape):
     rows, cols = shape
     say("transpose %dx%d" % shape)
