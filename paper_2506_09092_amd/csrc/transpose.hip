@@ -81,8 +81,8 @@ hipError_t launch(const float *A, int64_t lda, float *T, int64_t ldt, int rows, 
 }  // namespace
 
 // A matrix that gives the 64 x 128 tile no more than two workgroups per compute unit is moved in 32 x 64 tiles: such a
-// launch is a few microseconds of latency, not of bandwidth, and four times the workgroups hide more of it (1024^2
-// 8.0 -> 3.9 us, 2048^2 5.8 -> 4.9; level at 4096^2, 8 % slower at 8192^2 and beyond).
+// launch is a few microseconds of latency, not of bandwidth, and four times the workgroups hide more of it (kernel
+// time 1024^2 3.4 -> 3.0 us, 2048^2 6.5 -> 5.3; level at 4096^2, 8 % slower at 8192^2 and beyond).
 static bool small_matrix(int rows, int cols) { return (int64_t)((rows + 63) / 64) * ((cols + 127) / 128) <= 512; }
 
 // <tile rows, tile columns, checked>: as a profiler trace prints the kernel
