@@ -196,6 +196,13 @@ class DeviceBackend:
         one = max(e0.elapsed_time(e1) / n, 1e-3)
         for r in range(int(min(256, warm_ms / one))):
             self._call(c, r % n)
+        # the first calls may have paid for a first launch: size the runs by a run of warm calls
+        e0.record()
+        for r in range(16):
+            self._call(c, r % n)
+        e1.record()
+        torch.cuda.synchronize()
+        one = max(min(one, e0.elapsed_time(e1) / 16), 1e-3)
         reps = int(max(1, min(64, min_ms / one)))
         times = []
         for i in range(samples):

@@ -285,7 +285,8 @@ def test_forced_configurations_and_plan_queries():
     assert pb(0, 1, 8192, 8192, 8200, P, 8200, P, 8200) == (0, 1)              # a rest of K in whole 16-byte pieces: still the direct-to-LDS kernel
     assert pb(0, 1, 8192, 8192, 8196, P, 8200, P, 8200) == (1, 1)              # otherwise the general kernel of that tile
     assert pb(0, 1, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1) and pb(0, 0, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1)   # 256 x 192, in every storage order
-    assert pb(0, 1, 1536, 1536, 1536, P, 1536, P, 1536, False, True) == (3, 1) and pb(0, 1, 1536, 1536, 1536, P, 1536, P, 1536) == (10, 1)   # the rules; a row of the selection table
+    assert pb(0, 1, 512, 512, 512, P, 512, P, 512, True, True) == (3, 2) and pb(0, 1, 512, 512, 512, P, 512, P, 512, True) == (10, 1)   # the rules; a row of the selection table
+    assert pf(0, 0, 512, 512, 512, P, 512, P, 512, True, True) == (2, 2) and pf(0, 0, 512, 512, 512, P, 512, P, 512, True) == (2, 4)         # the same for fp32
     # between 64 and 127 tiles of 256 x 256: a larger shape in one round, or 128 x 128 tiles, by the modelled times
     assert pb(0, 1, 2560, 2560, 2560, P, 2560, P, 2560) == (6, 1) and pb(1, 0, 2048, 2560, 8192, P, 2048, P, 2560) == (6, 1)
     assert pb(0, 1, 2048, 2048, 2048, P, 2048, P, 2048) == (10, 1) and pb(0, 1, 2048, 2048, 512, P, 512, P, 512) == (10, 1)
@@ -372,7 +373,10 @@ def test_tuned_table_rows_are_well_formed():
         plan = (lib.fsrgemm_plan_bf16 if kind else lib.fsrgemm_plan_f32)(ta, tb, M, N, K, P, M if ta else K, P, K if tb else N, bool(ws))
         assert plan == (tile, slices), (plan, (tile, slices))
         rules = (lib.fsrgemm_plan_bf16 if kind else lib.fsrgemm_plan_f32)(ta, tb, M, N, K, P, M if ta else K, P, K if tb else N, bool(ws), True)
-        assert rules != plan                                              # a row that repeats the rules is never written
+        bands = (lib.fsrgemm_bands_bf16 if kind else lib.fsrgemm_bands_f32)(ta, tb, M, N, K, P, M if ta else K, P, K if tb else N, bool(ws), True)
+        assert rules != plan or bands[0] != 0                             # a row that repeats the rules is never written (one launch
+                                                                          # of the first band's tile is not the rules' two bands)
+        assert (lib.fsrgemm_bands_bf16 if kind else lib.fsrgemm_bands_f32)(ta, tb, M, N, K, P, M if ta else K, P, K if tb else N, bool(ws))[0] == 0    # a row is one launch
         if ws:
             q = lib.gemm_bf16_workspace_bytes if kind else lib.gemm_f32_workspace_bytes
             assert q(ta, tb, M, N, K) == (slices * M * N * 4 if slices > 1 else 0)
