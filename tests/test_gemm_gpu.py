@@ -101,6 +101,28 @@ def test_f32_transposed_storage_sweep(gpu):
     assert not failed, failed
 
 
+def test_bf16_sweep_64_shapes_every_storage_order(gpu):
+    # the 64 sweep shapes (ragged, padded, offset by an element) with bf16 operands in the four storage orders; one
+    # oracle result per shape serves all four.  Products of bf16 values are exact in fp32, so the error is that of fp32
+    # accumulation and the fp32 bound holds as well as the bf16 one
+    cases = inputs.sweep_cases(3, 64)
+    failed = []
+    for c in cases:
+        M, N, K = c["M"], c["N"], c["K"]
+        say("bf16 sweep case %d: M=%d N=%d K=%d" % (c["index"], M, N, K))
+        A = inputs.bf16_normal_scaled(3, 2 * c["index"] + 10, M, K, 1 / math.sqrt(max(K, 1)))
+        B = inputs.bf16_normal_scaled(3, 2 * c["index"] + 11, K, N, 1 / math.sqrt(max(K, 1)))
+        ref, S = oracle.gemm(A, B)
+        pad_a, pad_b = c["lda"] - K, c["ldb"] - N
+        for ta, tb in [(0, 1)] + BF16_STORAGE:
+            lda, ldb = (M if ta else K) + pad_a, (K if tb else N) + pad_b
+            got = run_bf16_ex(gpu, ta, tb, A, B, lda=max(lda, 1), ldb=max(ldb, 1), ldc=c["ldc"], offset=c["offset"], repeat=2)
+            e = oracle.componentwise_error(got, ref, S)
+            if not e <= TOL_F32:
+                failed.append((c["index"], ta, tb, e))
+    assert not failed, failed
+
+
 @pytest.mark.parametrize("ta,tb", LAYOUTS)
 def test_f32_transposed_storage_tile_configs(gpu, ta, tb):
     # every tile configuration in its unchecked-vector mode, small K included, and integers bit for bit
