@@ -564,7 +564,7 @@ def main():
     if not args.no_validate:
         log("validator: 64-shape sweep + fixed configs against the oracle")
         sweep = validator.run_validator(lib, log)
-        log("  pass rate %d/%d" % (sweep["passed"], sweep["total"]))
+        log("  pass rate %d/%d (fp32), %d/%d (bf16)" % (sweep["passed"], sweep["total"], sweep["bf16_sweep"]["passed"], sweep["bf16_sweep"]["total"]))
 
     results, baselines = {}, {}
     for name in ("f32_4096", "bf16_8192"):

@@ -11,7 +11,8 @@ from paper_2506_09092_amd.harness import run_bf16, run_f32
 
 
 def run_validator(lib, log=print):
-    """Pass rate of the 64-shape fp32 sweep plus the small fixed configurations, against the CPU oracle."""
+    """Pass rate of the 64-shape sweep (fp32, and the same shapes with bf16 operands) plus the small fixed configurations,
+    against the CPU oracle."""
     passed, total, worst = 0, 0, 0.0
     for c in inputs.sweep_cases(3, 64):
         A = inputs.uniform_pm1(3, 2 * c["index"] + 10, c["M"], c["K"])
@@ -25,6 +26,20 @@ def run_validator(lib, log=print):
             passed += int(e <= 1e-5)
         except Exception as ex:       # a failed launch or a trampled canary counts as a failed case
             log("sweep case %d failed: %s" % (c["index"], ex))
+    # the same shapes through gemm_bf16 (A row-major, B column-major; bf16 tolerance 1e-2)
+    passed16, worst16 = 0, 0.0
+    for c in inputs.sweep_cases(3, 64):
+        M, N, K = c["M"], c["N"], c["K"]
+        A = inputs.bf16_normal_scaled(3, 2 * c["index"] + 10, M, K, 1 / np.sqrt(max(K, 1)))
+        Bt = inputs.bf16_normal_scaled(3, 2 * c["index"] + 11, N, K, 1 / np.sqrt(max(K, 1)))
+        try:
+            got = run_bf16(lib, A, Bt, lda=max(c["lda"], 1), ldb=max(K + c["ldb"] - N, 1), ldc=c["ldc"], offset=c["offset"], repeat=2)
+            ref, S = oracle.gemm(A, np.ascontiguousarray(Bt.T))
+            e = oracle.componentwise_error(got, ref, S)
+            worst16 = max(worst16, e)
+            passed16 += int(e <= 1e-2)
+        except Exception as ex:
+            log("bf16 sweep case %d failed: %s" % (c["index"], ex))
     fixed = {}
     A, B = inputs.small_ints(0, 3, 256, 256), inputs.small_ints(0, 4, 256, 256)
     fixed["f32_256_int_bit_exact"] = bool(np.array_equal(run_f32(lib, A, B).astype(np.float64), oracle.gemm(A, B)[0]))
@@ -37,7 +52,8 @@ def run_validator(lib, log=print):
     A, Bt = inputs.bf16_small_ints(4, 30, 512, 512), inputs.bf16_small_ints(4, 31, 512, 512)
     fixed["bf16_512_int_bit_exact"] = bool(np.array_equal(run_bf16(lib, A, Bt).astype(np.float64), oracle.gemm(A, Bt.T)[0]))
     return dict(passed=passed, total=total, pass_rate=passed / total, worst_componentwise_error=worst,
-                tolerance=1e-5, fixed_configs=fixed)
+                tolerance=1e-5, fixed_configs=fixed,
+                bf16_sweep=dict(passed=passed16, total=total, pass_rate=passed16 / total, worst_componentwise_error=worst16, tolerance=1e-2))
 
 
 def one_entry_per_block(M, N, block, seed):
