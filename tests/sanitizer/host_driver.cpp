@@ -17,7 +17,7 @@ template <class T, size_t N> static T pick(const T (&a)[N]) { return a[next() % 
 
 int main()
 {
-    const int64_t dims[] = {0, 1, 2, 7, 10, 16, 17, 63, 64, 65, 255, 256, 257, 1000, 4096, 4097, 8192, 1 << 16, 1 << 20, (1 << 22) + 3, (1ll << 31) - 1};
+    const int64_t dims[] = {0, 1, 2, 7, 10, 16, 17, 63, 64, 65, 255, 256, 257, 1000, 2048, 2560, 3072, 4096, 4097, 5120, 8192, 1 << 16, 1 << 20, (1 << 22) + 3, (1ll << 31) - 1};
     const int64_t pads[] = {0, 0, 1, 3, 4, 8, 1 << 24, 1ll << 25, 1ll << 31};
     const uintptr_t offs[] = {0, 0, 1, 2, 4};
     const uintptr_t P = 0x1000;
