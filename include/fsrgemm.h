@@ -95,7 +95,9 @@ int gemm_f32_ex(int transA, int transB,
  * goes to the workspace and a second kernel adds the slices in slice order, so the result is still the same
  * on every call (it may differ in the last bits from gemm_f32_ex, which sums along K in one piece).
  *   gemm_f32_workspace_bytes: bytes that make the split possible for this shape, 0 when the problem is not
- *     split (the answer depends on M, N, K and the storage orders only; at most 16 MiB).
+ *     split (the answer depends on M, N, K and the storage orders only; at most 16 MiB).  How a problem is cut
+ *     also depends on the operands' alignment (16-byte aligned bases and rows let the direct-to-LDS kernel take
+ *     the slices); the figure is the larger of the two needs, so a call may use less of the workspace than it names.
  *   gemm_f32_ws: as gemm_f32_ex; `workspace` is device memory of `workspace_bytes` bytes, 4-byte aligned, not
  *     overlapping A, B or C, owned by the caller and free for reuse once the stream has passed the call.
  *     Its contents on entry are ignored, on exit unspecified.  With a NULL, misaligned or too small workspace
@@ -199,9 +201,10 @@ int gemm_bf16_ws(int transA, int transB,
  * count out of range, a split without a fitting workspace, fp32 candidate 3 or bf16 candidate 4 on a product
  * without a vector,
  * fp32 candidate 4 on a result that is too large,
- * fp32 tiles 5..16 with a split or where their kernel's conditions fail (M, N at least one tile, K >= 32 and a
+ * fp32 tiles 5..16 where their kernel's conditions fail (M, N at least one tile, K >= 32 and a
  * multiple of 4, 16-byte aligned operands with leading dimensions that are multiples of 4 and below 2^24;
- * M or N a multiple of 4 for an operand contiguous along it),
+ * M or N a multiple of 4 for an operand contiguous along it) or with a slice count that does not leave every
+ * slice a whole K-tile (slices are ceil(ceil(K / 32) / k_slices) K-tiles of 32 long, the last one takes the rest),
  * bf16 tiles 0 and 5..10 with a split or where their kernel's
  * conditions fail (M, N at least one tile, K >= 64 and a multiple of 8, 16-byte aligned operands with leading
  * dimensions that are multiples of 8 and below 2^25; with an operand contiguous along m or n, M or N a multiple

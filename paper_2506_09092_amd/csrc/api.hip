@@ -139,6 +139,39 @@ int tile_rule_f32(int64_t M, int64_t N, unsigned main_fits, int64_t *cost_out = 
     return best;
 }
 
+// K slices on the direct-to-LDS shapes, for calls that bring a workspace: the shape and slice count with the least modelled
+// time.  With w = ceil(tiles x slices / 256) workgroups to a compute unit one after (or beside) the other, each over a
+// slice of L k, a launch takes w L t: t the shape's tile time, or, for the 64-wide shapes with a unit to themselves, the
+// time of a workgroup running alone (161 / 301 / 324); plus 1 us per workgroup in a unit's queue for what surrounds its K
+// loop, and for slices the second launch (4 us) and its traffic (slices + 1 results at 3 TB/s); a slice keeps 256 k or more.  Measured against the
+// plans this replaced (64 x 64 and 128 x 128 tiles of the general kernel in up to 64 slices): 256^2 x 16384 39 -> 26 us,
+// 512^2 x 4096 28 -> 23, 768^2 x 2048 41 -> 28, 1024^2 x 2048 42 -> 34 (unsplit), 128 x 2048 x 4096 29 -> 23.
+// A split is taken for a modelled gain of 5 % over the best unsplit shape.  Units of 0.1 ns.
+struct MainSplit {
+    int shape = -1, slices = 1;
+    int64_t cost = 0;
+};
+MainSplit best_main_split(int64_t M, int64_t N, int64_t K, unsigned main_fits)
+{
+    constexpr int64_t kAlone[kF32MainShapes] = {2230, 1710, 1120, 1120, 838, 566, 1715, 1286, 845, 161, 301, 324};
+    MainSplit best, unsplit;
+    for (int sh = 0; sh < kF32MainShapes; ++sh) {
+        if (!(main_fits >> sh & 1)) continue;
+        const int64_t tiles = ceil_div(M, f32_main_tile_m(sh)) * ceil_div(N, f32_main_tile_n(sh));
+        for (int sl = 1; sl <= kMaxSlices; ++sl) {
+            if (sl > 1 && (int64_t)sl * M * N * 4 > kMaxWorkspace) break;
+            if (!f32_main_slices_fit(K, sl)) continue;       // the last slice would be left without a whole K-tile
+            const int64_t w = ceil_div(tiles * sl, 256), len = ceil_div(ceil_div(K, 32), sl) * 32;
+            int64_t cost = w * len * (w == 1 ? kAlone[sh] : kMainTileTime[sh]) + w * 10000;
+            if (sl > 1 && len < 256) continue;                // a slice keeps at least eight K-tiles
+            if (sl > 1) cost += 40000 + (sl + 1) * M * N * 4 / 300;
+            if (sl == 1 && (unsplit.shape < 0 || cost < unsplit.cost)) unsplit.shape = sh, unsplit.cost = cost;
+            if (best.shape < 0 || cost < best.cost) best.shape = sh, best.slices = sl, best.cost = cost;
+        }
+    }
+    return best.slices > 1 && best.cost * 100 > unsplit.cost * 95 ? unsplit : best;
+}
+
 // Two bands.  Where no tile shape fills whole rounds of the compute units, two launches often do: C is cut once, along
 // its rows or its columns, and each band takes the shape that suits its own tile count (fp32 5120^2: 729 tiles of
 // 192 x 192 are 2.85 rounds; rows 0 .. 1023 as 1280 tiles of 64 x 64 and the rest as 1280 tiles of 128 x 128 are five whole
@@ -305,7 +338,17 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
         unsigned main_fits = 0;
         for (int sh = 0; sh < kF32MainShapes; ++sh)
             main_fits |= (unsigned)f32_main_fits(sh, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, A, lda, B, ldb) << sh;
-        if (t && t->tile >= kF32_Main && (!(main_fits >> (t->tile - kF32_Main) & 1) || t->slices > 1)) t = nullptr;    // a row for operands aligned otherwise
+        if (t && t->tile >= kF32_Main && (!(main_fits >> (t->tile - kF32_Main) & 1) || !f32_main_slices_fit(K, t->slices))) t = nullptr;    // a row for operands aligned otherwise
+        if (!t && split && main_fits) {
+            // the direct-to-LDS shapes in K slices where that pays; otherwise the call is planned as one without a workspace
+            const MainSplit ms = best_main_split(M, N, K, main_fits);
+            p->slices = ms.slices;
+            if (ms.slices > 1) {
+                p->cfg = kF32_Main + ms.shape;
+                return mode_f32(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
+            }
+            if (use_table) t = find_tuned(0, transA, transB, M, N, K, false);
+        }
         // a split runs on 64 x 64 tiles, or on 128 x 128 ones where those still give every compute unit a workgroup
         // and a slice keeps at least 1024 k (10-17 % faster there, measured on 256^2 ... 1024^2 with K up to 65536)
         // (not for a sliver under 128 rows or columns, part of whose 128-wide tile would be padding: 8 x 8192 x 8192 runs 57 %
@@ -538,9 +581,15 @@ int run_f32(const Plan &p, int transA, int transB, int64_t M, int64_t N, int64_t
     const bool split = p.slices > 1;
     hipError_t e;
     if (p.cfg >= kF32_Main) {
-        if (split) return FSRGEMM_ERR_INVALID_ARG;      // the planners never pair the two
         const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
-        if (p.band_dim == 0) {
+        if (split) {        // partial products of the K slices into the workspace, then their sum in slice order
+            if (p.band_dim != 0) return FSRGEMM_ERR_INVALID_ARG;        // the planners never pair the two
+            GemmArgs a = pack(M, N, K, A, lda, B, ldb, ws, N);
+            a.k_slices = p.slices;
+            a.slice_stride = M * N;
+            e = launch_f32_main(p.cfg - kF32_Main, a_lay, b_lay, a, s);
+            if (e == hipSuccess) e = launch_splitk_reduce(ws, p.slices, M * N, C, (int)M, (int)N, ldc, s);
+        } else if (p.band_dim == 0) {
             e = launch_f32_main(p.cfg - kF32_Main, a_lay, b_lay, pack(M, N, K, A, lda, B, ldb, C, ldc), s);
         } else {
             const int64_t m1 = p.band_dim == 1 ? p.band_at : M, n1 = p.band_dim == 2 ? p.band_at : N;
@@ -695,9 +744,16 @@ int gemm_f32_noalloc(int transA, int transB, int64_t M, int64_t N, int64_t K, co
 int64_t gemm_f32_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K)
 {
     if (!extents_ok(M, N, K)) return 0;
-    Plan p;
-    if (plan_f32(transA, transB, M, N, K, nullptr, 4, nullptr, 4, true, &p) != FSRGEMM_OK) return 0;
-    return p.slices > 1 || p.cfg == kF32_Skinny ? (int64_t)p.slices * M * N * 4 : 0;
+    // The slices depend on whether the operands' alignment lets the direct-to-LDS kernel run, which the query cannot
+    // know: the larger of the two plans' workspaces serves either.
+    int64_t bytes = 0;
+    for (const float *fake : {static_cast<const float *>(nullptr), reinterpret_cast<const float *>(uintptr_t{4})}) {
+        Plan p;
+        if (plan_f32(transA, transB, M, N, K, fake, 4, fake, 4, true, &p) != FSRGEMM_OK) continue;
+        const int64_t need = p.slices > 1 || p.cfg == kF32_Skinny ? (int64_t)p.slices * M * N * 4 : 0;
+        if (need > bytes) bytes = need;
+    }
+    return bytes;
 }
 
 int gemm_f32_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
@@ -730,10 +786,11 @@ int gemm_f32_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int6
             return FSRGEMM_ERR_INVALID_ARG;
         probe.K = (int)K, probe.parts = k_slices;
         if (!skinny_offsets_fit(probe)) return FSRGEMM_ERR_INVALID_ARG;
-    } else if (tile >= kF32_Main && tile < kF32_Main + kF32MainShapes) {     // unsplit, and only problems it fits
-        if (k_slices != 1 || workspace_bytes < 0 || (workspace_bytes > 0 && workspace == nullptr)) return FSRGEMM_ERR_INVALID_ARG;
+    } else if (tile >= kF32_Main && tile < kF32_Main + kF32MainShapes) {     // only problems it fits; slices of whole K-tiles
+        if (!forced_ok(tile, kF32_Main + kF32MainShapes, k_slices, M, N, K, 32, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
         if (M == 0 || N == 0) return FSRGEMM_OK;
-        if (!f32_main_fits(tile - kF32_Main, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, A, lda, B, ldb))
+        if (!f32_main_fits(tile - kF32_Main, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, A, lda, B, ldb) ||
+            !f32_main_slices_fit(K, k_slices))
             return FSRGEMM_ERR_INVALID_ARG;
     } else {
         if (!forced_ok(tile, kF32_Vector + 1, k_slices, M, N, K, 16, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;

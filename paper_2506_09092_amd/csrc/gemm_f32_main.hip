@@ -62,6 +62,9 @@ namespace {
 
 constexpr int kBK = 32, kThreads = 256;
 
+// k per slice when K is cut into `slices`: a whole number of K-tiles, the last slice takes what is left
+__host__ __device__ constexpr int main_slice_length(int K, int slices) { return ((K + kBK - 1) / kBK + slices - 1) / slices * kBK; }
+
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
 #define LDS_PTR __attribute__((address_space(3)))
 #define GLOBAL_PTR __attribute__((address_space(1)))
@@ -81,8 +84,22 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_f32_main_kernel(GemmArgs g, 
     constexpr int kLoadsA = 2 * WM, kLoadsB = 2 * WN, kLoads = kLoadsA + kLoadsB;     // 1 KB each, per wavefront and K-tile
     constexpr int kMfmas = 4 * WM * WN;                                               // per chunk of 8 k
     extern __shared__ __attribute__((aligned(1024))) char lds[];
+    // K slices (a call with a workspace): workgroup ids beyond the first tiles_m * tiles_n belong to further slices.
+    // Slice s is the product over k in [s per, s per + its length) with per a whole number of K-tiles, written to the
+    // s-th M x N block behind g.C (the workspace, tightly packed: the launcher sets ldc = N): for the rest of the kernel
+    // it is simply a product of its own, on operands shifted along k.
+    int pid = blockIdx.x;
+    if (g.k_slices > 1) {
+        const int tiles = tiles_m * tiles_n, slice = pid / tiles;
+        pid -= slice * tiles;
+        const int per = main_slice_length(g.K, g.k_slices), k0 = slice * per;
+        g.A = static_cast<const float *>(g.A) + (ALAY == kKContig ? (int64_t)k0 : (int64_t)k0 * g.lda);
+        g.B = static_cast<const float *>(g.B) + (BLAY == kKContig ? (int64_t)k0 : (int64_t)k0 * g.ldb);
+        g.K = min(per, g.K - k0);
+        g.C += (int64_t)slice * g.slice_stride;
+    }
     int tile_m, tile_n;
-    tile_coords(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    tile_coords(pid, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_origin(tile_m, BM, g.M), n0 = tile_origin(tile_n, BN, g.N);
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm0 = (wave >> 1) * 32 * WM, wn0 = (wave & 1) * 32 * WN;
@@ -335,7 +352,7 @@ hipError_t launch_main(const GemmArgs &a, hipStream_t s)
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kLdsBytes, configured);
     if (e != hipSuccess) return e;
     const int tiles_m = (a.M + 64 * WM - 1) / (64 * WM), tiles_n = (a.N + 64 * WN - 1) / (64 * WN);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLdsBytes, s, a, tiles_m, tiles_n);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n * a.k_slices)), dim3(kThreads), kLdsBytes, s, a, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
@@ -387,10 +404,17 @@ bool f32_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_
            (b_lay == kKContig || N % 4 == 0) && ((M + bm - 1) / bm) * ((N + bn - 1) / bn) < ((int64_t)1 << 31);
 }
 
-// requires f32_main_fits(...) and a.k_slices == 1
+// K may be cut into `slices` whole numbers of K-tiles if the last slice still has a whole K-tile
+bool f32_main_slices_fit(int64_t K, int slices)
+{
+    return slices >= 1 && K < ((int64_t)1 << 31) && (int64_t)(slices - 1) * main_slice_length((int)K, slices) + kBK <= K;
+}
+
+// requires f32_main_fits(...) and f32_main_slices_fit(a.K, a.k_slices); with slices, a.C is the workspace and a.ldc = a.N
 hipError_t launch_f32_main(int shape, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
-    if (!f32_main_fits(shape, a_lay, b_lay, a.M, a.N, a.K, a.A, a.lda, a.B, a.ldb) || a.k_slices != 1) return hipErrorInvalidValue;
+    if (!f32_main_fits(shape, a_lay, b_lay, a.M, a.N, a.K, a.A, a.lda, a.B, a.ldb) || !f32_main_slices_fit(a.K, a.k_slices)) return hipErrorInvalidValue;
+    if (((a.M + kShapeM[shape] - 1) / kShapeM[shape]) * (int64_t)((a.N + kShapeN[shape] - 1) / kShapeN[shape]) * a.k_slices >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     switch (shape) {
     case 0: return launch_shape<4, 4>(a_lay, b_lay, a, s);
     case 1: return launch_shape<3, 4>(a_lay, b_lay, a, s);

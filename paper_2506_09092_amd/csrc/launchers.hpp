@@ -112,6 +112,7 @@ int f32_main_tile_m(int shape);
 int f32_main_tile_n(int shape);
 bool f32_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb);
 const char *f32_main_kernel_name(int shape, int a_lay, int b_lay);
+bool f32_main_slices_fit(int64_t K, int slices);       // K slices of whole K-tiles, the last with at least one
 hipError_t launch_f32_main(int shape, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 
 // register-only MFMA loops (mfma_ceiling.hip): kind 0 = the fp32 kernels' instruction, 1 = the bf16 kernels'

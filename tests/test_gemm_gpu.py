@@ -191,19 +191,21 @@ def test_f32_workspace_split_k(gpu, shape):
 
 @pytest.mark.parametrize("shape", [(512, 512, 16384), (256, 1024, 16384), (384, 388, 28672)])
 def test_splits_on_the_larger_tile(gpu, shape):
-    # long-K splits that still fill the compute units with 128 x 128 tiles take those (fp32 candidate 1, bf16 candidate 2):
+    # long-K splits that still fill the compute units with 128 x 128 tiles take those -- fp32: the direct-to-LDS kernel's
+    # (candidate 10), or the general kernel's (candidate 1) for operands that are only 4-byte aligned; bf16: candidate 2 --
     # sampled entries against the oracle, and the dispatcher's bits are the forced candidate's
     M, N, K = shape
     rng = np.random.default_rng(23)
     ii, jj = rng.integers(0, M, 4096), rng.integers(0, N, 4096)
-    say("split on 128 x 128 tiles, fp32 %dx%dx%d" % shape)
-    tile, slices = gpu.fsrgemm_plan_f32(0, 0, M, N, K, 0x1000, K, 0x1000, N, True)
-    assert tile == 1 and slices > 1
     A, B = inputs.uniform_pm1(23, 1, M, K), inputs.uniform_pm1(23, 2, K, N)
-    got = run_f32_ws(gpu, 0, 0, A, B, repeat=2)
     ref, S = oracle.gemm_entries(A, B, ii, jj)
-    assert np.all(np.isfinite(got)) and oracle.componentwise_error(got[ii, jj], ref, S) <= TOL_F32
-    assert np.array_equal(run_cfg(gpu, "f32", tile, slices, 0, 0, A, B).view(np.uint32), got.view(np.uint32))
+    for offset, want in ((0, 10 if N % 128 == 0 else 14), (1, 1)):       # (a ragged 388 columns: 64 x 64 tiles waste less)
+        say("split on 128 x 128 tiles, fp32 %dx%dx%d, operands offset by %d" % (shape + (offset,)))
+        tile, slices = gpu.fsrgemm_plan_f32(0, 0, M, N, K, 0x1000 + 4 * offset, K, 0x1000 + 4 * offset, N, True)
+        assert tile == want and slices > 1
+        got = run_f32_ws(gpu, 0, 0, A, B, offset=offset, repeat=2)
+        assert np.all(np.isfinite(got)) and oracle.componentwise_error(got[ii, jj], ref, S) <= TOL_F32
+        assert np.array_equal(run_cfg(gpu, "f32", tile, slices, 0, 0, A, B, offset=offset).view(np.uint32), got.view(np.uint32))
     say("split on 128 x 128 tiles, bf16 %dx%dx%d" % shape)
     tile, slices = gpu.fsrgemm_plan_bf16(0, 1, M, N, K, 0x1000, K, 0x1000, K, True)
     assert tile == 2 and slices > 1
@@ -403,7 +405,7 @@ MAIN_SHAPES = {5: (256, 256), 6: (192, 256), 7: (128, 256), 8: (256, 128), 9: (1
                                    (64, 64, 32), (68, 132, 72), (196, 64, 164)])                        # the tiles with a side of 64 only
 def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
     # the direct-to-LDS fp32 kernel in its twelve tile shapes, forced: prologue, odd / even tails, the clamped loads two
-    # K-tiles ahead, operands contiguous along k and along m / n, padded leading dimensions, small integers
+    # K-tiles ahead, operands contiguous along k and along m / n, padded leading dimensions, small integers, K slices
     M, N, K = shape
     lda, ldb = (M if ta else K), (K if tb else N)
     A, B = inputs.uniform_pm1(19, 1, M, K), inputs.uniform_pm1(19, 2, K, N)
@@ -425,10 +427,21 @@ def test_f32_main_kernel_storage_orders(gpu, shape, ta, tb):
         got = run_cfg(gpu, "f32", tile, 1, ta, tb, A, B, lda=lda + 4, ldb=ldb + 36, ldc=N + 3, repeat=2)
         assert oracle.componentwise_error(got, ref, S) <= TOL_F32
         assert np.array_equal(run_cfg(gpu, "f32", tile, 1, ta, tb, Ai, Bi).astype(np.float64), refi)
-        # where the candidate does not fit it is rejected: a split, a misaligned base, rows that are not whole pieces
-        for kw, slices in ((dict(), 2), (dict(offset=1), 1), (dict(lda=lda + 2), 1)):
+        # K slices of whole K-tiles (the last one takes the rest of K): partial products in the workspace, summed in slice
+        # order; a count that would leave the last slice without a whole K-tile is rejected
+        for slices in (2, 3):
+            per = -(-(-(-K // 32)) // slices) * 32
+            if (slices - 1) * per + 32 <= K:
+                got = run_cfg(gpu, "f32", tile, slices, ta, tb, A, B, lda=lda + 4, ldb=ldb + 36, ldc=N + 3, repeat=2)
+                assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+                assert np.array_equal(run_cfg(gpu, "f32", tile, slices, ta, tb, Ai, Bi).astype(np.float64), refi)
+            else:
+                with pytest.raises(gpu.FsrGemmError):
+                    run_cfg(gpu, "f32", tile, slices, ta, tb, A, B)
+        # where the candidate does not fit it is rejected: a misaligned base, rows that are not whole pieces
+        for kw in (dict(offset=1), dict(lda=lda + 2)):
             with pytest.raises(gpu.FsrGemmError):
-                run_cfg(gpu, "f32", tile, slices, ta, tb, A, B, **kw)
+                run_cfg(gpu, "f32", tile, 1, ta, tb, A, B, **kw)
 
 
 def test_f32_main_kernel_is_the_dispatchers_choice(gpu):
