@@ -444,7 +444,10 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
         p->mode = 0;
         return ceil_div(M > N ? M : N, 4) * p->slices >= ((int64_t)1 << 31) ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_OK;
     }
-    p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 64) : 1;
+    // (bf16 tiles get through a short K quickly enough that a second launch costs more than the split gains: measured on
+    // 256^2 ... 1024^2, splits lose 5-80 % with K up to 2560 and win from 3072 on -- 768^2 x 3072 24 -> 15 us, 512^2 x 8192 60 -> 18;
+    // a sliver under 64 rows or columns runs on checked loads and gains at any K the rule cuts: 16 x 8192 x 2048 23 -> 12 us)
+    p->slices = t ? t->slices : split && (K >= 3072 || M < 64 || N < 64) ? splitk_slices(M, N, K, 64) : 1;
     if (!t && p->slices == 1 && use_table) t = find_tuned(1, transA, transB, M, N, K, false);
     unsigned main_fits = 0;
     for (int sh = 0; sh < kBf16MainShapes; ++sh) main_fits |= (unsigned)bf16_main_fits(sh, a_lay, b_lay, M, N, K, A, lda, B, ldb) << sh;

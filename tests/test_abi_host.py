@@ -304,7 +304,9 @@ def test_forced_configurations_and_plan_queries():
     assert pb(0, 1, 8192, 8192, 8200, P, 8200, P, 8200) == (0, 1)              # a rest of K in whole 16-byte pieces: still the direct-to-LDS kernel
     assert pb(0, 1, 8192, 8192, 8196, P, 8200, P, 8200) == (1, 1)              # otherwise the general kernel of that tile
     assert pb(0, 1, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1) and pb(0, 0, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1)   # 256 x 192, in every storage order
-    assert pb(0, 1, 512, 512, 512, P, 512, P, 512, True, True) == (3, 2) and pb(0, 1, 512, 512, 512, P, 512, P, 512, True) == (10, 1)   # the rules; a row of the selection table
+    # the rules (two bands); a row of the selection table (one launch of 64 x 64 tiles)
+    assert lib.fsrgemm_bands_f32(0, 0, 2560, 2560, 2560, P, 2560, P, 2560, False, True)[0] == 1 and lib.fsrgemm_bands_f32(0, 0, 2560, 2560, 2560, P, 2560, P, 2560)[0] == 0
+    assert pb(0, 1, 512, 512, 512, P, 512, P, 512, True) == (3, 1) and pb(0, 1, 512, 512, 4096, P, 4096, P, 4096, True) == (2, 16)       # bf16 splits from K = 3072 on
     # between 64 and 127 tiles of 256 x 256: a larger shape in one round, or 128 x 128 tiles, by the modelled times
     assert pb(0, 1, 2560, 2560, 2560, P, 2560, P, 2560) == (6, 1) and pb(1, 0, 2048, 2560, 8192, P, 2048, P, 2560) == (6, 1)
     assert pb(0, 1, 2048, 2048, 2048, P, 2048, P, 2048) == (10, 1) and pb(0, 1, 2048, 2048, 512, P, 512, P, 512) == (10, 1)

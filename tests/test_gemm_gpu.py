@@ -228,7 +228,7 @@ def test_f32_workspace_integers_bit_exact_and_large_problem_unsplit(gpu):
     assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=4096).view(np.uint32), run_f32(gpu, A, B).view(np.uint32))
 
 
-@pytest.mark.parametrize("shape", [(1, 4096, 4096), (4096, 1, 4096), (8, 1000, 3000), (64, 64, 4100), (130, 70, 2050),
+@pytest.mark.parametrize("shape", [(1, 4096, 4096), (4096, 1, 4096), (8, 1000, 3000), (64, 64, 4100), (130, 70, 3082),
                                    (16, 8192, 2048), (256, 256, 8192)])
 def test_bf16_workspace_split_k(gpu, shape):
     M, N, K = shape
