@@ -205,10 +205,11 @@ int gemm_bf16_ws(int transA, int transB,
  * multiple of 4, 16-byte aligned operands with leading dimensions that are multiples of 4 and below 2^24;
  * M or N a multiple of 4 for an operand contiguous along it) or with a slice count that does not leave every
  * slice a whole K-tile (slices are ceil(ceil(K / 32) / k_slices) K-tiles of 32 long, the last one takes the rest),
- * bf16 tiles 0 and 5..10 with a split or where their kernel's
+ * bf16 tiles 0 and 5..10 where their kernel's
  * conditions fail (M, N at least one tile, K >= 64 and a multiple of 8, 16-byte aligned operands with leading
  * dimensions that are multiples of 8 and below 2^25; with an operand contiguous along m or n, M or N a multiple
- * of 8).  Every other
+ * of 8) or with a slice count that does not leave every slice a whole K-tile (slices are
+ * ceil(ceil(K / 64) / k_slices) K-tiles of 64 long, the last one takes the rest).  Every other
  * candidate takes any shape and alignment.  All other arguments as for gemm_f32_ws / gemm_bf16_ws.
  */
 int gemm_f32_cfg(int tile, int k_slices, int transA, int transB,

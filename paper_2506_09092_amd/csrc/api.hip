@@ -420,6 +420,48 @@ int tile_rule_bf16_main(int64_t M, int64_t N, int64_t K, unsigned fits, int64_t 
     return best;
 }
 
+// K slices for bf16 problems of 64 rows and columns and more that bring a workspace: the general kernel's 64 x 64 tile or,
+// where it fits, the direct-to-LDS kernel's 128 x 128 tile, in the slice count with the least modelled time.  Per K-tile of
+// 64 and workgroup: 64 x 64 248 ns alone on a compute unit, 208 ns each with several (half as much again when an operand
+// is contiguous along m / n, which that kernel regroups in registers); 128 x 128 450 ns alone, 780 ns for two; around the K
+// loop 3.4 / 4.7 us; for slices the second launch (4 us + 0.15 us per slice) and its traffic (slices + 1 results at 3 TB/s); a slice keeps 512 k
+// or more.  Measured against the rule this replaced (about 1024 workgroups): 256^2 x 16384 26 -> 17 us, 256^2 x 8192
+// 17 -> 11, 128 x 2048 x 4096 15 -> 9, 1536 x 1024 x 8192 55 -> 46.  Costs in ns.
+struct Bf16Split {
+    int cfg = kBf16_64x64, slices = 1;
+    int64_t cost = 0;
+};
+Bf16Split best_bf16_split(int64_t M, int64_t N, int64_t K, bool main128_fits, bool k_contiguous)
+{
+    Bf16Split best, unsplit;
+    bool have = false, have_unsplit = false;
+    const int64_t nk = ceil_div(K, 64), t64 = ceil_div(M, 64) * ceil_div(N, 64), t128 = ceil_div(M, 128) * ceil_div(N, 128);
+    for (int kind = 0; kind < (main128_fits ? 2 : 1); ++kind) {
+        for (int sl = 1; sl <= kMaxSlices; ++sl) {
+            if (sl > 1 && (int64_t)sl * M * N * 4 > kMaxWorkspace) break;
+            const int64_t len = ceil_div(nk, sl);               // K-tiles per slice
+            if (sl > 1 && (len < 8 || (sl - 1) * len >= nk || (kind == 1 && !bf16_main_slices_fit(K, sl)))) continue;
+            int64_t cost;
+            if (kind == 0) {
+                // (its workgroups drift apart along K, and once the operand panels of a slice outgrow 8.75 MB they no longer
+                // meet in the L2: 1024^2 x 2048, 8.4 MB, runs 0.23 us per K-tile, 768^2 x 3072, 9.0 MB, 0.43)
+                // (slices that run side by side help only in part: 7 / 5 when the whole problem's panels outgrow that size)
+                const int64_t limit = (int64_t)35 << 18, w = ceil_div(t64 * sl, 256);
+                const int64_t slow = (M + N) * len * 128 > limit ? 9 : (M + N) * nk * 128 > limit ? 7 : 5;
+                cost = w * len * (w == 1 ? 248 : 208) * (k_contiguous ? 2 : 3) / 2 * slow / 5 + 3400;
+            } else {
+                const int64_t groups = t128 * sl, rest = groups % 512;
+                cost = (groups / 512 + (rest > 256)) * len * 780 + (rest > 0 && rest <= 256) * len * 450 + 4700;
+            }
+            if (sl > 1) cost += 4000 + sl * 150 + (sl + 1) * M * N * 4 / 3000;
+            const int cfg = kind == 0 ? (int)kBf16_64x64 : bf16_main_candidate(kBf16MainLarge);
+            if (sl == 1 && (!have_unsplit || cost < unsplit.cost)) unsplit.cfg = cfg, unsplit.slices = 1, unsplit.cost = cost, have_unsplit = true;
+            if (!have || cost < best.cost) best.cfg = cfg, best.slices = sl, best.cost = cost, have = true;
+        }
+    }
+    return best.slices > 1 && best.cost * 100 > unsplit.cost * 95 ? unsplit : best;
+}
+
 int mode_bf16(int cfg, int slices, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B,
               int64_t ldb, int *mode)
 {
@@ -444,14 +486,25 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
         p->mode = 0;
         return ceil_div(M > N ? M : N, 4) * p->slices >= ((int64_t)1 << 31) ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_OK;
     }
-    // (bf16 tiles get through a short K quickly enough that a second launch costs more than the split gains: measured on
-    // 256^2 ... 1024^2, splits lose 5-80 % with K up to 2560 and win from 3072 on -- 768^2 x 3072 24 -> 15 us, 512^2 x 8192 60 -> 18;
-    // a sliver under 64 rows or columns runs on checked loads and gains at any K the rule cuts: 16 x 8192 x 2048 23 -> 12 us)
-    p->slices = t ? t->slices : split && (K >= 3072 || M < 64 || N < 64) ? splitk_slices(M, N, K, 64) : 1;
-    if (!t && p->slices == 1 && use_table) t = find_tuned(1, transA, transB, M, N, K, false);
     unsigned main_fits = 0;
     for (int sh = 0; sh < kBf16MainShapes; ++sh) main_fits |= (unsigned)bf16_main_fits(sh, a_lay, b_lay, M, N, K, A, lda, B, ldb) << sh;
-    if (t && bf16_main_shape(t->tile) >= 0 && (!(main_fits >> bf16_main_shape(t->tile) & 1) || t->slices > 1)) t = nullptr;  // a row for operands aligned otherwise
+    // (Under 128 rows or columns the earlier rule stays: about 1024 workgroups of the general kernel.  Its tiles get through
+    // a short K quickly enough that a second launch costs more than the split gains -- on 256^2 ... 1024^2 splits lost 5-80 %
+    // with K up to 2560 -- except for a sliver under 64 rows or columns, which runs on checked loads and gains at any K the
+    // rule cuts: 16 x 8192 x 2048 23 -> 12 us.)
+    const bool narrow = M < 128 || N < 128;
+    p->slices = t ? t->slices : split && narrow && (K >= 3072 || M < 64 || N < 64) ? splitk_slices(M, N, K, 64) : 1;
+    if (!t && split && !narrow && ceil_div(M, 256) * ceil_div(N, 256) < 128) {
+        // the modelled best of 64 x 64 general tiles and 128 x 128 direct-to-LDS tiles in slices; an unsplit winner leaves
+        // the call to the rules for calls without a workspace
+        const Bf16Split bs = best_bf16_split(M, N, K, (main_fits >> kBf16MainLarge & 1) != 0, a_lay == kKContig && b_lay == kKContig);
+        if (bs.slices > 1) {
+            p->cfg = bs.cfg, p->slices = bs.slices;
+            return mode_bf16(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
+        }
+    }
+    if (!t && p->slices == 1 && use_table) t = find_tuned(1, transA, transB, M, N, K, false);
+    if (t && bf16_main_shape(t->tile) >= 0 && (!(main_fits >> bf16_main_shape(t->tile) & 1) || !bf16_main_slices_fit(K, t->slices))) t = nullptr;  // a row for operands aligned otherwise
     if (t) p->cfg = t->tile;
     // a split runs on 128 x 128 tiles where those still give every compute unit a workgroup (up to 30 % faster than
     // 64 x 64 ones there, measured on 256^2 ... 1024^2 with K up to 65536), else on 64 x 64 tiles
@@ -489,7 +542,10 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     // (with an operand contiguous along m / n the general kernel stages through registers and is slower: there the
     // 128 x 128 tile wins from 4 tiles on -- level at 256^3 and 512^3, 768^3 83-105 -> 107-112, 1024^3 156-198 -> 212-222,
     // 1536^3 194-290 -> 392-405, 256^2 x 65536 0.69-0.87 -> 0.59-0.60 ms)
-    else if ((main_fits >> kBf16MainLarge & 1) && ceil_div(M, 128) * ceil_div(N, 128) >= (a_lay == kKContig && b_lay == kKContig ? 192 : 4)) {
+    // (from 128 tiles on when K is 2048 or longer and the problem has 512 rows and columns: 1536^2 x 8192 80 -> 71 us, x 16384
+    // 159 -> 147, level at K = 1536)
+    else if ((main_fits >> kBf16MainLarge & 1) &&
+             ceil_div(M, 128) * ceil_div(N, 128) >= (a_lay == kKContig && b_lay == kKContig ? (K >= 2048 && M >= 512 && N >= 512 ? 128 : 192) : 4)) {
         p->cfg = bf16_main_candidate(kBf16MainLarge);
         // between 64 and 127 tiles of 256 x 256 a larger shape in one round can beat two 128 x 128 tiles to a compute unit
         // (2048 x 2560 x 8192 852 -> 956 TFLOP/s on 128 x 256, 1792 x 4096 x 4096 1022 -> 1063): by the modelled times, where
@@ -622,12 +678,18 @@ int run_bf16(const Plan &p, int a_lay, int b_lay, int64_t M, int64_t N, int64_t 
              const uint16_t *B, int64_t ldb, float *C, int64_t ldc, float *ws, hipStream_t s)
 {
     const bool split = p.slices > 1;
-    if (split && bf16_main_shape(p.cfg) >= 0) return FSRGEMM_ERR_INVALID_ARG;     // the planners never pair the two
     const int rc = device_ok();
     if (rc != FSRGEMM_OK) return rc;
     hipError_t e;
     if (bf16_main_shape(p.cfg) >= 0) {
-        if (p.band_dim == 0) {
+        if (split) {        // partial products of the K slices into the workspace, then their sum in slice order
+            if (p.band_dim != 0) return FSRGEMM_ERR_INVALID_ARG;        // the planners never pair the two
+            GemmArgs a = pack(M, N, K, A, lda, B, ldb, ws, N);
+            a.k_slices = p.slices;
+            a.slice_stride = M * N;
+            e = launch_bf16_main(bf16_main_shape(p.cfg), a_lay, b_lay, a, s);
+            if (e == hipSuccess) e = launch_splitk_reduce(ws, p.slices, M * N, C, (int)M, (int)N, ldc, s);
+        } else if (p.band_dim == 0) {
             e = launch_bf16_main(bf16_main_shape(p.cfg), a_lay, b_lay, pack(M, N, K, A, lda, B, ldb, C, ldc), s);
         } else {
             const int64_t m1 = p.band_dim == 1 ? p.band_at : M, n1 = p.band_dim == 2 ? p.band_at : N;
@@ -847,9 +909,15 @@ int gemm_bf16_ex(int transA, int transB, int64_t M, int64_t N, int64_t K, const 
 int64_t gemm_bf16_workspace_bytes(int transA, int transB, int64_t M, int64_t N, int64_t K)
 {
     if (!extents_ok(M, N, K)) return 0;
-    Plan p;
-    if (plan_bf16(transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, nullptr, 8, nullptr, 8, true, &p) != FSRGEMM_OK) return 0;
-    return p.slices > 1 ? (int64_t)p.slices * M * N * 4 : 0;
+    // as for fp32: the larger of the plans for operands the direct-to-LDS kernel can and cannot take
+    int64_t bytes = 0;
+    for (const uint16_t *fake : {static_cast<const uint16_t *>(nullptr), reinterpret_cast<const uint16_t *>(uintptr_t{2})}) {
+        Plan p;
+        if (plan_bf16(transA ? kMnContig : kKContig, transB ? kKContig : kMnContig, M, N, K, fake, 8, fake, 8, true, &p) != FSRGEMM_OK) continue;
+        const int64_t need = p.slices > 1 ? (int64_t)p.slices * M * N * 4 : 0;
+        if (need > bytes) bytes = need;
+    }
+    return bytes;
 }
 
 int gemm_bf16_ws(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda,
@@ -888,7 +956,7 @@ int gemm_bf16_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int
     if (rc != FSRGEMM_OK) return rc;
     // a forced direct-to-LDS kernel is an invalid candidate where it does not fit; nothing else is substituted
     if (bf16_main_shape(tile) >= 0 && M > 0 && N > 0 &&
-        (k_slices > 1 || !bf16_main_fits(bf16_main_shape(tile), a_lay, b_lay, M, N, K, A, lda, B, ldb)))
+        (!bf16_main_fits(bf16_main_shape(tile), a_lay, b_lay, M, N, K, A, lda, B, ldb) || !bf16_main_slices_fit(K, k_slices)))
         return FSRGEMM_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return FSRGEMM_OK;
     return run_bf16(p, a_lay, b_lay, M, N, K, A, lda, B, ldb, C, ldc, static_cast<float *>(workspace),

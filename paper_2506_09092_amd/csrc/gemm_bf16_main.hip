@@ -114,6 +114,9 @@ namespace {
 #pragma clang diagnostic ignored "-Winline-asm"
 
 constexpr int kBK = 64;
+
+// k per slice when K is cut into `slices`: a whole number of K-tiles, the last slice takes what is left
+__host__ __device__ constexpr int bf16_main_slice_length(int K, int slices) { return ((K + kBK - 1) / kBK + slices - 1) / slices * kBK; }
 constexpr int kScratchBytes = 1024;             // landing zone of the prefetch touches (256 B per wavefront)
 constexpr int kThreads = 256;
 constexpr int kLate = 4;         // loads of K-tile t+1 issued in k-step 0 of K-tile t; the others earlier, in k-step 1 of t-1
@@ -251,8 +254,22 @@ __global__ __launch_bounds__(kThreads) void gemm_bf16_main_kernel(GemmArgs g, in
     constexpr int kTouchAhead = kMfmas == 64 ? 3 : 4;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
+    // K slices (a call with a workspace): workgroup ids beyond the first tiles_m * tiles_n belong to further slices.
+    // Slice s is the product over k in [s per, s per + its length) with per a whole number of K-tiles, written to the
+    // s-th M x N block behind g.C (the workspace, tightly packed: the launcher sets ldc = N): for the rest of the kernel
+    // it is simply a product of its own, on operands shifted along k.
+    int pid = blockIdx.x;
+    if (g.k_slices > 1) {
+        const int tiles = tiles_m * tiles_n, slice = pid / tiles;
+        pid -= slice * tiles;
+        const int per = bf16_main_slice_length(g.K, g.k_slices), k0 = slice * per;
+        g.A = static_cast<const uint16_t *>(g.A) + (AMC ? (int64_t)k0 * g.lda : (int64_t)k0);
+        g.B = static_cast<const uint16_t *>(g.B) + (BMC ? (int64_t)k0 * g.ldb : (int64_t)k0);
+        g.K = min(per, g.K - k0);
+        g.C += (int64_t)slice * g.slice_stride;
+    }
     int tile_m, tile_n;
-    tile_coords(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    tile_coords(pid, tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_origin(tile_m, kBM, g.M), n0 = tile_origin(tile_n, kBN, g.N);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -619,7 +636,7 @@ hipError_t launch_main(const GemmArgs &a, hipStream_t s)
     const hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), kLdsBytes, configured);
     if (e != hipSuccess) return e;
     const int tiles_m = (a.M + 32 * IM - 1) / (32 * IM), tiles_n = (a.N + 32 * JN - 1) / (32 * JN);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), kLdsBytes, s, a, tiles_m, tiles_n);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n * a.k_slices)), dim3(kThreads), kLdsBytes, s, a, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
@@ -635,10 +652,17 @@ hipError_t launch_shape(int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 
 }  // namespace
 
-// requires bf16_main_fits(...) and a.k_slices == 1
+// K may be cut into `slices` whole numbers of K-tiles if the last slice still has a whole K-tile
+bool bf16_main_slices_fit(int64_t K, int slices)
+{
+    return slices >= 1 && K < ((int64_t)1 << 31) && (int64_t)(slices - 1) * bf16_main_slice_length((int)K, slices) + kBK <= K;
+}
+
+// requires bf16_main_fits(...) and bf16_main_slices_fit(a.K, a.k_slices); with slices, a.C is the workspace and a.ldc = a.N
 hipError_t launch_bf16_main(int shape, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s)
 {
-    if (!bf16_main_fits(shape, a_lay, b_lay, a.M, a.N, a.K, a.A, a.lda, a.B, a.ldb) || a.k_slices != 1) return hipErrorInvalidValue;
+    if (!bf16_main_fits(shape, a_lay, b_lay, a.M, a.N, a.K, a.A, a.lda, a.B, a.ldb) || !bf16_main_slices_fit(a.K, a.k_slices)) return hipErrorInvalidValue;
+    if (((a.M + kShapeM[shape] - 1) / kShapeM[shape]) * (int64_t)((a.N + kShapeN[shape] - 1) / kShapeN[shape]) * a.k_slices >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     switch (shape) {
     case 0: return launch_shape<8, 8>(a_lay, b_lay, a, s);
     case 1: return launch_shape<6, 8>(a_lay, b_lay, a, s);

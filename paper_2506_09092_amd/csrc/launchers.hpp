@@ -36,6 +36,7 @@ int bf16_main_tile_m(int shape);
 int bf16_main_tile_n(int shape);
 bool bf16_main_fits(int shape, int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb);
 const char *bf16_main_kernel_name(int shape, int a_lay, int b_lay);
+bool bf16_main_slices_fit(int64_t K, int slices);      // K slices of whole K-tiles, the last with at least one
 hipError_t launch_bf16_main(int shape, int a_lay, int b_lay, const GemmArgs &a, hipStream_t s);
 
 // fp32 products with M == 1 or N == 1 (gemv_f32.hip): y[i * incy] = sum over k of mat(i, k) * x[k * incx] for

@@ -208,10 +208,14 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
     assert pf(512, 512, 65536) == (1, 16) and pf(384, 384, 65536) == (1, 28) and pf(1024, 1024, 4096) == (1, 4)
     assert pf(768, 768, 4096) == (2, 4)             # 36 tiles x 4 slices: too few workgroups
     assert pf(256, 256, 16384) == (2, 64)           # slices of 256 k: too short
-    assert pb(512, 512, 65536) == (2, 16) and pb(256, 256, 16384) == (2, 64) and pb(768, 768, 4096) == (3, 4)
+    # bf16 from 128 rows and columns on: 64 x 64 tiles of the general kernel or 128 x 128 direct-to-LDS tiles (candidate 10) in
+    # the slice count with the least modelled time, about a workgroup per compute unit; no split where K is short
+    assert pb(512, 512, 65536) == (10, 16) and pb(256, 256, 16384) == (3, 16) and pb(768, 768, 4096) == (10, 5) and pb(512, 512, 8192) == (10, 10)
+    assert pb(128, 2048, 4096) == (3, 4) and pb(1024, 1024, 2048) == (3, 1) and pb(512, 512, 512) == (3, 1)
+    assert lib.fsrgemm_plan_bf16(0, 1, 512, 512, 65536, P + 2, 65536, P, 65536, True, True) == (3, 16)       # misaligned A: the general kernel only
     assert lib.gemm_f32_workspace_bytes(0, 0, 512, 512, 65536) == 16 * 512 * 512 * 4
     # a problem under 128 rows or columns keeps 64 x 64 tiles: most of a 128-wide tile would be padding
-    assert pf(8, 8192, 8192) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and pb(32, 28672, 8192) == (3, 2) and pb(96, 8192, 8192)[0] == 3 and pb(128, 8192, 8192)[0] == 2
+    assert pf(8, 8192, 8192) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and pb(32, 28672, 8192) == (3, 2) and pb(96, 8192, 8192) == (3, 4) and pb(128, 8192, 8192) == (10, 4)
 
 
 def test_f32_slices_on_the_direct_to_lds_shapes():
@@ -242,7 +246,8 @@ def test_forced_configurations_and_plan_queries():
     g = lambda tile, s, M, N, K, a=P, lda=None, ws=None, wsb=0: lib.gemm_bf16_cfg(tile, s, 0, 1, M, N, K, a, lda or K, P, K, P, N, ws, wsb, 0)
     # the direct-to-LDS candidate is rejected where its kernel's conditions fail, never replaced
     assert g(0, 1, 255, 512, 512) == bad and g(0, 1, 512, 512, 100) == bad and g(0, 1, 512, 512, 56) == bad and g(0, 1, 512, 512, 512, a=P + 2) == bad
-    assert g(0, 1, 512, 512, 512, lda=516) == bad and g(0, 2, 512, 512, 512, ws=P, wsb=1 << 24) == bad
+    assert g(0, 1, 512, 512, 512, lda=516) == bad and g(0, 2, 512, 512, 512) == bad and g(0, 2, 512, 512, 64, ws=P, wsb=1 << 24) == bad
+    assert g(0, 4, 512, 512, 320, ws=P, wsb=1 << 24) == bad            # 5 K-tiles of 64 in slices of 2: the fourth slice would be empty
     assert g(4, 1, 512, 512, 512) == bad and g(5, 1, 1, 512, 512) == bad and g(1, 1, 0, 512, 512) == ok     # candidate 4: vector shapes only
     # names of forced candidates; None where the forced call would reject the candidate
     qc, qh = lib.fsrgemm_kernel_for_f32_cfg, lib.fsrgemm_kernel_for_bf16_cfg
@@ -306,7 +311,7 @@ def test_forced_configurations_and_plan_queries():
     assert pb(0, 1, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1) and pb(0, 0, 6144, 6144, 6144, P, 6144, P, 6144) == (7, 1)   # 256 x 192, in every storage order
     # the rules (two bands); a row of the selection table (one launch of 64 x 64 tiles)
     assert lib.fsrgemm_bands_f32(0, 0, 2560, 2560, 2560, P, 2560, P, 2560, False, True)[0] == 1 and lib.fsrgemm_bands_f32(0, 0, 2560, 2560, 2560, P, 2560, P, 2560)[0] == 0
-    assert pb(0, 1, 512, 512, 512, P, 512, P, 512, True) == (3, 1) and pb(0, 1, 512, 512, 4096, P, 4096, P, 4096, True) == (2, 16)       # bf16 splits from K = 3072 on
+    assert pb(0, 1, 512, 512, 512, P, 512, P, 512, True) == (3, 1) and pb(0, 1, 512, 512, 4096, P, 4096, P, 4096, True) == (3, 4)       # bf16: no split of a short K
     # between 64 and 127 tiles of 256 x 256: a larger shape in one round, or 128 x 128 tiles, by the modelled times
     assert pb(0, 1, 2560, 2560, 2560, P, 2560, P, 2560) == (6, 1) and pb(1, 0, 2048, 2560, 8192, P, 2048, P, 2560) == (6, 1)
     assert pb(0, 1, 2048, 2048, 2048, P, 2048, P, 2048) == (10, 1) and pb(0, 1, 2048, 2048, 512, P, 512, P, 512) == (10, 1)
@@ -372,7 +377,7 @@ def test_dispatcher_only_plans_candidates_that_the_forced_calls_accept():
                 assert slices * M * N * 4 <= 16 << 20 and slices <= K, ctx
                 assert query(ta, tb, M, N, K) >= slices * M * N * 4, ctx         # (the query covers either alignment's plan)
             else:
-                assert kind == "f32" or query(ta, tb, M, N, K) == 0, ctx
+                pass            # (a plan for otherwise aligned operands may be split: the query names that need)
             if kind == "bf16" and (tile == 0 or tile >= 5):        # the bf16 direct-to-LDS kernel is never split
                 assert slices == 1, ctx
 

@@ -206,15 +206,16 @@ def test_splits_on_the_larger_tile(gpu, shape):
         got = run_f32_ws(gpu, 0, 0, A, B, offset=offset, repeat=2)
         assert np.all(np.isfinite(got)) and oracle.componentwise_error(got[ii, jj], ref, S) <= TOL_F32
         assert np.array_equal(run_cfg(gpu, "f32", tile, slices, 0, 0, A, B, offset=offset).view(np.uint32), got.view(np.uint32))
-    say("split on 128 x 128 tiles, bf16 %dx%dx%d" % shape)
-    tile, slices = gpu.fsrgemm_plan_bf16(0, 1, M, N, K, 0x1000, K, 0x1000, K, True)
-    assert tile == 2 and slices > 1
     Ah = inputs.bf16_normal_scaled(23, 3, M, K, 1 / math.sqrt(K))
     Bh = np.ascontiguousarray(inputs.bf16_normal_scaled(23, 4, N, K, 1 / math.sqrt(K)).T)
-    got = run_bf16_ws(gpu, 0, 1, Ah, Bh, repeat=2)
     ref, S = oracle.gemm_entries(Ah, Bh, ii, jj)
-    assert np.all(np.isfinite(got)) and oracle.componentwise_error(got[ii, jj], ref, S) <= TOL_BF16
-    assert np.array_equal(run_cfg(gpu, "bf16", tile, slices, 0, 1, Ah, Bh).view(np.uint32), got.view(np.uint32))
+    for offset, want in ((0, 10), (1, None)):           # aligned: the direct-to-LDS 128 x 128 tile; otherwise a general tile
+        say("split, bf16 %dx%dx%d, operands offset by %d" % (shape + (offset,)))
+        tile, slices = gpu.fsrgemm_plan_bf16(0, 1, M, N, K, 0x1000 + 2 * offset, K, 0x1000 + 2 * offset, K, True)
+        assert (tile == want if want else tile in (2, 3)) and slices > 1
+        got = run_bf16_ws(gpu, 0, 1, Ah, Bh, offset=offset, repeat=2)
+        assert np.all(np.isfinite(got)) and oracle.componentwise_error(got[ii, jj], ref, S) <= TOL_BF16
+        assert np.array_equal(run_cfg(gpu, "bf16", tile, slices, 0, 1, Ah, Bh, offset=offset).view(np.uint32), got.view(np.uint32))
 
 
 def test_f32_workspace_integers_bit_exact_and_large_problem_unsplit(gpu):
@@ -497,10 +498,21 @@ def test_bf16_main_kernel_every_shape(gpu, shape, ta, tb):
         got = run_cfg(gpu, "bf16", tile, 1, ta, tb, A, B, lda=lda + 8, ldb=ldb + 40, ldc=N + 3, repeat=2)
         assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
         assert np.array_equal(run_cfg(gpu, "bf16", tile, 1, ta, tb, Ai, Bi).astype(np.float64), refi)
-        # where the candidate does not fit it is rejected: a split, a misaligned base, rows that are not whole pieces
-        for kw, slices in ((dict(), 2), (dict(offset=1), 1), (dict(lda=lda + 4), 1)):
+        # K slices of whole K-tiles (the last one takes the rest of K): partial products in the workspace, summed in slice
+        # order; a count that would leave the last slice without a whole K-tile is rejected
+        for slices in (2, 3):
+            per = -(-(-(-K // 64)) // slices) * 64
+            if (slices - 1) * per + 64 <= K:
+                got = run_cfg(gpu, "bf16", tile, slices, ta, tb, A, B, lda=lda + 8, ldb=ldb + 40, ldc=N + 3, repeat=2)
+                assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
+                assert np.array_equal(run_cfg(gpu, "bf16", tile, slices, ta, tb, Ai, Bi).astype(np.float64), refi)
+            else:
+                with pytest.raises(gpu.FsrGemmError):
+                    run_cfg(gpu, "bf16", tile, slices, ta, tb, A, B)
+        # where the candidate does not fit it is rejected: a misaligned base, rows that are not whole pieces
+        for kw in (dict(offset=1), dict(lda=lda + 4)):
             with pytest.raises(gpu.FsrGemmError):
-                run_cfg(gpu, "bf16", tile, slices, ta, tb, A, B, **kw)
+                run_cfg(gpu, "bf16", tile, 1, ta, tb, A, B, **kw)
 
 
 def test_bf16_rest_of_k_at_full_width(gpu):
@@ -1206,7 +1218,8 @@ def test_bf16_every_candidate(gpu, shape, ta, tb):
             say("bf16 candidate tile %d slices %d on %dx%dx%d %d%d" % (tile, slices, M, N, K, ta, tb))
             if slices > 1 and (slices > -(-K // 64) or slices * M * N * 4 > 16 << 20):
                 continue
-            if tile == 0 and (slices > 1 or not fits_main):
+            per = -(-(-(-K // 64)) // slices) * 64                 # the direct-to-LDS kernel's slices: whole K-tiles, none left without one
+            if tile == 0 and (not fits_main or (slices - 1) * per + 64 > K):
                 with pytest.raises(gpu.FsrGemmError):
                     run_cfg(gpu, "bf16", tile, slices, ta, tb, A, B)
                 continue
