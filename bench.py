@@ -28,8 +28,8 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense MFMA peaks
 # profiles/gemm_f32_4096_bf16_8192_hbm_traffic.txt (scaled by a 1 GiB copy).  Each entry is tied to the
 # kernel sources it was measured on: once those change the figure is stale and the bench reports null.
 TRAFFIC = {
-    "f32_4096": {"bytes": 470091089, "sources": {"gemm_f32_main.hip": "de51751b875e6a09", "common.hpp": "fcd7c27e4bf90732"}},
-    "bf16_8192": {"bytes": 2103968485, "sources": {"gemm_bf16_main.hip": "947b2a1ff8a60ba1", "common.hpp": "fcd7c27e4bf90732"}},
+    "f32_4096": {"bytes": 470113020, "sources": {"gemm_f32_main.hip": "d31f2c4fcf463724", "common.hpp": "fcd7c27e4bf90732"}},
+    "bf16_8192": {"bytes": 2091149134, "sources": {"gemm_bf16_main.hip": "931ab26717423255", "common.hpp": "fcd7c27e4bf90732"}},
 }
 # the same for the transposes (profiles/transpose_f32_paper_sizes.txt), by N
 _T8_SOURCES = {"transpose.hip": "5bcb289871390c86", "common.hpp": "fcd7c27e4bf90732"}
