@@ -284,14 +284,15 @@ VecMap16 vector_map16(int transA, int transB, int64_t M, int64_t N, int64_t K, c
 
 // Workgroups of the vector kernels for an output of `len` elements, and the K slices of a call with a
 // workspace.  A split costs a second launch, so K is cut only to reach enough workgroups to keep the memory
-// system busy, and never finer than 2048 (1024 for the column pattern): 256 workgroups, or 512 (fp32) / 1024 (bf16)
-// for the column pattern on a matrix of 128 MiB and more, whose workgroups each keep 32 KB in flight (measured: fp32 1 x 4096 x 4096 gains 15 % from two
-// slices, 1 x 1024 x 1024 loses 40 % to any split; bf16 1 x 16384 x 16384 with a row-major B gains 35 % from four).
+// system busy, and never finer than 2048 (1024 for the column pattern): 256 workgroups, or 1024 for the bf16 column pattern
+// on a matrix of 128 MiB and more, whose workgroups each keep 32 KB in flight (measured: fp32 1 x 4096 x 4096 gains 15 % from
+// two slices, 1 x 8192 x 8192 loses 15 % to two, 1 x 1024 x 1024 loses 40 % to any split; bf16 1 x 16384 x 16384 with a row-major
+// B gains 35 % from four).
 int64_t vector_groups(int pattern, int64_t len, int cols_per_group) { return pattern == kVecRows ? ceil_div(len, 4) : ceil_div(len, cols_per_group); }
 int vector_slices(int pattern, int64_t len, int64_t K, int cols_per_group = 32)
 {
     const int64_t matrix_bytes = len * K * (cols_per_group == 32 ? 4 : 2);
-    const int64_t target = pattern == kVecCols && matrix_bytes >= ((int64_t)128 << 20) ? (cols_per_group == 64 ? 1024 : 512) : 256;
+    const int64_t target = pattern == kVecCols && matrix_bytes >= ((int64_t)128 << 20) && cols_per_group == 64 ? 1024 : 256;
     int64_t s = target / vector_groups(pattern, len, cols_per_group);
     const int64_t shortest = pattern == kVecCols ? 1024 : 2048;
     if (s > K / shortest) s = K / shortest;
