@@ -149,7 +149,7 @@ int tile_rule_f32(int64_t M, int64_t N, unsigned main_fits, int64_t *cost_out = 
 // A split is taken for a modelled gain of 5 % over the best unsplit shape.  Units of 0.1 ns.
 struct MainSplit {
     int shape = -1, slices = 1;
-    int64_t cost = 0;
+    double cost = 0;        // (a double: tiles x K x tile time leaves 64 bits for extents near their limits)
 };
 MainSplit best_main_split(int64_t M, int64_t N, int64_t K, unsigned main_fits)
 {
@@ -162,14 +162,14 @@ MainSplit best_main_split(int64_t M, int64_t N, int64_t K, unsigned main_fits)
             if (sl > 1 && (int64_t)sl * M * N * 4 > kMaxWorkspace) break;
             if (!f32_main_slices_fit(K, sl)) continue;       // the last slice would be left without a whole K-tile
             const int64_t w = ceil_div(tiles * sl, 256), len = ceil_div(ceil_div(K, 32), sl) * 32;
-            int64_t cost = w * len * (w == 1 ? kAlone[sh] : kMainTileTime[sh]) + w * 10000;
+            double cost = (double)w * (double)len * (double)(w == 1 ? kAlone[sh] : kMainTileTime[sh]) + (double)w * 10000.0;
             if (sl > 1 && len < 256) continue;                // a slice keeps at least eight K-tiles
-            if (sl > 1) cost += 40000 + (sl + 1) * M * N * 4 / 300;
+            if (sl > 1) cost += 40000.0 + (double)(sl + 1) * (double)M * (double)N * 4.0 / 300.0;
             if (sl == 1 && (unsplit.shape < 0 || cost < unsplit.cost)) unsplit.shape = sh, unsplit.cost = cost;
             if (best.shape < 0 || cost < best.cost) best.shape = sh, best.slices = sl, best.cost = cost;
         }
     }
-    return best.slices > 1 && best.cost * 100 > unsplit.cost * 95 ? unsplit : best;
+    return best.slices > 1 && best.cost > unsplit.cost * 0.95 ? unsplit : best;
 }
 
 // Two bands.  Where no tile shape fills whole rounds of the compute units, two launches often do: C is cut once, along
