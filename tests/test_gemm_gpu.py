@@ -162,7 +162,8 @@ def test_bf16_shapes(gpu, shape):
 
 
 SKINNY = [(1, 4096, 4096), (4096, 1, 4096), (1, 1, 4096), (64, 64, 4097), (16, 1000, 3000), (257, 100, 2049),
-          (3, 700, 1031), (300, 5, 8192), (128, 128, 16384), (512, 512, 1024)]
+          (3, 700, 1031), (300, 5, 8192), (128, 128, 16384), (512, 512, 1024),
+          (256, 256, 16384), (768, 768, 2048), (320, 264, 1000)]       # K slices on the direct-to-LDS shapes (64 x 64 x 16, 128 x 64 x 3, ..)
 
 
 @pytest.mark.parametrize("shape", SKINNY)
@@ -182,10 +183,14 @@ def test_f32_workspace_split_k(gpu, shape):
     pad = 3 if (M + N) % 2 else 4
     got = run_f32_ws(gpu, 0, 0, A, B, lda=K + pad, ldb=N + pad, ldc=N + 1, offset=1 if pad == 3 else 0, repeat=2)
     assert oracle.componentwise_error(got, ref, S) <= TOL_F32
-    # a workspace one float short, or none, must leave the call equal to gemm_f32_ex bit for bit
+    # a workspace one float short of what the plan for these (aligned) operands uses, or none, must leave the call equal to
+    # gemm_f32_ex bit for bit; the query names at least that much (it also covers the plan for misaligned operands)
     plain = run_f32_ex(gpu, 0, 0, A, B)
-    if need:
-        assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=need - 4).view(np.uint32), plain.view(np.uint32))
+    tile, slices = gpu.fsrgemm_plan_f32(0, 0, M, N, K, P_FAKE, K, P_FAKE, N, True)
+    used = slices * M * N * 4 if slices > 1 or tile == 4 else 0
+    assert used <= need
+    if used:
+        assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=used - 4).view(np.uint32), plain.view(np.uint32))
     assert np.array_equal(run_f32_ws(gpu, 0, 0, A, B, workspace_bytes=0).view(np.uint32), plain.view(np.uint32))
 
 
@@ -230,7 +235,8 @@ def test_f32_workspace_integers_bit_exact_and_large_problem_unsplit(gpu):
 
 
 @pytest.mark.parametrize("shape", [(1, 4096, 4096), (4096, 1, 4096), (8, 1000, 3000), (64, 64, 4100), (130, 70, 3082),
-                                   (16, 8192, 2048), (256, 256, 8192)])
+                                   (16, 8192, 2048), (256, 256, 8192),
+                                   (512, 512, 8192), (768, 776, 4096)])     # 128 x 128 direct-to-LDS tiles in K slices
 def test_bf16_workspace_split_k(gpu, shape):
     M, N, K = shape
     need = gpu.gemm_bf16_workspace_bytes(0, 1, M, N, K)
@@ -246,8 +252,10 @@ def test_bf16_workspace_split_k(gpu, shape):
     got = run_bf16_ws(gpu, 0, 1, A, B, lda=K + 3, ldb=K + 3, ldc=N + 1, offset=1, repeat=2)
     assert oracle.componentwise_error(got, ref, S) <= TOL_BF16
     plain = run_bf16_ex(gpu, 0, 1, A, B)
-    if need:
-        assert np.array_equal(run_bf16_ws(gpu, 0, 1, A, B, workspace_bytes=need - 4).view(np.uint32), plain.view(np.uint32))
+    tile, slices = gpu.fsrgemm_plan_bf16(0, 1, M, N, K, P_FAKE, K, P_FAKE, K, True)
+    assert slices * M * N * 4 <= need or slices == 1
+    if slices > 1:          # one float short of what the plan for these (aligned) operands uses: exactly the plain call
+        assert np.array_equal(run_bf16_ws(gpu, 0, 1, A, B, workspace_bytes=slices * M * N * 4 - 4).view(np.uint32), plain.view(np.uint32))
     Ai, Bi = inputs.bf16_small_ints(4, 52, M, K), inputs.bf16_small_ints(4, 53, K, N)
     refi, _ = oracle.gemm(Ai, Bi)
     assert np.array_equal(run_bf16_ws(gpu, 0, 1, Ai, Bi).astype(np.float64), refi)
