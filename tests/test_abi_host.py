@@ -378,8 +378,51 @@ def test_dispatcher_only_plans_candidates_that_the_forced_calls_accept():
                 assert query(ta, tb, M, N, K) >= slices * M * N * 4, ctx         # (the query covers either alignment's plan)
             else:
                 pass            # (a plan for otherwise aligned operands may be split: the query names that need)
-            if kind == "bf16" and (tile == 0 or tile >= 5):        # the bf16 direct-to-LDS kernel is never split
+            if kind == "bf16" and (tile == 0 or 5 <= tile <= 9):   # of the bf16 direct-to-LDS shapes only 128x128 takes K slices
                 assert slices == 1, ctx
+
+
+def _slices_fit(K, slices, k_tile):
+    # whole K-tiles per slice, the last slice takes the rest and must hold at least one whole K-tile
+    per = ((K + k_tile - 1) // k_tile + slices - 1) // slices * k_tile
+    return (slices - 1) * per + k_tile <= K
+
+
+def test_slice_plans_for_problems_of_few_tiles():
+    # the shapes the slice planners are for (sides of 128 to 3072, K up to 65536, aligned and padded operands in every
+    # storage order): a split plan on a direct-to-LDS tile has slices of whole K-tiles with a last slice that is not
+    # empty, fits the workspace the query names (at most 16 MiB), and is never slower by the planner's own rule than
+    # no split at all would need to be: it is only taken with a workspace
+    import random
+
+    rng = random.Random(21)
+    sides = [128, 192, 256, 320, 384, 512, 640, 768, 1000, 1024, 1536, 2048, 2560, 3072]
+    depths = [64, 256, 512, 1000, 1024, 2048, 3072, 4096, 8192, 16384, 65536]
+    seen = {"f32": 0, "bf16": 0}
+    for case in range(3000):
+        kind = rng.choice(("f32", "bf16"))
+        ta, tb = rng.randint(0, 1), rng.randint(0, 1)
+        M, N, K = rng.choice(sides), rng.choice(sides), rng.choice(depths)
+        pad = 4 if kind == "f32" else 8                      # keeps 16-byte rows
+        lda, ldb = (M if ta else K) + rng.choice((0, 0, pad)), (K if tb else N) + rng.choice((0, 0, pad))
+        plan, named = ((lib.fsrgemm_plan_f32, lib.fsrgemm_kernel_for_f32_cfg) if kind == "f32" else
+                       (lib.fsrgemm_plan_bf16, lib.fsrgemm_kernel_for_bf16_cfg))
+        query = lib.gemm_f32_workspace_bytes if kind == "f32" else lib.gemm_bf16_workspace_bytes
+        assert plan(ta, tb, M, N, K, P, lda, P, ldb, False)[1] == 1
+        tile, slices = plan(ta, tb, M, N, K, P, lda, P, ldb, True)
+        ctx = (kind, ta, tb, M, N, K, lda, ldb, tile, slices)
+        name = named(tile, ta, tb, M, N, K, P, lda, P, ldb, P, N)
+        assert name is not None, ctx
+        if slices == 1:
+            continue
+        assert slices * M * N * 4 <= query(ta, tb, M, N, K) <= 16 << 20, ctx
+        if "main" in name:                                   # a direct-to-LDS tile: slices of whole K-tiles
+            seen[kind] += 1
+            k_tile = 32 if kind == "f32" else 64
+            assert _slices_fit(K, slices, k_tile), ctx
+            per = ((K + k_tile - 1) // k_tile + slices - 1) // slices * k_tile
+            assert per >= (256 if kind == "f32" else 512), ctx              # the planners' shortest slices
+    assert seen["f32"] > 50 and seen["bf16"] > 50, seen
 
 
 def test_tuned_table_rows_are_well_formed():
