@@ -916,6 +916,41 @@ def test_random_small_bf16_shapes_in_every_storage_order(gpu):
     assert main >= 12, main
 
 
+def test_random_aligned_shapes_with_a_workspace(gpu):
+    # 48 seeded cases of 128 .. 1536 rows and columns and K up to 32768, aligned, every storage order, padded leading
+    # dimensions, with a workspace: what the slice planners make of them (K slices on the direct-to-LDS tiles or on the
+    # general kernels, or no split) against the oracle's whole product, and bit for bit the same on a second call
+    import random
+
+    rng = random.Random(35)
+    split_main = {"f32": 0, "bf16": 0}
+    for case in range(48):
+        kind = ("f32", "bf16")[case % 2]
+        ta, tb = rng.randint(0, 1), rng.randint(0, 1)
+        M, N = 8 * rng.randint(16, 192), 8 * rng.randint(16, 192)
+        K = 8 * int(2 ** (6 + 6 * rng.random()))
+        while M * N * K > 4e9:
+            M = max(128, M // 2 // 8 * 8)
+        pad = 8 * rng.choice((0, 0, 1, 3))
+        lda, ldb = (M if ta else K) + pad, (K if tb else N) + pad
+        if kind == "f32":
+            A, B = inputs.uniform_pm1(35, 2 * case, M, K), inputs.uniform_pm1(35, 2 * case + 1, K, N)
+            tol, run_ws, plan, named = TOL_F32, run_f32_ws, gpu.fsrgemm_plan_f32, gpu.fsrgemm_kernel_for_f32_cfg
+        else:
+            A = inputs.bf16_normal_scaled(35, 2 * case, M, K, 1 / math.sqrt(K))
+            B = inputs.bf16_normal_scaled(35, 2 * case + 1, K, N, 1 / math.sqrt(K))
+            tol, run_ws, plan, named = 1e-5, run_bf16_ws, gpu.fsrgemm_plan_bf16, gpu.fsrgemm_kernel_for_bf16_cfg
+        tile, slices = plan(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb, True)
+        name = named(tile, ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N)
+        say("workspace case %d: %s %d%d %dx%dx%d lda %d ldb %d -> %s, %d slices" % (case, kind, ta, tb, M, N, K, lda, ldb, name, slices))
+        split_main[kind] += slices > 1 and "main" in name
+        ref, S = oracle.gemm(A, B)
+        got = run_ws(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + rng.choice((0, 4)), repeat=2)
+        e = oracle.componentwise_error(got, ref, S)
+        assert e <= tol, (case, kind, ta, tb, M, N, K, name, slices, e)
+    assert split_main["f32"] >= 4 and split_main["bf16"] >= 4, split_main
+
+
 # ---- the library under HIP graph capture ----
 
 def test_calls_captured_in_a_hip_graph_replay_bit_exact(gpu):
