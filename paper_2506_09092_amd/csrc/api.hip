@@ -240,8 +240,9 @@ void shift_to_band(int dim, int64_t at, int a_lay, int b_lay, const T *&A, int64
     C = reinterpret_cast<float *>(reinterpret_cast<uintptr_t>(C) + (uintptr_t)off_c * sizeof(float));
 }
 
-// How a product with M == 1 or N == 1 maps onto the vector kernels: which operand is the matrix, how it is
-// walked, and the strides of the two vectors.  ARGS: VecArgs (fp32) or VecArgs16 (bf16); T the element type.
+// How a product with M == 1 or N == 1 (fp32: with up to kMaxFewVectors rows or columns on the smaller side) maps onto
+// the vector kernels: which operand is the matrix, how it is walked, and the strides of the vectors on either side.
+// ARGS: VecArgs (fp32) or VecArgs16 (bf16); T the element type.
 template <class ARGS, class T>
 struct VecMapT {
     int pattern;
@@ -256,16 +257,18 @@ VecMapT<ARGS, T> vector_map_t(int transA, int transB, int64_t M, int64_t N, int6
     v.a.k_slices = 1;
     v.a.slice_stride = 0;
     v.a.xvec = false;
-    if (N == 1) {       // a matrix times a column: y = C's column, x = B's
+    if (N <= M) {       // a matrix times columns: y = C's columns, x = B's
         v.pattern = transA ? kVecCols : kVecRows;
         v.a.mat = A, v.a.ld = lda, v.a.len = (int)M;
-        v.a.x = B, v.a.incx = transB ? 1 : ldb;
-        v.a.y = C, v.a.incy = ldc;
-    } else {            // a row times a matrix: y = C's row, x = A's
+        v.a.x = B, v.a.incx = transB ? 1 : ldb, v.a.ldx = transB ? ldb : 1;
+        v.a.y = C, v.a.incy = ldc, v.a.ldy = 1;
+        v.a.nvec = (int)N;
+    } else {            // rows times a matrix: y = C's rows, x = A's
         v.pattern = transB ? kVecRows : kVecCols;
         v.a.mat = B, v.a.ld = ldb, v.a.len = (int)N;
-        v.a.x = A, v.a.incx = transA ? lda : 1;
-        v.a.y = C, v.a.incy = 1;
+        v.a.x = A, v.a.incx = transA ? lda : 1, v.a.ldx = transA ? 1 : lda;
+        v.a.y = C, v.a.incy = 1, v.a.ldy = ldc;
+        v.a.nvec = (int)M;
     }
     return v;
 }
@@ -288,12 +291,12 @@ VecMap16 vector_map16(int transA, int transB, int64_t M, int64_t N, int64_t K, c
 // on a matrix of 128 MiB and more, whose workgroups each keep 32 KB in flight (measured: fp32 1 x 4096 x 4096 gains 15 % from
 // two slices, 1 x 8192 x 8192 loses 15 % to two, 1 x 1024 x 1024 loses 40 % to any split; bf16 1 x 16384 x 16384 with a row-major
 // B gains 35 % from four).
-int64_t vector_groups(int pattern, int64_t len, int cols_per_group) { return pattern == kVecRows ? ceil_div(len, 4) : ceil_div(len, cols_per_group); }
-int vector_slices(int pattern, int64_t len, int64_t K, int cols_per_group = 32)
+int64_t vector_groups(int pattern, int64_t len, int cols_per_group, int rows_per_group = 4) { return pattern == kVecRows ? ceil_div(len, rows_per_group) : ceil_div(len, cols_per_group); }
+int vector_slices(int pattern, int64_t len, int64_t K, int cols_per_group = 32, int rows_per_group = 4)
 {
     const int64_t matrix_bytes = len * K * (cols_per_group == 32 ? 4 : 2);
     const int64_t target = pattern == kVecCols && matrix_bytes >= ((int64_t)128 << 20) && cols_per_group == 64 ? 1024 : 256;
-    int64_t s = target / vector_groups(pattern, len, cols_per_group);
+    int64_t s = target / vector_groups(pattern, len, cols_per_group, rows_per_group);
     const int64_t shortest = pattern == kVecCols ? 1024 : 2048;
     if (s > K / shortest) s = K / shortest;
     if (s > kMaxSlices) s = kMaxSlices;
@@ -302,6 +305,15 @@ int vector_slices(int pattern, int64_t len, int64_t K, int cols_per_group = 32)
 
 // (K beyond 2^30 stays with the tile kernels: the vector kernels count k in 32-bit steps of up to 1024)
 bool vector_shape(int64_t M, int64_t N, int64_t K) { return (M == 1 || N == 1) && M > 0 && N > 0 && K > 0 && K <= ((int64_t)1 << 30); }
+// fp32 also with 2 .. kMaxFewVectors rows or columns on the smaller side, where the other operand (the matrix that is
+// streamed) consists of aligned 16-byte pieces
+bool vector_call_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb)
+{
+    if (vector_shape(M, N, K)) return true;
+    if (M < 1 || N < 1 || K < 1 || K > ((int64_t)1 << 30) || (M > kMaxFewVectors && N > kMaxFewVectors)) return false;
+    const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
+    return gemv_takes_few(v.pattern, v.a);
+}
 
 // The small-result kernel wants both operands stored with k as the row index: a transposed A (K x M) and a
 // row-major B (K x N).  A vector is that in either storage order: a 1 x K row is a K x 1 column with leading
@@ -319,7 +331,7 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
              int64_t ldb, bool split, Plan *p, bool use_table = true)
 {
     const Tuned *t = use_table ? find_tuned(0, transA, transB, M, N, K, split) : nullptr;
-    const bool vector = vector_shape(M, N, K);
+    const bool vector = vector_call_f32(transA, transB, M, N, K, A, lda, B, ldb);
     SkinnyArgs sk;
     sk.K = (int)K;
     sk.parts = (int)(K / 256 < kSkinnyMaxParts ? K / 256 : kSkinnyMaxParts);
@@ -332,7 +344,8 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
     } else if (!t && vector) {
         const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
         p->cfg = kF32_Vector;
-        p->slices = split ? vector_slices(v.pattern, v.a.len, K) : 1;
+        p->slices = split ? vector_slices(v.pattern, v.a.len, K, 32, v.a.nvec > 1 ? 16 : 4) : 1;
+        if (p->slices > 1 && (int64_t)p->slices * M * N * 4 > kMaxWorkspace) p->slices = (int)(kMaxWorkspace / (M * N * 4)) < 2 ? 1 : (int)(kMaxWorkspace / (M * N * 4));
     } else {
         p->slices = t ? t->slices : split ? splitk_slices(M, N, K, 16) : 1;
         if (!t && p->slices == 1 && use_table) t = find_tuned(0, transA, transB, M, N, K, false);
@@ -663,7 +676,11 @@ int run_f32(const Plan &p, int transA, int transB, int64_t M, int64_t N, int64_t
     }
     if (p.cfg == kF32_Vector) {
         VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, C, ldc);
-        if (split) v.a.y = ws, v.a.incy = 1, v.a.k_slices = p.slices, v.a.slice_stride = v.a.len;
+        if (split) {        // a slice of the workspace is an M x N matrix with rows of N
+            v.a.y = ws, v.a.k_slices = p.slices, v.a.slice_stride = M * N;
+            if (N <= M) v.a.incy = N, v.a.ldy = 1;
+            else v.a.incy = 1, v.a.ldy = N;
+        }
         e = launch_gemv_f32(v.pattern, v.a, s);
     } else {
         GemmArgs a = pack(M, N, K, A, lda, B, ldb, split ? ws : C, split ? N : ldc);
@@ -860,7 +877,7 @@ int gemm_f32_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int6
             return FSRGEMM_ERR_INVALID_ARG;
     } else {
         if (!forced_ok(tile, kF32_Vector + 1, k_slices, M, N, K, 16, workspace, workspace_bytes)) return FSRGEMM_ERR_INVALID_ARG;
-        if (tile == kF32_Vector && !vector_shape(M, N, K) && M > 0 && N > 0) return FSRGEMM_ERR_INVALID_ARG;
+        if (tile == kF32_Vector && !vector_call_f32(transA, transB, M, N, K, A, lda, B, ldb) && M > 0 && N > 0) return FSRGEMM_ERR_INVALID_ARG;
     }
     Plan p = {tile, 0, k_slices};
     rc = mode_f32(tile, k_slices, M, N, K, A, lda, B, ldb, &p.mode);
@@ -1010,7 +1027,7 @@ const char *fsrgemm_kernel_for_f32_ex(int transA, int transB, int64_t M, int64_t
     }
     if (p.cfg == kF32_Vector) {
         const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
-        return gemv_kernel_name(v.pattern, gemv_takes_vectors(v.a));
+        return gemv_kernel_name(v.pattern, gemv_takes_vectors(v.a), v.a.nvec);
     }
     return f32_kernel_name(p.cfg, p.mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig);
 }
@@ -1052,12 +1069,12 @@ const char *fsrgemm_kernel_for_f32_cfg(int tile, int transA, int transB, int64_t
         const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;
         return f32_main_fits(tile - kF32_Main, a_lay, b_lay, M, N, K, A, lda, B, ldb) ? f32_main_kernel_name(tile - kF32_Main, a_lay, b_lay) : nullptr;
     }
-    if (tile < 0 || tile > kF32_Vector || (tile == kF32_Vector && !vector_shape(M, N, K))) return nullptr;
+    if (tile < 0 || tile > kF32_Vector || (tile == kF32_Vector && !vector_call_f32(transA, transB, M, N, K, A, lda, B, ldb))) return nullptr;
     int mode;
     if (mode_f32(tile, 1, M, N, K, A, lda, B, ldb, &mode) != FSRGEMM_OK) return nullptr;
     if (tile == kF32_Vector) {
         const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
-        return gemv_kernel_name(v.pattern, gemv_takes_vectors(v.a));
+        return gemv_kernel_name(v.pattern, gemv_takes_vectors(v.a), v.a.nvec);
     }
     return f32_kernel_name(tile, mode, transA ? kMnContig : kKContig, transB ? kKContig : kMnContig);
 }

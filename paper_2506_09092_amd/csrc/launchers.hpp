@@ -55,9 +55,13 @@ struct VecArgs {
     int k_slices;
     int64_t slice_stride;
     bool xvec;
+    int nvec;               // vectors x_r = x + r * ldx, y_r = y + r * ldy, r < nvec <= kMaxFewVectors
+    int64_t ldx, ldy;
 };
-const char *gemv_kernel_name(int pattern, bool vec);
+constexpr int kMaxFewVectors = 8;
+const char *gemv_kernel_name(int pattern, bool vec, int nvec = 1);
 bool gemv_takes_vectors(const VecArgs &a);
+bool gemv_takes_few(int pattern, const VecArgs &a);     // whether a.nvec > 1 vectors can go through these kernels
 hipError_t launch_gemv_f32(int pattern, VecArgs a, hipStream_t s);
 
 // the same for bf16 operands (gemv_bf16.hip); y is fp32
@@ -80,6 +84,8 @@ struct VecArgs16 {
     int k_slices;
     int64_t slice_stride;
     bool xvec;
+    int nvec;               // always 1: the bf16 kernels take one vector
+    int64_t ldx, ldy;
 };
 const char *gemv_bf16_kernel_name(int pattern, bool vec);
 bool gemv_bf16_takes_vectors(const VecArgs16 &a);

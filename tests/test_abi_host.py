@@ -215,7 +215,17 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
     assert lib.fsrgemm_plan_bf16(0, 1, 512, 512, 65536, P + 2, 65536, P, 65536, True, True) == (3, 16)       # misaligned A: the general kernel only
     assert lib.gemm_f32_workspace_bytes(0, 0, 512, 512, 65536) == 16 * 512 * 512 * 4
     # a problem under 128 rows or columns keeps 64 x 64 tiles: most of a 128-wide tile would be padding
-    assert pf(8, 8192, 8192) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and pb(32, 28672, 8192) == (3, 2) and pb(96, 8192, 8192) == (3, 4) and pb(128, 8192, 8192) == (10, 4)
+    assert pf(16, 8192, 8192) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 16, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and pb(32, 28672, 8192) == (3, 2) and pb(96, 8192, 8192) == (3, 4) and pb(128, 8192, 8192) == (10, 4)
+    # fp32 with up to eight rows (or columns) streams the other operand through the vector kernels (candidate 3) where that
+    # operand consists of aligned 16-byte pieces: K slices only up to 256 workgroups; otherwise tiles as above
+    assert pf(8, 8192, 8192) == (3, 1) and pf(8, 2048, 8192) == (3, 4) and lib.fsrgemm_plan_f32(0, 1, 8, 2048, 8192, P, 8192, P, 8192, True, True) == (3, 2)
+    assert lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P + 4, 8192, True, True) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P, 8193, True, True) == (2, 8)
+    assert lib.fsrgemm_plan_f32(0, 0, 9, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 8, 2048, 8192, P, 8192, P, 2048, False, True) == (3, 1)
+    assert lib.fsrgemm_kernel_for_f32_ex(0, 0, 8, 2048, 8192, P, 8192, P, 2048, P, 2048) == "gemv_cols_f32_few_kernel<8>"
+    assert lib.fsrgemm_kernel_for_f32_ex(0, 1, 3, 2048, 8192, P, 8192, P, 8192, P, 2048) == "gemv_rows_f32_few_kernel<4>"
+    assert lib.fsrgemm_kernel_for_f32_ex(1, 0, 2048, 2, 8192, P, 2048, P, 2, P, 2) == "gemv_cols_f32_few_kernel<2>"
+    assert lib.fsrgemm_kernel_for_f32_ex(1, 0, 3, 2, 8192, P, 4, P, 2, P, 2).startswith("gemm_f32_kernel<")     # three columns to walk: no whole piece
+    assert lib.gemm_f32_workspace_bytes(0, 0, 8, 2048, 8192) == 32 * 8 * 2048 * 4       # (the larger need: misaligned operands on tiles, 32 slices)
 
 
 def test_f32_slices_on_the_direct_to_lds_shapes():

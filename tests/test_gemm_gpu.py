@@ -1170,8 +1170,80 @@ def test_f32_vector_every_slice_count(gpu):
             say("f32 vector candidate, %d slices, storage %d%d" % (slices, ta, tb))
             assert oracle.componentwise_error(run_cfg(gpu, "f32", 3, slices, ta, tb, A, B, repeat=2), ref, S) <= TOL_F32
             assert oracle.componentwise_error(run_cfg(gpu, "f32", 3, slices, ta, tb, B.T.copy(), A.T.copy(), repeat=2), ref.T, S.T) <= TOL_F32
-    with pytest.raises(gpu.FsrGemmError):
-        run_cfg(gpu, "f32", 3, 1, 0, 0, inputs.uniform_pm1(14, 5, 2, 64), inputs.uniform_pm1(14, 6, 64, 2))
+    with pytest.raises(gpu.FsrGemmError):       # nine rows and nine columns: no vector side
+        run_cfg(gpu, "f32", 3, 1, 0, 0, inputs.uniform_pm1(14, 5, 9, 64), inputs.uniform_pm1(14, 6, 64, 9))
+
+
+# ---- a few vectors on one side (2 .. 8 rows or columns): the streaming kernels with the vectors staged in LDS ----
+
+def _ceil4(n):
+    return n + (-n) % 4
+
+
+FEW_SHAPES = [(8, 1000, 777), (3, 513, 2050), (2, 64, 9), (5, 36, 1300), (1000, 8, 777), (516, 3, 2050), (7, 4100, 5000),
+              (4, 4, 4096), (8, 8, 600), (6, 2049, 515), (2050, 5, 1027), (2, 4, 1), (8, 31, 3), (3, 3, 50)]
+
+
+@pytest.mark.parametrize("M,N,K", FEW_SHAPES)
+def test_f32_few_vector_shapes(gpu, M, N, K):
+    A, B = inputs.uniform_pm1(15, 1, M, K), inputs.uniform_pm1(15, 2, K, N)
+    ref, S = oracle.gemm(A, B)
+    Ai, Bi = inputs.small_ints(0, 13, M, K), inputs.small_ints(0, 14, K, N)
+    refi, _ = oracle.gemm(Ai, Bi)
+    for ta, tb in [(0, 0)] + LAYOUTS:
+        lda, ldb = _ceil4(M if ta else K), _ceil4(K if tb else N)            # rows of whole 16-byte pieces
+        name = gpu.fsrgemm_kernel_for_f32_ex(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N)
+        say("f32 few vectors %dx%dx%d storage %d%d -> %s" % (M, N, K, ta, tb, name))
+        # the streamed operand is the larger side; where it is walked along its columns it needs four of them
+        cols = (ta if N <= M else not tb)
+        assert ("few_kernel" in name) == (not cols or max(M, N) >= 4), name
+        got = run_f32_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 3, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        got = run_f32_ws(gpu, ta, tb, A, B, lda=lda + 4, ldb=ldb + 8, repeat=2)            # with the workspace the library asks for
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        got = run_f32_ex(gpu, ta, tb, A, B, lda=lda + 1, ldb=ldb + 3, offset=1, repeat=2)  # 4-byte aligned only: the tile kernels
+        assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        if K <= 4097:
+            assert np.array_equal(run_f32_ws(gpu, ta, tb, Ai, Bi, lda=lda, ldb=ldb).astype(np.float64), refi)
+            assert np.array_equal(run_f32_ex(gpu, ta, tb, Ai, Bi, lda=lda, ldb=ldb).astype(np.float64), refi)
+
+
+def test_f32_few_vectors_every_count_and_slice_count(gpu):
+    # 2 .. 8 vectors on either side through the vector candidate with 1 .. 64 K slices (slices of a few elements, empty
+    # slices, a last chunk that is not whole), every storage order
+    K = 1500
+    for nvec in range(2, 9):
+        A, B = inputs.uniform_pm1(15, 10 + nvec, nvec, K), inputs.uniform_pm1(15, 20 + nvec, K, 332)
+        ref, S = oracle.gemm(A, B)
+        for ta, tb in [(0, 0)] + LAYOUTS:
+            for slices in (1, 2, 3, 7, 64):
+                say("f32 vector candidate, %d vectors, %d slices, storage %d%d" % (nvec, slices, ta, tb))
+                kw = dict(lda=_ceil4(nvec if ta else K), ldb=_ceil4(K if tb else 332), repeat=2)
+                assert oracle.componentwise_error(run_cfg(gpu, "f32", 3, slices, ta, tb, A, B, **kw), ref, S) <= TOL_F32
+                kw = dict(lda=_ceil4(332 if ta else K), ldb=_ceil4(K if tb else nvec), repeat=2)
+                assert oracle.componentwise_error(run_cfg(gpu, "f32", 3, slices, ta, tb, B.T.copy(), A.T.copy(), **kw), ref.T, S.T) <= TOL_F32
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 300, 700), (300, 5, 700), (3, 132, 515)])
+def test_f32_few_vectors_special_values(gpu, M, N, K):
+    # infinities and NaNs in the streamed matrix, among them its last row and column (which the kernels read again in
+    # place of pieces outside the matrix): the class of every entry must match the oracle's
+    Ai, Bi = inputs.small_ints(0, 15, M, K), inputs.small_ints(0, 16, K, N)
+    mat = Bi if M <= N else Ai
+    mat = _plant_specials(mat, 3, 5)
+    mat[-1, -1], mat[-1, 0], mat[0, -1] = np.inf, np.nan, -np.inf
+    A, B = (Ai, mat) if M <= N else (mat, Bi)
+    ref, S = oracle.gemm(A, B)
+    assert np.isnan(ref).any() and np.isfinite(ref).any()
+    fin = np.isfinite(ref)
+    for ta, tb in [(0, 0)] + LAYOUTS:
+        kw = dict(lda=_ceil4(M if ta else K), ldb=_ceil4(K if tb else N))
+        for slices in (1, 3):
+            say("f32 few vectors, specials, %dx%dx%d storage %d%d, %d slices" % (M, N, K, ta, tb, slices))
+            got = run_cfg(gpu, "f32", 3, slices, ta, tb, A, B, **kw)
+            assert _same_class(got, ref)
+            assert np.array_equal(got[fin].astype(np.float64), ref[fin])          # small integers: exact
+        assert _same_class(run_f32_ex(gpu, ta, tb, A, B, **kw), ref)
 
 
 # ---- small results of long sums (the normal equations of the paper's Task 20) ----
