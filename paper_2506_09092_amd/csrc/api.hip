@@ -295,7 +295,7 @@ int64_t vector_groups(int pattern, int64_t len, int cols_per_group, int rows_per
 int vector_slices(int pattern, int64_t len, int64_t K, int cols_per_group = 32, int rows_per_group = 4)
 {
     const int64_t matrix_bytes = len * K * (cols_per_group == 32 ? 4 : 2);
-    const int64_t target = pattern == kVecCols && matrix_bytes >= ((int64_t)128 << 20) && cols_per_group == 64 ? 1024 : 256;
+    const int64_t target = pattern == kVecCols && matrix_bytes >= ((int64_t)128 << 20) && cols_per_group == 64 && rows_per_group == 4 ? 1024 : 256;
     int64_t s = target / vector_groups(pattern, len, cols_per_group, rows_per_group);
     const int64_t shortest = pattern == kVecCols ? 1024 : 2048;
     if (s > K / shortest) s = K / shortest;
@@ -313,6 +313,14 @@ bool vector_call_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, co
     if (M < 1 || N < 1 || K < 1 || K > ((int64_t)1 << 30) || (M > kMaxFewVectors && N > kMaxFewVectors)) return false;
     const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
     return gemv_takes_few(v.pattern, v.a);
+}
+
+bool vector_call_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb)
+{
+    if (vector_shape(M, N, K)) return true;
+    if (M < 1 || N < 1 || K < 1 || K > ((int64_t)1 << 30) || (M > kMaxFewVectors && N > kMaxFewVectors)) return false;
+    const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
+    return gemv_bf16_takes_few(v.pattern, v.a);
 }
 
 // The small-result kernel wants both operands stored with k as the row index: a transposed A (K x M) and a
@@ -493,10 +501,16 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
 {
     const int transA = a_lay == kMnContig, transB = b_lay == kKContig;
     const Tuned *t = use_table ? find_tuned(1, transA, transB, M, N, K, split) : nullptr;
-    if (!t && vector_shape(M, N, K)) {
+    // With 5 .. 8 vectors the widening and the multiply-adds of the streaming kernels occupy the vector units (2.6 - 2.9 TB/s
+    // on 8 x 8192 x 8192); where a workspace lets the 64 x 64 tiles split K they stream faster (26 - 34 us against 35 - 46), so
+    // such calls stay with the tiles.  Without a workspace, and up to 4 vectors either way, the streaming kernels win (plain
+    // 8 x 8192 x 8192 46 - 81 us against 78 - 140; 4 x 8192 x 8192 36 - 53 against 78 - 411).
+    const bool tiles_split = split && (M > 4 && N > 4) && (K >= 3072 || M < 64 || N < 64) && splitk_slices(M, N, K, 64) > 1;
+    if (!t && vector_call_bf16(transA, transB, M, N, K, A, lda, B, ldb) && (vector_shape(M, N, K) || !tiles_split)) {
         const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
         p->cfg = kBf16_Vector;
-        p->slices = split ? vector_slices(v.pattern, v.a.len, K, 64) : 1;
+        p->slices = split ? vector_slices(v.pattern, v.a.len, K, 64, v.a.nvec > 1 ? 16 : 4) : 1;
+        if (p->slices > 1 && (int64_t)p->slices * M * N * 4 > kMaxWorkspace) p->slices = (int)(kMaxWorkspace / (M * N * 4)) < 2 ? 1 : (int)(kMaxWorkspace / (M * N * 4));
         p->mode = 0;
         return ceil_div(M > N ? M : N, 4) * p->slices >= ((int64_t)1 << 31) ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_OK;
     }
@@ -574,7 +588,7 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     else p->cfg = kBf16_64x64;
     if (p->cfg == kBf16_Vector) {       // a row of the selection table
         p->mode = 0;
-        return vector_shape(M, N, K) ? FSRGEMM_OK : FSRGEMM_ERR_INVALID_ARG;
+        return vector_call_bf16(transA, transB, M, N, K, A, lda, B, ldb) ? FSRGEMM_OK : FSRGEMM_ERR_INVALID_ARG;
     }
     return mode_bf16(p->cfg, p->slices, M, N, K, A, lda, B, ldb, &p->mode);
 }
@@ -721,7 +735,11 @@ int run_bf16(const Plan &p, int a_lay, int b_lay, int64_t M, int64_t N, int64_t 
     }
     if (p.cfg == kBf16_Vector) {
         VecMap16 v = vector_map16(a_lay == kMnContig, b_lay == kKContig, M, N, K, A, lda, B, ldb, C, ldc);
-        if (split) v.a.y = ws, v.a.incy = 1, v.a.k_slices = p.slices, v.a.slice_stride = v.a.len;
+        if (split) {        // a slice of the workspace is an M x N matrix with rows of N
+            v.a.y = ws, v.a.k_slices = p.slices, v.a.slice_stride = M * N;
+            if (N <= M) v.a.incy = N, v.a.ldy = 1;
+            else v.a.incy = 1, v.a.ldy = N;
+        }
         e = launch_gemv_bf16(v.pattern, v.a, s);
     } else {
         GemmArgs a = pack(M, N, K, A, lda, B, ldb, split ? ws : C, split ? N : ldc);
@@ -967,7 +985,7 @@ int gemm_bf16_cfg(int tile, int k_slices, int transA, int transB, int64_t M, int
     Plan p = {tile, 0, k_slices};
     if (tile == kBf16_Vector) {
         if (M == 0 || N == 0) return FSRGEMM_OK;
-        if (!vector_shape(M, N, K) || ceil_div(M > N ? M : N, 4) * k_slices >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
+        if (!vector_call_bf16(transA, transB, M, N, K, A, lda, B, ldb) || ceil_div(M > N ? M : N, 4) * k_slices >= ((int64_t)1 << 31)) return FSRGEMM_ERR_INVALID_ARG;
         return run_bf16(p, a_lay, b_lay, M, N, K, A, lda, B, ldb, C, ldc, static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
     }
     rc = mode_bf16(tile, k_slices, M, N, K, A, lda, B, ldb, &p.mode);
@@ -1047,7 +1065,7 @@ const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB, int64_t M, int64_
     if (plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, false, &p) != FSRGEMM_OK) return nullptr;
     if (p.cfg == kBf16_Vector) {
         const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
-        return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a));
+        return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a), v.a.nvec);
     }
     const char *first = bf16_kernel_name(p.cfg, p.mode, a_lay, b_lay);
     return p.band_dim == 0 ? first : two_band_name(p, first, bf16_kernel_name(p.cfg2, 0, a_lay, b_lay));
@@ -1085,9 +1103,9 @@ const char *fsrgemm_kernel_for_bf16_cfg(int tile, int transA, int transB, int64_
 {
     if (check_args(M, N, K, A, lda, transA ? M : K, B, ldb, transB ? K : N, C, ldc) != FSRGEMM_OK) return nullptr;
     if (tile == kBf16_Vector) {
-        if (!vector_shape(M, N, K)) return nullptr;
+        if (!vector_call_bf16(transA, transB, M, N, K, A, lda, B, ldb)) return nullptr;
         const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
-        return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a));
+        return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a), v.a.nvec);
     }
     if (tile < 0 || tile >= kBf16_MainMore + kBf16MainShapes - 1) return nullptr;
     const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;

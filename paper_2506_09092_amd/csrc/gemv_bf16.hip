@@ -9,6 +9,17 @@
 //          output columns (one 128-byte line of every matrix row): 8 lanes cover the line, 32 groups of lanes
 //          take every 32nd row, eight rows in flight each, and the 32 partial sums per column are added in
 //          group order through LDS.
+// A few vectors on one side (2 .. 8 rows of A or columns of B, kMaxFewVectors) go the way they go in fp32: the
+// workgroup stages its K range of the vectors through LDS (as bf16, any strides on the global side, zeros behind
+// the last vector and behind the K range), chunk by chunk in two buffers with one barrier per chunk; the registers of
+// the matrix pieces are a ring (a register's next content is requested as soon as its current content has been
+// used); no branch in the loops, and no value replaced right behind its load: pieces outside the K range or the
+// matrix are read from a valid place and replaced by zeros where they are used.
+//   rows:  a wavefront takes four matrix rows, two pieces of each in flight per lane (1024 k per chunk).
+//   cols:  64 columns, 32 groups of lanes, eight rows in flight each (256 k per chunk); the vectors' elements of
+//          a matrix row sit side by side in LDS; the sums of a wavefront's eight groups are added by lane exchange,
+//          the four wavefronts' through LDS, in fixed order.
+// These need a matrix of aligned 16-byte pieces and, in the cols pattern, at least eight columns (gemv_bf16_takes_few).
 // Values are widened to fp32 (exact), products and sums are fp32 FMAs.  With k_slices > 1 the K range is cut
 // into slices that write partial results behind g.y (a workspace), added afterwards by the split-K reduction
 // kernel.  All sums have a fixed order: results repeat bit for bit.
@@ -155,23 +166,257 @@ __global__ __launch_bounds__(kThreads) void gemv_cols_bf16_kernel(VecArgs16 g)
     }
 }
 
+// a 16-byte load from an address that is only element-aligned (allowed on this target)
+typedef u16x8 u16x8_elem_aligned __attribute__((aligned(2)));
+__device__ __forceinline__ u16x8 load8_any(const uint16_t *p) { return *reinterpret_cast<const u16x8_elem_aligned *>(p); }
+
+// The K range [kc, kc + KC) of the R vectors on its way into LDS, in two steps so that the loads' latency passes
+// behind other work: fetch_vectors reads a lane's share into registers, store_vectors writes it: element (k, r) to
+// xs[k * R + r] (K_MAJOR) or xs[r * KC + k].  Lanes walk k fastest when the vectors are contiguous along k, r
+// fastest otherwise.  Every load is issued, from the last valid element where its own lies outside (behind vector
+// g.nvec - 1, from k1 on), and store_vectors writes zeros for those.  k1 >= 1.
+template <int R, int KC>
+__device__ __forceinline__ void fetch_vectors(uint16_t (&xr)[R * KC / kThreads], const VecArgs16 &g, int kc, int k1)
+{
+    const int tid = threadIdx.x;
+    const uint16_t *__restrict__ x = g.x;
+    if (g.incx == 1) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int q = 0; q < KC / kThreads; ++q)
+                xr[r * (KC / kThreads) + q] = x[(int64_t)min(kc + tid + q * kThreads, k1 - 1) + (int64_t)min(r, g.nvec - 1) * g.ldx];
+    } else {
+        const uint16_t *__restrict__ xl = x + (int64_t)min(tid % R, g.nvec - 1) * g.ldx;    // (kThreads is a multiple of R)
+#pragma unroll
+        for (int q = 0; q < R * KC / kThreads; ++q) xr[q] = xl[(int64_t)min(kc + tid / R + q * (kThreads / R), k1 - 1) * g.incx];
+    }
+}
+template <int R, int KC, bool K_MAJOR>
+__device__ __forceinline__ void store_vectors(uint16_t *__restrict__ xs, const uint16_t (&xr)[R * KC / kThreads], const VecArgs16 &g, int kc, int k1)
+{
+    const int tid = threadIdx.x;
+    if (g.incx == 1) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int q = 0; q < KC / kThreads; ++q) {
+                const int kl = tid + q * kThreads;
+                xs[K_MAJOR ? kl * R + r : r * KC + kl] = r < g.nvec && kc + kl < k1 ? xr[r * (KC / kThreads) + q] : (uint16_t)0;
+            }
+    } else {
+        const int r = tid % R;
+#pragma unroll
+        for (int q = 0; q < R * KC / kThreads; ++q) {
+            const int kl = tid / R + q * (kThreads / R);
+            xs[K_MAJOR ? kl * R + r : r * KC + kl] = r < g.nvec && kc + kl < k1 ? xr[q] : (uint16_t)0;
+        }
+    }
+}
+
+// rows pattern, R vectors (g.nvec <= R): y_r[i] = sum_k Mat[i][k] x_r[k]; requires gemv_bf16_takes_few(kVecRows, g)
+template <int R>
+__global__ __launch_bounds__(kThreads) void gemv_rows_bf16_few_kernel(VecArgs16 g)
+{
+    constexpr int RW = 4, KC = 1024;                          // matrix rows per wavefront, k per chunk
+    __shared__ __attribute__((aligned(16))) uint16_t xs[2][R * KC];
+    const int groups = (g.len + 4 * RW - 1) / (4 * RW);
+    const int slice = (int)blockIdx.x / groups;
+    const int row0 = ((int)blockIdx.x - slice * groups) * (4 * RW) + ((int)threadIdx.x >> 6) * RW;
+    const int lane = threadIdx.x & 63;
+    const int per = (((g.K + g.k_slices - 1) / g.k_slices) + 7) & ~7;     // slices start at multiples of 8: pieces stay aligned
+    const int k0 = (int)min((int64_t)slice * per, (int64_t)g.K), k1 = (int)min((int64_t)k0 + per, (int64_t)g.K);
+    const int k8 = k0 + ((k1 - k0) & ~7);                     // whole pieces up to here, up to seven elements behind
+    const uint16_t *__restrict__ rowp[RW];
+#pragma unroll
+    for (int i = 0; i < RW; ++i) rowp[i] = g.mat + (int64_t)min(row0 + i, g.len - 1) * g.ld;      // rows behind the last repeat it
+    float acc[RW][R];
+#pragma unroll
+    for (int i = 0; i < RW; ++i)
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[i][r] = 0.f;
+    u16x8 m[RW][2];
+    uint16_t xr[R * KC / kThreads];
+    if (k0 < k8) {
+        // pieces u of chunk kc, two per row and lane; in place of a piece that lies behind the whole pieces the slice's
+        // first piece is read, and zeros are used
+        auto fetch_rows = [&](int kc, int u) {
+            const int k = kc + 8 * lane + 512 * u;
+            const int kk = k < k8 ? k : k0;
+#pragma unroll
+            for (int i = 0; i < RW; ++i) m[i][u] = load8(rowp[i] + kk);
+        };
+        fetch_rows(k0, 0);
+        fetch_rows(k0, 1);
+        fetch_vectors<R, KC>(xr, g, k0, k8);
+        store_vectors<R, KC, false>(xs[0], xr, g, k0, k8);
+        __syncthreads();
+        int buf = 0;
+        for (int kc = k0; kc < k8; kc += KC, buf ^= 1) {
+            fetch_vectors<R, KC>(xr, g, kc + KC, k8);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const bool in = kc + 8 * lane + 512 * u < k8;
+                float mm[RW][8];
+#pragma unroll
+                for (int i = 0; i < RW; ++i)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) mm[i][e] = in ? widen(m[i][u][e]) : 0.f;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const u16x8 v = *reinterpret_cast<const u16x8 *>(&xs[buf][r * KC + 8 * lane + 512 * u]);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float ve = widen(v[e]);
+#pragma unroll
+                        for (int i = 0; i < RW; ++i) acc[i][r] = __builtin_fmaf(mm[i][e], ve, acc[i][r]);
+                    }
+                }
+                fetch_rows(kc + KC, u);
+            }
+            store_vectors<R, KC, false>(xs[buf ^ 1], xr, g, kc + KC, k8);
+            __syncthreads();
+        }
+    }
+    if (lane < k1 - k8) {                                     // the up to seven elements behind the last whole piece
+        const int k = k8 + lane;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float v = r < g.nvec ? widen(g.x[(int64_t)k * g.incx + (int64_t)r * g.ldx]) : 0.f;
+#pragma unroll
+            for (int i = 0; i < RW; ++i) acc[i][r] = __builtin_fmaf(widen(rowp[i][k]), v, acc[i][r]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RW; ++i)
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float s = acc[i][r];
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+            if (lane == 0 && row0 + i < g.len && r < g.nvec)
+                g.y[(int64_t)slice * g.slice_stride + (int64_t)(row0 + i) * g.incy + (int64_t)r * g.ldy] = s;
+        }
+}
+
+// cols pattern, R vectors (g.nvec <= R): y_r[j] = sum_k x_r[k] Mat[k][j]; requires gemv_bf16_takes_few(kVecCols, g)
+template <int R>
+__global__ __launch_bounds__(kThreads) void gemv_cols_bf16_few_kernel(VecArgs16 g)
+{
+    constexpr int CW = 64, LANES = 8, KG = kThreads / LANES, UNROLL = 8, KC = KG * UNROLL;
+    __shared__ __attribute__((aligned(16))) uint16_t xs[2][KC * R];
+    __shared__ float red[kThreads / 64][R][CW];
+    const int groups = (g.len + CW - 1) / CW;
+    const int slice = (int)blockIdx.x / groups;
+    const int j0 = ((int)blockIdx.x - slice * groups) * CW;
+    const int tid = threadIdx.x, cl = tid % LANES, kg = tid / LANES;
+    const int per = (g.K + g.k_slices - 1) / g.k_slices;
+    const int k0 = (int)min((int64_t)slice * per, (int64_t)g.K), k1 = (int)min((int64_t)k0 + per, (int64_t)g.K);
+    // a lane whose eight columns straddle or lie behind the last one takes the matrix's last eight instead: it repeats
+    // sums that other lanes of its group form from the same values in the same order
+    const int j = min(j0 + cl * 8, g.len - 8);
+    const uint16_t *__restrict__ col = g.mat + j;
+    float acc[R][8];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
+    u16x8 m[UNROLL];
+    uint16_t xr[R * KC / kThreads];
+    if (k0 < k1) {
+        // piece u of chunk kc: matrix row kc + kg + 32 u; behind the K range the range's last row is read, and zeros are used
+        auto fetch_cols = [&](int kc, int u) { m[u] = load8_any(col + (int64_t)min(kc + kg + u * KG, k1 - 1) * g.ld); };
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) fetch_cols(k0, u);
+        fetch_vectors<R, KC>(xr, g, k0, k1);
+        store_vectors<R, KC, true>(xs[0], xr, g, k0, k1);
+        __syncthreads();
+        int buf = 0;
+        for (int kc = k0; kc < k1; kc += KC, buf ^= 1) {
+            fetch_vectors<R, KC>(xr, g, kc + KC, k1);
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const uint16_t *xk = &xs[buf][(kg + u * KG) * R];
+                typedef uint16_t u16xR __attribute__((ext_vector_type(R)));
+                const u16xR xv = *reinterpret_cast<const u16xR *>(xk);       // (R elements of 2 bytes at a multiple of 2 R bytes)
+                float v[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) v[r] = widen(xv[r]);
+                const bool in = kc + kg + u * KG < k1;
+                float mm[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) mm[e] = in ? widen(m[u][e]) : 0.f;
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[r][e] = __builtin_fmaf(v[r], mm[e], acc[r][e]);
+                fetch_cols(kc + KC, u);
+            }
+            store_vectors<R, KC, true>(xs[buf ^ 1], xr, g, kc + KC, k1);
+            __syncthreads();
+        }
+    }
+    // the eight groups of a wavefront by lane exchange (8, 16, 32 lanes apart), then the four wavefronts in order
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float s = acc[r][e];
+            s += __shfl_xor(s, 8, 64);
+            s += __shfl_xor(s, 16, 64);
+            s += __shfl_xor(s, 32, 64);
+            const int c = j + e - j0;                         // (negative where the last eight columns begin in the group before)
+            if ((tid & 63) < LANES && c >= 0) red[tid >> 6][r][c] = s;
+        }
+    __syncthreads();
+    for (int o = tid; o < R * CW; o += kThreads) {
+        const int r = o / CW, c = o % CW;
+        if (r < g.nvec && j0 + c < g.len) {
+            float s = red[0][r][c];
+            for (int q = 1; q < kThreads / 64; ++q) s += red[q][r][c];
+            g.y[(int64_t)slice * g.slice_stride + (int64_t)(j0 + c) * g.incy + (int64_t)r * g.ldy] = s;
+        }
+    }
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <int R>
+void launch_few(int pattern, const VecArgs16 &a, hipStream_t s)
+{
+    if (pattern == kVecRows) hipLaunchKernelGGL(gemv_rows_bf16_few_kernel<R>, dim3((unsigned)((a.len + 15) / 16 * a.k_slices)), dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL(gemv_cols_bf16_few_kernel<R>, dim3((unsigned)((a.len + 63) / 64 * a.k_slices)), dim3(kThreads), 0, s, a);
+}
 
 }  // namespace
 
 // as a profiler trace prints the kernels
-const char *gemv_bf16_kernel_name(int pattern, bool vec)
+const char *gemv_bf16_kernel_name(int pattern, bool vec, int nvec)
 {
+    if (nvec > 1) {
+        if (pattern == kVecRows) return nvec <= 2 ? "gemv_rows_bf16_few_kernel<2>" : nvec <= 4 ? "gemv_rows_bf16_few_kernel<4>" : "gemv_rows_bf16_few_kernel<8>";
+        return nvec <= 2 ? "gemv_cols_bf16_few_kernel<2>" : nvec <= 4 ? "gemv_cols_bf16_few_kernel<4>" : "gemv_cols_bf16_few_kernel<8>";
+    }
     if (pattern == kVecRows) return vec ? "gemv_rows_bf16_kernel<true>" : "gemv_rows_bf16_kernel<false>";
     return vec ? "gemv_cols_bf16_kernel<true>" : "gemv_cols_bf16_kernel<false>";
 }
 
 bool gemv_bf16_takes_vectors(const VecArgs16 &a) { return aligned16(a.mat) && a.ld % 8 == 0; }
+// the kernels for several vectors: a matrix of aligned pieces, and at least one whole piece of columns
+bool gemv_bf16_takes_few(int pattern, const VecArgs16 &a) { return gemv_bf16_takes_vectors(a) && (pattern == kVecRows || a.len >= 8); }
 
-// len >= 1, K >= 1, k_slices >= 1; the number of workgroups must fit a grid (checked by the caller)
+// len >= 1, K >= 1, k_slices >= 1; the number of workgroups must fit a grid (checked by the caller); more than one
+// vector only on a matrix of aligned pieces
 hipError_t launch_gemv_bf16(int pattern, VecArgs16 a, hipStream_t s)
 {
     const bool vec = gemv_bf16_takes_vectors(a);
+    if (a.nvec < 1 || a.nvec > kMaxFewVectors || (a.nvec > 1 && !gemv_bf16_takes_few(pattern, a))) return hipErrorInvalidValue;
+    if (a.nvec > 1) {
+        if (a.nvec <= 2) launch_few<2>(pattern, a, s);
+        else if (a.nvec <= 4) launch_few<4>(pattern, a, s);
+        else launch_few<8>(pattern, a, s);
+        return hipGetLastError();
+    }
     a.xvec = a.incx == 1 && aligned16(a.x);
     if (pattern == kVecRows) {
         const dim3 grid((unsigned)((a.len + 3) / 4 * a.k_slices));

@@ -1157,8 +1157,8 @@ def test_bf16_vector_shapes(gpu, M, N, K):
         refi, _ = oracle.gemm(Ai, Bi)
         for ta, tb in [(0, 0)] + LAYOUTS:
             assert np.array_equal(run_bf16_ws(gpu, ta, tb, Ai, Bi).astype(np.float64), refi)
-    with pytest.raises(gpu.FsrGemmError):
-        run_cfg(gpu, "bf16", 4, 1, 0, 1, inputs.bf16_small_ints(4, 72, 2, 64), inputs.bf16_small_ints(4, 73, 64, 2))
+    with pytest.raises(gpu.FsrGemmError):       # nine rows and nine columns: no vector side
+        run_cfg(gpu, "bf16", 4, 1, 0, 1, inputs.bf16_small_ints(4, 72, 9, 64), inputs.bf16_small_ints(4, 73, 64, 9))
 
 
 def test_f32_vector_every_slice_count(gpu):
@@ -1222,6 +1222,80 @@ def test_f32_few_vectors_every_count_and_slice_count(gpu):
                 assert oracle.componentwise_error(run_cfg(gpu, "f32", 3, slices, ta, tb, A, B, **kw), ref, S) <= TOL_F32
                 kw = dict(lda=_ceil4(332 if ta else K), ldb=_ceil4(K if tb else nvec), repeat=2)
                 assert oracle.componentwise_error(run_cfg(gpu, "f32", 3, slices, ta, tb, B.T.copy(), A.T.copy(), **kw), ref.T, S.T) <= TOL_F32
+
+
+def _ceil8(n):
+    return n + (-n) % 8
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 1000, 777), (3, 520, 2050), (2, 64, 9), (5, 40, 1300), (1000, 8, 777), (516, 3, 2050),
+                                   (7, 4100, 5000), (4, 8, 4096), (8, 8, 600), (6, 2049, 515), (2050, 5, 1027), (2, 8, 1),
+                                   (8, 63, 3), (3, 7, 50)])
+def test_bf16_few_vector_shapes(gpu, M, N, K):
+    A = inputs.bf16_normal_scaled(19, 1, M, K, 1 / math.sqrt(K))
+    B = inputs.bf16_normal_scaled(19, 2, K, N, 1 / math.sqrt(K))
+    ref, S = oracle.gemm(A, B)
+    Ai, Bi = inputs.bf16_small_ints(4, 74, M, K), inputs.bf16_small_ints(4, 75, K, N)
+    refi, _ = oracle.gemm(Ai, Bi)
+    for ta, tb in [(0, 1), (0, 0), (1, 0), (1, 1)]:
+        lda, ldb = _ceil8(M if ta else K), _ceil8(K if tb else N)            # rows of whole 16-byte pieces
+        name = gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N)
+        say("bf16 few vectors %dx%dx%d storage %d%d -> %s" % (M, N, K, ta, tb, name))
+        cols = (ta if N <= M else not tb)                    # the streamed operand walked along its columns needs eight of them
+        assert ("few_kernel" in name) == (not cols or max(M, N) >= 8), name
+        got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 3, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= 1e-5
+        got = run_bf16_ws(gpu, ta, tb, A, B, lda=lda + 8, ldb=ldb + 16, repeat=2)            # with the workspace the library asks for
+        assert oracle.componentwise_error(got, ref, S) <= 1e-5
+        got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda + 1, ldb=ldb + 3, offset=1, repeat=2)   # 2-byte aligned only: the tile kernels
+        assert oracle.componentwise_error(got, ref, S) <= 1e-5
+        for slices in (1, 2, 7, 64):
+            if slices <= -(-K // 64) and "few_kernel" in name:
+                got = run_cfg(gpu, "bf16", 4, slices, ta, tb, A, B, lda=lda, ldb=ldb, repeat=2)
+                assert oracle.componentwise_error(got, ref, S) <= 1e-5
+        if K <= 4097:
+            assert np.array_equal(run_bf16_ws(gpu, ta, tb, Ai, Bi, lda=lda, ldb=ldb).astype(np.float64), refi)
+            assert np.array_equal(run_bf16_ex(gpu, ta, tb, Ai, Bi, lda=lda, ldb=ldb).astype(np.float64), refi)
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 300, 700), (300, 5, 700), (3, 136, 515)])
+def test_bf16_few_vectors_special_values(gpu, M, N, K):
+    # infinities and NaNs in the streamed matrix, among them its last row and column (which the kernels read again in
+    # place of pieces outside the matrix): the class of every entry must match the oracle's
+    Ai, Bi = inputs.bf16_small_ints(4, 76, M, K), inputs.bf16_small_ints(4, 77, K, N)
+    mat = (Bi if M <= N else Ai).copy()
+    rng = np.random.default_rng(5)
+    for pattern in (0x7F80, 0xFF80, 0x7FC0):                # +inf, -inf, NaN
+        mat[rng.integers(0, mat.shape[0], 5), rng.integers(0, mat.shape[1], 5)] = pattern
+    mat[-1, -1], mat[-1, 0], mat[0, -1] = 0x7F80, 0x7FC0, 0xFF80
+    A, B = (Ai, mat) if M <= N else (mat, Bi)
+    ref, _ = oracle.gemm(A, B)
+    assert np.isnan(ref).any() and np.isfinite(ref).any()
+    fin = np.isfinite(ref)
+    for ta, tb in [(0, 1), (0, 0), (1, 0), (1, 1)]:
+        kw = dict(lda=_ceil8(M if ta else K), ldb=_ceil8(K if tb else N))
+        for slices in (1, 3):
+            say("bf16 few vectors, specials, %dx%dx%d storage %d%d, %d slices" % (M, N, K, ta, tb, slices))
+            got = run_cfg(gpu, "bf16", 4, slices, ta, tb, A, B, **kw)
+            assert _same_class(got, ref)
+            assert np.array_equal(got[fin].astype(np.float64), ref[fin])          # small integers: exact
+        assert _same_class(run_bf16_ex(gpu, ta, tb, A, B, **kw), ref)
+
+
+def test_bf16_few_vectors_every_count(gpu):
+    # 2 .. 8 vectors on either side through the vector candidate, 1 and 3 K slices, every storage order
+    K = 1500
+    for nvec in range(2, 9):
+        A = inputs.bf16_normal_scaled(19, 10 + nvec, nvec, K, 1 / math.sqrt(K))
+        B = inputs.bf16_normal_scaled(19, 20 + nvec, K, 328, 1 / math.sqrt(K))
+        ref, S = oracle.gemm(A, B)
+        for ta, tb in [(0, 1), (0, 0), (1, 0), (1, 1)]:
+            for slices in (1, 3):
+                say("bf16 vector candidate, %d vectors, %d slices, storage %d%d" % (nvec, slices, ta, tb))
+                kw = dict(lda=_ceil8(nvec if ta else K), ldb=_ceil8(K if tb else 328), repeat=2)
+                assert oracle.componentwise_error(run_cfg(gpu, "bf16", 4, slices, ta, tb, A, B, **kw), ref, S) <= 1e-5
+                kw = dict(lda=_ceil8(328 if ta else K), ldb=_ceil8(K if tb else nvec), repeat=2)
+                assert oracle.componentwise_error(run_cfg(gpu, "bf16", 4, slices, ta, tb, B.T.copy(), A.T.copy(), **kw), ref.T, S.T) <= 1e-5
 
 
 @pytest.mark.parametrize("M,N,K", [(8, 300, 700), (300, 5, 700), (3, 132, 515)])
