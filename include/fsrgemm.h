@@ -196,14 +196,16 @@ int gemm_bf16_ws(int transA, int transB,
  *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64, 4 = the streaming
  *               kernels for M == 1 or N == 1 with K > 0, and for M <= 8 or N <= 8 where the operand on the other side
  *               (B for M < N, else A) is 16-byte aligned with a leading dimension that is a multiple of 8 and, if it is
- *               stored contiguous along n (m), N (M) >= 8; 5..10 = the direct-to-LDS kernel with tiles 192 x 256,
+ *               stored contiguous along n (m), N (M) >= 8; with transA == 0, transB != 0, K a multiple of 8 and both
+ *               operands 16-byte aligned with leading dimensions that are multiples of 8 also for M <= 16 or N <= 16 (a
+ *               streaming kernel on the matrix cores); 5..10 = the direct-to-LDS kernel with tiles 192 x 256,
  *               128 x 256, 256 x 192, 192 x 192, 256 x 128, 128 x 128 (fsrgemm_tile_count_bf16() = 11).
  *   k_slices: 1 = K in one piece; 2..64 = split along K as gemm_f32_ws does, which needs a workspace of
  *         k_slices * M * N * 4 bytes (4-byte aligned, at most 16 MiB) and k_slices <= ceil(K / 16) (fp32) or
  *         ceil(K / 64) (bf16).
  * A candidate that cannot run this problem is FSRGEMM_ERR_INVALID_ARG and launches nothing: a tile or slice
  * count out of range, a split without a fitting workspace, fp32 candidate 3 or bf16 candidate 4 on a product
- * without 1 .. 8 rows or columns as described above,
+ * without 1 .. 8 (bf16, where described above: 16) rows or columns on one side,
  * fp32 candidate 4 on a result that is too large,
  * fp32 tiles 5..16 where their kernel's conditions fail (M, N at least one tile, K >= 32 and a
  * multiple of 4, 16-byte aligned operands with leading dimensions that are multiples of 4 and below 2^24;

@@ -318,9 +318,9 @@ bool vector_call_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, co
 bool vector_call_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb)
 {
     if (vector_shape(M, N, K)) return true;
-    if (M < 1 || N < 1 || K < 1 || K > ((int64_t)1 << 30) || (M > kMaxFewVectors && N > kMaxFewVectors)) return false;
+    if (M < 1 || N < 1 || K < 1 || K > ((int64_t)1 << 30) || (M > kMaxMfmaVectors && N > kMaxMfmaVectors)) return false;
     const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
-    return gemv_bf16_takes_few(v.pattern, v.a);
+    return gemv_bf16_takes_mfma(v.pattern, v.a) || (v.a.nvec <= kMaxFewVectors && gemv_bf16_takes_few(v.pattern, v.a));
 }
 
 // The small-result kernel wants both operands stored with k as the row index: a transposed A (K x M) and a
@@ -505,8 +505,17 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     // on 8 x 8192 x 8192); where a workspace lets the 64 x 64 tiles split K they stream faster (26 - 34 us against 35 - 46), so
     // such calls stay with the tiles.  Without a workspace, and up to 4 vectors either way, the streaming kernels win (plain
     // 8 x 8192 x 8192 46 - 81 us against 78 - 140; 4 x 8192 x 8192 36 - 53 against 78 - 411).
-    const bool tiles_split = split && (M > 4 && N > 4) && (K >= 3072 || M < 64 || N < 64) && splitk_slices(M, N, K, 64) > 1;
-    if (!t && vector_call_bf16(transA, transB, M, N, K, A, lda, B, ldb) && (vector_shape(M, N, K) || !tiles_split)) {
+    // The matrix-core kernel (up to 16 vectors contiguous along k against a matrix contiguous along k) runs 16 x 8192 x 8192
+    // in 33 us without a workspace against the tiles' 79, 8 x ... in 27.5, 2 x ... in 23; with a workspace the tiles' split still
+    // wins on long matrices with more than 8 vectors (16 x 8192 x 8192 26 us, 16 x 28672 x 8192 100 - 113 against 135), not on
+    // short ones (12 x 1024 x 16384: 12 us in 4 slices against 20).
+    const bool tiles_can_split = split && (K >= 3072 || M < 64 || N < 64) && splitk_slices(M, N, K, 64) > 1;
+    bool vector = !t && vector_call_bf16(transA, transB, M, N, K, A, lda, B, ldb);
+    if (vector && !vector_shape(M, N, K) && tiles_can_split) {
+        const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
+        vector = gemv_bf16_takes_mfma(v.pattern, v.a) ? v.a.nvec <= 8 || v.a.len < 8192 : v.a.nvec <= 4;
+    }
+    if (vector) {
         const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
         p->cfg = kBf16_Vector;
         p->slices = split ? vector_slices(v.pattern, v.a.len, K, 64, v.a.nvec > 1 ? 16 : 4) : 1;
@@ -1065,7 +1074,7 @@ const char *fsrgemm_kernel_for_bf16_ex(int transA, int transB, int64_t M, int64_
     if (plan_bf16(a_lay, b_lay, M, N, K, A, lda, B, ldb, false, &p) != FSRGEMM_OK) return nullptr;
     if (p.cfg == kBf16_Vector) {
         const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
-        return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a), v.a.nvec);
+        return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a), v.a.nvec, gemv_bf16_takes_mfma(v.pattern, v.a));
     }
     const char *first = bf16_kernel_name(p.cfg, p.mode, a_lay, b_lay);
     return p.band_dim == 0 ? first : two_band_name(p, first, bf16_kernel_name(p.cfg2, 0, a_lay, b_lay));
@@ -1105,7 +1114,7 @@ const char *fsrgemm_kernel_for_bf16_cfg(int tile, int transA, int transB, int64_
     if (tile == kBf16_Vector) {
         if (!vector_call_bf16(transA, transB, M, N, K, A, lda, B, ldb)) return nullptr;
         const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, ldc);
-        return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a), v.a.nvec);
+        return gemv_bf16_kernel_name(v.pattern, gemv_bf16_takes_vectors(v.a), v.a.nvec, gemv_bf16_takes_mfma(v.pattern, v.a));
     }
     if (tile < 0 || tile >= kBf16_MainMore + kBf16MainShapes - 1) return nullptr;
     const int a_lay = transA ? kMnContig : kKContig, b_lay = transB ? kKContig : kMnContig;

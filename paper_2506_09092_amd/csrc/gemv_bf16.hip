@@ -379,6 +379,72 @@ __global__ __launch_bounds__(kThreads) void gemv_cols_bf16_few_kernel(VecArgs16 
     }
 }
 
+// rows pattern on the matrix cores, up to 16 vectors that are contiguous along k (kMaxMfmaVectors; the storage gemm_bf16
+// takes: a few rows of a row-major A against a column-major B, or a row-major A against a few columns of such a B):
+// y_r[i] = sum_k Mat[i][k] x_r[k] as D = X . Mat^T in 16 x 16 x 32 steps, so that the arithmetic no longer occupies the
+// vector units.  Both fragments of v_mfma_f32_16x16x32_bf16 are 16-byte pieces of memory as it lies: lane l holds the
+// 8 values k = 8 (l / 16) .. + 7 of row l % 16 -- of the vectors for the first operand, of the matrix block for the
+// second -- and register r of the result holds vector 4 (l / 16) + r against matrix row l % 16.  A workgroup takes 16
+// matrix rows (32 or 64 rows per workgroup, every vector fragment serving several matrix fragments, and 16 steps in
+// flight were tried: no faster); its four wavefronts take a quarter of the K range each, in blocks of 256 k = eight steps whose loads form
+// a ring as above; their four partial blocks are added through LDS in wavefront order.
+// Pieces outside the quarter are read from its first piece and both fragments replaced by zeros where they are used,
+// vectors behind the last and matrix rows behind the last repeat the last.  Requires gemv_bf16_takes_mfma(g).
+__global__ __launch_bounds__(kThreads) void gemv_rows_bf16_mfma_kernel(VecArgs16 g)
+{
+    constexpr int STEPS = 8, BLOCK = 32 * STEPS;
+    __shared__ float red[kThreads / 64][16][17];
+    const int groups = (g.len + 15) / 16;
+    const int slice = (int)blockIdx.x / groups;
+    const int row0 = ((int)blockIdx.x - slice * groups) * 16;
+    const int lane = threadIdx.x & 63, l16 = lane & 15, lq = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);      // (a scalar: the K loop below is uniform)
+    const int per = (((g.K + g.k_slices - 1) / g.k_slices) + 7) & ~7;     // slices start at multiples of 8: pieces stay aligned
+    const int k0 = (int)min((int64_t)slice * per, (int64_t)g.K), k1 = (int)min((int64_t)k0 + per, (int64_t)g.K);
+    const uint16_t *__restrict__ mp = g.mat + (int64_t)min(row0 + l16, g.len - 1) * g.ld;
+    const uint16_t *__restrict__ xp = g.x + (int64_t)min(l16, g.nvec - 1) * g.ldx;
+    const bool vec_in = l16 < g.nvec;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    u16x8 m[STEPS], x[STEPS];
+    // the wavefront's quarter of the K range, in whole blocks
+    const int quarter = ((k1 - k0 + 4 * BLOCK - 1) / (4 * BLOCK)) * BLOCK;
+    const int w0 = k0 + wave * quarter, w1 = min(k1, w0 + quarter);
+    if (w0 < w1) {
+        // step u of the block that begins at kb: the lane's pieces at k = kb + 32 u + 8 (l / 16)
+        auto fetch = [&](int kb, int u) {
+            const int k = kb + 32 * u + 8 * lq;
+            const int kk = k < w1 ? k : w0;
+            m[u] = load8(mp + kk);
+            x[u] = load8(xp + kk);
+            // the loads stay here, between the step before and the step behind: without the fence the compiler moves them
+            // down to their use, and without the tie to the sums it moves all the steps ahead of all the loads
+            asm volatile("" : "+v"(acc) : : "memory");
+        };
+#pragma unroll
+        for (int u = 0; u < STEPS; ++u) fetch(w0, u);
+        for (int kb = w0; kb < w1; kb += BLOCK) {
+#pragma unroll
+            for (int u = 0; u < STEPS; ++u) {
+                const bool in = kb + 32 * u + 8 * lq < w1;
+                u16x8 mm, xx;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) mm[e] = in ? m[u][e] : (uint16_t)0, xx[e] = in && vec_in ? x[u][e] : (uint16_t)0;
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xx), __builtin_bit_cast(bf16x8, mm), acc, 0, 0, 0);
+                fetch(kb + BLOCK, u);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wave][4 * lq + r][l16] = acc[r];
+    __syncthreads();
+    const int v = threadIdx.x >> 4, n = threadIdx.x & 15;
+    if (v < g.nvec && row0 + n < g.len) {
+        float s = red[0][v][n];
+        for (int q = 1; q < kThreads / 64; ++q) s += red[q][v][n];
+        g.y[(int64_t)slice * g.slice_stride + (int64_t)(row0 + n) * g.incy + (int64_t)v * g.ldy] = s;
+    }
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 template <int R>
@@ -391,8 +457,9 @@ void launch_few(int pattern, const VecArgs16 &a, hipStream_t s)
 }  // namespace
 
 // as a profiler trace prints the kernels
-const char *gemv_bf16_kernel_name(int pattern, bool vec, int nvec)
+const char *gemv_bf16_kernel_name(int pattern, bool vec, int nvec, bool mfma)
 {
+    if (mfma) return "gemv_rows_bf16_mfma_kernel";
     if (nvec > 1) {
         if (pattern == kVecRows) return nvec <= 2 ? "gemv_rows_bf16_few_kernel<2>" : nvec <= 4 ? "gemv_rows_bf16_few_kernel<4>" : "gemv_rows_bf16_few_kernel<8>";
         return nvec <= 2 ? "gemv_cols_bf16_few_kernel<2>" : nvec <= 4 ? "gemv_cols_bf16_few_kernel<4>" : "gemv_cols_bf16_few_kernel<8>";
@@ -404,12 +471,23 @@ const char *gemv_bf16_kernel_name(int pattern, bool vec, int nvec)
 bool gemv_bf16_takes_vectors(const VecArgs16 &a) { return aligned16(a.mat) && a.ld % 8 == 0; }
 // the kernels for several vectors: a matrix of aligned pieces, and at least one whole piece of columns
 bool gemv_bf16_takes_few(int pattern, const VecArgs16 &a) { return gemv_bf16_takes_vectors(a) && (pattern == kVecRows || a.len >= 8); }
+// the matrix-core kernel: the rows pattern with 2 .. 16 vectors that are contiguous along k, everything in aligned
+// pieces, K whole pieces
+bool gemv_bf16_takes_mfma(int pattern, const VecArgs16 &a)
+{
+    return pattern == kVecRows && a.nvec >= 2 && a.nvec <= kMaxMfmaVectors && gemv_bf16_takes_vectors(a) && a.incx == 1 &&
+           aligned16(a.x) && a.ldx % 8 == 0 && a.K % 8 == 0;
+}
 
 // len >= 1, K >= 1, k_slices >= 1; the number of workgroups must fit a grid (checked by the caller); more than one
 // vector only on a matrix of aligned pieces
 hipError_t launch_gemv_bf16(int pattern, VecArgs16 a, hipStream_t s)
 {
     const bool vec = gemv_bf16_takes_vectors(a);
+    if (gemv_bf16_takes_mfma(pattern, a)) {
+        hipLaunchKernelGGL(gemv_rows_bf16_mfma_kernel, dim3((unsigned)((a.len + 15) / 16 * a.k_slices)), dim3(kThreads), 0, s, a);
+        return hipGetLastError();
+    }
     if (a.nvec < 1 || a.nvec > kMaxFewVectors || (a.nvec > 1 && !gemv_bf16_takes_few(pattern, a))) return hipErrorInvalidValue;
     if (a.nvec > 1) {
         if (a.nvec <= 2) launch_few<2>(pattern, a, s);

@@ -84,12 +84,14 @@ struct VecArgs16 {
     int k_slices;
     int64_t slice_stride;
     bool xvec;
-    int nvec;               // vectors x_r = x + r * ldx, y_r = y + r * ldy, r < nvec <= kMaxFewVectors
+    int nvec;               // vectors x_r = x + r * ldx, y_r = y + r * ldy, r < nvec <= kMaxFewVectors (kMaxMfmaVectors)
     int64_t ldx, ldy;
 };
-const char *gemv_bf16_kernel_name(int pattern, bool vec, int nvec = 1);
+constexpr int kMaxMfmaVectors = 16;
+const char *gemv_bf16_kernel_name(int pattern, bool vec, int nvec = 1, bool mfma = false);
 bool gemv_bf16_takes_vectors(const VecArgs16 &a);
 bool gemv_bf16_takes_few(int pattern, const VecArgs16 &a);      // whether a.nvec > 1 vectors can go through these kernels
+bool gemv_bf16_takes_mfma(int pattern, const VecArgs16 &a);     // whether the matrix-core kernel takes them (then it is the one launched)
 hipError_t launch_gemv_bf16(int pattern, VecArgs16 a, hipStream_t s);
 
 // fp32 products with M, N <= 16 and a long K, both operands stored with k as the row index (gemm_f32_skinny.hip):

@@ -176,14 +176,22 @@ def test_workspace_query_and_argument_checks():
     assert qb(0, 0, 1, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemv_cols_bf16_kernel<true>"
     assert qb(0, 1, 1, 8192, 8196, P, 8196, P, 8196, P, 8192) == "gemv_rows_bf16_kernel<false>"         # rows not 16-byte aligned
     assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 1, 8192, P, 8192, P, 8192, P, 1) == "gemv_rows_bf16_kernel<true>"
-    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 2, 8192, P, 8192, P, 8192, P, 2) == "gemv_rows_bf16_few_kernel<2>"
-    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 9, 8192, P, 8192, P, 8192, P, 9) is None              # nine columns: no vector side
+    # up to 16 vectors contiguous along k against a matrix contiguous along k, K whole 16-byte pieces: the matrix-core kernel
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 2, 8192, P, 8192, P, 8192, P, 2) == "gemv_rows_bf16_mfma_kernel"
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 16, 8192, P, 8192, P, 8192, P, 16) == "gemv_rows_bf16_mfma_kernel"
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 2, 8188, P, 8192, P, 8192, P, 2) == "gemv_rows_bf16_few_kernel<2>"      # K not whole pieces
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 1, 1, 8192, 2, 8192, P, 8192, P, 8192, P, 2) == "gemv_cols_bf16_few_kernel<2>"
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 17, 8192, P, 8192, P, 8192, P, 17) is None            # 17 columns: no vector side
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 1, 1, 8192, 9, 8192, P, 8192, P, 8192, P, 9) is None              # nine, and not the matrix-core kernel's storage
     assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 2, 8192, P + 2, 8192, P, 8192, P, 2) is None          # the streamed operand misaligned
-    # bf16 with up to eight rows or columns: the streaming kernels without a workspace; with one, 5 .. 8 vectors go to the
-    # 64 x 64 tiles where those split K
+    # without a workspace the streaming kernels take such calls; with one, the 64 x 64 tiles where they split K and there are
+    # more than 8 vectors on a long matrix (matrix-core kernel) or more than 4 (the others)
     pbx = lambda M, N, K, ws: lib.fsrgemm_plan_bf16(0, 1, M, N, K, P, K, P, K, ws, True)
-    assert pbx(8, 8192, 8192, False) == (4, 1) and pbx(8, 8192, 8192, True) == (3, 8) and pbx(4, 8192, 8192, True) == (4, 1)
-    assert lib.fsrgemm_plan_bf16(0, 0, 4, 8192, 8192, P, 8192, P, 8192, True, True) == (4, 2) and pbx(8, 8192, 128, True) == (4, 1)
+    assert pbx(8, 8192, 8192, False) == (4, 1) and pbx(8, 8192, 8192, True) == (4, 1) and pbx(16, 8192, 8192, False) == (4, 1)
+    assert pbx(16, 8192, 8192, True) == (3, 8) and pbx(16, 2048, 8192, True) == (4, 2) and pbx(12, 1024, 16384, True) == (4, 4)
+    assert pbx(17, 8192, 8192, False) == (3, 1) and pbx(8, 8192, 128, True) == (4, 1)
+    pbn = lambda M, N, K, ws: lib.fsrgemm_plan_bf16(0, 0, M, N, K, P, K, P, N, ws, True)
+    assert pbn(4, 8192, 8192, True) == (4, 2) and pbn(8, 8192, 8192, True) == (3, 8) and pbn(8, 8192, 8192, False) == (4, 1) and pbn(16, 8192, 8192, False) == (3, 1)
     assert lib.fsrgemm_kernel_for_bf16_ex(0, 0, 3, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemv_cols_bf16_few_kernel<4>"
     bad = lib.FSRGEMM_ERR_INVALID_ARG
     assert lib.gemm_bf16_ws(0, 1, 1, 8, 4096, P, 4096, P, 4096, P, 8, None, 64, 0) == bad

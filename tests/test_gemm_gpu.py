@@ -1157,8 +1157,10 @@ def test_bf16_vector_shapes(gpu, M, N, K):
         refi, _ = oracle.gemm(Ai, Bi)
         for ta, tb in [(0, 0)] + LAYOUTS:
             assert np.array_equal(run_bf16_ws(gpu, ta, tb, Ai, Bi).astype(np.float64), refi)
-    with pytest.raises(gpu.FsrGemmError):       # nine rows and nine columns: no vector side
-        run_cfg(gpu, "bf16", 4, 1, 0, 1, inputs.bf16_small_ints(4, 72, 9, 64), inputs.bf16_small_ints(4, 73, 64, 9))
+    with pytest.raises(gpu.FsrGemmError):       # 17 rows and 17 columns: no vector side
+        run_cfg(gpu, "bf16", 4, 1, 0, 1, inputs.bf16_small_ints(4, 72, 17, 64), inputs.bf16_small_ints(4, 73, 64, 17))
+    with pytest.raises(gpu.FsrGemmError):       # nine and nine, and not the storage the matrix-core kernel takes
+        run_cfg(gpu, "bf16", 4, 1, 0, 0, inputs.bf16_small_ints(4, 72, 9, 64), inputs.bf16_small_ints(4, 73, 64, 9))
 
 
 def test_f32_vector_every_slice_count(gpu):
@@ -1242,7 +1244,8 @@ def test_bf16_few_vector_shapes(gpu, M, N, K):
         name = gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N)
         say("bf16 few vectors %dx%dx%d storage %d%d -> %s" % (M, N, K, ta, tb, name))
         cols = (ta if N <= M else not tb)                    # the streamed operand walked along its columns needs eight of them
-        assert ("few_kernel" in name) == (not cols or max(M, N) >= 8), name
+        assert ("few_kernel" in name or "mfma_kernel" in name) == (not cols or max(M, N) >= 8), name
+        assert ("mfma_kernel" in name) == ((ta, tb) == (0, 1) and K % 8 == 0), name       # both sides contiguous along k, whole pieces
         got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 3, repeat=2)
         assert oracle.componentwise_error(got, ref, S) <= 1e-5
         got = run_bf16_ws(gpu, ta, tb, A, B, lda=lda + 8, ldb=ldb + 16, repeat=2)            # with the workspace the library asks for
@@ -1250,7 +1253,7 @@ def test_bf16_few_vector_shapes(gpu, M, N, K):
         got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda + 1, ldb=ldb + 3, offset=1, repeat=2)   # 2-byte aligned only: the tile kernels
         assert oracle.componentwise_error(got, ref, S) <= 1e-5
         for slices in (1, 2, 7, 64):
-            if slices <= -(-K // 64) and "few_kernel" in name:
+            if slices <= -(-K // 64) and "gemv_" in name:
                 got = run_cfg(gpu, "bf16", 4, slices, ta, tb, A, B, lda=lda, ldb=ldb, repeat=2)
                 assert oracle.componentwise_error(got, ref, S) <= 1e-5
         if K <= 4097:
@@ -1258,7 +1261,34 @@ def test_bf16_few_vector_shapes(gpu, M, N, K):
             assert np.array_equal(run_bf16_ex(gpu, ta, tb, Ai, Bi, lda=lda, ldb=ldb).astype(np.float64), refi)
 
 
-@pytest.mark.parametrize("M,N,K", [(8, 300, 700), (300, 5, 700), (3, 136, 515)])
+@pytest.mark.parametrize("M,N,K", [(16, 1000, 776), (13, 520, 2056), (16, 16, 64), (9, 33, 8), (1000, 16, 1000), (1001, 11, 4104),
+                                   (2, 8200, 256), (16, 17, 8192), (10, 300, 1032)])
+def test_bf16_up_to_16_vectors_on_the_matrix_cores(gpu, M, N, K):
+    # row-major A against column-major B with up to 16 rows or columns on one side: the matrix-core streaming kernel,
+    # through the plain entry point, with the workspace the library asks for, and as the vector candidate in 1 .. 64 K slices
+    A = inputs.bf16_normal_scaled(21, 1, M, K, 1 / math.sqrt(K))
+    B = inputs.bf16_normal_scaled(21, 2, K, N, 1 / math.sqrt(K))
+    ref, S = oracle.gemm(A, B)
+    for pad in (0, 8):
+        lda, ldb = K + pad, K + 2 * pad
+        assert gpu.fsrgemm_kernel_for_bf16_ex(0, 1, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N) == "gemv_rows_bf16_mfma_kernel"
+        say("bf16 matrix-core vectors %dx%dx%d, leading dimensions %d %d" % (M, N, K, lda, ldb))
+        got = run_bf16_ex(gpu, 0, 1, A, B, lda=lda, ldb=ldb, ldc=N + pad // 2, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= 1e-5
+        got = run_bf16_ws(gpu, 0, 1, A, B, lda=lda, ldb=ldb, repeat=2)
+        assert oracle.componentwise_error(got, ref, S) <= 1e-5
+        for slices in (1, 2, 3, 7, 64):
+            if slices <= -(-K // 64):
+                got = run_cfg(gpu, "bf16", 4, slices, 0, 1, A, B, lda=lda, ldb=ldb, repeat=2)
+                assert oracle.componentwise_error(got, ref, S) <= 1e-5
+    if K <= 4104:
+        Ai, Bi = inputs.bf16_small_ints(4, 78, M, K), inputs.bf16_small_ints(4, 79, K, N)
+        refi, _ = oracle.gemm(Ai, Bi)
+        assert np.array_equal(run_bf16_ex(gpu, 0, 1, Ai, Bi).astype(np.float64), refi)
+        assert np.array_equal(run_cfg(gpu, "bf16", 4, min(3, -(-K // 64)), 0, 1, Ai, Bi).astype(np.float64), refi)
+
+
+@pytest.mark.parametrize("M,N,K", [(8, 300, 700), (300, 5, 700), (3, 136, 515), (12, 300, 704), (300, 16, 520)])
 def test_bf16_few_vectors_special_values(gpu, M, N, K):
     # infinities and NaNs in the streamed matrix, among them its last row and column (which the kernels read again in
     # place of pieces outside the matrix): the class of every entry must match the oracle's
@@ -1273,6 +1303,8 @@ def test_bf16_few_vectors_special_values(gpu, M, N, K):
     assert np.isnan(ref).any() and np.isfinite(ref).any()
     fin = np.isfinite(ref)
     for ta, tb in [(0, 1), (0, 0), (1, 0), (1, 1)]:
+        if min(M, N) > 8 and (ta, tb) != (0, 1):
+            continue                # more than 8 vectors: only in the storage the matrix-core kernel takes
         kw = dict(lda=_ceil8(M if ta else K), ldb=_ceil8(K if tb else N))
         for slices in (1, 3):
             say("bf16 few vectors, specials, %dx%dx%d storage %d%d, %d slices" % (M, N, K, ta, tb, slices))
@@ -1283,7 +1315,17 @@ def test_bf16_few_vectors_special_values(gpu, M, N, K):
 
 
 def test_bf16_few_vectors_every_count(gpu):
-    # 2 .. 8 vectors on either side through the vector candidate, 1 and 3 K slices, every storage order
+    # 2 .. 8 vectors on either side through the vector candidate, 1 and 3 K slices, every storage order (K = 1500: no
+    # whole 16-byte pieces, so the lane-arithmetic kernels everywhere), and 2 .. 16 on the matrix cores (K = 1504)
+    for nvec in range(2, 17):
+        K = 1504
+        A = inputs.bf16_normal_scaled(19, 40 + nvec, nvec, K, 1 / math.sqrt(K))
+        B = inputs.bf16_normal_scaled(19, 60 + nvec, K, 330, 1 / math.sqrt(K))
+        ref, S = oracle.gemm(A, B)
+        for slices in (1, 3):
+            say("bf16 vector candidate on the matrix cores, %d vectors, %d slices" % (nvec, slices))
+            assert oracle.componentwise_error(run_cfg(gpu, "bf16", 4, slices, 0, 1, A, B, repeat=2), ref, S) <= 1e-5
+            assert oracle.componentwise_error(run_cfg(gpu, "bf16", 4, slices, 0, 1, B.T.copy(), A.T.copy(), repeat=2), ref.T, S.T) <= 1e-5
     K = 1500
     for nvec in range(2, 9):
         A = inputs.bf16_normal_scaled(19, 10 + nvec, nvec, K, 1 / math.sqrt(K))
