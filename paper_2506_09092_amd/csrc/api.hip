@@ -518,7 +518,9 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     if (vector) {
         const VecMap16 v = vector_map16(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
         p->cfg = kBf16_Vector;
-        p->slices = split ? vector_slices(v.pattern, v.a.len, K, 64, v.a.nvec > 1 ? 16 : 4) : 1;
+        // (matrix rows per workgroup: 4 with one vector, 16 with several, 32 in the matrix-core kernel that stages the vectors in LDS)
+        const int rows_per_group = v.a.nvec == 1 ? 4 : gemv_bf16_takes_mfma(v.pattern, v.a) && v.a.nvec > kMfmaDirectVectors ? 32 : 16;
+        p->slices = split ? vector_slices(v.pattern, v.a.len, K, 64, rows_per_group) : 1;
         if (p->slices > 1 && (int64_t)p->slices * M * N * 4 > kMaxWorkspace) p->slices = (int)(kMaxWorkspace / (M * N * 4)) < 2 ? 1 : (int)(kMaxWorkspace / (M * N * 4));
         p->mode = 0;
         return ceil_div(M > N ? M : N, 4) * p->slices >= ((int64_t)1 << 31) ? FSRGEMM_ERR_INVALID_ARG : FSRGEMM_OK;

@@ -381,16 +381,112 @@ __global__ __launch_bounds__(kThreads) void gemv_cols_bf16_few_kernel(VecArgs16 
 
 // rows pattern on the matrix cores, up to 16 vectors that are contiguous along k (kMaxMfmaVectors; the storage gemm_bf16
 // takes: a few rows of a row-major A against a column-major B, or a row-major A against a few columns of such a B):
-// y_r[i] = sum_k Mat[i][k] x_r[k] as D = X . Mat^T in 16 x 16 x 32 steps, so that the arithmetic no longer occupies the
-// vector units.  Both fragments of v_mfma_f32_16x16x32_bf16 are 16-byte pieces of memory as it lies: lane l holds the
-// 8 values k = 8 (l / 16) .. + 7 of row l % 16 -- of the vectors for the first operand, of the matrix block for the
-// second -- and register r of the result holds vector 4 (l / 16) + r against matrix row l % 16.  A workgroup takes 16
-// matrix rows (32 or 64 rows per workgroup, every vector fragment serving several matrix fragments, and 16 steps in
-// flight were tried: no faster); its four wavefronts take a quarter of the K range each, in blocks of 256 k = eight steps whose loads form
-// a ring as above; their four partial blocks are added through LDS in wavefront order.
-// Pieces outside the quarter are read from its first piece and both fragments replaced by zeros where they are used,
-// vectors behind the last and matrix rows behind the last repeat the last.  Requires gemv_bf16_takes_mfma(g).
+// y_r[i] = sum_k Mat[i][k] x_r[k] as D = X . Mat^T in steps of v_mfma_f32_16x16x32_bf16, so that the arithmetic no
+// longer occupies the vector units.  Both fragments of that instruction are 16-byte pieces of memory as it lies: lane l
+// holds the 8 values k = 8 (l / 16) .. + 7 of row l % 16 of its operand, and register r of the result holds row
+// 4 (l / 16) + r of the first operand against row l % 16 of the second.
+// Read that way, one load instruction fetches 64 bytes of each of 16 matrix rows (the kernel below does).  Here the 16
+// columns of the second operand are 8 matrix rows times the two halves of a 128-byte line instead -- lane l reads piece
+// 4 (l % 2) + l / 16 of the line of row (l % 16) / 2: one instruction, 8 whole lines, and a wavefront's 8 rows leave a
+// workgroup of four wavefronts 32 rows over one K range -- and a step of 64 k takes two MFMAs on the same matrix fragment: one with the vectors' pieces 0 .. 3
+// (its columns with l % 2 == 0 are products of matching k, the others are not and are never read), one with pieces
+// 4 .. 7 (the other way round).  At the end the two halves of a row are added.
+// A workgroup takes 32 matrix rows, 8 per wavefront, all over the same K range; the vectors' elements of a chunk of
+// 1024 k go through LDS (read from global memory as whole rows of 1 KB, once per workgroup; two buffers, one barrier per
+// chunk; rows padded by 16 bytes so that the 16 lanes of a fragment read hit different banks), and the 16 matrix
+// pieces of a chunk are a ring of loads as above (a ring over two chunks, 32 KB per wavefront in flight, was no faster).  Pieces outside the K range are read from its first piece and
+// replaced by zeros where they are used, vectors behind the last are zeros in LDS, matrix rows behind the last repeat
+// the last.  Requires gemv_bf16_takes_mfma(g).
 __global__ __launch_bounds__(kThreads) void gemv_rows_bf16_mfma_kernel(VecArgs16 g)
+{
+    constexpr int STEPS = 16, KC = 64 * STEPS, XROW = KC + 8;              // steps of 64 k per chunk; LDS row of a vector, in elements
+    constexpr int XPER = 16 * (KC / 8) / kThreads;                         // 16-byte pieces of the vectors per lane and chunk
+    __shared__ __attribute__((aligned(16))) uint16_t xs[2][16 * XROW];
+    __shared__ float red[kThreads / 64][16][17];
+    const int groups = (g.len + 31) / 32;
+    const int slice = (int)blockIdx.x / groups;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int row0 = ((int)blockIdx.x - slice * groups) * 32 + 8 * wave;
+    const int tid = threadIdx.x, lane = tid & 63, l16 = lane & 15, lq = lane >> 4;
+    const int per = (((g.K + g.k_slices - 1) / g.k_slices) + 7) & ~7;     // slices start at multiples of 8: pieces stay aligned
+    const int k0 = (int)min((int64_t)slice * per, (int64_t)g.K), k1 = (int)min((int64_t)k0 + per, (int64_t)g.K);
+    const int piece = 4 * (l16 & 1) + lq;                                  // the lane's piece of a 128-byte line
+    const uint16_t *__restrict__ mp = g.mat + (int64_t)min(row0 + (l16 >> 1), g.len - 1) * g.ld;
+    f32x4 acc_lo = {0.f, 0.f, 0.f, 0.f}, acc_hi = {0.f, 0.f, 0.f, 0.f};     // against the vectors' pieces 0 .. 3 / 4 .. 7
+    u16x8 m[STEPS], xr[XPER];
+    if (k0 < k1) {
+        // the lane's share of the vectors' chunk: piece tid % 128 of vector tid / 128 + 2 q
+        auto fetch_x = [&](int kc) {
+#pragma unroll
+            for (int q = 0; q < XPER; ++q) {
+                const int k = kc + 8 * (tid % (KC / 8));
+                xr[q] = load8(g.x + (int64_t)min(tid / (KC / 8) + (kThreads / (KC / 8)) * q, g.nvec - 1) * g.ldx + (k < k1 ? k : k0));
+            }
+        };
+        auto store_x = [&](uint16_t *dst, int kc) {
+#pragma unroll
+            for (int q = 0; q < XPER; ++q) {
+                const int v = tid / (KC / 8) + (kThreads / (KC / 8)) * q, kl = 8 * (tid % (KC / 8));
+                const bool in = v < g.nvec && kc + kl < k1;
+                u16x8 t;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) t[e] = in ? xr[q][e] : (uint16_t)0;
+                *reinterpret_cast<u16x8 *>(dst + v * XROW + kl) = t;
+            }
+        };
+        // step u of the chunk that begins at kc: the lane's piece of the line at k = kc + 64 u
+        auto fetch_m = [&](int kc, int u) {
+            const int k = kc + 64 * u + 8 * piece;
+            m[u] = load8(mp + (k < k1 ? k : k0));
+            // the load stays here, between the step before and the step behind: without the fence the compiler moves it
+            // down to its use, and without the tie to the sums it moves all the steps ahead of all the loads
+            asm volatile("" : "+v"(acc_lo) : : "memory");
+        };
+#pragma unroll
+        for (int u = 0; u < STEPS; ++u) fetch_m(k0, u);
+        fetch_x(k0);
+        store_x(xs[0], k0);
+        __syncthreads();
+        int buf = 0;
+        for (int kc = k0; kc < k1; kc += KC, buf ^= 1) {
+            fetch_x(kc + KC);
+#pragma unroll
+            for (int u = 0; u < STEPS; ++u) {
+                const uint16_t *xk = &xs[buf][l16 * XROW + 64 * u + 8 * lq];
+                const u16x8 x_lo = *reinterpret_cast<const u16x8 *>(xk), x_hi = *reinterpret_cast<const u16x8 *>(xk + 32);
+                const bool in = kc + 64 * u + 8 * piece < k1;
+                u16x8 mm;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) mm[e] = in ? m[u][e] : (uint16_t)0;
+                acc_hi = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x_hi), __builtin_bit_cast(bf16x8, mm), acc_hi, 0, 0, 0);
+                acc_lo = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x_lo), __builtin_bit_cast(bf16x8, mm), acc_lo, 0, 0, 0);
+                fetch_m(kc + KC, u);
+            }
+            store_x(xs[buf ^ 1], kc + KC);
+            __syncthreads();
+        }
+    }
+    // column l % 16 of a lane is matrix row (l % 16) / 2 against the half l % 2 of its lines: that half's sums are valid
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wave][l16][4 * lq + r] = (l16 & 1) ? acc_hi[r] : acc_lo[r];
+    __syncthreads();
+    for (int o = tid; o < 32 * 16; o += kThreads) {
+        const int w = o / 128, rho = (o / 16) % 8, v = o % 16, row = row0 - 8 * wave + 8 * w + rho;
+        if (v < g.nvec && row < g.len)
+            g.y[(int64_t)slice * g.slice_stride + (int64_t)row * g.incy + (int64_t)v * g.ldy] = red[w][2 * rho][v] + red[w][2 * rho + 1][v];
+    }
+}
+
+// The same product for up to kMfmaDirectVectors vectors, without LDS and without a barrier in the loop: both fragments
+// come straight from global memory in the instruction's own layout (lane l: the 8 values k = 8 (l / 16) .. + 7 of row
+// l % 16 of its operand, 16 matrix rows per workgroup, one MFMA per step of 32 k), the four wavefronts take a quarter
+// of the K range each in blocks of 256 k = eight steps whose 16 loads are the ring, and the four partial blocks are added
+// through LDS in wavefront order.  Every workgroup reads the vectors' whole K range from the L2 (with 16 vectors as many
+// bytes as its share of the matrix), which is what this form costs as the vectors get more: 2 x 8192 x 8192 runs in
+// 23 us, 8 x ... in 27.5, 16 x ... in 33, against 30 - 31 us for any number of vectors in the kernel above, which reads
+// them once per 32 rows and in whole lines; on 16 x 28672 x 8192 it is 135 us against 110.  (A form with the matrix read
+// in whole lines as above but the vectors still straight from memory, 8 rows per workgroup, was slower than both.)
+__global__ __launch_bounds__(kThreads) void gemv_rows_bf16_mfma_direct_kernel(VecArgs16 g)
 {
     constexpr int STEPS = 8, BLOCK = 32 * STEPS;
     __shared__ float red[kThreads / 64][16][17];
@@ -459,7 +555,7 @@ void launch_few(int pattern, const VecArgs16 &a, hipStream_t s)
 // as a profiler trace prints the kernels
 const char *gemv_bf16_kernel_name(int pattern, bool vec, int nvec, bool mfma)
 {
-    if (mfma) return "gemv_rows_bf16_mfma_kernel";
+    if (mfma) return nvec <= kMfmaDirectVectors ? "gemv_rows_bf16_mfma_direct_kernel" : "gemv_rows_bf16_mfma_kernel";
     if (nvec > 1) {
         if (pattern == kVecRows) return nvec <= 2 ? "gemv_rows_bf16_few_kernel<2>" : nvec <= 4 ? "gemv_rows_bf16_few_kernel<4>" : "gemv_rows_bf16_few_kernel<8>";
         return nvec <= 2 ? "gemv_cols_bf16_few_kernel<2>" : nvec <= 4 ? "gemv_cols_bf16_few_kernel<4>" : "gemv_cols_bf16_few_kernel<8>";
@@ -485,7 +581,8 @@ hipError_t launch_gemv_bf16(int pattern, VecArgs16 a, hipStream_t s)
 {
     const bool vec = gemv_bf16_takes_vectors(a);
     if (gemv_bf16_takes_mfma(pattern, a)) {
-        hipLaunchKernelGGL(gemv_rows_bf16_mfma_kernel, dim3((unsigned)((a.len + 15) / 16 * a.k_slices)), dim3(kThreads), 0, s, a);
+        if (a.nvec <= kMfmaDirectVectors) hipLaunchKernelGGL(gemv_rows_bf16_mfma_direct_kernel, dim3((unsigned)((a.len + 15) / 16 * a.k_slices)), dim3(kThreads), 0, s, a);
+        else hipLaunchKernelGGL(gemv_rows_bf16_mfma_kernel, dim3((unsigned)((a.len + 31) / 32 * a.k_slices)), dim3(kThreads), 0, s, a);
         return hipGetLastError();
     }
     if (a.nvec < 1 || a.nvec > kMaxFewVectors || (a.nvec > 1 && !gemv_bf16_takes_few(pattern, a))) return hipErrorInvalidValue;

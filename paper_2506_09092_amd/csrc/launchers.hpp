@@ -88,6 +88,7 @@ struct VecArgs16 {
     int64_t ldx, ldy;
 };
 constexpr int kMaxMfmaVectors = 16;
+constexpr int kMfmaDirectVectors = 8;       // up to here the matrix-core kernel reads the vectors' fragments straight from global memory
 const char *gemv_bf16_kernel_name(int pattern, bool vec, int nvec = 1, bool mfma = false);
 bool gemv_bf16_takes_vectors(const VecArgs16 &a);
 bool gemv_bf16_takes_few(int pattern, const VecArgs16 &a);      // whether a.nvec > 1 vectors can go through these kernels

@@ -177,7 +177,8 @@ def test_workspace_query_and_argument_checks():
     assert qb(0, 1, 1, 8192, 8196, P, 8196, P, 8196, P, 8192) == "gemv_rows_bf16_kernel<false>"         # rows not 16-byte aligned
     assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 1, 8192, P, 8192, P, 8192, P, 1) == "gemv_rows_bf16_kernel<true>"
     # up to 16 vectors contiguous along k against a matrix contiguous along k, K whole 16-byte pieces: the matrix-core kernel
-    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 2, 8192, P, 8192, P, 8192, P, 2) == "gemv_rows_bf16_mfma_kernel"
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 2, 8192, P, 8192, P, 8192, P, 2) == "gemv_rows_bf16_mfma_direct_kernel"       # up to 8: the form without LDS
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 9, 8192, P, 8192, P, 8192, P, 9) == "gemv_rows_bf16_mfma_kernel"
     assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 16, 8192, P, 8192, P, 8192, P, 16) == "gemv_rows_bf16_mfma_kernel"
     assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 2, 8188, P, 8192, P, 8192, P, 2) == "gemv_rows_bf16_few_kernel<2>"      # K not whole pieces
     assert lib.fsrgemm_kernel_for_bf16_cfg(4, 1, 1, 8192, 2, 8192, P, 8192, P, 8192, P, 2) == "gemv_cols_bf16_few_kernel<2>"
@@ -188,7 +189,7 @@ def test_workspace_query_and_argument_checks():
     # more than 8 vectors on a long matrix (matrix-core kernel) or more than 4 (the others)
     pbx = lambda M, N, K, ws: lib.fsrgemm_plan_bf16(0, 1, M, N, K, P, K, P, K, ws, True)
     assert pbx(8, 8192, 8192, False) == (4, 1) and pbx(8, 8192, 8192, True) == (4, 1) and pbx(16, 8192, 8192, False) == (4, 1)
-    assert pbx(16, 8192, 8192, True) == (3, 8) and pbx(16, 2048, 8192, True) == (4, 2) and pbx(12, 1024, 16384, True) == (4, 4)
+    assert pbx(16, 8192, 8192, True) == (3, 8) and pbx(16, 2048, 8192, True) == (4, 4) and pbx(12, 1024, 16384, True) == (4, 8)
     assert pbx(17, 8192, 8192, False) == (3, 1) and pbx(8, 8192, 128, True) == (4, 1)
     pbn = lambda M, N, K, ws: lib.fsrgemm_plan_bf16(0, 0, M, N, K, P, K, P, N, ws, True)
     assert pbn(4, 8192, 8192, True) == (4, 2) and pbn(8, 8192, 8192, True) == (3, 8) and pbn(8, 8192, 8192, False) == (4, 1) and pbn(16, 8192, 8192, False) == (3, 1)

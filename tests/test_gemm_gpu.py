@@ -1244,8 +1244,8 @@ def test_bf16_few_vector_shapes(gpu, M, N, K):
         name = gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N)
         say("bf16 few vectors %dx%dx%d storage %d%d -> %s" % (M, N, K, ta, tb, name))
         cols = (ta if N <= M else not tb)                    # the streamed operand walked along its columns needs eight of them
-        assert ("few_kernel" in name or "mfma_kernel" in name) == (not cols or max(M, N) >= 8), name
-        assert ("mfma_kernel" in name) == ((ta, tb) == (0, 1) and K % 8 == 0), name       # both sides contiguous along k, whole pieces
+        assert ("few_kernel" in name or "_mfma_" in name) == (not cols or max(M, N) >= 8), name
+        assert ("_mfma_" in name) == ((ta, tb) == (0, 1) and K % 8 == 0), name       # both sides contiguous along k, whole pieces
         got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda, ldb=ldb, ldc=N + 3, repeat=2)
         assert oracle.componentwise_error(got, ref, S) <= 1e-5
         got = run_bf16_ws(gpu, ta, tb, A, B, lda=lda + 8, ldb=ldb + 16, repeat=2)            # with the workspace the library asks for
@@ -1262,7 +1262,8 @@ def test_bf16_few_vector_shapes(gpu, M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K", [(16, 1000, 776), (13, 520, 2056), (16, 16, 64), (9, 33, 8), (1000, 16, 1000), (1001, 11, 4104),
-                                   (2, 8200, 256), (16, 17, 8192), (10, 300, 1032)])
+                                   (2, 8200, 256), (16, 17, 8192), (10, 300, 1032), (8, 1000, 776), (5, 33, 8), (3, 700, 3080),
+                                   (9, 40, 1024), (16, 31, 1096), (11, 100, 2048)])
 def test_bf16_up_to_16_vectors_on_the_matrix_cores(gpu, M, N, K):
     # row-major A against column-major B with up to 16 rows or columns on one side: the matrix-core streaming kernel,
     # through the plain entry point, with the workspace the library asks for, and as the vector candidate in 1 .. 64 K slices
@@ -1271,7 +1272,7 @@ def test_bf16_up_to_16_vectors_on_the_matrix_cores(gpu, M, N, K):
     ref, S = oracle.gemm(A, B)
     for pad in (0, 8):
         lda, ldb = K + pad, K + 2 * pad
-        assert gpu.fsrgemm_kernel_for_bf16_ex(0, 1, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N) == "gemv_rows_bf16_mfma_kernel"
+        assert gpu.fsrgemm_kernel_for_bf16_ex(0, 1, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N) == ("gemv_rows_bf16_mfma_direct_kernel" if min(M, N) <= 8 else "gemv_rows_bf16_mfma_kernel")
         say("bf16 matrix-core vectors %dx%dx%d, leading dimensions %d %d" % (M, N, K, lda, ldb))
         got = run_bf16_ex(gpu, 0, 1, A, B, lda=lda, ldb=ldb, ldc=N + pad // 2, repeat=2)
         assert oracle.componentwise_error(got, ref, S) <= 1e-5
