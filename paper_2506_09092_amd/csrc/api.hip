@@ -240,7 +240,7 @@ void shift_to_band(int dim, int64_t at, int a_lay, int b_lay, const T *&A, int64
     C = reinterpret_cast<float *>(reinterpret_cast<uintptr_t>(C) + (uintptr_t)off_c * sizeof(float));
 }
 
-// How a product with M == 1 or N == 1 (fp32: with up to kMaxFewVectors rows or columns on the smaller side) maps onto
+// How a product with M == 1 or N == 1 (or with a few rows or columns on the smaller side: kMaxFewVectors, kMaxMfmaVectors) maps onto
 // the vector kernels: which operand is the matrix, how it is walked, and the strides of the vectors on either side.
 // ARGS: VecArgs (fp32) or VecArgs16 (bf16); T the element type.
 template <class ARGS, class T>
@@ -505,10 +505,10 @@ int plan_bf16(int a_lay, int b_lay, int64_t M, int64_t N, int64_t K, const uint1
     // on 8 x 8192 x 8192); where a workspace lets the 64 x 64 tiles split K they stream faster (26 - 34 us against 35 - 46), so
     // such calls stay with the tiles.  Without a workspace, and up to 4 vectors either way, the streaming kernels win (plain
     // 8 x 8192 x 8192 46 - 81 us against 78 - 140; 4 x 8192 x 8192 36 - 53 against 78 - 411).
-    // The matrix-core kernel (up to 16 vectors contiguous along k against a matrix contiguous along k) runs 16 x 8192 x 8192
-    // in 33 us without a workspace against the tiles' 79, 8 x ... in 27.5, 2 x ... in 23; with a workspace the tiles' split still
-    // wins on long matrices with more than 8 vectors (16 x 8192 x 8192 26 us, 16 x 28672 x 8192 100 - 113 against 135), not on
-    // short ones (12 x 1024 x 16384: 12 us in 4 slices against 20).
+    // The matrix-core kernels (up to 16 vectors contiguous along k against a matrix contiguous along k) run 16 x 8192 x 8192
+    // in 31 us without a workspace against the tiles' 79, 8 x ... in 27.5, 2 x ... in 23; with a workspace the tiles' split is
+    // level or ahead on long matrices with more than 8 vectors (16 x 8192 x 8192 26 us against 29, 16 x 28672 x 8192 100 - 113
+    // against 108), not on short ones (12 x 1024 x 16384: 13 us in 8 slices against 20).
     const bool tiles_can_split = split && (K >= 3072 || M < 64 || N < 64) && splitk_slices(M, N, K, 64) > 1;
     bool vector = !t && vector_call_bf16(transA, transB, M, N, K, A, lda, B, ldb);
     if (vector && !vector_shape(M, N, K) && tiles_can_split) {
