@@ -288,14 +288,15 @@ VecMap16 vector_map16(int transA, int transB, int64_t M, int64_t N, int64_t K, c
 // Workgroups of the vector kernels for an output of `len` elements, and the K slices of a call with a
 // workspace.  A split costs a second launch, so K is cut only to reach enough workgroups to keep the memory
 // system busy, and never finer than 2048 (1024 for the column pattern): 256 workgroups, or 1024 for the bf16 column pattern
-// on a matrix of 128 MiB and more, whose workgroups each keep 32 KB in flight (measured: fp32 1 x 4096 x 4096 gains 15 % from
+// on a matrix of 128 MiB and more, whose workgroups each keep 32 KB in flight, 512 for that pattern with several vectors
+// (the selection loop: 4 x 8192 x 8192 and 8192 x 4 x 8192 3 - 4 % faster in 4 slices than in 2) (measured: fp32 1 x 4096 x 4096 gains 15 % from
 // two slices, 1 x 8192 x 8192 loses 15 % to two, 1 x 1024 x 1024 loses 40 % to any split; bf16 1 x 16384 x 16384 with a row-major
 // B gains 35 % from four).
 int64_t vector_groups(int pattern, int64_t len, int cols_per_group, int rows_per_group = 4) { return pattern == kVecRows ? ceil_div(len, rows_per_group) : ceil_div(len, cols_per_group); }
 int vector_slices(int pattern, int64_t len, int64_t K, int cols_per_group = 32, int rows_per_group = 4)
 {
     const int64_t matrix_bytes = len * K * (cols_per_group == 32 ? 4 : 2);
-    const int64_t target = pattern == kVecCols && matrix_bytes >= ((int64_t)128 << 20) && cols_per_group == 64 && rows_per_group == 4 ? 1024 : 256;
+    const int64_t target = pattern == kVecCols && cols_per_group == 64 ? (rows_per_group != 4 ? 512 : matrix_bytes >= ((int64_t)128 << 20) ? 1024 : 256) : 256;
     int64_t s = target / vector_groups(pattern, len, cols_per_group, rows_per_group);
     const int64_t shortest = pattern == kVecCols ? 1024 : 2048;
     if (s > K / shortest) s = K / shortest;

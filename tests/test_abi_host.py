@@ -192,7 +192,7 @@ def test_workspace_query_and_argument_checks():
     assert pbx(16, 8192, 8192, True) == (3, 8) and pbx(16, 2048, 8192, True) == (4, 4) and pbx(12, 1024, 16384, True) == (4, 8)
     assert pbx(17, 8192, 8192, False) == (3, 1) and pbx(8, 8192, 128, True) == (4, 1)
     pbn = lambda M, N, K, ws: lib.fsrgemm_plan_bf16(0, 0, M, N, K, P, K, P, N, ws, True)
-    assert pbn(4, 8192, 8192, True) == (4, 2) and pbn(8, 8192, 8192, True) == (3, 8) and pbn(8, 8192, 8192, False) == (4, 1) and pbn(16, 8192, 8192, False) == (3, 1)
+    assert pbn(4, 8192, 8192, True) == (4, 4) and pbn(8, 8192, 8192, True) == (3, 8) and pbn(8, 8192, 8192, False) == (4, 1) and pbn(16, 8192, 8192, False) == (3, 1)
     assert lib.fsrgemm_kernel_for_bf16_ex(0, 0, 3, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemv_cols_bf16_few_kernel<4>"
     bad = lib.FSRGEMM_ERR_INVALID_ARG
     assert lib.gemm_bf16_ws(0, 1, 1, 8, 4096, P, 4096, P, 4096, P, 8, None, 64, 0) == bad

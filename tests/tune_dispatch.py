@@ -3,7 +3,7 @@ on a list of problems with the CPU oracle as the function validator, and writes 
 paper_2506_09092_amd/csrc/tuned_table.inc for the problems whose measured best beats the dispatcher's rules.
 Lives under tests/ because it compares the HIP path with the oracle.
 
-    python -m tests.tune_dispatch --out <file> [--log <file>] [--only f32|bf16]        (on an MI355X)
+    python -m tests.tune_dispatch --out <file> [--log <file>] [--only f32|bf16|bf16-orders|thin]        (on an MI355X)
 
 A row is written only when the winner is at least `--gain` (default 4 %) faster than what the dispatcher's rules
 alone would take, measured twice; everything else stays with the rules.  After replacing the table, rebuild the library.
@@ -43,6 +43,15 @@ BF16_ORDERS = [(ta, tb, n) for n in (1024, 1536, 2048, 2560, 3072, 3584, 4096, 5
 
 # the normal equations of the paper's Task 20: X^T X and X^T y for X of n x 10 (a transposed A against a row-major B)
 F32_TALL = [(10, 10, 1 << e) for e in (14, 18, 22)] + [(10, 1, 1 << e) for e in (14, 18, 22)]
+
+
+# a few rows or columns on one side (the streaming kernels, on the vector units or the matrix cores, against tiles with K slices):
+# (kind, transA, transB, M, N, K)
+THIN = [("f32", 0, 0, 8, 8192, 8192), ("f32", 0, 1, 8, 8192, 8192), ("f32", 0, 0, 4, 8192, 8192), ("f32", 0, 0, 8192, 8, 8192),
+        ("f32", 1, 0, 8192, 8, 8192), ("f32", 0, 0, 8, 2048, 8192), ("f32", 0, 0, 8, 1024, 16384), ("f32", 0, 0, 3, 16384, 4096),
+        ("bf16", 0, 1, 8, 8192, 8192), ("bf16", 0, 0, 8, 8192, 8192), ("bf16", 0, 1, 16, 8192, 8192), ("bf16", 0, 0, 4, 8192, 8192),
+        ("bf16", 0, 1, 2, 8192, 8192), ("bf16", 0, 1, 12, 1024, 16384), ("bf16", 0, 1, 16, 28672, 8192), ("bf16", 0, 1, 8192, 16, 8192),
+        ("bf16", 1, 1, 8192, 4, 8192)]
 
 
 def host_operands(p: Problem, seed: int):
@@ -107,7 +116,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", required=True)
     ap.add_argument("--log", default=None)
-    ap.add_argument("--only", choices=["f32", "bf16", "bf16-orders"], default=None)
+    ap.add_argument("--only", choices=["f32", "bf16", "bf16-orders", "thin"], default=None)
     ap.add_argument("--gain", type=float, default=0.04)
     args = ap.parse_args()
 
@@ -125,7 +134,8 @@ def main():
     problems = [Problem("f32", 0, 0, *s) for s in F32 if args.only in (None, "f32")] + \
                [Problem("f32", 1, 0, *s) for s in F32_TALL if args.only in (None, "f32")] + \
                [Problem("bf16", 0, 1, *s) for s in BF16 if args.only in (None, "bf16")] + \
-               [Problem("bf16", ta, tb, n, n, n) for ta, tb, n in BF16_ORDERS if args.only in (None, "bf16-orders")]
+               [Problem("bf16", ta, tb, n, n, n) for ta, tb, n in BF16_ORDERS if args.only in (None, "bf16-orders")] + \
+               [Problem(*t) for t in THIN if args.only in (None, "thin")]
     rows, reports = [], []
     for p in problems:
         log("== %s" % (p,))
