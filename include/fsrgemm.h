@@ -184,7 +184,7 @@ int gemm_bf16_ws(int transA, int transB,
  * validate, keep the one with the least measured time), with tile configurations and K slices in the place of
  * generated kernels.
  *   tile: fp32  0 = 256 x 128, 1 = 128 x 128, 2 = 64 x 64 output tile per workgroup, 3 = the streaming kernels for
- *               M == 1 or N == 1 with K > 0, which use no matrix cores, and for M <= 8 or N <= 8 where the operand on the
+ *               M == 1 or N == 1 with K > 0, which use no matrix cores, and for M <= 16 or N <= 16 where the operand on the
  *               other side (B for M < N, else A) is 16-byte aligned with a leading dimension that is a multiple of 4
  *               and, if it is stored contiguous along n (m), N (M) >= 4; 4 = the kernel for small results of long
  *               sums (both operands stored with k as the row index: transA != 0 or M == 1, transB == 0 or N == 1; M, N <= 16 with
@@ -205,7 +205,7 @@ int gemm_bf16_ws(int transA, int transB,
  *         ceil(K / 64) (bf16).
  * A candidate that cannot run this problem is FSRGEMM_ERR_INVALID_ARG and launches nothing: a tile or slice
  * count out of range, a split without a fitting workspace, fp32 candidate 3 or bf16 candidate 4 on a product
- * without 1 .. 8 (bf16, where described above: 16) rows or columns on one side,
+ * without 1 .. 16 (bf16: 8, and 16 only where described above) rows or columns on one side,
  * fp32 candidate 4 on a result that is too large,
  * fp32 tiles 5..16 where their kernel's conditions fail (M, N at least one tile, K >= 32 and a
  * multiple of 4, 16-byte aligned operands with leading dimensions that are multiples of 4 and below 2^24;

@@ -240,7 +240,7 @@ void shift_to_band(int dim, int64_t at, int a_lay, int b_lay, const T *&A, int64
     C = reinterpret_cast<float *>(reinterpret_cast<uintptr_t>(C) + (uintptr_t)off_c * sizeof(float));
 }
 
-// How a product with M == 1 or N == 1 (or with a few rows or columns on the smaller side: kMaxFewVectors, kMaxMfmaVectors) maps onto
+// How a product with M == 1 or N == 1 (or with a few rows or columns on the smaller side: kMaxFewVectorsF32, kMaxFewVectors, kMaxMfmaVectors) maps onto
 // the vector kernels: which operand is the matrix, how it is walked, and the strides of the vectors on either side.
 // ARGS: VecArgs (fp32) or VecArgs16 (bf16); T the element type.
 template <class ARGS, class T>
@@ -306,12 +306,12 @@ int vector_slices(int pattern, int64_t len, int64_t K, int cols_per_group = 32, 
 
 // (K beyond 2^30 stays with the tile kernels: the vector kernels count k in 32-bit steps of up to 1024)
 bool vector_shape(int64_t M, int64_t N, int64_t K) { return (M == 1 || N == 1) && M > 0 && N > 0 && K > 0 && K <= ((int64_t)1 << 30); }
-// fp32 also with 2 .. kMaxFewVectors rows or columns on the smaller side, where the other operand (the matrix that is
+// fp32 also with 2 .. kMaxFewVectorsF32 rows or columns on the smaller side, where the other operand (the matrix that is
 // streamed) consists of aligned 16-byte pieces
 bool vector_call_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb)
 {
     if (vector_shape(M, N, K)) return true;
-    if (M < 1 || N < 1 || K < 1 || K > ((int64_t)1 << 30) || (M > kMaxFewVectors && N > kMaxFewVectors)) return false;
+    if (M < 1 || N < 1 || K < 1 || K > ((int64_t)1 << 30) || (M > kMaxFewVectorsF32 && N > kMaxFewVectorsF32)) return false;
     const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
     return gemv_takes_few(v.pattern, v.a);
 }
@@ -340,7 +340,14 @@ int plan_f32(int transA, int transB, int64_t M, int64_t N, int64_t K, const floa
              int64_t ldb, bool split, Plan *p, bool use_table = true)
 {
     const Tuned *t = use_table ? find_tuned(0, transA, transB, M, N, K, split) : nullptr;
-    const bool vector = vector_call_f32(transA, transB, M, N, K, A, lda, B, ldb);
+    bool vector = vector_call_f32(transA, transB, M, N, K, A, lda, B, ldb);
+    if (vector && split && M > 8 && N > 8 && splitk_slices(M, N, K, 16) > 1) {
+        // 9 .. 16 vectors against a matrix that is contiguous along k: a workgroup of that pattern fetches as many bytes of
+        // vectors from the L2 as of matrix (16 x 8192 x 8192 103 - 155 us); the 64 x 64 tiles in K slices do it in 84 - 90.
+        // Without a workspace the tiles take 270, and the other pattern streams at 3.2 - 3.6 TB/s either way (74 - 85 us).
+        const VecMap v = vector_map(transA, transB, M, N, K, A, lda, B, ldb, nullptr, 1);
+        vector = v.pattern == kVecCols;
+    }
     SkinnyArgs sk;
     sk.K = (int)K;
     sk.parts = (int)(K / 256 < kSkinnyMaxParts ? K / 256 : kSkinnyMaxParts);

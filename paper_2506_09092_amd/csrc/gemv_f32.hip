@@ -11,7 +11,7 @@
 //          output columns (one 128-byte line of every matrix row): 8 lanes cover the line, 32 groups of lanes
 //          take every 32nd row, eight rows in flight each, and the 32 partial sums per column are added in
 //          group order through LDS.
-// A few vectors on one side (2 .. 8 rows of A or columns of B, kMaxFewVectors) stream the matrix once as well, every
+// A few vectors on one side (2 .. 16 rows of A or columns of B, kMaxFewVectorsF32) stream the matrix once as well, every
 // element now feeding one multiply-add per vector.  The two patterns keep their shape; what changes is that a
 // workgroup stages its K range of the vectors through LDS (any strides on the global side, zeros behind the
 // last vector and behind the K range), chunk by chunk in two buffers, one barrier per chunk, and requests a matrix
@@ -405,8 +405,8 @@ void launch_few(int pattern, const VecArgs &a, hipStream_t s)
 const char *gemv_kernel_name(int pattern, bool vec, int nvec)
 {
     if (nvec > 1) {
-        if (pattern == kVecRows) return nvec <= 2 ? "gemv_rows_f32_few_kernel<2>" : nvec <= 4 ? "gemv_rows_f32_few_kernel<4>" : "gemv_rows_f32_few_kernel<8>";
-        return nvec <= 2 ? "gemv_cols_f32_few_kernel<2>" : nvec <= 4 ? "gemv_cols_f32_few_kernel<4>" : "gemv_cols_f32_few_kernel<8>";
+        if (pattern == kVecRows) return nvec <= 2 ? "gemv_rows_f32_few_kernel<2>" : nvec <= 4 ? "gemv_rows_f32_few_kernel<4>" : nvec <= 8 ? "gemv_rows_f32_few_kernel<8>" : "gemv_rows_f32_few_kernel<16>";
+        return nvec <= 2 ? "gemv_cols_f32_few_kernel<2>" : nvec <= 4 ? "gemv_cols_f32_few_kernel<4>" : nvec <= 8 ? "gemv_cols_f32_few_kernel<8>" : "gemv_cols_f32_few_kernel<16>";
     }
     if (pattern == kVecRows) return vec ? "gemv_rows_f32_kernel<true>" : "gemv_rows_f32_kernel<false>";
     return vec ? "gemv_cols_f32_kernel<true>" : "gemv_cols_f32_kernel<false>";
@@ -421,11 +421,12 @@ bool gemv_takes_few(int pattern, const VecArgs &a) { return gemv_takes_vectors(a
 hipError_t launch_gemv_f32(int pattern, VecArgs a, hipStream_t s)
 {
     const bool vec = gemv_takes_vectors(a);
-    if (a.nvec < 1 || a.nvec > kMaxFewVectors || (a.nvec > 1 && !gemv_takes_few(pattern, a))) return hipErrorInvalidValue;
+    if (a.nvec < 1 || a.nvec > kMaxFewVectorsF32 || (a.nvec > 1 && !gemv_takes_few(pattern, a))) return hipErrorInvalidValue;
     if (a.nvec > 1) {
         if (a.nvec <= 2) launch_few<2>(pattern, a, s);
         else if (a.nvec <= 4) launch_few<4>(pattern, a, s);
-        else launch_few<8>(pattern, a, s);
+        else if (a.nvec <= 8) launch_few<8>(pattern, a, s);
+        else launch_few<16>(pattern, a, s);
         return hipGetLastError();
     }
     a.xvec = a.incx == 1 && aligned16(a.x);

@@ -55,10 +55,11 @@ struct VecArgs {
     int k_slices;
     int64_t slice_stride;
     bool xvec;
-    int nvec;               // vectors x_r = x + r * ldx, y_r = y + r * ldy, r < nvec <= kMaxFewVectors
+    int nvec;               // vectors x_r = x + r * ldx, y_r = y + r * ldy, r < nvec <= kMaxFewVectorsF32
     int64_t ldx, ldy;
 };
-constexpr int kMaxFewVectors = 8;
+constexpr int kMaxFewVectors = 8;           // bf16, lane arithmetic
+constexpr int kMaxFewVectorsF32 = 16;
 const char *gemv_kernel_name(int pattern, bool vec, int nvec = 1);
 bool gemv_takes_vectors(const VecArgs &a);
 bool gemv_takes_few(int pattern, const VecArgs &a);     // whether a.nvec > 1 vectors can go through these kernels

@@ -212,7 +212,7 @@ def test_f32_tile_rule_follows_the_round_model():
     assert pf(1024, P + 4) == 2 and pf(2560) == 14 and lib.fsrgemm_plan_f32(0, 0, 1024, 2048, 4096, P, 4096, P, 2048)[0] == 15
     assert [pf(n, P + 4) for n in (4096, 8192)] == [0, 0] and pf(4096, K=4112) == 5      # misaligned A: the general kernel; a rest of K: the same tile
     assert lib.fsrgemm_plan_f32(0, 0, 4096, 4096, 4110, P, 4112, P, 4096)[0] == 0 and pf(4096, K=16) == 0     # K not a multiple of 4, K below a K-tile
-    assert lib.fsrgemm_plan_f32(0, 0, 10, 100000, 64, P, 64, P, 100000)[0] == 2          # a sliver: small tiles waste least
+    assert lib.fsrgemm_plan_f32(0, 0, 17, 100000, 64, P, 64, P, 100000)[0] == 2          # a sliver: small tiles waste least
     assert lib.fsrgemm_plan_f32(0, 0, 262144, 2048, 4096, P, 4096, P, 2048)[0] == 5        # the paper's largest Task-2 size
 
 
@@ -232,12 +232,16 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
     assert lib.fsrgemm_plan_bf16(0, 1, 512, 512, 65536, P + 2, 65536, P, 65536, True, True) == (3, 16)       # misaligned A: the general kernel only
     assert lib.gemm_f32_workspace_bytes(0, 0, 512, 512, 65536) == 16 * 512 * 512 * 4
     # a problem under 128 rows or columns keeps 64 x 64 tiles: most of a 128-wide tile would be padding
-    assert pf(16, 8192, 8192) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 16, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and pb(32, 28672, 8192) == (3, 2) and pb(96, 8192, 8192) == (3, 4) and pb(128, 8192, 8192) == (10, 4)
-    # fp32 with up to eight rows (or columns) streams the other operand through the vector kernels (candidate 3) where that
-    # operand consists of aligned 16-byte pieces: K slices only up to 256 workgroups; otherwise tiles as above
+    assert pf(17, 8192, 8192) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 17, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and pb(32, 28672, 8192) == (3, 2) and pb(96, 8192, 8192) == (3, 4) and pb(128, 8192, 8192) == (10, 4)
+    # fp32 with up to 16 rows (or columns) streams the other operand through the vector kernels (candidate 3) where that
+    # operand consists of aligned 16-byte pieces: K slices only up to 256 workgroups; otherwise tiles as above.  With 9 .. 16
+    # vectors against a matrix contiguous along k, and a workspace, the tiles in K slices stay
     assert pf(8, 8192, 8192) == (3, 1) and pf(8, 2048, 8192) == (3, 4) and lib.fsrgemm_plan_f32(0, 1, 8, 2048, 8192, P, 8192, P, 8192, True, True) == (3, 2)
     assert lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P + 4, 8192, True, True) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P, 8193, True, True) == (2, 8)
-    assert lib.fsrgemm_plan_f32(0, 0, 9, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 8, 2048, 8192, P, 8192, P, 2048, False, True) == (3, 1)
+    assert lib.fsrgemm_plan_f32(0, 0, 9, 8192, 8192, P, 8192, P, 8192, True, True) == (3, 1) and lib.fsrgemm_plan_f32(0, 0, 8, 2048, 8192, P, 8192, P, 2048, False, True) == (3, 1)
+    assert lib.fsrgemm_plan_f32(0, 1, 16, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and lib.fsrgemm_plan_f32(0, 1, 16, 8192, 8192, P, 8192, P, 8192, False, True) == (3, 1)
+    assert lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P, 8192, True, True) == (3, 1)
+    assert lib.fsrgemm_kernel_for_f32_ex(0, 0, 12, 8192, 8192, P, 8192, P, 8192, P, 8192) == "gemv_cols_f32_few_kernel<16>"
     assert lib.fsrgemm_kernel_for_f32_ex(0, 0, 8, 2048, 8192, P, 8192, P, 2048, P, 2048) == "gemv_cols_f32_few_kernel<8>"
     assert lib.fsrgemm_kernel_for_f32_ex(0, 1, 3, 2048, 8192, P, 8192, P, 8192, P, 2048) == "gemv_rows_f32_few_kernel<4>"
     assert lib.fsrgemm_kernel_for_f32_ex(1, 0, 2048, 2, 8192, P, 2048, P, 2, P, 2) == "gemv_cols_f32_few_kernel<2>"
@@ -554,7 +558,7 @@ def test_f32_direct_to_lds_kernel_is_not_planned_beyond_its_32_bit_lane_offsets(
 
 def test_small_result_kernel_is_planned_only_where_its_launcher_accepts_the_pieces():
     # normal equations with a widely padded X: 2^22 rows in 256 pieces are 16384 rows a piece, and 16384 * 40000
-    # elements do not fit the kernel's 32-bit lane offsets -- the plan must fall back to the split tile kernels, and
+    # elements do not fit the kernel's 32-bit lane offsets -- the plan must fall back to another kernel in K slices, and
     # whatever it names must be what the forced entry point accepts for the same arguments
     bad = lib.FSRGEMM_ERR_INVALID_ARG
     K = 1 << 22
@@ -566,7 +570,7 @@ def test_small_result_kernel_is_planned_only_where_its_launcher_accepts_the_piec
         assert (lib.fsrgemm_kernel_for_f32_cfg(4, 1, 0, 10, 10, K, P, lda, P, 10, P, 10) is None) == (not fits)
         if not fits:        # (only rejected calls are made here: the addresses are fake)
             assert lib.gemm_f32_cfg(4, 256, 1, 0, 10, 10, K, P, lda, P, 10, P, 10, P, 256 * 100 * 4, 0) == bad
-            assert tile == 2 and slices > 1
+            assert tile == 3 and slices > 1             # (ten columns of a transposed X in aligned pieces: the streaming kernel)
     # the same on B's side, and for a dot product of two strided vectors
     assert lib.fsrgemm_plan_f32(1, 0, 10, 10, K, P, 10, P, 40000, True)[0] == 2
     assert lib.fsrgemm_plan_f32(1, 1, 1, 1, K, P, 1, P, K, True) == (4, 256)

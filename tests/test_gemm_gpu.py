@@ -1172,8 +1172,8 @@ def test_f32_vector_every_slice_count(gpu):
             say("f32 vector candidate, %d slices, storage %d%d" % (slices, ta, tb))
             assert oracle.componentwise_error(run_cfg(gpu, "f32", 3, slices, ta, tb, A, B, repeat=2), ref, S) <= TOL_F32
             assert oracle.componentwise_error(run_cfg(gpu, "f32", 3, slices, ta, tb, B.T.copy(), A.T.copy(), repeat=2), ref.T, S.T) <= TOL_F32
-    with pytest.raises(gpu.FsrGemmError):       # nine rows and nine columns: no vector side
-        run_cfg(gpu, "f32", 3, 1, 0, 0, inputs.uniform_pm1(14, 5, 9, 64), inputs.uniform_pm1(14, 6, 64, 9))
+    with pytest.raises(gpu.FsrGemmError):       # 17 rows and 17 columns: no vector side
+        run_cfg(gpu, "f32", 3, 1, 0, 0, inputs.uniform_pm1(14, 5, 17, 64), inputs.uniform_pm1(14, 6, 64, 17))
 
 
 # ---- a few vectors on one side (2 .. 8 rows or columns): the streaming kernels with the vectors staged in LDS ----
@@ -1183,7 +1183,8 @@ def _ceil4(n):
 
 
 FEW_SHAPES = [(8, 1000, 777), (3, 513, 2050), (2, 64, 9), (5, 36, 1300), (1000, 8, 777), (516, 3, 2050), (7, 4100, 5000),
-              (4, 4, 4096), (8, 8, 600), (6, 2049, 515), (2050, 5, 1027), (2, 4, 1), (8, 31, 3), (3, 3, 50)]
+              (4, 4, 4096), (8, 8, 600), (6, 2049, 515), (2050, 5, 1027), (2, 4, 1), (8, 31, 3), (3, 3, 50),
+              (16, 1000, 777), (13, 513, 2050), (1000, 12, 777), (9, 4100, 5000), (16, 16, 300), (11, 40, 9)]
 
 
 @pytest.mark.parametrize("M,N,K", FEW_SHAPES)
@@ -1211,10 +1212,10 @@ def test_f32_few_vector_shapes(gpu, M, N, K):
 
 
 def test_f32_few_vectors_every_count_and_slice_count(gpu):
-    # 2 .. 8 vectors on either side through the vector candidate with 1 .. 64 K slices (slices of a few elements, empty
+    # 2 .. 16 vectors on either side through the vector candidate with 1 .. 64 K slices (slices of a few elements, empty
     # slices, a last chunk that is not whole), every storage order
     K = 1500
-    for nvec in range(2, 9):
+    for nvec in range(2, 17):
         A, B = inputs.uniform_pm1(15, 10 + nvec, nvec, K), inputs.uniform_pm1(15, 20 + nvec, K, 332)
         ref, S = oracle.gemm(A, B)
         for ta, tb in [(0, 0)] + LAYOUTS:
@@ -1341,7 +1342,7 @@ def test_bf16_few_vectors_every_count(gpu):
                 assert oracle.componentwise_error(run_cfg(gpu, "bf16", 4, slices, ta, tb, B.T.copy(), A.T.copy(), **kw), ref.T, S.T) <= 1e-5
 
 
-@pytest.mark.parametrize("M,N,K", [(8, 300, 700), (300, 5, 700), (3, 132, 515)])
+@pytest.mark.parametrize("M,N,K", [(8, 300, 700), (300, 5, 700), (3, 132, 515), (12, 300, 700), (300, 16, 515)])
 def test_f32_few_vectors_special_values(gpu, M, N, K):
     # infinities and NaNs in the streamed matrix, among them its last row and column (which the kernels read again in
     # place of pieces outside the matrix): the class of every entry must match the oracle's
