@@ -347,7 +347,7 @@ def split_k(lib, torch, kind):
     def median_ms(fn):
         return steady_ms(torch, fn)
 
-    shapes = (((1, 4096, 4096), (4096, 1, 4096), (1, 16384, 16384), (8, 8192, 8192), (2, 8192, 8192), (8192, 8, 8192),
+    shapes = (((1, 4096, 4096), (4096, 1, 4096), (1, 16384, 16384), (8, 8192, 8192), (2, 8192, 8192), (16, 8192, 8192), (8192, 8, 8192),
                (8, 1024, 16384), (64, 64, 4097), (256, 256, 65536), (512, 512, 16384)) if kind == "f32" else
               ((1, 8192, 8192), (4, 8192, 8192), (8, 8192, 8192), (16, 8192, 8192), (32, 28672, 8192), (256, 256, 65536), (512, 512, 16384)))
     for M, N, K in shapes:
