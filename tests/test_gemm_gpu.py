@@ -853,6 +853,57 @@ def test_random_shapes_through_every_entry_point(gpu):
         assert oracle.componentwise_error(got, ref, S) <= tol, (case, kind, ta, tb, M, N, K, mode)
 
 
+def test_random_thin_shapes_through_every_entry_point(gpu):
+    # 120 seeded cases with 1 .. 17 rows or columns on one side: precision, storage orders, the long side and K from lists
+    # around the streaming kernels' pieces, chunks and blocks, leading dimensions that keep or break 16-byte rows, offsets
+    # that keep or break 16-byte bases; without a workspace, with one, or as the vector candidate in 1 .. 5 K slices
+    import random
+
+    rng = random.Random(36)
+    seen = set()
+    for case in range(120):
+        kind = rng.choice(("f32", "bf16"))
+        q = 4 if kind == "f32" else 8                       # elements per 16-byte piece
+        small = rng.randint(1, 17)
+        big = rng.choice((1, 3, 4, 7, 8, 9, 15, 16, 31, 33, 64, 100, 257, 1000, 4097, 20000))
+        K = rng.choice((1, 2, 7, 8, 9, 31, 64, 100, 255, 256, 257, 511, 512, 1000, 1024, 1032, 2048, 3000, 5000, 8200))
+        if big * K > 2e7:
+            K = 1000
+        M, N = (small, big) if rng.random() < 0.5 else (big, small)
+        ta, tb = rng.randint(0, 1), rng.randint(0, 1)
+        ca, cb = (M if ta else K), (K if tb else N)
+        pa, pb = rng.choice((0, 0, q, 3 * q, -1)), rng.choice((0, 0, q, 2 * q, -1))
+        lda = ca + 1 if pa < 0 else ca + (-ca) % q + pa      # (-1: a leading dimension that breaks the 16-byte rows)
+        ldb = cb + 3 if pb < 0 else cb + (-cb) % q + pb
+        off = rng.choice((0, 0, 0, 1))
+        if kind == "f32":
+            A, B = inputs.uniform_pm1(36, 2 * case, M, K), inputs.uniform_pm1(36, 2 * case + 1, K, N)
+            tol, run_ws, run_ex, cand, named = TOL_F32, run_f32_ws, run_f32_ex, 3, gpu.fsrgemm_kernel_for_f32_ex
+        else:
+            A = inputs.bf16_normal_scaled(36, 2 * case, M, K, 1 / math.sqrt(K))
+            B = inputs.bf16_normal_scaled(36, 2 * case + 1, K, N, 1 / math.sqrt(K))
+            tol, run_ws, run_ex, cand, named = 1e-5, run_bf16_ws, run_bf16_ex, 4, gpu.fsrgemm_kernel_for_bf16_ex
+        if off == 0:
+            seen.add(named(ta, tb, M, N, K, P_FAKE, lda, P_FAKE, ldb, P_FAKE, N).split("<")[0])
+        mode = rng.choice(("plain", "workspace", "forced"))
+        say("thin case %d: %s %d%d %dx%dx%d lda %d ldb %d offset %d %s" % (case, kind, ta, tb, M, N, K, lda, ldb, off, mode))
+        ref, S = oracle.gemm(A, B)
+        kw = dict(lda=lda, ldb=ldb, ldc=N + rng.choice((0, 1, 4)), offset=off, repeat=2)
+        if mode == "plain":
+            got = run_ex(gpu, ta, tb, A, B, **kw)
+        elif mode == "workspace":
+            got = run_ws(gpu, ta, tb, A, B, **kw)
+        else:
+            try:
+                got = run_cfg(gpu, kind, cand, rng.choice((1, 2, 3, 5)), ta, tb, A, B, **kw)
+            except gpu.FsrGemmError:
+                continue                        # not a problem for the vector candidate (17 vectors, a misaligned matrix, ...)
+        assert oracle.componentwise_error(got, ref, S) <= tol, (case, kind, ta, tb, M, N, K, mode)
+    # the draw reaches the kernels it is there for
+    assert {"gemv_rows_f32_few_kernel", "gemv_cols_f32_few_kernel", "gemv_rows_bf16_few_kernel", "gemv_cols_bf16_few_kernel",
+            "gemv_rows_bf16_mfma_direct_kernel"} <= seen, seen
+
+
 def test_random_larger_aligned_shapes_through_the_plain_entry_points(gpu):
     # 28 seeded cases of 1024 .. 6000 rows and columns, aligned, every storage order, ragged against every tile: what the
     # dispatcher makes of them (tiles of every size, two bands, a rest of K) against the oracle's whole product
