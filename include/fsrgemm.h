@@ -185,8 +185,9 @@ int gemm_bf16_ws(int transA, int transB,
  * generated kernels.
  *   tile: fp32  0 = 256 x 128, 1 = 128 x 128, 2 = 64 x 64 output tile per workgroup, 3 = the streaming kernels for
  *               M == 1 or N == 1 with K > 0, which use no matrix cores, and for M <= 16 or N <= 16 where the operand on the
- *               other side (B for M < N, else A) is 16-byte aligned with a leading dimension that is a multiple of 4
- *               and, if it is stored contiguous along n (m), N (M) >= 4; 4 = the kernel for small results of long
+ *               other side (B for M < N, else A) either is stored contiguous along n (m) with N (M) >= 4, or is stored
+ *               contiguous along k, 16-byte aligned and with a leading dimension that is a multiple of 4;
+ *               4 = the kernel for small results of long
  *               sums (both operands stored with k as the row index: transA != 0 or M == 1, transB == 0 or N == 1; M, N <= 16 with
  *               at most 144 entries after rounding both up to multiples of 4; K > 0), whose
  *               k_slices are workgroups (1..256, at most K) that each keep a partial result in the workspace, so it
@@ -195,8 +196,8 @@ int gemm_bf16_ws(int transA, int transB,
  *               64 x 128 (fsrgemm_tile_count_f32() = 17);
  *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64, 4 = the streaming
  *               kernels for M == 1 or N == 1 with K > 0, and for M <= 8 or N <= 8 where the operand on the other side
- *               (B for M < N, else A) is 16-byte aligned with a leading dimension that is a multiple of 8 and, if it is
- *               stored contiguous along n (m), N (M) >= 8; with transA == 0, transB != 0, K a multiple of 8 and both
+ *               (B for M < N, else A) either is stored contiguous along n (m) with N (M) >= 8, or is stored contiguous
+ *               along k, 16-byte aligned and with a leading dimension that is a multiple of 8; with transA == 0, transB != 0, K a multiple of 8 and both
  *               operands 16-byte aligned with leading dimensions that are multiples of 8 also for M <= 16 or N <= 16 (a
  *               streaming kernel on the matrix cores); 5..10 = the direct-to-LDS kernel with tiles 192 x 256,
  *               128 x 256, 256 x 192, 192 x 192, 256 x 128, 128 x 128 (fsrgemm_tile_count_bf16() = 11).

@@ -19,7 +19,7 @@
 //   cols:  64 columns, 32 groups of lanes, eight rows in flight each (256 k per chunk); the vectors' elements of
 //          a matrix row sit side by side in LDS; the sums of a wavefront's eight groups are added by lane exchange,
 //          the four wavefronts' through LDS, in fixed order.
-// These need a matrix of aligned 16-byte pieces and, in the cols pattern, at least eight columns (gemv_bf16_takes_few).
+// The rows pattern needs a matrix of aligned 16-byte pieces, the cols pattern at least eight columns (gemv_bf16_takes_few).
 // Values are widened to fp32 (exact), products and sums are fp32 FMAs.  With k_slices > 1 the K range is cut
 // into slices that write partial results behind g.y (a workspace), added afterwards by the split-K reduction
 // kernel.  All sums have a fixed order: results repeat bit for bit.
@@ -565,8 +565,9 @@ const char *gemv_bf16_kernel_name(int pattern, bool vec, int nvec, bool mfma)
 }
 
 bool gemv_bf16_takes_vectors(const VecArgs16 &a) { return aligned16(a.mat) && a.ld % 8 == 0; }
-// the kernels for several vectors: a matrix of aligned pieces, and at least one whole piece of columns
-bool gemv_bf16_takes_few(int pattern, const VecArgs16 &a) { return gemv_bf16_takes_vectors(a) && (pattern == kVecRows || a.len >= 8); }
+// the kernels for several vectors: rows pattern -- a matrix of aligned pieces; cols pattern -- at least one whole piece of
+// columns (its 16-byte loads are issued from any element-aligned address)
+bool gemv_bf16_takes_few(int pattern, const VecArgs16 &a) { return pattern == kVecRows ? gemv_bf16_takes_vectors(a) : a.len >= 8; }
 // the matrix-core kernel: the rows pattern with 2 .. 16 vectors that are contiguous along k, everything in aligned
 // pieces, K whole pieces
 bool gemv_bf16_takes_mfma(int pattern, const VecArgs16 &a)

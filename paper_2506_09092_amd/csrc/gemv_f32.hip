@@ -21,7 +21,7 @@
 //   cols:  as above (32 columns, 32 groups of lanes, eight rows in flight), the vectors' elements of a matrix
 //          row sit side by side in LDS and are read as 16-byte pieces; 4 x R sums per lane, added over a
 //          wavefront's eight groups by lane exchange and over the four wavefronts through LDS, in fixed order.
-// These need a matrix of aligned 16-byte pieces and, in the cols pattern, at least four columns (gemv_takes_few).
+// The rows pattern needs a matrix of aligned 16-byte pieces, the cols pattern at least four columns (gemv_takes_few).
 // With k_slices > 1 the K range is cut into slices, workgroup ids beyond the first round belong to further
 // slices and every slice writes its partial y to its own vector behind g.y (a workspace); the caller adds the
 // slices with the split-K reduction kernel.  All sums have a fixed order: results repeat bit for bit.
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(kThreads) void gemv_rows_f32_few_kernel(VecArgs g)
         }
 }
 
-// cols pattern, R vectors (g.nvec <= R): y_r[j] = sum_k x_r[k] Mat[k][j]; requires gemv_takes_few(kVecCols, g)
+// cols pattern, R vectors (g.nvec <= R): y_r[j] = sum_k x_r[k] Mat[k][j]; requires gemv_takes_few(kVecCols, g): any alignment
 template <int R>
 __global__ __launch_bounds__(kThreads) void gemv_cols_f32_few_kernel(VecArgs g)
 {
@@ -413,8 +413,9 @@ const char *gemv_kernel_name(int pattern, bool vec, int nvec)
 }
 
 bool gemv_takes_vectors(const VecArgs &a) { return aligned16(a.mat) && a.ld % 4 == 0; }
-// the kernels for several vectors: a matrix of aligned pieces, and at least one whole piece of columns
-bool gemv_takes_few(int pattern, const VecArgs &a) { return gemv_takes_vectors(a) && (pattern == kVecRows || a.len >= 4); }
+// the kernels for several vectors: rows pattern -- a matrix of aligned pieces; cols pattern -- at least one whole piece of
+// columns (its 16-byte loads are issued from any element-aligned address)
+bool gemv_takes_few(int pattern, const VecArgs &a) { return pattern == kVecRows ? gemv_takes_vectors(a) : a.len >= 4; }
 
 // len >= 1, K >= 1, k_slices >= 1; the number of workgroups must fit a grid (checked by the caller); more than one
 // vector only on a matrix of aligned pieces

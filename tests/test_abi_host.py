@@ -152,8 +152,10 @@ def test_transposed_storage_arguments(ta, tb):
 def test_workspace_query_and_argument_checks():
     wb = lib.gemm_f32_workspace_bytes
     # (under 64 rows the direct-to-LDS shapes do not fit: the general 64 x 64 tile in slices)
-    assert wb(0, 0, 8, 4096, 4096) == 16 * 8 * 4096 * 4             # 64 tiles, 256 K-tiles -> 16 slices of 16 K-tiles
-    assert wb(0, 0, 8, 16384, 16384) == 4 * 8 * 16384 * 4           # 256 tiles -> 4 slices
+    assert wb(0, 1, 8, 4096, 4096) == 16 * 8 * 4096 * 4             # 64 tiles, 256 K-tiles -> 16 slices of 16 K-tiles (the plan for a misaligned B: tiles)
+    assert wb(0, 0, 8, 4096, 4096) == 2 * 8 * 4096 * 4              # a row-major B streams through the vector kernels whatever its alignment: 2 slices
+    assert wb(0, 1, 8, 16384, 16384) == 4 * 8 * 16384 * 4           # 256 tiles -> 4 slices (a misaligned B on tiles)
+    assert wb(0, 0, 8, 16384, 16384) == 0                           # streamed in one piece: 512 workgroups
     assert wb(0, 0, 1, 4096, 4096) == 2 * 4096 * 4                  # a row times a matrix: 128 workgroups of 32 columns -> 2 slices
     assert wb(0, 0, 4096, 1, 4096) == 0                             # a matrix times a column: 1024 workgroups of 4 rows
     assert wb(0, 0, 1280, 1280, 1280) == 0                           # 400 tiles, but only 80 K-tiles
@@ -237,7 +239,9 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
     # operand consists of aligned 16-byte pieces: K slices only up to 256 workgroups; otherwise tiles as above.  With 9 .. 16
     # vectors against a matrix contiguous along k, and a workspace, the tiles in K slices stay
     assert pf(8, 8192, 8192) == (3, 1) and pf(8, 2048, 8192) == (3, 4) and lib.fsrgemm_plan_f32(0, 1, 8, 2048, 8192, P, 8192, P, 8192, True, True) == (3, 2)
-    assert lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P + 4, 8192, True, True) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P, 8193, True, True) == (2, 8)
+    # (a matrix walked along its columns streams from any alignment; one walked along k must consist of aligned pieces)
+    assert lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P + 4, 8192, True, True) == (3, 1) and lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P, 8193, True, True) == (3, 1)
+    assert lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P + 4, 8192, True, True) == (2, 8) and lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P, 8193, True, True) == (2, 8)
     assert lib.fsrgemm_plan_f32(0, 0, 9, 8192, 8192, P, 8192, P, 8192, True, True) == (3, 1) and lib.fsrgemm_plan_f32(0, 0, 8, 2048, 8192, P, 8192, P, 2048, False, True) == (3, 1)
     assert lib.fsrgemm_plan_f32(0, 1, 16, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and lib.fsrgemm_plan_f32(0, 1, 16, 8192, 8192, P, 8192, P, 8192, False, True) == (3, 1)
     assert lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P, 8192, True, True) == (3, 1)
@@ -246,7 +250,7 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
     assert lib.fsrgemm_kernel_for_f32_ex(0, 1, 3, 2048, 8192, P, 8192, P, 8192, P, 2048) == "gemv_rows_f32_few_kernel<4>"
     assert lib.fsrgemm_kernel_for_f32_ex(1, 0, 2048, 2, 8192, P, 2048, P, 2, P, 2) == "gemv_cols_f32_few_kernel<2>"
     assert lib.fsrgemm_kernel_for_f32_ex(1, 0, 3, 2, 8192, P, 4, P, 2, P, 2).startswith("gemm_f32_kernel<")     # three columns to walk: no whole piece
-    assert lib.gemm_f32_workspace_bytes(0, 0, 8, 2048, 8192) == 32 * 8 * 2048 * 4       # (the larger need: misaligned operands on tiles, 32 slices)
+    assert lib.gemm_f32_workspace_bytes(0, 0, 8, 2048, 8192) == 4 * 8 * 2048 * 4 and lib.gemm_f32_workspace_bytes(0, 1, 8, 2048, 8192) == 32 * 8 * 2048 * 4       # (the larger need: misaligned operands on tiles, 32 slices)
 
 
 def test_f32_slices_on_the_direct_to_lds_shapes():
@@ -309,7 +313,7 @@ def test_forced_configurations_and_plan_queries():
     # the dispatcher takes it for such shapes when the call brings a workspace: the normal equations of least squares
     pfw = lambda M, N, K: lib.fsrgemm_plan_f32(1, 0, M, N, K, P, M, P, N, True)
     assert pfw(10, 10, 1 << 22) == (4, 256) and pfw(10, 1, 1 << 14) == (4, 64) and pfw(10, 10, 4095)[0] != 4
-    assert lib.fsrgemm_plan_f32(1, 0, 10, 10, 1 << 22, P, 10, P, 10, False) == (2, 1)
+    assert lib.fsrgemm_plan_f32(1, 0, 10, 10, 1 << 22, P, 10, P, 10, False) == (3, 1)             # ten columns of a transposed X: the streaming kernel
     assert lib.gemm_f32_workspace_bytes(1, 0, 10, 10, 1 << 22) == 256 * 100 * 4 and lib.gemm_f32_workspace_bytes(1, 0, 10, 1, 4096) == 16 * 10 * 4
     # candidates 5..13: the direct-to-LDS kernel with tiles 256 x 256, 192 x 256, 128 x 256, 256 x 128, 192 x 128, 128 x 128,
     # 256 x 192, 192 x 192, 128 x 192;
@@ -572,7 +576,7 @@ def test_small_result_kernel_is_planned_only_where_its_launcher_accepts_the_piec
             assert lib.gemm_f32_cfg(4, 256, 1, 0, 10, 10, K, P, lda, P, 10, P, 10, P, 256 * 100 * 4, 0) == bad
             assert tile == 3 and slices > 1             # (ten columns of a transposed X in aligned pieces: the streaming kernel)
     # the same on B's side, and for a dot product of two strided vectors
-    assert lib.fsrgemm_plan_f32(1, 0, 10, 10, K, P, 10, P, 40000, True)[0] == 2
+    assert lib.fsrgemm_plan_f32(1, 0, 10, 10, K, P, 10, P, 40000, True) == (3, 64)
     assert lib.fsrgemm_plan_f32(1, 1, 1, 1, K, P, 1, P, K, True) == (4, 256)
 
 

@@ -172,7 +172,7 @@ def test_f32_workspace_split_k(gpu, shape):
     M, N, K = shape
     need = gpu.gemm_f32_workspace_bytes(0, 0, M, N, K)
     say("split-K %dx%dx%d workspace %d bytes" % (M, N, K, need))
-    vector = M == 1 or N == 1               # the streaming kernels: whether they split depends on the storage order
+    vector = min(M, N) <= 16                # the streaming kernels: whether they split depends on the storage order
     assert (need > 0 or vector) and need % (4 * M * N) == 0 and need <= 16 << 20
     A, B = inputs.uniform_pm1(7, 1, M, K), inputs.uniform_pm1(7, 2, K, N)
     ref, S = oracle.gemm(A, B)
@@ -241,7 +241,7 @@ def test_bf16_workspace_split_k(gpu, shape):
     M, N, K = shape
     need = gpu.gemm_bf16_workspace_bytes(0, 1, M, N, K)
     say("bf16 split-K %dx%dx%d workspace %d bytes" % (M, N, K, need))
-    vector = M == 1 or N == 1               # the streaming kernels: whether they split depends on the storage order
+    vector = min(M, N) <= 16                # the streaming kernels: whether they split depends on the storage order
     assert (need > 0 or vector) and need % (4 * M * N) == 0 and need <= 16 << 20
     A = inputs.bf16_normal_scaled(4, 50, M, K, 1 / math.sqrt(K))
     B = inputs.bf16_normal_scaled(4, 51, K, N, 1 / math.sqrt(K))
@@ -1255,8 +1255,11 @@ def test_f32_few_vector_shapes(gpu, M, N, K):
         assert oracle.componentwise_error(got, ref, S) <= TOL_F32
         got = run_f32_ws(gpu, ta, tb, A, B, lda=lda + 4, ldb=ldb + 8, repeat=2)            # with the workspace the library asks for
         assert oracle.componentwise_error(got, ref, S) <= TOL_F32
-        got = run_f32_ex(gpu, ta, tb, A, B, lda=lda + 1, ldb=ldb + 3, offset=1, repeat=2)  # 4-byte aligned only: the tile kernels
+        # 4-byte aligned only: a matrix walked along its columns still streams, one walked along k goes to the tile kernels
+        got = run_f32_ex(gpu, ta, tb, A, B, lda=lda + 1, ldb=ldb + 3, offset=1, repeat=2)
         assert oracle.componentwise_error(got, ref, S) <= TOL_F32
+        name = gpu.fsrgemm_kernel_for_f32_ex(ta, tb, M, N, K, P_FAKE + 4, lda + 1, P_FAKE + 4, ldb + 3, P_FAKE, N)
+        assert ("few_kernel" in name) == (cols and max(M, N) >= 4), name
         if K <= 4097:
             assert np.array_equal(run_f32_ws(gpu, ta, tb, Ai, Bi, lda=lda, ldb=ldb).astype(np.float64), refi)
             assert np.array_equal(run_f32_ex(gpu, ta, tb, Ai, Bi, lda=lda, ldb=ldb).astype(np.float64), refi)
@@ -1302,8 +1305,11 @@ def test_bf16_few_vector_shapes(gpu, M, N, K):
         assert oracle.componentwise_error(got, ref, S) <= 1e-5
         got = run_bf16_ws(gpu, ta, tb, A, B, lda=lda + 8, ldb=ldb + 16, repeat=2)            # with the workspace the library asks for
         assert oracle.componentwise_error(got, ref, S) <= 1e-5
-        got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda + 1, ldb=ldb + 3, offset=1, repeat=2)   # 2-byte aligned only: the tile kernels
+        # 2-byte aligned only: a matrix walked along its columns still streams, one walked along k goes to the tile kernels
+        got = run_bf16_ex(gpu, ta, tb, A, B, lda=lda + 1, ldb=ldb + 3, offset=1, repeat=2)
         assert oracle.componentwise_error(got, ref, S) <= 1e-5
+        name = gpu.fsrgemm_kernel_for_bf16_ex(ta, tb, M, N, K, P_FAKE + 2, lda + 1, P_FAKE + 2, ldb + 3, P_FAKE, N)
+        assert ("few_kernel" in name) == (cols and max(M, N) >= 8 and min(M, N) <= 8), name
         for slices in (1, 2, 7, 64):
             if slices <= -(-K // 64) and "gemv_" in name:
                 got = run_cfg(gpu, "bf16", 4, slices, ta, tb, A, B, lda=lda, ldb=ldb, repeat=2)
