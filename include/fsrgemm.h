@@ -184,9 +184,8 @@ int gemm_bf16_ws(int transA, int transB,
  * validate, keep the one with the least measured time), with tile configurations and K slices in the place of
  * generated kernels.
  *   tile: fp32  0 = 256 x 128, 1 = 128 x 128, 2 = 64 x 64 output tile per workgroup, 3 = the streaming kernels for
- *               M == 1 or N == 1 with K > 0, which use no matrix cores, and for M <= 16 or N <= 16 where the operand on the
- *               other side (B for M < N, else A) either is stored contiguous along n (m) with N (M) >= 4, or is stored
- *               contiguous along k, 16-byte aligned and with a leading dimension that is a multiple of 4;
+ *               M == 1 or N == 1 with K > 0, which use no matrix cores, and for M <= 16 or N <= 16 (any alignment) unless
+ *               the operand on the other side (B for M < N, else A) is stored contiguous along n (m) and N (M) < 4;
  *               4 = the kernel for small results of long
  *               sums (both operands stored with k as the row index: transA != 0 or M == 1, transB == 0 or N == 1; M, N <= 16 with
  *               at most 144 entries after rounding both up to multiples of 4; K > 0), whose
@@ -195,9 +194,8 @@ int gemm_bf16_ws(int transA, int transB,
  *               128 x 256, 256 x 128, 192 x 128, 128 x 128, 256 x 192, 192 x 192, 128 x 192, 64 x 64, 128 x 64,
  *               64 x 128 (fsrgemm_tile_count_f32() = 17);
  *         bf16  0 = 256 x 256 with direct-to-LDS loads, 1 = 256 x 256, 2 = 128 x 128, 3 = 64 x 64, 4 = the streaming
- *               kernels for M == 1 or N == 1 with K > 0, and for M <= 8 or N <= 8 where the operand on the other side
- *               (B for M < N, else A) either is stored contiguous along n (m) with N (M) >= 8, or is stored contiguous
- *               along k, 16-byte aligned and with a leading dimension that is a multiple of 8; with transA == 0, transB != 0, K a multiple of 8 and both
+ *               kernels for M == 1 or N == 1 with K > 0, and for M <= 8 or N <= 8 (any alignment) unless the operand on
+ *               the other side (B for M < N, else A) is stored contiguous along n (m) and N (M) < 8; with transA == 0, transB != 0, K a multiple of 8 and both
  *               operands 16-byte aligned with leading dimensions that are multiples of 8 also for M <= 16 or N <= 16 (a
  *               streaming kernel on the matrix cores); 5..10 = the direct-to-LDS kernel with tiles 192 x 256,
  *               128 x 256, 256 x 192, 192 x 192, 256 x 128, 128 x 128 (fsrgemm_tile_count_bf16() = 11).

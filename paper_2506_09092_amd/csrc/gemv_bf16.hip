@@ -19,7 +19,7 @@
 //   cols:  64 columns, 32 groups of lanes, eight rows in flight each (256 k per chunk); the vectors' elements of
 //          a matrix row sit side by side in LDS; the sums of a wavefront's eight groups are added by lane exchange,
 //          the four wavefronts' through LDS, in fixed order.
-// The rows pattern needs a matrix of aligned 16-byte pieces, the cols pattern at least eight columns (gemv_bf16_takes_few).
+// Any alignment of the matrix; the cols pattern needs at least eight columns (gemv_bf16_takes_few).
 // Values are widened to fp32 (exact), products and sums are fp32 FMAs.  With k_slices > 1 the K range is cut
 // into slices that write partial results behind g.y (a workspace), added afterwards by the split-K reduction
 // kernel.  All sums have a fixed order: results repeat bit for bit.
@@ -214,7 +214,7 @@ __device__ __forceinline__ void store_vectors(uint16_t *__restrict__ xs, const u
     }
 }
 
-// rows pattern, R vectors (g.nvec <= R): y_r[i] = sum_k Mat[i][k] x_r[k]; requires gemv_bf16_takes_few(kVecRows, g)
+// rows pattern, R vectors (g.nvec <= R): y_r[i] = sum_k Mat[i][k] x_r[k]; any alignment
 template <int R>
 __global__ __launch_bounds__(kThreads) void gemv_rows_bf16_few_kernel(VecArgs16 g)
 {
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(kThreads) void gemv_rows_bf16_few_kernel(VecArgs16 
             const int k = kc + 8 * lane + 512 * u;
             const int kk = k < k8 ? k : k0;
 #pragma unroll
-            for (int i = 0; i < RW; ++i) m[i][u] = load8(rowp[i] + kk);
+            for (int i = 0; i < RW; ++i) m[i][u] = load8_any(rowp[i] + kk);
         };
         fetch_rows(k0, 0);
         fetch_rows(k0, 1);
@@ -565,9 +565,9 @@ const char *gemv_bf16_kernel_name(int pattern, bool vec, int nvec, bool mfma)
 }
 
 bool gemv_bf16_takes_vectors(const VecArgs16 &a) { return aligned16(a.mat) && a.ld % 8 == 0; }
-// the kernels for several vectors: rows pattern -- a matrix of aligned pieces; cols pattern -- at least one whole piece of
-// columns (its 16-byte loads are issued from any element-aligned address)
-bool gemv_bf16_takes_few(int pattern, const VecArgs16 &a) { return pattern == kVecRows ? gemv_bf16_takes_vectors(a) : a.len >= 8; }
+// the kernels for several vectors: any alignment (their 16-byte loads are issued from element-aligned addresses); the
+// cols pattern needs at least one whole piece of columns
+bool gemv_bf16_takes_few(int pattern, const VecArgs16 &a) { return pattern == kVecRows || a.len >= 8; }
 // the matrix-core kernel: the rows pattern with 2 .. 16 vectors that are contiguous along k, everything in aligned
 // pieces, K whole pieces
 bool gemv_bf16_takes_mfma(int pattern, const VecArgs16 &a)

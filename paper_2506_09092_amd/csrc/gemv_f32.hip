@@ -21,7 +21,7 @@
 //   cols:  as above (32 columns, 32 groups of lanes, eight rows in flight), the vectors' elements of a matrix
 //          row sit side by side in LDS and are read as 16-byte pieces; 4 x R sums per lane, added over a
 //          wavefront's eight groups by lane exchange and over the four wavefronts through LDS, in fixed order.
-// The rows pattern needs a matrix of aligned 16-byte pieces, the cols pattern at least four columns (gemv_takes_few).
+// Any alignment of the matrix; the cols pattern needs at least four columns (gemv_takes_few).
 // With k_slices > 1 the K range is cut into slices, workgroup ids beyond the first round belong to further
 // slices and every slice writes its partial y to its own vector behind g.y (a workspace); the caller adds the
 // slices with the split-K reduction kernel.  All sums have a fixed order: results repeat bit for bit.
@@ -214,7 +214,7 @@ __device__ __forceinline__ void store_vectors(float *__restrict__ xs, const floa
     }
 }
 
-// rows pattern, R vectors (g.nvec <= R): y_r[i] = sum_k Mat[i][k] x_r[k]; requires gemv_takes_few(kVecRows, g)
+// rows pattern, R vectors (g.nvec <= R): y_r[i] = sum_k Mat[i][k] x_r[k]; any alignment
 template <int R>
 __global__ __launch_bounds__(kThreads) void gemv_rows_f32_few_kernel(VecArgs g)
 {
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(kThreads) void gemv_rows_f32_few_kernel(VecArgs g)
     const int slice = (int)blockIdx.x / groups;
     const int row0 = ((int)blockIdx.x - slice * groups) * (4 * RW) + ((int)threadIdx.x >> 6) * RW;
     const int lane = threadIdx.x & 63;
-    const int per = (((g.K + g.k_slices - 1) / g.k_slices) + 3) & ~3;     // slices start at multiples of 4: pieces stay aligned
+    const int per = (((g.K + g.k_slices - 1) / g.k_slices) + 3) & ~3;     // slices start at multiples of 4: pieces of an aligned matrix stay aligned
     const int k0 = (int)min((int64_t)slice * per, (int64_t)g.K), k1 = (int)min((int64_t)k0 + per, (int64_t)g.K);
     const int k4 = k0 + ((k1 - k0) & ~3);                     // whole pieces up to here, up to three elements behind
     const float *__restrict__ rowp[RW];
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(kThreads) void gemv_rows_f32_few_kernel(VecArgs g)
             const int k = kc + 4 * lane + 256 * u;
             const int kk = k < k4 ? k : k0;
 #pragma unroll
-            for (int i = 0; i < RW; ++i) m[i][u] = load4(rowp[i] + kk);
+            for (int i = 0; i < RW; ++i) m[i][u] = load4_any(rowp[i] + kk);
         };
         fetch_rows(k0, 0);
         fetch_rows(k0, 1);
@@ -413,9 +413,9 @@ const char *gemv_kernel_name(int pattern, bool vec, int nvec)
 }
 
 bool gemv_takes_vectors(const VecArgs &a) { return aligned16(a.mat) && a.ld % 4 == 0; }
-// the kernels for several vectors: rows pattern -- a matrix of aligned pieces; cols pattern -- at least one whole piece of
-// columns (its 16-byte loads are issued from any element-aligned address)
-bool gemv_takes_few(int pattern, const VecArgs &a) { return pattern == kVecRows ? gemv_takes_vectors(a) : a.len >= 4; }
+// the kernels for several vectors: any alignment (their 16-byte loads are issued from element-aligned addresses); the
+// cols pattern needs at least one whole piece of columns
+bool gemv_takes_few(int pattern, const VecArgs &a) { return pattern == kVecRows || a.len >= 4; }
 
 // len >= 1, K >= 1, k_slices >= 1; the number of workgroups must fit a grid (checked by the caller); more than one
 // vector only on a matrix of aligned pieces

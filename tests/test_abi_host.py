@@ -63,7 +63,7 @@ def test_dispatch_query_names_variants():
     q = lib.fsrgemm_kernel_for_f32
     fast = q(4096, 4096, 4096, P, 4096, P, 4096, P, 4096)
     ragged = q(4097, 17, 1000, P, 1000, P, 20, P, 17)
-    unaligned = q(123, 5, 8, P + 4, 8, P + 4, 5, P, 5)
+    unaligned = q(123, 20, 8, P + 4, 8, P + 4, 20, P, 20)
     # <TM, TN, min waves, load mode, A layout, B layout>: tile (64 TM) x (64 TN); mode 0 unchecked vectors,
     # 1 vectors + predicated edges, 2 scalar; row-major A is contiguous along k (0), row-major B along n (1)
     # the direct-to-LDS kernel <blocks per wavefront, A layout, B layout> where it fits, in the shape that fills whole
@@ -152,9 +152,9 @@ def test_transposed_storage_arguments(ta, tb):
 def test_workspace_query_and_argument_checks():
     wb = lib.gemm_f32_workspace_bytes
     # (under 64 rows the direct-to-LDS shapes do not fit: the general 64 x 64 tile in slices)
-    assert wb(0, 1, 8, 4096, 4096) == 16 * 8 * 4096 * 4             # 64 tiles, 256 K-tiles -> 16 slices of 16 K-tiles (the plan for a misaligned B: tiles)
+    assert wb(0, 0, 17, 4096, 4096) == 16 * 17 * 4096 * 4           # 64 tiles, 256 K-tiles -> 16 slices of 16 K-tiles
     assert wb(0, 0, 8, 4096, 4096) == 2 * 8 * 4096 * 4              # a row-major B streams through the vector kernels whatever its alignment: 2 slices
-    assert wb(0, 1, 8, 16384, 16384) == 4 * 8 * 16384 * 4           # 256 tiles -> 4 slices (a misaligned B on tiles)
+    assert wb(0, 0, 17, 16384, 16384) == 4 * 17 * 16384 * 4         # 256 tiles -> 4 slices
     assert wb(0, 0, 8, 16384, 16384) == 0                           # streamed in one piece: 512 workgroups
     assert wb(0, 0, 1, 4096, 4096) == 2 * 4096 * 4                  # a row times a matrix: 128 workgroups of 32 columns -> 2 slices
     assert wb(0, 0, 4096, 1, 4096) == 0                             # a matrix times a column: 1024 workgroups of 4 rows
@@ -186,7 +186,8 @@ def test_workspace_query_and_argument_checks():
     assert lib.fsrgemm_kernel_for_bf16_cfg(4, 1, 1, 8192, 2, 8192, P, 8192, P, 8192, P, 2) == "gemv_cols_bf16_few_kernel<2>"
     assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 17, 8192, P, 8192, P, 8192, P, 17) is None            # 17 columns: no vector side
     assert lib.fsrgemm_kernel_for_bf16_cfg(4, 1, 1, 8192, 9, 8192, P, 8192, P, 8192, P, 9) is None              # nine, and not the matrix-core kernel's storage
-    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 2, 8192, P + 2, 8192, P, 8192, P, 2) is None          # the streamed operand misaligned
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 2, 8192, P + 2, 8192, P, 8192, P, 2) == "gemv_rows_bf16_few_kernel<2>"       # the streamed operand misaligned: lane arithmetic
+    assert lib.fsrgemm_kernel_for_bf16_cfg(4, 0, 1, 8192, 9, 8192, P + 2, 8192, P, 8192, P, 9) is None          # nine vectors need the matrix-core kernel, which needs aligned pieces
     # without a workspace the streaming kernels take such calls; with one, the 64 x 64 tiles where they split K and there are
     # more than 8 vectors on a long matrix (matrix-core kernel) or more than 4 (the others)
     pbx = lambda M, N, K, ws: lib.fsrgemm_plan_bf16(0, 1, M, N, K, P, K, P, K, ws, True)
@@ -235,13 +236,13 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
     assert lib.gemm_f32_workspace_bytes(0, 0, 512, 512, 65536) == 16 * 512 * 512 * 4
     # a problem under 128 rows or columns keeps 64 x 64 tiles: most of a 128-wide tile would be padding
     assert pf(17, 8192, 8192) == (2, 8) and lib.fsrgemm_plan_f32(0, 0, 17, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and pb(32, 28672, 8192) == (3, 2) and pb(96, 8192, 8192) == (3, 4) and pb(128, 8192, 8192) == (10, 4)
-    # fp32 with up to 16 rows (or columns) streams the other operand through the vector kernels (candidate 3) where that
-    # operand consists of aligned 16-byte pieces: K slices only up to 256 workgroups; otherwise tiles as above.  With 9 .. 16
+    # fp32 with up to 16 rows (or columns) streams the other operand through the vector kernels (candidate 3), whatever that
+    # operand's alignment: K slices only up to 256 workgroups.  With 9 .. 16
     # vectors against a matrix contiguous along k, and a workspace, the tiles in K slices stay
     assert pf(8, 8192, 8192) == (3, 1) and pf(8, 2048, 8192) == (3, 4) and lib.fsrgemm_plan_f32(0, 1, 8, 2048, 8192, P, 8192, P, 8192, True, True) == (3, 2)
-    # (a matrix walked along its columns streams from any alignment; one walked along k must consist of aligned pieces)
+    # (the streamed matrix may have any alignment)
     assert lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P + 4, 8192, True, True) == (3, 1) and lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P, 8193, True, True) == (3, 1)
-    assert lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P + 4, 8192, True, True) == (2, 8) and lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P, 8193, True, True) == (2, 8)
+    assert lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P + 4, 8192, True, True) == (3, 1) and lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P, 8193, True, True) == (3, 1)
     assert lib.fsrgemm_plan_f32(0, 0, 9, 8192, 8192, P, 8192, P, 8192, True, True) == (3, 1) and lib.fsrgemm_plan_f32(0, 0, 8, 2048, 8192, P, 8192, P, 2048, False, True) == (3, 1)
     assert lib.fsrgemm_plan_f32(0, 1, 16, 8192, 8192, P, 8192, P, 8192, True, True) == (2, 8) and lib.fsrgemm_plan_f32(0, 1, 16, 8192, 8192, P, 8192, P, 8192, False, True) == (3, 1)
     assert lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P, 8192, True, True) == (3, 1)
@@ -250,7 +251,7 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
     assert lib.fsrgemm_kernel_for_f32_ex(0, 1, 3, 2048, 8192, P, 8192, P, 8192, P, 2048) == "gemv_rows_f32_few_kernel<4>"
     assert lib.fsrgemm_kernel_for_f32_ex(1, 0, 2048, 2, 8192, P, 2048, P, 2, P, 2) == "gemv_cols_f32_few_kernel<2>"
     assert lib.fsrgemm_kernel_for_f32_ex(1, 0, 3, 2, 8192, P, 4, P, 2, P, 2).startswith("gemm_f32_kernel<")     # three columns to walk: no whole piece
-    assert lib.gemm_f32_workspace_bytes(0, 0, 8, 2048, 8192) == 4 * 8 * 2048 * 4 and lib.gemm_f32_workspace_bytes(0, 1, 8, 2048, 8192) == 32 * 8 * 2048 * 4       # (the larger need: misaligned operands on tiles, 32 slices)
+    assert lib.gemm_f32_workspace_bytes(0, 0, 8, 2048, 8192) == 4 * 8 * 2048 * 4 and lib.gemm_f32_workspace_bytes(0, 1, 8, 2048, 8192) == 2 * 8 * 2048 * 4
 
 
 def test_f32_slices_on_the_direct_to_lds_shapes():
@@ -287,7 +288,7 @@ def test_forced_configurations_and_plan_queries():
     # names of forced candidates; None where the forced call would reject the candidate
     qc, qh = lib.fsrgemm_kernel_for_f32_cfg, lib.fsrgemm_kernel_for_bf16_cfg
     assert qc(0, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) == "gemm_f32_kernel<4, 2, 2, 2, 0, 1>"        # the largest tile on a tiny unaligned problem
-    assert qc(3, 0, 0, 10, 10, 10, P, 10, P, 10, P, 10) is None and qc(14, 0, 0, 1, 10, 10, P, 10, P, 10, P, 10) is None
+    assert qc(3, 0, 0, 17, 17, 10, P, 10, P, 17, P, 17) is None and qc(14, 0, 0, 1, 10, 10, P, 10, P, 10, P, 10) is None
     assert qc(3, 0, 0, 1, 16, 16, P, 16, P, 16, P, 16) == "gemv_cols_f32_kernel<true>"
     assert qh(0, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) == "gemm_bf16_main_kernel<8, 8, 0, 0>"
     assert qh(0, 0, 1, 520, 392, 100, P, 104, P, 104, P, 392) is None and qh(4, 0, 1, 520, 392, 128, P, 128, P, 128, P, 392) is None
