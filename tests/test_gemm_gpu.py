@@ -1044,6 +1044,20 @@ def test_calls_captured_in_a_hip_graph_replay_bit_exact(gpu):
     m_in = torch.randn(5000, 300, device="cuda")
     calls.append(lambda: gpu.gemm_f32(1, 300, 5000, v_in, 5000, m_in, 300, v_out, 300, stream()))
     outs.append(v_out)
+    # a few rows on one side: the streaming kernels that stage the vectors in LDS (fp32: both patterns; bf16: lane arithmetic
+    # and both matrix-core kernels)
+    f_in, f_out = torch.randn(6, 5000, device="cuda"), torch.empty(2, 6, 300, device="cuda")
+    mt_in = torch.randn(300, 5000, device="cuda")
+    calls.append(lambda: gpu.gemm_f32(6, 300, 5000, f_in, 5000, m_in, 300, f_out[0], 300, stream()))
+    calls.append(lambda: gpu.gemm_f32_ex(0, 1, 6, 300, 5000, f_in, 5000, mt_in, 5000, f_out[1], 300, stream()))
+    outs.append(f_out)
+    h_in = (torch.randn(12, 4096, device="cuda") / 64).to(torch.bfloat16)
+    hm_in, hn_in = (torch.randn(264, 4096, device="cuda") / 64).to(torch.bfloat16), (torch.randn(4096, 264, device="cuda") / 64).to(torch.bfloat16)
+    h_out, h5_out = torch.empty(12, 264, device="cuda"), torch.empty(2, 5, 264, device="cuda")
+    calls.append(lambda: gpu.gemm_bf16(12, 264, 4096, h_in, 4096, hm_in, 4096, h_out, 264, stream()))
+    calls.append(lambda: gpu.gemm_bf16(5, 264, 4096, h_in, 4096, hm_in, 4096, h5_out[0], 264, stream()))
+    calls.append(lambda: gpu.gemm_bf16_ex(0, 0, 5, 264, 4096, h_in, 4096, hn_in, 264, h5_out[1], 264, stream()))
+    outs += [h_out, h5_out]
 
     for f in calls:                          # eager pass: also the first use of every kernel, outside the capture
         gpu.check(f())
