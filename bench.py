@@ -337,7 +337,8 @@ def split_k(lib, torch, kind):
     """Shapes with few output tiles and a long K (row or column vector times matrix, a few rows against a large
     weight matrix, small squares of long dot products): the plain entry point against the workspace one with the
     workspace the library asks for.  These are HBM-bound: bytes = the operands and the result once, against the
-    8 TB/s peak.  kind: "f32" (row-major operands) or "bf16" (A row-major, B column-major)."""
+    8 TB/s peak; torch.matmul (the vendor library) on the same operands for scale.  kind: "f32" (row-major operands) or
+    "bf16" (A row-major, B column-major)."""
     import math
 
     stream = torch.cuda.current_stream().cuda_stream
@@ -357,6 +358,7 @@ def split_k(lib, torch, kind):
             need = lib.gemm_f32_workspace_bytes(0, 0, M, N, K)
             plain = median_ms(lambda: lib.check(lib.gemm_f32(M, N, K, a, K, b, N, c, N, stream)))
             split = median_ms(lambda: lib.check(lib.gemm_f32_ws(0, 0, M, N, K, a, K, b, N, c, N, ws, need, stream)))
+            vendor = median_ms(lambda: torch.matmul(a, b, out=c))
             byts = 4.0 * (M * K + K * N + M * N)
         else:
             a = (torch.randn(M, K, device="cuda") / math.sqrt(K)).to(torch.bfloat16)
@@ -364,9 +366,11 @@ def split_k(lib, torch, kind):
             need = lib.gemm_bf16_workspace_bytes(0, 1, M, N, K)
             plain = median_ms(lambda: lib.check(lib.gemm_bf16(M, N, K, a, K, b, K, c, N, stream)))
             split = median_ms(lambda: lib.check(lib.gemm_bf16_ws(0, 1, M, N, K, a, K, b, K, c, N, ws, need, stream)))
+            ch = torch.empty(M, N, device="cuda", dtype=torch.bfloat16)
+            vendor = median_ms(lambda: torch.matmul(a, b.t(), out=ch))          # (bf16 output: half the bytes written)
             byts = 2.0 * (M * K + K * N) + 4.0 * M * N
         out.append({"M": M, "N": N, "K": K, "slices": need // (4 * M * N), "workspace_bytes": need, "plain_ms": plain,
-                    "ms": split, "tflops": 2.0 * M * N * K / (split * 1e-3) / 1e12,
+                    "ms": split, "torch_matmul_ms": vendor, "tflops": 2.0 * M * N * K / (split * 1e-3) / 1e12,
                     "hbm_GBps_algorithmic": byts / (split * 1e-3) / 1e9, "hbm_frac_of_8TBps": byts / (split * 1e-3) / 8e12})
         del a, b, c
     return out
