@@ -20,6 +20,9 @@
 //          a matrix row sit side by side in LDS; the sums of a wavefront's eight groups are added by lane exchange,
 //          the four wavefronts' through LDS, in fixed order.
 // Any alignment of the matrix; the cols pattern needs at least eight columns (gemv_bf16_takes_few).
+// Where vectors and matrix are both contiguous along k, aligned, and K is whole 16-byte pieces, up to 16 vectors go
+// through the matrix cores instead (gemv_rows_bf16_mfma_direct_kernel, gemv_rows_bf16_mfma_kernel, described where
+// they stand).
 // Values are widened to fp32 (exact), products and sums are fp32 FMAs.  With k_slices > 1 the K range is cut
 // into slices that write partial results behind g.y (a workspace), added afterwards by the split-K reduction
 // kernel.  All sums have a fixed order: results repeat bit for bit.
