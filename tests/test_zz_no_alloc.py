@@ -39,9 +39,10 @@ def _noalloc(gpu, ta, tb, A, B, ldc=None):
 @pytest.mark.gpu
 def test_no_alloc_entry_point_matches_the_workspace_entry_point(gpu):
     # (transA, transB, M, N, K): a larger problem first, then smaller ones on the same array -- split tile kernels
-    # (64 x 64 and 128 x 128 tiles), the small-result kernel, a split vector kernel, and problems that need no scratch
+    # (64 x 64 and 128 x 128 tiles), the small-result kernel, split vector kernels, and problems that need no scratch
     calls = [(0, 0, 1024, 1024, 16384), (0, 0, 512, 512, 16384), (0, 0, 64, 64, 4097), (1, 0, 10, 10, 1 << 16), (1, 0, 10, 1, 1 << 14),
-             (0, 0, 1, 4096, 4096), (0, 0, 256, 256, 65536), (0, 0, 130, 70, 2050), (0, 0, 300, 260, 200), (0, 0, 1, 1, 100003)]
+             (0, 0, 1, 4096, 4096), (0, 0, 256, 256, 65536), (0, 0, 130, 70, 2050), (0, 0, 300, 260, 200), (0, 0, 1, 1, 100003),
+             (0, 0, 8, 1024, 16384), (0, 1, 12, 2048, 8192), (1, 0, 3000, 5, 4100)]        # a few rows or columns: streaming kernels in K slices
     seen = set()
     for ta, tb, M, N, K in calls:
         print("no-alloc %d%d %dx%dx%d" % (ta, tb, M, N, K), flush=True)
