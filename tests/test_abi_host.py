@@ -239,7 +239,7 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
     # fp32 with up to 16 rows (or columns) streams the other operand through the vector kernels (candidate 3), whatever that
     # operand's alignment: K slices only up to 256 workgroups.  With 9 .. 16
     # vectors against a matrix contiguous along k, and a workspace, the tiles in K slices stay
-    assert pf(8, 8192, 8192) == (3, 1) and pf(8, 2048, 8192) == (3, 4) and lib.fsrgemm_plan_f32(0, 1, 8, 2048, 8192, P, 8192, P, 8192, True, True) == (3, 2)
+    assert pf(8, 8192, 8192) == (3, 1) and pf(8, 2048, 8192) == (3, 4) and lib.fsrgemm_plan_f32(0, 1, 8, 2048, 8192, P, 8192, P, 8192, True, True) == (3, 4)
     # (the streamed matrix may have any alignment)
     assert lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P + 4, 8192, True, True) == (3, 1) and lib.fsrgemm_plan_f32(0, 0, 8, 8192, 8192, P, 8192, P, 8193, True, True) == (3, 1)
     assert lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P + 4, 8192, True, True) == (3, 1) and lib.fsrgemm_plan_f32(0, 1, 8, 8192, 8192, P, 8192, P, 8193, True, True) == (3, 1)
@@ -251,7 +251,7 @@ def test_splits_take_the_larger_tile_where_it_still_fills_the_compute_units():
     assert lib.fsrgemm_kernel_for_f32_ex(0, 1, 3, 2048, 8192, P, 8192, P, 8192, P, 2048) == "gemv_rows_f32_few_kernel<4>"
     assert lib.fsrgemm_kernel_for_f32_ex(1, 0, 2048, 2, 8192, P, 2048, P, 2, P, 2) == "gemv_cols_f32_few_kernel<2>"
     assert lib.fsrgemm_kernel_for_f32_ex(1, 0, 3, 2, 8192, P, 4, P, 2, P, 2).startswith("gemm_f32_kernel<")     # three columns to walk: no whole piece
-    assert lib.gemm_f32_workspace_bytes(0, 0, 8, 2048, 8192) == 4 * 8 * 2048 * 4 and lib.gemm_f32_workspace_bytes(0, 1, 8, 2048, 8192) == 2 * 8 * 2048 * 4
+    assert lib.gemm_f32_workspace_bytes(0, 0, 8, 2048, 8192) == 4 * 8 * 2048 * 4 and lib.gemm_f32_workspace_bytes(0, 1, 8, 2048, 8192) == 4 * 8 * 2048 * 4
 
 
 def test_f32_slices_on_the_direct_to_lds_shapes():
