@@ -52,7 +52,7 @@ THIN = [("f32", 0, 0, 8, 8192, 8192), ("f32", 0, 1, 8, 8192, 8192), ("f32", 0, 0
         ("bf16", 0, 1, 8, 8192, 8192), ("bf16", 0, 0, 8, 8192, 8192), ("bf16", 0, 1, 16, 8192, 8192), ("bf16", 0, 0, 4, 8192, 8192),
         ("bf16", 0, 1, 2, 8192, 8192), ("bf16", 0, 1, 12, 1024, 16384), ("bf16", 0, 1, 16, 28672, 8192), ("bf16", 0, 1, 8192, 16, 8192),
         ("bf16", 1, 1, 8192, 4, 8192), ("f32", 0, 0, 16, 8192, 8192), ("f32", 0, 1, 16, 8192, 8192), ("f32", 1, 0, 8192, 12, 8192),
-        ("f32", 0, 0, 8192, 16, 8192)]
+        ("f32", 0, 0, 8192, 16, 8192), ("f32", 0, 1, 8, 2048, 8192), ("f32", 0, 1, 8, 1024, 16384)]
 
 
 def host_operands(p: Problem, seed: int):
